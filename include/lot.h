@@ -1,0 +1,116 @@
+/*
+ * libLOT -- LOT attention forward on AMD MI355X (gfx950): C ABI.
+ *
+ * The operation (paper, Method section, "Conditional OT", "Glued coupling and
+ * doubly-stochastic attention", eq. (lotattn), "Rank and complexity"): for every (batch, head)
+ * problem, with queries Q and keys K (n tokens each, uniform masses 1/n) and a per-head pivot
+ * measure with r locations Z and masses beta,
+ *
+ *     C1 = Q Z^T,  C2 = K Z^T                                   (n x r similarities)
+ *     Gamma1 = T Sinkhorn iterations on exp(C1/eps), marginals (1/n, beta)     n x r
+ *     Gamma2 = transpose of the same for C2                                    r x n
+ *     O = n * Gamma1 * Diag(beta)^-1 * (Gamma2 * V)                            n x d_v
+ *
+ * One Sinkhorn iteration is a token-side scaling followed by a pivot-side scaling, started from
+ * the pivot-side scaling vector equal to one; there is no convergence test.  The n x n matrix
+ * n * Gamma1 Diag(beta)^-1 Gamma2 is never formed.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller; the library allocates and frees
+ *    nothing and keeps no state between calls.  Outputs must not alias inputs or the workspace.
+ *  - Layout: dense row-major, last index fastest.
+ *        Q, K : [B, H, n, d_k]      V, out : [B, H, n, d_v]      (element type = shape.io_dtype)
+ *        Z    : [H, r, d_k] float   beta   : [H, r] float        (one pivot measure per head)
+ *        gamma1 : [B, H, n, r] float    gamma2 : [B, H, r, n] float
+ *    Q, K, V, out must be 16-byte aligned; workspace 256-byte aligned.
+ *  - beta must be strictly positive and sum to one per head (the paper's p^0); this is a caller
+ *    precondition and is not checked.
+ *  - With io_dtype = LOT_BF16 the similarities are computed from bf16 operands with fp32
+ *    accumulation: Z is rounded to bf16 (nearest even) inside the library.  Potentials, sums and
+ *    the r x d_v intermediate are fp32 in both modes.  The output is rounded to io_dtype.
+ *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream) and
+ *    the call returns without synchronising.  Results are bit-identical from run to run.
+ *  - Return value: LOT_OK (0) or a negative lot_status.  Argument validation happens before any
+ *    HIP call.  No exception or abort crosses this boundary.
+ */
+#ifndef LOT_H
+#define LOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LOT_F32 = 0, LOT_BF16 = 1 } lot_dtype;
+
+typedef enum {
+    LOT_OK = 0,
+    LOT_ERR_NULL = -1,       /* a required pointer is NULL */
+    LOT_ERR_SHAPE = -2,      /* a dimension is < 1 or beyond the supported range */
+    LOT_ERR_EPS = -3,        /* eps is not a finite positive number */
+    LOT_ERR_ITERS = -4,      /* iters < 1 */
+    LOT_ERR_DTYPE = -5,      /* io_dtype is not a lot_dtype */
+    LOT_ERR_WORKSPACE = -6,  /* workspace too small or misaligned */
+    LOT_ERR_ALIGN = -7,      /* a tensor pointer is not 16-byte aligned */
+    LOT_ERR_HIP = -8,        /* a HIP call failed (see lot_strerror) */
+    LOT_ERR_PATH = -9,       /* the requested execution path does not support this shape */
+    LOT_ERR_SYNC = -10       /* lot_workspace_status: a device-side wait gave up */
+} lot_status;
+
+typedef struct {
+    int32_t B, H;        /* batch, heads */
+    int32_t n;           /* tokens (queries = keys) */
+    int32_t d_k, d_v;    /* head dims of Q/K and of V/out */
+    int32_t r;           /* pivot size */
+    int32_t io_dtype;    /* lot_dtype of Q, K, V, out */
+} lot_shape;
+
+/* Which kernels run.  AUTO picks FUSED when the shape is in its compiled set, else REFERENCE. */
+typedef enum {
+    LOT_PATH_AUTO = 0,
+    LOT_PATH_REFERENCE = 1,  /* one plain kernel per step, similarities materialised (any shape) */
+    LOT_PATH_FUSED = 2       /* single persistent kernel; d_k = d_v in {32, 64}, r <= 64 */
+} lot_path;
+
+/* Bytes of device workspace needed by either entry point for this shape (covers both paths). */
+int lot_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out);
+
+/* out = LOTAttn(Q, K, V) as defined above (paper eq. (lotattn) with A = n * glued coupling). */
+int lot_attention_fwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                      const float* Z, const float* beta, float eps, int iters, void* out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Debug route: the two couplings themselves (paper: Gamma^(1) and Gamma^(2) in scaling form). */
+int lot_couplings(const lot_shape* shape, const void* Q, const void* K,
+                  const float* Z, const float* beta, float eps, int iters,
+                  float* gamma1, float* gamma2,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Same two operations with the execution path chosen by the caller (lot_path). */
+int lot_attention_fwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                           const float* Z, const float* beta, float eps, int iters, void* out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream, int path);
+int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,
+                       const float* Z, const float* beta, float eps, int iters,
+                       float* gamma1, float* gamma2,
+                       void* workspace, size_t workspace_bytes, void* hip_stream, int path);
+
+/*
+ * Debug: synchronises the device and reads the status word that the fused kernel leaves in the
+ * workspace.  LOT_OK, or LOT_ERR_SYNC if a bounded device-side wait between cooperating
+ * workgroups gave up (the output of that call is then undefined).  Not part of the hot path.
+ */
+int lot_workspace_status(const void* workspace);
+
+/* Text for a lot_status; for LOT_ERR_HIP the text of the most recent HIP error on this thread. */
+const char* lot_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int lot_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOT_H */

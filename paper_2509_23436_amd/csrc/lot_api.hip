@@ -1,0 +1,160 @@
+// libLOT C ABI: argument validation, workspace carving and dispatch.  No kernels here.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+
+#include "lot_internal.h"
+
+namespace lot {
+
+hipError_t& last_hip_error()
+{
+    static thread_local hipError_t e = hipSuccess;
+    return e;
+}
+
+static int validate_shape(const lot_shape* s)
+{
+    if (!s) return LOT_ERR_NULL;
+    if (s->io_dtype != LOT_F32 && s->io_dtype != LOT_BF16) return LOT_ERR_DTYPE;
+    if (s->B < 1 || s->H < 1 || s->n < 1 || s->d_k < 1 || s->d_v < 1 || s->r < 1) return LOT_ERR_SHAPE;
+    // ranges that keep every index computation inside 63 bits and every grid inside HIP's limits
+    if (s->n > (1 << 24) || s->d_k > 1024 || s->d_v > 1024 || s->r > 1024) return LOT_ERR_SHAPE;
+    if ((int64_t)s->B * s->H > (1 << 20)) return LOT_ERR_SHAPE;
+    // rows of Q, K, V, out must stay 16-byte aligned for the vector loads
+    const int esz = s->io_dtype == LOT_BF16 ? 2 : 4;
+    if ((s->d_k * esz) % 16 != 0 || (s->d_v * esz) % 16 != 0) return LOT_ERR_SHAPE;
+    return LOT_OK;
+}
+
+static bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+static int common_checks(const lot_shape* s, const void* Q, const void* K, const float* Z,
+                         const float* beta, float eps, int iters, void* ws, size_t ws_bytes)
+{
+    int rc = validate_shape(s);
+    if (rc != LOT_OK) return rc;
+    if (!Q || !K || !Z || !beta || !ws) return LOT_ERR_NULL;
+    if (!(eps > 0.0f) || !std::isfinite(eps)) return LOT_ERR_EPS;
+    if (iters < 1) return LOT_ERR_ITERS;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(Z, 4) || misaligned(beta, 4)) return LOT_ERR_ALIGN;
+    if (misaligned(ws, 256)) return LOT_ERR_WORKSPACE;
+    if (ws_bytes < carve(*s).total) return LOT_ERR_WORKSPACE;
+    return LOT_OK;
+}
+
+static int pick_path(const lot_shape& s, int path, bool* fused)
+{
+    switch (path) {
+    case LOT_PATH_AUTO: *fused = fused_supports(s); return LOT_OK;
+    case LOT_PATH_REFERENCE: *fused = false; return LOT_OK;
+    case LOT_PATH_FUSED:
+        if (!fused_supports(s)) return LOT_ERR_PATH;
+        *fused = true;
+        return LOT_OK;
+    default: return LOT_ERR_PATH;
+    }
+}
+
+}  // namespace lot
+
+using namespace lot;
+
+extern "C" {
+
+int lot_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out)
+{
+    int rc = validate_shape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!bytes_out) return LOT_ERR_NULL;
+    if (iters < 1) return LOT_ERR_ITERS;
+    *bytes_out = carve(*shape).total;
+    return LOT_OK;
+}
+
+int lot_attention_fwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                           const float* Z, const float* beta, float eps, int iters, void* out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream, int path)
+{
+    int rc = common_checks(shape, Q, K, Z, beta, eps, iters, workspace, workspace_bytes);
+    if (rc != LOT_OK) return rc;
+    if (!V || !out) return LOT_ERR_NULL;
+    if (misaligned(V, 16) || misaligned(out, 16)) return LOT_ERR_ALIGN;
+    bool fused = false;
+    rc = pick_path(*shape, path, &fused);
+    if (rc != LOT_OK) return rc;
+    Args a{};
+    a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
+    a.out = out; a.ws = (char*)workspace; a.lay = carve(*shape); a.stream = (hipStream_t)hip_stream;
+    if (fused) return run_fused(a, true);
+    a.gamma1 = (float*)(a.ws + a.lay.gamma1);
+    a.gamma2 = (float*)(a.ws + a.lay.gamma2);
+    return run_reference(a, true);
+}
+
+int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,
+                       const float* Z, const float* beta, float eps, int iters,
+                       float* gamma1, float* gamma2,
+                       void* workspace, size_t workspace_bytes, void* hip_stream, int path)
+{
+    int rc = common_checks(shape, Q, K, Z, beta, eps, iters, workspace, workspace_bytes);
+    if (rc != LOT_OK) return rc;
+    if (!gamma1 || !gamma2) return LOT_ERR_NULL;
+    if (misaligned(gamma1, 16) || misaligned(gamma2, 16)) return LOT_ERR_ALIGN;
+    bool fused = false;
+    rc = pick_path(*shape, path, &fused);
+    if (rc != LOT_OK) return rc;
+    Args a{};
+    a.s = *shape; a.Q = Q; a.K = K; a.V = nullptr; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
+    a.out = nullptr; a.gamma1 = gamma1; a.gamma2 = gamma2;
+    a.ws = (char*)workspace; a.lay = carve(*shape); a.stream = (hipStream_t)hip_stream;
+    return fused ? run_fused(a, false) : run_reference(a, false);
+}
+
+int lot_attention_fwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                      const float* Z, const float* beta, float eps, int iters, void* out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return lot_attention_fwd_path(shape, Q, K, V, Z, beta, eps, iters, out, workspace, workspace_bytes,
+                                  hip_stream, LOT_PATH_AUTO);
+}
+
+int lot_couplings(const lot_shape* shape, const void* Q, const void* K,
+                  const float* Z, const float* beta, float eps, int iters,
+                  float* gamma1, float* gamma2,
+                  void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return lot_couplings_path(shape, Q, K, Z, beta, eps, iters, gamma1, gamma2, workspace, workspace_bytes,
+                              hip_stream, LOT_PATH_AUTO);
+}
+
+int lot_workspace_status(const void* workspace)
+{
+    if (!workspace) return LOT_ERR_NULL;
+    uint32_t word = 0;
+    LOT_HIP_CHECK(hipDeviceSynchronize());
+    LOT_HIP_CHECK(hipMemcpy(&word, workspace, sizeof(word), hipMemcpyDeviceToHost));
+    return word == 0 ? LOT_OK : LOT_ERR_SYNC;
+}
+
+const char* lot_strerror(int code)
+{
+    switch (code) {
+    case LOT_OK: return "ok";
+    case LOT_ERR_NULL: return "a required pointer is NULL";
+    case LOT_ERR_SHAPE: return "a dimension is out of range or breaks row alignment";
+    case LOT_ERR_EPS: return "eps must be a finite positive number";
+    case LOT_ERR_ITERS: return "iters must be at least 1";
+    case LOT_ERR_DTYPE: return "io_dtype is not LOT_F32 or LOT_BF16";
+    case LOT_ERR_WORKSPACE: return "workspace is too small or not 256-byte aligned";
+    case LOT_ERR_ALIGN: return "a tensor pointer is not sufficiently aligned";
+    case LOT_ERR_HIP: return hipGetErrorString(last_hip_error());
+    case LOT_ERR_PATH: return "the requested execution path does not support this shape";
+    case LOT_ERR_SYNC: return "a device-side wait between workgroups gave up";
+    default: return "unknown status";
+    }
+}
+
+int lot_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,135 @@
+// Internal declarations shared by the translation units of libLOT (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/lot.h"
+
+namespace lot {
+
+constexpr int kTileTokens = 32;        // tokens per MFMA tile of the fused kernel
+constexpr int kFusedThreads = 256;     // 4 wavefronts per workgroup
+constexpr int kFusedWaves = kFusedThreads / 64;
+constexpr int kMaxCluster = 64;        // most workgroups that share one (problem, side)
+constexpr int kMaxResidentWgs = 2048;  // upper bound on co-resident workgroups (256 CUs x 8)
+constexpr int kRefChunk = 1024;        // tokens per workgroup in the reference column reduction
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Largest cluster size the fused launcher may pick for this shape (host-only arithmetic, so
+// the workspace size can be computed without a device).
+inline int fused_cluster_bound(const lot_shape& s)
+{
+    const int pairs = 2 * s.B * s.H;
+    const int tiles = (s.n + kTileTokens - 1) / kTileTokens;
+    int c = (tiles + kFusedWaves - 1) / kFusedWaves;
+    if (c > kMaxCluster) c = kMaxCluster;
+    int by_capacity = kMaxResidentWgs / pairs;
+    if (by_capacity < 1) by_capacity = 1;
+    if (c > by_capacity) c = by_capacity;
+    return c < 1 ? 1 : c;
+}
+
+inline bool fused_supports(const lot_shape& s)
+{
+    return s.d_k == s.d_v && (s.d_k == 32 || s.d_k == 64) && s.r >= 1 && s.r <= 64;
+}
+
+// Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
+struct Workspace {
+    // fused path
+    size_t status;        // 64 x uint32: word 0 = sync failure flag
+    size_t counters;      // uint32 [pairs] arrivals + uint32 [G] y-ready, zeroed per launch
+    size_t counters_bytes;
+    size_t colsum_part;   // float [pairs][2][cluster_bound][64]
+    size_t u_part;        // float [G][cluster_bound][64][d_v]
+    size_t y_tile;        // float [G][64][d_v]
+    // reference path
+    size_t C;             // float [2][G][n][r]
+    size_t f;             // float [2][G][n]
+    size_t g;             // float [2][G][r]
+    size_t part_m;        // float [2][G][chunks][r]
+    size_t part_s;        // float [2][G][chunks][r]
+    size_t Y;             // float [G][r][d_v]
+    size_t gamma1;        // float [G][n][r]   (attention via the reference path only)
+    size_t gamma2;        // float [G][r][n]
+    size_t total;
+};
+
+inline Workspace carve(const lot_shape& s)
+{
+    Workspace w{};
+    const size_t G = (size_t)s.B * s.H, n = s.n, r = s.r, dv = s.d_v;
+    const size_t cb = fused_cluster_bound(s);
+    const size_t chunks = (n + kRefChunk - 1) / kRefChunk;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    w.status = take(64 * 4);
+    w.counters_bytes = align_up((2 * G + G) * 4, 256);
+    w.counters = take(w.counters_bytes);
+    w.colsum_part = take(2 * G * 2 * cb * 64 * 4);
+    w.u_part = take(G * cb * 64 * dv * 4);
+    w.y_tile = take(G * 64 * dv * 4);
+    w.C = take(2 * G * n * r * 4);
+    w.f = take(2 * G * n * 4);
+    w.g = take(2 * G * r * 4);
+    w.part_m = take(2 * G * chunks * r * 4);
+    w.part_s = take(2 * G * chunks * r * 4);
+    w.Y = take(G * r * dv * 4);
+    w.gamma1 = take(G * n * r * 4);
+    w.gamma2 = take(G * n * r * 4);
+    w.total = off;
+    return w;
+}
+
+struct Args {
+    lot_shape s;
+    const void* Q;
+    const void* K;
+    const void* V;       // null for couplings
+    const float* Z;
+    const float* beta;
+    float eps;
+    int iters;
+    void* out;           // null for couplings
+    float* gamma1;       // null for attention on the fused path
+    float* gamma2;
+    char* ws;
+    Workspace lay;
+    hipStream_t stream;
+};
+
+// Each returns LOT_OK or LOT_ERR_HIP (the failing hipError_t is left in last_hip_error()).
+int run_reference(const Args& a, bool want_out);
+int run_fused(const Args& a, bool want_out);
+
+hipError_t& last_hip_error();
+
+#define LOT_HIP_CHECK(expr)                                   \
+    do {                                                      \
+        hipError_t e_ = (expr);                               \
+        if (e_ != hipSuccess) {                               \
+            ::lot::last_hip_error() = e_;                     \
+            return LOT_ERR_HIP;                               \
+        }                                                     \
+    } while (0)
+
+// bf16 <-> fp32 on raw bits (device and host)
+__host__ __device__ inline float bf16_to_f32(uint16_t b)
+{
+    union { uint32_t u; float f; } v;
+    v.u = (uint32_t)b << 16;
+    return v.f;
+}
+__host__ __device__ inline uint16_t f32_to_bf16_rne(float f)
+{
+    union { uint32_t u; float f; } v;
+    v.f = f;
+    if ((v.u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((v.u >> 16) | 0x40);  // NaN stays NaN
+    uint32_t bias = ((v.u >> 16) & 1u) + 0x7fffu;
+    return (uint16_t)((v.u + bias) >> 16);
+}
+
+}  // namespace lot

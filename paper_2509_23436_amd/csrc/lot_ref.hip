@@ -1,0 +1,197 @@
+// Reference execution path of libLOT: one plain fp32 kernel per step of the method, with the
+// similarity matrices, potentials and couplings materialised in the workspace.  Any shape.
+// It exists for debugging, for shapes outside the fused kernel's compiled set, and as the
+// route by which lot_couplings can always show every intermediate.  Every reduction has a
+// fixed order, so results are reproducible bit for bit.
+//
+// Steps (paper, Method section): similarities C = X Z^T ("Conditional OT"); T rounds of
+// token-side then pivot-side scaling in the log domain (scaling form of Gamma^(1), Gamma^(2));
+// couplings; Y = Gamma2 V, Y' = Diag(beta)^-1 Y, O = n Gamma1 Y' ("Rank and complexity").
+#include "lot_internal.h"
+
+namespace lot {
+namespace {
+
+template <typename T> __device__ inline float ld(const T* p, size_t i);
+template <> __device__ inline float ld<float>(const float* p, size_t i) { return p[i]; }
+template <> __device__ inline float ld<uint16_t>(const uint16_t* p, size_t i) { return bf16_to_f32(p[i]); }
+
+template <typename T> __device__ inline void st(T* p, size_t i, float v);
+template <> __device__ inline void st<float>(float* p, size_t i, float v) { p[i] = v; }
+template <> __device__ inline void st<uint16_t>(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_rne(v); }
+
+// C[side][g][i][t] = <x_i, z_t>, x from Q (side 0) or K (side 1); bf16 mode rounds Z to bf16.
+template <typename T>
+__global__ void ref_cost(const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ Z,
+                         float* __restrict__ C, int G, int H, int n, int d, int r, int round_z)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t per_side = (size_t)G * n * r;
+    if (idx >= 2 * per_side) return;
+    const int side = (int)(idx / per_side);
+    size_t rem = idx % per_side;
+    const int g = (int)(rem / ((size_t)n * r));
+    rem %= (size_t)n * r;
+    const int i = (int)(rem / r), t = (int)(rem % r);
+    const T* x = (side == 0 ? Q : K) + ((size_t)g * n + i) * d;
+    const float* z = Z + ((size_t)(g % H) * r + t) * d;
+    float acc = 0.f;
+    for (int c = 0; c < d; ++c) {
+        float zv = z[c];
+        if (round_z) zv = bf16_to_f32(f32_to_bf16_rne(zv));
+        acc = fmaf(ld(x, c), zv, acc);
+    }
+    C[idx] = acc;
+}
+
+__global__ void ref_zero(float* p, size_t count)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < count) p[idx] = 0.f;
+}
+
+// f_i = eps (log(1/n) - LSE_t((C_it + g_t)/eps)), one thread per (side, g, i).
+__global__ void ref_f_update(const float* __restrict__ C, const float* __restrict__ gpot,
+                             float* __restrict__ f, size_t rows, int n, int r, float eps)
+{
+    const size_t row = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    const float* c = C + row * r;
+    const float* g = gpot + (row / n) * r;
+    float m = -INFINITY;
+    for (int t = 0; t < r; ++t) m = fmaxf(m, (c[t] + g[t]) / eps);
+    float s = 0.f;
+    for (int t = 0; t < r; ++t) s += expf((c[t] + g[t]) / eps - m);
+    f[row] = eps * (-logf((float)n) - (m + logf(s)));
+}
+
+// Per (pair, chunk of tokens, pivot): running maximum and scaled sum of exp((C_it + f_i)/eps).
+__global__ void ref_g_partial(const float* __restrict__ C, const float* __restrict__ f,
+                              float* __restrict__ part_m, float* __restrict__ part_s,
+                              int n, int r, int chunks, float eps)
+{
+    const int pair = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
+    const int i0 = chunk * kRefChunk;
+    const int i1 = min(n, i0 + kRefChunk);
+    for (int t = threadIdx.x; t < r; t += blockDim.x) {
+        float m = -INFINITY, s = 0.f;
+        for (int i = i0; i < i1; ++i) {
+            const float x = (C[((size_t)pair * n + i) * r + t] + f[(size_t)pair * n + i]) / eps;
+            if (x > m) { s = s * expf(m - x) + 1.f; m = x; }
+            else s += expf(x - m);
+        }
+        part_m[((size_t)pair * chunks + chunk) * r + t] = m;
+        part_s[((size_t)pair * chunks + chunk) * r + t] = s;
+    }
+}
+
+// g_t = eps (log beta_t - LSE over all tokens), combining the chunks in index order.
+__global__ void ref_g_final(const float* __restrict__ part_m, const float* __restrict__ part_s,
+                            const float* __restrict__ beta, float* __restrict__ gpot,
+                            int pairs, int G, int H, int r, int chunks, float eps)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= pairs * r) return;
+    const int pair = idx / r, t = idx % r;
+    const int h = (pair % G) % H;
+    float m = -INFINITY;
+    for (int k = 0; k < chunks; ++k) m = fmaxf(m, part_m[((size_t)pair * chunks + k) * r + t]);
+    float s = 0.f;
+    for (int k = 0; k < chunks; ++k)
+        s += part_s[((size_t)pair * chunks + k) * r + t] * expf(part_m[((size_t)pair * chunks + k) * r + t] - m);
+    gpot[idx] = eps * (logf(beta[h * r + t]) - (m + logf(s)));
+}
+
+// Gamma_it = exp((C_it + f_i + g_t)/eps); side 0 -> gamma1 [g][i][t], side 1 -> gamma2 [g][t][i].
+__global__ void ref_couplings(const float* __restrict__ C, const float* __restrict__ f,
+                              const float* __restrict__ gpot, float* __restrict__ gamma1,
+                              float* __restrict__ gamma2, int G, int n, int r, float eps)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t per_side = (size_t)G * n * r;
+    if (idx >= 2 * per_side) return;
+    const int side = (int)(idx / per_side);
+    size_t rem = idx % per_side;
+    const size_t g = rem / ((size_t)n * r);
+    rem %= (size_t)n * r;
+    const size_t i = rem / r, t = rem % r;
+    const size_t pair = (size_t)side * G + g;
+    const float v = expf((C[idx] + f[pair * n + i] + gpot[pair * r + t]) / eps);
+    if (side == 0) gamma1[(g * n + i) * r + t] = v;
+    else gamma2[(g * r + t) * n + i] = v;
+}
+
+// Y'[g][t][c] = (sum_j gamma2[g][t][j] V[g][j][c]) / beta_t ; one block per (g, t), thread per c.
+template <typename T>
+__global__ void ref_reduce_y(const float* __restrict__ gamma2, const T* __restrict__ V,
+                             const float* __restrict__ beta, float* __restrict__ Y,
+                             int H, int n, int r, int dv)
+{
+    const int g = blockIdx.x / r, t = blockIdx.x % r;
+    const float* row = gamma2 + ((size_t)g * r + t) * n;
+    for (int c = threadIdx.x; c < dv; c += blockDim.x) {
+        float acc = 0.f;
+        for (int j = 0; j < n; ++j) acc = fmaf(row[j], ld(V, ((size_t)g * n + j) * dv + c), acc);
+        Y[((size_t)g * r + t) * dv + c] = acc / beta[(g % H) * r + t];
+    }
+}
+
+// O[g][i][c] = n * sum_t gamma1[g][i][t] Y'[g][t][c]
+template <typename T>
+__global__ void ref_expand(const float* __restrict__ gamma1, const float* __restrict__ Y,
+                           T* __restrict__ out, size_t total, int n, int r, int dv)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const size_t gi = idx / dv;           // g * n + i
+    const int c = (int)(idx % dv);
+    const size_t g = gi / n;
+    float acc = 0.f;
+    for (int t = 0; t < r; ++t) acc = fmaf(gamma1[gi * r + t], Y[(g * r + t) * dv + c], acc);
+    st(out, idx, (float)n * acc);
+}
+
+inline unsigned blocks_for(size_t count, int threads) { return (unsigned)((count + threads - 1) / threads); }
+
+template <typename T>
+int run_reference_t(const Args& a, bool want_out)
+{
+    const lot_shape& s = a.s;
+    const int G = s.B * s.H, n = s.n, r = s.r, pairs = 2 * G;
+    const int chunks = (n + kRefChunk - 1) / kRefChunk;
+    float* C = (float*)(a.ws + a.lay.C);
+    float* f = (float*)(a.ws + a.lay.f);
+    float* g = (float*)(a.ws + a.lay.g);
+    float* pm = (float*)(a.ws + a.lay.part_m);
+    float* ps = (float*)(a.ws + a.lay.part_s);
+    float* Y = (float*)(a.ws + a.lay.Y);
+    const size_t nelem = (size_t)pairs * n * r;
+    const size_t rows = (size_t)pairs * n;
+    hipStream_t st_ = a.stream;
+
+    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, s.d_k, r,
+                                                         s.io_dtype == LOT_BF16);
+    ref_zero<<<blocks_for((size_t)pairs * r, 256), 256, 0, st_>>>(g, (size_t)pairs * r);
+    for (int it = 0; it < a.iters; ++it) {
+        ref_f_update<<<blocks_for(rows, 256), 256, 0, st_>>>(C, g, f, rows, n, r, a.eps);
+        ref_g_partial<<<(unsigned)pairs * chunks, 64, 0, st_>>>(C, f, pm, ps, n, r, chunks, a.eps);
+        ref_g_final<<<blocks_for((size_t)pairs * r, 256), 256, 0, st_>>>(pm, ps, a.beta, g, pairs, G, s.H, r, chunks, a.eps);
+    }
+    ref_couplings<<<blocks_for(nelem, 256), 256, 0, st_>>>(C, f, g, a.gamma1, a.gamma2, G, n, r, a.eps);
+    if (want_out) {
+        ref_reduce_y<T><<<(unsigned)G * r, 64, 0, st_>>>(a.gamma2, (const T*)a.V, a.beta, Y, s.H, n, r, s.d_v);
+        const size_t total = (size_t)G * n * s.d_v;
+        ref_expand<T><<<blocks_for(total, 256), 256, 0, st_>>>(a.gamma1, Y, (T*)a.out, total, n, r, s.d_v);
+    }
+    LOT_HIP_CHECK(hipGetLastError());
+    return LOT_OK;
+}
+
+}  // namespace
+
+int run_reference(const Args& a, bool want_out)
+{
+    return a.s.io_dtype == LOT_BF16 ? run_reference_t<uint16_t>(a, want_out) : run_reference_t<float>(a, want_out);
+}
+
+}  // namespace lot

@@ -1,0 +1,92 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and rejects bad
+arguments before touching the device (so none of this needs a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_23436_amd import lot
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(lot.LIB_PATH):
+        from paper_2509_23436_amd import build
+        build.build()
+    return lot.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "lot.h")).read()
+    declared = set(re.findall(r"\b(lot_[a-z_]+)\s*\(", header))
+    assert declared == set(lot.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert L.lot_version() >= 100
+
+
+def _shape(**kw):
+    base = dict(B=1, H=1, n=64, d_k=32, d_v=32, r=8, io_dtype=0)
+    base.update(kw)
+    return lot.lot_shape(**base)
+
+
+def test_workspace_bytes_and_shape_validation(L):
+    out = ctypes.c_size_t(0)
+    assert L.lot_workspace_bytes(ctypes.byref(_shape()), 5, ctypes.byref(out)) == 0
+    assert out.value > 0 and out.value % 256 == 0
+    big = ctypes.c_size_t(0)
+    assert L.lot_workspace_bytes(ctypes.byref(_shape(n=4096)), 5, ctypes.byref(big)) == 0
+    assert big.value > out.value
+    for bad in (dict(n=0), dict(r=0), dict(B=0), dict(H=-1), dict(d_k=0), dict(d_v=0), dict(n=1 << 25),
+                dict(d_k=30), dict(d_v=6)):
+        assert L.lot_workspace_bytes(ctypes.byref(_shape(**bad)), 5, ctypes.byref(out)) == -2, bad
+    assert L.lot_workspace_bytes(ctypes.byref(_shape(io_dtype=7)), 5, ctypes.byref(out)) == -5
+    assert L.lot_workspace_bytes(ctypes.byref(_shape()), 0, ctypes.byref(out)) == -4
+    assert L.lot_workspace_bytes(None, 5, ctypes.byref(out)) == -1
+    assert L.lot_workspace_bytes(ctypes.byref(_shape()), 5, None) == -1
+
+
+def _call_fwd(L, shape=None, Q=4096, K=8192, V=12288, Z=256, beta=512, eps=0.1, iters=5, out=16384,
+              ws=1 << 20, ws_bytes=1 << 40, path=0):
+    shape = shape or _shape()
+    vp = ctypes.c_void_p
+    return L.lot_attention_fwd_path(ctypes.byref(shape), vp(Q), vp(K), vp(V), vp(Z), vp(beta), ctypes.c_float(eps),
+                                    iters, vp(out), vp(ws), ws_bytes, None, path)
+
+
+def test_attention_rejects_bad_arguments_before_any_device_work(L):
+    # the pointers are fake: every one of these must return before they are used
+    for kw, code in ((dict(Q=0), -1), (dict(K=0), -1), (dict(V=0), -1), (dict(Z=0), -1), (dict(beta=0), -1),
+                     (dict(out=0), -1), (dict(ws=0), -1),
+                     (dict(eps=0.0), -3), (dict(eps=-1.0), -3), (dict(eps=float("nan")), -3),
+                     (dict(eps=float("inf")), -3), (dict(iters=0), -4),
+                     (dict(Q=4100), -7), (dict(V=12290), -7), (dict(out=16388), -7),
+                     (dict(ws=(1 << 20) + 64), -6), (dict(ws_bytes=1024), -6),
+                     (dict(path=9), -9), (dict(shape=_shape(d_k=128, d_v=128), path=2), -9),
+                     (dict(shape=_shape(r=65), path=2), -9),
+                     (dict(shape=_shape(n=0)), -2), (dict(shape=_shape(io_dtype=3)), -5)):
+        assert _call_fwd(L, **kw) == code, (kw, code)
+
+
+def test_couplings_rejects_bad_arguments(L):
+    vp = ctypes.c_void_p
+    s = _shape()
+
+    def call(g1=4096, g2=8192, eps=0.1, iters=3, ws_bytes=1 << 40):
+        return L.lot_couplings(ctypes.byref(s), vp(256), vp(512), vp(1024), vp(2048), ctypes.c_float(eps), iters,
+                               vp(g1), vp(g2), vp(1 << 20), ws_bytes, None)
+    assert call(g1=0) == -1 and call(g2=0) == -1
+    assert call(eps=0.0) == -3 and call(iters=-2) == -4 and call(ws_bytes=0) == -6
+
+
+def test_strerror_texts(L):
+    for code in range(0, -11, -1):
+        if code == -8:
+            continue
+        text = L.lot_strerror(code).decode()
+        assert text and text != "unknown status"
+    assert L.lot_strerror(-99).decode() == "unknown status"

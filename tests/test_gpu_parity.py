@@ -1,0 +1,137 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle, element by element,
+on the same seeded inputs.  Bars (stated for the target): fp32 I/O max-norm relative error on O
+<= 1e-4 and marginal-residual error <= 1e-5; bf16 I/O with fp32 accumulation <= 2e-2 on O."""
+import functools
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2509_23436_amd import synth
+from util import rel_max_err, to_device, to_host_f64, tolerance
+
+pytestmark = pytest.mark.gpu
+
+S = synth.shrink
+W = synth.WORKLOADS
+
+# Sizes the oracle finishes in seconds, still spanning several tiles and ragged tails.
+CASES = {
+    "tiny": W["tiny"],
+    "deit_tiny": W["deit_tiny"],
+    "bert_base_b4": S(W["bert_base"], B=4),
+    "swin_t_s1_b2": S(W["swin_t_s1"], B=2),
+    "long_4k_h2": S(W["long_4k"], B=1, H=2),
+    "ragged_f32": S(W["tiny"], B=2, H=2, n=77, d=32, r=5, iters=7, seed=21),
+    "ragged_bf16": S(W["bert_base"], B=1, H=3, n=1000, d=64, r=33, iters=4, seed=22),
+    "one_token": S(W["tiny"], n=1, r=3, iters=2, seed=23),
+    "n31_r1": S(W["tiny"], n=31, r=1, iters=3, seed=24),
+    "n33_r64_bf16": S(W["bert_base"], B=1, H=2, n=33, r=64, iters=5, seed=25),
+    "f32_d64_r64": S(W["tiny"], B=1, H=2, n=300, d=64, r=64, iters=6, seed=26),
+    "bf16_d32_r8": S(W["swin_t_s1"], B=1, H=2, n=500, d=32, r=8, iters=6, seed=27),
+    "eps_small": S(W["tiny"], n=256, d=32, r=16, eps=0.02, iters=8, seed=28),
+    "eps_large": S(W["tiny"], n=256, d=32, r=16, eps=5.0, iters=3, seed=29),
+}
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@functools.lru_cache(maxsize=None)
+def _oracle_case(name):
+    from oracle import lot_oracle
+    w = CASES[name]
+    x = synth.make_inputs(w)
+    O, g1, g2, _ = lot_oracle.attention(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters,
+                                        want_couplings=True, threads=16)
+    return x, O, g1, g2
+
+
+
+@pytest.mark.parametrize("path_name", ["reference", "fused", "auto"])
+@pytest.mark.parametrize("name", list(CASES))
+def test_attention_and_couplings_match_oracle(name, path_name):
+    import torch
+    from oracle import lot_oracle
+    from paper_2509_23436_amd import lot
+    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED, "auto": lot.PATH_AUTO}[path_name]
+    w = CASES[name]
+    _say("case %s path %s: %r" % (name, path_name, w))
+    x, O_ref, g1_ref, g2_ref = _oracle_case(name)
+    dev = to_device(x, w.dtype)
+    shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
+    ws = lot.alloc_workspace(shape, w.iters)
+    ws.zero_()
+    tol_o, tol_m = tolerance(w.dtype)
+
+    out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters,
+                                workspace=ws, path=path)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(ws) == 0
+    O = to_host_f64(out)
+    assert np.isfinite(O).all()
+    err = rel_max_err(O, O_ref)
+    _say("  O: max-norm rel err %.3e (bar %.0e), max abs %.3e" % (err, tol_o, np.abs(O - O_ref).max()))
+    assert err <= tol_o
+
+    g1, g2 = lot.lot_couplings(dev["Q"], dev["K"], dev["Z"], dev["beta"], w.eps, w.iters, workspace=ws, path=path)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(ws) == 0
+    g1, g2 = to_host_f64(g1), to_host_f64(g2)
+    res = lot_oracle.marginal_residuals(g1, g2, x["beta"])
+    res_ref = lot_oracle.marginal_residuals(g1_ref, g2_ref, x["beta"])
+    merr = max(float(np.abs(a - b).max()) for a, b in zip(res, res_ref))
+    piv = max(float(np.abs(res[1]).max()), float(np.abs(res[3]).max()))
+    gerr = max(rel_max_err(g1, g1_ref), rel_max_err(g2, g2_ref))
+    _say("  marginal residual err %.3e, pivot-side residual %.3e (bar %.0e), couplings rel err %.3e"
+         % (merr, piv, tol_m, gerr))
+    assert merr <= tol_m
+    assert piv <= tol_m
+    assert gerr <= 1e-4
+
+
+@pytest.mark.parametrize("path_name", ["reference", "fused"])
+def test_runs_are_bit_identical(path_name):
+    import torch
+    from paper_2509_23436_amd import lot
+    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED}[path_name]
+    w = CASES["swin_t_s1_b2"]
+    x, *_ = _oracle_case("swin_t_s1_b2")
+    dev = to_device(x, w.dtype)
+    outs = []
+    for _ in range(3):
+        out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, path=path)
+        torch.cuda.synchronize()
+        outs.append(out.view(torch.int16).cpu().numpy().copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+@pytest.mark.parametrize("eps", [0.01, 100.0])
+@pytest.mark.parametrize("path_name", ["reference", "fused"])
+def test_extreme_eps_of_the_ablation_sweep_stay_finite(eps, path_name):
+    import torch
+    from paper_2509_23436_amd import lot
+    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED}[path_name]
+    w = S(W["long_4k"], B=1, H=2, n=2048, eps=eps, seed=31)
+    dev = to_device(synth.make_inputs(w), w.dtype)
+    out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, path=path)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+
+
+def test_reference_path_takes_shapes_outside_the_fused_set():
+    # d_v != d_k, r > 64: only the reference kernels apply; AUTO must route there by itself.
+    import torch
+    from oracle import lot_oracle
+    from paper_2509_23436_amd import lot
+    w = S(W["tiny"], B=1, H=2, n=150, d=16, r=80, iters=4, seed=32)
+    x = synth.make_inputs(w, d_v=24)
+    O_ref, _ = lot_oracle.attention(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, threads=4)
+    dev = to_device(x, w.dtype)
+    out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters)
+    torch.cuda.synchronize()
+    assert rel_max_err(to_host_f64(out), O_ref) <= 1e-4
+    with pytest.raises(lot.LotError):
+        lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, path=lot.PATH_FUSED)
