@@ -1,4 +1,728 @@
+// Fused execution path of libLOT: the whole LOT attention forward in one persistent kernel.
+//
+// Work decomposition.  A "pair" is one (batch*head problem, side) with side 0 = keys and
+// side 1 = queries; the two Sinkhorn solves of a problem are independent until the very end
+// (paper, Method: the two entropic problems share only Z, beta and eps).  Each pair is split
+// over `cluster` workgroups ("chunks" of consecutive 32-token tiles).  A workgroup has four
+// wavefronts; a wavefront owns every fourth tile of the chunk.
+//
+// One Sinkhorn iteration is ONE pass over the chunk's tokens.  For a tile of 32 tokens the
+// similarities C^T (pivots x tokens) come out of MFMA with the pivots as the M dimension, the
+// current pivot potential g added for free through the accumulator input, so that a lane owns
+// one token and 16*RB of its pivots:
+//     m_i = max_t (C_it + g_t),  e_it = exp((C_it + g_t - m_i)/eps),  s_i = sum_t e_it
+// is the token-side update (f_i is implicit: a_i e_it / s_i is the coupling after it), and the
+// pivot-side update needs only the column sums of e_it / s_i, accumulated per lane across the
+// tiles and reduced once per pass: lanes -> wavefront -> workgroup (LDS) -> cluster (global
+// partials in a fixed order, so results are bit-reproducible):
+//     g_t += eps * log(n beta_t / sum_i e_it/s_i).
+// The last key-side pass also accumulates U = sum_j (e_jt/s_j) V_j with MFMA (the coupling tile
+// is transposed through LDS), giving Y'_t = U_t / colsum_t = (Gamma2 V)_t / beta_t.  The query
+// side runs one more pass that rebuilds its coupling tile and multiplies it with
+// Y''_t = n beta_t/colsum_t * Y'_t by MFMA to write O (paper: "Rank and complexity", factored
+// apply O = Gamma1 (Diag(beta)^-1 (Gamma2 V)), times n so that the attention matrix is doubly
+// stochastic).  lot_couplings runs the same passes and stores the coupling tiles instead.
+//
+// Cross-workgroup waits are bounded: a wait that exceeds its poll budget raises the status word
+// in the workspace and the workgroup leaves the kernel, so every wavefront always exits.
 #include "lot_internal.h"
+
 namespace lot {
-int run_fused(const Args&, bool) { return LOT_ERR_PATH; }
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kNegBig = -1.0e30f;   // potential of a padding pivot: its exponential is exactly 0
+constexpr int kTrStride = 40;         // uint16 per row of the transposed coupling tile (32 + 8 pad)
+constexpr float kLog2e = 1.44269504088896340736f;
+
+enum { EPI_NONE = 0, EPI_ACCUM_U = 1, EPI_EXPAND = 2, EPI_GAMMA = 3 };
+enum { MODE_ATTENTION = 0, MODE_COUPLINGS = 1 };
+
+struct FusedParams {
+    const void* Q;
+    const void* K;
+    const void* V;
+    const float* Z;
+    const float* beta;
+    void* out;
+    float* gamma1;
+    float* gamma2;
+    uint32_t* status;
+    uint32_t* arrive;     // [pairs]
+    uint32_t* yready;     // [G]
+    float* colsum_part;   // [pairs][2][cluster_cap][64]
+    float* u_part;        // [G][cluster_cap][64][D]
+    float* y_tile;        // [G][64][D]
+    int G, H, n, r;
+    int cluster, cluster_cap, tiles_per_wg, num_items, iters, mode;
+    float eps;
+    uint32_t spin_limit;
+};
+
+// ---------------------------------------------------------------------------------------------
+// small device helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float rcp_fast(float x) { return __builtin_amdgcn_rcpf(x); }
+
+// Combine a value with the one held by the lane 32 away (same token, other half of the pivots).
+// v_permlane32_swap with both operands equal to x leaves x[lane % 32] in the first result and
+// x[32 + lane % 32] in the second, in every lane.  The results are copied to scalars before the
+// bit cast: casting the vector elements in place reads the first element twice with this compiler.
+__device__ __forceinline__ void both_halves(float x, float& lo, float& hi)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const unsigned r0 = r[0], r1 = r[1];
+    lo = __builtin_bit_cast(float, r0);
+    hi = __builtin_bit_cast(float, r1);
 }
+__device__ __forceinline__ float pair_max(float x)
+{
+    float lo, hi;
+    both_halves(x, lo, hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float pair_sum(float x)
+{
+    float lo, hi;
+    both_halves(x, lo, hi);
+    return lo + hi;
+}
+
+template <int CTRL> __device__ __forceinline__ float dpp_move(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+// sum over the 32 lanes that share (lane >> 5); the result is exact-order only in lane 0 / 32
+__device__ __forceinline__ float sum_over_tokens(float x)
+{
+    x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
+    x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
+    x += dpp_move<0x124>(x);   // row_ror 4
+    x += dpp_move<0x128>(x);   // row_ror 8
+    x += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0x401F));  // lane ^ 16
+    return x;
+}
+
+__device__ __forceinline__ float ld_coherent(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coherent(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void split_bf16(const f32x8& x, bf16x8& hi, bf16x8& lo)
+{
+    hi = __builtin_convertvector(x, bf16x8);
+    const f32x8 back = __builtin_convertvector(hi, f32x8);
+    lo = __builtin_convertvector(x - back, bf16x8);
+}
+__device__ __forceinline__ uint16_t bf16_bits_of(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
+
+// Poll *counter until it reaches target.  Thread 0 only.  False if the budget ran out or another
+// workgroup already gave up.
+__device__ inline bool spin_until(uint32_t* counter, uint32_t target, uint32_t* status, uint32_t limit)
+{
+    for (uint32_t k = 0; k < limit; ++k) {
+        if (__hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= target) return true;
+        if ((k & 63u) == 63u && __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return false;
+        __builtin_amdgcn_s_sleep(2);
+    }
+    return false;
+}
+
+// ---------------------------------------------------------------------------------------------
+// operand fragments of the similarity MFMA
+// ---------------------------------------------------------------------------------------------
+// bf16: v_mfma_f32_32x32x16_bf16, lane (i = lane % 32, kg = lane / 32) supplies, for step s,
+//       elements [16 s + 8 kg, +8) of row i.                       D/16 steps.
+// fp32: v_mfma_f32_32x32x2_f32, lane supplies element kg*(D/2) + s. D/2 steps.
+template <typename IO, int D> struct Frag;
+template <int D> struct Frag<uint16_t, D> { bf16x8 v[D / 16]; };
+template <int D> struct Frag<float, D> { float v[D / 2]; };
+
+template <int D>
+__device__ __forceinline__ void load_tokens(Frag<uint16_t, D>& f, const uint16_t* row, int kg)
+{
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) f.v[s] = *reinterpret_cast<const bf16x8*>(row + 16 * s + 8 * kg);
+}
+template <int D>
+__device__ __forceinline__ void load_tokens(Frag<float, D>& f, const float* row, int kg)
+{
+#pragma unroll
+    for (int q = 0; q < D / 8; ++q) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(row + kg * (D / 2) + 4 * q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f.v[4 * q + e] = t[e];
+    }
+}
+
+// pivot rows: Z is fp32 in memory; the bf16 path rounds it to bf16 (nearest even) here
+template <int D>
+__device__ __forceinline__ void load_pivots(Frag<uint16_t, D>& f, const float* zrow, int kg, bool valid)
+{
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+        f32x8 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = valid ? zrow[16 * s + 8 * kg + e] : 0.f;
+        f.v[s] = __builtin_convertvector(t, bf16x8);
+    }
+}
+template <int D>
+__device__ __forceinline__ void load_pivots(Frag<float, D>& f, const float* zrow, int kg, bool valid)
+{
+#pragma unroll
+    for (int s = 0; s < D / 2; ++s) f.v[s] = valid ? zrow[kg * (D / 2) + s] : 0.f;
+}
+
+// acc[mb] = Z_block(mb) X_tile^T + G[mb]   (pivots x tokens)
+template <int D, int RB>
+__device__ __forceinline__ void similarity(f32x16 (&acc)[RB], const Frag<uint16_t, D> (&zf)[RB],
+                                           const Frag<uint16_t, D>& xf, const f32x16 (&G)[RB])
+{
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zf[mb].v[0], xf.v[0], G[mb], 0, 0, 0);
+#pragma unroll
+    for (int s = 1; s < D / 16; ++s)
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zf[mb].v[s], xf.v[s], acc[mb], 0, 0, 0);
+}
+template <int D, int RB>
+__device__ __forceinline__ void similarity(f32x16 (&acc)[RB], const Frag<float, D> (&zf)[RB],
+                                           const Frag<float, D>& xf, const f32x16 (&G)[RB])
+{
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(zf[mb].v[0], xf.v[0], G[mb], 0, 0, 0);
+#pragma unroll
+    for (int s = 1; s < D / 2; ++s)
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(zf[mb].v[s], xf.v[s], acc[mb], 0, 0, 0);
+}
+
+// pivot index of accumulator register j of block mb in lane-half kg
+__device__ __forceinline__ int pivot_of(int mb, int j, int kg) { return 32 * mb + 8 * (j >> 2) + 4 * kg + (j & 3); }
+
+// load a per-pivot vector from LDS into accumulator layout
+template <int RB>
+__device__ __forceinline__ void load_pivot_vector(f32x16 (&dst)[RB], const float* src, int kg)
+{
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 t = *reinterpret_cast<const f32x4*>(src + 32 * mb + 8 * q + 4 * kg);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[mb][4 * q + e] = t[e];
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// values / output element access by I/O type
+// ---------------------------------------------------------------------------------------------
+// Loads V[token][NB*i + nb], nb < NB, for 8 tokens and returns them as MFMA B fragments (hi, lo).
+template <int D>
+__device__ __forceinline__ void load_values(bf16x8 (&hi)[D / 32], bf16x8 (&lo)[D / 32], const uint16_t* V,
+                                            size_t row0, int n_left, int i)
+{
+    constexpr int NB = D / 32;
+    union { bf16x8 v; uint16_t u[8]; } h[NB];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const size_t row = row0 + (e < n_left ? e : n_left - 1);
+        if (NB == 2) {
+            const uint32_t w = *reinterpret_cast<const uint32_t*>(V + row * D + 2 * i);
+            h[0].u[e] = (uint16_t)(w & 0xffffu);
+            h[NB - 1].u[e] = (uint16_t)(w >> 16);
+        } else {
+            h[0].u[e] = V[row * D + i];
+        }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) { hi[nb] = h[nb].v; lo[nb] = h[nb].v; }
+}
+template <int D>
+__device__ __forceinline__ void load_values(bf16x8 (&hi)[D / 32], bf16x8 (&lo)[D / 32], const float* V,
+                                            size_t row0, int n_left, int i)
+{
+    constexpr int NB = D / 32;
+    f32x8 t[NB];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const size_t row = row0 + (e < n_left ? e : n_left - 1);
+        if (NB == 2) {
+            const f32x2 w = *reinterpret_cast<const f32x2*>(V + row * D + 2 * i);
+            t[0][e] = w[0];
+            t[NB - 1][e] = w[1];
+        } else {
+            t[0][e] = V[row * D + i];
+        }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) split_bf16(t[nb], hi[nb], lo[nb]);
+}
+
+template <int NB> __device__ __forceinline__ void store_out(uint16_t* row, int i, float a, float b)
+{
+    if (NB == 2) *reinterpret_cast<uint32_t*>(row + 2 * i) = (uint32_t)bf16_bits_of(a) | ((uint32_t)bf16_bits_of(b) << 16);
+    else row[i] = bf16_bits_of(a);
+}
+template <int NB> __device__ __forceinline__ void store_out(float* row, int i, float a, float b)
+{
+    if (NB == 2) { f32x2 w; w[0] = a; w[1] = b; *reinterpret_cast<f32x2*>(row + 2 * i) = w; }
+    else row[i] = a;
+}
+
+template <typename IO> struct io_is_f32 { static constexpr bool value = false; };
+template <> struct io_is_f32<float> { static constexpr bool value = true; };
+
+// ---------------------------------------------------------------------------------------------
+// one pass over this wavefront's tiles
+// ---------------------------------------------------------------------------------------------
+template <typename IO, int D, int RB, int EPI>
+__device__ __forceinline__ void run_pass(
+    const FusedParams& p, const IO* __restrict__ X, int g, int side, int tile_begin, int tile_end,
+    int lane, int wave, float c1,
+    const Frag<IO, D> (&zf)[RB], const f32x16 (&G)[RB], f32x16 (&cs)[RB],
+    const IO* __restrict__ V, f32x16 (&U)[RB][D / 32], uint16_t* tr_hi, uint16_t* tr_lo,
+    const bf16x8* yf_hi, const bf16x8* yf_lo, IO* __restrict__ out)
+{
+    constexpr int NB = D / 32;
+    const int i = lane & 31, kg = lane >> 5;
+    const int n = p.n;
+    int tile = tile_begin + wave;
+    if (tile >= tile_end) return;
+
+    Frag<IO, D> xc;
+    {
+        const int tok = min(tile * kTileTokens + i, n - 1);
+        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
+    }
+    for (; tile < tile_end; tile += kFusedWaves) {
+        Frag<IO, D> xn = xc;
+        if (tile + kFusedWaves < tile_end) {
+            const int tok = min((tile + kFusedWaves) * kTileTokens + i, n - 1);
+            load_tokens<D>(xn, X + ((size_t)g * n + tok) * D, kg);
+        }
+
+        f32x16 acc[RB];
+        similarity<D, RB>(acc, zf, xc, G);
+
+        // token-side update: row maximum, exponentials, row sum
+        float m0 = acc[0][0], m1 = acc[0][1], m2 = acc[0][2], m3 = acc[0][3];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = (mb == 0 ? 4 : 0); j < 16; j += 4) {
+                m0 = fmaxf(m0, acc[mb][j]);
+                m1 = fmaxf(m1, acc[mb][j + 1]);
+                m2 = fmaxf(m2, acc[mb][j + 2]);
+                m3 = fmaxf(m3, acc[mb][j + 3]);
+            }
+        const float m = pair_max(fmaxf(fmaxf(m0, m1), fmaxf(m2, m3)));
+        const float mc = m * c1;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; j += 4) {
+                const float e0 = exp2_fast(fmaf(acc[mb][j], c1, -mc));
+                const float e1 = exp2_fast(fmaf(acc[mb][j + 1], c1, -mc));
+                const float e2 = exp2_fast(fmaf(acc[mb][j + 2], c1, -mc));
+                const float e3 = exp2_fast(fmaf(acc[mb][j + 3], c1, -mc));
+                acc[mb][j] = e0; acc[mb][j + 1] = e1; acc[mb][j + 2] = e2; acc[mb][j + 3] = e3;
+                s0 += e0; s1 += e1; s2 += e2; s3 += e3;
+            }
+        const float s = pair_sum((s0 + s1) + (s2 + s3));
+        const int tok = tile * kTileTokens + i;
+        const float w = tok < n ? rcp_fast(s) : 0.f;    // tokens past the end carry no mass
+
+        if (EPI == EPI_NONE || EPI == EPI_ACCUM_U) {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) cs[mb][j] = fmaf(acc[mb][j], w, cs[mb][j]);
+        }
+
+        if (EPI == EPI_ACCUM_U) {
+            // transpose the coupling tile (tokens in lanes -> tokens along K) through LDS as bf16 hi + lo
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const float v = acc[mb][j] * w;
+                    const __bf16 h = (__bf16)v;
+                    const __bf16 l = (__bf16)(v - (float)h);
+                    const int pv = pivot_of(mb, j, kg);
+                    tr_hi[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, h);
+                    tr_lo[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, l);
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                bf16x8 vh[NB], vl[NB];
+                const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
+                const int left = max(1, min(8, n - t0));
+                load_values<D>(vh, vl, V, (size_t)g * n + min(t0, n - 1), left, i);
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb) {
+                    const bf16x8 ah = *reinterpret_cast<const bf16x8*>(tr_hi + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
+                    const bf16x8 al = *reinterpret_cast<const bf16x8*>(tr_lo + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vh[nb], U[mb][nb], 0, 0, 0);
+                        U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, vh[nb], U[mb][nb], 0, 0, 0);
+                        if (io_is_f32<IO>::value)
+                            U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vl[nb], U[mb][nb], 0, 0, 0);
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        if (EPI == EPI_EXPAND) {
+            f32x16 oacc[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) oacc[nb][j] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 2 * RB; ++s) {
+                f32x8 wv;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wv[e] = acc[s >> 1][8 * (s & 1) + e] * w;
+                bf16x8 ah, al;
+                split_bf16(wv, ah, al);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const bf16x8 yh = yf_hi[(s * NB + nb) * 64 + lane];
+                    oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, yh, oacc[nb], 0, 0, 0);
+                    oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, yh, oacc[nb], 0, 0, 0);
+                    if (io_is_f32<IO>::value) {
+                        const bf16x8 yl = yf_lo[(s * NB + nb) * 64 + lane];
+                        oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, yl, oacc[nb], 0, 0, 0);
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int tr = tile * kTileTokens + 8 * (j >> 2) + 4 * kg + (j & 3);
+                if (tr < n) store_out<NB>(out + ((size_t)g * n + tr) * D, i, oacc[0][j], oacc[NB - 1][j]);
+            }
+        }
+
+        if (EPI == EPI_GAMMA) {
+            // cs holds rho_t = beta_t / colsum_t in accumulator layout
+            if (tok < n) {
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int pv = pivot_of(mb, j, kg);
+                        if (pv < p.r) {
+                            const float v = acc[mb][j] * w * cs[mb][j];
+                            if (side == 1) p.gamma1[((size_t)g * n + tok) * p.r + pv] = v;
+                            else p.gamma2[((size_t)g * p.r + pv) * n + tok] = v;
+                        }
+                    }
+            }
+        }
+        xc = xn;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// the kernel
+// ---------------------------------------------------------------------------------------------
+template <typename IO, int D, int RB>
+__global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams p)
+{
+    constexpr int NB = D / 32;
+    __shared__ float s_wave_part[kFusedWaves][64];
+    __shared__ float s_g[64];
+    __shared__ float s_rho[64];        // beta_t / colsum_t after the last iteration
+    __shared__ float s_csinv[64];      // 1 / colsum_t after the last iteration
+    __shared__ __attribute__((aligned(16))) float s_u[64 * D];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kFusedWaves * 2 * 64 * kTrStride];
+    __shared__ int s_ok;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 31, kg = lane >> 5;
+    const int n = p.n, r = p.r;
+    const float c1 = kLog2e / p.eps;
+    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    uint16_t* tr_hi = s_tr + (wave * 2 + 0) * 64 * kTrStride;
+    uint16_t* tr_lo = s_tr + (wave * 2 + 1) * 64 * kTrStride;
+    bf16x8* yf_hi = reinterpret_cast<bf16x8*>(s_tr);
+    bf16x8* yf_lo = yf_hi + 2 * RB * NB * 64;
+
+    for (int item = blockIdx.x; item < p.num_items; item += gridDim.x) {
+        const int pair = item / p.cluster, chunk = item % p.cluster;
+        const int g = pair >> 1, side = pair & 1, h = g % p.H;
+        const IO* X = reinterpret_cast<const IO*>(side ? p.Q : p.K);
+        const int tile_begin = chunk * p.tiles_per_wg;
+        const int tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
+        uint32_t* arrive = p.arrive + pair;
+        const float* beta = p.beta + (size_t)h * r;
+
+        Frag<IO, D> zf[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) {
+            const int t = 32 * mb + i;
+            load_pivots<D>(zf[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
+        }
+        if (tid < 64) s_g[tid] = tid < r ? 0.f : kNegBig;
+        __syncthreads();
+        f32x16 G[RB], cs[RB], U[RB][NB];
+        load_pivot_vector<RB>(G, s_g, kg);
+        const bool fuse_u = side == 0 && p.mode == MODE_ATTENTION;
+
+        for (int it = 1; it <= p.iters; ++it) {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) cs[mb][j] = 0.f;
+            const bool last = it == p.iters;
+            if (last && fuse_u) {
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
+                run_pass<IO, D, RB, EPI_ACCUM_U>(p, X, g, side, tile_begin, tile_end, lane, wave, c1, zf, G, cs,
+                                                 reinterpret_cast<const IO*>(p.V), U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
+            } else {
+                run_pass<IO, D, RB, EPI_NONE>(p, X, g, side, tile_begin, tile_end, lane, wave, c1, zf, G, cs,
+                                              nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
+            }
+
+            // column sums: lanes -> wavefront -> workgroup
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) cs[mb][j] = sum_over_tokens(cs[mb][j]);
+            if (i == 0) {
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        f32x4 t;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) t[e] = cs[mb][4 * q + e];
+                        *reinterpret_cast<f32x4*>(&s_wave_part[wave][32 * mb + 8 * q + 4 * kg]) = t;
+                    }
+            }
+            if (last && fuse_u) {
+                // workgroup total of U in s_u, one wavefront at a time (fixed order)
+                for (int turn = 0; turn < kFusedWaves; ++turn) {
+                    if (wave == turn) {
+#pragma unroll
+                        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                                for (int j = 0; j < 16; ++j) {
+                                    float* dst = &s_u[pivot_of(mb, j, kg) * D + NB * i + nb];
+                                    *dst = turn == 0 ? U[mb][nb][j] : *dst + U[mb][nb][j];
+                                }
+                    }
+                    __syncthreads();
+                }
+            } else {
+                __syncthreads();
+            }
+
+            float tot = 0.f;
+            if (tid < 64) {
+                tot = s_wave_part[0][tid];
+                tot += s_wave_part[1][tid];
+                tot += s_wave_part[2][tid];
+                tot += s_wave_part[3][tid];
+            }
+            if (p.cluster > 1) {
+                float* slot = p.colsum_part + (((size_t)pair * 2 + (it & 1)) * p.cluster_cap + chunk) * 64;
+                if (tid < 64) st_coherent(slot + tid, tot);
+                if (last && fuse_u) {
+                    float* up = p.u_part + ((size_t)g * p.cluster_cap + chunk) * 64 * D;
+                    for (int e = tid; e < 64 * D; e += kFusedThreads) st_coherent(up + e, s_u[e]);
+                }
+                __syncthreads();
+                if (tid == 0) {
+                    __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                    const bool ok = spin_until(arrive, (uint32_t)p.cluster * (uint32_t)it, p.status, p.spin_limit);
+                    if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    s_ok = ok;
+                }
+                __syncthreads();
+                if (!s_ok) return;
+                if (tid < 64) {
+                    const float* base = p.colsum_part + ((size_t)pair * 2 + (it & 1)) * p.cluster_cap * 64;
+                    tot = 0.f;
+                    for (int k = 0; k < p.cluster; ++k) tot += ld_coherent(base + (size_t)k * 64 + tid);
+                }
+            }
+            if (tid < 64) {
+                if (tid < r) {
+                    const float c = fmaxf(tot, 1.0e-37f);
+                    const float b = beta[tid];
+                    s_g[tid] += p.eps * logf((float)n * b / c);
+                    s_rho[tid] = b / c;
+                    s_csinv[tid] = 1.f / c;
+                } else {
+                    s_rho[tid] = 0.f;
+                    s_csinv[tid] = 0.f;
+                }
+            }
+            __syncthreads();
+            if (!last) load_pivot_vector<RB>(G, s_g, kg);   // the last pass's potentials stay for the epilogue
+        }
+
+        if (p.mode == MODE_COUPLINGS) {
+            load_pivot_vector<RB>(cs, s_rho, kg);
+            run_pass<IO, D, RB, EPI_GAMMA>(p, X, g, side, tile_begin, tile_end, lane, wave, c1, zf, G, cs,
+                                           nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
+        } else if (side == 0) {
+            // key side: Y'_t = U_t / colsum_t, written to global for the query side
+            float* yt = p.y_tile + (size_t)g * 64 * D;
+            if (p.cluster == 1) {
+                for (int e = tid; e < 64 * D; e += kFusedThreads) st_coherent(yt + e, s_u[e] * s_csinv[e / D]);
+            } else {
+                const int per = (64 * D + p.cluster - 1) / p.cluster;
+                const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
+                const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
+                for (int e = e0 + tid; e < e1; e += kFusedThreads) {
+                    float acc = 0.f;
+                    for (int k = 0; k < p.cluster; ++k) acc += ld_coherent(up + (size_t)k * 64 * D + e);
+                    st_coherent(yt + e, acc * s_csinv[e / D]);
+                }
+            }
+            __syncthreads();
+            if (tid == 0) __hip_atomic_fetch_add(p.yready + g, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            // query side: wait for Y', fold n * rho_t into it, lay it out as MFMA B fragments, expand
+            if (tid == 0) {
+                const bool ok = spin_until(p.yready + g, (uint32_t)p.cluster, p.status, p.spin_limit);
+                if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_ok = ok;
+            }
+            __syncthreads();
+            if (!s_ok) return;
+            const float* yt = p.y_tile + (size_t)g * 64 * D;
+            for (int e = tid; e < 64 * D; e += kFusedThreads) s_u[e] = ld_coherent(yt + e) * ((float)n * s_rho[e / D]);
+            __syncthreads();
+            for (int f = tid; f < 2 * RB * NB * 64; f += kFusedThreads) {
+                const int fl = f & 63, fi = fl & 31, fkg = fl >> 5;
+                const int snb = f >> 6, s = snb / NB, nb = snb % NB;
+                f32x8 t;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int pv = 32 * (s >> 1) + 16 * (s & 1) + 8 * (e >> 2) + 4 * fkg + (e & 3);
+                    t[e] = s_u[pv * D + NB * fi + nb];
+                }
+                bf16x8 hi, lo;
+                split_bf16(t, hi, lo);
+                yf_hi[f] = hi;
+                yf_lo[f] = lo;
+            }
+            __syncthreads();
+            run_pass<IO, D, RB, EPI_EXPAND>(p, X, g, side, tile_begin, tile_end, lane, wave, c1, zf, G, cs,
+                                            nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, reinterpret_cast<IO*>(p.out));
+        }
+        __syncthreads();   // LDS is reused by the next item
+    }
+}
+
+__global__ void lot_fused_clear(uint32_t* words, int count)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < count) words[idx] = 0u;
+}
+
+template <typename IO, int D, int RB>
+int launch(const Args& a, bool want_out)
+{
+    const lot_shape& s = a.s;
+    const int G = s.B * s.H, pairs = 2 * G;
+    auto kernel = lot_fused_kernel<IO, D, RB>;
+
+    static thread_local int capacity_cache[8] = {0};   // per device ordinal
+    int dev = 0;
+    LOT_HIP_CHECK(hipGetDevice(&dev));
+    int capacity = (dev >= 0 && dev < 8) ? capacity_cache[dev] : 0;
+    if (capacity == 0) {
+        int per_cu = 0, cus = 0;
+        LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kFusedThreads, 0));
+        LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        capacity = per_cu * cus;
+        if (capacity < 1) { last_hip_error() = hipErrorLaunchOutOfResources; return LOT_ERR_HIP; }
+        if (capacity > kMaxResidentWgs) capacity = kMaxResidentWgs;
+        if (dev >= 0 && dev < 8) capacity_cache[dev] = capacity;
+    }
+
+    const int ntiles = (s.n + kTileTokens - 1) / kTileTokens;
+    int cluster = fused_cluster_bound(s);
+    if (cluster > capacity / pairs) cluster = capacity / pairs;
+    if (cluster < 1) cluster = 1;
+    const int tiles_per_wg = (ntiles + cluster - 1) / cluster;
+    cluster = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
+
+    FusedParams p{};
+    p.Q = a.Q; p.K = a.K; p.V = a.V; p.Z = a.Z; p.beta = a.beta; p.out = a.out;
+    p.gamma1 = a.gamma1; p.gamma2 = a.gamma2;
+    p.status = (uint32_t*)(a.ws + a.lay.status);
+    p.arrive = (uint32_t*)(a.ws + a.lay.counters);
+    p.yready = p.arrive + pairs;
+    p.colsum_part = (float*)(a.ws + a.lay.colsum_part);
+    p.u_part = (float*)(a.ws + a.lay.u_part);
+    p.y_tile = (float*)(a.ws + a.lay.y_tile);
+    p.G = G; p.H = s.H; p.n = s.n; p.r = s.r;
+    p.cluster = cluster; p.cluster_cap = fused_cluster_bound(s); p.tiles_per_wg = tiles_per_wg;
+    p.num_items = pairs * cluster; p.iters = a.iters; p.mode = want_out ? MODE_ATTENTION : MODE_COUPLINGS;
+    p.eps = a.eps;
+    p.spin_limit = 1u << 21;
+
+    // status word + counters start at zero (a fill kernel, so the call can be captured in a graph)
+    const int words = 64 + (int)(a.lay.counters_bytes / 4);
+    lot_fused_clear<<<(words + 255) / 256, 256, 0, a.stream>>>((uint32_t*)(a.ws + a.lay.status), words);
+
+    const int grid = p.num_items < capacity ? p.num_items : capacity;
+    void* kargs[] = {&p};
+    LOT_HIP_CHECK(hipLaunchCooperativeKernel((const void*)kernel, dim3(grid), dim3(kFusedThreads), kargs, 0, a.stream));
+    return LOT_OK;
+}
+
+template <typename IO>
+int dispatch(const Args& a, bool want_out)
+{
+    const int d = a.s.d_k, rb = a.s.r <= 32 ? 1 : 2;
+    if (d == 32 && rb == 1) return launch<IO, 32, 1>(a, want_out);
+    if (d == 32 && rb == 2) return launch<IO, 32, 2>(a, want_out);
+    if (d == 64 && rb == 1) return launch<IO, 64, 1>(a, want_out);
+    if (d == 64 && rb == 2) return launch<IO, 64, 2>(a, want_out);
+    return LOT_ERR_PATH;
+}
+
+}  // namespace
+
+int run_fused(const Args& a, bool want_out)
+{
+    if (!fused_supports(a.s)) return LOT_ERR_PATH;
+    return a.s.io_dtype == LOT_BF16 ? dispatch<uint16_t>(a, want_out) : dispatch<float>(a, want_out);
+}
+
+}  // namespace lot
