@@ -25,6 +25,8 @@
 //
 // Cross-workgroup waits are bounded: a wait that exceeds its poll budget raises the status word
 // in the workspace and the workgroup leaves the kernel, so every wavefront always exits.
+#include <cmath>
+
 #include "lot_internal.h"
 
 namespace lot {
@@ -53,14 +55,15 @@ struct FusedParams {
     float* gamma1;
     float* gamma2;
     uint32_t* status;
-    uint32_t* arrive;     // [pairs]
+    uint32_t* arrive;     // [G]: workgroups that have posted their share of U
     uint32_t* yready;     // [G]
-    float* colsum_part;   // [pairs][2][cluster_cap][64]
+    unsigned long long* colacc;   // [G][2 sides][2 parities][64]: count << 56 | fixed-point column sum
     float* u_part;        // [G][cluster_cap][64][D]
     float* y_tile;        // [G][64][D]
     int G, H, n, r;
     int cluster, cluster_cap, tiles_per_wg, num_items, iters, mode;
     float eps;
+    float fx_scale, fx_unscale;   // 2^F and 2^-F of the fixed-point column sums
     uint32_t spin_limit;
 };
 
@@ -110,9 +113,27 @@ __device__ __forceinline__ float sum_over_tokens(float x)
     return x;
 }
 
-__device__ __forceinline__ float ld_coherent(const float* p)
+// Agent-coherent loads issued back to back with ONE wait at the end.  (An atomic load written in
+// C++ is followed by a full wait each time, which turns a gather of k partial results into k
+// sequential round trips to memory.)  The loads are raw instructions; the final wait is tied to
+// the destination registers so that no use can be scheduled before it.
+template <int N>
+__device__ __forceinline__ void ld_coherent_batch(float (&v)[N], const float* const (&ptr)[N])
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int k = 0; k < N; ++k) asm volatile("global_load_dword %0, %1, off sc1" : "=v"(v[k]) : "v"(ptr[k]) : "memory");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int k = 0; k < N; ++k) asm volatile("" : "+v"(v[k]));
+}
+template <int N>
+__device__ __forceinline__ void ld_coherent_batch4(f32x4 (&v)[N], const float* const (&ptr)[N])
+{
+#pragma unroll
+    for (int k = 0; k < N; ++k) asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[k]) : "v"(ptr[k]) : "memory");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int k = 0; k < N; ++k) asm volatile("" : "+v"(v[k]));
 }
 __device__ __forceinline__ void st_coherent(float* p, float v)
 {
@@ -127,14 +148,22 @@ __device__ __forceinline__ void split_bf16(const f32x8& x, bf16x8& hi, bf16x8& l
 }
 __device__ __forceinline__ uint16_t bf16_bits_of(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
 
+// Cross-workgroup exchange protocol.  Every word that one workgroup writes and another reads
+// (partial sums, the Y tile, the counters) is accessed ONLY with agent-scope relaxed atomics, which
+// go to the device-wide coherence point.  Ordering comes from the workgroup barrier: it waits until
+// the writers' stores have been acknowledged before thread 0 bumps the counter, and the readers load
+// after thread 0 has seen the counter.  No agent-scope release/acquire fence is used on purpose:
+// on this multi-die part such a fence writes back / invalidates a whole L2, once per workgroup per
+// iteration, which costs far more than the iteration itself.
+//
 // Poll *counter until it reaches target.  Thread 0 only.  False if the budget ran out or another
 // workgroup already gave up.
 __device__ inline bool spin_until(uint32_t* counter, uint32_t target, uint32_t* status, uint32_t limit)
 {
     for (uint32_t k = 0; k < limit; ++k) {
-        if (__hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= target) return true;
+        if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) return true;
         if ((k & 63u) == 63u && __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return false;
-        __builtin_amdgcn_s_sleep(2);
+        __builtin_amdgcn_s_sleep(1);
     }
     return false;
 }
@@ -183,6 +212,45 @@ __device__ __forceinline__ void load_pivots(Frag<float, D>& f, const float* zrow
 {
 #pragma unroll
     for (int s = 0; s < D / 2; ++s) f.v[s] = valid ? zrow[kg * (D / 2) + s] : 0.f;
+}
+
+// Pivot fragments kept in LDS as [block][step][lane], so that the heavier passes need not hold
+// them in registers.  `skew` is an opaque zero that keeps the loads inside the tile loop.
+template <int D, int RB>
+__device__ __forceinline__ void stash_pivots(void* lds, const Frag<uint16_t, D> (&zf)[RB], int lane)
+{
+    bf16x8* dst = reinterpret_cast<bf16x8*>(lds);
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) dst[(mb * (D / 16) + s) * 64 + lane] = zf[mb].v[s];
+}
+template <int D, int RB>
+__device__ __forceinline__ void stash_pivots(void* lds, const Frag<float, D> (&zf)[RB], int lane)
+{
+    float* dst = reinterpret_cast<float*>(lds);
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int s = 0; s < D / 2; ++s) dst[(mb * (D / 2) + s) * 64 + lane] = zf[mb].v[s];
+}
+template <int D, int RB>
+__device__ __forceinline__ void fetch_pivots(Frag<uint16_t, D> (&zf)[RB], const void* lds, int lane, int skew)
+{
+    const bf16x8* src = reinterpret_cast<const bf16x8*>(lds) + skew;
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) zf[mb].v[s] = src[(mb * (D / 16) + s) * 64 + lane];
+}
+template <int D, int RB>
+__device__ __forceinline__ void fetch_pivots(Frag<float, D> (&zf)[RB], const void* lds, int lane, int skew)
+{
+    const float* src = reinterpret_cast<const float*>(lds) + skew;
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int s = 0; s < D / 2; ++s) zf[mb].v[s] = src[(mb * (D / 2) + s) * 64 + lane];
 }
 
 // acc[mb] = Z_block(mb) X_tile^T + G[mb]   (pivots x tokens)
@@ -294,7 +362,7 @@ template <typename IO, int D, int RB, int EPI>
 __device__ __forceinline__ void run_pass(
     const FusedParams& p, const IO* __restrict__ X, int g, int side, int tile_begin, int tile_end,
     int lane, int wave, float c1,
-    const Frag<IO, D> (&zf)[RB], const f32x16 (&G)[RB], f32x16 (&cs)[RB],
+    const Frag<IO, D> (&zf)[RB], const void* zlds, const f32x16 (&G)[RB], f32x16 (&cs)[RB],
     const IO* __restrict__ V, f32x16 (&U)[RB][D / 32], uint16_t* tr_hi, uint16_t* tr_lo,
     const bf16x8* yf_hi, const bf16x8* yf_lo, IO* __restrict__ out)
 {
@@ -317,7 +385,15 @@ __device__ __forceinline__ void run_pass(
         }
 
         f32x16 acc[RB];
-        similarity<D, RB>(acc, zf, xc, G);
+        if (EPI == EPI_NONE) {
+            similarity<D, RB>(acc, zf, xc, G);
+        } else {
+            int skew = 0;
+            asm volatile("" : "+v"(skew));
+            Frag<IO, D> zl[RB];
+            fetch_pivots<D, RB>(zl, zlds, lane, skew);
+            similarity<D, RB>(acc, zl, xc, G);
+        }
 
         // token-side update: row maximum, exponentials, row sum
         float m0 = acc[0][0], m1 = acc[0][1], m2 = acc[0][2], m3 = acc[0][3];
@@ -448,16 +524,24 @@ __device__ __forceinline__ void run_pass(
 // ---------------------------------------------------------------------------------------------
 // the kernel
 // ---------------------------------------------------------------------------------------------
+// A workgroup owns one chunk of tokens of one problem and runs BOTH solves on it, alternating
+// key-side and query-side passes.  The cross-workgroup reduction of a pass is split in two: the
+// partial column sums are posted right after the pass, and collected only when that side's next
+// pass is about to start -- one whole pass of the other side later -- so the latency of the
+// exchange (and the spread between workgroups) is hidden behind useful work.
 template <typename IO, int D, int RB>
 __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams p)
 {
     constexpr int NB = D / 32;
     __shared__ float s_wave_part[kFusedWaves][64];
-    __shared__ float s_g[64];
-    __shared__ float s_rho[64];        // beta_t / colsum_t after the last iteration
-    __shared__ float s_csinv[64];      // 1 / colsum_t after the last iteration
+    __shared__ float s_tot[2][64];     // cluster == 1: this workgroup's column sums, per side
+    __shared__ float s_g[2][64];       // pivot potentials per side (0 = keys, 1 = queries)
+    __shared__ float s_rho[2][64];     // beta_t / colsum_t after the last iteration
+    __shared__ float s_csinv[64];      // 1 / colsum_t of the key side after the last iteration
     __shared__ __attribute__((aligned(16))) float s_u[64 * D];
     __shared__ __attribute__((aligned(16))) uint16_t s_tr[kFusedWaves * 2 * 64 * kTrStride];
+    __shared__ __attribute__((aligned(16))) char s_zf[RB * sizeof(Frag<IO, D>) * 64];
+    __shared__ unsigned long long s_prev[2][2][64];   // last word seen per (side, parity, pivot)
     __shared__ int s_ok;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -469,15 +553,14 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
     uint16_t* tr_lo = s_tr + (wave * 2 + 1) * 64 * kTrStride;
     bf16x8* yf_hi = reinterpret_cast<bf16x8*>(s_tr);
     bf16x8* yf_lo = yf_hi + 2 * RB * NB * 64;
+    const bool attention = p.mode == MODE_ATTENTION;
 
     for (int item = blockIdx.x; item < p.num_items; item += gridDim.x) {
-        const int pair = item / p.cluster, chunk = item % p.cluster;
-        const int g = pair >> 1, side = pair & 1, h = g % p.H;
-        const IO* X = reinterpret_cast<const IO*>(side ? p.Q : p.K);
+        const int g = item / p.cluster, chunk = item % p.cluster, h = g % p.H;
         const int tile_begin = chunk * p.tiles_per_wg;
         const int tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
-        uint32_t* arrive = p.arrive + pair;
         const float* beta = p.beta + (size_t)h * r;
+        const IO* Xs[2] = {reinterpret_cast<const IO*>(p.K), reinterpret_cast<const IO*>(p.Q)};
 
         Frag<IO, D> zf[RB];
 #pragma unroll
@@ -485,33 +568,15 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             const int t = 32 * mb + i;
             load_pivots<D>(zf[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
         }
-        if (tid < 64) s_g[tid] = tid < r ? 0.f : kNegBig;
+        if (wave == 0) stash_pivots<D, RB>(s_zf, zf, lane);
+        if (tid < 128) s_g[tid >> 6][tid & 63] = (tid & 63) < r ? 0.f : kNegBig;
+        (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
         __syncthreads();
         f32x16 G[RB], cs[RB], U[RB][NB];
-        load_pivot_vector<RB>(G, s_g, kg);
-        const bool fuse_u = side == 0 && p.mode == MODE_ATTENTION;
 
-        for (int it = 1; it <= p.iters; ++it) {
-#pragma unroll
-            for (int mb = 0; mb < RB; ++mb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) cs[mb][j] = 0.f;
-            const bool last = it == p.iters;
-            if (last && fuse_u) {
-#pragma unroll
-                for (int mb = 0; mb < RB; ++mb)
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                        for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
-                run_pass<IO, D, RB, EPI_ACCUM_U>(p, X, g, side, tile_begin, tile_end, lane, wave, c1, zf, G, cs,
-                                                 reinterpret_cast<const IO*>(p.V), U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
-            } else {
-                run_pass<IO, D, RB, EPI_NONE>(p, X, g, side, tile_begin, tile_end, lane, wave, c1, zf, G, cs,
-                                              nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
-            }
-
-            // column sums: lanes -> wavefront -> workgroup
+        // ---- post this workgroup's share of a pass (column sums, and U on the last key pass) ----
+        auto post = [&](int side, int it, bool with_u) {
+            __builtin_amdgcn_s_setprio(3);
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -527,7 +592,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                         *reinterpret_cast<f32x4*>(&s_wave_part[wave][32 * mb + 8 * q + 4 * kg]) = t;
                     }
             }
-            if (last && fuse_u) {
+            if (with_u) {
                 // workgroup total of U in s_u, one wavefront at a time (fixed order)
                 for (int turn = 0; turn < kFusedWaves; ++turn) {
                     if (wave == turn) {
@@ -546,85 +611,176 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             } else {
                 __syncthreads();
             }
-
-            float tot = 0.f;
             if (tid < 64) {
-                tot = s_wave_part[0][tid];
+                float tot = s_wave_part[0][tid];
                 tot += s_wave_part[1][tid];
                 tot += s_wave_part[2][tid];
                 tot += s_wave_part[3][tid];
+                if (tid >= r) tot = 0.f;   // padding pivots (their LDS slots may never have been written)
+                if (p.cluster > 1) {
+                    // one fire-and-forget atomic per pivot: the workgroup's column sum in fixed point
+                    // (integer addition: the total does not depend on arrival order) plus one count
+                    const unsigned long long word = (1ull << 56) + (unsigned long long)__float2ll_rn(tot * p.fx_scale);
+                    __hip_atomic_fetch_add(p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + tid, word,
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    s_tot[side][tid] = tot;
+                }
             }
+            if (p.cluster > 1 && with_u) {
+                float* up = p.u_part + ((size_t)g * p.cluster_cap + chunk) * 64 * D;
+                for (int e = tid; e < 64 * D; e += kFusedThreads) st_coherent(up + e, s_u[e]);
+                __syncthreads();   // the stores above have been acknowledged
+                if (tid == 0) __hip_atomic_fetch_add(p.arrive + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();   // s_wave_part / s_tot may be reused
+            __builtin_amdgcn_s_setprio(0);
+        };
+
+        // ---- collect the column sums of pass `it` of `side` and apply the pivot-side update ----
+        auto collect = [&](int side, int it, bool final) -> bool {
+            __builtin_amdgcn_s_setprio(3);
+            float tot = 0.f;
             if (p.cluster > 1) {
-                float* slot = p.colsum_part + (((size_t)pair * 2 + (it & 1)) * p.cluster_cap + chunk) * 64;
-                if (tid < 64) st_coherent(slot + tid, tot);
-                if (last && fuse_u) {
-                    float* up = p.u_part + ((size_t)g * p.cluster_cap + chunk) * 64 * D;
-                    for (int e = tid; e < 64 * D; e += kFusedThreads) st_coherent(up + e, s_u[e]);
+                if (wave == 0) {
+                    // every pivot's word carries its own arrival count: poll until all 64 are complete
+                    const unsigned long long* src = p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + lane;
+                    const unsigned long long prev = s_prev[side][it & 1][lane];
+                    unsigned long long word = 0;
+                    bool ok = false;
+                    for (uint32_t k = 0; k < p.spin_limit; ++k) {
+                        word = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const unsigned arrived = (unsigned)((word >> 56) - (prev >> 56)) & 0xffu;
+                        if (__all(arrived == (unsigned)p.cluster)) { ok = true; break; }
+                        if ((k & 63u) == 63u && __hip_atomic_load(p.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                    s_prev[side][it & 1][lane] = word;
+                    const unsigned long long mask = (1ull << 56) - 1ull;
+                    tot = (float)(long long)((word & mask) - (prev & mask)) * p.fx_unscale;
+                    if (lane == 0) {
+                        if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        s_ok = ok;
+                    }
                 }
                 __syncthreads();
-                if (tid == 0) {
-                    __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-                    const bool ok = spin_until(arrive, (uint32_t)p.cluster * (uint32_t)it, p.status, p.spin_limit);
-                    if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    s_ok = ok;
-                }
-                __syncthreads();
-                if (!s_ok) return;
-                if (tid < 64) {
-                    const float* base = p.colsum_part + ((size_t)pair * 2 + (it & 1)) * p.cluster_cap * 64;
-                    tot = 0.f;
-                    for (int k = 0; k < p.cluster; ++k) tot += ld_coherent(base + (size_t)k * 64 + tid);
-                }
+                if (!s_ok) return false;
+            } else if (tid < 64) {
+                tot = s_tot[side][tid];
             }
             if (tid < 64) {
                 if (tid < r) {
                     const float c = fmaxf(tot, 1.0e-37f);
                     const float b = beta[tid];
-                    s_g[tid] += p.eps * logf((float)n * b / c);
-                    s_rho[tid] = b / c;
-                    s_csinv[tid] = 1.f / c;
-                } else {
-                    s_rho[tid] = 0.f;
-                    s_csinv[tid] = 0.f;
+                    if (!final) {
+                        s_g[side][tid] += p.eps * logf((float)n * b / c);
+                    } else {
+                        // the last pass's potentials stay: the epilogue rebuilds its coupling from them
+                        s_rho[side][tid] = b / c;
+                        if (side == 0) s_csinv[tid] = 1.f / c;
+                    }
+                } else if (final) {
+                    s_rho[side][tid] = 0.f;
+                    if (side == 0) s_csinv[tid] = 0.f;
                 }
             }
             __syncthreads();
-            if (!last) load_pivot_vector<RB>(G, s_g, kg);   // the last pass's potentials stay for the epilogue
-        }
+            __builtin_amdgcn_s_setprio(0);
+            return true;
+        };
 
-        if (p.mode == MODE_COUPLINGS) {
-            load_pivot_vector<RB>(cs, s_rho, kg);
-            run_pass<IO, D, RB, EPI_GAMMA>(p, X, g, side, tile_begin, tile_end, lane, wave, c1, zf, G, cs,
-                                           nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
-        } else if (side == 0) {
-            // key side: Y'_t = U_t / colsum_t, written to global for the query side
-            float* yt = p.y_tile + (size_t)g * 64 * D;
+        for (int it = 1; it <= p.iters; ++it) {
+            for (int side = 0; side < 2; ++side) {
+                if (it > 1 && !collect(side, it - 1, false)) return;
+                load_pivot_vector<RB>(G, s_g[side], kg);
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) cs[mb][j] = 0.f;
+                const bool with_u = attention && side == 0 && it == p.iters;
+                if (with_u) {
+#pragma unroll
+                    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                            for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
+                    run_pass<IO, D, RB, EPI_ACCUM_U>(p, Xs[side], g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, G, cs,
+                                                     reinterpret_cast<const IO*>(p.V), U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
+                } else {
+                    run_pass<IO, D, RB, EPI_NONE>(p, Xs[side], g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, G, cs,
+                                                  nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
+                }
+                post(side, it, with_u);
+            }
+        }
+        if (!collect(0, p.iters, true)) return;
+        if (!collect(1, p.iters, true)) return;
+
+        if (!attention) {
+            for (int side = 0; side < 2; ++side) {
+                load_pivot_vector<RB>(G, s_g[side], kg);
+                load_pivot_vector<RB>(cs, s_rho[side], kg);
+                run_pass<IO, D, RB, EPI_GAMMA>(p, Xs[side], g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, G, cs,
+                                               nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
+            }
+        } else {
+            // Y''_t = n * rho1_t * U_t / colsum2_t  ->  s_u
             if (p.cluster == 1) {
-                for (int e = tid; e < 64 * D; e += kFusedThreads) st_coherent(yt + e, s_u[e] * s_csinv[e / D]);
+                for (int e = tid; e < 64 * D; e += kFusedThreads) s_u[e] *= s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
             } else {
+                // each workgroup of the cluster reduces one slice of the U partials into Y'
+                __builtin_amdgcn_s_setprio(3);
+                if (tid == 0) {
+                    const bool ok = spin_until(p.arrive + g, (uint32_t)p.cluster, p.status, p.spin_limit);
+                    if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    s_ok = ok;
+                }
+                __syncthreads();
+                if (!s_ok) return;
+                float* yt = p.y_tile + (size_t)g * 64 * D;
                 const int per = (64 * D + p.cluster - 1) / p.cluster;
                 const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
                 const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
                 for (int e = e0 + tid; e < e1; e += kFusedThreads) {
                     float acc = 0.f;
-                    for (int k = 0; k < p.cluster; ++k) acc += ld_coherent(up + (size_t)k * 64 * D + e);
+                    for (int k0 = 0; k0 < p.cluster; k0 += 8) {
+                        float v[8];
+                        const float* ptr[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) ptr[j] = up + (size_t)min(k0 + j, p.cluster - 1) * 64 * D + e;
+                        ld_coherent_batch<8>(v, ptr);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) acc += (k0 + j < p.cluster) ? v[j] : 0.f;
+                    }
                     st_coherent(yt + e, acc * s_csinv[e / D]);
                 }
+                __syncthreads();
+                if (tid == 0) {
+                    __hip_atomic_fetch_add(p.yready + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const bool ok = spin_until(p.yready + g, (uint32_t)p.cluster, p.status, p.spin_limit);
+                    if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    s_ok = ok;
+                }
+                __syncthreads();
+                if (!s_ok) return;
+                constexpr int kChunks = 64 * D / 4 / kFusedThreads;   // 16-byte chunks per thread
+                f32x4 v[kChunks];
+                const float* ptr[kChunks];
+#pragma unroll
+                for (int j = 0; j < kChunks; ++j) ptr[j] = yt + 4 * (tid + j * kFusedThreads);
+                ld_coherent_batch4<kChunks>(v, ptr);
+#pragma unroll
+                for (int j = 0; j < kChunks; ++j) {
+                    const int e = 4 * (tid + j * kFusedThreads);
+                    const float sc = (float)n * s_rho[1][e / D];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) s_u[e + c] = v[j][c] * sc;
+                }
+                __builtin_amdgcn_s_setprio(0);
             }
             __syncthreads();
-            if (tid == 0) __hip_atomic_fetch_add(p.yready + g, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            // query side: wait for Y', fold n * rho_t into it, lay it out as MFMA B fragments, expand
-            if (tid == 0) {
-                const bool ok = spin_until(p.yready + g, (uint32_t)p.cluster, p.status, p.spin_limit);
-                if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s_ok = ok;
-            }
-            __syncthreads();
-            if (!s_ok) return;
-            const float* yt = p.y_tile + (size_t)g * 64 * D;
-            for (int e = tid; e < 64 * D; e += kFusedThreads) s_u[e] = ld_coherent(yt + e) * ((float)n * s_rho[e / D]);
-            __syncthreads();
+            // lay Y'' out as MFMA B fragments (bf16 hi + lo)
             for (int f = tid; f < 2 * RB * NB * 64; f += kFusedThreads) {
                 const int fl = f & 63, fi = fl & 31, fkg = fl >> 5;
                 const int snb = f >> 6, s = snb / NB, nb = snb % NB;
@@ -640,7 +796,8 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 yf_lo[f] = lo;
             }
             __syncthreads();
-            run_pass<IO, D, RB, EPI_EXPAND>(p, X, g, side, tile_begin, tile_end, lane, wave, c1, zf, G, cs,
+            load_pivot_vector<RB>(G, s_g[1], kg);
+            run_pass<IO, D, RB, EPI_EXPAND>(p, Xs[1], g, 1, tile_begin, tile_end, lane, wave, c1, zf, s_zf, G, cs,
                                             nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, reinterpret_cast<IO*>(p.out));
         }
         __syncthreads();   // LDS is reused by the next item
@@ -657,7 +814,7 @@ template <typename IO, int D, int RB>
 int launch(const Args& a, bool want_out)
 {
     const lot_shape& s = a.s;
-    const int G = s.B * s.H, pairs = 2 * G;
+    const int G = s.B * s.H;
     auto kernel = lot_fused_kernel<IO, D, RB>;
 
     static thread_local int capacity_cache[8] = {0};   // per device ordinal
@@ -676,7 +833,7 @@ int launch(const Args& a, bool want_out)
 
     const int ntiles = (s.n + kTileTokens - 1) / kTileTokens;
     int cluster = fused_cluster_bound(s);
-    if (cluster > capacity / pairs) cluster = capacity / pairs;
+    if (cluster > capacity / G) cluster = capacity / G;
     if (cluster < 1) cluster = 1;
     const int tiles_per_wg = (ntiles + cluster - 1) / cluster;
     cluster = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
@@ -686,23 +843,39 @@ int launch(const Args& a, bool want_out)
     p.gamma1 = a.gamma1; p.gamma2 = a.gamma2;
     p.status = (uint32_t*)(a.ws + a.lay.status);
     p.arrive = (uint32_t*)(a.ws + a.lay.counters);
-    p.yready = p.arrive + pairs;
-    p.colsum_part = (float*)(a.ws + a.lay.colsum_part);
+    p.yready = p.arrive + G;
+    p.colacc = (unsigned long long*)(a.ws + a.lay.colacc);
     p.u_part = (float*)(a.ws + a.lay.u_part);
     p.y_tile = (float*)(a.ws + a.lay.y_tile);
     p.G = G; p.H = s.H; p.n = s.n; p.r = s.r;
     p.cluster = cluster; p.cluster_cap = fused_cluster_bound(s); p.tiles_per_wg = tiles_per_wg;
-    p.num_items = pairs * cluster; p.iters = a.iters; p.mode = want_out ? MODE_ATTENTION : MODE_COUPLINGS;
+    p.num_items = G * cluster; p.iters = a.iters; p.mode = want_out ? MODE_ATTENTION : MODE_COUPLINGS;
     p.eps = a.eps;
     p.spin_limit = 1u << 21;
 
-    // status word + counters start at zero (a fill kernel, so the call can be captured in a graph)
-    const int words = 64 + (int)(a.lay.counters_bytes / 4);
+    // Fixed-point format of the exchanged column sums: a parity buffer receives at most
+    // iters/2 + 1 passes, each adding at most n per pivot, and must stay below 2^55.
+    {
+        const double max_sum = ((double)a.iters / 2.0 + 1.0) * (double)s.n;
+        int frac = 55 - (int)std::ceil(std::log2(max_sum + 1.0));
+        if (frac > 40) frac = 40;
+        if (frac < 8) return LOT_ERR_PATH;
+        p.fx_scale = std::ldexp(1.0f, frac);
+        p.fx_unscale = std::ldexp(1.0f, -frac);
+    }
+
+    // status word, counters and accumulators start at zero (a fill kernel, so the call can be
+    // captured in a graph); they are adjacent in the workspace
+    const int words = (int)((a.lay.colacc + (cluster > 1 ? a.lay.colacc_bytes : 0) - a.lay.status) / 4);
     lot_fused_clear<<<(words + 255) / 256, 256, 0, a.stream>>>((uint32_t*)(a.ws + a.lay.status), words);
 
     const int grid = p.num_items < capacity ? p.num_items : capacity;
-    void* kargs[] = {&p};
-    LOT_HIP_CHECK(hipLaunchCooperativeKernel((const void*)kernel, dim3(grid), dim3(kFusedThreads), kargs, 0, a.stream));
+    // An ordinary launch: the grid never exceeds the number of workgroups the device can hold at
+    // once (occupancy query above), which is what the cross-workgroup waits need, and the waits are
+    // bounded in any case.  (A cooperative launch would assert the same thing, but kernel tracing
+    // tools do not survive it.)
+    kernel<<<dim3(grid), dim3(kFusedThreads), 0, a.stream>>>(p);
+    LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }
 

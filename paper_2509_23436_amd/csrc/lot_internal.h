@@ -12,7 +12,7 @@ namespace lot {
 constexpr int kTileTokens = 32;        // tokens per MFMA tile of the fused kernel
 constexpr int kFusedThreads = 256;     // 4 wavefronts per workgroup
 constexpr int kFusedWaves = kFusedThreads / 64;
-constexpr int kMaxCluster = 64;        // most workgroups that share one (problem, side)
+constexpr int kMaxCluster = 64;        // most workgroups that share one problem
 constexpr int kMaxResidentWgs = 2048;  // upper bound on co-resident workgroups (256 CUs x 8)
 constexpr int kRefChunk = 1024;        // tokens per workgroup in the reference column reduction
 
@@ -22,11 +22,11 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // the workspace size can be computed without a device).
 inline int fused_cluster_bound(const lot_shape& s)
 {
-    const int pairs = 2 * s.B * s.H;
+    const int problems = s.B * s.H;
     const int tiles = (s.n + kTileTokens - 1) / kTileTokens;
     int c = (tiles + kFusedWaves - 1) / kFusedWaves;
     if (c > kMaxCluster) c = kMaxCluster;
-    int by_capacity = kMaxResidentWgs / pairs;
+    int by_capacity = kMaxResidentWgs / problems;
     if (by_capacity < 1) by_capacity = 1;
     if (c > by_capacity) c = by_capacity;
     return c < 1 ? 1 : c;
@@ -41,9 +41,10 @@ inline bool fused_supports(const lot_shape& s)
 struct Workspace {
     // fused path
     size_t status;        // 64 x uint32: word 0 = sync failure flag
-    size_t counters;      // uint32 [pairs] arrivals + uint32 [G] y-ready, zeroed per launch
+    size_t counters;      // uint32 [G] U arrivals + uint32 [G] y-ready, zeroed per launch
     size_t counters_bytes;
-    size_t colsum_part;   // float [pairs][2][cluster_bound][64]
+    size_t colacc;        // uint64 [G][2][2][64] fixed-point column sums, zeroed per launch
+    size_t colacc_bytes;
     size_t u_part;        // float [G][cluster_bound][64][d_v]
     size_t y_tile;        // float [G][64][d_v]
     // reference path
@@ -67,9 +68,10 @@ inline Workspace carve(const lot_shape& s)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     w.status = take(64 * 4);
-    w.counters_bytes = align_up((2 * G + G) * 4, 256);
+    w.counters_bytes = align_up(2 * G * 4, 256);
     w.counters = take(w.counters_bytes);
-    w.colsum_part = take(2 * G * 2 * cb * 64 * 4);
+    w.colacc_bytes = G * 2 * 2 * 64 * 8;
+    w.colacc = take(w.colacc_bytes);
     w.u_part = take(G * cb * 64 * dv * 4);
     w.y_tile = take(G * 64 * dv * 4);
     w.C = take(2 * G * n * r * 4);
