@@ -38,6 +38,16 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
+// Pointers that reach the kernel inside the parameter block are generic; loads through them
+// become flat instructions, which also count as LDS traffic and defeat the prefetch.  Every
+// tensor is device memory, so the accesses are made through explicitly global pointers.
+#define LOT_GLOBAL __attribute__((address_space(1)))
+template <typename T> __device__ __forceinline__ const LOT_GLOBAL T* as_global(const T* p)
+{
+    return (const LOT_GLOBAL T*)p;
+}
+template <typename T> __device__ __forceinline__ LOT_GLOBAL T* as_global(T* p) { return (LOT_GLOBAL T*)p; }
+
 constexpr float kNegBig = -1.0e30f;   // potential of a padding pivot: its exponential is exactly 0
 constexpr int kTrStride = 40;         // uint16 per row of the transposed coupling tile (32 + 8 pad)
 constexpr float kLog2e = 1.44269504088896340736f;
@@ -98,6 +108,16 @@ __device__ __forceinline__ float pair_sum(float x)
     return lo + hi;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global access of the wavefront, which would stall on the tile rows that are
+// loaded ahead of the next pass.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <int CTRL> __device__ __forceinline__ float dpp_move(float x)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
@@ -113,27 +133,30 @@ __device__ __forceinline__ float sum_over_tokens(float x)
     return x;
 }
 
-// Agent-coherent loads issued back to back with ONE wait at the end.  (An atomic load written in
-// C++ is followed by a full wait each time, which turns a gather of k partial results into k
-// sequential round trips to memory.)  The loads are raw instructions; the final wait is tied to
-// the destination registers so that no use can be scheduled before it.
-template <int N>
-__device__ __forceinline__ void ld_coherent_batch(float (&v)[N], const float* const (&ptr)[N])
+// Agent-coherent loads that the compiler can schedule: raw buffer loads carrying the sc1 cache
+// policy (the same policy an agent-scope atomic load uses).  An atomic load written in C++ is
+// followed by a full wait each time, which turns a gather of k partial results into k sequential
+// round trips to memory; these are tracked like ordinary loads, so several can be in flight and
+// other work can be placed between issue and first use.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kCoherent = 16;   // cache-policy operand: sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t coherent_view(const void* base)
 {
-#pragma unroll
-    for (int k = 0; k < N; ++k) asm volatile("global_load_dword %0, %1, off sc1" : "=v"(v[k]) : "v"(ptr[k]) : "memory");
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-    for (int k = 0; k < N; ++k) asm volatile("" : "+v"(v[k]));
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
 }
-template <int N>
-__device__ __forceinline__ void ld_coherent_batch4(f32x4 (&v)[N], const float* const (&ptr)[N])
+__device__ __forceinline__ float ldc_f32(__amdgpu_buffer_rsrc_t v, uint32_t byte_offset)
 {
-#pragma unroll
-    for (int k = 0; k < N; ++k) asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[k]) : "v"(ptr[k]) : "memory");
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-    for (int k = 0; k < N; ++k) asm volatile("" : "+v"(v[k]));
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(v, byte_offset, 0, kCoherent));
+}
+__device__ __forceinline__ unsigned long long ldc_u64(__amdgpu_buffer_rsrc_t v, uint32_t byte_offset)
+{
+    const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(v, byte_offset, 0, kCoherent);
+    return ((unsigned long long)w[1] << 32) | (unsigned long long)w[0];
+}
+__device__ __forceinline__ f32x4 ldc_f32x4(__amdgpu_buffer_rsrc_t v, uint32_t byte_offset)
+{
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(v, byte_offset, 0, kCoherent));
 }
 __device__ __forceinline__ void st_coherent(float* p, float v)
 {
@@ -182,14 +205,14 @@ template <int D>
 __device__ __forceinline__ void load_tokens(Frag<uint16_t, D>& f, const uint16_t* row, int kg)
 {
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) f.v[s] = *reinterpret_cast<const bf16x8*>(row + 16 * s + 8 * kg);
+    for (int s = 0; s < D / 16; ++s) f.v[s] = *as_global(reinterpret_cast<const bf16x8*>(row + 16 * s + 8 * kg));
 }
 template <int D>
 __device__ __forceinline__ void load_tokens(Frag<float, D>& f, const float* row, int kg)
 {
 #pragma unroll
     for (int q = 0; q < D / 8; ++q) {
-        const f32x4 t = *reinterpret_cast<const f32x4*>(row + kg * (D / 2) + 4 * q);
+        const f32x4 t = *as_global(reinterpret_cast<const f32x4*>(row + kg * (D / 2) + 4 * q));
 #pragma unroll
         for (int e = 0; e < 4; ++e) f.v[4 * q + e] = t[e];
     }
@@ -203,7 +226,7 @@ __device__ __forceinline__ void load_pivots(Frag<uint16_t, D>& f, const float* z
     for (int s = 0; s < D / 16; ++s) {
         f32x8 t;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = valid ? zrow[16 * s + 8 * kg + e] : 0.f;
+        for (int e = 0; e < 8; ++e) t[e] = valid ? as_global(zrow)[16 * s + 8 * kg + e] : 0.f;
         f.v[s] = __builtin_convertvector(t, bf16x8);
     }
 }
@@ -211,7 +234,7 @@ template <int D>
 __device__ __forceinline__ void load_pivots(Frag<float, D>& f, const float* zrow, int kg, bool valid)
 {
 #pragma unroll
-    for (int s = 0; s < D / 2; ++s) f.v[s] = valid ? zrow[kg * (D / 2) + s] : 0.f;
+    for (int s = 0; s < D / 2; ++s) f.v[s] = valid ? as_global(zrow)[kg * (D / 2) + s] : 0.f;
 }
 
 // Pivot fragments kept in LDS as [block][step][lane], so that the heavier passes need not hold
@@ -253,27 +276,23 @@ __device__ __forceinline__ void fetch_pivots(Frag<float, D> (&zf)[RB], const voi
         for (int s = 0; s < D / 2; ++s) zf[mb].v[s] = src[(mb * (D / 2) + s) * 64 + lane];
 }
 
-// acc[mb] = Z_block(mb) X_tile^T + G[mb]   (pivots x tokens)
+// acc[mb] += Z_block(mb) X_tile^T   (pivots x tokens); acc enters holding the pivot potentials
 template <int D, int RB>
 __device__ __forceinline__ void similarity(f32x16 (&acc)[RB], const Frag<uint16_t, D> (&zf)[RB],
-                                           const Frag<uint16_t, D>& xf, const f32x16 (&G)[RB])
+                                           const Frag<uint16_t, D>& xf)
 {
 #pragma unroll
-    for (int mb = 0; mb < RB; ++mb) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zf[mb].v[0], xf.v[0], G[mb], 0, 0, 0);
-#pragma unroll
-    for (int s = 1; s < D / 16; ++s)
+    for (int s = 0; s < D / 16; ++s)
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
             acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zf[mb].v[s], xf.v[s], acc[mb], 0, 0, 0);
 }
 template <int D, int RB>
 __device__ __forceinline__ void similarity(f32x16 (&acc)[RB], const Frag<float, D> (&zf)[RB],
-                                           const Frag<float, D>& xf, const f32x16 (&G)[RB])
+                                           const Frag<float, D>& xf)
 {
 #pragma unroll
-    for (int mb = 0; mb < RB; ++mb) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(zf[mb].v[0], xf.v[0], G[mb], 0, 0, 0);
-#pragma unroll
-    for (int s = 1; s < D / 2; ++s)
+    for (int s = 0; s < D / 2; ++s)
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
             acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(zf[mb].v[s], xf.v[s], acc[mb], 0, 0, 0);
@@ -310,11 +329,11 @@ __device__ __forceinline__ void load_values(bf16x8 (&hi)[D / 32], bf16x8 (&lo)[D
     for (int e = 0; e < 8; ++e) {
         const size_t row = row0 + (e < n_left ? e : n_left - 1);
         if (NB == 2) {
-            const uint32_t w = *reinterpret_cast<const uint32_t*>(V + row * D + 2 * i);
+            const uint32_t w = *as_global(reinterpret_cast<const uint32_t*>(V + row * D + 2 * i));
             h[0].u[e] = (uint16_t)(w & 0xffffu);
             h[NB - 1].u[e] = (uint16_t)(w >> 16);
         } else {
-            h[0].u[e] = V[row * D + i];
+            h[0].u[e] = as_global(V)[row * D + i];
         }
     }
 #pragma unroll
@@ -330,11 +349,11 @@ __device__ __forceinline__ void load_values(bf16x8 (&hi)[D / 32], bf16x8 (&lo)[D
     for (int e = 0; e < 8; ++e) {
         const size_t row = row0 + (e < n_left ? e : n_left - 1);
         if (NB == 2) {
-            const f32x2 w = *reinterpret_cast<const f32x2*>(V + row * D + 2 * i);
+            const f32x2 w = *as_global(reinterpret_cast<const f32x2*>(V + row * D + 2 * i));
             t[0][e] = w[0];
             t[NB - 1][e] = w[1];
         } else {
-            t[0][e] = V[row * D + i];
+            t[0][e] = as_global(V)[row * D + i];
         }
     }
 #pragma unroll
@@ -343,13 +362,13 @@ __device__ __forceinline__ void load_values(bf16x8 (&hi)[D / 32], bf16x8 (&lo)[D
 
 template <int NB> __device__ __forceinline__ void store_out(uint16_t* row, int i, float a, float b)
 {
-    if (NB == 2) *reinterpret_cast<uint32_t*>(row + 2 * i) = (uint32_t)bf16_bits_of(a) | ((uint32_t)bf16_bits_of(b) << 16);
-    else row[i] = bf16_bits_of(a);
+    if (NB == 2) *as_global(reinterpret_cast<uint32_t*>(row + 2 * i)) = (uint32_t)bf16_bits_of(a) | ((uint32_t)bf16_bits_of(b) << 16);
+    else as_global(row)[i] = bf16_bits_of(a);
 }
 template <int NB> __device__ __forceinline__ void store_out(float* row, int i, float a, float b)
 {
-    if (NB == 2) { f32x2 w; w[0] = a; w[1] = b; *reinterpret_cast<f32x2*>(row + 2 * i) = w; }
-    else row[i] = a;
+    if (NB == 2) { f32x2 w; w[0] = a; w[1] = b; *as_global(reinterpret_cast<f32x2*>(row + 2 * i)) = w; }
+    else as_global(row)[i] = a;
 }
 
 template <typename IO> struct io_is_f32 { static constexpr bool value = false; };
@@ -360,9 +379,9 @@ template <> struct io_is_f32<float> { static constexpr bool value = true; };
 // ---------------------------------------------------------------------------------------------
 template <typename IO, int D, int RB, int EPI>
 __device__ __forceinline__ void run_pass(
-    const FusedParams& p, const IO* __restrict__ X, int g, int side, int tile_begin, int tile_end,
-    int lane, int wave, float c1,
-    const Frag<IO, D> (&zf)[RB], const void* zlds, const f32x16 (&G)[RB], f32x16 (&cs)[RB],
+    const FusedParams& p, const IO* __restrict__ X, const IO* __restrict__ Xnext, Frag<IO, D>& xfirst,
+    int g, int side, int tile_begin, int tile_end, int lane, int wave, float c1,
+    const Frag<IO, D> (&zf)[RB], const void* zlds, const float* glds, f32x16 (&cs)[RB],
     const IO* __restrict__ V, f32x16 (&U)[RB][D / 32], uint16_t* tr_hi, uint16_t* tr_lo,
     const bf16x8* yf_hi, const bf16x8* yf_lo, IO* __restrict__ out)
 {
@@ -372,27 +391,33 @@ __device__ __forceinline__ void run_pass(
     int tile = tile_begin + wave;
     if (tile >= tile_end) return;
 
-    Frag<IO, D> xc;
-    {
-        const int tok = min(tile * kTileTokens + i, n - 1);
-        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
-    }
+    // the first tile's rows were loaded before the previous pass ended (xfirst); the last
+    // iteration below loads the first tile of the NEXT pass (same tile range, rows of Xnext),
+    // so that no pass starts with an exposed round trip to memory
+    Frag<IO, D> xc = xfirst;
     for (; tile < tile_end; tile += kFusedWaves) {
         Frag<IO, D> xn = xc;
         if (tile + kFusedWaves < tile_end) {
             const int tok = min((tile + kFusedWaves) * kTileTokens + i, n - 1);
             load_tokens<D>(xn, X + ((size_t)g * n + tok) * D, kg);
+        } else if (Xnext != nullptr) {
+            const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
+            load_tokens<D>(xn, Xnext + ((size_t)g * n + tok) * D, kg);
         }
 
+        // The accumulators start from the pivot potentials g_t, read from LDS for every tile (an
+        // opaque zero offset keeps the reads inside the loop): holding them in registers for the
+        // whole pass costs 16*RB registers that the prefetched tile rows need more.
+        int skew = 0;
+        asm volatile("" : "+v"(skew));
         f32x16 acc[RB];
-        if (EPI == EPI_NONE) {
-            similarity<D, RB>(acc, zf, xc, G);
+        load_pivot_vector<RB>(acc, glds + skew, kg);
+        if (EPI != EPI_ACCUM_U) {
+            similarity<D, RB>(acc, zf, xc);
         } else {
-            int skew = 0;
-            asm volatile("" : "+v"(skew));
             Frag<IO, D> zl[RB];
             fetch_pivots<D, RB>(zl, zlds, lane, skew);
-            similarity<D, RB>(acc, zl, xc, G);
+            similarity<D, RB>(acc, zl, xc);
         }
 
         // token-side update: row maximum, exponentials, row sum
@@ -511,14 +536,15 @@ __device__ __forceinline__ void run_pass(
                         const int pv = pivot_of(mb, j, kg);
                         if (pv < p.r) {
                             const float v = acc[mb][j] * w * cs[mb][j];
-                            if (side == 1) p.gamma1[((size_t)g * n + tok) * p.r + pv] = v;
-                            else p.gamma2[((size_t)g * p.r + pv) * n + tok] = v;
+                            if (side == 1) as_global(p.gamma1)[((size_t)g * n + tok) * p.r + pv] = v;
+                            else as_global(p.gamma2)[((size_t)g * p.r + pv) * n + tok] = v;
                         }
                     }
             }
         }
         xc = xn;
     }
+    xfirst = xc;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -571,12 +597,19 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
         if (wave == 0) stash_pivots<D, RB>(s_zf, zf, lane);
         if (tid < 128) s_g[tid >> 6][tid & 63] = (tid & 63) < r ? 0.f : kNegBig;
         (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
-        __syncthreads();
-        f32x16 G[RB], cs[RB], U[RB][NB];
+        lds_barrier();
+        f32x16 cs[RB], U[RB][NB];
 
         // ---- post this workgroup's share of a pass (column sums, and U on the last key pass) ----
-        auto post = [&](int side, int it, bool with_u) {
+        unsigned long long early_word = 0;   // wavefront 0: a poll issued ahead of its use
+        auto post = [&](int side, int it, bool with_u, int next_side, int next_it) {
             __builtin_amdgcn_s_setprio(3);
+            if (p.cluster > 1 && wave == 0 && next_it >= 1) {
+                // start the poll that the following collect() needs; it completes while this
+                // pass's sums are reduced and posted.  collect() validates what arrives.
+                early_word = ldc_u64(coherent_view(p.colacc),
+                                     (uint32_t)(((((size_t)2 * g + next_side) * 2 + (next_it & 1)) * 64 + lane) * 8));
+            }
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -606,10 +639,10 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                                     *dst = turn == 0 ? U[mb][nb][j] : *dst + U[mb][nb][j];
                                 }
                     }
-                    __syncthreads();
+                    lds_barrier();
                 }
             } else {
-                __syncthreads();
+                lds_barrier();
             }
             if (tid < 64) {
                 float tot = s_wave_part[0][tid];
@@ -633,12 +666,12 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 __syncthreads();   // the stores above have been acknowledged
                 if (tid == 0) __hip_atomic_fetch_add(p.arrive + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            __syncthreads();   // s_wave_part / s_tot may be reused
+            lds_barrier();   // s_wave_part / s_tot may be reused
             __builtin_amdgcn_s_setprio(0);
         };
 
         // ---- collect the column sums of pass `it` of `side` and apply the pivot-side update ----
-        auto collect = [&](int side, int it, bool final) -> bool {
+        auto collect = [&](int side, int it, bool final, bool have_early) -> bool {
             __builtin_amdgcn_s_setprio(3);
             float tot = 0.f;
             if (p.cluster > 1) {
@@ -648,7 +681,12 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                     const unsigned long long prev = s_prev[side][it & 1][lane];
                     unsigned long long word = 0;
                     bool ok = false;
-                    for (uint32_t k = 0; k < p.spin_limit; ++k) {
+                    if (have_early) {
+                        word = early_word;
+                        const unsigned arrived = (unsigned)((word >> 56) - (prev >> 56)) & 0xffu;
+                        ok = __all(arrived == (unsigned)p.cluster);
+                    }
+                    for (uint32_t k = 0; !ok && k < p.spin_limit; ++k) {
                         word = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         const unsigned arrived = (unsigned)((word >> 56) - (prev >> 56)) & 0xffu;
                         if (__all(arrived == (unsigned)p.cluster)) { ok = true; break; }
@@ -663,7 +701,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                         s_ok = ok;
                     }
                 }
-                __syncthreads();
+                lds_barrier();
                 if (!s_ok) return false;
             } else if (tid < 64) {
                 tot = s_tot[side][tid];
@@ -671,7 +709,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             if (tid < 64) {
                 if (tid < r) {
                     const float c = fmaxf(tot, 1.0e-37f);
-                    const float b = beta[tid];
+                    const float b = as_global(beta)[tid];
                     if (!final) {
                         s_g[side][tid] += p.eps * logf((float)n * b / c);
                     } else {
@@ -684,15 +722,23 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                     if (side == 0) s_csinv[tid] = 0.f;
                 }
             }
-            __syncthreads();
+            lds_barrier();
             __builtin_amdgcn_s_setprio(0);
             return true;
         };
 
+        Frag<IO, D> xfirst;
+        {
+            const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
+            load_tokens<D>(xfirst, Xs[0] + ((size_t)g * n + tok) * D, kg);
+        }
         for (int it = 1; it <= p.iters; ++it) {
             for (int side = 0; side < 2; ++side) {
-                if (it > 1 && !collect(side, it - 1, false)) return;
-                load_pivot_vector<RB>(G, s_g[side], kg);
+                // the pass after this one: the other side, except that the last query pass is
+                // followed by an epilogue pass (queries again for attention, keys for couplings)
+                const IO* Xnext = (side == 1 && it == p.iters) ? Xs[attention ? 1 : 0] : Xs[side ^ 1];
+                // the post of the previous pass (other side) started this side's poll
+                if (it > 1 && !collect(side, it - 1, false, true)) return;
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -705,23 +751,24 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                             for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
-                    run_pass<IO, D, RB, EPI_ACCUM_U>(p, Xs[side], g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, G, cs,
+                    run_pass<IO, D, RB, EPI_ACCUM_U>(p, Xs[side], Xnext, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                      reinterpret_cast<const IO*>(p.V), U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
                 } else {
-                    run_pass<IO, D, RB, EPI_NONE>(p, Xs[side], g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, G, cs,
+                    run_pass<IO, D, RB, EPI_NONE>(p, Xs[side], Xnext, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                   nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
                 }
-                post(side, it, with_u);
+                // what is collected right after this post: keys' pass `it` after a query pass,
+                // queries' pass `it - 1` after a key pass
+                post(side, it, with_u, side ^ 1, side == 1 ? it : it - 1);
             }
         }
-        if (!collect(0, p.iters, true)) return;
-        if (!collect(1, p.iters, true)) return;
+        if (!collect(0, p.iters, true, true)) return;
+        if (!collect(1, p.iters, true, false)) return;
 
         if (!attention) {
             for (int side = 0; side < 2; ++side) {
-                load_pivot_vector<RB>(G, s_g[side], kg);
                 load_pivot_vector<RB>(cs, s_rho[side], kg);
-                run_pass<IO, D, RB, EPI_GAMMA>(p, Xs[side], g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, G, cs,
+                run_pass<IO, D, RB, EPI_GAMMA>(p, Xs[side], side == 0 ? Xs[1] : nullptr, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
             }
         } else {
@@ -736,20 +783,20 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                     if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     s_ok = ok;
                 }
-                __syncthreads();
+                lds_barrier();
                 if (!s_ok) return;
                 float* yt = p.y_tile + (size_t)g * 64 * D;
                 const int per = (64 * D + p.cluster - 1) / p.cluster;
                 const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
                 const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
+                const __amdgpu_buffer_rsrc_t upv = coherent_view(up);
                 for (int e = e0 + tid; e < e1; e += kFusedThreads) {
                     float acc = 0.f;
                     for (int k0 = 0; k0 < p.cluster; k0 += 8) {
                         float v[8];
-                        const float* ptr[8];
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) ptr[j] = up + (size_t)min(k0 + j, p.cluster - 1) * 64 * D + e;
-                        ld_coherent_batch<8>(v, ptr);
+                        for (int j = 0; j < 8; ++j)
+                            v[j] = ldc_f32(upv, (uint32_t)(((size_t)min(k0 + j, p.cluster - 1) * 64 * D + e) * 4));
 #pragma unroll
                         for (int j = 0; j < 8; ++j) acc += (k0 + j < p.cluster) ? v[j] : 0.f;
                     }
@@ -762,14 +809,13 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                     if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     s_ok = ok;
                 }
-                __syncthreads();
+                lds_barrier();
                 if (!s_ok) return;
                 constexpr int kChunks = 64 * D / 4 / kFusedThreads;   // 16-byte chunks per thread
                 f32x4 v[kChunks];
-                const float* ptr[kChunks];
+                const __amdgpu_buffer_rsrc_t ytv = coherent_view(yt);
 #pragma unroll
-                for (int j = 0; j < kChunks; ++j) ptr[j] = yt + 4 * (tid + j * kFusedThreads);
-                ld_coherent_batch4<kChunks>(v, ptr);
+                for (int j = 0; j < kChunks; ++j) v[j] = ldc_f32x4(ytv, (uint32_t)(16 * (tid + j * kFusedThreads)));
 #pragma unroll
                 for (int j = 0; j < kChunks; ++j) {
                     const int e = 4 * (tid + j * kFusedThreads);
@@ -779,7 +825,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 }
                 __builtin_amdgcn_s_setprio(0);
             }
-            __syncthreads();
+            lds_barrier();
             // lay Y'' out as MFMA B fragments (bf16 hi + lo)
             for (int f = tid; f < 2 * RB * NB * 64; f += kFusedThreads) {
                 const int fl = f & 63, fi = fl & 31, fkg = fl >> 5;
@@ -795,9 +841,8 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 yf_hi[f] = hi;
                 yf_lo[f] = lo;
             }
-            __syncthreads();
-            load_pivot_vector<RB>(G, s_g[1], kg);
-            run_pass<IO, D, RB, EPI_EXPAND>(p, Xs[1], g, 1, tile_begin, tile_end, lane, wave, c1, zf, s_zf, G, cs,
+            lds_barrier();
+            run_pass<IO, D, RB, EPI_EXPAND>(p, Xs[1], nullptr, xfirst, g, 1, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[1], cs,
                                             nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, reinterpret_cast<IO*>(p.out));
         }
         __syncthreads();   // LDS is reused by the next item

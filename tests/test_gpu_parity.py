@@ -31,6 +31,13 @@ CASES = {
     "bf16_d32_r8": S(W["swin_t_s1"], B=1, H=2, n=500, d=32, r=8, iters=6, seed=27),
     "eps_small": S(W["tiny"], n=256, d=32, r=16, eps=0.02, iters=8, seed=28),
     "eps_large": S(W["tiny"], n=256, d=32, r=16, eps=5.0, iters=3, seed=29),
+    # many problems, so that each workgroup keeps a long chunk: several tiles per wavefront
+    # (the in-loop prefetch and the ragged last chunk), and more work items than the device
+    # holds at once (the persistent loop takes a second round)
+    "many_tiles_bf16": S(W["long_4k"], B=16, H=8, n=2000, iters=4, seed=33),
+    "many_tiles_f32": S(W["deit_tiny"], B=32, H=4, n=700, d=64, r=16, iters=5, seed=34),
+    "two_rounds_f32": S(W["tiny"], B=150, H=4, n=160, d=32, r=8, iters=5, seed=35),
+    "two_rounds_bf16": S(W["bert_base"], B=50, H=12, n=300, r=32, iters=3, seed=36),
 }
 
 
