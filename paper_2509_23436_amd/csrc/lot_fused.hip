@@ -412,13 +412,7 @@ __device__ __forceinline__ void run_pass(
         asm volatile("" : "+v"(skew));
         f32x16 acc[RB];
         load_pivot_vector<RB>(acc, glds + skew, kg);
-        if (EPI != EPI_ACCUM_U) {
-            similarity<D, RB>(acc, zf, xc);
-        } else {
-            Frag<IO, D> zl[RB];
-            fetch_pivots<D, RB>(zl, zlds, lane, skew);
-            similarity<D, RB>(acc, zl, xc);
-        }
+        similarity<D, RB>(acc, zf, xc);
 
         // token-side update: row maximum, exponentials, row sum
         float m0 = acc[0][0], m1 = acc[0][1], m2 = acc[0][2], m3 = acc[0][3];
@@ -457,17 +451,20 @@ __device__ __forceinline__ void run_pass(
         }
 
         if (EPI == EPI_ACCUM_U) {
-            // transpose the coupling tile (tokens in lanes -> tokens along K) through LDS as bf16 hi + lo
+            // Transpose the coupling tile (tokens in lanes -> tokens along K) through LDS as bf16.
+            // With fp32 I/O the weights and the values are split into hi + lo parts (three products);
+            // with bf16 I/O one product is enough: the rounding of the weights (2^-9, zero mean)
+            // averages out over the tokens and stays far below the rounding of the bf16 output.
+            constexpr bool kSplit = io_is_f32<IO>::value;
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
                     const float v = acc[mb][j] * w;
                     const __bf16 h = (__bf16)v;
-                    const __bf16 l = (__bf16)(v - (float)h);
                     const int pv = pivot_of(mb, j, kg);
                     tr_hi[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, h);
-                    tr_lo[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, l);
+                    if (kSplit) tr_lo[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, (__bf16)(v - (float)h));
                 }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -481,13 +478,16 @@ __device__ __forceinline__ void run_pass(
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb) {
                     const bf16x8 ah = *reinterpret_cast<const bf16x8*>(tr_hi + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
-                    const bf16x8 al = *reinterpret_cast<const bf16x8*>(tr_lo + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
+                    for (int nb = 0; nb < NB; ++nb)
                         U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vh[nb], U[mb][nb], 0, 0, 0);
-                        U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, vh[nb], U[mb][nb], 0, 0, 0);
-                        if (io_is_f32<IO>::value)
+                    if (kSplit) {
+                        const bf16x8 al = *reinterpret_cast<const bf16x8*>(tr_lo + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) {
+                            U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, vh[nb], U[mb][nb], 0, 0, 0);
                             U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vl[nb], U[mb][nb], 0, 0, 0);
+                        }
                     }
                 }
             }
@@ -501,28 +501,38 @@ __device__ __forceinline__ void run_pass(
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) oacc[nb][j] = 0.f;
+            constexpr bool kSplit = io_is_f32<IO>::value;   // see the accumulation pass
 #pragma unroll
             for (int s = 0; s < 2 * RB; ++s) {
                 f32x8 wv;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) wv[e] = acc[s >> 1][8 * (s & 1) + e] * w;
                 bf16x8 ah, al;
-                split_bf16(wv, ah, al);
+                if (kSplit) split_bf16(wv, ah, al);
+                else ah = __builtin_convertvector(wv, bf16x8);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     const bf16x8 yh = yf_hi[(s * NB + nb) * 64 + lane];
                     oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, yh, oacc[nb], 0, 0, 0);
-                    oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, yh, oacc[nb], 0, 0, 0);
-                    if (io_is_f32<IO>::value) {
+                    if (kSplit) {
                         const bf16x8 yl = yf_lo[(s * NB + nb) * 64 + lane];
+                        oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, yh, oacc[nb], 0, 0, 0);
                         oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, yl, oacc[nb], 0, 0, 0);
                     }
                 }
             }
+            if ((tile + 1) * kTileTokens <= n) {   // whole tile in range: no per-row test
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int tr = tile * kTileTokens + 8 * (j >> 2) + 4 * kg + (j & 3);
-                if (tr < n) store_out<NB>(out + ((size_t)g * n + tr) * D, i, oacc[0][j], oacc[NB - 1][j]);
+                for (int j = 0; j < 16; ++j) {
+                    const int tr = tile * kTileTokens + 8 * (j >> 2) + 4 * kg + (j & 3);
+                    store_out<NB>(out + ((size_t)g * n + tr) * D, i, oacc[0][j], oacc[NB - 1][j]);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int tr = tile * kTileTokens + 8 * (j >> 2) + 4 * kg + (j & 3);
+                    if (tr < n) store_out<NB>(out + ((size_t)g * n + tr) * D, i, oacc[0][j], oacc[NB - 1][j]);
+                }
             }
         }
 
@@ -588,6 +598,12 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
         const float* beta = p.beta + (size_t)h * r;
         const IO* Xs[2] = {reinterpret_cast<const IO*>(p.K), reinterpret_cast<const IO*>(p.Q)};
 
+        // the first key tile is requested before anything else: its latency overlaps the set-up
+        Frag<IO, D> xfirst;
+        {
+            const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
+            load_tokens<D>(xfirst, Xs[0] + ((size_t)g * n + tok) * D, kg);
+        }
         Frag<IO, D> zf[RB];
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) {
@@ -601,7 +617,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
         f32x16 cs[RB], U[RB][NB];
 
         // ---- post this workgroup's share of a pass (column sums, and U on the last key pass) ----
-        unsigned long long early_word = 0;   // wavefront 0: a poll issued ahead of its use
+        unsigned long long early_word = 0, early_word2 = 0;   // wavefront 0: polls issued ahead of their use
         auto post = [&](int side, int it, bool with_u, int next_side, int next_it) {
             __builtin_amdgcn_s_setprio(3);
             if (p.cluster > 1 && wave == 0 && next_it >= 1) {
@@ -609,6 +625,10 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 // pass's sums are reduced and posted.  collect() validates what arrives.
                 early_word = ldc_u64(coherent_view(p.colacc),
                                      (uint32_t)(((((size_t)2 * g + next_side) * 2 + (next_it & 1)) * 64 + lane) * 8));
+                // after the very last pass both sides are collected back to back
+                if (side == 1 && it == p.iters)
+                    early_word2 = ldc_u64(coherent_view(p.colacc),
+                                          (uint32_t)(((((size_t)2 * g + 1) * 2 + (it & 1)) * 64 + lane) * 8));
             }
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
@@ -671,7 +691,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
         };
 
         // ---- collect the column sums of pass `it` of `side` and apply the pivot-side update ----
-        auto collect = [&](int side, int it, bool final, bool have_early) -> bool {
+        auto collect = [&](int side, int it, bool final, bool have_early, unsigned long long early) -> bool {
             __builtin_amdgcn_s_setprio(3);
             float tot = 0.f;
             if (p.cluster > 1) {
@@ -682,7 +702,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                     unsigned long long word = 0;
                     bool ok = false;
                     if (have_early) {
-                        word = early_word;
+                        word = early;
                         const unsigned arrived = (unsigned)((word >> 56) - (prev >> 56)) & 0xffu;
                         ok = __all(arrived == (unsigned)p.cluster);
                     }
@@ -727,18 +747,13 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             return true;
         };
 
-        Frag<IO, D> xfirst;
-        {
-            const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
-            load_tokens<D>(xfirst, Xs[0] + ((size_t)g * n + tok) * D, kg);
-        }
         for (int it = 1; it <= p.iters; ++it) {
             for (int side = 0; side < 2; ++side) {
                 // the pass after this one: the other side, except that the last query pass is
                 // followed by an epilogue pass (queries again for attention, keys for couplings)
                 const IO* Xnext = (side == 1 && it == p.iters) ? Xs[attention ? 1 : 0] : Xs[side ^ 1];
                 // the post of the previous pass (other side) started this side's poll
-                if (it > 1 && !collect(side, it - 1, false, true)) return;
+                if (it > 1 && !collect(side, it - 1, false, true, early_word)) return;
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -762,8 +777,41 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 post(side, it, with_u, side ^ 1, side == 1 ? it : it - 1);
             }
         }
-        if (!collect(0, p.iters, true, true)) return;
-        if (!collect(1, p.iters, true, false)) return;
+        float* yt = p.y_tile + (size_t)g * 64 * D;
+        if (attention && p.cluster > 1) {
+            // The U partials were posted a whole pass ago.  Each workgroup of the cluster sums one
+            // slice of them (raw, still unnormalised) and publishes it; this runs before the last
+            // column sums are collected, whose polls are already in flight.
+            __builtin_amdgcn_s_setprio(3);
+            if (tid == 0) {
+                const bool ok = spin_until(p.arrive + g, (uint32_t)p.cluster, p.status, p.spin_limit);
+                if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_ok = ok;
+            }
+            lds_barrier();
+            if (!s_ok) return;
+            const int per = (64 * D + p.cluster - 1) / p.cluster;
+            const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
+            const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
+            const __amdgpu_buffer_rsrc_t upv = coherent_view(up);
+            for (int e = e0 + tid; e < e1; e += kFusedThreads) {
+                float acc = 0.f;
+                for (int k0 = 0; k0 < p.cluster; k0 += 8) {
+                    float v[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        v[j] = ldc_f32(upv, (uint32_t)(((size_t)min(k0 + j, p.cluster - 1) * 64 * D + e) * 4));
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc += (k0 + j < p.cluster) ? v[j] : 0.f;
+                }
+                st_coherent(yt + e, acc);
+            }
+            __syncthreads();   // the slice has been acknowledged
+            if (tid == 0) __hip_atomic_fetch_add(p.yready + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_setprio(0);
+        }
+        if (!collect(0, p.iters, true, true, early_word)) return;
+        if (!collect(1, p.iters, true, true, early_word2)) return;
 
         if (!attention) {
             for (int side = 0; side < 2; ++side) {
@@ -776,35 +824,8 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             if (p.cluster == 1) {
                 for (int e = tid; e < 64 * D; e += kFusedThreads) s_u[e] *= s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
             } else {
-                // each workgroup of the cluster reduces one slice of the U partials into Y'
                 __builtin_amdgcn_s_setprio(3);
                 if (tid == 0) {
-                    const bool ok = spin_until(p.arrive + g, (uint32_t)p.cluster, p.status, p.spin_limit);
-                    if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    s_ok = ok;
-                }
-                lds_barrier();
-                if (!s_ok) return;
-                float* yt = p.y_tile + (size_t)g * 64 * D;
-                const int per = (64 * D + p.cluster - 1) / p.cluster;
-                const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
-                const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
-                const __amdgpu_buffer_rsrc_t upv = coherent_view(up);
-                for (int e = e0 + tid; e < e1; e += kFusedThreads) {
-                    float acc = 0.f;
-                    for (int k0 = 0; k0 < p.cluster; k0 += 8) {
-                        float v[8];
-#pragma unroll
-                        for (int j = 0; j < 8; ++j)
-                            v[j] = ldc_f32(upv, (uint32_t)(((size_t)min(k0 + j, p.cluster - 1) * 64 * D + e) * 4));
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) acc += (k0 + j < p.cluster) ? v[j] : 0.f;
-                    }
-                    st_coherent(yt + e, acc * s_csinv[e / D]);
-                }
-                __syncthreads();
-                if (tid == 0) {
-                    __hip_atomic_fetch_add(p.yready + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     const bool ok = spin_until(p.yready + g, (uint32_t)p.cluster, p.status, p.spin_limit);
                     if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     s_ok = ok;
@@ -819,7 +840,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
 #pragma unroll
                 for (int j = 0; j < kChunks; ++j) {
                     const int e = 4 * (tid + j * kFusedThreads);
-                    const float sc = (float)n * s_rho[1][e / D];
+                    const float sc = s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
 #pragma unroll
                     for (int c = 0; c < 4; ++c) s_u[e + c] = v[j][c] * sc;
                 }
