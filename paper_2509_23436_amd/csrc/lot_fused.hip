@@ -218,23 +218,33 @@ __device__ __forceinline__ void load_tokens(Frag<float, D>& f, const float* row,
     }
 }
 
-// pivot rows: Z is fp32 in memory; the bf16 path rounds it to bf16 (nearest even) here
+// pivot rows: Z is fp32 in memory; the bf16 path rounds it to bf16 (nearest even) here.
+// zrow always points at a real row (the caller clamps the index), so the loads are unconditional
+// 16-byte vectors; rows of padding pivots are zeroed afterwards.
 template <int D>
 __device__ __forceinline__ void load_pivots(Frag<uint16_t, D>& f, const float* zrow, int kg, bool valid)
 {
+    f32x4 raw[D / 16][2];
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) raw[s][q] = *as_global(reinterpret_cast<const f32x4*>(zrow + 16 * s + 8 * kg + 4 * q));
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
         f32x8 t;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = valid ? as_global(zrow)[16 * s + 8 * kg + e] : 0.f;
+        for (int e = 0; e < 8; ++e) t[e] = valid ? raw[s][e >> 2][e & 3] : 0.f;
         f.v[s] = __builtin_convertvector(t, bf16x8);
     }
 }
 template <int D>
 __device__ __forceinline__ void load_pivots(Frag<float, D>& f, const float* zrow, int kg, bool valid)
 {
+    f32x4 raw[D / 8];
 #pragma unroll
-    for (int s = 0; s < D / 2; ++s) f.v[s] = valid ? as_global(zrow)[kg * (D / 2) + s] : 0.f;
+    for (int q = 0; q < D / 8; ++q) raw[q] = *as_global(reinterpret_cast<const f32x4*>(zrow + kg * (D / 2) + 4 * q));
+#pragma unroll
+    for (int s = 0; s < D / 2; ++s) f.v[s] = valid ? raw[s >> 2][s & 3] : 0.f;
 }
 
 // Pivot fragments kept in LDS as [block][step][lane], so that the heavier passes need not hold
@@ -405,6 +415,17 @@ __device__ __forceinline__ void run_pass(
             load_tokens<D>(xn, Xnext + ((size_t)g * n + tok) * D, kg);
         }
 
+        // the value rows this tile will be multiplied with are requested now and used at the end
+        bf16x8 vh[2][NB], vl[2][NB];
+        if (EPI == EPI_ACCUM_U) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
+                const int left = max(1, min(8, n - t0));
+                load_values<D>(vh[s], vl[s], V, (size_t)g * n + min(t0, n - 1), left, i);
+            }
+        }
+
         // The accumulators start from the pivot potentials g_t, read from LDS for every tile (an
         // opaque zero offset keeps the reads inside the loop): holding them in registers for the
         // whole pass costs 16*RB registers that the prefetched tile rows need more.
@@ -471,22 +492,18 @@ __device__ __forceinline__ void run_pass(
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                bf16x8 vh[NB], vl[NB];
-                const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
-                const int left = max(1, min(8, n - t0));
-                load_values<D>(vh, vl, V, (size_t)g * n + min(t0, n - 1), left, i);
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb) {
                     const bf16x8 ah = *reinterpret_cast<const bf16x8*>(tr_hi + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
-                        U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vh[nb], U[mb][nb], 0, 0, 0);
+                        U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vh[s][nb], U[mb][nb], 0, 0, 0);
                     if (kSplit) {
                         const bf16x8 al = *reinterpret_cast<const bf16x8*>(tr_lo + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
 #pragma unroll
                         for (int nb = 0; nb < NB; ++nb) {
-                            U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, vh[nb], U[mb][nb], 0, 0, 0);
-                            U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vl[nb], U[mb][nb], 0, 0, 0);
+                            U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, vh[s][nb], U[mb][nb], 0, 0, 0);
+                            U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vl[s][nb], U[mb][nb], 0, 0, 0);
                         }
                     }
                 }
