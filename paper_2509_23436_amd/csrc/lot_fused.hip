@@ -55,6 +55,15 @@ constexpr float kLog2e = 1.44269504088896340736f;
 enum { EPI_NONE = 0, EPI_ACCUM_U = 1, EPI_EXPAND = 2, EPI_GAMMA = 3 };
 enum { MODE_ATTENTION = 0, MODE_COUPLINGS = 1 };
 
+// Developer instrumentation (compiled out unless LOT_TRACE is defined): thread 0 of every workgroup
+// stamps the constant-rate clock into slot `slot` of its 128-slot record, kept in the last 8 MiB of
+// the workspace (a region only the reference path uses).
+#ifdef LOT_TRACE
+#define LOT_STAMP(slot) do { if (threadIdx.x == 0 && (slot) < 128) p.trace[(size_t)blockIdx.x * 128 + (slot)] = wall_clock64(); } while (0)
+#else
+#define LOT_STAMP(slot) do { } while (0)
+#endif
+
 struct FusedParams {
     const void* Q;
     const void* K;
@@ -75,6 +84,7 @@ struct FusedParams {
     float eps;
     float fx_scale, fx_unscale;   // 2^F and 2^-F of the fixed-point column sums
     uint32_t spin_limit;
+    unsigned long long* trace;   // LOT_TRACE builds only
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -591,6 +601,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
     __shared__ float s_g[2][64];       // pivot potentials per side (0 = keys, 1 = queries)
     __shared__ float s_rho[2][64];     // beta_t / colsum_t after the last iteration
     __shared__ float s_csinv[64];      // 1 / colsum_t of the key side after the last iteration
+    __shared__ float s_beta[64];
     __shared__ __attribute__((aligned(16))) float s_u[64 * D];
     __shared__ __attribute__((aligned(16))) uint16_t s_tr[kFusedWaves * 2 * 64 * kTrStride];
     __shared__ __attribute__((aligned(16))) char s_zf[RB * sizeof(Frag<IO, D>) * 64];
@@ -609,6 +620,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
     const bool attention = p.mode == MODE_ATTENTION;
 
     for (int item = blockIdx.x; item < p.num_items; item += gridDim.x) {
+        LOT_STAMP(0);
         const int g = item / p.cluster, chunk = item % p.cluster, h = g % p.H;
         const int tile_begin = chunk * p.tiles_per_wg;
         const int tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
@@ -629,20 +641,66 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
         }
         if (wave == 0) stash_pivots<D, RB>(s_zf, zf, lane);
         if (tid < 128) s_g[tid >> 6][tid & 63] = (tid & 63) < r ? 0.f : kNegBig;
+        if (tid < 64) s_beta[tid] = tid < r ? as_global(beta)[tid] : 1.f;
         (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
         lds_barrier();
         f32x16 cs[RB], U[RB][NB];
+        LOT_STAMP(1);
 
-        // ---- post this workgroup's share of a pass (column sums, and U on the last key pass) ----
         unsigned long long early_word = 0, early_word2 = 0;   // wavefront 0: polls issued ahead of their use
-        auto post = [&](int side, int it, bool with_u, int next_side, int next_it) {
+
+        // ---- wavefront 0: take the column sums of pass `it` of `side` (lane = pivot) and apply the
+        //      pivot-side update.  No barrier inside; the caller publishes the result.
+        auto collect_w0 = [&](int side, int it, bool final, unsigned long long early) -> bool {
+            float tot = 0.f;
+            bool ok = true;
+            if (p.cluster > 1) {
+                // every pivot's word carries its own arrival count: complete when all 64 agree
+                const unsigned long long* src = p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + lane;
+                const unsigned long long prev = s_prev[side][it & 1][lane];
+                unsigned long long word = early;   // a poll that was started ahead; validated here
+                ok = __all(((unsigned)((word >> 56) - (prev >> 56)) & 0xffu) == (unsigned)p.cluster);
+                for (uint32_t k = 0; !ok && k < p.spin_limit; ++k) {
+                    word = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (__all(((unsigned)((word >> 56) - (prev >> 56)) & 0xffu) == (unsigned)p.cluster)) { ok = true; break; }
+                    if ((k & 63u) == 63u && __hip_atomic_load(p.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                s_prev[side][it & 1][lane] = word;
+                const unsigned long long mask = (1ull << 56) - 1ull;
+                tot = (float)(long long)((word & mask) - (prev & mask)) * p.fx_unscale;
+                if (!ok && lane == 0) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                tot = s_tot[side][lane];
+            }
+            if (lane < r) {
+                const float c = fmaxf(tot, 1.0e-37f);
+                const float b = s_beta[lane];
+                if (!final) {
+                    s_g[side][lane] += p.eps * logf((float)n * b / c);
+                } else {
+                    // the last pass's potentials stay: the epilogue rebuilds its coupling from them
+                    s_rho[side][lane] = b / c;
+                    if (side == 0) s_csinv[lane] = 1.f / c;
+                }
+            } else if (final) {
+                s_rho[side][lane] = 0.f;
+                if (side == 0) s_csinv[lane] = 0.f;
+            }
+            return ok;
+        };
+
+        // ---- after a pass: post this workgroup's share (column sums; U on the last key pass) and,
+        //      in the same breath, collect the other side's previous pass, which was posted one
+        //      whole pass ago.  Two workgroup barriers in all.
+        auto exchange = [&](int side, int it, bool with_u, int cside, int cit, bool cfinal) -> bool {
+            LOT_STAMP(9 + 6 * ((it - 1) * 2 + side));   // pass done
             __builtin_amdgcn_s_setprio(3);
-            if (p.cluster > 1 && wave == 0 && next_it >= 1) {
-                // start the poll that the following collect() needs; it completes while this
-                // pass's sums are reduced and posted.  collect() validates what arrives.
+            if (p.cluster > 1 && wave == 0 && cit >= 1) {
+                // start the poll now; it completes while this pass's sums are reduced
                 early_word = ldc_u64(coherent_view(p.colacc),
-                                     (uint32_t)(((((size_t)2 * g + next_side) * 2 + (next_it & 1)) * 64 + lane) * 8));
-                // after the very last pass both sides are collected back to back
+                                     (uint32_t)(((((size_t)2 * g + cside) * 2 + (cit & 1)) * 64 + lane) * 8));
+                // after the very last pass the query side is collected as well
                 if (side == 1 && it == p.iters)
                     early_word2 = ldc_u64(coherent_view(p.colacc),
                                           (uint32_t)(((((size_t)2 * g + 1) * 2 + (it & 1)) * 64 + lane) * 8));
@@ -662,6 +720,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                         *reinterpret_cast<f32x4*>(&s_wave_part[wave][32 * mb + 8 * q + 4 * kg]) = t;
                     }
             }
+            LOT_STAMP(10 + 6 * ((it - 1) * 2 + side));   // own sums reduced
             if (with_u) {
                 // workgroup total of U in s_u, one wavefront at a time (fixed order)
                 for (int turn = 0; turn < kFusedWaves; ++turn) {
@@ -681,21 +740,27 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             } else {
                 lds_barrier();
             }
-            if (tid < 64) {
-                float tot = s_wave_part[0][tid];
-                tot += s_wave_part[1][tid];
-                tot += s_wave_part[2][tid];
-                tot += s_wave_part[3][tid];
-                if (tid >= r) tot = 0.f;   // padding pivots (their LDS slots may never have been written)
+            LOT_STAMP(11 + 6 * ((it - 1) * 2 + side));   // all wavefronts' sums in LDS
+            if (wave == 0) {
+                float tot = s_wave_part[0][lane];
+                tot += s_wave_part[1][lane];
+                tot += s_wave_part[2][lane];
+                tot += s_wave_part[3][lane];
+                if (lane >= r) tot = 0.f;   // padding pivots (their LDS slots may never have been written)
                 if (p.cluster > 1) {
                     // one fire-and-forget atomic per pivot: the workgroup's column sum in fixed point
                     // (integer addition: the total does not depend on arrival order) plus one count
                     const unsigned long long word = (1ull << 56) + (unsigned long long)__float2ll_rn(tot * p.fx_scale);
-                    __hip_atomic_fetch_add(p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + tid, word,
+                    __hip_atomic_fetch_add(p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + lane, word,
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 } else {
-                    s_tot[side][tid] = tot;
+                    s_tot[side][lane] = tot;
                 }
+                LOT_STAMP(12 + 6 * ((it - 1) * 2 + side));   // posted
+                bool ok = true;
+                if (cit >= 1) ok = collect_w0(cside, cit, cfinal, early_word);
+                LOT_STAMP(13 + 6 * ((it - 1) * 2 + side));   // collected
+                if (lane == 0) s_ok = ok;
             }
             if (p.cluster > 1 && with_u) {
                 float* up = p.u_part + ((size_t)g * p.cluster_cap + chunk) * 64 * D;
@@ -703,65 +768,9 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 __syncthreads();   // the stores above have been acknowledged
                 if (tid == 0) __hip_atomic_fetch_add(p.arrive + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            lds_barrier();   // s_wave_part / s_tot may be reused
+            lds_barrier();   // potentials published; s_wave_part / s_tot may be reused
             __builtin_amdgcn_s_setprio(0);
-        };
-
-        // ---- collect the column sums of pass `it` of `side` and apply the pivot-side update ----
-        auto collect = [&](int side, int it, bool final, bool have_early, unsigned long long early) -> bool {
-            __builtin_amdgcn_s_setprio(3);
-            float tot = 0.f;
-            if (p.cluster > 1) {
-                if (wave == 0) {
-                    // every pivot's word carries its own arrival count: poll until all 64 are complete
-                    const unsigned long long* src = p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + lane;
-                    const unsigned long long prev = s_prev[side][it & 1][lane];
-                    unsigned long long word = 0;
-                    bool ok = false;
-                    if (have_early) {
-                        word = early;
-                        const unsigned arrived = (unsigned)((word >> 56) - (prev >> 56)) & 0xffu;
-                        ok = __all(arrived == (unsigned)p.cluster);
-                    }
-                    for (uint32_t k = 0; !ok && k < p.spin_limit; ++k) {
-                        word = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        const unsigned arrived = (unsigned)((word >> 56) - (prev >> 56)) & 0xffu;
-                        if (__all(arrived == (unsigned)p.cluster)) { ok = true; break; }
-                        if ((k & 63u) == 63u && __hip_atomic_load(p.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
-                        __builtin_amdgcn_s_sleep(1);
-                    }
-                    s_prev[side][it & 1][lane] = word;
-                    const unsigned long long mask = (1ull << 56) - 1ull;
-                    tot = (float)(long long)((word & mask) - (prev & mask)) * p.fx_unscale;
-                    if (lane == 0) {
-                        if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        s_ok = ok;
-                    }
-                }
-                lds_barrier();
-                if (!s_ok) return false;
-            } else if (tid < 64) {
-                tot = s_tot[side][tid];
-            }
-            if (tid < 64) {
-                if (tid < r) {
-                    const float c = fmaxf(tot, 1.0e-37f);
-                    const float b = as_global(beta)[tid];
-                    if (!final) {
-                        s_g[side][tid] += p.eps * logf((float)n * b / c);
-                    } else {
-                        // the last pass's potentials stay: the epilogue rebuilds its coupling from them
-                        s_rho[side][tid] = b / c;
-                        if (side == 0) s_csinv[tid] = 1.f / c;
-                    }
-                } else if (final) {
-                    s_rho[side][tid] = 0.f;
-                    if (side == 0) s_csinv[tid] = 0.f;
-                }
-            }
-            lds_barrier();
-            __builtin_amdgcn_s_setprio(0);
-            return true;
+            return s_ok != 0;
         };
 
         for (int it = 1; it <= p.iters; ++it) {
@@ -769,13 +778,12 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 // the pass after this one: the other side, except that the last query pass is
                 // followed by an epilogue pass (queries again for attention, keys for couplings)
                 const IO* Xnext = (side == 1 && it == p.iters) ? Xs[attention ? 1 : 0] : Xs[side ^ 1];
-                // the post of the previous pass (other side) started this side's poll
-                if (it > 1 && !collect(side, it - 1, false, true, early_word)) return;
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
                     for (int j = 0; j < 16; ++j) cs[mb][j] = 0.f;
                 const bool with_u = attention && side == 0 && it == p.iters;
+                LOT_STAMP(8 + 6 * ((it - 1) * 2 + side));   // pass starts
                 if (with_u) {
 #pragma unroll
                     for (int mb = 0; mb < RB; ++mb)
@@ -789,9 +797,10 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                     run_pass<IO, D, RB, EPI_NONE>(p, Xs[side], Xnext, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                   nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
                 }
-                // what is collected right after this post: keys' pass `it` after a query pass,
-                // queries' pass `it - 1` after a key pass
-                post(side, it, with_u, side ^ 1, side == 1 ? it : it - 1);
+                // what is collected along with this post: keys' pass `it` after a query pass (for
+                // the last iteration that is the keys' final update), queries' pass `it - 1` after
+                // a key pass
+                if (!exchange(side, it, with_u, side ^ 1, side == 1 ? it : it - 1, side == 1 && it == p.iters)) return;
             }
         }
         float* yt = p.y_tile + (size_t)g * 64 * D;
@@ -827,9 +836,17 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             if (tid == 0) __hip_atomic_fetch_add(p.yready + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __builtin_amdgcn_s_setprio(0);
         }
-        if (!collect(0, p.iters, true, true, early_word)) return;
-        if (!collect(1, p.iters, true, true, early_word2)) return;
+        // the queries' final update (the keys' was taken with the last exchange)
+        __builtin_amdgcn_s_setprio(3);
+        if (wave == 0) {
+            const bool ok = collect_w0(1, p.iters, true, early_word2);
+            if (lane == 0) s_ok = ok;
+        }
+        lds_barrier();
+        __builtin_amdgcn_s_setprio(0);
+        if (!s_ok) return;
 
+        LOT_STAMP(2);
         if (!attention) {
             for (int side = 0; side < 2; ++side) {
                 load_pivot_vector<RB>(cs, s_rho[side], kg);
@@ -865,6 +882,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             }
             lds_barrier();
             // lay Y'' out as MFMA B fragments (bf16 hi + lo)
+            LOT_STAMP(3);
             for (int f = tid; f < 2 * RB * NB * 64; f += kFusedThreads) {
                 const int fl = f & 63, fi = fl & 31, fkg = fl >> 5;
                 const int snb = f >> 6, s = snb / NB, nb = snb % NB;
@@ -880,9 +898,11 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 yf_lo[f] = lo;
             }
             lds_barrier();
+            LOT_STAMP(4);
             run_pass<IO, D, RB, EPI_EXPAND>(p, Xs[1], nullptr, xfirst, g, 1, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[1], cs,
                                             nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, reinterpret_cast<IO*>(p.out));
         }
+        LOT_STAMP(5);
         __syncthreads();   // LDS is reused by the next item
     }
 }
@@ -935,6 +955,7 @@ int launch(const Args& a, bool want_out)
     p.num_items = G * cluster; p.iters = a.iters; p.mode = want_out ? MODE_ATTENTION : MODE_COUPLINGS;
     p.eps = a.eps;
     p.spin_limit = 1u << 21;
+    p.trace = (unsigned long long*)(a.ws + a.lay.total - (8u << 20));
 
     // Fixed-point format of the exchanged column sums: a parity buffer receives at most
     // iters/2 + 1 passes, each adding at most n per pivot, and must stay below 2^55.
