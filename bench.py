@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--rotate", type=int, default=8)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "reference"])
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="instead of the benchmark, run a plain device copy of this many MiB ten times "
+                         "(used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the (batch, head) problems are independent; "
@@ -67,6 +70,14 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.calibrate_copy > 0:
+        src = torch.full((args.calibrate_copy << 20,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": args.calibrate_copy << 20, "copies": 10}))
+        return 0
     w = synth.WORKLOADS[args.workload]
     path = {"auto": lot.PATH_AUTO, "fused": lot.PATH_FUSED, "reference": lot.PATH_REFERENCE}[args.path]
     x = synth.make_inputs(w)

@@ -86,7 +86,12 @@ int lot_attention_fwd_path(const lot_shape* shape, const void* Q, const void* K,
     Args a{};
     a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.out = out; a.ws = (char*)workspace; a.lay = carve(*shape); a.stream = (hipStream_t)hip_stream;
-    if (fused) return run_fused(a, true);
+    if (fused) {
+        rc = run_fused(a, true);
+        // AUTO falls back to the reference kernels for the (astronomical) iteration counts whose
+        // column sums do not fit the fused kernel's fixed-point exchange format
+        if (!(rc == LOT_ERR_PATH && path == LOT_PATH_AUTO)) return rc;
+    }
     a.gamma1 = (float*)(a.ws + a.lay.gamma1);
     a.gamma2 = (float*)(a.ws + a.lay.gamma2);
     return run_reference(a, true);
@@ -108,7 +113,11 @@ int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,
     a.s = *shape; a.Q = Q; a.K = K; a.V = nullptr; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.out = nullptr; a.gamma1 = gamma1; a.gamma2 = gamma2;
     a.ws = (char*)workspace; a.lay = carve(*shape); a.stream = (hipStream_t)hip_stream;
-    return fused ? run_fused(a, false) : run_reference(a, false);
+    if (fused) {
+        rc = run_fused(a, false);
+        if (!(rc == LOT_ERR_PATH && path == LOT_PATH_AUTO)) return rc;
+    }
+    return run_reference(a, false);
 }
 
 int lot_attention_fwd(const lot_shape* shape, const void* Q, const void* K, const void* V,

@@ -1,0 +1,71 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The library runs the WHOLE workload (so the cluster size, tiles per wavefront and number of
+rounds are those of the benchmark); the fp64 oracle recomputes a SAMPLE of the (batch, head)
+problems one by one -- they are independent, so each sampled problem is compared in full, element
+by element.  Bars: fp32 I/O <= 1e-4 (max-norm relative) on O, bf16 I/O <= 2e-2; marginal residuals
+<= 1e-5 on the sampled problems.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2509_23436_amd import synth
+from util import rel_max_err, to_device, to_host_f64, tolerance
+
+pytestmark = pytest.mark.gpu
+
+# workload -> sampled problems (flat index b*H + h): first, last and some in between
+SAMPLES = {
+    "tiny": [0],
+    "deit_tiny": [0, 95, 191],
+    "bert_base": [0, 200, 383],
+    "swin_t_s1": [0, 25, 47],
+    "long_4k": [0, 9, 15],
+    "long_16k": [0, 7, 15],
+    "long_64k": [3, 12],
+}
+
+
+@pytest.mark.parametrize("name", list(SAMPLES))
+def test_full_size_workload_matches_oracle_on_sampled_problems(name):
+    import torch
+    from oracle import lot_oracle
+    from paper_2509_23436_amd import lot
+    w = synth.WORKLOADS[name]
+    print("workload %r" % (w,), flush=True)
+    sys.stdout.flush()
+    x = synth.make_inputs(w)
+    dev = to_device(x, w.dtype)
+    shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
+    ws = lot.alloc_workspace(shape, w.iters)
+    out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, workspace=ws)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(ws) == 0
+    g1, g2 = lot.lot_couplings(dev["Q"], dev["K"], dev["Z"], dev["beta"], w.eps, w.iters, workspace=ws)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(ws) == 0
+    assert torch.isfinite(out.float()).all()
+    tol_o, tol_m = tolerance(w.dtype)
+
+    idx = SAMPLES[name]
+    flat = lambda t: t.reshape(w.G, *t.shape[2:])                       # noqa: E731
+    q, k, v = (np.ascontiguousarray(flat(x[key])[idx])[None] for key in ("Q", "K", "V"))
+    z = np.ascontiguousarray(np.stack([x["Z"][g % w.H] for g in idx]))
+    b = np.ascontiguousarray(np.stack([x["beta"][g % w.H] for g in idx]))
+    O_ref, g1_ref, g2_ref, _ = lot_oracle.attention(q, k, v, z, b, w.eps, w.iters, want_couplings=True,
+                                                    threads=len(idx))
+    sel = torch.tensor(idx, device="cuda")
+    O = to_host_f64(out.reshape(w.G, w.n, w.d)[sel])
+    err = rel_max_err(O, O_ref[0])
+    print("  O on %d sampled problems: max-norm rel err %.3e (bar %.0e)" % (len(idx), err, tol_o), flush=True)
+    assert err <= tol_o
+    G1 = to_host_f64(g1.reshape(w.G, w.n, w.r)[sel])
+    G2 = to_host_f64(g2.reshape(w.G, w.r, w.n)[sel])
+    res = lot_oracle.marginal_residuals(G1, G2, b)
+    res_ref = lot_oracle.marginal_residuals(g1_ref[0], g2_ref[0], b)
+    merr = max(float(np.abs(a - c).max()) for a, c in zip(res, res_ref))
+    piv = max(float(np.abs(res[1]).max()), float(np.abs(res[3]).max()))
+    print("  marginal residual err %.3e, pivot-side residual %.3e (bar %.0e)" % (merr, piv, tol_m), flush=True)
+    assert merr <= tol_m and piv <= tol_m
