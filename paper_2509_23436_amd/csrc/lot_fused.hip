@@ -25,6 +25,8 @@
 //
 // Cross-workgroup waits are bounded: a wait that exceeds its poll budget raises the status word
 // in the workspace and the workgroup leaves the kernel, so every wavefront always exits.
+#include <atomic>
+#include <chrono>
 #include <cmath>
 
 #include "lot_internal.h"
@@ -76,6 +78,8 @@ struct FusedParams {
     uint32_t* status;
     uint32_t* arrive;     // [G]: workgroups that have posted their share of U
     uint32_t* yready;     // [G]
+    unsigned long long* cleared;   // [G]: holds this launch's nonce once the problem's counters are zero
+    unsigned long long nonce;
     unsigned long long* colacc;   // [G][2 sides][2 parities][64]: count << 56 | fixed-point column sum
     float* u_part;        // [G][cluster_cap][64][D]
     float* y_tile;        // [G][64][D]
@@ -643,6 +647,20 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
         if (tid < 128) s_g[tid >> 6][tid & 63] = (tid & 63) < r ? 0.f : kNegBig;
         if (tid < 64) s_beta[tid] = tid < r ? as_global(beta)[tid] : 1.f;
         (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
+        if (blockIdx.x == 0 && tid == 0 && item == (int)blockIdx.x)
+            __hip_atomic_store(p.status, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (p.cluster > 1 && chunk == 0) {
+            // The first workgroup of a problem zeroes the problem's accumulators and counters, then
+            // publishes this launch's nonce; the cluster waits for it before its first post.  (No
+            // separate clearing kernel: one launch per call.)
+            __hip_atomic_store(p.colacc + (size_t)g * 256 + tid, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid == 0) {
+                __hip_atomic_store(p.arrive + g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(p.yready + g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();   // the zeroes have been acknowledged
+            if (tid == 0) __hip_atomic_store(p.cleared + g, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         lds_barrier();
         f32x16 cs[RB], U[RB][NB];
         LOT_STAMP(1);
@@ -694,6 +712,20 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
         //      in the same breath, collect the other side's previous pass, which was posted one
         //      whole pass ago.  Two workgroup barriers in all.
         auto exchange = [&](int side, int it, bool with_u, int cside, int cit, bool cfinal) -> bool {
+            if (p.cluster > 1 && it == 1 && side == 0) {
+                // first post of this launch: the problem's accumulators must have been zeroed
+                if (tid == 0) {
+                    bool ok = false;
+                    for (uint32_t k = 0; k < p.spin_limit; ++k) {
+                        if (__hip_atomic_load(p.cleared + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nonce) { ok = true; break; }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                    if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    s_ok = ok;
+                }
+                lds_barrier();
+                if (!s_ok) return false;
+            }
             LOT_STAMP(9 + 6 * ((it - 1) * 2 + side));   // pass done
             __builtin_amdgcn_s_setprio(3);
             if (p.cluster > 1 && wave == 0 && cit >= 1) {
@@ -907,12 +939,6 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
     }
 }
 
-__global__ void lot_fused_clear(uint32_t* words, int count)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx < count) words[idx] = 0u;
-}
-
 template <typename IO, int D, int RB>
 int launch(const Args& a, bool want_out)
 {
@@ -947,6 +973,7 @@ int launch(const Args& a, bool want_out)
     p.status = (uint32_t*)(a.ws + a.lay.status);
     p.arrive = (uint32_t*)(a.ws + a.lay.counters);
     p.yready = p.arrive + G;
+    p.cleared = (unsigned long long*)(a.ws + a.lay.cleared);
     p.colacc = (unsigned long long*)(a.ws + a.lay.colacc);
     p.u_part = (float*)(a.ws + a.lay.u_part);
     p.y_tile = (float*)(a.ws + a.lay.y_tile);
@@ -968,10 +995,14 @@ int launch(const Args& a, bool want_out)
         p.fx_unscale = std::ldexp(1.0f, -frac);
     }
 
-    // status word, counters and accumulators start at zero (a fill kernel, so the call can be
-    // captured in a graph); they are adjacent in the workspace
-    const int words = (int)((a.lay.colacc + (cluster > 1 ? a.lay.colacc_bytes : 0) - a.lay.status) / 4);
-    lot_fused_clear<<<(words + 255) / 256, 256, 0, a.stream>>>((uint32_t*)(a.ws + a.lay.status), words);
+    // A value that no earlier launch has used: the kernel's own clearing of its counters is
+    // published under it (process-wide counter seeded from the clock; never zero).
+    {
+        static std::atomic<unsigned long long> counter{
+            (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() << 20};
+        unsigned long long v = counter.fetch_add(1) + 1;
+        p.nonce = v ? v : counter.fetch_add(1) + 1;
+    }
 
     const int grid = p.num_items < capacity ? p.num_items : capacity;
     // An ordinary launch: the grid never exceeds the number of workgroups the device can hold at

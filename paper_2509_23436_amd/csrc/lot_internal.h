@@ -43,6 +43,7 @@ struct Workspace {
     size_t status;        // 64 x uint32: word 0 = sync failure flag
     size_t counters;      // uint32 [G] U arrivals + uint32 [G] y-ready, zeroed per launch
     size_t counters_bytes;
+    size_t cleared;       // uint64 [G]: launch nonce, written once a problem's counters are zero
     size_t colacc;        // uint64 [G][2][2][64] fixed-point column sums, zeroed per launch
     size_t colacc_bytes;
     size_t u_part;        // float [G][cluster_bound][64][d_v]
@@ -70,6 +71,7 @@ inline Workspace carve(const lot_shape& s)
     w.status = take(64 * 4);
     w.counters_bytes = align_up(2 * G * 4, 256);
     w.counters = take(w.counters_bytes);
+    w.cleared = take(G * 8);
     w.colacc_bytes = G * 2 * 2 * 64 * 8;
     w.colacc = take(w.colacc_bytes);
     w.u_part = take(G * cb * 64 * dv * 4);
