@@ -401,7 +401,7 @@ template <> struct io_is_f32<float> { static constexpr bool value = true; };
 // ---------------------------------------------------------------------------------------------
 // one pass over this wavefront's tiles
 // ---------------------------------------------------------------------------------------------
-template <typename IO, int D, int RB, int EPI>
+template <typename IO, int D, int RB, int EPI, int WAVES>
 __device__ __forceinline__ void run_pass(
     const FusedParams& p, const IO* __restrict__ X, const IO* __restrict__ Xnext, Frag<IO, D>& xfirst,
     int g, int side, int tile_begin, int tile_end, int lane, int wave, float c1,
@@ -419,10 +419,10 @@ __device__ __forceinline__ void run_pass(
     // iteration below loads the first tile of the NEXT pass (same tile range, rows of Xnext),
     // so that no pass starts with an exposed round trip to memory
     Frag<IO, D> xc = xfirst;
-    for (; tile < tile_end; tile += kFusedWaves) {
+    for (; tile < tile_end; tile += WAVES) {
         Frag<IO, D> xn = xc;
-        if (tile + kFusedWaves < tile_end) {
-            const int tok = min((tile + kFusedWaves) * kTileTokens + i, n - 1);
+        if (tile + WAVES < tile_end) {
+            const int tok = min((tile + WAVES) * kTileTokens + i, n - 1);
             load_tokens<D>(xn, X + ((size_t)g * n + tok) * D, kg);
         } else if (Xnext != nullptr) {
             const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
@@ -596,18 +596,19 @@ __device__ __forceinline__ void run_pass(
 // partial column sums are posted right after the pass, and collected only when that side's next
 // pass is about to start -- one whole pass of the other side later -- so the latency of the
 // exchange (and the spread between workgroups) is hidden behind useful work.
-template <typename IO, int D, int RB>
-__global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams p)
+template <typename IO, int D, int RB, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
 {
     constexpr int NB = D / 32;
-    __shared__ float s_wave_part[kFusedWaves][64];
+    constexpr int kThreads = WAVES * 64;
+    __shared__ float s_wave_part[WAVES][64];
     __shared__ float s_tot[2][64];     // cluster == 1: this workgroup's column sums, per side
     __shared__ float s_g[2][64];       // pivot potentials per side (0 = keys, 1 = queries)
     __shared__ float s_rho[2][64];     // beta_t / colsum_t after the last iteration
     __shared__ float s_csinv[64];      // 1 / colsum_t of the key side after the last iteration
     __shared__ float s_beta[64];
     __shared__ __attribute__((aligned(16))) float s_u[64 * D];
-    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kFusedWaves * 2 * 64 * kTrStride];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[WAVES * 2 * 64 * kTrStride];
     __shared__ __attribute__((aligned(16))) char s_zf[RB * sizeof(Frag<IO, D>) * 64];
     __shared__ unsigned long long s_prev[2][2][64];   // last word seen per (side, parity, pivot)
     __shared__ int s_ok;
@@ -646,14 +647,14 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
         if (wave == 0) stash_pivots<D, RB>(s_zf, zf, lane);
         if (tid < 128) s_g[tid >> 6][tid & 63] = (tid & 63) < r ? 0.f : kNegBig;
         if (tid < 64) s_beta[tid] = tid < r ? as_global(beta)[tid] : 1.f;
-        (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
+        if (tid < 256) (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
         if (blockIdx.x == 0 && tid == 0 && item == (int)blockIdx.x)
             __hip_atomic_store(p.status, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (p.cluster > 1 && chunk == 0) {
             // The first workgroup of a problem zeroes the problem's accumulators and counters, then
             // publishes this launch's nonce; the cluster waits for it before its first post.  (No
             // separate clearing kernel: one launch per call.)
-            __hip_atomic_store(p.colacc + (size_t)g * 256 + tid, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid < 256) __hip_atomic_store(p.colacc + (size_t)g * 256 + tid, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (tid == 0) {
                 __hip_atomic_store(p.arrive + g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(p.yready + g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -755,7 +756,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             LOT_STAMP(10 + 6 * ((it - 1) * 2 + side));   // own sums reduced
             if (with_u) {
                 // workgroup total of U in s_u, one wavefront at a time (fixed order)
-                for (int turn = 0; turn < kFusedWaves; ++turn) {
+                for (int turn = 0; turn < WAVES; ++turn) {
                     if (wave == turn) {
 #pragma unroll
                         for (int mb = 0; mb < RB; ++mb)
@@ -775,9 +776,8 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             LOT_STAMP(11 + 6 * ((it - 1) * 2 + side));   // all wavefronts' sums in LDS
             if (wave == 0) {
                 float tot = s_wave_part[0][lane];
-                tot += s_wave_part[1][lane];
-                tot += s_wave_part[2][lane];
-                tot += s_wave_part[3][lane];
+#pragma unroll
+                for (int wv = 1; wv < WAVES; ++wv) tot += s_wave_part[wv][lane];
                 if (lane >= r) tot = 0.f;   // padding pivots (their LDS slots may never have been written)
                 if (p.cluster > 1) {
                     // one fire-and-forget atomic per pivot: the workgroup's column sum in fixed point
@@ -796,7 +796,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             }
             if (p.cluster > 1 && with_u) {
                 float* up = p.u_part + ((size_t)g * p.cluster_cap + chunk) * 64 * D;
-                for (int e = tid; e < 64 * D; e += kFusedThreads) st_coherent(up + e, s_u[e]);
+                for (int e = tid; e < 64 * D; e += kThreads) st_coherent(up + e, s_u[e]);
                 __syncthreads();   // the stores above have been acknowledged
                 if (tid == 0) __hip_atomic_fetch_add(p.arrive + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -823,10 +823,10 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                             for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
-                    run_pass<IO, D, RB, EPI_ACCUM_U>(p, Xs[side], Xnext, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
+                    run_pass<IO, D, RB, EPI_ACCUM_U, WAVES>(p, Xs[side], Xnext, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                      reinterpret_cast<const IO*>(p.V), U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
                 } else {
-                    run_pass<IO, D, RB, EPI_NONE>(p, Xs[side], Xnext, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
+                    run_pass<IO, D, RB, EPI_NONE, WAVES>(p, Xs[side], Xnext, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                   nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
                 }
                 // what is collected along with this post: keys' pass `it` after a query pass (for
@@ -852,7 +852,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
             const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
             const __amdgpu_buffer_rsrc_t upv = coherent_view(up);
-            for (int e = e0 + tid; e < e1; e += kFusedThreads) {
+            for (int e = e0 + tid; e < e1; e += kThreads) {
                 float acc = 0.f;
                 for (int k0 = 0; k0 < p.cluster; k0 += 8) {
                     float v[8];
@@ -882,13 +882,13 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
         if (!attention) {
             for (int side = 0; side < 2; ++side) {
                 load_pivot_vector<RB>(cs, s_rho[side], kg);
-                run_pass<IO, D, RB, EPI_GAMMA>(p, Xs[side], side == 0 ? Xs[1] : nullptr, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
+                run_pass<IO, D, RB, EPI_GAMMA, WAVES>(p, Xs[side], side == 0 ? Xs[1] : nullptr, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
             }
         } else {
             // Y''_t = n * rho1_t * U_t / colsum2_t  ->  s_u
             if (p.cluster == 1) {
-                for (int e = tid; e < 64 * D; e += kFusedThreads) s_u[e] *= s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
+                for (int e = tid; e < 64 * D; e += kThreads) s_u[e] *= s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
             } else {
                 __builtin_amdgcn_s_setprio(3);
                 if (tid == 0) {
@@ -898,14 +898,14 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
                 }
                 lds_barrier();
                 if (!s_ok) return;
-                constexpr int kChunks = 64 * D / 4 / kFusedThreads;   // 16-byte chunks per thread
+                constexpr int kChunks = 64 * D / 4 / kThreads;   // 16-byte chunks per thread
                 f32x4 v[kChunks];
                 const __amdgpu_buffer_rsrc_t ytv = coherent_view(yt);
 #pragma unroll
-                for (int j = 0; j < kChunks; ++j) v[j] = ldc_f32x4(ytv, (uint32_t)(16 * (tid + j * kFusedThreads)));
+                for (int j = 0; j < kChunks; ++j) v[j] = ldc_f32x4(ytv, (uint32_t)(16 * (tid + j * kThreads)));
 #pragma unroll
                 for (int j = 0; j < kChunks; ++j) {
-                    const int e = 4 * (tid + j * kFusedThreads);
+                    const int e = 4 * (tid + j * kThreads);
                     const float sc = s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
 #pragma unroll
                     for (int c = 0; c < 4; ++c) s_u[e + c] = v[j][c] * sc;
@@ -915,7 +915,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             lds_barrier();
             // lay Y'' out as MFMA B fragments (bf16 hi + lo)
             LOT_STAMP(3);
-            for (int f = tid; f < 2 * RB * NB * 64; f += kFusedThreads) {
+            for (int f = tid; f < 2 * RB * NB * 64; f += kThreads) {
                 const int fl = f & 63, fi = fl & 31, fkg = fl >> 5;
                 const int snb = f >> 6, s = snb / NB, nb = snb % NB;
                 f32x8 t;
@@ -931,7 +931,7 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
             }
             lds_barrier();
             LOT_STAMP(4);
-            run_pass<IO, D, RB, EPI_EXPAND>(p, Xs[1], nullptr, xfirst, g, 1, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[1], cs,
+            run_pass<IO, D, RB, EPI_EXPAND, WAVES>(p, Xs[1], nullptr, xfirst, g, 1, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[1], cs,
                                             nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, reinterpret_cast<IO*>(p.out));
         }
         LOT_STAMP(5);
@@ -939,12 +939,13 @@ __global__ void __launch_bounds__(kFusedThreads, 2) lot_fused_kernel(FusedParams
     }
 }
 
-template <typename IO, int D, int RB>
+template <typename IO, int D, int RB, int WAVES>
 int launch(const Args& a, bool want_out)
 {
+    constexpr int kThreads = WAVES * 64;
     const lot_shape& s = a.s;
     const int G = s.B * s.H;
-    auto kernel = lot_fused_kernel<IO, D, RB>;
+    auto kernel = lot_fused_kernel<IO, D, RB, WAVES>;
 
     static thread_local int capacity_cache[8] = {0};   // per device ordinal
     int dev = 0;
@@ -952,7 +953,7 @@ int launch(const Args& a, bool want_out)
     int capacity = (dev >= 0 && dev < 8) ? capacity_cache[dev] : 0;
     if (capacity == 0) {
         int per_cu = 0, cus = 0;
-        LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kFusedThreads, 0));
+        LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0));
         LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         capacity = per_cu * cus;
         if (capacity < 1) { last_hip_error() = hipErrorLaunchOutOfResources; return LOT_ERR_HIP; }
@@ -962,6 +963,10 @@ int launch(const Args& a, bool want_out)
 
     const int ntiles = (s.n + kTileTokens - 1) / kTileTokens;
     int cluster = fused_cluster_bound(s);
+    {
+        const int by_tiles = (ntiles + WAVES - 1) / WAVES;   // at least one tile per wavefront
+        if (cluster > by_tiles) cluster = by_tiles;
+    }
     if (cluster > capacity / G) cluster = capacity / G;
     if (cluster < 1) cluster = 1;
     const int tiles_per_wg = (ntiles + cluster - 1) / cluster;
@@ -1009,19 +1014,33 @@ int launch(const Args& a, bool want_out)
     // once (occupancy query above), which is what the cross-workgroup waits need, and the waits are
     // bounded in any case.  (A cooperative launch would assert the same thing, but kernel tracing
     // tools do not survive it.)
-    kernel<<<dim3(grid), dim3(kFusedThreads), 0, a.stream>>>(p);
+    kernel<<<dim3(grid), dim3(kThreads), 0, a.stream>>>(p);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
+}
+
+// Workgroup size: eight wavefronts (one workgroup per compute unit) when the problems fit one
+// round of such workgroups -- fewer, larger workgroups mean fewer participants per exchange and a
+// shorter dispatch ramp; four wavefronts (two workgroups per compute unit) otherwise, which keeps
+// twice as many work items resident.
+template <typename IO, int D, int RB>
+int launch_sized(const Args& a, bool want_out)
+{
+    int dev = 0, cus = 0;
+    LOT_HIP_CHECK(hipGetDevice(&dev));
+    LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (a.s.B * a.s.H <= cus) return launch<IO, D, RB, 8>(a, want_out);
+    return launch<IO, D, RB, 4>(a, want_out);
 }
 
 template <typename IO>
 int dispatch(const Args& a, bool want_out)
 {
     const int d = a.s.d_k, rb = a.s.r <= 32 ? 1 : 2;
-    if (d == 32 && rb == 1) return launch<IO, 32, 1>(a, want_out);
-    if (d == 32 && rb == 2) return launch<IO, 32, 2>(a, want_out);
-    if (d == 64 && rb == 1) return launch<IO, 64, 1>(a, want_out);
-    if (d == 64 && rb == 2) return launch<IO, 64, 2>(a, want_out);
+    if (d == 32 && rb == 1) return launch_sized<IO, 32, 1>(a, want_out);
+    if (d == 32 && rb == 2) return launch_sized<IO, 32, 2>(a, want_out);
+    if (d == 64 && rb == 1) return launch_sized<IO, 64, 1>(a, want_out);
+    if (d == 64 && rb == 2) return launch_sized<IO, 64, 2>(a, want_out);
     return LOT_ERR_PATH;
 }
 

@@ -10,8 +10,7 @@
 namespace lot {
 
 constexpr int kTileTokens = 32;        // tokens per MFMA tile of the fused kernel
-constexpr int kFusedThreads = 256;     // 4 wavefronts per workgroup
-constexpr int kFusedWaves = kFusedThreads / 64;
+constexpr int kFusedWaves = 4;         // fewest wavefronts per workgroup of the fused kernel
 constexpr int kMaxCluster = 64;        // most workgroups that share one problem
 constexpr int kMaxResidentWgs = 2048;  // upper bound on co-resident workgroups (256 CUs x 8)
 constexpr int kRefChunk = 1024;        // tokens per workgroup in the reference column reduction
