@@ -125,6 +125,22 @@ __device__ __forceinline__ float pair_sum(float x)
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
 // outstanding global access of the wavefront, which would stall on the tile rows that are
 // loaded ahead of the next pass.
+// The lane index, materialised on the spot.  Code that runs once per pass on one wavefront derives its
+// addresses from this instead of from values hoisted out of the iteration loop: under the register
+// pressure of the passes those hoisted values are spilled, and every reload from scratch memory costs
+// a full memory round trip on the critical path of the exchange.
+__device__ __forceinline__ int fresh_lane()
+{
+    int l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
+}
+__device__ __forceinline__ int opaque_scalar(int x)
+{
+    asm volatile("" : "+s"(x));
+    return x;
+}
+
 __device__ __forceinline__ void lds_barrier()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -552,35 +568,57 @@ __device__ __forceinline__ void run_pass(
                     }
                 }
             }
+            // one address per lane and tile; the row of accumulator register j is a compile-time offset
+            const int row0 = tile * kTileTokens + 4 * kg;
+            IO* const lane_base = out + ((size_t)g * n + row0) * D;
             if ((tile + 1) * kTileTokens <= n) {   // whole tile in range: no per-row test
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int tr = tile * kTileTokens + 8 * (j >> 2) + 4 * kg + (j & 3);
-                    store_out<NB>(out + ((size_t)g * n + tr) * D, i, oacc[0][j], oacc[NB - 1][j]);
-                }
+                for (int j = 0; j < 16; ++j)
+                    store_out<NB>(lane_base + (8 * (j >> 2) + (j & 3)) * D, i, oacc[0][j], oacc[NB - 1][j]);
             } else {
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int tr = tile * kTileTokens + 8 * (j >> 2) + 4 * kg + (j & 3);
-                    if (tr < n) store_out<NB>(out + ((size_t)g * n + tr) * D, i, oacc[0][j], oacc[NB - 1][j]);
-                }
+                for (int j = 0; j < 16; ++j)
+                    if (row0 + 8 * (j >> 2) + (j & 3) < n)
+                        store_out<NB>(lane_base + (8 * (j >> 2) + (j & 3)) * D, i, oacc[0][j], oacc[NB - 1][j]);
             }
         }
 
         if (EPI == EPI_GAMMA) {
-            // cs holds rho_t = beta_t / colsum_t in accumulator layout
+            // cs holds rho_t = beta_t / colsum_t in accumulator layout.  The addresses are built here,
+            // per tile, from opaque copies of the sizes: hoisted out of the tile loop they would be 32
+            // live 64-bit values, i.e. spills reloaded in front of every store.
             if (tok < n) {
+                const int rr = opaque_scalar(p.r);
+                const size_t nn = (size_t)opaque_scalar(n);
+                if (side == 1) {
+                    float* const row = p.gamma1 + ((size_t)g * nn + tok) * rr + 4 * kg;
+                    const bool vec = (rr & 3) == 0;   // rows stay 16-byte aligned
 #pragma unroll
-                for (int mb = 0; mb < RB; ++mb)
+                    for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const int pv = pivot_of(mb, j, kg);
-                        if (pv < p.r) {
-                            const float v = acc[mb][j] * w * cs[mb][j];
-                            if (side == 1) as_global(p.gamma1)[((size_t)g * n + tok) * p.r + pv] = v;
-                            else as_global(p.gamma2)[((size_t)g * p.r + pv) * n + tok] = v;
+                        for (int q = 0; q < 4; ++q) {
+                            const int pv0 = 32 * mb + 8 * q + 4 * kg;
+                            f32x4 v;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = acc[mb][4 * q + e] * w * cs[mb][4 * q + e];
+                            if (vec) {
+                                if (pv0 < rr) *as_global(reinterpret_cast<f32x4*>(row + 32 * mb + 8 * q)) = v;
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (pv0 + e < rr) as_global(row)[32 * mb + 8 * q + e] = v[e];
+                            }
                         }
-                    }
+                } else {
+                    float* const col = p.gamma2 + ((size_t)g * rr + 4 * kg) * nn + tok;
+#pragma unroll
+                    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) {
+                            const int pc = 32 * mb + 8 * (j >> 2) + (j & 3);   // pivot minus 4 * kg
+                            if (pc + 4 * kg < rr) as_global(col)[(size_t)pc * nn] = acc[mb][j] * w * cs[mb][j];
+                        }
+                }
             }
         }
         xc = xn;
@@ -613,7 +651,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
     __shared__ unsigned long long s_prev[2][2][64];   // last word seen per (side, parity, pivot)
     __shared__ int s_ok;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile indices and bases stay scalar
     const int i = lane & 31, kg = lane >> 5;
     const int n = p.n, r = p.r;
     const float c1 = kLog2e / p.eps;
@@ -667,44 +706,55 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         LOT_STAMP(1);
 
         unsigned long long early_word = 0, early_word2 = 0;   // wavefront 0: polls issued ahead of their use
+#ifdef LOT_TRACE
+        unsigned long long repolls = 0, valid_a = 0;
+#endif
 
         // ---- wavefront 0: take the column sums of pass `it` of `side` (lane = pivot) and apply the
         //      pivot-side update.  No barrier inside; the caller publishes the result.
         auto collect_w0 = [&](int side, int it, bool final, unsigned long long early) -> bool {
+            const int ln = fresh_lane();
+            const int rr = opaque_scalar(r);
             float tot = 0.f;
             bool ok = true;
             if (p.cluster > 1) {
                 // every pivot's word carries its own arrival count: complete when all 64 agree
-                const unsigned long long* src = p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + lane;
-                const unsigned long long prev = s_prev[side][it & 1][lane];
+                const unsigned long long* src = p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + ln;
+                const unsigned long long prev = s_prev[side][it & 1][ln];
                 unsigned long long word = early;   // a poll that was started ahead; validated here
                 ok = __all(((unsigned)((word >> 56) - (prev >> 56)) & 0xffu) == (unsigned)p.cluster);
+#ifdef LOT_TRACE
+                valid_a += ok ? 1 : 0;
+#endif
                 for (uint32_t k = 0; !ok && k < p.spin_limit; ++k) {
+#ifdef LOT_TRACE
+                    ++repolls;
+#endif
                     word = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if (__all(((unsigned)((word >> 56) - (prev >> 56)) & 0xffu) == (unsigned)p.cluster)) { ok = true; break; }
                     if ((k & 63u) == 63u && __hip_atomic_load(p.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
                     __builtin_amdgcn_s_sleep(1);
                 }
-                s_prev[side][it & 1][lane] = word;
+                s_prev[side][it & 1][ln] = word;
                 const unsigned long long mask = (1ull << 56) - 1ull;
                 tot = (float)(long long)((word & mask) - (prev & mask)) * p.fx_unscale;
-                if (!ok && lane == 0) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (!ok && ln == 0) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
-                tot = s_tot[side][lane];
+                tot = s_tot[side][ln];
             }
-            if (lane < r) {
+            if (ln < rr) {
                 const float c = fmaxf(tot, 1.0e-37f);
-                const float b = s_beta[lane];
+                const float b = s_beta[ln];
                 if (!final) {
-                    s_g[side][lane] += p.eps * logf((float)n * b / c);
+                    s_g[side][ln] += p.eps * logf((float)opaque_scalar(n) * b / c);
                 } else {
                     // the last pass's potentials stay: the epilogue rebuilds its coupling from them
-                    s_rho[side][lane] = b / c;
-                    if (side == 0) s_csinv[lane] = 1.f / c;
+                    s_rho[side][ln] = b / c;
+                    if (side == 0) s_csinv[ln] = 1.f / c;
                 }
             } else if (final) {
-                s_rho[side][lane] = 0.f;
-                if (side == 0) s_csinv[lane] = 0.f;
+                s_rho[side][ln] = 0.f;
+                if (side == 0) s_csinv[ln] = 0.f;
             }
             return ok;
         };
@@ -728,6 +778,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 if (!s_ok) return false;
             }
             LOT_STAMP(9 + 6 * ((it - 1) * 2 + side));   // pass done
+#ifdef LOT_RTT
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            LOT_STAMP(8 + 6 * ((it - 1) * 2 + side));   // everything before the poll has landed
+#endif
             __builtin_amdgcn_s_setprio(3);
             if (p.cluster > 1 && wave == 0 && cit >= 1) {
                 // start the poll now; it completes while this pass's sums are reduced
@@ -738,6 +792,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     early_word2 = ldc_u64(coherent_view(p.colacc),
                                           (uint32_t)(((((size_t)2 * g + 1) * 2 + (it & 1)) * 64 + lane) * 8));
             }
+#ifdef LOT_RTT
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            LOT_STAMP(9 + 6 * ((it - 1) * 2 + side));   // pass done
+#endif
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -775,28 +833,32 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             }
             LOT_STAMP(11 + 6 * ((it - 1) * 2 + side));   // all wavefronts' sums in LDS
             if (wave == 0) {
-                float tot = s_wave_part[0][lane];
+                const int ln = fresh_lane();
+                float tot = s_wave_part[0][ln];
 #pragma unroll
-                for (int wv = 1; wv < WAVES; ++wv) tot += s_wave_part[wv][lane];
-                if (lane >= r) tot = 0.f;   // padding pivots (their LDS slots may never have been written)
+                for (int wv = 1; wv < WAVES; ++wv) tot += s_wave_part[wv][ln];
+                if (ln >= opaque_scalar(r)) tot = 0.f;   // padding pivots (their LDS slots may never have been written)
+                // The other side's sums are taken first: their poll has been in flight since the pass
+                // ended, while a wait placed after the post below would also wait for the post's own
+                // acknowledgement (the memory counter drains in order).
+                bool ok = true;
+                if (cit >= 1) ok = collect_w0(cside, cit, cfinal, early_word);
+                LOT_STAMP(12 + 6 * ((it - 1) * 2 + side));   // collected
                 if (p.cluster > 1) {
                     // one fire-and-forget atomic per pivot: the workgroup's column sum in fixed point
                     // (integer addition: the total does not depend on arrival order) plus one count
                     const unsigned long long word = (1ull << 56) + (unsigned long long)__float2ll_rn(tot * p.fx_scale);
-                    __hip_atomic_fetch_add(p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + lane, word,
+                    __hip_atomic_fetch_add(p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + ln, word,
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 } else {
-                    s_tot[side][lane] = tot;
+                    s_tot[side][ln] = tot;
                 }
-                LOT_STAMP(12 + 6 * ((it - 1) * 2 + side));   // posted
-                bool ok = true;
-                if (cit >= 1) ok = collect_w0(cside, cit, cfinal, early_word);
-                LOT_STAMP(13 + 6 * ((it - 1) * 2 + side));   // collected
-                if (lane == 0) s_ok = ok;
+                LOT_STAMP(13 + 6 * ((it - 1) * 2 + side));   // posted
+                if (ln == 0) s_ok = ok;
             }
             if (p.cluster > 1 && with_u) {
                 float* up = p.u_part + ((size_t)g * p.cluster_cap + chunk) * 64 * D;
-                for (int e = tid; e < 64 * D; e += kThreads) st_coherent(up + e, s_u[e]);
+                for (int e = wave * 64 + fresh_lane(); e < 64 * D; e += kThreads) st_coherent(up + e, s_u[e]);
                 __syncthreads();   // the stores above have been acknowledged
                 if (tid == 0) __hip_atomic_fetch_add(p.arrive + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -852,7 +914,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
             const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
             const __amdgpu_buffer_rsrc_t upv = coherent_view(up);
-            for (int e = e0 + tid; e < e1; e += kThreads) {
+            for (int e = e0 + wave * 64 + fresh_lane(); e < e1; e += kThreads) {
                 float acc = 0.f;
                 for (int k0 = 0; k0 < p.cluster; k0 += 8) {
                     float v[8];
@@ -888,7 +950,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         } else {
             // Y''_t = n * rho1_t * U_t / colsum2_t  ->  s_u
             if (p.cluster == 1) {
-                for (int e = tid; e < 64 * D; e += kThreads) s_u[e] *= s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
+                for (int e = wave * 64 + fresh_lane(); e < 64 * D; e += kThreads) s_u[e] *= s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
             } else {
                 __builtin_amdgcn_s_setprio(3);
                 if (tid == 0) {
@@ -899,13 +961,14 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 lds_barrier();
                 if (!s_ok) return;
                 constexpr int kChunks = 64 * D / 4 / kThreads;   // 16-byte chunks per thread
+                const int ft = wave * 64 + fresh_lane();
                 f32x4 v[kChunks];
                 const __amdgpu_buffer_rsrc_t ytv = coherent_view(yt);
 #pragma unroll
-                for (int j = 0; j < kChunks; ++j) v[j] = ldc_f32x4(ytv, (uint32_t)(16 * (tid + j * kThreads)));
+                for (int j = 0; j < kChunks; ++j) v[j] = ldc_f32x4(ytv, (uint32_t)(16 * (ft + j * kThreads)));
 #pragma unroll
                 for (int j = 0; j < kChunks; ++j) {
-                    const int e = 4 * (tid + j * kThreads);
+                    const int e = 4 * (ft + j * kThreads);
                     const float sc = s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
 #pragma unroll
                     for (int c = 0; c < 4; ++c) s_u[e + c] = v[j][c] * sc;
@@ -915,7 +978,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             lds_barrier();
             // lay Y'' out as MFMA B fragments (bf16 hi + lo)
             LOT_STAMP(3);
-            for (int f = tid; f < 2 * RB * NB * 64; f += kThreads) {
+            for (int f = wave * 64 + fresh_lane(); f < 2 * RB * NB * 64; f += kThreads) {
                 const int fl = f & 63, fi = fl & 31, fkg = fl >> 5;
                 const int snb = f >> 6, s = snb / NB, nb = snb % NB;
                 f32x8 t;
@@ -935,6 +998,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                                             nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, reinterpret_cast<IO*>(p.out));
         }
         LOT_STAMP(5);
+#ifdef LOT_TRACE
+        if (threadIdx.x == 0) p.trace[(size_t)blockIdx.x * 128 + 6] = repolls;
+        if (threadIdx.x == 0) p.trace[(size_t)blockIdx.x * 128 + 7] = valid_a;
+#endif
         __syncthreads();   // LDS is reused by the next item
     }
 }
