@@ -122,9 +122,6 @@ __device__ __forceinline__ float pair_sum(float x)
     return lo + hi;
 }
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
-// outstanding global access of the wavefront, which would stall on the tile rows that are
-// loaded ahead of the next pass.
 // The lane index, materialised on the spot.  Code that runs once per pass on one wavefront derives its
 // addresses from this instead of from values hoisted out of the iteration loop: under the register
 // pressure of the passes those hoisted values are spilled, and every reload from scratch memory costs
@@ -141,6 +138,9 @@ __device__ __forceinline__ int opaque_scalar(int x)
     return x;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global access of the wavefront, which would stall on the tile rows that are
+// loaded ahead of the next pass.
 __device__ __forceinline__ void lds_barrier()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -152,15 +152,55 @@ template <int CTRL> __device__ __forceinline__ float dpp_move(float x)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
 }
-// sum over the 32 lanes that share (lane >> 5); the result is exact-order only in lane 0 / 32
-__device__ __forceinline__ float sum_over_tokens(float x)
+// Transposing reduction over the 32 lanes that share (lane >> 5).  Every lane comes in with N partial
+// sums c[0..N) (one per pivot it covers) and leaves with ONE total: the sum over the 32 lanes of
+// c[q], where q = lane % 32 for N = 32 and q = (lane % 32) / 2 for N = 16.  Each step pairs lanes,
+// keeps half of the registers and adds the partner's copy of the kept half, so the work halves from
+// step to step (about 2 N operations instead of 5 N for N separate butterfly sums).
+//   step 1  lane ^ 16   v_permlane16_swap exchanges odd rows of one register with even rows of another
+//   step 2  lane ^ 8    row rotation by 8, the write limited to lanes 0-7 / 8-15 of a row by the bank mask
+//   step 3  7 - lane    mirror within 8 lanes, bank mask again
+//   step 4, 5           within a quad, where bank masks cannot tell lanes apart: select, then add
+__device__ __forceinline__ float swap16_add(float a, float b)
 {
-    x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
-    x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
-    x += dpp_move<0x124>(x);   // row_ror 4
-    x += dpp_move<0x128>(x);   // row_ror 8
-    x += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0x401F));  // lane ^ 16
-    return x;
+    auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b), false, false);
+    const unsigned r0 = r[0], r1 = r[1];   // copied out before the casts, as for the 32-lane swap above
+    return __builtin_bit_cast(float, r0) + __builtin_bit_cast(float, r1);
+}
+// The s_nop covers the two wait states required between a vector write of a register and its use as
+// a DPP source, which the assembler does not insert inside an asm block.
+__device__ __forceinline__ float ror8_add(float a, float b)
+{
+    float r;
+    asm("s_nop 1\n\tv_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %0, %2, %2 row_ror:8 row_mask:0xf bank_mask:0xc" : "=&v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float mirror8_add(float a, float b)
+{
+    float r;
+    asm("s_nop 1\n\tv_add_f32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %0, %2, %2 row_half_mirror row_mask:0xf bank_mask:0xa" : "=&v"(r) : "v"(a), "v"(b));
+    return r;
+}
+template <int CTRL> __device__ __forceinline__ float quad_add(float a, float b, bool upper)
+{
+    const float keep = upper ? b : a, give = upper ? a : b;
+    return keep + dpp_move<CTRL>(give);
+}
+template <int N> __device__ __forceinline__ float reduce_scatter_tokens(float (&c)[N], int i)
+{
+    static_assert(N == 32 || N == 16, "16 accumulator registers per block of 32 pivots");
+#pragma unroll
+    for (int q = 0; q < N / 2; ++q) c[q] = swap16_add(c[q], c[q + N / 2]);
+#pragma unroll
+    for (int q = 0; q < N / 4; ++q) c[q] = ror8_add(c[q], c[q + N / 4]);
+#pragma unroll
+    for (int q = 0; q < N / 8; ++q) c[q] = mirror8_add(c[q], c[q + N / 8]);
+#pragma unroll
+    for (int q = 0; q < N / 16; ++q) c[q] = quad_add<0x4E>(c[q], c[q + N / 16], (i & 2) != 0);   // quad_perm [2,3,0,1]
+    if (N == 32) return quad_add<0xB1>(c[0], c[1], (i & 1) != 0);                                // quad_perm [1,0,3,2]
+    return c[0] + dpp_move<0xB1>(c[0]);
 }
 
 // Agent-coherent loads that the compiler can schedule: raw buffer loads carrying the sc1 cache
@@ -796,20 +836,16 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             LOT_STAMP(9 + 6 * ((it - 1) * 2 + side));   // pass done
 #endif
-#pragma unroll
-            for (int mb = 0; mb < RB; ++mb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) cs[mb][j] = sum_over_tokens(cs[mb][j]);
-            if (i == 0) {
+            {
+                // this wavefront's column sums: one pivot per lane after the transposing reduction
+                float c[16 * RB];
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        f32x4 t;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) t[e] = cs[mb][4 * q + e];
-                        *reinterpret_cast<f32x4*>(&s_wave_part[wave][32 * mb + 8 * q + 4 * kg]) = t;
-                    }
+                    for (int j = 0; j < 16; ++j) c[16 * mb + j] = cs[mb][j];
+                const float total = reduce_scatter_tokens<16 * RB>(c, i);
+                const int q = RB == 2 ? i : i >> 1;   // accumulator register this lane ended up with
+                s_wave_part[wave][32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3)] = total;
             }
             LOT_STAMP(10 + 6 * ((it - 1) * 2 + side));   // own sums reduced
             if (with_u) {
