@@ -679,7 +679,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
 {
     constexpr int NB = D / 32;
     constexpr int kThreads = WAVES * 64;
-    __shared__ float s_wave_part[WAVES][64];
+    __shared__ float s_wave_part[2][WAVES][64];   // per side: the reader of one pass never meets the writers of the next
     __shared__ float s_tot[2][64];     // cluster == 1: this workgroup's column sums, per side
     __shared__ float s_g[2][64];       // pivot potentials per side (0 = keys, 1 = queries)
     __shared__ float s_rho[2][64];     // beta_t / colsum_t after the last iteration
@@ -690,6 +690,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
     __shared__ __attribute__((aligned(16))) char s_zf[RB * sizeof(Frag<IO, D>) * 64];
     __shared__ unsigned long long s_prev[2][2][64];   // last word seen per (side, parity, pivot)
     __shared__ int s_ok;
+    __shared__ int s_okx[2];           // outcome of the collect inside an exchange, per side
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile indices and bases stay scalar
@@ -717,6 +718,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
             load_tokens<D>(xfirst, Xs[0] + ((size_t)g * n + tok) * D, kg);
         }
+        // (beta is requested together with the pivots: one wait for both, not two round trips)
+        const float beta_mine = (tid < 64 && tid < r) ? as_global(beta)[tid] : 1.f;
         Frag<IO, D> zf[RB];
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) {
@@ -725,7 +728,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         }
         if (wave == 0) stash_pivots<D, RB>(s_zf, zf, lane);
         if (tid < 128) s_g[tid >> 6][tid & 63] = (tid & 63) < r ? 0.f : kNegBig;
-        if (tid < 64) s_beta[tid] = tid < r ? as_global(beta)[tid] : 1.f;
+        if (tid < 64) s_beta[tid] = beta_mine;
         if (tid < 256) (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
         if (blockIdx.x == 0 && tid == 0 && item == (int)blockIdx.x)
             __hip_atomic_store(p.status, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -801,7 +804,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
 
         // ---- after a pass: post this workgroup's share (column sums; U on the last key pass) and,
         //      in the same breath, collect the other side's previous pass, which was posted one
-        //      whole pass ago.  Two workgroup barriers in all.
+        //      whole pass ago.  One workgroup barrier in all (more when U is reduced).
         auto exchange = [&](int side, int it, bool with_u, int cside, int cit, bool cfinal) -> bool {
             if (p.cluster > 1 && it == 1 && side == 0) {
                 // first post of this launch: the problem's accumulators must have been zeroed
@@ -818,10 +821,6 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 if (!s_ok) return false;
             }
             LOT_STAMP(9 + 6 * ((it - 1) * 2 + side));   // pass done
-#ifdef LOT_RTT
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            LOT_STAMP(8 + 6 * ((it - 1) * 2 + side));   // everything before the poll has landed
-#endif
             __builtin_amdgcn_s_setprio(3);
             if (p.cluster > 1 && wave == 0 && cit >= 1) {
                 // start the poll now; it completes while this pass's sums are reduced
@@ -832,10 +831,6 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     early_word2 = ldc_u64(coherent_view(p.colacc),
                                           (uint32_t)(((((size_t)2 * g + 1) * 2 + (it & 1)) * 64 + lane) * 8));
             }
-#ifdef LOT_RTT
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            LOT_STAMP(9 + 6 * ((it - 1) * 2 + side));   // pass done
-#endif
             {
                 // this wavefront's column sums: one pivot per lane after the transposing reduction
                 float c[16 * RB];
@@ -845,41 +840,61 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     for (int j = 0; j < 16; ++j) c[16 * mb + j] = cs[mb][j];
                 const float total = reduce_scatter_tokens<16 * RB>(c, i);
                 const int q = RB == 2 ? i : i >> 1;   // accumulator register this lane ended up with
-                s_wave_part[wave][32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3)] = total;
+                s_wave_part[side][wave][32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3)] = total;
             }
             LOT_STAMP(10 + 6 * ((it - 1) * 2 + side));   // own sums reduced
+            if (wave == 0) {
+                // The other side's sums do not depend on this pass at all: they are taken now, while
+                // the slower wavefronts are still arriving, and the updated potentials are published
+                // by the barrier below.
+                bool ok = true;
+                if (cit >= 1) ok = collect_w0(cside, cit, cfinal, early_word);
+                if (fresh_lane() == 0) s_okx[side] = ok;
+            }
+            LOT_STAMP(11 + 6 * ((it - 1) * 2 + side));   // collected
             if (with_u) {
-                // workgroup total of U in s_u, one wavefront at a time (fixed order)
-                for (int turn = 0; turn < WAVES; ++turn) {
-                    if (wave == turn) {
+                // Workgroup total of U in s_u.  The wavefronts dump their accumulators into separate
+                // buffers (s_u itself and the now idle transposition area), in rounds when there are
+                // more wavefronts than buffers; then every thread sums its elements over the buffers.
+                // The order of the additions is fixed.
+                constexpr int kElems = 64 * D;
+                constexpr int kExtra = (int)(sizeof(s_tr) / (kElems * sizeof(float)));
+                constexpr int kBufs = WAVES < 1 + kExtra ? WAVES : 1 + kExtra;
+                float* const extra = reinterpret_cast<float*>(s_tr);
+                lds_barrier();   // every wavefront has finished its transpositions: the area is free
+                for (int round = 0; round * kBufs < WAVES; ++round) {
+                    if (wave / kBufs == round) {
+                        const int b = wave % kBufs;
+                        float* const buf = b == 0 ? s_u : extra + (b - 1) * kElems;
 #pragma unroll
                         for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
                             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                                 for (int j = 0; j < 16; ++j) {
-                                    float* dst = &s_u[pivot_of(mb, j, kg) * D + NB * i + nb];
-                                    *dst = turn == 0 ? U[mb][nb][j] : *dst + U[mb][nb][j];
+                                    float* dst = &buf[pivot_of(mb, j, kg) * D + NB * i + nb];
+                                    *dst = round == 0 ? U[mb][nb][j] : *dst + U[mb][nb][j];
                                 }
                     }
                     lds_barrier();
                 }
+                for (int e = wave * 64 + fresh_lane(); e < kElems; e += kThreads) {
+                    float acc = s_u[e];
+#pragma unroll
+                    for (int b = 1; b < kBufs; ++b) acc += extra[(b - 1) * kElems + e];
+                    s_u[e] = acc;
+                }
+                lds_barrier();
             } else {
                 lds_barrier();
             }
-            LOT_STAMP(11 + 6 * ((it - 1) * 2 + side));   // all wavefronts' sums in LDS
+            LOT_STAMP(12 + 6 * ((it - 1) * 2 + side));   // all wavefronts' sums in LDS, potentials published
             if (wave == 0) {
                 const int ln = fresh_lane();
-                float tot = s_wave_part[0][ln];
+                float tot = s_wave_part[side][0][ln];
 #pragma unroll
-                for (int wv = 1; wv < WAVES; ++wv) tot += s_wave_part[wv][ln];
+                for (int wv = 1; wv < WAVES; ++wv) tot += s_wave_part[side][wv][ln];
                 if (ln >= opaque_scalar(r)) tot = 0.f;   // padding pivots (their LDS slots may never have been written)
-                // The other side's sums are taken first: their poll has been in flight since the pass
-                // ended, while a wait placed after the post below would also wait for the post's own
-                // acknowledgement (the memory counter drains in order).
-                bool ok = true;
-                if (cit >= 1) ok = collect_w0(cside, cit, cfinal, early_word);
-                LOT_STAMP(12 + 6 * ((it - 1) * 2 + side));   // collected
                 if (p.cluster > 1) {
                     // one fire-and-forget atomic per pivot: the workgroup's column sum in fixed point
                     // (integer addition: the total does not depend on arrival order) plus one count
@@ -890,7 +905,6 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     s_tot[side][ln] = tot;
                 }
                 LOT_STAMP(13 + 6 * ((it - 1) * 2 + side));   // posted
-                if (ln == 0) s_ok = ok;
             }
             if (p.cluster > 1 && with_u) {
                 float* up = p.u_part + ((size_t)g * p.cluster_cap + chunk) * 64 * D;
@@ -898,9 +912,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 __syncthreads();   // the stores above have been acknowledged
                 if (tid == 0) __hip_atomic_fetch_add(p.arrive + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            lds_barrier();   // potentials published; s_wave_part / s_tot may be reused
             __builtin_amdgcn_s_setprio(0);
-            return s_ok != 0;
+            return s_okx[side] != 0;
         };
 
         for (int it = 1; it <= p.iters; ++it) {
