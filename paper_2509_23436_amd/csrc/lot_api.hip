@@ -1,4 +1,6 @@
 // libLOT C ABI: argument validation, workspace carving and dispatch.  No kernels here.
+#include <atomic>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -11,6 +13,15 @@ hipError_t& last_hip_error()
 {
     static thread_local hipError_t e = hipSuccess;
     return e;
+}
+
+unsigned long long next_nonce()
+{
+    // process-wide counter seeded from the clock
+    static std::atomic<unsigned long long> counter{
+        (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() << 20};
+    unsigned long long v = counter.fetch_add(1) + 1;
+    return v ? v : counter.fetch_add(1) + 1;
 }
 
 static int validate_shape(const lot_shape* s)
@@ -140,10 +151,11 @@ int lot_couplings(const lot_shape* shape, const void* Q, const void* K,
 int lot_workspace_status(const void* workspace)
 {
     if (!workspace) return LOT_ERR_NULL;
-    uint32_t word = 0;
+    // word 0: nonce of a launch that gave up; word 1: nonce of the last launch on this workspace
+    unsigned long long words[2] = {0, 0};
     LOT_HIP_CHECK(hipDeviceSynchronize());
-    LOT_HIP_CHECK(hipMemcpy(&word, workspace, sizeof(word), hipMemcpyDeviceToHost));
-    return word == 0 ? LOT_OK : LOT_ERR_SYNC;
+    LOT_HIP_CHECK(hipMemcpy(words, workspace, sizeof(words), hipMemcpyDeviceToHost));
+    return (words[1] != 0 && words[0] == words[1]) ? LOT_ERR_SYNC : LOT_OK;
 }
 
 const char* lot_strerror(int code)

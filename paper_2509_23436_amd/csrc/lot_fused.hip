@@ -25,8 +25,6 @@
 //
 // Cross-workgroup waits are bounded: a wait that exceeds its poll budget raises the status word
 // in the workspace and the workgroup leaves the kernel, so every wavefront always exits.
-#include <atomic>
-#include <chrono>
 #include <cmath>
 
 #include "lot_internal.h"
@@ -75,7 +73,7 @@ struct FusedParams {
     void* out;
     float* gamma1;
     float* gamma2;
-    uint32_t* status;
+    unsigned long long* status;   // [0] = nonce of a launch in which a wait gave up, [1] = nonce of the last launch
     uint32_t* arrive;     // [G]: workgroups that have posted their share of U
     uint32_t* yready;     // [G]
     unsigned long long* cleared;   // [G]: holds this launch's nonce once the problem's counters are zero
@@ -138,9 +136,21 @@ __device__ __forceinline__ int opaque_scalar(int x)
     return x;
 }
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
-// outstanding global access of the wavefront, which would stall on the tile rows that are
-// loaded ahead of the next pass.
+// Workgroup barrier after which one thread may announce, with a relaxed atomic, what the workgroup
+// has just stored to global memory.  Every wavefront first waits until its own stores have been
+// acknowledged: __syncthreads() alone does not do that (a workgroup-scope release needs no such wait
+// on this target, the workgroup shares one L1), and an announcement that overtakes the data lets
+// another workgroup read what an earlier launch left at the same address.  The stores themselves
+// are write-through (sc1), so the acknowledgement means they have reached the level that agent-
+// scope loads read from; no cache write-back is needed.
+__device__ __forceinline__ void publish_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
+
+// Workgroup barrier that orders LDS traffic only: nothing here waits for the global loads that
+// are in flight for the next tiles.
 __device__ __forceinline__ void lds_barrier()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -251,11 +261,20 @@ __device__ __forceinline__ uint16_t bf16_bits_of(float x) { return __builtin_bit
 //
 // Poll *counter until it reaches target.  Thread 0 only.  False if the budget ran out or another
 // workgroup already gave up.
-__device__ inline bool spin_until(uint32_t* counter, uint32_t target, uint32_t* status, uint32_t limit)
+__device__ inline bool gave_up(const unsigned long long* status, unsigned long long nonce)
+{
+    return __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nonce;
+}
+__device__ inline void give_up(unsigned long long* status, unsigned long long nonce)
+{
+    __hip_atomic_store(status, nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline bool spin_until(uint32_t* counter, uint32_t target, const unsigned long long* status,
+                                  unsigned long long nonce, uint32_t limit)
 {
     for (uint32_t k = 0; k < limit; ++k) {
         if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) return true;
-        if ((k & 63u) == 63u && __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return false;
+        if ((k & 63u) == 63u && gave_up(status, nonce)) return false;
         __builtin_amdgcn_s_sleep(1);
     }
     return false;
@@ -731,7 +750,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         if (tid < 64) s_beta[tid] = beta_mine;
         if (tid < 256) (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
         if (blockIdx.x == 0 && tid == 0 && item == (int)blockIdx.x)
-            __hip_atomic_store(p.status, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.status + 1, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // this launch; nobody else writes it
         if (p.cluster > 1 && chunk == 0) {
             // The first workgroup of a problem zeroes the problem's accumulators and counters, then
             // publishes this launch's nonce; the cluster waits for it before its first post.  (No
@@ -741,7 +760,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 __hip_atomic_store(p.arrive + g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(p.yready + g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            __syncthreads();   // the zeroes have been acknowledged
+            publish_barrier();   // the zeroes have been acknowledged
             if (tid == 0) __hip_atomic_store(p.cleared + g, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         lds_barrier();
@@ -775,13 +794,13 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
 #endif
                     word = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if (__all(((unsigned)((word >> 56) - (prev >> 56)) & 0xffu) == (unsigned)p.cluster)) { ok = true; break; }
-                    if ((k & 63u) == 63u && __hip_atomic_load(p.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+                    if ((k & 63u) == 63u && gave_up(p.status, p.nonce)) break;
                     __builtin_amdgcn_s_sleep(1);
                 }
                 s_prev[side][it & 1][ln] = word;
                 const unsigned long long mask = (1ull << 56) - 1ull;
                 tot = (float)(long long)((word & mask) - (prev & mask)) * p.fx_unscale;
-                if (!ok && ln == 0) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (!ok && ln == 0) give_up(p.status, p.nonce);
             } else {
                 tot = s_tot[side][ln];
             }
@@ -814,7 +833,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                         if (__hip_atomic_load(p.cleared + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nonce) { ok = true; break; }
                         __builtin_amdgcn_s_sleep(1);
                     }
-                    if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (!ok) give_up(p.status, p.nonce);
                     s_ok = ok;
                 }
                 lds_barrier();
@@ -909,7 +928,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             if (p.cluster > 1 && with_u) {
                 float* up = p.u_part + ((size_t)g * p.cluster_cap + chunk) * 64 * D;
                 for (int e = wave * 64 + fresh_lane(); e < 64 * D; e += kThreads) st_coherent(up + e, s_u[e]);
-                __syncthreads();   // the stores above have been acknowledged
+                publish_barrier();   // the stores above have been acknowledged
                 if (tid == 0) __hip_atomic_fetch_add(p.arrive + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             __builtin_amdgcn_s_setprio(0);
@@ -953,8 +972,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             // column sums are collected, whose polls are already in flight.
             __builtin_amdgcn_s_setprio(3);
             if (tid == 0) {
-                const bool ok = spin_until(p.arrive + g, (uint32_t)p.cluster, p.status, p.spin_limit);
-                if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const bool ok = spin_until(p.arrive + g, (uint32_t)p.cluster, p.status, p.nonce, p.spin_limit);
+                if (!ok) give_up(p.status, p.nonce);
                 s_ok = ok;
             }
             lds_barrier();
@@ -975,7 +994,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 }
                 st_coherent(yt + e, acc);
             }
-            __syncthreads();   // the slice has been acknowledged
+            publish_barrier();   // the slice has been acknowledged
             if (tid == 0) __hip_atomic_fetch_add(p.yready + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __builtin_amdgcn_s_setprio(0);
         }
@@ -1003,8 +1022,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             } else {
                 __builtin_amdgcn_s_setprio(3);
                 if (tid == 0) {
-                    const bool ok = spin_until(p.yready + g, (uint32_t)p.cluster, p.status, p.spin_limit);
-                    if (!ok) __hip_atomic_store(p.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const bool ok = spin_until(p.yready + g, (uint32_t)p.cluster, p.status, p.nonce, p.spin_limit);
+                    if (!ok) give_up(p.status, p.nonce);
                     s_ok = ok;
                 }
                 lds_barrier();
@@ -1091,7 +1110,7 @@ int launch(const Args& a, bool want_out)
     FusedParams p{};
     p.Q = a.Q; p.K = a.K; p.V = a.V; p.Z = a.Z; p.beta = a.beta; p.out = a.out;
     p.gamma1 = a.gamma1; p.gamma2 = a.gamma2;
-    p.status = (uint32_t*)(a.ws + a.lay.status);
+    p.status = (unsigned long long*)(a.ws + a.lay.status);
     p.arrive = (uint32_t*)(a.ws + a.lay.counters);
     p.yready = p.arrive + G;
     p.cleared = (unsigned long long*)(a.ws + a.lay.cleared);
@@ -1117,13 +1136,8 @@ int launch(const Args& a, bool want_out)
     }
 
     // A value that no earlier launch has used: the kernel's own clearing of its counters is
-    // published under it (process-wide counter seeded from the clock; never zero).
-    {
-        static std::atomic<unsigned long long> counter{
-            (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() << 20};
-        unsigned long long v = counter.fetch_add(1) + 1;
-        p.nonce = v ? v : counter.fetch_add(1) + 1;
-    }
+    // published under it, and so is a wait that gives up.
+    p.nonce = next_nonce();
 
     const int grid = p.num_items < capacity ? p.num_items : capacity;
     // An ordinary launch: the grid never exceeds the number of workgroups the device can hold at

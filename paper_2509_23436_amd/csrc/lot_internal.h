@@ -39,7 +39,8 @@ inline bool fused_supports(const lot_shape& s)
 // Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
 struct Workspace {
     // fused path
-    size_t status;        // 64 x uint32: word 0 = sync failure flag
+    size_t status;        // uint64 [0] = nonce of a launch in which a device-side wait gave up,
+                          // uint64 [1] = nonce of the last launch (equal words = that launch failed)
     size_t counters;      // uint32 [G] U arrivals + uint32 [G] y-ready, zeroed per launch
     size_t counters_bytes;
     size_t cleared;       // uint64 [G]: launch nonce, written once a problem's counters are zero
@@ -109,6 +110,10 @@ int run_reference(const Args& a, bool want_out);
 int run_fused(const Args& a, bool want_out);
 
 hipError_t& last_hip_error();
+
+// A value no earlier launch of this process has used (never zero): launches mark the workspace with
+// it, so that nothing in the workspace has to be cleared by the host or by an extra kernel.
+unsigned long long next_nonce();
 
 #define LOT_HIP_CHECK(expr)                                   \
     do {                                                      \

@@ -44,6 +44,10 @@ __global__ void ref_cost(const T* __restrict__ Q, const T* __restrict__ K, const
     C[idx] = acc;
 }
 
+// Marks the workspace as used by a launch that cannot fail on the device: word 1 of the status area
+// takes a fresh nonce, which word 0 (written only by a launch that gave up) cannot hold.
+__global__ void ref_mark(unsigned long long* status, unsigned long long nonce) { status[1] = nonce; }
+
 __global__ void ref_zero(float* p, size_t count)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -169,6 +173,7 @@ int run_reference_t(const Args& a, bool want_out)
     const size_t rows = (size_t)pairs * n;
     hipStream_t st_ = a.stream;
 
+    ref_mark<<<1, 1, 0, st_>>>((unsigned long long*)(a.ws + a.lay.status), next_nonce());
     ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, s.d_k, r,
                                                          s.io_dtype == LOT_BF16);
     ref_zero<<<blocks_for((size_t)pairs * r, 256), 256, 0, st_>>>(g, (size_t)pairs * r);
