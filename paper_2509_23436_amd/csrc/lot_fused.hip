@@ -738,7 +738,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             load_tokens<D>(xfirst, Xs[0] + ((size_t)g * n + tok) * D, kg);
         }
         // (beta is requested together with the pivots: one wait for both, not two round trips)
-        const float beta_mine = (tid < 64 && tid < r) ? as_global(beta)[tid] : 1.f;
+        const float beta_read = as_global(beta)[min(tid & 63, r - 1)];   // unconditional: issued with the loads around it
         Frag<IO, D> zf[RB];
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) {
@@ -747,7 +747,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         }
         if (wave == 0) stash_pivots<D, RB>(s_zf, zf, lane);
         if (tid < 128) s_g[tid >> 6][tid & 63] = (tid & 63) < r ? 0.f : kNegBig;
-        if (tid < 64) s_beta[tid] = beta_mine;
+        if (tid < 64) s_beta[tid] = tid < r ? beta_read : 1.f;
         if (tid < 256) (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
         if (blockIdx.x == 0 && tid == 0 && item == (int)blockIdx.x)
             __hip_atomic_store(p.status + 1, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // this launch; nobody else writes it
