@@ -98,6 +98,27 @@ int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,
                        void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
+ * Backward pass (paper, "Learning": the pivots, their masses and the projections are trained by
+ * backpropagating through both Sinkhorn problems and the glued composition).  Given dO = dL/dO of
+ * the forward call with the same inputs, eps and iters, writes
+ *   dQ, dK [B,H,n,d_k], dV [B,H,n,d_v] in io_dtype (same layout as their tensors; dO as out),
+ *   dZ [H,r,d_k], dbeta [H,r] in fp32, summed over the batch (Z and beta are shared across it).
+ * These are the exact derivatives of the T-iteration forward function (every iteration of both
+ * solves is differentiated, nothing is truncated); dbeta treats the r masses as free variables (no
+ * projection onto the simplex).  The forward intermediates are recomputed inside; nothing has to be
+ * saved from the forward call.  All gradient buffers are overwritten, not accumulated into.
+ * Workspace: lot_attention_bwd_workspace_bytes (separate from, and larger than, the forward one);
+ * contents on entry do not matter.  Same ownership, stream and error rules as the forward call;
+ * gradient buffers must not alias the inputs, the workspace or each other.  iters <= 65536.
+ * One execution path (plain kernels, any shape); results are reproducible bit for bit.
+ */
+int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out);
+int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                      const float* Z, const float* beta, float eps, int iters, const void* dO,
+                      void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Debug: synchronises the device and reads the status word that the fused kernel leaves in the
  * workspace.  LOT_OK, or LOT_ERR_SYNC if a bounded device-side wait between cooperating
  * workgroups gave up (the output of that call is then undefined).  Not part of the hot path.

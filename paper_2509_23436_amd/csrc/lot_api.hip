@@ -148,6 +148,41 @@ int lot_couplings(const lot_shape* shape, const void* Q, const void* K,
                               hip_stream, LOT_PATH_AUTO);
 }
 
+int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out)
+{
+    int rc = validate_shape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!bytes_out) return LOT_ERR_NULL;
+    if (iters < 1) return LOT_ERR_ITERS;
+    if (iters > (1 << 16)) return LOT_ERR_ITERS;   // one stored vector of potentials per iteration
+    *bytes_out = carve_bwd(*shape, iters).total;
+    return LOT_OK;
+}
+
+int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                      const float* Z, const float* beta, float eps, int iters, const void* dO,
+                      void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                      void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int rc = validate_shape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!Q || !K || !V || !Z || !beta || !dO || !dQ || !dK || !dV || !dZ || !dbeta || !workspace) return LOT_ERR_NULL;
+    if (!(eps > 0.0f) || !std::isfinite(eps)) return LOT_ERR_EPS;
+    if (iters < 1 || iters > (1 << 16)) return LOT_ERR_ITERS;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(dO, 16) || misaligned(dQ, 16) ||
+        misaligned(dK, 16) || misaligned(dV, 16) || misaligned(Z, 4) || misaligned(beta, 4) || misaligned(dZ, 4) ||
+        misaligned(dbeta, 4))
+        return LOT_ERR_ALIGN;
+    if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
+    BwdArgs a{};
+    a.lay = carve_bwd(*shape, iters);
+    if (workspace_bytes < a.lay.total) return LOT_ERR_WORKSPACE;
+    a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
+    a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
+    a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
+    return run_backward(a);
+}
+
 int lot_workspace_status(const void* workspace)
 {
     if (!workspace) return LOT_ERR_NULL;

@@ -105,9 +105,42 @@ struct Args {
     hipStream_t stream;
 };
 
+// Workspace of the backward pass (plain path): byte offsets, multiples of 256.
+struct BwdWorkspace {
+    size_t C, f, ghist, part_m, part_s;   // forward recomputation; ghist = float [iters+1][2G][r]
+    size_t gam, dgam, dC, ybuf;           // float [2G][n][r] each
+    size_t tx_part;                       // float [G][chunks][r][max(d_k, d_v)]
+    size_t Yp, dYp, db_glue;              // float [G][r][d_v] x 2, float [G][r]
+    size_t colpart, dc, rho, dg, db_pair; // float [2G][chunks][r], float [2G][r] x 4
+    size_t dZ_pair, Zr;                   // float [2G][r][d_k], float [H][r][d_k]
+    size_t total;
+};
+BwdWorkspace carve_bwd(const lot_shape& s, int iters);
+
+struct BwdArgs {
+    lot_shape s;
+    const void* Q;
+    const void* K;
+    const void* V;
+    const float* Z;
+    const float* beta;
+    float eps;
+    int iters;
+    const void* dO;
+    void* dQ;
+    void* dK;
+    void* dV;
+    float* dZ;
+    float* dbeta;
+    char* ws;
+    BwdWorkspace lay;
+    hipStream_t stream;
+};
+
 // Each returns LOT_OK or LOT_ERR_HIP (the failing hipError_t is left in last_hip_error()).
 int run_reference(const Args& a, bool want_out);
 int run_fused(const Args& a, bool want_out);
+int run_backward(const BwdArgs& a);
 
 hipError_t& last_hip_error();
 

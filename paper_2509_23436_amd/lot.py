@@ -17,7 +17,8 @@ LOT_F32, LOT_BF16 = 0, 1
 PATH_AUTO, PATH_REFERENCE, PATH_FUSED = 0, 1, 2
 
 EXPORTS = ("lot_workspace_bytes", "lot_attention_fwd", "lot_couplings", "lot_attention_fwd_path",
-           "lot_couplings_path", "lot_workspace_status", "lot_strerror", "lot_version")
+           "lot_couplings_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd",
+           "lot_workspace_status", "lot_strerror", "lot_version")
 
 
 class lot_shape(ctypes.Structure):
@@ -144,3 +145,31 @@ def lot_workspace_status(workspace) -> int:
 
 def lot_version() -> int:
     return lib().lot_version()
+
+
+def lot_attention_bwd_workspace_bytes(shape: lot_shape, iters: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().lot_attention_bwd_workspace_bytes(ctypes.byref(shape), int(iters), ctypes.byref(out)))
+    return out.value
+
+
+def lot_attention_bwd(Q, K, V, Z, beta, eps, iters, dO, workspace=None):
+    """(dQ, dK, dV, dZ, dbeta) of <LOTAttn(Q, K, V), dO>; dZ and dbeta are summed over the batch."""
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
+        _require(t, nm, Q.dtype)
+    _require(Z, "Z", torch.float32)
+    _require(beta, "beta", torch.float32)
+    if dO.shape != V.shape:
+        raise ValueError("dO must have the shape of V")
+    shape = _shape_of(Q, V, Z)
+    need = lot_attention_bwd_workspace_bytes(shape, iters)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    _require(workspace, "workspace", torch.uint8)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    dZ, dbeta = torch.empty_like(Z), torch.empty_like(beta)
+    _check(lib().lot_attention_bwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
+                                   ctypes.c_float(eps), int(iters), _ptr(dO),
+                                   _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dZ), _ptr(dbeta),
+                                   _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
+    return dQ, dK, dV, dZ, dbeta

@@ -8,7 +8,7 @@ def to_device(x, dtype):
     """numpy inputs (float32, bf16-representable when dtype == 'bf16') -> torch device tensors."""
     import torch
     dev = {}
-    for k in ("Q", "K", "V"):
+    for k in ("Q", "K", "V", "dO"):
         if k not in x:
             continue
         if dtype == "bf16":
