@@ -110,13 +110,20 @@ int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,
  * Workspace: lot_attention_bwd_workspace_bytes (separate from, and larger than, the forward one);
  * contents on entry do not matter.  Same ownership, stream and error rules as the forward call;
  * gradient buffers must not alias the inputs, the workspace or each other.  iters <= 65536.
- * One execution path (plain kernels, any shape); results are reproducible bit for bit.
+ * Two execution paths, chosen like the forward ones (lot_path): REFERENCE = one plain kernel per
+ * step with the n x r intermediates in the workspace, any shape; FUSED = tiled MFMA kernels that
+ * keep nothing of size n x r (d_k = d_v in {32, 64}, r <= 64, iters <= 32).  AUTO prefers FUSED.
+ * Results are reproducible bit for bit on either path.
  */
 int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out);
 int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
                       const float* Z, const float* beta, float eps, int iters, const void* dO,
                       void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
+int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                           const float* Z, const float* beta, float eps, int iters, const void* dO,
+                           void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                           void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
  * Debug: synchronises the device and reads the status word that the fused kernel leaves in the

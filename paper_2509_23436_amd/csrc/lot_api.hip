@@ -155,14 +155,20 @@ int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t*
     if (!bytes_out) return LOT_ERR_NULL;
     if (iters < 1) return LOT_ERR_ITERS;
     if (iters > (1 << 16)) return LOT_ERR_ITERS;   // one stored vector of potentials per iteration
-    *bytes_out = carve_bwd(*shape, iters).total;
+    // covers both execution paths (the plain one is the larger)
+    size_t need = carve_bwd(*shape, iters).total;
+    if (bwd_tiled_supports(*shape, iters)) {
+        const size_t tiled = carve_bwd_tiled(*shape, iters).total;
+        if (tiled > need) need = tiled;
+    }
+    *bytes_out = need;
     return LOT_OK;
 }
 
-int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
-                      const float* Z, const float* beta, float eps, int iters, const void* dO,
-                      void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
-                      void* workspace, size_t workspace_bytes, void* hip_stream)
+int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                           const float* Z, const float* beta, float eps, int iters, const void* dO,
+                           void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                           void* workspace, size_t workspace_bytes, void* hip_stream, int path)
 {
     int rc = validate_shape(shape);
     if (rc != LOT_OK) return rc;
@@ -174,13 +180,35 @@ int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, cons
         misaligned(dbeta, 4))
         return LOT_ERR_ALIGN;
     if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
+    bool tiled = false;
+    switch (path) {
+    case LOT_PATH_AUTO: tiled = bwd_tiled_supports(*shape, iters); break;
+    case LOT_PATH_REFERENCE: tiled = false; break;
+    case LOT_PATH_FUSED:
+        if (!bwd_tiled_supports(*shape, iters)) return LOT_ERR_PATH;
+        tiled = true;
+        break;
+    default: return LOT_ERR_PATH;
+    }
+    size_t need = 0;
+    rc = lot_attention_bwd_workspace_bytes(shape, iters, &need);
+    if (rc != LOT_OK) return rc;
+    if (workspace_bytes < need) return LOT_ERR_WORKSPACE;
     BwdArgs a{};
     a.lay = carve_bwd(*shape, iters);
-    if (workspace_bytes < a.lay.total) return LOT_ERR_WORKSPACE;
     a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
     a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
-    return run_backward(a);
+    return tiled ? run_backward_tiled(a) : run_backward(a);
+}
+
+int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                      const float* Z, const float* beta, float eps, int iters, const void* dO,
+                      void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                      void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return lot_attention_bwd_path(shape, Q, K, V, Z, beta, eps, iters, dO, dQ, dK, dV, dZ, dbeta, workspace,
+                                  workspace_bytes, hip_stream, LOT_PATH_AUTO);
 }
 
 int lot_workspace_status(const void* workspace)

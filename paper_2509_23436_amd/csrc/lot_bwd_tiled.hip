@@ -1,0 +1,1007 @@
+// Backward pass of LOT attention, tiled path (d_k = d_v in {32, 64}, r <= 64): the same gradients
+// as the plain path, computed with the tile machinery of the fused forward kernel and without ever
+// materialising anything of size n x r.
+//
+// What makes that possible.  Write, for one solve, W^k_it = softmax_t((C_it + g^{k-1}_t)/eps) (the
+// row-normalised kernel of iteration k, so that the plan after the token-side update is a W^k with
+// a = 1/n), cs^k_t = sum_i W^k_it, c^k = a cs^k, and M^k = (W^k)^T W^k (r x r).  Differentiating the
+// pivot-side update g^k = g^{k-1} + eps log(beta / c^k) through the softmax gives, for the
+// adjoints dg^k of the potentials and dc^k = -eps dg^k / c^k of the column sums,
+//       dg^{k-1} = -(a/eps) M^k dc^k                                   (k = T-1 .. 1)
+// so the whole reverse recursion over the iterations is a chain of r x r matrix-vector products,
+// once the Gram matrices M^k have been accumulated during the forward passes.  The last step,
+// where the coupling Gamma = a W^T Diag(beta / c^T) meets its incoming gradient dGamma, starts it:
+//       s_t = sum_i dGamma_it Gamma_it,   dc^T_t = -s_t / c^T_t,
+//       q_i = sum_t Gamma_it dGamma_it,   N_t = sum_i W^T_it q_i,
+//       dg^{T-1} = -(1/eps) (N + a M^T dc^T).
+// With every dc^k known, the gradient of the similarities is local to a token,
+//       dC_it = (a/eps) sum_k W^k_it (dP^k_it - e^k_i),  dP^k = dc^k (k < T),  dP^T = dGamma beta/c^T + dc^T,
+//       e^k_i = sum_t dP^k_it W^k_it,
+// and is assembled tile by tile in registers, all T iterations of a tile at once, then contracted
+// with Z (-> dQ, dK) and with the token rows (-> dZ) by MFMA before it is dropped.
+// (Paper, "Learning": the pivots, their masses and the projections are trained by backpropagating
+// through both Sinkhorn problems and the glued composition.  The derivation is this file's.)
+//
+// One kernel launch per step; launch boundaries are the only synchronisation between workgroups:
+//   clear | T x forward pass (column sums, Gram, and at k = T the two token contractions
+//   U = sum W2 V, Wd = sum W1 dO) | mid (Y', dYraw) | glue (s, N, dV) | Gram reduce | recursion |
+//   assemble (dQ, dK, dZ partials) | final (dZ, dbeta).
+// Both solves share every launch (pair = side * G + g, side 0 = queries).  All reductions have a
+// fixed order except the column sums, which are exchanged as integers: results are reproducible.
+#include "lot_internal.h"
+#include "lot_tile.h"
+
+namespace lot {
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+constexpr int kTilesPerWave = 4;
+constexpr int kTilesPerWg = kWaves * kTilesPerWave;
+
+struct BtParams {
+    const void* Q; const void* K; const void* V; const void* dO;
+    const float* Z; const float* beta;
+    void* dQ; void* dK; void* dV;
+    float* dZ; float* dbeta;
+    unsigned long long* colacc;   // [T+1][pairs][64] fixed-point column sums of W^k (k = 1..T)
+    float* ghist;                 // [T+1][pairs][64] g^k, k = 0..T-1 (padding pivots: -1e30)
+    float* gram_part;             // [T][pairs][chunks][R2]
+    float* gram_full;             // [T][pairs][R2]
+    float* u_part;                // [pairs][chunks][64][D]   side 1: sum W2 V, side 0: sum W1 dO
+    float* yp;                    // [G][64][D]  Y'
+    float* dyraw;                 // [G][64][D]  dY' / beta
+    float* sn_part;               // [pairs][chunks][2][64]
+    float* dcs;                   // [T+1][pairs][64]  dc^k, k = 1..T
+    float* rhop;                  // [pairs][64]  beta_t / cs^T_t
+    float* db_pair;               // [pairs][64]
+    float* db_glue;               // [G][64]
+    float* dz_part;               // [pairs][chunks][64][D]
+    int G, H, B, n, r, chunks, k, T;
+    float eps, fx_scale, fx_unscale;
+};
+
+// ---------------------------------------------------------------------------------------------
+// tile helpers
+// ---------------------------------------------------------------------------------------------
+// On return acc holds e_it = exp2((C_it + g_t) c1 - m_i) (pivots past r give exactly 0) and w the
+// reciprocal of their row sum, so the row-normalised kernel is W_it = acc * w.  pot: LDS, 64 floats.
+template <typename IO, int D, int RB>
+__device__ __forceinline__ void tile_weights(f32x16 (&acc)[RB], float& w, const Frag<IO, D> (&zf)[RB],
+                                             const Frag<IO, D>& xf, const float* pot, int kg, float c1, bool valid)
+{
+    int skew = 0;
+    asm volatile("" : "+v"(skew));
+    load_pivot_vector<RB>(acc, pot + skew, kg);
+    similarity<D, RB>(acc, zf, xf);
+    float m0 = acc[0][0], m1 = acc[0][1];
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int j = (mb == 0 ? 2 : 0); j < 16; j += 2) {
+            m0 = fmaxf(m0, acc[mb][j]);
+            m1 = fmaxf(m1, acc[mb][j + 1]);
+        }
+    const float mc = pair_max(fmaxf(m0, m1)) * c1;
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; j += 2) {
+            const float e0 = exp2_fast(fmaf(acc[mb][j], c1, -mc));
+            const float e1 = exp2_fast(fmaf(acc[mb][j + 1], c1, -mc));
+            acc[mb][j] = e0; acc[mb][j + 1] = e1;
+            s0 += e0; s1 += e1;
+        }
+    w = valid ? rcp_fast(pair_sum(s0 + s1)) : 0.f;
+}
+
+// Writes v (accumulator layout, tokens in lanes) transposed into the wavefront's LDS area as bf16
+// hi (+ lo when SPLIT), so that rows of 32 tokens can be read back as MFMA operands.
+template <int RB, bool SPLIT>
+__device__ __forceinline__ void transpose_tile(const f32x16 (&v)[RB], uint16_t* tr_hi, uint16_t* tr_lo, int i, int kg)
+{
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float x = v[mb][j];
+            const __bf16 h = (__bf16)x;
+            const int pv = pivot_of(mb, j, kg);
+            tr_hi[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, h);
+            if (SPLIT) tr_lo[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, (__bf16)(x - (float)h));
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+__device__ __forceinline__ void transpose_done()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// U[mb][nb] += sum over the tile's tokens of v_it * X_i[NB i' + nb]  (v transposed in LDS; the token
+// rows as B fragments vh / vl for the two halves of the tile)
+template <int D, int RB, bool SPLIT>
+__device__ __forceinline__ void contract_tokens(f32x16 (&U)[RB][D / 32], const uint16_t* tr_hi, const uint16_t* tr_lo,
+                                                const bf16x8 (&vh)[2][D / 32], const bf16x8 (&vl)[2][D / 32], int i, int kg)
+{
+    constexpr int NB = D / 32;
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) {
+            const bf16x8 ah = *reinterpret_cast<const bf16x8*>(tr_hi + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vh[s][nb], U[mb][nb], 0, 0, 0);
+            if (SPLIT) {
+                const bf16x8 al = *reinterpret_cast<const bf16x8*>(tr_lo + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, vh[s][nb], U[mb][nb], 0, 0, 0);
+                    U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vl[s][nb], U[mb][nb], 0, 0, 0);
+                }
+            }
+        }
+}
+
+// Gm[mb][mb2] += sum over the tile's tokens of v_it v_it'   (t in block mb: registers, t' in block mb2: lanes)
+template <int RB, bool SPLIT>
+__device__ __forceinline__ void contract_gram(f32x16 (&Gm)[RB][RB], const uint16_t* tr_hi, const uint16_t* tr_lo, int i, int kg)
+{
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        bf16x8 ah[RB], al[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) {
+            ah[mb] = *reinterpret_cast<const bf16x8*>(tr_hi + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
+            if (SPLIT) al[mb] = *reinterpret_cast<const bf16x8*>(tr_lo + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
+        }
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int mb2 = 0; mb2 < RB; ++mb2) {
+                Gm[mb][mb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[mb], ah[mb2], Gm[mb][mb2], 0, 0, 0);
+                if (SPLIT) {
+                    Gm[mb][mb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[mb], ah[mb2], Gm[mb][mb2], 0, 0, 0);
+                    Gm[mb][mb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[mb], al[mb2], Gm[mb][mb2], 0, 0, 0);
+                }
+            }
+    }
+}
+
+// out_tile[token][dcol] = sum_t v_it Y_t[dcol]: v in accumulator layout as the A operand, Y as B
+// fragments in LDS laid out for the same order of pivots (see lay_out_fragments).
+template <int D, int RB, bool SPLIT>
+__device__ __forceinline__ void contract_pivots(f32x16 (&o)[D / 32], const f32x16 (&v)[RB],
+                                                const bf16x8* yf_hi, const bf16x8* yf_lo, int lane)
+{
+    constexpr int NB = D / 32;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[nb][j] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 2 * RB; ++s) {
+        f32x8 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = v[s >> 1][8 * (s & 1) + e];
+        bf16x8 ah, al;
+        if (SPLIT) split_bf16(t, ah, al);
+        else ah = __builtin_convertvector(t, bf16x8);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const bf16x8 yh = yf_hi[(s * NB + nb) * 64 + lane];
+            o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, yh, o[nb], 0, 0, 0);
+            if (SPLIT) {
+                const bf16x8 yl = yf_lo[(s * NB + nb) * 64 + lane];
+                o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, yh, o[nb], 0, 0, 0);
+                o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, yl, o[nb], 0, 0, 0);
+            }
+        }
+    }
+}
+
+// Lays a [64][D] fp32 matrix in LDS (rows = pivots) out as the B fragments contract_pivots reads.
+template <int D, int RB>
+__device__ __forceinline__ void lay_out_fragments(const float* src, bf16x8* yf_hi, bf16x8* yf_lo, int tid)
+{
+    constexpr int NB = D / 32;
+    for (int f = tid; f < 2 * RB * NB * 64; f += kThreads) {
+        const int fl = f & 63, fi = fl & 31, fkg = fl >> 5;
+        const int snb = f >> 6, s = snb / NB, nb = snb % NB;
+        f32x8 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int pv = 32 * (s >> 1) + 16 * (s & 1) + 8 * (e >> 2) + 4 * fkg + (e & 3);
+            t[e] = src[pv * D + NB * fi + nb];
+        }
+        bf16x8 hi, lo;
+        split_bf16(t, hi, lo);
+        yf_hi[f] = hi;
+        yf_lo[f] = lo;
+    }
+}
+
+// Sum of a 16 RB NB-register accumulator over the workgroup's wavefronts, in wavefront order, into
+// buf (LDS, [64][D], element (pivot, NB i + nb)).  Contains barriers: all wavefronts call it.
+template <int D, int RB>
+__device__ __forceinline__ void sum_over_waves(const f32x16 (&U)[RB][D / 32], float* buf, int wave, int i, int kg)
+{
+    constexpr int NB = D / 32;
+    for (int turn = 0; turn < kWaves; ++turn) {
+        if (wave == turn) {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        float* dst = &buf[pivot_of(mb, j, kg) * D + NB * i + nb];
+                        *dst = turn == 0 ? U[mb][nb][j] : *dst + U[mb][nb][j];
+                    }
+        }
+        __syncthreads();
+    }
+}
+
+// Operand fragment of the similarity MFMA from a row of fp32 numbers in LDS (the bf16 variant rounds
+// them to bf16: the products they enter are accumulated in fp32 and the rounding, 2^-9 and zero-mean,
+// stays well inside the bf16 output bar).
+template <int D>
+__device__ __forceinline__ void load_pivots_lds(Frag<uint16_t, D>& f, const float* row, int kg)
+{
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+        f32x8 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = row[16 * s + 8 * kg + e];
+        f.v[s] = __builtin_convertvector(t, bf16x8);
+    }
+}
+template <int D>
+__device__ __forceinline__ void load_pivots_lds(Frag<float, D>& f, const float* row, int kg)
+{
+#pragma unroll
+    for (int s = 0; s < D / 2; ++s) f.v[s] = row[kg * (D / 2) + s];
+}
+
+template <typename IO, int D, int RB> struct StashBytes { static constexpr int value = RB * (int)sizeof(Frag<IO, D>) * 64; };
+
+template <typename IO> __device__ __forceinline__ const IO* rows_of(const BtParams& p, int side)
+{
+    return reinterpret_cast<const IO*>(side == 0 ? p.Q : p.K);
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward pass k: column sums and Gram matrix of W^k; at k = T also the token contraction with V
+// (keys) or dO (queries)
+// ---------------------------------------------------------------------------------------------
+template <typename IO, int D, int RB, bool WITH_U>
+__global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
+{
+    constexpr int NB = D / 32;
+    constexpr bool kSplit = io_is_f32<IO>::value;
+    constexpr int R = 32 * RB;
+    __shared__ float s_g[64];
+    __shared__ float s_cs[kWaves][64];
+    __shared__ __attribute__((aligned(16))) float s_buf[64 * 64 > 64 * D ? 64 * 64 : 64 * D];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * 2 * 64 * kTrStride];
+    __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 31, kg = lane >> 5;
+    const int pairs = 2 * p.G;
+    const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
+    const int side = pair / p.G, g = pair % p.G, h = g % p.H;
+    const int n = p.n, r = p.r, k = p.k;
+    const float c1 = kLog2e / p.eps;
+    const IO* X = rows_of<IO>(p, side);
+    uint16_t* tr_hi = s_tr + (wave * 2 + 0) * 64 * kTrStride;
+    uint16_t* tr_lo = s_tr + (wave * 2 + 1) * 64 * kTrStride;
+
+    // g^{k-1} from the column sums of the previous launch
+    if (tid < 64) {
+        float gv = tid < r ? 0.f : kNegBig;
+        if (k > 1 && tid < r) {
+            const unsigned long long word = p.colacc[((size_t)(k - 1) * pairs + pair) * 64 + tid];
+            const float cs = fmaxf((float)(long long)word * p.fx_unscale, 1.0e-37f);
+            gv = p.ghist[((size_t)(k - 2) * pairs + pair) * 64 + tid] + p.eps * logf((float)n * p.beta[h * r + tid] / cs);
+        }
+        s_g[tid] = gv;
+        if (chunk == 0) p.ghist[((size_t)(k - 1) * pairs + pair) * 64 + tid] = gv;
+    }
+    if (wave == 0) {
+        Frag<IO, D> z0[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) {
+            const int t = 32 * mb + i;
+            load_pivots<D>(z0[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
+        }
+        stash_pivots<D, RB>(s_zstash, z0, lane);
+    }
+    __syncthreads();
+
+    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    const int tile_begin = chunk * kTilesPerWg, tile_end = min(ntiles, tile_begin + kTilesPerWg);
+    f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cs[mb][j] = 0.f;
+#pragma unroll
+        for (int mb2 = 0; mb2 < RB; ++mb2)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) Gm[mb][mb2][j] = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
+    }
+    const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
+
+    Frag<IO, D> xc;
+    if (tile_begin + wave < tile_end) {
+        const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
+        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
+    }
+    for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
+        Frag<IO, D> xn = xc;
+        if (tile + kWaves < tile_end) {
+            const int tok = min((tile + kWaves) * kTileTokens + i, n - 1);
+            load_tokens<D>(xn, X + ((size_t)g * n + tok) * D, kg);
+        }
+        bf16x8 vh[2][NB], vl[2][NB];
+        if (WITH_U) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
+                const int left = max(1, min(8, n - t0));
+                load_values<D>(vh[s], vl[s], vals, (size_t)g * n + min(t0, n - 1), left, i);
+            }
+        }
+        f32x16 acc[RB];
+        float w;
+        {
+            int skew = 0;
+            asm volatile("" : "+v"(skew));
+            Frag<IO, D> zf[RB];
+            fetch_pivots<D, RB>(zf, s_zstash, lane, skew);
+            tile_weights<IO, D, RB>(acc, w, zf, xc, s_g, kg, c1, tile * kTileTokens + i < n);
+        }
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                acc[mb][j] *= w;
+                cs[mb][j] += acc[mb][j];
+            }
+        transpose_tile<RB, kSplit>(acc, tr_hi, tr_lo, i, kg);
+        contract_gram<RB, kSplit>(Gm, tr_hi, tr_lo, i, kg);
+        if (WITH_U) contract_tokens<D, RB, kSplit>(U, tr_hi, tr_lo, vh, vl, i, kg);
+        transpose_done();
+        xc = xn;
+    }
+
+    // column sums: one pivot per lane, then across the wavefronts, then one integer atomic per pivot
+    {
+        float c[16 * RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) c[16 * mb + j] = cs[mb][j];
+        const float total = reduce_scatter_tokens<16 * RB>(c, i);
+        const int q = RB == 2 ? i : i >> 1;
+        s_cs[wave][32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3)] = total;
+        if (RB == 1) s_cs[wave][32 + lane % 32] = 0.f;
+    }
+    __syncthreads();
+    if (tid < r) {
+        float tot = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) tot += s_cs[wv][tid];
+        const unsigned long long word = (unsigned long long)__float2ll_rn(tot * p.fx_scale);
+        __hip_atomic_fetch_add(p.colacc + ((size_t)k * pairs + pair) * 64 + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // Gram matrix: block (mb, mb2) holds rows t = pivot_of(mb, j, kg), columns t' = 32 mb2 + i
+    {
+        float* gp = p.gram_part + (((size_t)(k - 1) * pairs + pair) * p.chunks + chunk) * R * R;
+        for (int turn = 0; turn < kWaves; ++turn) {
+            if (wave == turn) {
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int mb2 = 0; mb2 < RB; ++mb2)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) {
+                            float* dst = &s_buf[pivot_of(mb, j, kg) * R + 32 * mb2 + i];
+                            *dst = turn == 0 ? Gm[mb][mb2][j] : *dst + Gm[mb][mb2][j];
+                        }
+            }
+            __syncthreads();
+        }
+        for (int e = tid; e < R * R; e += kThreads) gp[e] = s_buf[e];
+        __syncthreads();
+    }
+    if (WITH_U) {
+        sum_over_waves<D, RB>(U, s_buf, wave, i, kg);
+        float* up = p.u_part + ((size_t)pair * p.chunks + chunk) * 64 * D;
+        for (int e = tid; e < R * D; e += kThreads) up[e] = s_buf[e];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// mid: Y'_t = U_t / cs2_t, dYraw_t = n Wd_t / cs1_t, db_glue_t = -<dYraw_t, Y'_t>, rho'_t = beta_t / cs_t
+// one workgroup per problem, thread = (t, column)
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ void bt_mid(BtParams p)
+{
+    const int g = blockIdx.x, h = g % p.H, pairs = 2 * p.G, T = p.T;
+    const int tid = threadIdx.x;
+    for (int e = tid; e < 64 * D; e += blockDim.x) {
+        const int t = e / D;
+        float y = 0.f, dy = 0.f;
+        if (t < p.r) {
+            float u = 0.f, wd = 0.f;
+            for (int c = 0; c < p.chunks; ++c) {
+                wd += p.u_part[((size_t)(0 * p.G + g) * p.chunks + c) * 64 * D + e];
+                u += p.u_part[((size_t)(1 * p.G + g) * p.chunks + c) * 64 * D + e];
+            }
+            const float cs1 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
+            const float cs2 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
+            y = u / cs2;
+            dy = (float)p.n * wd / cs1;
+        }
+        p.yp[(size_t)g * 64 * D + e] = y;
+        p.dyraw[(size_t)g * 64 * D + e] = dy;
+    }
+    __syncthreads();
+    if (tid < 64) {
+        const int t = tid;
+        float dot = 0.f, r1 = 0.f, r2 = 0.f;
+        if (t < p.r) {
+            for (int c = 0; c < D; ++c) dot = fmaf(p.dyraw[(size_t)g * 64 * D + t * D + c], p.yp[(size_t)g * 64 * D + t * D + c], dot);
+            const float b = p.beta[h * p.r + t];
+            r1 = b / fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
+            r2 = b / fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
+        }
+        p.db_glue[g * 64 + t] = -dot;
+        p.rhop[(size_t)g * 64 + t] = r1;
+        p.rhop[(size_t)(p.G + g) * 64 + t] = r2;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// glue: per tile the incoming gradient of the coupling, dGamma1_it = n <dO_i, Y'_t> (queries) or
+// dGamma2_jt = <V_j, dYraw_t> (keys), and from it s_t, q_i, N_t; the key side also writes
+// dV_j = sum_t Gamma2_jt dYraw_t.
+// ---------------------------------------------------------------------------------------------
+template <typename IO, int D, int RB>
+__global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
+{
+    constexpr int NB = D / 32;
+    constexpr bool kSplit = io_is_f32<IO>::value;
+    __shared__ float s_g[64], s_rho[64];
+    __shared__ float s_part[kWaves][2][64];
+    __shared__ __attribute__((aligned(16))) float s_y[64 * D];
+    __shared__ __attribute__((aligned(16))) bf16x8 s_yf[2][2 * RB * NB * 64];
+    __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
+    __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 31, kg = lane >> 5;
+    const int pairs = 2 * p.G;
+    const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
+    const int side = pair / p.G, g = pair % p.G, h = g % p.H;
+    const int n = p.n, r = p.r, T = p.T;
+    const float c1 = kLog2e / p.eps;
+    const IO* X = rows_of<IO>(p, side);
+    const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
+    // the matrix whose rows meet the value rows: n Y' for the queries, dYraw for the keys
+    const float* ymat = (side == 0 ? p.yp : p.dyraw) + (size_t)g * 64 * D;
+    const float yscale = side == 0 ? (float)n : 1.f;
+
+    if (tid < 64) {
+        s_g[tid] = p.ghist[((size_t)(T - 1) * pairs + pair) * 64 + tid];
+        s_rho[tid] = p.rhop[(size_t)pair * 64 + tid];
+    }
+    if (wave == 0) {
+        Frag<IO, D> z0[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) {
+            const int t = 32 * mb + i;
+            load_pivots<D>(z0[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
+        }
+        stash_pivots<D, RB>(s_zstash, z0, lane);
+    }
+    // keys: the expansion to dV needs rho'_t dYraw_t as B fragments
+    if (side == 1) {
+        for (int e = tid; e < 64 * D; e += kThreads) s_y[e] = p.dyraw[(size_t)g * 64 * D + e] * p.rhop[(size_t)pair * 64 + e / D];
+    } else {
+        for (int e = tid; e < 64 * D; e += kThreads) s_y[e] = 0.f;
+    }
+    __syncthreads();
+    lay_out_fragments<D, RB>(s_y, s_yf[0], s_yf[1], tid);
+    __syncthreads();
+    // rows of ymat as the "pivot" operand of the similarity MFMA (scaled), via LDS staging
+    for (int e = tid; e < 64 * D; e += kThreads) s_y[e] = ymat[e] * yscale;
+    __syncthreads();
+    if (wave == 0) {
+        Frag<IO, D> y0[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) load_pivots_lds<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
+        stash_pivots<D, RB>(s_ystash, y0, lane);
+    }
+    __syncthreads();
+
+    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    const int tile_begin = chunk * kTilesPerWg, tile_end = min(ntiles, tile_begin + kTilesPerWg);
+    f32x16 sacc[RB], nacc[RB];
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) { sacc[mb][j] = 0.f; nacc[mb][j] = 0.f; }
+
+    for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
+        const int tok = min(tile * kTileTokens + i, n - 1);
+        Frag<IO, D> xc, vc;
+        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * n + tok) * D, kg);
+        f32x16 acc[RB], dgam[RB], rho[RB];
+        float w;
+        int skew = 0;
+        asm volatile("" : "+v"(skew));
+        {
+            Frag<IO, D> zf[RB];
+            fetch_pivots<D, RB>(zf, s_zstash, lane, skew);
+            tile_weights<IO, D, RB>(acc, w, zf, xc, s_g, kg, c1, tile * kTileTokens + i < n);
+        }
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) { acc[mb][j] *= w; dgam[mb][j] = 0.f; }
+        {
+            Frag<IO, D> yfrag[RB];
+            fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
+            similarity<D, RB>(dgam, yfrag, vc);
+        }
+        load_pivot_vector<RB>(rho, s_rho + skew, kg);
+        // q_i = sum_t Gamma_it dGamma_it with Gamma_it = W_it rho'_t
+        float q0 = 0.f, q1 = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; j += 2) {
+                const float a0 = acc[mb][j] * dgam[mb][j], a1 = acc[mb][j + 1] * dgam[mb][j + 1];
+                sacc[mb][j] += a0; sacc[mb][j + 1] += a1;          // s_t / rho'_t, scaled at the end
+                q0 = fmaf(a0, rho[mb][j], q0);
+                q1 = fmaf(a1, rho[mb][j + 1], q1);
+            }
+        const float q = pair_sum(q0 + q1);
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) nacc[mb][j] = fmaf(acc[mb][j], q, nacc[mb][j]);
+        if (side == 1) {
+            f32x16 o[NB];
+            contract_pivots<D, RB, kSplit>(o, acc, s_yf[0], s_yf[1], lane);
+            IO* out = reinterpret_cast<IO*>(p.dV);
+            const int row0 = tile * kTileTokens + 4 * kg;
+            IO* const lane_base = out + ((size_t)g * n + row0) * D;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (row0 + 8 * (j >> 2) + (j & 3) < n)
+                    store_out<NB>(lane_base + (8 * (j >> 2) + (j & 3)) * D, i, o[0][j], o[NB - 1][j]);
+        }
+    }
+    // per-workgroup partials of s (scaled by rho') and N
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        float c[16 * RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) c[16 * mb + j] = which == 0 ? sacc[mb][j] : nacc[mb][j];
+        const float total = reduce_scatter_tokens<16 * RB>(c, i);
+        const int q = RB == 2 ? i : i >> 1;
+        s_part[wave][which][32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3)] = total;
+        if (RB == 1) s_part[wave][which][32 + lane % 32] = 0.f;
+    }
+    __syncthreads();
+    if (tid < 128) {
+        const int which = tid >> 6, t = tid & 63;
+        float tot = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) tot += s_part[wv][which][t];
+        if (which == 0) tot *= s_rho[t];
+        p.sn_part[(((size_t)pair * p.chunks + chunk) * 2 + which) * 64 + t] = tot;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gram reduce: gram_full[k][pair] = sum over chunks (index order)
+// ---------------------------------------------------------------------------------------------
+__global__ void bt_gram_reduce(BtParams p, int R2)
+{
+    const size_t kp = blockIdx.x;     // (k-1) * pairs + pair
+    for (int e = threadIdx.x; e < R2; e += blockDim.x) {
+        float acc = 0.f;
+        for (int c = 0; c < p.chunks; ++c) acc += p.gram_part[(kp * p.chunks + c) * R2 + e];
+        p.gram_full[kp * R2 + e] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// recursion over the iterations: one workgroup of 64 threads per pair, thread = pivot
+// ---------------------------------------------------------------------------------------------
+__global__ void bt_recursion(BtParams p, int R)
+{
+    __shared__ float s_v[64];
+    const int pair = blockIdx.x, t = threadIdx.x, pairs = 2 * p.G, T = p.T;
+    const int h = (pair % p.G) % p.H;
+    const bool live = t < p.r;
+    const float a = 1.f / (float)p.n;
+    const float b = live ? p.beta[h * p.r + t] : 1.f;
+    float s = 0.f, nn = 0.f;
+    for (int c = 0; c < p.chunks; ++c) {
+        s += p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 0) * 64 + t];
+        nn += p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 1) * 64 + t];
+    }
+    auto colsum = [&](int k) {
+        return fmaxf((float)(long long)p.colacc[((size_t)k * pairs + pair) * 64 + t] * p.fx_unscale, 1.0e-37f) * a;   // c^k_t
+    };
+    auto gram_times = [&](int k, float v) {      // (M^k v)_t, v given per thread
+        s_v[t] = live ? v : 0.f;
+        __syncthreads();
+        float acc = 0.f;
+        if (live && t < R) {
+            const float* row = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + (size_t)t * R;
+            for (int u = 0; u < R; ++u) acc = fmaf(row[u], s_v[u], acc);
+        }
+        __syncthreads();
+        return acc;
+    };
+    float db = live ? s / b : 0.f;
+    float dc = live ? -s / colsum(T) : 0.f;
+    p.dcs[((size_t)T * pairs + pair) * 64 + t] = dc;
+    float dg = -(nn + a * gram_times(T, dc)) / p.eps;          // dg^{T-1}
+    for (int k = T - 1; k >= 1; --k) {
+        dc = live ? -p.eps * dg / colsum(k) : 0.f;
+        db += live ? p.eps * dg / b : 0.f;
+        p.dcs[((size_t)k * pairs + pair) * 64 + t] = dc;
+        dg = -(a / p.eps) * gram_times(k, dc);                  // dg^{k-1}
+    }
+    p.db_pair[(size_t)pair * 64 + t] = live ? db : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// assemble: dC tile over all iterations, then dQ / dK rows and the workgroup's share of dZ
+// ---------------------------------------------------------------------------------------------
+template <typename IO, int D, int RB>
+__global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
+{
+    constexpr int NB = D / 32;
+    constexpr bool kSplit = io_is_f32<IO>::value;
+    extern __shared__ __attribute__((aligned(16))) char s_dyn[];   // [Tcap][2][64] floats: g^{k-1} c1, dc^k
+    __shared__ float s_rho[64];
+    __shared__ __attribute__((aligned(16))) float s_y[64 * D];
+    __shared__ __attribute__((aligned(16))) bf16x8 s_zf[2][2 * RB * NB * 64];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * 2 * 64 * kTrStride];
+    __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
+    __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
+    float* s_hist = reinterpret_cast<float*>(s_dyn);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 31, kg = lane >> 5;
+    const int pairs = 2 * p.G;
+    const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
+    const int side = pair / p.G, g = pair % p.G, h = g % p.H;
+    const int n = p.n, r = p.r, T = p.T;
+    const float c1 = kLog2e / p.eps;
+    const IO* X = rows_of<IO>(p, side);
+    const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
+    const float* ymat = (side == 0 ? p.yp : p.dyraw) + (size_t)g * 64 * D;
+    const float yscale = side == 0 ? (float)n : 1.f;
+    uint16_t* tr_hi = s_tr + (wave * 2 + 0) * 64 * kTrStride;
+    uint16_t* tr_lo = s_tr + (wave * 2 + 1) * 64 * kTrStride;
+
+    for (int e = tid; e < T * 64; e += kThreads) {
+        const int k = e / 64 + 1, t = e % 64;
+        s_hist[((k - 1) * 2 + 0) * 64 + t] = p.ghist[((size_t)(k - 1) * pairs + pair) * 64 + t] * c1;   // padding: -1e30 c1
+        s_hist[((k - 1) * 2 + 1) * 64 + t] = p.dcs[((size_t)k * pairs + pair) * 64 + t];
+    }
+    if (tid < 64) s_rho[tid] = p.rhop[(size_t)pair * 64 + tid];
+    if (wave == 0) {
+        Frag<IO, D> z0[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) {
+            const int t = 32 * mb + i;
+            load_pivots<D>(z0[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
+        }
+        stash_pivots<D, RB>(s_zstash, z0, lane);
+    }
+    // Z rows as B fragments (the values the forward pass multiplied with: rounded to bf16 for bf16 I/O)
+    for (int e = tid; e < 64 * D; e += kThreads) {
+        const int t = e / D;
+        float z = t < r ? p.Z[((size_t)h * r + t) * D + e % D] : 0.f;
+        if (!kSplit) z = (float)(__bf16)z;
+        s_y[e] = z;
+    }
+    __syncthreads();
+    lay_out_fragments<D, RB>(s_y, s_zf[0], s_zf[1], tid);
+    __syncthreads();
+    for (int e = tid; e < 64 * D; e += kThreads) s_y[e] = ymat[e] * yscale;
+    __syncthreads();
+    if (wave == 0) {
+        Frag<IO, D> y0[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) load_pivots_lds<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
+        stash_pivots<D, RB>(s_ystash, y0, lane);
+    }
+    __syncthreads();   // s_y is reused below for the dZ partial
+
+    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    const int tile_begin = chunk * kTilesPerWg, tile_end = min(ntiles, tile_begin + kTilesPerWg);
+    f32x16 dZacc[RB][NB];
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) dZacc[mb][nb][j] = 0.f;
+    const float scale_out = 1.f / ((float)n * p.eps);   // a / eps
+
+    for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
+        const int tok = min(tile * kTileTokens + i, n - 1);
+        const bool valid = tile * kTileTokens + i < n;
+        Frag<IO, D> xc, vc;
+        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * n + tok) * D, kg);
+        int skew = 0;
+        asm volatile("" : "+v"(skew));
+        // similarities scaled to base-2 exponents, once
+        f32x16 sc[RB], dacc[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) { sc[mb][j] = 0.f; dacc[mb][j] = 0.f; }
+        {
+            Frag<IO, D> zf[RB];
+            fetch_pivots<D, RB>(zf, s_zstash, lane, skew);
+            similarity<D, RB>(sc, zf, xc);
+        }
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) sc[mb][j] *= c1;
+
+        for (int k = T; k >= 1; --k) {
+            f32x16 e[RB], dp[RB];
+            load_pivot_vector<RB>(e, s_hist + ((k - 1) * 2 + 0) * 64 + skew, kg);
+            load_pivot_vector<RB>(dp, s_hist + ((k - 1) * 2 + 1) * 64 + skew, kg);
+            if (k == T) {
+                // dP^T = dGamma rho' n... : dGamma_it rho_t with rho_t = beta_t / c^T_t = n rho'_t
+                f32x16 dgam[RB], rho[RB];
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) dgam[mb][j] = 0.f;
+                {
+                    Frag<IO, D> yfrag[RB];
+                    fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
+                    similarity<D, RB>(dgam, yfrag, vc);
+                }
+                load_pivot_vector<RB>(rho, s_rho + skew, kg);
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) dp[mb][j] = fmaf(dgam[mb][j] * (float)n, rho[mb][j], dp[mb][j]);
+            }
+            float m0 = -INFINITY, m1 = -INFINITY;
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; j += 2) {
+                    e[mb][j] += sc[mb][j];
+                    e[mb][j + 1] += sc[mb][j + 1];
+                    m0 = fmaxf(m0, e[mb][j]);
+                    m1 = fmaxf(m1, e[mb][j + 1]);
+                }
+            const float m = pair_max(fmaxf(m0, m1));
+            float s0 = 0.f, s1 = 0.f, d0 = 0.f, d1 = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; j += 2) {
+                    const float e0 = exp2_fast(e[mb][j] - m), e1 = exp2_fast(e[mb][j + 1] - m);
+                    e[mb][j] = e0; e[mb][j + 1] = e1;
+                    s0 += e0; s1 += e1;
+                    d0 = fmaf(dp[mb][j], e0, d0);
+                    d1 = fmaf(dp[mb][j + 1], e1, d1);
+                }
+            float ssum, sdot;
+            {
+                float lo, hi;
+                both_halves(s0 + s1, lo, hi); ssum = lo + hi;
+                both_halves(d0 + d1, lo, hi); sdot = lo + hi;
+            }
+            const float w = valid ? rcp_fast(ssum) : 0.f;
+            const float ei = sdot * w;                    // e^k_i = sum_t dP_it W_it
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(e[mb][j] * w, dp[mb][j] - ei, dacc[mb][j]);
+        }
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) dacc[mb][j] *= scale_out;      // dC tile
+
+        // dQ (or dK) rows = dC Z
+        {
+            f32x16 o[NB];
+            contract_pivots<D, RB, kSplit>(o, dacc, s_zf[0], s_zf[1], lane);
+            IO* out = reinterpret_cast<IO*>(side == 0 ? p.dQ : p.dK);
+            const int row0 = tile * kTileTokens + 4 * kg;
+            IO* const lane_base = out + ((size_t)g * n + row0) * D;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (row0 + 8 * (j >> 2) + (j & 3) < n)
+                    store_out<NB>(lane_base + (8 * (j >> 2) + (j & 3)) * D, i, o[0][j], o[NB - 1][j]);
+        }
+        // dZ += dC^T X
+        bf16x8 vh[2][NB], vl[2][NB];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
+            const int left = max(1, min(8, n - t0));
+            load_values<D>(vh[s], vl[s], X, (size_t)g * n + min(t0, n - 1), left, i);
+        }
+        transpose_tile<RB, kSplit>(dacc, tr_hi, tr_lo, i, kg);
+        contract_tokens<D, RB, kSplit>(dZacc, tr_hi, tr_lo, vh, vl, i, kg);
+        transpose_done();
+    }
+    __syncthreads();
+    sum_over_waves<D, RB>(dZacc, s_y, wave, i, kg);
+    float* zp = p.dz_part + ((size_t)pair * p.chunks + chunk) * 64 * D;
+    for (int e = tid; e < 32 * RB * D; e += kThreads) zp[e] = s_y[e];
+}
+
+// ---------------------------------------------------------------------------------------------
+// final: dZ[h][t][c] and dbeta[h][t], summed over chunks, sides and the batch in index order
+// ---------------------------------------------------------------------------------------------
+__global__ void bt_final(BtParams p, int D)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (h, t, c), c == D meaning beta
+    const int per = p.r * (D + 1);
+    if (idx >= p.H * per) return;
+    const int h = idx / per, t = (idx % per) / (D + 1), c = idx % (D + 1);
+    float acc = 0.f;
+    for (int b = 0; b < p.B; ++b) {
+        const int g = b * p.H + h;
+        if (c < D) {
+            for (int side = 0; side < 2; ++side)
+                for (int ch = 0; ch < p.chunks; ++ch)
+                    acc += p.dz_part[(((size_t)(side * p.G + g)) * p.chunks + ch) * 64 * D + t * D + c];
+        } else {
+            acc += p.db_glue[g * 64 + t];
+            acc += p.db_pair[(size_t)g * 64 + t];
+            acc += p.db_pair[(size_t)(p.G + g) * 64 + t];
+        }
+    }
+    if (c < D) p.dZ[((size_t)h * p.r + t) * D + c] = acc;
+    else p.dbeta[h * p.r + t] = acc;
+}
+
+__global__ void bt_clear(unsigned long long* p, size_t count)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < count) p[idx] = 0ull;
+}
+
+template <typename IO, int D, int RB>
+int launch_all(const BwdArgs& a, BtParams p)
+{
+    const lot_shape& s = a.s;
+    const int pairs = 2 * p.G, T = a.iters, R = 32 * RB;
+    hipStream_t st = a.stream;
+    const size_t words = (size_t)(T + 1) * pairs * 64;
+    bt_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words);
+    const unsigned grid = (unsigned)pairs * p.chunks;
+    for (int k = 1; k <= T; ++k) {
+        p.k = k;
+        if (k < T) bt_forward<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
+        else bt_forward<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);
+    }
+    bt_mid<D><<<p.G, 256, 0, st>>>(p);
+    bt_glue<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
+    bt_gram_reduce<<<(unsigned)T * pairs, 256, 0, st>>>(p, R * R);
+    bt_recursion<<<pairs, 64, 0, st>>>(p, R);
+    const size_t dyn = (size_t)T * 2 * 64 * sizeof(float);
+    bt_assemble<IO, D, RB><<<grid, kThreads, dyn, st>>>(p, T);
+    bt_final<<<(unsigned)((s.H * s.r * (D + 1) + 255) / 256), 256, 0, st>>>(p, D);
+    LOT_HIP_CHECK(hipGetLastError());
+    return LOT_OK;
+}
+
+}  // namespace
+
+bool bwd_tiled_supports(const lot_shape& s, int iters)
+{
+    // the assemble kernel keeps the potentials and column-sum adjoints of all iterations in LDS
+    return fused_supports(s) && iters <= 32;
+}
+
+BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters)
+{
+    BwdTiledWorkspace w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off += (bytes + 255) / 256 * 256; return at; };
+    const size_t G = (size_t)s.B * s.H, pairs = 2 * G, T = iters, D = s.d_k;
+    const size_t ntiles = ((size_t)s.n + kTileTokens - 1) / kTileTokens;
+    const size_t chunks = (ntiles + kTilesPerWg - 1) / kTilesPerWg;
+    const size_t R = s.r <= 32 ? 32 : 64;
+    w.chunks = (int)chunks;
+    w.colacc = take((T + 1) * pairs * 64 * 8);
+    w.ghist = take((T + 1) * pairs * 64 * 4);
+    w.gram_part = take(T * pairs * chunks * R * R * 4);
+    w.gram_full = take(T * pairs * R * R * 4);
+    w.u_part = take(pairs * chunks * 64 * D * 4);
+    w.yp = take(G * 64 * D * 4);
+    w.dyraw = take(G * 64 * D * 4);
+    w.sn_part = take(pairs * chunks * 2 * 64 * 4);
+    w.dcs = take((T + 1) * pairs * 64 * 4);
+    w.rhop = take(pairs * 64 * 4);
+    w.db_pair = take(pairs * 64 * 4);
+    w.db_glue = take(G * 64 * 4);
+    w.dz_part = take(pairs * chunks * 64 * D * 4);
+    w.total = off;
+    return w;
+}
+
+int run_backward_tiled(const BwdArgs& a)
+{
+    const lot_shape& s = a.s;
+    if (!bwd_tiled_supports(s, a.iters)) return LOT_ERR_PATH;
+    const BwdTiledWorkspace L = carve_bwd_tiled(s, a.iters);
+    BtParams p{};
+    p.Q = a.Q; p.K = a.K; p.V = a.V; p.dO = a.dO; p.Z = a.Z; p.beta = a.beta;
+    p.dQ = a.dQ; p.dK = a.dK; p.dV = a.dV; p.dZ = a.dZ; p.dbeta = a.dbeta;
+    p.colacc = (unsigned long long*)(a.ws + L.colacc);
+    p.ghist = (float*)(a.ws + L.ghist);
+    p.gram_part = (float*)(a.ws + L.gram_part);
+    p.gram_full = (float*)(a.ws + L.gram_full);
+    p.u_part = (float*)(a.ws + L.u_part);
+    p.yp = (float*)(a.ws + L.yp);
+    p.dyraw = (float*)(a.ws + L.dyraw);
+    p.sn_part = (float*)(a.ws + L.sn_part);
+    p.dcs = (float*)(a.ws + L.dcs);
+    p.rhop = (float*)(a.ws + L.rhop);
+    p.db_pair = (float*)(a.ws + L.db_pair);
+    p.db_glue = (float*)(a.ws + L.db_glue);
+    p.dz_part = (float*)(a.ws + L.dz_part);
+    p.G = s.B * s.H; p.H = s.H; p.B = s.B; p.n = s.n; p.r = s.r; p.chunks = L.chunks; p.T = a.iters;
+    p.eps = a.eps;
+    {
+        // column sums of a row-normalised kernel are at most n: 2^(62 - ceil(log2(n + 1))) never overflows
+        int frac = 62 - (int)std::ceil(std::log2((double)s.n + 1.0));
+        if (frac > 40) frac = 40;
+        p.fx_scale = std::ldexp(1.0f, frac);
+        p.fx_unscale = std::ldexp(1.0f, -frac);
+    }
+    const bool bf16 = s.io_dtype == LOT_BF16;
+    const int D = s.d_k, RB = s.r <= 32 ? 1 : 2;
+    if (bf16) {
+        if (D == 64) return RB == 2 ? launch_all<uint16_t, 64, 2>(a, p) : launch_all<uint16_t, 64, 1>(a, p);
+        return RB == 2 ? launch_all<uint16_t, 32, 2>(a, p) : launch_all<uint16_t, 32, 1>(a, p);
+    }
+    if (D == 64) return RB == 2 ? launch_all<float, 64, 2>(a, p) : launch_all<float, 64, 1>(a, p);
+    return RB == 2 ? launch_all<float, 32, 2>(a, p) : launch_all<float, 32, 1>(a, p);
+}
+
+}  // namespace lot

@@ -137,10 +137,20 @@ struct BwdArgs {
     hipStream_t stream;
 };
 
+// Workspace of the backward pass, tiled path.
+struct BwdTiledWorkspace {
+    size_t colacc, ghist, gram_part, gram_full, u_part, yp, dyraw, sn_part, dcs, rhop, db_pair, db_glue, dz_part;
+    size_t total;
+    int chunks;
+};
+bool bwd_tiled_supports(const lot_shape& s, int iters);
+BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters);
+
 // Each returns LOT_OK or LOT_ERR_HIP (the failing hipError_t is left in last_hip_error()).
 int run_reference(const Args& a, bool want_out);
 int run_fused(const Args& a, bool want_out);
 int run_backward(const BwdArgs& a);
+int run_backward_tiled(const BwdArgs& a);   // LOT_ERR_PATH when the shape is outside its set
 
 hipError_t& last_hip_error();
 

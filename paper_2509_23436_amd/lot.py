@@ -17,7 +17,7 @@ LOT_F32, LOT_BF16 = 0, 1
 PATH_AUTO, PATH_REFERENCE, PATH_FUSED = 0, 1, 2
 
 EXPORTS = ("lot_workspace_bytes", "lot_attention_fwd", "lot_couplings", "lot_attention_fwd_path",
-           "lot_couplings_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd",
+           "lot_couplings_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
            "lot_workspace_status", "lot_strerror", "lot_version")
 
 
@@ -153,7 +153,7 @@ def lot_attention_bwd_workspace_bytes(shape: lot_shape, iters: int) -> int:
     return out.value
 
 
-def lot_attention_bwd(Q, K, V, Z, beta, eps, iters, dO, workspace=None):
+def lot_attention_bwd(Q, K, V, Z, beta, eps, iters, dO, workspace=None, path=PATH_AUTO):
     """(dQ, dK, dV, dZ, dbeta) of <LOTAttn(Q, K, V), dO>; dZ and dbeta are summed over the batch."""
     for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
         _require(t, nm, Q.dtype)
@@ -168,8 +168,8 @@ def lot_attention_bwd(Q, K, V, Z, beta, eps, iters, dO, workspace=None):
     _require(workspace, "workspace", torch.uint8)
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
     dZ, dbeta = torch.empty_like(Z), torch.empty_like(beta)
-    _check(lib().lot_attention_bwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
-                                   ctypes.c_float(eps), int(iters), _ptr(dO),
-                                   _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dZ), _ptr(dbeta),
-                                   _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
+    _check(lib().lot_attention_bwd_path(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
+                                        ctypes.c_float(eps), int(iters), _ptr(dO),
+                                        _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dZ), _ptr(dbeta),
+                                        _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(), int(path)))
     return dQ, dK, dV, dZ, dbeta

@@ -37,13 +37,19 @@ def _say(msg):
     print(msg, flush=True)
 
 
-@pytest.mark.parametrize("name", list(CASES))
-def test_backward_matches_oracle(name):
+def _paths_for(w):
+    tiled = w.d in (32, 64) and w.r <= 64 and w.iters <= 32
+    return ["reference", "fused"] if tiled else ["reference"]
+
+
+@pytest.mark.parametrize("name,path_name", [(nm, pn) for nm in CASES for pn in _paths_for(CASES[nm])])
+def test_backward_matches_oracle(name, path_name):
     import torch
     from oracle import lot_oracle_bwd
     from paper_2509_23436_amd import lot
+    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED}[path_name]
     w = CASES[name]
-    _say("case %s: %r" % (name, w))
+    _say("case %s path %s: %r" % (name, path_name, w))
     x = synth.make_inputs(w)
     rng = np.random.default_rng(w.seed + 17)
     dO = rng.standard_normal(x["V"].shape).astype(np.float32)
@@ -52,7 +58,8 @@ def test_backward_matches_oracle(name):
     (dQ_r, dK_r, dV_r, dZ_r, db_r), _ = lot_oracle_bwd.attention_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"],
                                                                      w.eps, w.iters, dO)
     dev = to_device(dict(x, dO=dO), w.dtype)
-    got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, dev["dO"])
+    got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, dev["dO"],
+                                path=path)
     torch.cuda.synchronize()
     tol = 2e-2 if w.dtype == "bf16" else 1e-4
     for nm, g, ref in zip(("dQ", "dK", "dV", "dZ", "dbeta"), got, (dQ_r, dK_r, dV_r, dZ_r, db_r)):
