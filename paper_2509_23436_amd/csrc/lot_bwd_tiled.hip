@@ -36,8 +36,21 @@ namespace {
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
-constexpr int kTilesPerWave = 4;
-constexpr int kTilesPerWg = kWaves * kTilesPerWave;
+constexpr int kTargetWgs = 512;     // two workgroups of four wavefronts on each of 256 CUs
+
+// Tiles per workgroup: enough workgroups to fill the device once (set-up and the cross-wavefront
+// reductions at the end of a workgroup are amortised over more tiles, and fewer partial results go
+// through memory), a multiple of the wavefront count, between one and sixteen tiles per wavefront.
+inline int tiles_per_wg_for(const lot_shape& s)
+{
+    const long long ntiles = ((long long)s.n + kTileTokens - 1) / kTileTokens;
+    const long long pairs = 2LL * s.B * s.H;
+    long long per = (ntiles * pairs + kTargetWgs - 1) / kTargetWgs;
+    per = (per + kWaves - 1) / kWaves * kWaves;
+    if (per < kWaves) per = kWaves;
+    if (per > 16 * kWaves) per = 16 * kWaves;
+    return (int)per;
+}
 
 struct BtParams {
     const void* Q; const void* K; const void* V; const void* dO;
@@ -57,7 +70,7 @@ struct BtParams {
     float* db_pair;               // [pairs][64]
     float* db_glue;               // [G][64]
     float* dz_part;               // [pairs][chunks][64][D]
-    int G, H, B, n, r, chunks, k, T;
+    int G, H, B, n, r, chunks, tiles_per_wg, k, T;
     float eps, fx_scale, fx_unscale;
 };
 
@@ -325,7 +338,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
     __syncthreads();
 
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
-    const int tile_begin = chunk * kTilesPerWg, tile_end = min(ntiles, tile_begin + kTilesPerWg);
+    const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
     f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
 #pragma unroll
     for (int mb = 0; mb < RB; ++mb) {
@@ -434,44 +447,51 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
 
 // ---------------------------------------------------------------------------------------------
 // mid: Y'_t = U_t / cs2_t, dYraw_t = n Wd_t / cs1_t, db_glue_t = -<dYraw_t, Y'_t>, rho'_t = beta_t / cs_t
-// one workgroup per problem, thread = (t, column)
 // ---------------------------------------------------------------------------------------------
+// stage 1: one thread per (g, t, column): sums the per-chunk contractions in chunk order
 template <int D>
 __global__ void bt_mid(BtParams p)
 {
-    const int g = blockIdx.x, h = g % p.H, pairs = 2 * p.G, T = p.T;
-    const int tid = threadIdx.x;
-    for (int e = tid; e < 64 * D; e += blockDim.x) {
-        const int t = e / D;
-        float y = 0.f, dy = 0.f;
-        if (t < p.r) {
-            float u = 0.f, wd = 0.f;
-            for (int c = 0; c < p.chunks; ++c) {
-                wd += p.u_part[((size_t)(0 * p.G + g) * p.chunks + c) * 64 * D + e];
-                u += p.u_part[((size_t)(1 * p.G + g) * p.chunks + c) * 64 * D + e];
-            }
-            const float cs1 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
-            const float cs2 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
-            y = u / cs2;
-            dy = (float)p.n * wd / cs1;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= p.G * 64 * D) return;
+    const int g = idx / (64 * D), e = idx % (64 * D), t = e / D;
+    const int pairs = 2 * p.G, T = p.T;
+    float y = 0.f, dy = 0.f;
+    if (t < p.r) {
+        float u0 = 0.f, u1 = 0.f, w0 = 0.f, w1 = 0.f;     // two interleaved chains each: the loads overlap
+        const float* wp = p.u_part + ((size_t)(0 * p.G + g) * p.chunks) * 64 * D + e;
+        const float* up = p.u_part + ((size_t)(1 * p.G + g) * p.chunks) * 64 * D + e;
+        int c = 0;
+        for (; c + 1 < p.chunks; c += 2) {
+            w0 += wp[(size_t)c * 64 * D]; w1 += wp[(size_t)(c + 1) * 64 * D];
+            u0 += up[(size_t)c * 64 * D]; u1 += up[(size_t)(c + 1) * 64 * D];
         }
-        p.yp[(size_t)g * 64 * D + e] = y;
-        p.dyraw[(size_t)g * 64 * D + e] = dy;
+        if (c < p.chunks) { w0 += wp[(size_t)c * 64 * D]; u0 += up[(size_t)c * 64 * D]; }
+        const float cs1 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
+        const float cs2 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
+        y = (u0 + u1) / cs2;
+        dy = (float)p.n * (w0 + w1) / cs1;
     }
-    __syncthreads();
-    if (tid < 64) {
-        const int t = tid;
-        float dot = 0.f, r1 = 0.f, r2 = 0.f;
-        if (t < p.r) {
-            for (int c = 0; c < D; ++c) dot = fmaf(p.dyraw[(size_t)g * 64 * D + t * D + c], p.yp[(size_t)g * 64 * D + t * D + c], dot);
-            const float b = p.beta[h * p.r + t];
-            r1 = b / fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
-            r2 = b / fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
-        }
-        p.db_glue[g * 64 + t] = -dot;
-        p.rhop[(size_t)g * 64 + t] = r1;
-        p.rhop[(size_t)(p.G + g) * 64 + t] = r2;
+    p.yp[idx] = y;
+    p.dyraw[idx] = dy;
+}
+// stage 2: one thread per (g, t)
+template <int D>
+__global__ void bt_mid2(BtParams p)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= p.G * 64) return;
+    const int g = idx / 64, t = idx % 64, h = g % p.H, pairs = 2 * p.G, T = p.T;
+    float dot = 0.f, r1 = 0.f, r2 = 0.f;
+    if (t < p.r) {
+        for (int c = 0; c < D; ++c) dot = fmaf(p.dyraw[(size_t)idx * D + c], p.yp[(size_t)idx * D + c], dot);
+        const float b = p.beta[h * p.r + t];
+        r1 = b / fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
+        r2 = b / fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
     }
+    p.db_glue[idx] = -dot;
+    p.rhop[(size_t)g * 64 + t] = r1;
+    p.rhop[(size_t)(p.G + g) * 64 + t] = r2;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -539,7 +559,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
     __syncthreads();
 
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
-    const int tile_begin = chunk * kTilesPerWg, tile_end = min(ntiles, tile_begin + kTilesPerWg);
+    const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
     f32x16 sacc[RB], nacc[RB];
 #pragma unroll
     for (int mb = 0; mb < RB; ++mb)
@@ -625,14 +645,21 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
 // ---------------------------------------------------------------------------------------------
 // Gram reduce: gram_full[k][pair] = sum over chunks (index order)
 // ---------------------------------------------------------------------------------------------
-__global__ void bt_gram_reduce(BtParams p, int R2)
+__global__ void bt_gram_reduce(BtParams p, int R2, size_t total)
 {
-    const size_t kp = blockIdx.x;     // (k-1) * pairs + pair
-    for (int e = threadIdx.x; e < R2; e += blockDim.x) {
-        float acc = 0.f;
-        for (int c = 0; c < p.chunks; ++c) acc += p.gram_part[(kp * p.chunks + c) * R2 + e];
-        p.gram_full[kp * R2 + e] = acc;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;    // (kp, e)
+    if (idx >= total) return;
+    const size_t kp = idx / R2;
+    const int e = (int)(idx % R2);
+    const float* src = p.gram_part + kp * p.chunks * R2 + e;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int c = 0;
+    for (; c + 3 < p.chunks; c += 4) {
+        a0 += src[(size_t)c * R2]; a1 += src[(size_t)(c + 1) * R2];
+        a2 += src[(size_t)(c + 2) * R2]; a3 += src[(size_t)(c + 3) * R2];
     }
+    for (; c < p.chunks; ++c) a0 += src[(size_t)c * R2];
+    p.gram_full[idx] = (a0 + a1) + (a2 + a3);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -659,8 +686,10 @@ __global__ void bt_recursion(BtParams p, int R)
         __syncthreads();
         float acc = 0.f;
         if (live && t < R) {
-            const float* row = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + (size_t)t * R;
-            for (int u = 0; u < R; ++u) acc = fmaf(row[u], s_v[u], acc);
+            // M^k is symmetric: thread t walks column t, so that a wavefront reads whole rows
+            const float* col = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + t;
+#pragma unroll 16
+            for (int u = 0; u < R; ++u) acc = fmaf(col[(size_t)u * R], s_v[u], acc);
         }
         __syncthreads();
         return acc;
@@ -689,8 +718,9 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
     extern __shared__ __attribute__((aligned(16))) char s_dyn[];   // [Tcap][2][64] floats: g^{k-1} c1, dc^k
     __shared__ float s_rho[64];
     __shared__ __attribute__((aligned(16))) float s_y[64 * D];
+    constexpr int kParts = kSplit ? 2 : 1;     // bf16 hi only, or hi and lo
     __shared__ __attribute__((aligned(16))) bf16x8 s_zf[2][2 * RB * NB * 64];
-    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * 2 * 64 * kTrStride];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 64 * kTrStride];
     __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
     __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
     float* s_hist = reinterpret_cast<float*>(s_dyn);
@@ -707,8 +737,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
     const float* ymat = (side == 0 ? p.yp : p.dyraw) + (size_t)g * 64 * D;
     const float yscale = side == 0 ? (float)n : 1.f;
-    uint16_t* tr_hi = s_tr + (wave * 2 + 0) * 64 * kTrStride;
-    uint16_t* tr_lo = s_tr + (wave * 2 + 1) * 64 * kTrStride;
+    uint16_t* tr_hi = s_tr + (wave * kParts + 0) * 64 * kTrStride;
+    uint16_t* tr_lo = s_tr + (wave * kParts + kParts - 1) * 64 * kTrStride;
 
     for (int e = tid; e < T * 64; e += kThreads) {
         const int k = e / 64 + 1, t = e % 64;
@@ -746,7 +776,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
     __syncthreads();   // s_y is reused below for the dZ partial
 
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
-    const int tile_begin = chunk * kTilesPerWg, tile_end = min(ntiles, tile_begin + kTilesPerWg);
+    const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
     f32x16 dZacc[RB][NB];
 #pragma unroll
     for (int mb = 0; mb < RB; ++mb)
@@ -780,28 +810,11 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
 #pragma unroll
             for (int j = 0; j < 16; ++j) sc[mb][j] *= c1;
 
-        for (int k = T; k >= 1; --k) {
-            f32x16 e[RB], dp[RB];
-            load_pivot_vector<RB>(e, s_hist + ((k - 1) * 2 + 0) * 64 + skew, kg);
-            load_pivot_vector<RB>(dp, s_hist + ((k - 1) * 2 + 1) * 64 + skew, kg);
-            if (k == T) {
-                // dP^T = dGamma rho' n... : dGamma_it rho_t with rho_t = beta_t / c^T_t = n rho'_t
-                f32x16 dgam[RB], rho[RB];
-#pragma unroll
-                for (int mb = 0; mb < RB; ++mb)
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) dgam[mb][j] = 0.f;
-                {
-                    Frag<IO, D> yfrag[RB];
-                    fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
-                    similarity<D, RB>(dgam, yfrag, vc);
-                }
-                load_pivot_vector<RB>(rho, s_rho + skew, kg);
-#pragma unroll
-                for (int mb = 0; mb < RB; ++mb)
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) dp[mb][j] = fmaf(dgam[mb][j] * (float)n, rho[mb][j], dp[mb][j]);
-            }
+        // one iteration's share: dacc += W^k (dP - e_i), with W^k rebuilt from the scaled similarities
+        // and that iteration's potentials (pot, LDS, already times c1)
+        auto add_iteration = [&](const float* pot, f32x16 (&dp)[RB]) {
+            f32x16 e[RB];
+            load_pivot_vector<RB>(e, pot + skew, kg);
             float m0 = -INFINITY, m1 = -INFINITY;
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
@@ -836,6 +849,34 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(e[mb][j] * w, dp[mb][j] - ei, dacc[mb][j]);
+        };
+        {
+            // last iteration: dP^T = dGamma rho + dc^T with rho_t = beta_t / c^T_t = n rho'_t
+            f32x16 dp[RB];
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) dp[mb][j] = 0.f;
+            {
+                Frag<IO, D> yfrag[RB];
+                fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
+                similarity<D, RB>(dp, yfrag, vc);                 // dGamma tile
+            }
+            {
+                f32x16 rho[RB], dc[RB];
+                load_pivot_vector<RB>(rho, s_rho + skew, kg);
+                load_pivot_vector<RB>(dc, s_hist + ((T - 1) * 2 + 1) * 64 + skew, kg);
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) dp[mb][j] = fmaf(dp[mb][j] * (float)n, rho[mb][j], dc[mb][j]);
+            }
+            add_iteration(s_hist + ((T - 1) * 2 + 0) * 64, dp);
+        }
+        for (int k = T - 1; k >= 1; --k) {
+            f32x16 dp[RB];
+            load_pivot_vector<RB>(dp, s_hist + ((k - 1) * 2 + 1) * 64 + skew, kg);
+            add_iteration(s_hist + ((k - 1) * 2 + 0) * 64, dp);
         }
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
@@ -885,9 +926,17 @@ __global__ void bt_final(BtParams p, int D)
     for (int b = 0; b < p.B; ++b) {
         const int g = b * p.H + h;
         if (c < D) {
-            for (int side = 0; side < 2; ++side)
-                for (int ch = 0; ch < p.chunks; ++ch)
-                    acc += p.dz_part[(((size_t)(side * p.G + g)) * p.chunks + ch) * 64 * D + t * D + c];
+            for (int side = 0; side < 2; ++side) {
+                const float* src = p.dz_part + ((size_t)(side * p.G + g) * p.chunks) * 64 * D + t * D + c;
+                float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+                int ch = 0;
+                for (; ch + 3 < p.chunks; ch += 4) {
+                    a0 += src[(size_t)ch * 64 * D]; a1 += src[(size_t)(ch + 1) * 64 * D];
+                    a2 += src[(size_t)(ch + 2) * 64 * D]; a3 += src[(size_t)(ch + 3) * 64 * D];
+                }
+                for (; ch < p.chunks; ++ch) a0 += src[(size_t)ch * 64 * D];
+                acc += (a0 + a1) + (a2 + a3);
+            }
         } else {
             acc += p.db_glue[g * 64 + t];
             acc += p.db_pair[(size_t)g * 64 + t];
@@ -918,9 +967,13 @@ int launch_all(const BwdArgs& a, BtParams p)
         if (k < T) bt_forward<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
         else bt_forward<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);
     }
-    bt_mid<D><<<p.G, 256, 0, st>>>(p);
+    bt_mid<D><<<(unsigned)((p.G * 64 * D + 255) / 256), 256, 0, st>>>(p);
+    bt_mid2<D><<<(unsigned)((p.G * 64 + 255) / 256), 256, 0, st>>>(p);
     bt_glue<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
-    bt_gram_reduce<<<(unsigned)T * pairs, 256, 0, st>>>(p, R * R);
+    {
+        const size_t total = (size_t)T * pairs * R * R;
+        bt_gram_reduce<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(p, R * R, total);
+    }
     bt_recursion<<<pairs, 64, 0, st>>>(p, R);
     const size_t dyn = (size_t)T * 2 * 64 * sizeof(float);
     bt_assemble<IO, D, RB><<<grid, kThreads, dyn, st>>>(p, T);
@@ -944,7 +997,8 @@ BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters)
     auto take = [&](size_t bytes) { size_t at = off; off += (bytes + 255) / 256 * 256; return at; };
     const size_t G = (size_t)s.B * s.H, pairs = 2 * G, T = iters, D = s.d_k;
     const size_t ntiles = ((size_t)s.n + kTileTokens - 1) / kTileTokens;
-    const size_t chunks = (ntiles + kTilesPerWg - 1) / kTilesPerWg;
+    const size_t per_wg = (size_t)tiles_per_wg_for(s);
+    const size_t chunks = (ntiles + per_wg - 1) / per_wg;
     const size_t R = s.r <= 32 ? 32 : 64;
     w.chunks = (int)chunks;
     w.colacc = take((T + 1) * pairs * 64 * 8);
@@ -985,7 +1039,7 @@ int run_backward_tiled(const BwdArgs& a)
     p.db_pair = (float*)(a.ws + L.db_pair);
     p.db_glue = (float*)(a.ws + L.db_glue);
     p.dz_part = (float*)(a.ws + L.dz_part);
-    p.G = s.B * s.H; p.H = s.H; p.B = s.B; p.n = s.n; p.r = s.r; p.chunks = L.chunks; p.T = a.iters;
+    p.G = s.B * s.H; p.H = s.H; p.B = s.B; p.n = s.n; p.r = s.r; p.chunks = L.chunks; p.tiles_per_wg = tiles_per_wg_for(s); p.T = a.iters;
     p.eps = a.eps;
     {
         // column sums of a row-normalised kernel are at most n: 2^(62 - ceil(log2(n + 1))) never overflows
