@@ -42,6 +42,15 @@ def algorithmic_bytes(w) -> int:
     return per_head_token * w.G * w.n
 
 
+def backward_algorithmic_bytes(w) -> int:
+    """Pass-streaming model of lot_attention_bwd (tiled path): T forward passes over Q and K, the
+    last one also reading V and dO; the glue pass reads Q, K, V, dO and writes dV; the assembly reads
+    Q, K, V, dO and writes dQ, dK (its second read of Q and K, for dZ, comes from cache)."""
+    s = 2 if w.dtype == "bf16" else 4
+    per_head_token = (2 * w.iters + 2 + 5 + 6) * w.d * s
+    return per_head_token * w.G * w.n
+
+
 def compulsory_bytes(w) -> int:
     s = 2 if w.dtype == "bf16" else 4
     return 4 * w.d * s * w.G * w.n
@@ -56,6 +65,8 @@ def main() -> int:
     ap.add_argument("--rotate", type=int, default=8)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--warm-too", action="store_true", help="also time calls on one fixed set of buffers")
+    ap.add_argument("--bwd-steps", type=int, default=50,
+                    help="timed calls of the backward pass (reported beside the headline; 0 skips it)")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "reference"])
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB ten times "
@@ -166,6 +177,36 @@ def main() -> int:
                      "algorithmic_bytes": m1, "compulsory_bytes": compulsory_bytes(w),
                      "compulsory_frac": compulsory_bytes(w) / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+
+    if args.bwd_steps > 0:
+        # backward pass on the same rotating inputs (separate, larger workspace)
+        dOs = [torch.randn_like(sets[k]["V"]) for k in range(rotate)]
+        ws_b = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape, w.iters), dtype=torch.uint8, device="cuda")
+
+        def bstep(k):
+            s_ = sets[k % rotate]
+            lot.lot_attention_bwd(s_["Q"], s_["K"], s_["V"], s_["Z"], s_["beta"], w.eps, w.iters, dOs[k % rotate],
+                                  workspace=ws_b)
+
+        for k in range(3):
+            bstep(k)
+        torch.cuda.synchronize()
+        b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        b0.record()
+        for k in range(args.bwd_steps):
+            bstep(k)
+        b1.record()
+        torch.cuda.synchronize()
+        bwd_ms = b0.elapsed_time(b1) / args.bwd_steps
+        mb = backward_algorithmic_bytes(w)
+        result["backward"] = {"ms_per_step": bwd_ms, "steps": args.bwd_steps,
+                              "tokens_per_s": w.tokens / (bwd_ms * 1e-3),
+                              "ratio_to_forward": bwd_ms / kernel_ms,
+                              "roofline": {"bound": "hbm", "achieved": mb / (bwd_ms * 1e-3) / 1e9,
+                                           "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                           "frac": mb / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                           "algorithmic_bytes": mb}}
+        del dOs, ws_b
 
     if not args.no_cpu:
         from oracle import lot_oracle

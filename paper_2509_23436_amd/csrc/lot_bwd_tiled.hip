@@ -391,10 +391,12 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
                 acc[mb][j] *= w;
                 cs[mb][j] += acc[mb][j];
             }
+#ifndef BT_NO_GRAM
         transpose_tile<RB, kSplit>(acc, tr_hi, tr_lo, i, kg);
         contract_gram<RB, kSplit>(Gm, tr_hi, tr_lo, i, kg);
         if (WITH_U) contract_tokens<D, RB, kSplit>(U, tr_hi, tr_lo, vh, vl, i, kg);
         transpose_done();
+#endif
         xc = xn;
     }
 

@@ -96,3 +96,77 @@ def test_backward_runs_are_bit_identical_and_ignore_workspace_contents():
         for a, b in zip(outs[0], other):
             assert torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
                                b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
+
+
+# Full benchmark sizes: the library runs the WHOLE workload (launch configuration of the benchmark);
+# the float64 oracle differentiates a sample of the (batch, head) problems one by one.  A problem's
+# dQ, dK, dV depend on that problem alone; dZ and dbeta are sums over the batch, so for them the
+# library is run on the sampled problems only (batch of one per head) and compared in full.
+FULL = {
+    "deit_tiny": [0, 191],
+    "swin_t_s1": [0, 47],
+    "long_4k": [5],
+    "long_16k": [9],
+}
+
+
+@pytest.mark.parametrize("name", list(FULL))
+def test_backward_full_size_on_sampled_problems(name):
+    import torch
+    from oracle import lot_oracle_bwd
+    from paper_2509_23436_amd import lot
+    w = W[name]
+    _say("workload %r" % (w,))
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(w.seed + 17)
+    dO = rng.standard_normal(x["V"].shape).astype(np.float32)
+    if w.dtype == "bf16":
+        dO = synth.round_to_bf16(dO)
+    dev = to_device(dict(x, dO=dO), w.dtype)
+    got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, dev["dO"])
+    torch.cuda.synchronize()
+    tol = 2e-2 if w.dtype == "bf16" else 1e-4
+    for nm, g in zip(("dQ", "dK", "dV", "dZ", "dbeta"), got):
+        assert torch.isfinite(g.float()).all(), nm
+    for gi in FULL[name]:
+        b, h = gi // w.H, gi % w.H
+        sl = lambda t: np.ascontiguousarray(t[b:b + 1, h:h + 1])           # noqa: E731
+        (dQ_r, dK_r, dV_r, dZ_r, db_r), _ = lot_oracle_bwd.attention_bwd(
+            sl(x["Q"]), sl(x["K"]), sl(x["V"]), x["Z"][h:h + 1], x["beta"][h:h + 1], w.eps, w.iters, sl(dO))
+        for nm, g, ref in zip(("dQ", "dK", "dV"), got[:3], (dQ_r, dK_r, dV_r)):
+            err = rel_max_err(to_host_f64(g[b:b + 1, h:h + 1]), ref)
+            _say("  problem %d %-5s max-norm rel err %.3e (bar %.0e)" % (gi, nm, err, tol))
+            assert err <= tol, nm
+        one = {k: dev[k][b:b + 1, h:h + 1].contiguous() for k in ("Q", "K", "V", "dO")}
+        g1 = lot.lot_attention_bwd(one["Q"], one["K"], one["V"], dev["Z"][h:h + 1].contiguous(),
+                                   dev["beta"][h:h + 1].contiguous(), w.eps, w.iters, one["dO"])
+        torch.cuda.synchronize()
+        for nm, g, ref in zip(("dZ", "dbeta"), g1[3:], (dZ_r, db_r)):
+            err = rel_max_err(to_host_f64(g), ref)
+            _say("  problem %d %-5s max-norm rel err %.3e (bar %.0e)" % (gi, nm, err, tol))
+            assert err <= tol, nm
+
+
+@pytest.mark.parametrize("path_name", ["reference", "fused"])
+def test_backward_paths_are_bit_identical_run_to_run(path_name):
+    import torch
+    from paper_2509_23436_amd import lot
+    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED}[path_name]
+    w = S(W["long_4k"], B=2, H=4, n=3000, iters=6, seed=77)
+    x = synth.make_inputs(w)
+    dO = synth.round_to_bf16(np.random.default_rng(5).standard_normal(x["V"].shape).astype(np.float32))
+    dev = to_device(dict(x, dO=dO), w.dtype)
+    shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
+    ws = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape, w.iters), dtype=torch.uint8, device="cuda")
+    first = None
+    for fill in (0x00, 0xFF, 0x77):
+        ws.fill_(fill)
+        got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, dev["dO"],
+                                    workspace=ws, path=path)
+        torch.cuda.synchronize()
+        bits = [g.view(torch.int16 if g.dtype == torch.bfloat16 else torch.int32).clone() for g in got]
+        if first is None:
+            first = bits
+        else:
+            for a, b in zip(first, bits):
+                assert torch.equal(a, b)
