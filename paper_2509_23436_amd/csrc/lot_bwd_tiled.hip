@@ -288,8 +288,10 @@ template <typename IO> __device__ __forceinline__ const IO* rows_of(const BtPara
 }
 
 // ---------------------------------------------------------------------------------------------
-// forward pass k: column sums and Gram matrix of W^k; at k = T also the token contraction with V
-// (keys) or dO (queries)
+// forward pass k.  WITH_U = false: column sums and Gram matrix of W^k.  WITH_U = true (run once more
+// for k = T, after the column sums of pass T are complete): the token contraction of W^T with V
+// (keys) or dO (queries) instead -- kept apart because the two sets of accumulators do not fit the
+// register file together.
 // ---------------------------------------------------------------------------------------------
 template <typename IO, int D, int RB, bool WITH_U>
 __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
@@ -314,6 +316,15 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
     const IO* X = rows_of<IO>(p, side);
     uint16_t* tr_hi = s_tr + (wave * 2 + 0) * 64 * kTrStride;
     uint16_t* tr_lo = s_tr + (wave * 2 + 1) * 64 * kTrStride;
+    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
+
+    // the first tile is requested before anything else: its latency overlaps the set-up
+    Frag<IO, D> xc;
+    {
+        const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
+        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
+    }
 
     // g^{k-1} from the column sums of the previous launch
     if (tid < 64) {
@@ -324,7 +335,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
             gv = p.ghist[((size_t)(k - 2) * pairs + pair) * 64 + tid] + p.eps * logf((float)n * p.beta[h * r + tid] / cs);
         }
         s_g[tid] = gv;
-        if (chunk == 0) p.ghist[((size_t)(k - 1) * pairs + pair) * 64 + tid] = gv;
+        if (!WITH_U && chunk == 0) p.ghist[((size_t)(k - 1) * pairs + pair) * 64 + tid] = gv;
     }
     if (wave == 0) {
         Frag<IO, D> z0[RB];
@@ -337,8 +348,6 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
     }
     __syncthreads();
 
-    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
-    const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
     f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
 #pragma unroll
     for (int mb = 0; mb < RB; ++mb) {
@@ -355,11 +364,6 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
     }
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
 
-    Frag<IO, D> xc;
-    if (tile_begin + wave < tile_end) {
-        const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
-        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
-    }
     for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
         Frag<IO, D> xn = xc;
         if (tile + kWaves < tile_end) {
@@ -389,15 +393,19 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 acc[mb][j] *= w;
-                cs[mb][j] += acc[mb][j];
+                if (!WITH_U) cs[mb][j] += acc[mb][j];
             }
-#ifndef BT_NO_GRAM
         transpose_tile<RB, kSplit>(acc, tr_hi, tr_lo, i, kg);
-        contract_gram<RB, kSplit>(Gm, tr_hi, tr_lo, i, kg);
         if (WITH_U) contract_tokens<D, RB, kSplit>(U, tr_hi, tr_lo, vh, vl, i, kg);
+        else contract_gram<RB, kSplit>(Gm, tr_hi, tr_lo, i, kg);
         transpose_done();
-#endif
         xc = xn;
+    }
+    if (WITH_U) {
+        sum_over_waves<D, RB>(U, s_buf, wave, i, kg);
+        float* up = p.u_part + ((size_t)pair * p.chunks + chunk) * 64 * D;
+        for (int e = tid; e < R * D; e += kThreads) up[e] = s_buf[e];
+        return;
     }
 
     // column sums: one pivot per lane, then across the wavefronts, then one integer atomic per pivot
@@ -438,12 +446,6 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
             __syncthreads();
         }
         for (int e = tid; e < R * R; e += kThreads) gp[e] = s_buf[e];
-        __syncthreads();
-    }
-    if (WITH_U) {
-        sum_over_waves<D, RB>(U, s_buf, wave, i, kg);
-        float* up = p.u_part + ((size_t)pair * p.chunks + chunk) * 64 * D;
-        for (int e = tid; e < R * D; e += kThreads) up[e] = s_buf[e];
     }
 }
 
@@ -669,44 +671,50 @@ __global__ void bt_gram_reduce(BtParams p, int R2, size_t total)
 // ---------------------------------------------------------------------------------------------
 __global__ void bt_recursion(BtParams p, int R)
 {
+    // 256 threads: thread (q, t) = (tid / 64, tid % 64) sums a quarter of the products of row t;
+    // the quarters are added in a fixed order by the threads with q == 0, which carry the recursion.
     __shared__ float s_v[64];
-    const int pair = blockIdx.x, t = threadIdx.x, pairs = 2 * p.G, T = p.T;
+    __shared__ float s_q[4][64];
+    const int pair = blockIdx.x, t = threadIdx.x & 63, q = threadIdx.x >> 6, pairs = 2 * p.G, T = p.T;
     const int h = (pair % p.G) % p.H;
     const bool live = t < p.r;
     const float a = 1.f / (float)p.n;
     const float b = live ? p.beta[h * p.r + t] : 1.f;
     float s = 0.f, nn = 0.f;
-    for (int c = 0; c < p.chunks; ++c) {
-        s += p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 0) * 64 + t];
-        nn += p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 1) * 64 + t];
-    }
+    if (q == 0)
+        for (int c = 0; c < p.chunks; ++c) {
+            s += p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 0) * 64 + t];
+            nn += p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 1) * 64 + t];
+        }
     auto colsum = [&](int k) {
         return fmaxf((float)(long long)p.colacc[((size_t)k * pairs + pair) * 64 + t] * p.fx_unscale, 1.0e-37f) * a;   // c^k_t
     };
-    auto gram_times = [&](int k, float v) {      // (M^k v)_t, v given per thread
-        s_v[t] = live ? v : 0.f;
+    auto gram_times = [&](int k, float v) {      // (M^k v)_t; v is meaningful in the threads with q == 0
+        if (q == 0) s_v[t] = live ? v : 0.f;
         __syncthreads();
         float acc = 0.f;
         if (live && t < R) {
             // M^k is symmetric: thread t walks column t, so that a wavefront reads whole rows
             const float* col = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + t;
-#pragma unroll 16
-            for (int u = 0; u < R; ++u) acc = fmaf(col[(size_t)u * R], s_v[u], acc);
+            const int u0 = q * (R / 4);
+#pragma unroll 8
+            for (int u = u0; u < u0 + R / 4; ++u) acc = fmaf(col[(size_t)u * R], s_v[u], acc);
         }
+        s_q[q][t] = acc;
         __syncthreads();
-        return acc;
+        return (s_q[0][t] + s_q[1][t]) + (s_q[2][t] + s_q[3][t]);
     };
     float db = live ? s / b : 0.f;
     float dc = live ? -s / colsum(T) : 0.f;
-    p.dcs[((size_t)T * pairs + pair) * 64 + t] = dc;
+    if (q == 0) p.dcs[((size_t)T * pairs + pair) * 64 + t] = dc;
     float dg = -(nn + a * gram_times(T, dc)) / p.eps;          // dg^{T-1}
     for (int k = T - 1; k >= 1; --k) {
         dc = live ? -p.eps * dg / colsum(k) : 0.f;
         db += live ? p.eps * dg / b : 0.f;
-        p.dcs[((size_t)k * pairs + pair) * 64 + t] = dc;
+        if (q == 0) p.dcs[((size_t)k * pairs + pair) * 64 + t] = dc;
         dg = -(a / p.eps) * gram_times(k, dc);                  // dg^{k-1}
     }
-    p.db_pair[(size_t)pair * 64 + t] = live ? db : 0.f;
+    if (q == 0) p.db_pair[(size_t)pair * 64 + t] = live ? db : 0.f;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -966,9 +974,9 @@ int launch_all(const BwdArgs& a, BtParams p)
     const unsigned grid = (unsigned)pairs * p.chunks;
     for (int k = 1; k <= T; ++k) {
         p.k = k;
-        if (k < T) bt_forward<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
-        else bt_forward<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);
+        bt_forward<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
     }
+    bt_forward<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);     // k = T once more: the contractions
     bt_mid<D><<<(unsigned)((p.G * 64 * D + 255) / 256), 256, 0, st>>>(p);
     bt_mid2<D><<<(unsigned)((p.G * 64 + 255) / 256), 256, 0, st>>>(p);
     bt_glue<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
@@ -976,7 +984,7 @@ int launch_all(const BwdArgs& a, BtParams p)
         const size_t total = (size_t)T * pairs * R * R;
         bt_gram_reduce<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(p, R * R, total);
     }
-    bt_recursion<<<pairs, 64, 0, st>>>(p, R);
+    bt_recursion<<<pairs, 256, 0, st>>>(p, R);
     const size_t dyn = (size_t)T * 2 * 64 * sizeof(float);
     bt_assemble<IO, D, RB><<<grid, kThreads, dyn, st>>>(p, T);
     bt_final<<<(unsigned)((s.H * s.r * (D + 1) + 255) / 256), 256, 0, st>>>(p, D);
