@@ -176,3 +176,33 @@ def marginal_residuals(gamma1, gamma2, beta):
     tok2 = n * g2.sum(axis=-2) - 1.0
     piv2 = g2.sum(axis=-1) / b - 1.0
     return tok1, piv1, tok2, piv2
+
+
+def attention_cls(Q, K, V, Z, beta, eps, T, beta_cls, threads=1):
+    """ViT variant with a [CLS] token at index 0 (paper, "[CLS] under DS attention").
+
+    Rows 1..n-1: the doubly-stochastic LOT attention among tokens 1..n-1 only (their own queries,
+    keys and values; masses 1/(n-1)), i.e. `attention` on the views without token 0.  Row 0: a
+    standard softmax row over ALL n keys with temperature beta_cls,
+    alpha_j = exp(beta_cls <q_0, k_j>) / sum_l exp(beta_cls <q_0, k_l>), out_0 = sum_j alpha_j v_j,
+    written out below with the usual maximum subtraction.  The paper does not say how [CLS] enters as
+    a key of the other rows; the reading taken is the literal one ("DS constraints only among the
+    image tokens"): it does not.
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    B, H, n, _ = Q.shape
+    out = np.empty(V.shape, dtype=np.float64)
+    inner, _ = attention(Q[:, :, 1:], K[:, :, 1:], V[:, :, 1:], Z, beta, eps, T, threads=threads)
+    out[:, :, 1:] = inner
+    for b in range(B):
+        for h in range(H):
+            score = np.array([beta_cls * float(np.dot(Q[b, h, 0], K[b, h, j])) for j in range(n)])
+            w = np.exp(score - score.max())
+            w /= w.sum()
+            acc = np.zeros(V.shape[-1])
+            for j in range(n):
+                acc += w[j] * V[b, h, j]
+            out[b, h, 0] = acc
+    return out
