@@ -98,6 +98,22 @@ int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,
                        void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
+ * ViT variant with a [CLS] token (paper, "[CLS] under DS attention"): token 0 of every (batch, head)
+ * is [CLS].  Rows 1 .. n-1 of out are the doubly-stochastic LOT attention AMONG tokens 1 .. n-1 (their
+ * queries, keys and values only: uniform masses 1/(n-1), the same Z, beta, eps, iters); row 0 is a
+ * standard softmax row over ALL n keys, alpha_j = softmax_j(beta_cls <q_0, k_j>), out_0 = sum_j
+ * alpha_j v_j.  Same tensors, layout, workspace size (lot_workspace_bytes of the full shape) and
+ * rules as lot_attention_fwd; n >= 2, beta_cls > 0 (LOT_ERR_EPS otherwise).  The [CLS] polarisation
+ * of the paper is not part of this entry point.
+ */
+int lot_attention_cls_fwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                          const float* Z, const float* beta, float eps, int iters, float beta_cls,
+                          void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+int lot_attention_cls_fwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                               const float* Z, const float* beta, float eps, int iters, float beta_cls,
+                               void* out, void* workspace, size_t workspace_bytes, void* hip_stream, int path);
+
+/*
  * Backward pass (paper, "Learning": the pivots, their masses and the projections are trained by
  * backpropagating through both Sinkhorn problems and the glued composition).  Given dO = dL/dO of
  * the forward call with the same inputs, eps and iters, writes

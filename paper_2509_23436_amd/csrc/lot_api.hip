@@ -83,9 +83,11 @@ int lot_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out)
     return LOT_OK;
 }
 
-int lot_attention_fwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
-                           const float* Z, const float* beta, float eps, int iters, void* out,
-                           void* workspace, size_t workspace_bytes, void* hip_stream, int path)
+// Shared by the dense entry point and the [CLS] variant: n_stride = tokens between consecutive
+// problems in memory (0 = shape->n).
+static int attention_impl(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                          const float* Z, const float* beta, float eps, int iters, void* out,
+                          void* workspace, size_t workspace_bytes, void* hip_stream, int path, int n_stride)
 {
     int rc = common_checks(shape, Q, K, Z, beta, eps, iters, workspace, workspace_bytes);
     if (rc != LOT_OK) return rc;
@@ -97,6 +99,7 @@ int lot_attention_fwd_path(const lot_shape* shape, const void* Q, const void* K,
     Args a{};
     a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.out = out; a.ws = (char*)workspace; a.lay = carve(*shape); a.stream = (hipStream_t)hip_stream;
+    a.n_stride = n_stride;
     if (fused) {
         rc = run_fused(a, true);
         // AUTO falls back to the reference kernels for the (astronomical) iteration counts whose
@@ -106,6 +109,41 @@ int lot_attention_fwd_path(const lot_shape* shape, const void* Q, const void* K,
     a.gamma1 = (float*)(a.ws + a.lay.gamma1);
     a.gamma2 = (float*)(a.ws + a.lay.gamma2);
     return run_reference(a, true);
+}
+
+int lot_attention_fwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                           const float* Z, const float* beta, float eps, int iters, void* out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream, int path)
+{
+    return attention_impl(shape, Q, K, V, Z, beta, eps, iters, out, workspace, workspace_bytes, hip_stream, path, 0);
+}
+
+int lot_attention_cls_fwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                               const float* Z, const float* beta, float eps, int iters, float beta_cls,
+                               void* out, void* workspace, size_t workspace_bytes, void* hip_stream, int path)
+{
+    int rc = validate_shape(shape);
+    if (rc != LOT_OK) return rc;
+    if (shape->n < 2) return LOT_ERR_SHAPE;                    // the [CLS] token and at least one other
+    if (!(beta_cls > 0.0f) || !std::isfinite(beta_cls)) return LOT_ERR_EPS;
+    if (!Q || !K || !V || !out) return LOT_ERR_NULL;
+    // doubly-stochastic attention among tokens 1 .. n-1: the same kernels on views that skip row 0
+    lot_shape inner = *shape;
+    inner.n = shape->n - 1;
+    const size_t esz = shape->io_dtype == LOT_BF16 ? 2 : 4;
+    rc = attention_impl(&inner, (const char*)Q + shape->d_k * esz, (const char*)K + shape->d_k * esz,
+                        (const char*)V + shape->d_v * esz, Z, beta, eps, iters, (char*)out + shape->d_v * esz,
+                        workspace, workspace_bytes, hip_stream, path, shape->n);
+    if (rc != LOT_OK) return rc;
+    return run_cls_row(*shape, Q, K, V, beta_cls, out, (hipStream_t)hip_stream);
+}
+
+int lot_attention_cls_fwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                          const float* Z, const float* beta, float eps, int iters, float beta_cls,
+                          void* out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return lot_attention_cls_fwd_path(shape, Q, K, V, Z, beta, eps, iters, beta_cls, out, workspace, workspace_bytes,
+                                      hip_stream, LOT_PATH_AUTO);
 }
 
 int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,

@@ -278,7 +278,7 @@ int run_backward_t(const BwdArgs& a)
     const unsigned pr_blocks = blocks_for(slab, 256);
 
     // ---- forward, keeping the pivot potentials of every iteration
-    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, s.d_k, r,
+    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, n, s.d_k, r,
                                                          s.io_dtype == LOT_BF16);
     ref_zero<<<pr_blocks, 256, 0, st_>>>(ghist, slab);
     for (int k = 1; k <= T_; ++k) {

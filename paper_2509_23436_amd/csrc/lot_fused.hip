@@ -64,6 +64,7 @@ struct FusedParams {
     float* u_part;        // [G][cluster_cap][64][D]
     float* y_tile;        // [G][64][D]
     int G, H, n, r;
+    int n_stride;         // tokens between consecutive problems in Q, K, V, out (>= n)
     int cluster, cluster_cap, tiles_per_wg, num_items, iters, mode;
     float eps;
     float fx_scale, fx_unscale;   // 2^F and 2^-F of the fixed-point column sums
@@ -119,10 +120,10 @@ __device__ __forceinline__ void run_pass(
         Frag<IO, D> xn = xc;
         if (tile + WAVES < tile_end) {
             const int tok = min((tile + WAVES) * kTileTokens + i, n - 1);
-            load_tokens<D>(xn, X + ((size_t)g * n + tok) * D, kg);
+            load_tokens<D>(xn, X + ((size_t)g * p.n_stride + tok) * D, kg);
         } else if (Xnext != nullptr) {
             const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
-            load_tokens<D>(xn, Xnext + ((size_t)g * n + tok) * D, kg);
+            load_tokens<D>(xn, Xnext + ((size_t)g * p.n_stride + tok) * D, kg);
         }
 
         // the value rows this tile will be multiplied with are requested now and used at the end
@@ -132,7 +133,7 @@ __device__ __forceinline__ void run_pass(
             for (int s = 0; s < 2; ++s) {
                 const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
                 const int left = max(1, min(8, n - t0));
-                load_values<D>(vh[s], vl[s], V, (size_t)g * n + min(t0, n - 1), left, i);
+                load_values<D>(vh[s], vl[s], V, (size_t)g * p.n_stride + min(t0, n - 1), left, i);
             }
         }
 
@@ -250,7 +251,7 @@ __device__ __forceinline__ void run_pass(
             }
             // one address per lane and tile; the row of accumulator register j is a compile-time offset
             const int row0 = tile * kTileTokens + 4 * kg;
-            IO* const lane_base = out + ((size_t)g * n + row0) * D;
+            IO* const lane_base = out + ((size_t)g * p.n_stride + row0) * D;
             if ((tile + 1) * kTileTokens <= n) {   // whole tile in range: no per-row test
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
@@ -356,7 +357,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         Frag<IO, D> xfirst;
         {
             const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
-            load_tokens<D>(xfirst, Xs[0] + ((size_t)g * n + tok) * D, kg);
+            load_tokens<D>(xfirst, Xs[0] + ((size_t)g * p.n_stride + tok) * D, kg);
         }
         // (beta is requested together with the pivots: one wait for both, not two round trips)
         const float beta_read = as_global(beta)[min(tid & 63, r - 1)];   // unconditional: issued with the loads around it
@@ -738,7 +739,7 @@ int launch(const Args& a, bool want_out)
     p.colacc = (unsigned long long*)(a.ws + a.lay.colacc);
     p.u_part = (float*)(a.ws + a.lay.u_part);
     p.y_tile = (float*)(a.ws + a.lay.y_tile);
-    p.G = G; p.H = s.H; p.n = s.n; p.r = s.r;
+    p.G = G; p.H = s.H; p.n = s.n; p.r = s.r; p.n_stride = a.n_stride > 0 ? a.n_stride : s.n;
     p.cluster = cluster; p.cluster_cap = fused_cluster_bound(s); p.tiles_per_wg = tiles_per_wg;
     p.num_items = G * cluster; p.iters = a.iters; p.mode = want_out ? MODE_ATTENTION : MODE_COUPLINGS;
     p.eps = a.eps;

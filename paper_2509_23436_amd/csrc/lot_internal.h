@@ -103,6 +103,7 @@ struct Args {
     char* ws;
     Workspace lay;
     hipStream_t stream;
+    int n_stride;        // tokens between consecutive problems in Q, K, V, out; 0 = dense (s.n)
 };
 
 // Workspace of the backward pass (plain path): byte offsets, multiples of 256.
@@ -150,7 +151,10 @@ BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters);
 int run_reference(const Args& a, bool want_out);
 int run_fused(const Args& a, bool want_out);
 int run_backward(const BwdArgs& a);
-int run_backward_tiled(const BwdArgs& a);   // LOT_ERR_PATH when the shape is outside its set
+int run_backward_tiled(const BwdArgs& a);
+// out[b][h][0][:] = softmax_j(beta_cls <q_0, k_j>) V, j over all n tokens of the problem
+int run_cls_row(const lot_shape& s, const void* Q, const void* K, const void* V, float beta_cls, void* out,
+                hipStream_t stream);   // LOT_ERR_PATH when the shape is outside its set
 
 hipError_t& last_hip_error();
 

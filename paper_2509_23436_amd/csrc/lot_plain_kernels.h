@@ -19,7 +19,7 @@ template <> __device__ inline void st<uint16_t>(uint16_t* p, size_t i, float v) 
 // C[side][g][i][t] = <x_i, z_t>, x from Q (side 0) or K (side 1); bf16 mode rounds Z to bf16.
 template <typename T>
 __global__ void ref_cost(const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ Z,
-                         float* __restrict__ C, int G, int H, int n, int d, int r, int round_z)
+                         float* __restrict__ C, int G, int H, int n, int n_stride, int d, int r, int round_z)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t per_side = (size_t)G * n * r;
@@ -29,7 +29,7 @@ __global__ void ref_cost(const T* __restrict__ Q, const T* __restrict__ K, const
     const int g = (int)(rem / ((size_t)n * r));
     rem %= (size_t)n * r;
     const int i = (int)(rem / r), t = (int)(rem % r);
-    const T* x = (side == 0 ? Q : K) + ((size_t)g * n + i) * d;
+    const T* x = (side == 0 ? Q : K) + ((size_t)g * n_stride + i) * d;
     const float* z = Z + ((size_t)(g % H) * r + t) * d;
     float acc = 0.f;
     for (int c = 0; c < d; ++c) {

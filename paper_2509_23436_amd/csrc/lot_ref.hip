@@ -36,13 +36,13 @@ __global__ void ref_couplings(const float* __restrict__ C, const float* __restri
 template <typename T>
 __global__ void ref_reduce_y(const float* __restrict__ gamma2, const T* __restrict__ V,
                              const float* __restrict__ beta, float* __restrict__ Y,
-                             int H, int n, int r, int dv)
+                             int H, int n, int n_stride, int r, int dv)
 {
     const int g = blockIdx.x / r, t = blockIdx.x % r;
     const float* row = gamma2 + ((size_t)g * r + t) * n;
     for (int c = threadIdx.x; c < dv; c += blockDim.x) {
         float acc = 0.f;
-        for (int j = 0; j < n; ++j) acc = fmaf(row[j], ld(V, ((size_t)g * n + j) * dv + c), acc);
+        for (int j = 0; j < n; ++j) acc = fmaf(row[j], ld(V, ((size_t)g * n_stride + j) * dv + c), acc);
         Y[((size_t)g * r + t) * dv + c] = acc / beta[(g % H) * r + t];
     }
 }
@@ -50,7 +50,7 @@ __global__ void ref_reduce_y(const float* __restrict__ gamma2, const T* __restri
 // O[g][i][c] = n * sum_t gamma1[g][i][t] Y'[g][t][c]
 template <typename T>
 __global__ void ref_expand(const float* __restrict__ gamma1, const float* __restrict__ Y,
-                           T* __restrict__ out, size_t total, int n, int r, int dv)
+                           T* __restrict__ out, size_t total, int n, int n_stride, int r, int dv)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
@@ -59,7 +59,7 @@ __global__ void ref_expand(const float* __restrict__ gamma1, const float* __rest
     const size_t g = gi / n;
     float acc = 0.f;
     for (int t = 0; t < r; ++t) acc = fmaf(gamma1[gi * r + t], Y[(g * r + t) * dv + c], acc);
-    st(out, idx, (float)n * acc);
+    st(out, ((g * n_stride + gi % n) * dv) + c, (float)n * acc);
 }
 
 
@@ -78,9 +78,10 @@ int run_reference_t(const Args& a, bool want_out)
     const size_t nelem = (size_t)pairs * n * r;
     const size_t rows = (size_t)pairs * n;
     hipStream_t st_ = a.stream;
+    const int nst = a.n_stride > 0 ? a.n_stride : n;
 
     ref_mark<<<1, 1, 0, st_>>>((unsigned long long*)(a.ws + a.lay.status), next_nonce());
-    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, s.d_k, r,
+    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, nst, s.d_k, r,
                                                          s.io_dtype == LOT_BF16);
     ref_zero<<<blocks_for((size_t)pairs * r, 256), 256, 0, st_>>>(g, (size_t)pairs * r);
     for (int it = 0; it < a.iters; ++it) {
@@ -90,15 +91,110 @@ int run_reference_t(const Args& a, bool want_out)
     }
     ref_couplings<<<blocks_for(nelem, 256), 256, 0, st_>>>(C, f, g, a.gamma1, a.gamma2, G, n, r, a.eps);
     if (want_out) {
-        ref_reduce_y<T><<<(unsigned)G * r, 64, 0, st_>>>(a.gamma2, (const T*)a.V, a.beta, Y, s.H, n, r, s.d_v);
+        ref_reduce_y<T><<<(unsigned)G * r, 64, 0, st_>>>(a.gamma2, (const T*)a.V, a.beta, Y, s.H, n, nst, r, s.d_v);
         const size_t total = (size_t)G * n * s.d_v;
-        ref_expand<T><<<blocks_for(total, 256), 256, 0, st_>>>(a.gamma1, Y, (T*)a.out, total, n, r, s.d_v);
+        ref_expand<T><<<blocks_for(total, 256), 256, 0, st_>>>(a.gamma1, Y, (T*)a.out, total, n, nst, r, s.d_v);
     }
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }
 
+// [CLS] row (paper, "[CLS] under DS attention"): a softmax row over ALL keys of the problem,
+// alpha_j = softmax_j(beta_cls <q_cls, k_j>), out_cls = sum_j alpha_j v_j.  One workgroup per problem.
+// The keys are taken in chunks of kClsChunk: scores of a chunk go to LDS once, the running maximum
+// and normaliser are updated the usual way (rescale by exp(old max - new max)), and the chunk's
+// weighted values are added; every reduction has a fixed order.
+constexpr int kClsChunk = 2048;
+constexpr int kClsThreads = 256;
+
+template <typename T>
+__global__ void cls_row(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                        T* __restrict__ out, int n, int d, int dv, float beta_cls)
+{
+    __shared__ float s_p[kClsChunk];
+    __shared__ float s_red[kClsThreads];
+    extern __shared__ float s_acc[];        // [parts][dv]
+    const size_t g = blockIdx.x;
+    const T* q = Q + g * n * d;
+    const int tid = threadIdx.x;
+    const int parts = kClsThreads / dv > 0 ? kClsThreads / dv : 1;      // threads per output column
+    float run_max = -INFINITY, run_z = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};   // up to 4 columns per thread when dv > 256
+    for (int j0 = 0; j0 < n; j0 += kClsChunk) {
+        const int cn = min(kClsChunk, n - j0);
+        float m = -INFINITY;
+        for (int j = tid; j < cn; j += kClsThreads) {
+            float sc = 0.f;
+            for (int c = 0; c < d; ++c) sc = fmaf(ld(q, c), ld(K, (g * n + j0 + j) * d + c), sc);
+            sc *= beta_cls;
+            s_p[j] = sc;
+            m = fmaxf(m, sc);
+        }
+        s_red[tid] = m;
+        __syncthreads();
+        for (int w = kClsThreads / 2; w > 0; w >>= 1) {
+            if (tid < w) s_red[tid] = fmaxf(s_red[tid], s_red[tid + w]);
+            __syncthreads();
+        }
+        const float new_max = fmaxf(run_max, s_red[0]);
+        __syncthreads();
+        float z = 0.f;
+        for (int j = tid; j < cn; j += kClsThreads) {
+            const float e = expf(s_p[j] - new_max);
+            s_p[j] = e;
+            z += e;
+        }
+        s_red[tid] = z;
+        __syncthreads();
+        for (int w = kClsThreads / 2; w > 0; w >>= 1) {
+            if (tid < w) s_red[tid] += s_red[tid + w];
+            __syncthreads();
+        }
+        const float scale = expf(run_max - new_max);      // 0 for the first chunk
+        run_z = run_z * scale + s_red[0];
+        run_max = new_max;
+        // weighted values of the chunk: thread = (column c, part); parts interleave the keys
+        int slot = 0;
+        for (int c0 = 0; c0 < dv; c0 += kClsThreads / parts, ++slot) {
+            const int c = c0 + tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
+            float a = 0.f;
+            if (c < dv && part < parts)
+                for (int j = part; j < cn; j += parts) a = fmaf(s_p[j], ld(V, (g * n + j0 + j) * dv + c), a);
+            acc[slot & 3] = acc[slot & 3] * scale + a;
+        }
+        __syncthreads();
+    }
+    // combine the parts of each column in order, normalise, store
+    int slot = 0;
+    for (int c0 = 0; c0 < dv; c0 += kClsThreads / parts, ++slot) {
+        const int c = c0 + tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
+        if (c < dv && part < parts) s_acc[part * dv + c] = acc[slot & 3];
+    }
+    __syncthreads();
+    for (int c = tid; c < dv; c += kClsThreads) {
+        float tot = 0.f;
+        for (int k = 0; k < parts; ++k) tot += s_acc[k * dv + c];
+        st(out, g * n * dv + c, tot / run_z);
+    }
+}
+
 }  // namespace
+
+int run_cls_row(const lot_shape& s, const void* Q, const void* K, const void* V, float beta_cls, void* out,
+                hipStream_t stream)
+{
+    const int G = s.B * s.H;
+    const int parts = kClsThreads / s.d_v > 0 ? kClsThreads / s.d_v : 1;
+    const size_t shmem = (size_t)parts * s.d_v * sizeof(float);      // d_v <= 1024: at most 4 columns per thread
+    if (s.io_dtype == LOT_BF16)
+        cls_row<uint16_t><<<G, kClsThreads, shmem, stream>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
+                                                              (uint16_t*)out, s.n, s.d_k, s.d_v, beta_cls);
+    else
+        cls_row<float><<<G, kClsThreads, shmem, stream>>>((const float*)Q, (const float*)K, (const float*)V,
+                                                           (float*)out, s.n, s.d_k, s.d_v, beta_cls);
+    LOT_HIP_CHECK(hipGetLastError());
+    return LOT_OK;
+}
 
 int run_reference(const Args& a, bool want_out)
 {

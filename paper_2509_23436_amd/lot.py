@@ -17,7 +17,7 @@ LOT_F32, LOT_BF16 = 0, 1
 PATH_AUTO, PATH_REFERENCE, PATH_FUSED = 0, 1, 2
 
 EXPORTS = ("lot_workspace_bytes", "lot_attention_fwd", "lot_couplings", "lot_attention_fwd_path",
-           "lot_couplings_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
+           "lot_couplings_path", "lot_attention_cls_fwd", "lot_attention_cls_fwd_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
            "lot_workspace_status", "lot_strerror", "lot_version")
 
 
@@ -173,3 +173,22 @@ def lot_attention_bwd(Q, K, V, Z, beta, eps, iters, dO, workspace=None, path=PAT
                                         _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dZ), _ptr(dbeta),
                                         _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(), int(path)))
     return dQ, dK, dV, dZ, dbeta
+
+
+def lot_attention_cls_fwd(Q, K, V, Z, beta, eps, iters, beta_cls, out=None, workspace=None, path=PATH_AUTO):
+    """LOT attention among tokens 1..n-1 plus a softmax row (temperature beta_cls) for token 0 ([CLS])."""
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _require(t, nm, Q.dtype)
+    _require(Z, "Z", torch.float32)
+    _require(beta, "beta", torch.float32)
+    shape = _shape_of(Q, V, Z)
+    if out is None:
+        out = torch.empty_like(V)
+    _require(out, "out", Q.dtype)
+    if workspace is None:
+        workspace = alloc_workspace(shape, iters, Q.device)
+    _require(workspace, "workspace", torch.uint8)
+    _check(lib().lot_attention_cls_fwd_path(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
+                                            ctypes.c_float(eps), int(iters), ctypes.c_float(beta_cls), _ptr(out),
+                                            _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(), int(path)))
+    return out

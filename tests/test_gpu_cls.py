@@ -1,0 +1,77 @@
+"""GPU parity of lot_attention_cls_fwd ([CLS] softmax row + LOT attention among the other tokens)
+against the oracle, element by element; both execution paths; the DeiT shape at full size on
+sampled problems.  Bars as for the plain forward: fp32 1e-4, bf16 I/O 2e-2 (max-norm relative)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2509_23436_amd import synth
+from util import rel_max_err, to_device, to_host_f64, tolerance
+
+pytestmark = pytest.mark.gpu
+W = synth.WORKLOADS
+
+
+def S(w, **kw):
+    return dataclasses.replace(w, **kw)
+
+
+CASES = {
+    "tiny": S(W["tiny"], n=65),
+    "deit_like_f32": S(W["deit_tiny"], B=4, H=3, seed=80),                 # n = 197 = 196 + [CLS]
+    "two_tokens": S(W["tiny"], n=2, r=1, seed=81),
+    "bf16_ragged": S(W["long_4k"], B=2, H=2, n=1030, iters=5, seed=82),
+    "bf16_d32": S(W["swin_t_s1"], B=2, H=3, n=400, seed=83),
+    "reference_only": S(W["tiny"], B=1, H=2, n=90, d=16, r=80, iters=4, seed=84),
+    "several_softmax_chunks": S(W["tiny"], B=1, H=2, n=5000, d=32, r=8, iters=4, seed=85),
+}
+
+
+def _paths(w):
+    fused = w.d in (32, 64) and w.r <= 64
+    return ["reference", "fused"] if fused else ["reference"]
+
+
+@pytest.mark.parametrize("name,path_name", [(nm, pn) for nm in CASES for pn in _paths(CASES[nm])])
+def test_cls_variant_matches_oracle(name, path_name):
+    import torch
+    from oracle import lot_oracle
+    from paper_2509_23436_amd import lot
+    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED}[path_name]
+    w = CASES[name]
+    print("case %s path %s: %r" % (name, path_name, w), flush=True)
+    x = synth.make_inputs(w)
+    beta_cls = 0.9
+    ref = lot_oracle.attention_cls(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, beta_cls, threads=4)
+    dev = to_device(x, w.dtype)
+    out = lot.lot_attention_cls_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, beta_cls,
+                                    path=path)
+    torch.cuda.synchronize()
+    tol, _ = tolerance(w.dtype)
+    O = to_host_f64(out)
+    assert np.isfinite(O).all()
+    err_cls = rel_max_err(O[:, :, 0], ref[:, :, 0])
+    err_rest = rel_max_err(O[:, :, 1:], ref[:, :, 1:]) if w.n > 1 else 0.0
+    print("  [CLS] row rel err %.3e, other rows rel err %.3e (bar %.0e)" % (err_cls, err_rest, tol), flush=True)
+    assert err_cls <= tol and err_rest <= tol
+
+
+def test_cls_variant_full_size_deit_on_sampled_problems():
+    import torch
+    from oracle import lot_oracle
+    from paper_2509_23436_amd import lot
+    w = W["deit_tiny"]
+    x = synth.make_inputs(w)
+    dev = to_device(x, w.dtype)
+    out = lot.lot_attention_cls_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, 1.0)
+    torch.cuda.synchronize()
+    O = to_host_f64(out).reshape(w.G, w.n, w.d)
+    for gi in (0, 100, 191):
+        b, h = gi // w.H, gi % w.H
+        sl = lambda t: np.ascontiguousarray(t[b:b + 1, h:h + 1])           # noqa: E731
+        ref = lot_oracle.attention_cls(sl(x["Q"]), sl(x["K"]), sl(x["V"]), x["Z"][h:h + 1], x["beta"][h:h + 1],
+                                       w.eps, w.iters, 1.0)
+        err = rel_max_err(O[gi], ref[0, 0])
+        print("  problem %d rel err %.3e" % (gi, err), flush=True)
+        assert err <= 1e-4
