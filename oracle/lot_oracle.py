@@ -206,3 +206,40 @@ def attention_cls(Q, K, V, Z, beta, eps, T, beta_cls, threads=1):
                 acc += w[j] * V[b, h, j]
             out[b, h, 0] = acc
     return out
+
+
+def cross_attention(Q, K, V, Z, beta, mass_q, mass_k, eps, T):
+    """Cross attention / non-uniform token masses (paper, "Empirical measures and pivot": mu = sum_i
+    p1_i delta_{q_i}, nu = sum_j p2_j delta_{k_j}; "Glued coupling": Gamma 1 = mu, Gamma^T 1 = nu).
+
+    Q [B,H,n_q,d_k], K [B,H,n_k,d_k], V [B,H,n_k,d_v], mass_q [B,H,n_q], mass_k [B,H,n_k]: nonnegative,
+    each summing to one; a token of mass zero is padding.  Per problem: C1 = Q Z^T, C2 = K Z^T; the two
+    Sinkhorn solves with marginals (mass_q, beta) and (mass_k, beta), token side first, pivot side
+    last, T iterations from g = 0; Gamma2 = exp((C2 + f2 + g2)/eps); Y' = Diag(beta)^-1 Gamma2^T V;
+    and the attention is the glued plan with its rows renormalised, A = Diag(mu)^-1 Gamma, which is
+    what A = n Gamma is for uniform masses (reading: the paper writes A only for the balanced case).
+    Row i of Diag(mu)^-1 Gamma1 is exp((C1_it + g1_t)/eps) / sum_t' exp((C1_it' + g1prev_t')/eps) with
+    g1prev the pivot potentials before the last pivot-side update -- the token potential
+    f_i = eps (log mu_i - LSE) cancels mu_i -- so it is defined for zero-mass queries as well.
+    Returns O [B,H,n_q,d_v].
+    """
+    Q = np.asarray(Q, dtype=np.float64); K = np.asarray(K, dtype=np.float64); V = np.asarray(V, dtype=np.float64)
+    B, H, n_q, _ = Q.shape
+    out = np.empty((B, H, n_q, V.shape[-1]), dtype=np.float64)
+    for b in range(B):
+        for h in range(H):
+            bt = np.asarray(beta[h], dtype=np.float64)
+            C1 = cost(Q[b, h], Z[h])
+            C2 = cost(K[b, h], Z[h])
+            with np.errstate(divide="ignore"):
+                _, g1 = sinkhorn(C1, mass_q[b, h], bt, eps, T)
+                _, g1prev = sinkhorn(C1, mass_q[b, h], bt, eps, T - 1) if T > 1 else (None, np.zeros_like(bt))
+                f2, g2 = sinkhorn(C2, mass_k[b, h], bt, eps, T)
+            gamma2 = coupling(C2, f2, g2, eps)                       # n_k x r, zero rows for zero masses
+            Yp = (gamma2.T @ V[b, h]) / bt[:, None]
+            x = (C1 + g1prev[None, :]) / eps
+            m = x.max(axis=1, keepdims=True)
+            lse = m + np.log(np.exp(x - m).sum(axis=1, keepdims=True))
+            R1 = np.exp((C1 + g1[None, :]) / eps - lse)               # rows of Diag(mu)^-1 Gamma1
+            out[b, h] = R1 @ Yp
+    return out
