@@ -114,6 +114,32 @@ int lot_attention_cls_fwd_path(const lot_shape* shape, const void* Q, const void
                                void* out, void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
+ * Cross attention and non-uniform token masses (paper, "Empirical measures and pivot": queries and
+ * keys are measures mu = sum_i p1_i delta_{q_i}, nu = sum_j p2_j delta_{k_j}, "typically" uniform;
+ * the glued plan has marginals mu and nu; cross attention is named as in scope).
+ *   Q [B,H,n_q,d_k], K [B,H,n_k,d_k], V [B,H,n_k,d_v], out [B,H,n_q,d_v] in io_dtype;
+ *   mass_q [B,H,n_q], mass_k [B,H,n_k] fp32 device pointers, or NULL for uniform masses.  Masses are
+ *   nonnegative and sum to one per (batch, head) (caller precondition, like beta); a token of mass
+ *   zero is padding: it receives and sends nothing, whatever its row holds (finite values).
+ * out = A V with A = Diag(mu)^-1 Gamma1 Diag(beta)^-1 Gamma2, the glued plan with renormalised rows
+ * (for uniform masses and n_q = n_k this is n Gamma, i.e. lot_attention_fwd).  The row of a
+ * zero-mass query is still defined (the limit of the formula) and written.
+ * One execution path so far: plain kernels, any shape.  Workspace: lot_cross_workspace_bytes.
+ */
+typedef struct {
+    int32_t B, H;
+    int32_t n_q, n_k;    /* query tokens, key/value tokens */
+    int32_t d_k, d_v;
+    int32_t r;
+    int32_t io_dtype;
+} lot_xshape;
+int lot_cross_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out);
+int lot_cross_attention_fwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                            const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                            float eps, int iters, void* out,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Backward pass (paper, "Learning": the pivots, their masses and the projections are trained by
  * backpropagating through both Sinkhorn problems and the glued composition).  Given dO = dL/dO of
  * the forward call with the same inputs, eps and iters, writes

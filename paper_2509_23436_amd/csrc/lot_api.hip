@@ -186,6 +186,50 @@ int lot_couplings(const lot_shape* shape, const void* Q, const void* K,
                               hip_stream, LOT_PATH_AUTO);
 }
 
+static int validate_xshape(const lot_xshape* s)
+{
+    if (!s) return LOT_ERR_NULL;
+    lot_shape q{s->B, s->H, s->n_q, s->d_k, s->d_v, s->r, s->io_dtype};
+    int rc = validate_shape(&q);
+    if (rc != LOT_OK) return rc;
+    q.n = s->n_k;
+    return validate_shape(&q);
+}
+
+int lot_cross_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out)
+{
+    int rc = validate_xshape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!bytes_out) return LOT_ERR_NULL;
+    if (iters < 1) return LOT_ERR_ITERS;
+    *bytes_out = carve_cross(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_v).total;
+    return LOT_OK;
+}
+
+int lot_cross_attention_fwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                            const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                            float eps, int iters, void* out,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int rc = validate_xshape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!Q || !K || !V || !Z || !beta || !out || !workspace) return LOT_ERR_NULL;
+    if (!(eps > 0.0f) || !std::isfinite(eps)) return LOT_ERR_EPS;
+    if (iters < 1) return LOT_ERR_ITERS;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(out, 16) || misaligned(Z, 4) ||
+        misaligned(beta, 4) || misaligned(mass_q, 4) || misaligned(mass_k, 4))
+        return LOT_ERR_ALIGN;
+    if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
+    CrossArgs a{};
+    a.B = shape->B; a.H = shape->H; a.n_q = shape->n_q; a.n_k = shape->n_k; a.d_k = shape->d_k; a.d_v = shape->d_v;
+    a.r = shape->r; a.io_dtype = shape->io_dtype;
+    a.lay = carve_cross(a.B, a.H, a.n_q, a.n_k, a.r, a.d_v);
+    if (workspace_bytes < a.lay.total) return LOT_ERR_WORKSPACE;
+    a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.mass_q = mass_q; a.mass_k = mass_k;
+    a.eps = eps; a.iters = iters; a.out = out; a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
+    return run_cross_reference(a);
+}
+
 int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out)
 {
     int rc = validate_shape(shape);

@@ -147,6 +147,30 @@ struct BwdTiledWorkspace {
 bool bwd_tiled_supports(const lot_shape& s, int iters);
 BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters);
 
+// Cross attention / non-uniform token masses.
+struct CrossWorkspace {
+    size_t C1, C2, lse1, lse2, g1, g2, part_m, part_s, Y;   // plain path (status words at offset 0)
+    size_t total;
+};
+CrossWorkspace carve_cross(int B, int H, int n_q, int n_k, int r, int d_v);
+struct CrossArgs {
+    int B, H, n_q, n_k, d_k, d_v, r, io_dtype;
+    const void* Q;          // [B,H,n_q,d_k]
+    const void* K;          // [B,H,n_k,d_k]
+    const void* V;          // [B,H,n_k,d_v]
+    const float* Z;
+    const float* beta;
+    const float* mass_q;    // [B,H,n_q] or null (uniform)
+    const float* mass_k;    // [B,H,n_k] or null
+    float eps;
+    int iters;
+    void* out;              // [B,H,n_q,d_v]
+    char* ws;
+    CrossWorkspace lay;
+    hipStream_t stream;
+};
+int run_cross_reference(const CrossArgs& a);
+
 // Each returns LOT_OK or LOT_ERR_HIP (the failing hipError_t is left in last_hip_error()).
 int run_reference(const Args& a, bool want_out);
 int run_fused(const Args& a, bool want_out);

@@ -17,12 +17,18 @@ LOT_F32, LOT_BF16 = 0, 1
 PATH_AUTO, PATH_REFERENCE, PATH_FUSED = 0, 1, 2
 
 EXPORTS = ("lot_workspace_bytes", "lot_attention_fwd", "lot_couplings", "lot_attention_fwd_path",
-           "lot_couplings_path", "lot_attention_cls_fwd", "lot_attention_cls_fwd_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
+           "lot_couplings_path", "lot_attention_cls_fwd", "lot_attention_cls_fwd_path", "lot_cross_workspace_bytes", "lot_cross_attention_fwd", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
            "lot_workspace_status", "lot_strerror", "lot_version")
 
 
 class lot_shape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("n", ctypes.c_int32),
+                ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32), ("r", ctypes.c_int32),
+                ("io_dtype", ctypes.c_int32)]
+
+
+class lot_xshape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("n_q", ctypes.c_int32), ("n_k", ctypes.c_int32),
                 ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32), ("r", ctypes.c_int32),
                 ("io_dtype", ctypes.c_int32)]
 
@@ -191,4 +197,35 @@ def lot_attention_cls_fwd(Q, K, V, Z, beta, eps, iters, beta_cls, out=None, work
     _check(lib().lot_attention_cls_fwd_path(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
                                             ctypes.c_float(eps), int(iters), ctypes.c_float(beta_cls), _ptr(out),
                                             _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(), int(path)))
+    return out
+
+
+def lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=None, mass_k=None, out=None, workspace=None):
+    """Cross attention with optional token masses: Q [B,H,n_q,d], K [B,H,n_k,d], V [B,H,n_k,d_v]."""
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _require(t, nm, Q.dtype)
+    _require(Z, "Z", torch.float32)
+    _require(beta, "beta", torch.float32)
+    B, H, n_q, d_k = Q.shape
+    n_k, d_v = K.shape[2], V.shape[3]
+    dt = LOT_F32 if Q.dtype == torch.float32 else LOT_BF16
+    shape = lot_xshape(B, H, n_q, n_k, d_k, d_v, Z.shape[1], dt)
+    for m, nm, n in ((mass_q, "mass_q", n_q), (mass_k, "mass_k", n_k)):
+        if m is not None:
+            _require(m, nm, torch.float32)
+            if tuple(m.shape) != (B, H, n):
+                raise ValueError(nm + " must be [B, H, n]")
+    if out is None:
+        out = torch.empty((B, H, n_q, d_v), dtype=Q.dtype, device=Q.device)
+    need = ctypes.c_size_t(0)
+    _check(lib().lot_cross_workspace_bytes(ctypes.byref(shape), int(iters), ctypes.byref(need)))
+    if workspace is None:
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=Q.device)
+    _require(workspace, "workspace", torch.uint8)
+    null = ctypes.c_void_p(0)
+    _check(lib().lot_cross_attention_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
+                                         _ptr(mass_q) if mass_q is not None else null,
+                                         _ptr(mass_k) if mass_k is not None else null,
+                                         ctypes.c_float(eps), int(iters), _ptr(out),
+                                         _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
     return out
