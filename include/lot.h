@@ -124,7 +124,9 @@ int lot_attention_cls_fwd_path(const lot_shape* shape, const void* Q, const void
  * out = A V with A = Diag(mu)^-1 Gamma1 Diag(beta)^-1 Gamma2, the glued plan with renormalised rows
  * (for uniform masses and n_q = n_k this is n Gamma, i.e. lot_attention_fwd).  The row of a
  * zero-mass query is still defined (the limit of the formula) and written.
- * One execution path so far: plain kernels, any shape.  Workspace: lot_cross_workspace_bytes.
+ * Execution paths as for lot_attention_fwd (lot_path): the fused kernel takes d_k = d_v in {32, 64},
+ * r <= 64; the plain kernels any shape; AUTO prefers the fused kernel.  Workspace:
+ * lot_cross_workspace_bytes; lot_workspace_status applies.
  */
 typedef struct {
     int32_t B, H;
@@ -138,6 +140,10 @@ int lot_cross_attention_fwd(const lot_xshape* shape, const void* Q, const void* 
                             const float* Z, const float* beta, const float* mass_q, const float* mass_k,
                             float eps, int iters, void* out,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                                 const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                                 float eps, int iters, void* out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
  * Backward pass (paper, "Learning": the pivots, their masses and the projections are trained by

@@ -196,20 +196,32 @@ static int validate_xshape(const lot_xshape* s)
     return validate_shape(&q);
 }
 
+// The shape the fused kernel is configured with for a cross-attention call: n = the longer side.
+static lot_shape fused_view(const lot_xshape& x)
+{
+    return lot_shape{x.B, x.H, x.n_q > x.n_k ? x.n_q : x.n_k, x.d_k, x.d_v, x.r, x.io_dtype};
+}
+
 int lot_cross_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out)
 {
     int rc = validate_xshape(shape);
     if (rc != LOT_OK) return rc;
     if (!bytes_out) return LOT_ERR_NULL;
     if (iters < 1) return LOT_ERR_ITERS;
-    *bytes_out = carve_cross(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_v).total;
+    size_t need = carve_cross(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_v).total;
+    const lot_shape fs = fused_view(*shape);
+    if (fused_supports(fs)) {
+        const size_t fused = carve(fs).C;      // the fused kernel's regions come first in that layout
+        if (fused > need) need = fused;
+    }
+    *bytes_out = need;
     return LOT_OK;
 }
 
-int lot_cross_attention_fwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
-                            const float* Z, const float* beta, const float* mass_q, const float* mass_k,
-                            float eps, int iters, void* out,
-                            void* workspace, size_t workspace_bytes, void* hip_stream)
+int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                                 const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                                 float eps, int iters, void* out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream, int path)
 {
     int rc = validate_xshape(shape);
     if (rc != LOT_OK) return rc;
@@ -220,14 +232,38 @@ int lot_cross_attention_fwd(const lot_xshape* shape, const void* Q, const void* 
         misaligned(beta, 4) || misaligned(mass_q, 4) || misaligned(mass_k, 4))
         return LOT_ERR_ALIGN;
     if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
+    size_t need = 0;
+    rc = lot_cross_workspace_bytes(shape, iters, &need);
+    if (rc != LOT_OK) return rc;
+    if (workspace_bytes < need) return LOT_ERR_WORKSPACE;
+    const lot_shape fs = fused_view(*shape);
+    bool fused = false;
+    rc = pick_path(fs, path, &fused);
+    if (rc != LOT_OK) return rc;
+    if (fused) {
+        Args f{};
+        f.s = fs; f.Q = Q; f.K = K; f.V = V; f.Z = Z; f.beta = beta; f.eps = eps; f.iters = iters; f.out = out;
+        f.ws = (char*)workspace; f.lay = carve(fs); f.stream = (hipStream_t)hip_stream;
+        f.n_q = shape->n_q; f.n_k = shape->n_k; f.mass_q = mass_q; f.mass_k = mass_k;
+        rc = run_fused(f, true);
+        if (!(rc == LOT_ERR_PATH && path == LOT_PATH_AUTO)) return rc;
+    }
     CrossArgs a{};
     a.B = shape->B; a.H = shape->H; a.n_q = shape->n_q; a.n_k = shape->n_k; a.d_k = shape->d_k; a.d_v = shape->d_v;
     a.r = shape->r; a.io_dtype = shape->io_dtype;
     a.lay = carve_cross(a.B, a.H, a.n_q, a.n_k, a.r, a.d_v);
-    if (workspace_bytes < a.lay.total) return LOT_ERR_WORKSPACE;
     a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.mass_q = mass_q; a.mass_k = mass_k;
     a.eps = eps; a.iters = iters; a.out = out; a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
     return run_cross_reference(a);
+}
+
+int lot_cross_attention_fwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                            const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                            float eps, int iters, void* out,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return lot_cross_attention_fwd_path(shape, Q, K, V, Z, beta, mass_q, mass_k, eps, iters, out, workspace,
+                                        workspace_bytes, hip_stream, LOT_PATH_AUTO);
 }
 
 int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out)

@@ -63,9 +63,13 @@ struct FusedParams {
     unsigned long long* colacc;   // [G][2 sides][2 parities][64]: count << 56 | fixed-point column sum
     float* u_part;        // [G][cluster_cap][64][D]
     float* y_tile;        // [G][64][D]
-    int G, H, n, r;
-    int n_stride;         // tokens between consecutive problems in Q, K, V, out (>= n)
-    int cluster, cluster_cap, tiles_per_wg, num_items, iters, mode;
+    int G, H, r;
+    // per side (0 = keys and values, 1 = queries and the output):
+    int n_side[2];          // tokens per problem
+    int stride_side[2];     // tokens between consecutive problems in memory (>= n_side)
+    int tpw_side[2];        // tiles per workgroup
+    const float* mass_side[2];   // [G][n_side] token masses, or null: uniform 1/n_side
+    int cluster, cluster_cap, num_items, iters, mode;
     float eps;
     float fx_scale, fx_unscale;   // 2^F and 2^-F of the fixed-point column sums
     uint32_t spin_limit;
@@ -100,30 +104,53 @@ __device__ inline bool spin_until(uint32_t* counter, uint32_t target, const unsi
 // ---------------------------------------------------------------------------------------------
 template <typename IO, int D, int RB, int EPI, int WAVES>
 __device__ __forceinline__ void run_pass(
-    const FusedParams& p, const IO* __restrict__ X, const IO* __restrict__ Xnext, Frag<IO, D>& xfirst,
-    int g, int side, int tile_begin, int tile_end, int lane, int wave, float c1,
+    const FusedParams& p, const IO* __restrict__ X, const IO* __restrict__ Xnext, int next_side,
+    Frag<IO, D>& xfirst, float& mfirst,
+    int g, int side, const int (&tile_begins)[2], int tile_end, int lane, int wave, float c1,
     const Frag<IO, D> (&zf)[RB], const void* zlds, const float* glds, f32x16 (&cs)[RB],
     const IO* __restrict__ V, f32x16 (&U)[RB][D / 32], uint16_t* tr_hi, uint16_t* tr_lo,
     const bf16x8* yf_hi, const bf16x8* yf_lo, IO* __restrict__ out)
 {
     constexpr int NB = D / 32;
     const int i = lane & 31, kg = lane >> 5;
-    const int n = p.n;
+    const int n = p.n_side[side];
+    const int stride = p.stride_side[side];
+    const int tile_begin = tile_begins[side];
+    // token masses times n (1 for uniform masses): they weight the column sums, the reduction over the
+    // keys and the couplings, but not the rows of the attention matrix
+    const float* const mass = p.mass_side[side];
     int tile = tile_begin + wave;
-    if (tile >= tile_end) return;
+    if (tile >= tile_end) {
+        // Nothing to do on this side (the two sides can have different numbers of tiles), but the next
+        // pass still expects its first tile in xfirst.
+        if (Xnext != nullptr) {
+            const int nn = p.n_side[next_side];
+            const int tok = min((tile_begins[next_side] + wave) * kTileTokens + i, nn - 1);
+            load_tokens<D>(xfirst, Xnext + ((size_t)g * p.stride_side[next_side] + tok) * D, kg);
+            const float* const mass_next = p.mass_side[next_side];
+            mfirst = mass_next ? (float)nn * as_global(mass_next)[(size_t)g * nn + tok] : 1.f;
+        }
+        return;
+    }
 
     // the first tile's rows were loaded before the previous pass ended (xfirst); the last
     // iteration below loads the first tile of the NEXT pass (same tile range, rows of Xnext),
     // so that no pass starts with an exposed round trip to memory
     Frag<IO, D> xc = xfirst;
+    float mcur = mfirst;
     for (; tile < tile_end; tile += WAVES) {
         Frag<IO, D> xn = xc;
+        float mnext = mcur;
         if (tile + WAVES < tile_end) {
             const int tok = min((tile + WAVES) * kTileTokens + i, n - 1);
-            load_tokens<D>(xn, X + ((size_t)g * p.n_stride + tok) * D, kg);
+            load_tokens<D>(xn, X + ((size_t)g * stride + tok) * D, kg);
+            if (mass) mnext = (float)n * as_global(mass)[(size_t)g * n + tok];
         } else if (Xnext != nullptr) {
-            const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
-            load_tokens<D>(xn, Xnext + ((size_t)g * p.n_stride + tok) * D, kg);
+            const int nn = p.n_side[next_side];
+            const int tok = min((tile_begins[next_side] + wave) * kTileTokens + i, nn - 1);
+            load_tokens<D>(xn, Xnext + ((size_t)g * p.stride_side[next_side] + tok) * D, kg);
+            const float* const mass_next = p.mass_side[next_side];
+            mnext = mass_next ? (float)nn * as_global(mass_next)[(size_t)g * nn + tok] : 1.f;
         }
 
         // the value rows this tile will be multiplied with are requested now and used at the end
@@ -133,7 +160,7 @@ __device__ __forceinline__ void run_pass(
             for (int s = 0; s < 2; ++s) {
                 const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
                 const int left = max(1, min(8, n - t0));
-                load_values<D>(vh[s], vl[s], V, (size_t)g * p.n_stride + min(t0, n - 1), left, i);
+                load_values<D>(vh[s], vl[s], V, (size_t)g * stride + min(t0, n - 1), left, i);
             }
         }
 
@@ -174,12 +201,13 @@ __device__ __forceinline__ void run_pass(
         const float s = pair_sum((s0 + s1) + (s2 + s3));
         const int tok = tile * kTileTokens + i;
         const float w = tok < n ? rcp_fast(s) : 0.f;    // tokens past the end carry no mass
+        const float wm = mass ? w * mcur : w;           // ... and every token its own
 
         if (EPI == EPI_NONE || EPI == EPI_ACCUM_U) {
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) cs[mb][j] = fmaf(acc[mb][j], w, cs[mb][j]);
+                for (int j = 0; j < 16; ++j) cs[mb][j] = fmaf(acc[mb][j], wm, cs[mb][j]);
         }
 
         if (EPI == EPI_ACCUM_U) {
@@ -192,7 +220,7 @@ __device__ __forceinline__ void run_pass(
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
-                    const float v = acc[mb][j] * w;
+                    const float v = acc[mb][j] * wm;
                     const __bf16 h = (__bf16)v;
                     const int pv = pivot_of(mb, j, kg);
                     tr_hi[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, h);
@@ -251,7 +279,7 @@ __device__ __forceinline__ void run_pass(
             }
             // one address per lane and tile; the row of accumulator register j is a compile-time offset
             const int row0 = tile * kTileTokens + 4 * kg;
-            IO* const lane_base = out + ((size_t)g * p.n_stride + row0) * D;
+            IO* const lane_base = out + ((size_t)g * stride + row0) * D;
             if ((tile + 1) * kTileTokens <= n) {   // whole tile in range: no per-row test
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
@@ -281,7 +309,7 @@ __device__ __forceinline__ void run_pass(
                             const int pv0 = 32 * mb + 8 * q + 4 * kg;
                             f32x4 v;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] = acc[mb][4 * q + e] * w * cs[mb][4 * q + e];
+                            for (int e = 0; e < 4; ++e) v[e] = acc[mb][4 * q + e] * wm * cs[mb][4 * q + e];
                             if (vec) {
                                 if (pv0 < rr) *as_global(reinterpret_cast<f32x4*>(row + 32 * mb + 8 * q)) = v;
                             } else {
@@ -297,14 +325,16 @@ __device__ __forceinline__ void run_pass(
 #pragma unroll
                         for (int j = 0; j < 16; ++j) {
                             const int pc = 32 * mb + 8 * (j >> 2) + (j & 3);   // pivot minus 4 * kg
-                            if (pc + 4 * kg < rr) as_global(col)[(size_t)pc * nn] = acc[mb][j] * w * cs[mb][j];
+                            if (pc + 4 * kg < rr) as_global(col)[(size_t)pc * nn] = acc[mb][j] * wm * cs[mb][j];
                         }
                 }
             }
         }
         xc = xn;
+        mcur = mnext;
     }
     xfirst = xc;
+    mfirst = mcur;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -336,9 +366,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile indices and bases stay scalar
     const int i = lane & 31, kg = lane >> 5;
-    const int n = p.n, r = p.r;
+    const int r = p.r;
     const float c1 = kLog2e / p.eps;
-    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    const int ntiles_side[2] = {(p.n_side[0] + kTileTokens - 1) / kTileTokens,
+                                (p.n_side[1] + kTileTokens - 1) / kTileTokens};
     uint16_t* tr_hi = s_tr + (wave * 2 + 0) * 64 * kTrStride;
     uint16_t* tr_lo = s_tr + (wave * 2 + 1) * 64 * kTrStride;
     bf16x8* yf_hi = reinterpret_cast<bf16x8*>(s_tr);
@@ -348,16 +379,19 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
     for (int item = blockIdx.x; item < p.num_items; item += gridDim.x) {
         LOT_STAMP(0);
         const int g = item / p.cluster, chunk = item % p.cluster, h = g % p.H;
-        const int tile_begin = chunk * p.tiles_per_wg;
-        const int tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
+        const int tile_begins[2] = {chunk * p.tpw_side[0], chunk * p.tpw_side[1]};
+        const int tile_ends[2] = {min(ntiles_side[0], tile_begins[0] + p.tpw_side[0]),
+                                  min(ntiles_side[1], tile_begins[1] + p.tpw_side[1])};
         const float* beta = p.beta + (size_t)h * r;
         const IO* Xs[2] = {reinterpret_cast<const IO*>(p.K), reinterpret_cast<const IO*>(p.Q)};
 
         // the first key tile is requested before anything else: its latency overlaps the set-up
         Frag<IO, D> xfirst;
+        float mfirst = 1.f;
         {
-            const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
-            load_tokens<D>(xfirst, Xs[0] + ((size_t)g * p.n_stride + tok) * D, kg);
+            const int tok = min((tile_begins[0] + wave) * kTileTokens + i, p.n_side[0] - 1);
+            load_tokens<D>(xfirst, Xs[0] + ((size_t)g * p.stride_side[0] + tok) * D, kg);
+            if (p.mass_side[0]) mfirst = (float)p.n_side[0] * as_global(p.mass_side[0])[(size_t)g * p.n_side[0] + tok];
         }
         // (beta is requested together with the pivots: one wait for both, not two round trips)
         const float beta_read = as_global(beta)[min(tid & 63, r - 1)];   // unconditional: issued with the loads around it
@@ -430,7 +464,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 const float c = fmaxf(tot, 1.0e-37f);
                 const float b = s_beta[ln];
                 if (!final) {
-                    s_g[side][ln] += p.eps * logf((float)opaque_scalar(n) * b / c);
+                    s_g[side][ln] += p.eps * logf((float)opaque_scalar(p.n_side[side]) * b / c);
                 } else {
                     // the last pass's potentials stay: the epilogue rebuilds its coupling from them
                     s_rho[side][ln] = b / c;
@@ -561,7 +595,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             for (int side = 0; side < 2; ++side) {
                 // the pass after this one: the other side, except that the last query pass is
                 // followed by an epilogue pass (queries again for attention, keys for couplings)
-                const IO* Xnext = (side == 1 && it == p.iters) ? Xs[attention ? 1 : 0] : Xs[side ^ 1];
+                const int next_side = (side == 1 && it == p.iters) ? (attention ? 1 : 0) : (side ^ 1);
+                const IO* Xnext = Xs[next_side];
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -575,10 +610,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                             for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
-                    run_pass<IO, D, RB, EPI_ACCUM_U, WAVES>(p, Xs[side], Xnext, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
+                    run_pass<IO, D, RB, EPI_ACCUM_U, WAVES>(p, Xs[side], Xnext, next_side, xfirst, mfirst, g, side, tile_begins, tile_ends[side], lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                      reinterpret_cast<const IO*>(p.V), U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
                 } else {
-                    run_pass<IO, D, RB, EPI_NONE, WAVES>(p, Xs[side], Xnext, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
+                    run_pass<IO, D, RB, EPI_NONE, WAVES>(p, Xs[side], Xnext, next_side, xfirst, mfirst, g, side, tile_begins, tile_ends[side], lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                   nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
                 }
                 // what is collected along with this post: keys' pass `it` after a query pass (for
@@ -634,13 +669,13 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         if (!attention) {
             for (int side = 0; side < 2; ++side) {
                 load_pivot_vector<RB>(cs, s_rho[side], kg);
-                run_pass<IO, D, RB, EPI_GAMMA, WAVES>(p, Xs[side], side == 0 ? Xs[1] : nullptr, xfirst, g, side, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[side], cs,
+                run_pass<IO, D, RB, EPI_GAMMA, WAVES>(p, Xs[side], side == 0 ? Xs[1] : nullptr, 1, xfirst, mfirst, g, side, tile_begins, tile_ends[side], lane, wave, c1, zf, s_zf, s_g[side], cs,
                                                nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, nullptr);
             }
         } else {
             // Y''_t = n * rho1_t * U_t / colsum2_t  ->  s_u
             if (p.cluster == 1) {
-                for (int e = wave * 64 + fresh_lane(); e < 64 * D; e += kThreads) s_u[e] *= s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
+                for (int e = wave * 64 + fresh_lane(); e < 64 * D; e += kThreads) s_u[e] *= s_csinv[e / D] * ((float)p.n_side[1] * s_rho[1][e / D]);
             } else {
                 __builtin_amdgcn_s_setprio(3);
                 if (tid == 0) {
@@ -659,7 +694,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
 #pragma unroll
                 for (int j = 0; j < kChunks; ++j) {
                     const int e = 4 * (ft + j * kThreads);
-                    const float sc = s_csinv[e / D] * ((float)n * s_rho[1][e / D]);
+                    const float sc = s_csinv[e / D] * ((float)p.n_side[1] * s_rho[1][e / D]);
 #pragma unroll
                     for (int c = 0; c < 4; ++c) s_u[e + c] = v[j][c] * sc;
                 }
@@ -684,7 +719,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             }
             lds_barrier();
             LOT_STAMP(4);
-            run_pass<IO, D, RB, EPI_EXPAND, WAVES>(p, Xs[1], nullptr, xfirst, g, 1, tile_begin, tile_end, lane, wave, c1, zf, s_zf, s_g[1], cs,
+            run_pass<IO, D, RB, EPI_EXPAND, WAVES>(p, Xs[1], nullptr, 1, xfirst, mfirst, g, 1, tile_begins, tile_ends[1], lane, wave, c1, zf, s_zf, s_g[1], cs,
                                             nullptr, U, tr_hi, tr_lo, yf_hi, yf_lo, reinterpret_cast<IO*>(p.out));
         }
         LOT_STAMP(5);
@@ -718,7 +753,10 @@ int launch(const Args& a, bool want_out)
         if (dev >= 0 && dev < 8) capacity_cache[dev] = capacity;
     }
 
-    const int ntiles = (s.n + kTileTokens - 1) / kTileTokens;
+    // per side: 0 = keys and values, 1 = queries; equal unless this is cross attention
+    const int n_side[2] = {a.n_k > 0 ? a.n_k : s.n, a.n_q > 0 ? a.n_q : s.n};
+    const int nt_side[2] = {(n_side[0] + kTileTokens - 1) / kTileTokens, (n_side[1] + kTileTokens - 1) / kTileTokens};
+    const int ntiles = nt_side[0] > nt_side[1] ? nt_side[0] : nt_side[1];
     int cluster = fused_cluster_bound(s);
     {
         const int by_tiles = (ntiles + WAVES - 1) / WAVES;   // at least one tile per wavefront
@@ -739,8 +777,14 @@ int launch(const Args& a, bool want_out)
     p.colacc = (unsigned long long*)(a.ws + a.lay.colacc);
     p.u_part = (float*)(a.ws + a.lay.u_part);
     p.y_tile = (float*)(a.ws + a.lay.y_tile);
-    p.G = G; p.H = s.H; p.n = s.n; p.r = s.r; p.n_stride = a.n_stride > 0 ? a.n_stride : s.n;
-    p.cluster = cluster; p.cluster_cap = fused_cluster_bound(s); p.tiles_per_wg = tiles_per_wg;
+    p.G = G; p.H = s.H; p.r = s.r;
+    for (int sd = 0; sd < 2; ++sd) {
+        p.n_side[sd] = n_side[sd];
+        p.stride_side[sd] = a.n_stride > 0 ? a.n_stride : n_side[sd];
+        p.tpw_side[sd] = (nt_side[sd] + cluster - 1) / cluster;
+    }
+    p.mass_side[0] = a.mass_k; p.mass_side[1] = a.mass_q;
+    p.cluster = cluster; p.cluster_cap = fused_cluster_bound(s);
     p.num_items = G * cluster; p.iters = a.iters; p.mode = want_out ? MODE_ATTENTION : MODE_COUPLINGS;
     p.eps = a.eps;
     p.spin_limit = 1u << 21;
@@ -749,7 +793,7 @@ int launch(const Args& a, bool want_out)
     // Fixed-point format of the exchanged column sums: a parity buffer receives at most
     // iters/2 + 1 passes, each adding at most n per pivot, and must stay below 2^55.
     {
-        const double max_sum = ((double)a.iters / 2.0 + 1.0) * (double)s.n;
+        const double max_sum = ((double)a.iters / 2.0 + 1.0) * (double)(n_side[0] > n_side[1] ? n_side[0] : n_side[1]);
         int frac = 55 - (int)std::ceil(std::log2(max_sum + 1.0));
         if (frac > 40) frac = 40;
         if (frac < 8) return LOT_ERR_PATH;

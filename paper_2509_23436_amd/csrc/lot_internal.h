@@ -104,6 +104,10 @@ struct Args {
     Workspace lay;
     hipStream_t stream;
     int n_stride;        // tokens between consecutive problems in Q, K, V, out; 0 = dense (s.n)
+    // cross attention (fused path): 0 / null = as in s.n, uniform.  s.n then holds max(n_q, n_k).
+    int n_q, n_k;
+    const float* mass_q;
+    const float* mass_k;
 };
 
 // Workspace of the backward pass (plain path): byte offsets, multiples of 256.

@@ -17,7 +17,7 @@ LOT_F32, LOT_BF16 = 0, 1
 PATH_AUTO, PATH_REFERENCE, PATH_FUSED = 0, 1, 2
 
 EXPORTS = ("lot_workspace_bytes", "lot_attention_fwd", "lot_couplings", "lot_attention_fwd_path",
-           "lot_couplings_path", "lot_attention_cls_fwd", "lot_attention_cls_fwd_path", "lot_cross_workspace_bytes", "lot_cross_attention_fwd", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
+           "lot_couplings_path", "lot_attention_cls_fwd", "lot_attention_cls_fwd_path", "lot_cross_workspace_bytes", "lot_cross_attention_fwd", "lot_cross_attention_fwd_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
            "lot_workspace_status", "lot_strerror", "lot_version")
 
 
@@ -200,7 +200,8 @@ def lot_attention_cls_fwd(Q, K, V, Z, beta, eps, iters, beta_cls, out=None, work
     return out
 
 
-def lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=None, mass_k=None, out=None, workspace=None):
+def lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=None, mass_k=None, out=None, workspace=None,
+                            path=PATH_AUTO):
     """Cross attention with optional token masses: Q [B,H,n_q,d], K [B,H,n_k,d], V [B,H,n_k,d_v]."""
     for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
         _require(t, nm, Q.dtype)
@@ -223,9 +224,10 @@ def lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=None, mass_k=No
         workspace = torch.empty(need.value, dtype=torch.uint8, device=Q.device)
     _require(workspace, "workspace", torch.uint8)
     null = ctypes.c_void_p(0)
-    _check(lib().lot_cross_attention_fwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
-                                         _ptr(mass_q) if mass_q is not None else null,
-                                         _ptr(mass_k) if mass_k is not None else null,
-                                         ctypes.c_float(eps), int(iters), _ptr(out),
-                                         _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
+    _check(lib().lot_cross_attention_fwd_path(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
+                                              _ptr(mass_q) if mass_q is not None else null,
+                                              _ptr(mass_k) if mass_k is not None else null,
+                                              ctypes.c_float(eps), int(iters), _ptr(out),
+                                              _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(),
+                                              int(path)))
     return out

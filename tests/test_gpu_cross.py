@@ -38,19 +38,27 @@ CASES = {
     "padded_f32": dict(B=2, H=3, n_q=197, n_k=300, d=64, d_v=64, r=16, seed=502, bf16=False, masses="padded", eps=0.1, iters=10),
     "bf16_cross": dict(B=1, H=2, n_q=700, n_k=2100, d=64, d_v=64, r=64, seed=503, bf16=True, masses="random", eps=0.05, iters=5),
     "bf16_padded_d32": dict(B=2, H=3, n_q=1000, n_k=600, d=32, d_v=32, r=32, seed=504, bf16=True, masses="padded", eps=0.1, iters=10),
+    "long_keys_bf16": dict(B=2, H=4, n_q=1024, n_k=9000, d=64, d_v=64, r=64, seed=506, bf16=True, masses="padded", eps=0.05, iters=6),
+    "long_queries_bf16": dict(B=2, H=4, n_q=9000, n_k=500, d=64, d_v=64, r=32, seed=507, bf16=True, masses="uniform", eps=0.05, iters=6),
     "other_dims": dict(B=1, H=2, n_q=60, n_k=90, d=16, d_v=24, r=80, seed=505, bf16=False, masses="random", eps=0.1, iters=4),
 }
 
 
-@pytest.mark.parametrize("name", list(CASES))
-def test_cross_attention_matches_oracle(name):
+def _paths(c):
+    fused = c["d"] == c["d_v"] and c["d"] in (32, 64) and c["r"] <= 64
+    return ["reference", "fused"] if fused else ["reference"]
+
+
+@pytest.mark.parametrize("name,path_name", [(nm, pn) for nm in CASES for pn in _paths(CASES[nm])])
+def test_cross_attention_matches_oracle(name, path_name):
     import torch
     from oracle import lot_oracle
     from paper_2509_23436_amd import lot
+    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED}[path_name]
     c = dict(CASES[name])
     eps, iters = c.pop("eps"), c.pop("iters")
     x = _inputs(**c)
-    print("case %s: %r" % (name, CASES[name]), flush=True)
+    print("case %s path %s: %r" % (name, path_name, CASES[name]), flush=True)
     B, H, n_q, n_k = c["B"], c["H"], c["n_q"], c["n_k"]
     mq = x["mq"] if x["mq"] is not None else np.full((B, H, n_q), 1.0 / n_q)
     mk = x["mk"] if x["mk"] is not None else np.full((B, H, n_k), 1.0 / n_k)
@@ -64,7 +72,7 @@ def test_cross_attention_matches_oracle(name):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
     out = lot.lot_cross_attention_fwd(dev(x["Q"], True), dev(x["K"], True), dev(x["V"], True), dev(x["Z"]),
-                                      dev(x["beta"]), eps, iters, mass_q=dev(x["mq"]), mass_k=dev(x["mk"]))
+                                      dev(x["beta"]), eps, iters, mass_q=dev(x["mq"]), mass_k=dev(x["mk"]), path=path)
     torch.cuda.synchronize()
     O = to_host_f64(out)
     assert np.isfinite(O).all()
