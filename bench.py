@@ -56,6 +56,52 @@ def compulsory_bytes(w) -> int:
     return 4 * w.d * s * w.G * w.n
 
 
+def runtime_grid(torch, lot, synth, to_device):
+    """Forward / backward time over the axes of the paper's runtime study (its values are not published):
+    B = 1, H = 8, d = 64, bf16 I/O, eps = 0.05, T = 5 (the paper's default)."""
+    import dataclasses
+    rows = []
+    base = synth.WORKLOADS["long_16k"]
+    for r in (32, 64, 128, 256):
+        for logn in range(10, 18):
+            n = 1 << logn
+            if r > 64 and n > (1 << 14):
+                continue                     # plain kernels only: keep the sweep short
+            w = dataclasses.replace(base, B=1, H=8, n=n, r=r, iters=5, seed=90)
+            dev = to_device(synth.make_inputs(w), w.dtype)
+            shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
+            ws = lot.alloc_workspace(shape, w.iters)
+            out = torch.empty_like(dev["V"])
+
+            def fwd():
+                lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, out=out,
+                                      workspace=ws)
+
+            def timed(fn, reps):
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(reps):
+                    fn()
+                b.record()
+                torch.cuda.synchronize()
+                return a.elapsed_time(b) / reps
+
+            reps = 50 if r <= 64 else 5
+            row = {"n": n, "r": r, "T": 5, "path": "fused" if r <= 64 else "plain", "fwd_ms": timed(fwd, reps)}
+            if r <= 64:
+                dO = torch.randn_like(dev["V"])
+                wsb = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape, w.iters), dtype=torch.uint8, device="cuda")
+                row["bwd_ms"] = timed(lambda: lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"],
+                                                                    w.eps, w.iters, dO, workspace=wsb), 20)
+                del wsb, dO
+            rows.append(row)
+            del dev, ws, out
+    return rows
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +114,9 @@ def main() -> int:
     ap.add_argument("--bwd-steps", type=int, default=50,
                     help="timed calls of the backward pass (reported beside the headline; 0 skips it)")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "reference"])
+    ap.add_argument("--runtime-grid", action="store_true",
+                    help="instead of the benchmark, time the forward (and backward where the tiled path applies) "
+                         "over the paper's runtime grid: n = 2^10..2^17, r in {32, 64, 128, 256}, T = 5; one JSON line")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB ten times "
                          "(used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -91,6 +140,9 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": args.calibrate_copy << 20, "copies": 10}))
+        return 0
+    if args.runtime_grid:
+        print(json.dumps({"runtime_grid": runtime_grid(torch, lot, synth, to_device)}))
         return 0
     w = synth.WORKLOADS[args.workload]
     path = {"auto": lot.PATH_AUTO, "fused": lot.PATH_FUSED, "reference": lot.PATH_REFERENCE}[args.path]

@@ -6,6 +6,7 @@ problems one by one -- they are independent, so each sampled problem is compared
 by element.  Bars: fp32 I/O <= 1e-4 (max-norm relative) on O, bf16 I/O <= 2e-2; marginal residuals
 <= 1e-5 on the sampled problems.
 """
+import dataclasses
 import sys
 
 import numpy as np
@@ -69,3 +70,35 @@ def test_full_size_workload_matches_oracle_on_sampled_problems(name):
     piv = max(float(np.abs(res[1]).max()), float(np.abs(res[3]).max()))
     print("  marginal residual err %.3e, pivot-side residual %.3e (bar %.0e)" % (merr, piv, tol_m), flush=True)
     assert merr <= tol_m and piv <= tol_m
+
+
+# The paper's runtime study sweeps the sequence length up to 2^17, the pivot size up to 256 and uses
+# T = 5 by default ("Runtime analysis" / appendix defaults).  r <= 64 runs on the fused kernel at any
+# length; r in {128, 256} is outside its compiled set and takes the plain kernels (AUTO).
+GRID = {
+    "n_131072_r64_T5": (dataclasses.replace(synth.WORKLOADS["long_64k"], B=1, H=2, n=131072, iters=5, seed=60), [1]),
+    "n_8192_r128_T5": (dataclasses.replace(synth.WORKLOADS["long_4k"], B=1, H=2, n=8192, r=128, iters=5, seed=61), [0, 1]),
+    "n_4096_r256_T5": (dataclasses.replace(synth.WORKLOADS["long_4k"], B=1, H=2, n=4096, r=256, iters=5, seed=62), [1]),
+}
+
+
+@pytest.mark.parametrize("name", list(GRID))
+def test_runtime_grid_corners_match_oracle(name):
+    import torch
+    from oracle import lot_oracle
+    from paper_2509_23436_amd import lot
+    w, idx = GRID[name]
+    print("workload %r" % (w,), flush=True)
+    x = synth.make_inputs(w)
+    dev = to_device(x, w.dtype)
+    out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters)
+    torch.cuda.synchronize()
+    flat = lambda t: t.reshape(w.G, *t.shape[2:])                       # noqa: E731
+    q, k, v = (np.ascontiguousarray(flat(x[key])[idx])[None] for key in ("Q", "K", "V"))
+    z = np.ascontiguousarray(np.stack([x["Z"][g % w.H] for g in idx]))
+    b = np.ascontiguousarray(np.stack([x["beta"][g % w.H] for g in idx]))
+    O_ref, _ = lot_oracle.attention(q, k, v, z, b, w.eps, w.iters, threads=len(idx))
+    O = to_host_f64(out.reshape(w.G, w.n, w.d)[torch.tensor(idx, device="cuda")])
+    err = rel_max_err(O, O_ref[0])
+    print("  max-norm rel err %.3e" % err, flush=True)
+    assert err <= tolerance(w.dtype)[0]
