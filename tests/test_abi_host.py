@@ -55,7 +55,7 @@ def _call_fwd(L, shape=None, Q=4096, K=8192, V=12288, Z=256, beta=512, eps=0.1, 
     shape = shape or _shape()
     vp = ctypes.c_void_p
     return L.lot_attention_fwd_path(ctypes.byref(shape), vp(Q), vp(K), vp(V), vp(Z), vp(beta), ctypes.c_float(eps),
-                                    iters, vp(out), vp(ws), ws_bytes, None, path)
+                                    iters, vp(out), vp(ws), ctypes.c_size_t(ws_bytes), None, path)
 
 
 def test_attention_rejects_bad_arguments_before_any_device_work(L):
@@ -78,7 +78,7 @@ def test_couplings_rejects_bad_arguments(L):
 
     def call(g1=4096, g2=8192, eps=0.1, iters=3, ws_bytes=1 << 40):
         return L.lot_couplings(ctypes.byref(s), vp(256), vp(512), vp(1024), vp(2048), ctypes.c_float(eps), iters,
-                               vp(g1), vp(g2), vp(1 << 20), ws_bytes, None)
+                               vp(g1), vp(g2), vp(1 << 20), ctypes.c_size_t(ws_bytes), None)
     assert call(g1=0) == -1 and call(g2=0) == -1
     assert call(eps=0.0) == -3 and call(iters=-2) == -4 and call(ws_bytes=0) == -6
 
@@ -90,3 +90,55 @@ def test_strerror_texts(L):
         text = L.lot_strerror(code).decode()
         assert text and text != "unknown status"
     assert L.lot_strerror(-99).decode() == "unknown status"
+
+
+def test_backward_rejects_bad_arguments(L):
+    vp = ctypes.c_void_p
+    s = _shape()
+    need = ctypes.c_size_t(0)
+    assert L.lot_attention_bwd_workspace_bytes(ctypes.byref(s), 5, ctypes.byref(need)) == 0
+    fwd = ctypes.c_size_t(0)
+    assert L.lot_workspace_bytes(ctypes.byref(s), 5, ctypes.byref(fwd)) == 0
+    assert need.value > 0 and need.value % 256 == 0
+    assert L.lot_attention_bwd_workspace_bytes(ctypes.byref(s), 0, ctypes.byref(need)) == -4
+    assert L.lot_attention_bwd_workspace_bytes(ctypes.byref(s), 1 << 17, ctypes.byref(need)) == -4
+
+    def call(dO=0x5000, dQ=0x6000, dZ=0x7000, eps=0.1, iters=5, ws=1 << 20, ws_bytes=1 << 40, path=0, shape=s):
+        return L.lot_attention_bwd_path(ctypes.byref(shape), vp(0x1000), vp(0x2000), vp(0x3000), vp(0x100), vp(0x200),
+                                        ctypes.c_float(eps), iters, vp(dO), vp(dQ), vp(0x8000), vp(0x9000), vp(dZ),
+                                        vp(0xA000), vp(ws), ctypes.c_size_t(ws_bytes), None, path)
+
+    for kw, code in ((dict(dO=0), -1), (dict(dQ=0), -1), (dict(dZ=0), -1), (dict(ws=0), -1),
+                     (dict(eps=0.0), -3), (dict(iters=0), -4), (dict(dO=0x5004), -7), (dict(dZ=0x7002), -7),
+                     (dict(ws=(1 << 20) + 8), -6), (dict(ws_bytes=64), -6), (dict(path=5), -9),
+                     (dict(path=2, shape=_shape(r=100)), -9), (dict(path=2, iters=40), -9)):
+        assert call(**kw) == code, (kw, code)
+
+
+def test_cls_and_cross_entry_points_reject_bad_arguments(L):
+    vp = ctypes.c_void_p
+    s = _shape()
+
+    def cls(beta_cls=1.0, shape=s, out=0x4000):
+        return L.lot_attention_cls_fwd(ctypes.byref(shape), vp(0x1000), vp(0x2000), vp(0x3000), vp(0x100), vp(0x200),
+                                       ctypes.c_float(0.1), 5, ctypes.c_float(beta_cls), vp(out), vp(1 << 20),
+                                       ctypes.c_size_t(1 << 40), None)
+
+    assert cls(beta_cls=0.0) == -3 and cls(beta_cls=float("nan")) == -3
+    assert cls(shape=_shape(n=1)) == -2
+    assert cls(out=0) == -1
+
+    x = lot.lot_xshape(1, 1, 40, 70, 32, 32, 8, 0)
+    need = ctypes.c_size_t(0)
+    assert L.lot_cross_workspace_bytes(ctypes.byref(x), 5, ctypes.byref(need)) == 0 and need.value % 256 == 0
+    assert L.lot_cross_workspace_bytes(ctypes.byref(lot.lot_xshape(1, 1, 0, 70, 32, 32, 8, 0)), 5, ctypes.byref(need)) == -2
+    assert L.lot_cross_workspace_bytes(ctypes.byref(lot.lot_xshape(1, 1, 40, 0, 32, 32, 8, 0)), 5, ctypes.byref(need)) == -2
+
+    def cross(mq=0x5000, K=0x2000, eps=0.1, ws_bytes=1 << 40, path=0, shape=x):
+        return L.lot_cross_attention_fwd_path(ctypes.byref(shape), vp(0x1000), vp(K), vp(0x3000), vp(0x100), vp(0x200),
+                                              vp(mq), vp(0), ctypes.c_float(eps), 5, vp(0x4000), vp(1 << 20),
+                                              ctypes.c_size_t(ws_bytes), None, path)
+
+    for kw, code in ((dict(K=0), -1), (dict(eps=-1.0), -3), (dict(mq=0x5002), -7), (dict(ws_bytes=128), -6),
+                     (dict(path=7), -9), (dict(path=2, shape=lot.lot_xshape(1, 1, 40, 70, 16, 16, 8, 0)), -9)):
+        assert cross(**kw) == code, (kw, code)
