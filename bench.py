@@ -65,8 +65,6 @@ def runtime_grid(torch, lot, synth, to_device):
     for r in (32, 64, 128, 256):
         for logn in range(10, 18):
             n = 1 << logn
-            if r > 64 and n > (1 << 14):
-                continue                     # plain kernels only: keep the sweep short
             w = dataclasses.replace(base, B=1, H=8, n=n, r=r, iters=5, seed=90)
             dev = to_device(synth.make_inputs(w), w.dtype)
             shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
@@ -89,8 +87,7 @@ def runtime_grid(torch, lot, synth, to_device):
                 torch.cuda.synchronize()
                 return a.elapsed_time(b) / reps
 
-            reps = 50 if r <= 64 else 5
-            row = {"n": n, "r": r, "T": 5, "path": "fused" if r <= 64 else "plain", "fwd_ms": timed(fwd, reps)}
+            row = {"n": n, "r": r, "T": 5, "path": "fused" if r <= 64 else "grouped", "fwd_ms": timed(fwd, 50)}
             if r <= 64:
                 dO = torch.randn_like(dev["V"])
                 wsb = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape, w.iters), dtype=torch.uint8, device="cuda")

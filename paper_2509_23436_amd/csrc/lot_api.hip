@@ -79,7 +79,12 @@ int lot_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out)
     if (rc != LOT_OK) return rc;
     if (!bytes_out) return LOT_ERR_NULL;
     if (iters < 1) return LOT_ERR_ITERS;
-    *bytes_out = carve(*shape).total;
+    size_t need = carve(*shape).total;
+    if (grouped_supports(*shape)) {
+        const size_t grouped = carve_grouped(*shape, iters).total;     // grows with iters
+        if (grouped > need) need = grouped;
+    }
+    *bytes_out = need;
     return LOT_OK;
 }
 
@@ -93,6 +98,14 @@ static int attention_impl(const lot_shape* shape, const void* Q, const void* K, 
     if (rc != LOT_OK) return rc;
     if (!V || !out) return LOT_ERR_NULL;
     if (misaligned(V, 16) || misaligned(out, 16)) return LOT_ERR_ALIGN;
+    // pivot sizes beyond one register tile: the grouped kernels stand in for the fused one
+    if (grouped_supports(*shape) && (path == LOT_PATH_AUTO || path == LOT_PATH_FUSED)) {
+        if (workspace_bytes < carve_grouped(*shape, iters).total) return LOT_ERR_WORKSPACE;
+        Args ga{};
+        ga.s = *shape; ga.Q = Q; ga.K = K; ga.V = V; ga.Z = Z; ga.beta = beta; ga.eps = eps; ga.iters = iters;
+        ga.out = out; ga.ws = (char*)workspace; ga.stream = (hipStream_t)hip_stream; ga.n_stride = n_stride;
+        return run_grouped(ga);
+    }
     bool fused = false;
     rc = pick_path(*shape, path, &fused);
     if (rc != LOT_OK) return rc;

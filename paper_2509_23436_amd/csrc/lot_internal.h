@@ -151,6 +151,16 @@ struct BwdTiledWorkspace {
 bool bwd_tiled_supports(const lot_shape& s, int iters);
 BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters);
 
+// Forward for 64 < r <= 256 (pivots in groups of 64; one launch per step).
+struct GroupedWorkspace {
+    size_t colacc, ghist, u_part, ypp;   // status words at offset 0
+    size_t total;
+    int chunks;
+};
+bool grouped_supports(const lot_shape& s);
+GroupedWorkspace carve_grouped(const lot_shape& s, int iters);
+int run_grouped(const Args& a);          // attention only; LOT_ERR_PATH outside its set
+
 // Cross attention / non-uniform token masses.
 struct CrossWorkspace {
     size_t C1, C2, lse1, lse2, g1, g2, part_m, part_s, Y;   // plain path (status words at offset 0)

@@ -203,3 +203,46 @@ def test_alternating_inputs_on_one_workspace_stay_reproducible():
             first[rep % 2] = out.clone()
         else:
             assert torch.equal(out.view(torch.int16), first[rep % 2].view(torch.int16)), "call %d differs" % rep
+
+
+# Pivot sizes beyond 64 (the paper's runtime study goes to 256) run on the grouped kernels through
+# PATH_FUSED / AUTO; the plain kernels remain available through PATH_REFERENCE.
+LARGE_R = {
+    "r65_f32": S(W["tiny"], B=1, H=2, n=150, d=32, r=65, iters=5, seed=40),
+    "r100_f32_ragged": S(W["deit_tiny"], B=2, H=2, n=197, d=64, r=100, iters=6, seed=41),
+    "r128_bf16": S(W["long_4k"], B=1, H=2, n=3000, r=128, iters=5, seed=42),
+    "r200_bf16_d32": S(W["swin_t_s1"], B=1, H=3, n=1000, r=200, iters=5, seed=43),
+    "r256_bf16": S(W["long_4k"], B=2, H=2, n=2100, r=256, iters=4, seed=44),
+    "r256_f32_one_iteration": S(W["tiny"], B=1, H=1, n=90, d=64, r=256, iters=1, seed=45),
+}
+
+
+@pytest.mark.parametrize("name", list(LARGE_R))
+def test_large_pivot_sizes_match_oracle_on_the_grouped_kernels(name):
+    import torch
+    from oracle import lot_oracle
+    from paper_2509_23436_amd import lot
+    w = LARGE_R[name]
+    _say("case %s: %r" % (name, w))
+    x = synth.make_inputs(w)
+    O_ref, _ = lot_oracle.attention(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, threads=4)
+    dev = to_device(x, w.dtype)
+    shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
+    ws = lot.alloc_workspace(shape, w.iters)
+    ws.fill_(0xA5)
+    tol_o, _ = tolerance(w.dtype)
+    outs = {}
+    for path_name, path in (("fused", lot.PATH_FUSED), ("reference", lot.PATH_REFERENCE)):
+        out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters,
+                                    workspace=ws, path=path)
+        torch.cuda.synchronize()
+        assert lot.lot_workspace_status(ws) == 0
+        err = rel_max_err(to_host_f64(out), O_ref)
+        _say("  %s: max-norm rel err %.3e (bar %.0e)" % (path_name, err, tol_o))
+        assert err <= tol_o
+        outs[path_name] = out.clone()
+    again = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters,
+                                  workspace=ws, path=lot.PATH_FUSED)
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int16 if w.dtype == "bf16" else torch.int32),
+                       outs["fused"].view(torch.int16 if w.dtype == "bf16" else torch.int32))
