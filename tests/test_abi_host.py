@@ -67,7 +67,7 @@ def test_attention_rejects_bad_arguments_before_any_device_work(L):
                      (dict(Q=4100), -7), (dict(V=12290), -7), (dict(out=16388), -7),
                      (dict(ws=(1 << 20) + 64), -6), (dict(ws_bytes=1024), -6),
                      (dict(path=9), -9), (dict(shape=_shape(d_k=128, d_v=128), path=2), -9),
-                     (dict(shape=_shape(r=65), path=2), -9),
+                     (dict(shape=_shape(r=257), path=2), -9),
                      (dict(shape=_shape(n=0)), -2), (dict(shape=_shape(io_dtype=3)), -5)):
         assert _call_fwd(L, **kw) == code, (kw, code)
 
