@@ -119,8 +119,9 @@ def main() -> int:
                          "(used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the (batch, head) problems are independent; "
-              "see DESIGN.md for how the path would shard); re-run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (the (batch, head) problems are independent and would "
+              "shard over GPUs without communication, but no multi-GPU path is built); re-run with --gpus 1",
+              file=sys.stderr)
         return 2
 
     import torch
