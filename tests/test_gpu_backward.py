@@ -170,3 +170,32 @@ def test_backward_paths_are_bit_identical_run_to_run(path_name):
         else:
             for a, b in zip(first, bits):
                 assert torch.equal(a, b)
+
+
+def test_alternating_inputs_and_paths_on_one_workspace_stay_reproducible():
+    # Stale intermediates must never leak from one call into the next: two different inputs take turns
+    # on ONE workspace, forward and backward interleaved, and every result must equal the first one
+    # obtained for that input.
+    import torch
+    from paper_2509_23436_amd import lot
+    w = S(W["long_4k"], B=4, H=4, n=2500, iters=5, seed=78)
+    cases = []
+    for k in range(2):
+        x = synth.make_inputs(dataclasses.replace(w, seed=w.seed + 50 * k))
+        dO = synth.round_to_bf16(np.random.default_rng(k).standard_normal(x["V"].shape).astype(np.float32))
+        cases.append(to_device(dict(x, dO=dO), w.dtype))
+    shape = lot._shape_of(cases[0]["Q"], cases[0]["V"], cases[0]["Z"])
+    nbytes = max(lot.lot_attention_bwd_workspace_bytes(shape, w.iters), lot.lot_workspace_bytes(shape, w.iters))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    first = {}
+    for rep in range(24):
+        d = cases[rep % 2]
+        out = lot.lot_attention_fwd(d["Q"], d["K"], d["V"], d["Z"], d["beta"], w.eps, w.iters, workspace=ws)
+        grads = lot.lot_attention_bwd(d["Q"], d["K"], d["V"], d["Z"], d["beta"], w.eps, w.iters, d["dO"], workspace=ws)
+        torch.cuda.synchronize()
+        bits = [t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).clone() for t in (out, *grads)]
+        if rep % 2 not in first:
+            first[rep % 2] = bits
+        else:
+            for a, b in zip(first[rep % 2], bits):
+                assert torch.equal(a, b), "call %d differs" % rep
