@@ -162,7 +162,8 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * Two execution paths, chosen like the forward ones (lot_path): REFERENCE = one plain kernel per
  * step with the n x r intermediates in the workspace, any shape; FUSED = tiled MFMA kernels that
  * keep nothing of size n x r (d_k = d_v in {32, 64}, r <= 64, iters <= 32).  AUTO prefers FUSED.
- * Results are reproducible bit for bit on either path.
+ * Results are reproducible bit for bit on either path.  lot_workspace_status applies to this
+ * workspace too (the FUSED path's forward sweep waits between workgroups when it runs as one kernel).
  */
 int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out);
 int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,

@@ -271,6 +271,7 @@ int run_backward_t(const BwdArgs& a)
     float* dZ_pair = (float*)(a.ws + L.dZ_pair);   // [pairs][r][d_k]
     float* Zr = (float*)(a.ws + L.Zr);
     hipStream_t st_ = a.stream;
+    ref_mark<<<1, 1, 0, st_>>>((unsigned long long*)a.ws, next_nonce());   // no device-side waits on this path
     const size_t slab = (size_t)pairs * r;
     const size_t nelem = (size_t)pairs * n * r;
     const size_t rows = (size_t)pairs * n;
@@ -336,7 +337,7 @@ int run_backward_t(const BwdArgs& a)
 BwdWorkspace carve_bwd(const lot_shape& s, int iters)
 {
     BwdWorkspace w{};
-    size_t off = 0;
+    size_t off = 256;      // the status words come first, as in the other workspaces
     auto take = [&](size_t bytes) { size_t at = off; off += (bytes + 255) / 256 * 256; return at; };
     const size_t G = (size_t)s.B * s.H, n = s.n, r = s.r, pairs = 2 * G;
     const size_t chunks = (n + kRefChunk - 1) / kRefChunk;

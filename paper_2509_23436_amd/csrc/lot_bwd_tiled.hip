@@ -22,12 +22,18 @@
 // (Paper, "Learning": the pivots, their masses and the projections are trained by backpropagating
 // through both Sinkhorn problems and the glued composition.  The derivation is this file's.)
 //
-// One kernel launch per step; launch boundaries are the only synchronisation between workgroups:
-//   clear | T x forward pass (column sums, Gram, and at k = T the two token contractions
+// Launches:
+//   clear | forward sweep (T passes: column sums and Gram matrices; then the two token contractions
 //   U = sum W2 V, Wd = sum W1 dO) | mid (Y', dYraw) | glue (s, N, dV) | Gram reduce | recursion |
 //   assemble (dQ, dK, dZ partials) | final (dZ, dbeta).
-// Both solves share every launch (pair = side * G + g, side 0 = queries).  All reductions have a
-// fixed order except the column sums, which are exchanged as integers: results are reproducible.
+// The forward sweep is one persistent kernel when all its workgroups can be resident at once: the
+// workgroups of a pair exchange their column sums through one integer atomic per pivot that also
+// counts the contributors, and wait (bounded) for the count before the next pass; the write-out of
+// the pass's Gram matrix sits between posting and waiting, so the exchange is rarely waited for.
+// Otherwise the sweep is T + 1 launches of the same tile code, with launch boundaries as the only
+// synchronisation.  Both solves share every launch (pair = side * G + g, side 0 = queries).  All
+// reductions have a fixed order except the column sums, which are exchanged as integers: results
+// are reproducible.
 #include "lot_internal.h"
 #include "lot_tile.h"
 #include "lot_tile_ops.h"
@@ -56,7 +62,9 @@ struct BtParams {
     const float* Z; const float* beta;
     void* dQ; void* dK; void* dV;
     float* dZ; float* dbeta;
-    unsigned long long* colacc;   // [T+1][pairs][64] fixed-point column sums of W^k (k = 1..T)
+    unsigned long long* status;   // [0] = nonce of a launch in which a wait gave up, [1] = nonce of the last launch
+    unsigned long long nonce;
+    unsigned long long* colacc;   // [T+1][pairs][64] column sums of W^k (k = 1..T): contributors << 56 | fixed point
     float* ghist;                 // [T+1][pairs][64] g^k, k = 0..T-1 (padding pivots: -1e30)
     float* gram_part;             // [T][pairs][chunks][R2]
     float* gram_full;             // [T][pairs][R2]
@@ -71,6 +79,7 @@ struct BtParams {
     float* dz_part;               // [pairs][chunks][64][D]
     int G, H, B, n, r, chunks, tiles_per_wg, k, T;
     float eps, fx_scale, fx_unscale;
+    uint32_t spin_limit;
 };
 
 template <typename IO> __device__ __forceinline__ const IO* rows_of(const BtParams& p, int side)
@@ -78,88 +87,88 @@ template <typename IO> __device__ __forceinline__ const IO* rows_of(const BtPara
     return reinterpret_cast<const IO*>(side == 0 ? p.Q : p.K);
 }
 
+// A column-sum word: the number of workgroups that have contributed in the top byte, their fixed-point
+// sum below.
+constexpr int kCountShift = 56;
+constexpr unsigned long long kSumMask = (1ull << kCountShift) - 1;
+__device__ __forceinline__ float colsum_of(unsigned long long word, float unscale)
+{
+    return fmaxf((float)(long long)(word & kSumMask) * unscale, 1.0e-37f);
+}
+
 // ---------------------------------------------------------------------------------------------
-// forward pass k.  WITH_U = false: column sums and Gram matrix of W^k.  WITH_U = true (run once more
-// for k = T, after the column sums of pass T are complete): the token contraction of W^T with V
-// (keys) or dO (queries) instead -- kept apart because the two sets of accumulators do not fit the
-// register file together.
+// forward sweep.  A pass k accumulates the column sums and the Gram matrix of W^k over the
+// workgroup's tiles; the contraction pass (run once, with the potentials of pass T) accumulates the
+// token contraction of W^T with V (keys) or dO (queries) instead -- kept apart because the two sets
+// of accumulators do not fit the register file together.
 // ---------------------------------------------------------------------------------------------
+template <typename IO, int D, int RB> struct SweepShared {
+    float g[64];                                   // g^{k-1}
+    float cs[kWaves][64];
+    __attribute__((aligned(16))) float buf[64 * 64 > 64 * D ? 64 * 64 : 64 * D];
+    __attribute__((aligned(16))) uint16_t tr[kWaves * 2 * 64 * kTrStride];
+    __attribute__((aligned(16))) char zstash[StashBytes<IO, D, RB>::value];
+};
+static_assert(kWaves * 2 * 64 * kTrStride * sizeof(uint16_t) >= 64 * 64 * sizeof(float),
+              "the transposition area doubles as the second buffer of the Gram reduction");
+
+// Where a workgroup of the sweep works
+struct SweepPlace {
+    int pair, chunk, side, g, h, tile_begin, tile_end;
+};
+__device__ __forceinline__ SweepPlace sweep_place(const BtParams& p)
+{
+    SweepPlace w;
+    w.pair = blockIdx.x / p.chunks; w.chunk = blockIdx.x % p.chunks;
+    w.side = w.pair / p.G; w.g = w.pair % p.G; w.h = w.g % p.H;
+    const int ntiles = (p.n + kTileTokens - 1) / kTileTokens;
+    w.tile_begin = w.chunk * p.tiles_per_wg;
+    w.tile_end = min(ntiles, w.tile_begin + p.tiles_per_wg);
+    return w;
+}
+
+template <typename IO, int D>
+__device__ __forceinline__ void load_first_tile(Frag<IO, D>& xc, const BtParams& p, const SweepPlace& w, const IO* X,
+                                                int wave, int i, int kg)
+{
+    const int tok = min((w.tile_begin + wave) * kTileTokens + i, p.n - 1);
+    load_tokens<D>(xc, X + ((size_t)w.g * p.n + tok) * D, kg);
+}
+
+template <typename IO, int D, int RB>
+__device__ __forceinline__ void stash_head_pivots(const BtParams& p, int h, char* zstash, int lane)
+{
+    const int i = lane & 31, kg = lane >> 5;
+    Frag<IO, D> z0[RB];
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb) {
+        const int t = 32 * mb + i;
+        load_pivots<D>(z0[mb], p.Z + ((size_t)h * p.r + min(t, p.r - 1)) * D, kg, t < p.r);
+    }
+    stash_pivots<D, RB>(zstash, z0, lane);
+}
+
+// One pass over the wavefront's tiles with the potentials in sh.g.  xc holds the first tile's rows on
+// entry and, when `again`, once more on return (requested during the last tile, so that the next
+// pass does not start with a round trip to memory).
 template <typename IO, int D, int RB, bool WITH_U>
-__global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
+__device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace& w, const IO* X, const IO* vals,
+                                            SweepShared<IO, D, RB>& sh, Frag<IO, D>& xc, bool again,
+                                            int wave, int lane, float c1,
+                                            f32x16 (&cs)[RB], f32x16 (&Gm)[RB][RB], f32x16 (&U)[RB][D / 32])
 {
     constexpr int NB = D / 32;
     constexpr bool kSplit = io_is_f32<IO>::value;
-    constexpr int R = 32 * RB;
-    __shared__ float s_g[64];
-    __shared__ float s_cs[kWaves][64];
-    __shared__ __attribute__((aligned(16))) float s_buf[64 * 64 > 64 * D ? 64 * 64 : 64 * D];
-    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * 2 * 64 * kTrStride];
-    __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int i = lane & 31, kg = lane >> 5;
-    const int pairs = 2 * p.G;
-    const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
-    const int side = pair / p.G, g = pair % p.G, h = g % p.H;
-    const int n = p.n, r = p.r, k = p.k;
-    const float c1 = kLog2e / p.eps;
-    const IO* X = rows_of<IO>(p, side);
-    uint16_t* tr_hi = s_tr + (wave * 2 + 0) * 64 * kTrStride;
-    uint16_t* tr_lo = s_tr + (wave * 2 + 1) * 64 * kTrStride;
-    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
-    const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
-
-    // the first tile is requested before anything else: its latency overlaps the set-up
-    Frag<IO, D> xc;
-    {
-        const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
-        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
-    }
-
-    // g^{k-1} from the column sums of the previous launch
-    if (tid < 64) {
-        float gv = tid < r ? 0.f : kNegBig;
-        if (k > 1 && tid < r) {
-            const unsigned long long word = p.colacc[((size_t)(k - 1) * pairs + pair) * 64 + tid];
-            const float cs = fmaxf((float)(long long)word * p.fx_unscale, 1.0e-37f);
-            gv = p.ghist[((size_t)(k - 2) * pairs + pair) * 64 + tid] + p.eps * logf((float)n * p.beta[h * r + tid] / cs);
-        }
-        s_g[tid] = gv;
-        if (!WITH_U && chunk == 0) p.ghist[((size_t)(k - 1) * pairs + pair) * 64 + tid] = gv;
-    }
-    if (wave == 0) {
-        Frag<IO, D> z0[RB];
-#pragma unroll
-        for (int mb = 0; mb < RB; ++mb) {
-            const int t = 32 * mb + i;
-            load_pivots<D>(z0[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
-        }
-        stash_pivots<D, RB>(s_zstash, z0, lane);
-    }
-    __syncthreads();
-
-    f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
-#pragma unroll
-    for (int mb = 0; mb < RB; ++mb) {
-#pragma unroll
-        for (int j = 0; j < 16; ++j) cs[mb][j] = 0.f;
-#pragma unroll
-        for (int mb2 = 0; mb2 < RB; ++mb2)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) Gm[mb][mb2][j] = 0.f;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
-    }
-    const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
-
-    for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
+    const int i = lane & 31, kg = lane >> 5, n = p.n;
+    uint16_t* tr_hi = sh.tr + (wave * 2 + 0) * 64 * kTrStride;
+    uint16_t* tr_lo = sh.tr + (wave * 2 + 1) * 64 * kTrStride;
+    for (int tile = w.tile_begin + wave; tile < w.tile_end; tile += kWaves) {
         Frag<IO, D> xn = xc;
-        if (tile + kWaves < tile_end) {
+        if (tile + kWaves < w.tile_end) {
             const int tok = min((tile + kWaves) * kTileTokens + i, n - 1);
-            load_tokens<D>(xn, X + ((size_t)g * n + tok) * D, kg);
+            load_tokens<D>(xn, X + ((size_t)w.g * n + tok) * D, kg);
+        } else if (again) {
+            load_first_tile<IO, D>(xn, p, w, X, wave, i, kg);
         }
         bf16x8 vh[2][NB], vl[2][NB];
         if (WITH_U) {
@@ -167,23 +176,23 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
             for (int s = 0; s < 2; ++s) {
                 const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
                 const int left = max(1, min(8, n - t0));
-                load_values<D>(vh[s], vl[s], vals, (size_t)g * n + min(t0, n - 1), left, i);
+                load_values<D>(vh[s], vl[s], vals, (size_t)w.g * n + min(t0, n - 1), left, i);
             }
         }
         f32x16 acc[RB];
-        float w;
+        float wt;
         {
             int skew = 0;
             asm volatile("" : "+v"(skew));
             Frag<IO, D> zf[RB];
-            fetch_pivots<D, RB>(zf, s_zstash, lane, skew);
-            tile_weights<IO, D, RB>(acc, w, zf, xc, s_g, kg, c1, tile * kTileTokens + i < n);
+            fetch_pivots<D, RB>(zf, sh.zstash, lane, skew);
+            tile_weights<IO, D, RB>(acc, wt, zf, xc, sh.g, kg, c1, tile * kTileTokens + i < n);
         }
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                acc[mb][j] *= w;
+                acc[mb][j] *= wt;
                 if (!WITH_U) cs[mb][j] += acc[mb][j];
             }
         transpose_tile<RB, kSplit>(acc, tr_hi, tr_lo, i, kg);
@@ -192,14 +201,19 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
         transpose_done();
         xc = xn;
     }
-    if (WITH_U) {
-        sum_over_waves<D, RB>(U, s_buf, wave, i, kg);
-        float* up = p.u_part + ((size_t)pair * p.chunks + chunk) * 64 * D;
-        for (int e = tid; e < R * D; e += kThreads) up[e] = s_buf[e];
-        return;
-    }
+}
 
-    // column sums: one pivot per lane, then across the wavefronts, then one integer atomic per pivot
+// End of pass k: the workgroup's column sums go to one integer atomic per pivot (which also counts
+// the workgroup), its Gram matrix to this chunk's slot of gram_part.  Contains barriers.
+// Only the blocks on and above the diagonal of the (symmetric) Gram matrix are accumulated and
+// written; the reduction over the chunks mirrors them.
+template <typename IO, int D, int RB>
+__device__ __forceinline__ void finish_pass(const BtParams& p, const SweepPlace& w, SweepShared<IO, D, RB>& sh, int k,
+                                            int tid, int wave, int lane, const f32x16 (&cs)[RB], const f32x16 (&Gm)[RB][RB])
+{
+    constexpr int R = 32 * RB;
+    const int i = lane & 31, kg = lane >> 5, pairs = 2 * p.G;
+    // column sums: one pivot per lane, then across the wavefronts
     {
         float c[16 * RB];
 #pragma unroll
@@ -208,35 +222,181 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
             for (int j = 0; j < 16; ++j) c[16 * mb + j] = cs[mb][j];
         const float total = reduce_scatter_tokens<16 * RB>(c, i);
         const int q = RB == 2 ? i : i >> 1;
-        s_cs[wave][32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3)] = total;
-        if (RB == 1) s_cs[wave][32 + lane % 32] = 0.f;
+        sh.cs[wave][32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3)] = total;
+        if (RB == 1) sh.cs[wave][32 + lane % 32] = 0.f;
     }
-    __syncthreads();
-    if (tid < r) {
+    __syncthreads();      // every wavefront has also left its tile loop: sh.tr is free
+    if (tid < 64) {
         float tot = 0.f;
 #pragma unroll
-        for (int wv = 0; wv < kWaves; ++wv) tot += s_cs[wv][tid];
-        const unsigned long long word = (unsigned long long)__float2ll_rn(tot * p.fx_scale);
-        __hip_atomic_fetch_add(p.colacc + ((size_t)k * pairs + pair) * 64 + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int wv = 0; wv < kWaves; ++wv) tot += sh.cs[wv][tid];
+        const unsigned long long word = (1ull << kCountShift) + (unsigned long long)__float2ll_rn(tot * p.fx_scale);
+        __hip_atomic_fetch_add(p.colacc + ((size_t)k * pairs + w.pair) * 64 + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    // Gram matrix: block (mb, mb2) holds rows t = pivot_of(mb, j, kg), columns t' = 32 mb2 + i
-    {
-        float* gp = p.gram_part + (((size_t)(k - 1) * pairs + pair) * p.chunks + chunk) * R * R;
-        for (int turn = 0; turn < kWaves; ++turn) {
-            if (wave == turn) {
+    // Gram matrix, block (mb, mb2): rows t = pivot_of(mb, j, kg), columns t' = 32 mb2 + i.  Wavefronts
+    // 0 and 1 lay theirs down in two buffers, 2 and 3 add to them, the write-out adds the buffers.
+    float* const bufs[2] = {sh.buf, reinterpret_cast<float*>(sh.tr)};
+    for (int turn = 0; turn < 2; ++turn) {
+        if ((wave >> 1) == turn) {
+            float* const b = bufs[wave & 1];
 #pragma unroll
-                for (int mb = 0; mb < RB; ++mb)
+            for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
-                    for (int mb2 = 0; mb2 < RB; ++mb2)
+                for (int mb2 = mb; mb2 < RB; ++mb2)
 #pragma unroll
-                        for (int j = 0; j < 16; ++j) {
-                            float* dst = &s_buf[pivot_of(mb, j, kg) * R + 32 * mb2 + i];
-                            *dst = turn == 0 ? Gm[mb][mb2][j] : *dst + Gm[mb][mb2][j];
-                        }
-            }
-            __syncthreads();
+                    for (int j = 0; j < 16; ++j) {
+                        float* dst = &b[pivot_of(mb, j, kg) * R + 32 * mb2 + i];
+                        *dst = turn == 0 ? Gm[mb][mb2][j] : *dst + Gm[mb][mb2][j];
+                    }
         }
-        for (int e = tid; e < R * R; e += kThreads) gp[e] = s_buf[e];
+        __syncthreads();
+    }
+    float* gp = p.gram_part + (((size_t)(k - 1) * pairs + w.pair) * p.chunks + w.chunk) * R * R;
+    for (int e = tid; e < R * R; e += kThreads)
+        if (e % R / 32 >= e / R / 32) gp[e] = bufs[0][e] + bufs[1][e];
+}
+
+template <typename IO, int D, int RB>
+__device__ __forceinline__ void finish_contraction(const BtParams& p, const SweepPlace& w, SweepShared<IO, D, RB>& sh,
+                                                   int tid, int wave, int lane, const f32x16 (&U)[RB][D / 32])
+{
+    sum_over_waves<D, RB>(U, sh.buf, wave, lane & 31, lane >> 5);
+    float* up = p.u_part + ((size_t)w.pair * p.chunks + w.chunk) * 64 * D;
+    for (int e = tid; e < 32 * RB * D; e += kThreads) up[e] = sh.buf[e];
+}
+
+template <int RB, int NB>
+__device__ __forceinline__ void zero_pass(f32x16 (&cs)[RB], f32x16 (&Gm)[RB][RB])
+{
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cs[mb][j] = 0.f;
+#pragma unroll
+        for (int mb2 = 0; mb2 < RB; ++mb2)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) Gm[mb][mb2][j] = 0.f;
+    }
+}
+
+// g^k from g^{k-1} and the complete column sums of pass k
+__device__ __forceinline__ float next_potential(const BtParams& p, float g_prev, unsigned long long word, int h, int t)
+{
+    return g_prev + p.eps * logf((float)p.n * p.beta[h * p.r + t] / colsum_of(word, p.fx_unscale));
+}
+
+// One pass per launch (WITH_U = false: pass p.k; true: the contraction pass), for grids that cannot
+// be resident at once.
+template <typename IO, int D, int RB, bool WITH_U>
+__global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
+{
+    constexpr int NB = D / 32;
+    __shared__ SweepShared<IO, D, RB> sh;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const SweepPlace w = sweep_place(p);
+    const int pairs = 2 * p.G, r = p.r, k = p.k;
+    const IO* X = rows_of<IO>(p, w.side);
+
+    // the first tile is requested before anything else: its latency overlaps the set-up
+    Frag<IO, D> xc;
+    load_first_tile<IO, D>(xc, p, w, X, wave, lane & 31, lane >> 5);
+
+    // g^{k-1} from the column sums of the previous launch
+    if (tid < 64) {
+        float gv = tid < r ? 0.f : kNegBig;
+        if (k > 1 && tid < r)
+            gv = next_potential(p, p.ghist[((size_t)(k - 2) * pairs + w.pair) * 64 + tid],
+                                p.colacc[((size_t)(k - 1) * pairs + w.pair) * 64 + tid], w.h, tid);
+        sh.g[tid] = gv;
+        if (!WITH_U && w.chunk == 0) p.ghist[((size_t)(k - 1) * pairs + w.pair) * 64 + tid] = gv;
+    }
+    if (wave == 0) stash_head_pivots<IO, D, RB>(p, w.h, sh.zstash, lane);
+    __syncthreads();
+
+    f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
+    zero_pass<RB, NB>(cs, Gm);
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
+    const IO* vals = reinterpret_cast<const IO*>(w.side == 0 ? p.dO : p.V);
+    const float c1 = kLog2e / p.eps;
+    sweep_tiles<IO, D, RB, WITH_U>(p, w, X, vals, sh, xc, false, wave, lane, c1, cs, Gm, U);
+    if (WITH_U) finish_contraction<IO, D, RB>(p, w, sh, tid, wave, lane, U);
+    else finish_pass<IO, D, RB>(p, w, sh, k, tid, wave, lane, cs, Gm);
+}
+
+// All T passes and the contraction pass in one launch.  Requires every workgroup of a pair to be
+// resident together (the host checks the grid against the device's capacity); the waits are bounded
+// all the same, and a wait that runs out marks the status word and ends the workgroup.
+template <typename IO, int D, int RB>
+__global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
+{
+    constexpr int NB = D / 32;
+    __shared__ SweepShared<IO, D, RB> sh;
+    __shared__ int s_ok;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const SweepPlace w = sweep_place(p);
+    const int pairs = 2 * p.G, r = p.r, T = p.T;
+    const IO* X = rows_of<IO>(p, w.side);
+    const float c1 = kLog2e / p.eps;
+
+    Frag<IO, D> xc;
+    load_first_tile<IO, D>(xc, p, w, X, wave, lane & 31, lane >> 5);
+    if (wave == 0) stash_head_pivots<IO, D, RB>(p, w.h, sh.zstash, lane);
+    if (tid == 0) s_ok = 1;
+    float gv = tid < r ? 0.f : kNegBig;     // g^{k-1}_t, carried by thread t < 64
+
+    for (int k = 1; k <= T; ++k) {
+        if (tid < 64) {
+            if (k > 1) {
+                // the column sums of pass k-1 are complete once every chunk has been counted
+                const unsigned long long* src = p.colacc + ((size_t)(k - 1) * pairs + w.pair) * 64 + tid;
+                unsigned long long word = 0;
+                bool done = false;
+                for (uint32_t it = 0; it < p.spin_limit; ++it) {
+                    word = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    done = (int)(word >> kCountShift) == p.chunks;
+                    if (__all(done)) break;
+                    if ((it & 63u) == 63u && __hip_atomic_load(p.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nonce) break;
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                if (!__all(done)) {
+                    if (tid == 0) {
+                        __hip_atomic_store(p.status, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        s_ok = 0;
+                    }
+                } else if (tid < r) {
+                    gv = next_potential(p, gv, word, w.h, tid);
+                }
+            }
+            sh.g[tid] = gv;
+            if (w.chunk == 0) p.ghist[((size_t)(k - 1) * pairs + w.pair) * 64 + tid] = gv;
+        }
+        __syncthreads();      // also: the previous pass's write-out has finished with sh.buf and sh.tr
+        if (!s_ok) return;
+        f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
+        zero_pass<RB, NB>(cs, Gm);
+        sweep_tiles<IO, D, RB, false>(p, w, X, nullptr, sh, xc, true, wave, lane, c1, cs, Gm, U);
+        finish_pass<IO, D, RB>(p, w, sh, k, tid, wave, lane, cs, Gm);
+    }
+    __syncthreads();
+    {
+        f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
+        const IO* vals = reinterpret_cast<const IO*>(w.side == 0 ? p.dO : p.V);
+        sweep_tiles<IO, D, RB, true>(p, w, X, vals, sh, xc, false, wave, lane, c1, cs, Gm, U);
+        __syncthreads();
+        finish_contraction<IO, D, RB>(p, w, sh, tid, wave, lane, U);
     }
 }
 
@@ -262,8 +422,8 @@ __global__ void bt_mid(BtParams p)
             u0 += up[(size_t)c * 64 * D]; u1 += up[(size_t)(c + 1) * 64 * D];
         }
         if (c < p.chunks) { w0 += wp[(size_t)c * 64 * D]; u0 += up[(size_t)c * 64 * D]; }
-        const float cs1 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
-        const float cs2 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
+        const float cs1 = colsum_of(p.colacc[((size_t)T * pairs + g) * 64 + t], p.fx_unscale);
+        const float cs2 = colsum_of(p.colacc[((size_t)T * pairs + p.G + g) * 64 + t], p.fx_unscale);
         y = (u0 + u1) / cs2;
         dy = (float)p.n * (w0 + w1) / cs1;
     }
@@ -281,8 +441,8 @@ __global__ void bt_mid2(BtParams p)
     if (t < p.r) {
         for (int c = 0; c < D; ++c) dot = fmaf(p.dyraw[(size_t)idx * D + c], p.yp[(size_t)idx * D + c], dot);
         const float b = p.beta[h * p.r + t];
-        r1 = b / fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
-        r2 = b / fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * 64 + t] * p.fx_unscale, 1.0e-37f);
+        r1 = b / colsum_of(p.colacc[((size_t)T * pairs + g) * 64 + t], p.fx_unscale);
+        r2 = b / colsum_of(p.colacc[((size_t)T * pairs + p.G + g) * 64 + t], p.fx_unscale);
     }
     p.db_glue[idx] = -dot;
     p.rhop[(size_t)g * 64 + t] = r1;
@@ -438,14 +598,19 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Gram reduce: gram_full[k][pair] = sum over chunks (index order)
+// Gram reduce: gram_full[k][pair] = sum over chunks (index order).  The partial results hold the
+// 32 x 32 blocks on and above the diagonal; a sum above the diagonal blocks is also written to its
+// mirror image.
 // ---------------------------------------------------------------------------------------------
-__global__ void bt_gram_reduce(BtParams p, int R2, size_t total)
+__global__ void bt_gram_reduce(BtParams p, int R, size_t total)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;    // (kp, e)
     if (idx >= total) return;
+    const int R2 = R * R;
     const size_t kp = idx / R2;
     const int e = (int)(idx % R2);
+    const int row = e / R, col = e % R;
+    if (col / 32 < row / 32) return;
     const float* src = p.gram_part + kp * p.chunks * R2 + e;
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     int c = 0;
@@ -454,7 +619,9 @@ __global__ void bt_gram_reduce(BtParams p, int R2, size_t total)
         a2 += src[(size_t)(c + 2) * R2]; a3 += src[(size_t)(c + 3) * R2];
     }
     for (; c < p.chunks; ++c) a0 += src[(size_t)c * R2];
-    p.gram_full[idx] = (a0 + a1) + (a2 + a3);
+    const float sum = (a0 + a1) + (a2 + a3);
+    p.gram_full[idx] = sum;
+    if (col / 32 > row / 32) p.gram_full[kp * R2 + (size_t)col * R + row] = sum;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -478,7 +645,7 @@ __global__ void bt_recursion(BtParams p, int R)
             nn += p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 1) * 64 + t];
         }
     auto colsum = [&](int k) {
-        return fmaxf((float)(long long)p.colacc[((size_t)k * pairs + pair) * 64 + t] * p.fx_unscale, 1.0e-37f) * a;   // c^k_t
+        return colsum_of(p.colacc[((size_t)k * pairs + pair) * 64 + t], p.fx_unscale) * a;   // c^k_t
     };
     auto gram_times = [&](int k, float v) {      // (M^k v)_t; v is meaningful in the threads with q == 0
         if (q == 0) s_v[t] = live ? v : 0.f;
@@ -748,10 +915,12 @@ __global__ void bt_final(BtParams p, int D)
     else p.dbeta[h * p.r + t] = acc;
 }
 
-__global__ void bt_clear(unsigned long long* p, size_t count)
+// zeroes the column-sum words and records the launch in the status area
+__global__ void bt_clear(unsigned long long* p, size_t count, unsigned long long* status, unsigned long long nonce)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx < count) p[idx] = 0ull;
+    if (idx == 0) status[1] = nonce;
 }
 
 template <typename IO, int D, int RB>
@@ -761,19 +930,41 @@ int launch_all(const BwdArgs& a, BtParams p)
     const int pairs = 2 * p.G, T = a.iters, R = 32 * RB;
     hipStream_t st = a.stream;
     const size_t words = (size_t)(T + 1) * pairs * 64;
-    bt_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words);
+    bt_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words, p.status, p.nonce);
     const unsigned grid = (unsigned)pairs * p.chunks;
-    for (int k = 1; k <= T; ++k) {
-        p.k = k;
-        bt_forward<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
+    // The persistent sweep needs the workgroups of a pair resident together: the whole grid fits the
+    // device, or a pair is a single workgroup (which then waits for nobody but itself).
+    bool persistent = p.chunks == 1;
+    if (!persistent && p.chunks <= 255) {
+        static thread_local int capacity_cache[8] = {0};   // per device ordinal
+        int dev = 0;
+        LOT_HIP_CHECK(hipGetDevice(&dev));
+        int capacity = (dev >= 0 && dev < 8) ? capacity_cache[dev] : 0;
+        if (capacity == 0) {
+            int per_cu = 0, cus = 0;
+            LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bt_sweep<IO, D, RB>, kThreads, 0));
+            LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+            capacity = per_cu * cus;
+            if (dev >= 0 && dev < 8) capacity_cache[dev] = capacity;
+        }
+        persistent = (int)grid <= capacity;
     }
-    bt_forward<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);     // k = T once more: the contractions
+    if (persistent) {
+        bt_sweep<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
+    } else {
+        for (int k = 1; k <= T; ++k) {
+            p.k = k;
+            bt_forward<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
+        }
+        p.k = T;
+        bt_forward<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);     // the contractions, with g^{T-1}
+    }
     bt_mid<D><<<(unsigned)((p.G * 64 * D + 255) / 256), 256, 0, st>>>(p);
     bt_mid2<D><<<(unsigned)((p.G * 64 + 255) / 256), 256, 0, st>>>(p);
     bt_glue<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
     {
         const size_t total = (size_t)T * pairs * R * R;
-        bt_gram_reduce<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(p, R * R, total);
+        bt_gram_reduce<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(p, R, total);
     }
     bt_recursion<<<pairs, 256, 0, st>>>(p, R);
     const size_t dyn = (size_t)T * 2 * 64 * sizeof(float);
@@ -794,7 +985,7 @@ bool bwd_tiled_supports(const lot_shape& s, int iters)
 BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters)
 {
     BwdTiledWorkspace w{};
-    size_t off = 0;
+    size_t off = 256;      // the status words come first, as in the other workspaces
     auto take = [&](size_t bytes) { size_t at = off; off += (bytes + 255) / 256 * 256; return at; };
     const size_t G = (size_t)s.B * s.H, pairs = 2 * G, T = iters, D = s.d_k;
     const size_t ntiles = ((size_t)s.n + kTileTokens - 1) / kTileTokens;
@@ -827,6 +1018,9 @@ int run_backward_tiled(const BwdArgs& a)
     BtParams p{};
     p.Q = a.Q; p.K = a.K; p.V = a.V; p.dO = a.dO; p.Z = a.Z; p.beta = a.beta;
     p.dQ = a.dQ; p.dK = a.dK; p.dV = a.dV; p.dZ = a.dZ; p.dbeta = a.dbeta;
+    p.status = (unsigned long long*)a.ws;
+    p.nonce = next_nonce();
+    p.spin_limit = 1u << 21;
     p.colacc = (unsigned long long*)(a.ws + L.colacc);
     p.ghist = (float*)(a.ws + L.ghist);
     p.gram_part = (float*)(a.ws + L.gram_part);
@@ -843,8 +1037,9 @@ int run_backward_tiled(const BwdArgs& a)
     p.G = s.B * s.H; p.H = s.H; p.B = s.B; p.n = s.n; p.r = s.r; p.chunks = L.chunks; p.tiles_per_wg = tiles_per_wg_for(s); p.T = a.iters;
     p.eps = a.eps;
     {
-        // column sums of a row-normalised kernel are at most n: 2^(62 - ceil(log2(n + 1))) never overflows
-        int frac = 62 - (int)std::ceil(std::log2((double)s.n + 1.0));
+        // column sums of a row-normalised kernel are at most n: with 2^(55 - ceil(log2(n + 1))) units per
+        // one the sum stays below 2^55, clear of the contributor count in the top byte
+        int frac = 55 - (int)std::ceil(std::log2((double)s.n + 1.0));
         if (frac > 40) frac = 40;
         p.fx_scale = std::ldexp(1.0f, frac);
         p.fx_unscale = std::ldexp(1.0f, -frac);

@@ -91,6 +91,7 @@ def test_backward_runs_are_bit_identical_and_ignore_workspace_contents():
         got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, dev["dO"],
                                     workspace=ws)
         torch.cuda.synchronize()
+        assert lot.lot_workspace_status(ws) == 0          # whatever the status words held before
         outs.append([g.clone() for g in got])
     for other in outs[1:]:
         for a, b in zip(outs[0], other):
@@ -102,11 +103,16 @@ def test_backward_runs_are_bit_identical_and_ignore_workspace_contents():
 # the float64 oracle differentiates a sample of the (batch, head) problems one by one.  A problem's
 # dQ, dK, dV depend on that problem alone; dZ and dbeta are sums over the batch, so for them the
 # library is run on the sampled problems only (batch of one per head) and compared in full.
+# The forward sweep of the tiled path has two forms; the shapes below cover both: one persistent
+# kernel (whole grid resident: deit_tiny, swin_t_s1, long_*; or one workgroup per pair on a grid
+# larger than the device: bert_base) and one launch per pass (many_chunks: 128 pairs x 5 chunks).
 FULL = {
-    "deit_tiny": [0, 191],
-    "swin_t_s1": [0, 47],
-    "long_4k": [5],
-    "long_16k": [9],
+    "deit_tiny": (W["deit_tiny"], [0, 191]),
+    "bert_base": (W["bert_base"], [0, 383]),
+    "swin_t_s1": (W["swin_t_s1"], [0, 47]),
+    "long_4k": (W["long_4k"], [5]),
+    "long_16k": (W["long_16k"], [9]),
+    "many_chunks": (S(W["swin_t_s1"], B=8, H=8, n=10240, iters=4, seed=77), [3, 60]),
 }
 
 
@@ -115,7 +121,7 @@ def test_backward_full_size_on_sampled_problems(name):
     import torch
     from oracle import lot_oracle_bwd
     from paper_2509_23436_amd import lot
-    w = W[name]
+    w, problems = FULL[name]
     _say("workload %r" % (w,))
     x = synth.make_inputs(w)
     rng = np.random.default_rng(w.seed + 17)
@@ -128,7 +134,7 @@ def test_backward_full_size_on_sampled_problems(name):
     tol = 2e-2 if w.dtype == "bf16" else 1e-4
     for nm, g in zip(("dQ", "dK", "dV", "dZ", "dbeta"), got):
         assert torch.isfinite(g.float()).all(), nm
-    for gi in FULL[name]:
+    for gi in problems:
         b, h = gi // w.H, gi % w.H
         sl = lambda t: np.ascontiguousarray(t[b:b + 1, h:h + 1])           # noqa: E731
         (dQ_r, dK_r, dV_r, dZ_r, db_r), _ = lot_oracle_bwd.attention_bwd(
