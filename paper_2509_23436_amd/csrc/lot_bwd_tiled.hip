@@ -34,6 +34,8 @@
 // synchronisation.  Both solves share every launch (pair = side * G + g, side 0 = queries).  All
 // reductions have a fixed order except the column sums, which are exchanged as integers: results
 // are reproducible.
+#include <cstdlib>
+
 #include "lot_internal.h"
 #include "lot_tile.h"
 #include "lot_tile_ops.h"
@@ -80,6 +82,7 @@ struct BtParams {
     int G, H, B, n, r, chunks, tiles_per_wg, k, T;
     float eps, fx_scale, fx_unscale;
     uint32_t spin_limit;
+    float sum_lo, sum_hi;         // row sums outside [sum_lo, sum_hi] make the assemble kernel re-shift its rows
 };
 
 template <typename IO> __device__ __forceinline__ const IO* rows_of(const BtParams& p, int side)
@@ -778,45 +781,58 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
 #pragma unroll
             for (int j = 0; j < 16; ++j) sc[mb][j] *= c1;
 
-        // one iteration's share: dacc += W^k (dP - e_i), with W^k rebuilt from the scaled similarities
-        // and that iteration's potentials (pot, LDS, already times c1)
-        auto add_iteration = [&](const float* pot, f32x16 (&dp)[RB]) {
+        // One iteration's share: dacc += W^k (dP - e_i), with W^k rebuilt from the scaled similarities
+        // and that iteration's potentials (pot, LDS, already times c1).  W^k = e / sum(e) with
+        // e = exp2(x - shift) for ANY row shift that keeps the row sum well inside the fp32 range, so
+        // the shift is not recomputed per iteration: it is the row maximum of the first iteration
+        // processed (folded into sc), and the maxima of the others differ from it by the change of
+        // the potentials, a few binary orders.  The row sums are checked; if one leaves the safe range
+        // the rows are re-shifted by this iteration's maxima and the iteration is redone (its sums
+        // then lie in [1, 64]).
+        auto add_iteration = [&](const float* pot, const f32x16 (&dp)[RB], bool fold) {
             f32x16 e[RB];
-            load_pivot_vector<RB>(e, pot + skew, kg);
-            float m0 = -INFINITY, m1 = -INFINITY;
-#pragma unroll
-            for (int mb = 0; mb < RB; ++mb)
-#pragma unroll
-                for (int j = 0; j < 16; j += 2) {
-                    e[mb][j] += sc[mb][j];
-                    e[mb][j + 1] += sc[mb][j + 1];
-                    m0 = fmaxf(m0, e[mb][j]);
-                    m1 = fmaxf(m1, e[mb][j + 1]);
-                }
-            const float m = pair_max(fmaxf(m0, m1));
-            float s0 = 0.f, s1 = 0.f, d0 = 0.f, d1 = 0.f;
-#pragma unroll
-            for (int mb = 0; mb < RB; ++mb)
-#pragma unroll
-                for (int j = 0; j < 16; j += 2) {
-                    const float e0 = exp2_fast(e[mb][j] - m), e1 = exp2_fast(e[mb][j + 1] - m);
-                    e[mb][j] = e0; e[mb][j + 1] = e1;
-                    s0 += e0; s1 += e1;
-                    d0 = fmaf(dp[mb][j], e0, d0);
-                    d1 = fmaf(dp[mb][j + 1], e1, d1);
-                }
             float ssum, sdot;
-            {
+            for (;;) {
+                load_pivot_vector<RB>(e, pot + skew, kg);
+                if (fold) {
+                    float m0 = -INFINITY, m1 = -INFINITY;
+#pragma unroll
+                    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                        for (int j = 0; j < 16; j += 2) {
+                            m0 = fmaxf(m0, e[mb][j] + sc[mb][j]);
+                            m1 = fmaxf(m1, e[mb][j + 1] + sc[mb][j + 1]);
+                        }
+                    const float m = pair_max(fmaxf(m0, m1));
+#pragma unroll
+                    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) sc[mb][j] -= m;
+                }
+                float s0 = 0.f, s1 = 0.f, d0 = 0.f, d1 = 0.f;
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; j += 2) {
+                        const float e0 = exp2_fast(e[mb][j] + sc[mb][j]), e1 = exp2_fast(e[mb][j + 1] + sc[mb][j + 1]);
+                        e[mb][j] = e0; e[mb][j + 1] = e1;
+                        s0 += e0; s1 += e1;
+                        d0 = fmaf(dp[mb][j], e0, d0);
+                        d1 = fmaf(dp[mb][j + 1], e1, d1);
+                    }
                 float lo, hi;
                 both_halves(s0 + s1, lo, hi); ssum = lo + hi;
                 both_halves(d0 + d1, lo, hi); sdot = lo + hi;
+                const bool safe = ssum >= p.sum_lo && ssum <= p.sum_hi;      // false for NaN too
+                if (fold || __all(safe)) break;
+                fold = true;
             }
             const float w = valid ? rcp_fast(ssum) : 0.f;
-            const float ei = sdot * w;                    // e^k_i = sum_t dP_it W_it
+            const float nwe = -(sdot * w) * w;            // -w e^k_i,  e^k_i = sum_t dP_it W_it
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(e[mb][j] * w, dp[mb][j] - ei, dacc[mb][j]);
+                for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(e[mb][j], fmaf(dp[mb][j], w, nwe), dacc[mb][j]);
         };
         {
             // last iteration: dP^T = dGamma rho + dc^T with rho_t = beta_t / c^T_t = n rho'_t
@@ -839,12 +855,12 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
 #pragma unroll
                     for (int j = 0; j < 16; ++j) dp[mb][j] = fmaf(dp[mb][j] * (float)n, rho[mb][j], dc[mb][j]);
             }
-            add_iteration(s_hist + ((T - 1) * 2 + 0) * 64, dp);
+            add_iteration(s_hist + ((T - 1) * 2 + 0) * 64, dp, true);
         }
         for (int k = T - 1; k >= 1; --k) {
             f32x16 dp[RB];
             load_pivot_vector<RB>(dp, s_hist + ((k - 1) * 2 + 1) * 64 + skew, kg);
-            add_iteration(s_hist + ((k - 1) * 2 + 0) * 64, dp);
+            add_iteration(s_hist + ((k - 1) * 2 + 0) * 64, dp, false);
         }
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
@@ -1021,6 +1037,18 @@ int run_backward_tiled(const BwdArgs& a)
     p.status = (unsigned long long*)a.ws;
     p.nonce = next_nonce();
     p.spin_limit = 1u << 21;
+    {
+        // 2^-40 .. 2^40 leaves every exponential that matters (down to 2^-24 of the row maximum) far from
+        // the ends of the fp32 range.  LOT_BWD_RESHIFT_BITS narrows the range: a testing aid that makes
+        // the re-shifting path run on ordinary inputs (0: practically every iteration is redone).
+        int bits = 40;
+        if (const char* e = std::getenv("LOT_BWD_RESHIFT_BITS")) {
+            const int v = std::atoi(e);
+            if (v >= 0 && v <= 40) bits = v;
+        }
+        p.sum_lo = std::ldexp(1.0f, -bits);
+        p.sum_hi = std::ldexp(1.0f, bits);
+    }
     p.colacc = (unsigned long long*)(a.ws + L.colacc);
     p.ghist = (float*)(a.ws + L.ghist);
     p.gram_part = (float*)(a.ws + L.gram_part);

@@ -99,6 +99,34 @@ def test_backward_runs_are_bit_identical_and_ignore_workspace_contents():
                                b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
 
 
+@pytest.mark.parametrize("bits", ["0", "3"])
+def test_reshifted_rows_give_the_same_gradients(bits, monkeypatch):
+    """The tiled path shifts a tile's exponents once and re-shifts only when a row sum leaves a safe
+    range; with the range narrowed from the host (0: practically always, 3: in some iterations) the
+    re-shifting branch runs on ordinary inputs and must still meet the oracle's bar."""
+    import torch
+    from oracle import lot_oracle_bwd
+    from paper_2509_23436_amd import lot
+    monkeypatch.setenv("LOT_BWD_RESHIFT_BITS", bits)
+    for name in ("eps_small_f32", "bf16_d64_r64"):
+        w = CASES[name]
+        _say("case %s, re-shift range 2^+-%s" % (name, bits))
+        x = synth.make_inputs(w)
+        dO = np.random.default_rng(w.seed + 17).standard_normal(x["V"].shape).astype(np.float32)
+        if w.dtype == "bf16":
+            dO = synth.round_to_bf16(dO)
+        refs, _ = lot_oracle_bwd.attention_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, dO)
+        dev = to_device(dict(x, dO=dO), w.dtype)
+        got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, dev["dO"],
+                                    path=lot.PATH_FUSED)
+        torch.cuda.synchronize()
+        tol = 2e-2 if w.dtype == "bf16" else 1e-4
+        for nm, g, ref in zip(("dQ", "dK", "dV", "dZ", "dbeta"), got, refs):
+            err = rel_max_err(to_host_f64(g), ref)
+            _say("  %-5s max-norm rel err %.3e (bar %.0e)" % (nm, err, tol))
+            assert err <= tol, nm
+
+
 # Full benchmark sizes: the library runs the WHOLE workload (launch configuration of the benchmark);
 # the float64 oracle differentiates a sample of the (batch, head) problems one by one.  A problem's
 # dQ, dK, dV depend on that problem alone; dZ and dbeta are sums over the batch, so for them the
