@@ -164,9 +164,11 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * keep nothing of size n x r (d_k = d_v in {32, 64}, r <= 64, iters <= 32).  AUTO prefers FUSED.
  * Results are reproducible bit for bit on either path.  lot_workspace_status applies to this
  * workspace too (the FUSED path's forward sweep waits between workgroups when it runs as one kernel).
- * Testing aid: the environment variable LOT_BWD_RESHIFT_BITS (0..40, default 40), read at each call,
- * narrows the range of row sums the FUSED path accepts before it re-shifts a tile's exponents, so
- * that this rarely taken branch runs on ordinary inputs; results agree to rounding for any value.
+ * Testing aid: the FUSED path rebuilds each tile's row-normalised kernels for all iterations with ONE
+ * shift per row instead of a maximum per iteration, and re-shifts when a row sum leaves
+ * [2^-40, 2^40]; the environment variable LOT_RESHIFT_BITS (0..40, read at each call) narrows that
+ * range to 2^-bits .. 2^bits so that the rarely taken branch runs on ordinary inputs (0: practically
+ * every iteration takes it).  Results agree to rounding for every value.
  */
 int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out);
 int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,

@@ -2,6 +2,7 @@
 #include <atomic>
 #include <chrono>
 #include <cmath>
+#include <cstdlib>
 #include <cstdio>
 #include <cstring>
 
@@ -22,6 +23,16 @@ unsigned long long next_nonce()
         (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() << 20};
     unsigned long long v = counter.fetch_add(1) + 1;
     return v ? v : counter.fetch_add(1) + 1;
+}
+
+float reshift_limit()
+{
+    int bits = 40;
+    if (const char* e = std::getenv("LOT_RESHIFT_BITS")) {
+        const int v = std::atoi(e);
+        if (v >= 0 && v <= 40) bits = v;
+    }
+    return std::ldexp(1.0f, bits);
 }
 
 static int validate_shape(const lot_shape* s)

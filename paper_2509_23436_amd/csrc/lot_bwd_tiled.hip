@@ -1037,18 +1037,8 @@ int run_backward_tiled(const BwdArgs& a)
     p.status = (unsigned long long*)a.ws;
     p.nonce = next_nonce();
     p.spin_limit = 1u << 21;
-    {
-        // 2^-40 .. 2^40 leaves every exponential that matters (down to 2^-24 of the row maximum) far from
-        // the ends of the fp32 range.  LOT_BWD_RESHIFT_BITS narrows the range: a testing aid that makes
-        // the re-shifting path run on ordinary inputs (0: practically every iteration is redone).
-        int bits = 40;
-        if (const char* e = std::getenv("LOT_BWD_RESHIFT_BITS")) {
-            const int v = std::atoi(e);
-            if (v >= 0 && v <= 40) bits = v;
-        }
-        p.sum_lo = std::ldexp(1.0f, -bits);
-        p.sum_hi = std::ldexp(1.0f, bits);
-    }
+    p.sum_hi = reshift_limit();
+    p.sum_lo = 1.0f / p.sum_hi;
     p.colacc = (unsigned long long*)(a.ws + L.colacc);
     p.ghist = (float*)(a.ws + L.ghist);
     p.gram_part = (float*)(a.ws + L.gram_part);

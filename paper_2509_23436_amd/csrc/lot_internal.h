@@ -200,6 +200,14 @@ hipError_t& last_hip_error();
 // it, so that nothing in the workspace has to be cleared by the host or by an extra kernel.
 unsigned long long next_nonce();
 
+// The backward assemble kernel normalises the rows of exponentials of all iterations of a tile with
+// one shift per row instead of each iteration's exact row maximum, checks the row sums, and re-shifts
+// when a sum leaves [1/limit, limit].  2^40 by default: every exponential that matters (down to 2^-24
+// of the row maximum) then stays far from the ends of the fp32 range.  The environment variable
+// LOT_RESHIFT_BITS (0..40), read at each call, lowers the limit to 2^bits: a testing aid that makes
+// the re-shifting branch run on ordinary inputs (0: practically every iteration takes it).
+float reshift_limit();
+
 #define LOT_HIP_CHECK(expr)                                   \
     do {                                                      \
         hipError_t e_ = (expr);                               \

@@ -107,7 +107,7 @@ def test_reshifted_rows_give_the_same_gradients(bits, monkeypatch):
     import torch
     from oracle import lot_oracle_bwd
     from paper_2509_23436_amd import lot
-    monkeypatch.setenv("LOT_BWD_RESHIFT_BITS", bits)
+    monkeypatch.setenv("LOT_RESHIFT_BITS", bits)
     for name in ("eps_small_f32", "bf16_d64_r64"):
         w = CASES[name]
         _say("case %s, re-shift range 2^+-%s" % (name, bits))
