@@ -21,6 +21,11 @@ forms (one pivot: O = beta_1 mean(V), which fixes dV and dbeta and makes dQ, dK,
 shift of all pivots changes no coupling, so the pivot gradients of a head sum to zero; O is linear
 in V, so dV = A^T dO with the dense plan A = n P built by the C oracle).
 
+The [CLS] variant ("[CLS] under DS attention") is differentiated the same way: its forward (row 0 a
+softmax row over all keys, rows 1.. the method among the other tokens) written with plain torch
+operations, pinned by the numpy/C oracle of that variant, by its central finite differences, and by
+the two cases in which one of the two parts receives no gradient.
+
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import this module.
 """
 from __future__ import annotations
@@ -64,4 +69,24 @@ def attention_bwd(Q, K, V, Z, beta, eps, T, dO):
     O = forward(*t, float(eps), int(T))
     loss = (O * torch.tensor(np.asarray(dO, dtype=np.float64))).sum()
     grads = torch.autograd.grad(loss, t)
+    return tuple(g.detach().numpy() for g in grads), O.detach().numpy()
+
+
+def forward_cls(Q, K, V, Z, beta, eps, T, beta_cls):
+    """[CLS] variant: row 0 = softmax_j(beta_cls[b,h] <q_0, k_j>) V over all n keys; rows 1..n-1 =
+    `forward` on tokens 1..n-1.  beta_cls is a [B,H] tensor (one temperature per problem)."""
+    inner = forward(Q[..., 1:, :], K[..., 1:, :], V[..., 1:, :], Z, beta, eps, T)
+    score = beta_cls[..., None] * torch.einsum("bhc,bhnc->bhn", Q[..., 0, :], K)
+    row0 = torch.einsum("bhn,bhnc->bhc", torch.softmax(score, dim=-1), V)
+    return torch.cat([row0[..., None, :], inner], dim=-2)
+
+
+def attention_cls_bwd(Q, K, V, Z, beta, eps, T, beta_cls, dO):
+    """Gradients of <O, dO> for the [CLS] variant with respect to Q, K, V, Z, beta and, per (b, h)
+    problem, the temperature (array [B,H]; its sum is the gradient of a shared scalar)."""
+    t = [torch.tensor(np.asarray(x, dtype=np.float64), requires_grad=True) for x in (Q, K, V, Z, beta)]
+    bc = torch.full(t[0].shape[:2], float(beta_cls), dtype=torch.float64, requires_grad=True)
+    O = forward_cls(*t, float(eps), int(T), bc)
+    loss = (O * torch.tensor(np.asarray(dO, dtype=np.float64))).sum()
+    grads = torch.autograd.grad(loss, t + [bc])
     return tuple(g.detach().numpy() for g in grads), O.detach().numpy()

@@ -59,3 +59,84 @@ def test_rows_of_the_hybrid_attention_matrix_sum_to_one(oracle):
     assert np.abs(A.sum(axis=-1) - 1.0).max() <= 1e-10
     assert np.abs(A[:, :, 1:, 0]).max() == 0.0
     assert np.abs(A[:, :, 1:, 1:].sum(axis=-2) - 1.0).max() <= 1e-9
+
+
+# ---- backward of the [CLS] variant (oracle.lot_oracle_bwd.attention_cls_bwd)
+
+def _bwd_case(seed=310, **kw):
+    w, x = _case(seed=seed, **kw)
+    dO = np.random.default_rng(seed + 1).standard_normal(x["V"].shape)
+    return w, x, dO
+
+
+def test_forward_of_the_cls_backward_oracle_equals_the_cls_oracle(oracle):
+    from oracle import lot_oracle_bwd
+    for kw in (dict(), dict(n=9, r=3), dict(eps=0.05)):
+        w, x, dO = _bwd_case(**kw)
+        _, O_t = lot_oracle_bwd.attention_cls_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, 0.7, dO)
+        O_c = oracle.attention_cls(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, 0.7)
+        assert np.abs(O_t - O_c).max() <= 1e-12 * max(1.0, np.abs(O_c).max())
+
+
+def test_cls_gradients_match_central_differences_of_the_cls_oracle(oracle):
+    from oracle import lot_oracle_bwd
+    w, x, dO = _bwd_case(n=14, r=4)
+    bc = 1.3
+    grads, _ = lot_oracle_bwd.attention_cls_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, bc, dO)
+    loss = lambda y, b: float((oracle.attention_cls(y["Q"], y["K"], y["V"], y["Z"], y["beta"], w.eps, w.iters, b) * dO).sum())  # noqa: E731
+    rng = np.random.default_rng(6)
+    h = 1e-6
+    for name, g in zip(("Q", "K", "V", "Z", "beta"), grads[:5]):
+        for _ in range(3):
+            v = rng.standard_normal(x[name].shape)
+            if name == "beta":
+                v *= 0.1 * x["beta"]
+            xp = dict(x); xm = dict(x)
+            xp[name] = x[name] + h * v
+            xm[name] = x[name] - h * v
+            fd = (loss(xp, bc) - loss(xm, bc)) / (2 * h)
+            an = float((g * v).sum())
+            assert abs(fd - an) <= 2e-6 * max(1.0, abs(an), abs(fd)), (name, fd, an)
+    # the temperature: the per-problem derivatives add up to that of the shared scalar
+    fd = (loss(x, bc + h) - loss(x, bc - h)) / (2 * h)
+    assert abs(fd - grads[5].sum()) <= 2e-6 * max(1.0, abs(fd))
+    assert grads[5].shape == x["Q"].shape[:2]
+
+
+def test_gradient_only_into_the_cls_row_is_textbook_softmax_attention(oracle):
+    """dO zero outside row 0: the doubly-stochastic part gets nothing (dZ = dbeta = 0, dQ rows >= 1
+    zero) and the rest is the backward of one softmax-attention row, written out here."""
+    from oracle import lot_oracle_bwd
+    w, x, dO = _bwd_case()
+    dO[:, :, 1:] = 0.0
+    bc = 0.9
+    (dQ, dK, dV, dZ, db, dbc), _ = lot_oracle_bwd.attention_cls_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"],
+                                                                    w.eps, w.iters, bc, dO)
+    assert np.abs(dZ).max() == 0.0 and np.abs(db).max() == 0.0 and np.abs(dQ[:, :, 1:]).max() == 0.0
+    for b in range(x["Q"].shape[0]):
+        for h in range(x["Q"].shape[1]):
+            q, K, V, do = x["Q"][b, h, 0], x["K"][b, h], x["V"][b, h], dO[b, h, 0]
+            raw = K @ q
+            p = scipy.special.softmax(bc * raw)
+            dp = V @ do
+            a = p * (dp - p @ dp)
+            assert np.allclose(dV[b, h], np.outer(p, do), rtol=0, atol=1e-13)
+            assert np.allclose(dK[b, h], bc * np.outer(a, q), rtol=0, atol=1e-13)
+            assert np.allclose(dQ[b, h, 0], bc * (a @ K), rtol=0, atol=1e-13)
+            assert abs(dbc[b, h] - a @ raw) <= 1e-13
+
+
+def test_gradient_only_into_the_other_rows_is_the_plain_backward_on_the_other_tokens(oracle):
+    from oracle import lot_oracle_bwd
+    w, x, dO = _bwd_case()
+    dO[:, :, 0] = 0.0
+    (dQ, dK, dV, dZ, db, dbc), _ = lot_oracle_bwd.attention_cls_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"],
+                                                                    w.eps, w.iters, 0.9, dO)
+    inner, _ = lot_oracle_bwd.attention_bwd(x["Q"][:, :, 1:], x["K"][:, :, 1:], x["V"][:, :, 1:], x["Z"], x["beta"],
+                                            w.eps, w.iters, dO[:, :, 1:])
+    for got, ref in zip((dQ, dK, dV), inner[:3]):
+        assert np.abs(got[:, :, 0]).max() == 0.0
+        assert np.abs(got[:, :, 1:] - ref).max() <= 1e-13 * max(1.0, np.abs(ref).max())
+    assert np.abs(dZ - inner[3]).max() <= 1e-13 * max(1.0, np.abs(inner[3]).max())
+    assert np.abs(db - inner[4]).max() <= 1e-13 * max(1.0, np.abs(inner[4]).max())
+    assert np.abs(dbc).max() == 0.0
