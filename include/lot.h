@@ -181,6 +181,25 @@ int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K,
                            void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
+ * Backward of lot_attention_cls_fwd (same inputs, eps, iters, beta_cls; dO = dL/dout, all n rows).
+ * dQ, dK, dV, dZ, dbeta as in lot_attention_bwd: rows 1 .. n-1 carry the gradient of the
+ * doubly-stochastic part plus, in dK and dV, the share of the [CLS] row; row 0 of dQ is the gradient
+ * of the [CLS] query, row 0 of dK and dV that of the [CLS] key and value (which only the softmax row
+ * sees).  dbeta_cls [B,H] fp32: the derivative with respect to beta_cls PER (batch, head) problem --
+ * sum it for a temperature shared by all of them.  Workspace: lot_attention_bwd_workspace_bytes of
+ * the full shape.  Paths and reproducibility as for lot_attention_bwd; the softmax row is one plain
+ * kernel (one workgroup per problem) on either path.
+ */
+int lot_attention_cls_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                          const float* Z, const float* beta, float eps, int iters, float beta_cls, const void* dO,
+                          void* dQ, void* dK, void* dV, float* dZ, float* dbeta, float* dbeta_cls,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+int lot_attention_cls_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                               const float* Z, const float* beta, float eps, int iters, float beta_cls, const void* dO,
+                               void* dQ, void* dK, void* dV, float* dZ, float* dbeta, float* dbeta_cls,
+                               void* workspace, size_t workspace_bytes, void* hip_stream, int path);
+
+/*
  * Debug: synchronises the device and reads the status word that the fused kernel leaves in the
  * workspace.  LOT_OK, or LOT_ERR_SYNC if a bounded device-side wait between cooperating
  * workgroups gave up (the output of that call is then undefined).  Not part of the hot path.

@@ -307,10 +307,11 @@ int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t*
     return LOT_OK;
 }
 
-int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
-                           const float* Z, const float* beta, float eps, int iters, const void* dO,
-                           void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
-                           void* workspace, size_t workspace_bytes, void* hip_stream, int path)
+// n_stride: tokens between consecutive problems in the token tensors (0 = shape->n)
+static int backward_impl(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                         const float* Z, const float* beta, float eps, int iters, const void* dO,
+                         void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                         void* workspace, size_t workspace_bytes, void* hip_stream, int path, int n_stride)
 {
     int rc = validate_shape(shape);
     if (rc != LOT_OK) return rc;
@@ -341,7 +342,49 @@ int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K,
     a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
     a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
+    a.n_stride = n_stride;
     return tiled ? run_backward_tiled(a) : run_backward(a);
+}
+
+int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                           const float* Z, const float* beta, float eps, int iters, const void* dO,
+                           void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                           void* workspace, size_t workspace_bytes, void* hip_stream, int path)
+{
+    return backward_impl(shape, Q, K, V, Z, beta, eps, iters, dO, dQ, dK, dV, dZ, dbeta, workspace, workspace_bytes,
+                         hip_stream, path, 0);
+}
+
+int lot_attention_cls_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                               const float* Z, const float* beta, float eps, int iters, float beta_cls, const void* dO,
+                               void* dQ, void* dK, void* dV, float* dZ, float* dbeta, float* dbeta_cls,
+                               void* workspace, size_t workspace_bytes, void* hip_stream, int path)
+{
+    int rc = validate_shape(shape);
+    if (rc != LOT_OK) return rc;
+    if (shape->n < 2) return LOT_ERR_SHAPE;
+    if (!(beta_cls > 0.0f) || !std::isfinite(beta_cls)) return LOT_ERR_EPS;
+    if (!Q || !K || !V || !dO || !dQ || !dK || !dV || !dbeta_cls) return LOT_ERR_NULL;
+    if (misaligned(dbeta_cls, 4)) return LOT_ERR_ALIGN;
+    // the doubly-stochastic part among tokens 1 .. n-1: the same kernels on views that skip row 0
+    lot_shape inner = *shape;
+    inner.n = shape->n - 1;
+    const size_t esz = shape->io_dtype == LOT_BF16 ? 2 : 4;
+    const size_t qk = shape->d_k * esz, vv = shape->d_v * esz;
+    rc = backward_impl(&inner, (const char*)Q + qk, (const char*)K + qk, (const char*)V + vv, Z, beta, eps, iters,
+                       (const char*)dO + vv, (char*)dQ + qk, (char*)dK + qk, (char*)dV + vv, dZ, dbeta,
+                       workspace, workspace_bytes, hip_stream, path, shape->n);
+    if (rc != LOT_OK) return rc;
+    return run_cls_row_bwd(*shape, Q, K, V, dO, beta_cls, dQ, dK, dV, dbeta_cls, (hipStream_t)hip_stream);
+}
+
+int lot_attention_cls_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                          const float* Z, const float* beta, float eps, int iters, float beta_cls, const void* dO,
+                          void* dQ, void* dK, void* dV, float* dZ, float* dbeta, float* dbeta_cls,
+                          void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return lot_attention_cls_bwd_path(shape, Q, K, V, Z, beta, eps, iters, beta_cls, dO, dQ, dK, dV, dZ, dbeta,
+                                      dbeta_cls, workspace, workspace_bytes, hip_stream, LOT_PATH_AUTO);
 }
 
 int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,

@@ -41,10 +41,10 @@ __global__ void bwd_couplings(const float* __restrict__ C, const float* __restri
 }
 
 // part[p][chunk][t][c] = sum over the chunk's tokens i of A[p][i][t] * X[p][i][c]
-// (A is fp32 [P][n][r]; X is [P][n][dx] in the I/O type).  One block per (p, chunk, t).
+// (A is fp32 [P][n][r]; X is [P][stride][dx] in the I/O type, n rows used).  One block per (p, chunk, t).
 template <typename T>
 __global__ void bwd_tx_partial(const float* __restrict__ A, const T* __restrict__ X, float* __restrict__ part,
-                               int n, int r, int dx, int chunks)
+                               int n, int stride, int r, int dx, int chunks)
 {
     const int t = blockIdx.x % r;
     const int chunk = (blockIdx.x / r) % chunks;
@@ -52,7 +52,7 @@ __global__ void bwd_tx_partial(const float* __restrict__ A, const T* __restrict_
     const int i0 = chunk * kChunk, i1 = min(n, i0 + kChunk);
     for (int c = threadIdx.x; c < dx; c += blockDim.x) {
         float acc = 0.f;
-        for (int i = i0; i < i1; ++i) acc = fmaf(A[(p * n + i) * r + t], ld(X, (p * n + i) * dx + c), acc);
+        for (int i = i0; i < i1; ++i) acc = fmaf(A[(p * n + i) * r + t], ld(X, (p * stride + i) * dx + c), acc);
         part[((p * chunks + chunk) * r + t) * dx + c] = acc;
     }
 }
@@ -90,7 +90,7 @@ __global__ void bwd_glue_pivots(float* __restrict__ Yp, float* __restrict__ dYp,
 // out[p][i][t] = scale * sum_c X[p][i][c] * M[p][t][c]        (dGamma1 = n dO Y'^T, dGamma2 = V dYraw^T)
 template <typename T>
 __global__ void bwd_outer(const T* __restrict__ X, const float* __restrict__ M, float* __restrict__ out,
-                          size_t total, int n, int r, int dx, float scale)
+                          size_t total, int n, int stride, int r, int dx, float scale)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // (p, i, t)
     if (idx >= total) return;
@@ -98,14 +98,15 @@ __global__ void bwd_outer(const T* __restrict__ X, const float* __restrict__ M, 
     const int t = (int)(idx % r);
     const size_t p = pi / n;
     float acc = 0.f;
-    for (int c = 0; c < dx; ++c) acc = fmaf(ld(X, pi * dx + c), M[(p * r + t) * dx + c], acc);
+    const size_t row = p * stride + pi % n;          // X is [P][stride][dx]
+    for (int c = 0; c < dx; ++c) acc = fmaf(ld(X, row * dx + c), M[(p * r + t) * dx + c], acc);
     out[idx] = scale * acc;
 }
 
 // out[p][i][c] = sum_t A[p][i][t] * M[m(p)][t][c], M per problem (per_head = 0) or per head.
 template <typename T>
 __global__ void bwd_apply(const float* __restrict__ A, const float* __restrict__ M, T* __restrict__ out,
-                          size_t total, int n, int r, int dx, int per_head, int H)
+                          size_t total, int n, int stride, int r, int dx, int per_head, int H)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // (p, i, c)
     if (idx >= total) return;
@@ -115,7 +116,7 @@ __global__ void bwd_apply(const float* __restrict__ A, const float* __restrict__
     const size_t m = per_head ? (p % H) : p;
     float acc = 0.f;
     for (int t = 0; t < r; ++t) acc = fmaf(A[pi * r + t], M[(m * r + t) * dx + c], acc);
-    st(out, idx, acc);
+    st(out, (p * stride + pi % n) * dx + c, acc);          // out is [P][stride][dx]
 }
 
 // colpart[pair][chunk][t] = sum over the chunk's tokens of A_it * B_it (B may be null: plain sum).
@@ -249,6 +250,7 @@ int run_backward_t(const BwdArgs& a)
     const lot_shape& s = a.s;
     const int G = s.B * s.H, n = s.n, r = s.r, pairs = 2 * G, T_ = a.iters;
     const int chunks = (n + kChunk - 1) / kChunk;
+    const int stride = a.n_stride > 0 ? a.n_stride : n;      // tokens between problems in the caller's tensors
     const BwdWorkspace& L = a.lay;
     float* C = (float*)(a.ws + L.C);
     float* f = (float*)(a.ws + L.f);
@@ -279,7 +281,7 @@ int run_backward_t(const BwdArgs& a)
     const unsigned pr_blocks = blocks_for(slab, 256);
 
     // ---- forward, keeping the pivot potentials of every iteration
-    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, n, s.d_k, r,
+    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, stride, s.d_k, r,
                                                          s.io_dtype == LOT_BF16);
     ref_zero<<<pr_blocks, 256, 0, st_>>>(ghist, slab);
     for (int k = 1; k <= T_; ++k) {
@@ -293,19 +295,19 @@ int run_backward_t(const BwdArgs& a)
 
     // ---- glue
     // Y' = Diag(beta)^-1 Gamma2 V
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(gam2, (const T*)a.V, tx_part, n, r, s.d_v, chunks);
+    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(gam2, (const T*)a.V, tx_part, n, stride, r, s.d_v, chunks);
     bwd_tx_final<<<blocks_for((size_t)G * r * s.d_v, 256), 256, 0, st_>>>(tx_part, Yp, (size_t)G * r * s.d_v, r, s.d_v, chunks, 1.f);
     bwd_glue_pivots<<<blocks_for((size_t)G * r, 128), 128, 0, st_>>>(Yp, dYp, a.beta, db_glue, G * r, s.H, r, s.d_v, 0);
     // dY' = n Gamma1^T dO
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(gam1, (const T*)a.dO, tx_part, n, r, s.d_v, chunks);
+    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(gam1, (const T*)a.dO, tx_part, n, stride, r, s.d_v, chunks);
     bwd_tx_final<<<blocks_for((size_t)G * r * s.d_v, 256), 256, 0, st_>>>(tx_part, dYp, (size_t)G * r * s.d_v, r, s.d_v, chunks, (float)n);
     // dGamma1 = n dO Y'^T (before dY' is rescaled; it does not use dY')
-    bwd_outer<T><<<blocks_for(half, 256), 256, 0, st_>>>((const T*)a.dO, Yp, dgam, half, n, r, s.d_v, (float)n);
+    bwd_outer<T><<<blocks_for(half, 256), 256, 0, st_>>>((const T*)a.dO, Yp, dgam, half, n, stride, r, s.d_v, (float)n);
     // db_glue, dYraw = dY'/beta
     bwd_glue_pivots<<<blocks_for((size_t)G * r, 128), 128, 0, st_>>>(Yp, dYp, a.beta, db_glue, G * r, s.H, r, s.d_v, 1);
     // dV = Gamma2^T dYraw ; dGamma2 = V dYraw^T
-    bwd_apply<T><<<blocks_for((size_t)G * n * s.d_v, 256), 256, 0, st_>>>(gam2, dYp, (T*)a.dV, (size_t)G * n * s.d_v, n, r, s.d_v, 0, s.H);
-    bwd_outer<T><<<blocks_for(half, 256), 256, 0, st_>>>((const T*)a.V, dYp, dgam + half, half, n, r, s.d_v, 1.f);
+    bwd_apply<T><<<blocks_for((size_t)G * n * s.d_v, 256), 256, 0, st_>>>(gam2, dYp, (T*)a.dV, (size_t)G * n * s.d_v, n, stride, r, s.d_v, 0, s.H);
+    bwd_outer<T><<<blocks_for(half, 256), 256, 0, st_>>>((const T*)a.V, dYp, dgam + half, half, n, stride, r, s.d_v, 1.f);
 
     // ---- both Sinkhorn solves, reverse sweep (the two solves side by side: pair = side * G + g)
     bwd_col_partial<<<(unsigned)pairs * chunks, 64, 0, st_>>>(dgam, gam, colpart, n, r, chunks);
@@ -321,11 +323,11 @@ int run_backward_t(const BwdArgs& a)
 
     // ---- similarities: dQ = dC1 Z, dK = dC2 Z, dZ = sum_b (dC1^T Q + dC2^T K)
     bwd_round_z<<<blocks_for((size_t)s.H * r * s.d_k, 256), 256, 0, st_>>>(a.Z, Zr, s.H * r * s.d_k, s.io_dtype == LOT_BF16);
-    bwd_apply<T><<<blocks_for((size_t)G * n * s.d_k, 256), 256, 0, st_>>>(dC, Zr, (T*)a.dQ, (size_t)G * n * s.d_k, n, r, s.d_k, 1, s.H);
-    bwd_apply<T><<<blocks_for((size_t)G * n * s.d_k, 256), 256, 0, st_>>>(dC + half, Zr, (T*)a.dK, (size_t)G * n * s.d_k, n, r, s.d_k, 1, s.H);
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(dC, (const T*)a.Q, tx_part, n, r, s.d_k, chunks);
+    bwd_apply<T><<<blocks_for((size_t)G * n * s.d_k, 256), 256, 0, st_>>>(dC, Zr, (T*)a.dQ, (size_t)G * n * s.d_k, n, stride, r, s.d_k, 1, s.H);
+    bwd_apply<T><<<blocks_for((size_t)G * n * s.d_k, 256), 256, 0, st_>>>(dC + half, Zr, (T*)a.dK, (size_t)G * n * s.d_k, n, stride, r, s.d_k, 1, s.H);
+    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(dC, (const T*)a.Q, tx_part, n, stride, r, s.d_k, chunks);
     bwd_tx_final<<<blocks_for((size_t)G * r * s.d_k, 256), 256, 0, st_>>>(tx_part, dZ_pair, (size_t)G * r * s.d_k, r, s.d_k, chunks, 1.f);
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(dC + half, (const T*)a.K, tx_part, n, r, s.d_k, chunks);
+    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(dC + half, (const T*)a.K, tx_part, n, stride, r, s.d_k, chunks);
     bwd_tx_final<<<blocks_for((size_t)G * r * s.d_k, 256), 256, 0, st_>>>(tx_part, dZ_pair + (size_t)G * r * s.d_k, (size_t)G * r * s.d_k, r, s.d_k, chunks, 1.f);
     bwd_head_sums<<<blocks_for((size_t)s.H * r * (s.d_k + 1), 256), 256, 0, st_>>>(dZ_pair, db_pair, db_glue, a.dZ, a.dbeta, s.B, s.H, r, s.d_k);
     LOT_HIP_CHECK(hipGetLastError());

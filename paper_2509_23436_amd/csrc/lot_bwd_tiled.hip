@@ -80,6 +80,7 @@ struct BtParams {
     float* db_glue;               // [G][64]
     float* dz_part;               // [pairs][chunks][64][D]
     int G, H, B, n, r, chunks, tiles_per_wg, k, T;
+    int stride;                   // tokens between consecutive problems in Q, K, V, dO, dQ, dK, dV (>= n)
     float eps, fx_scale, fx_unscale;
     uint32_t spin_limit;
     float sum_lo, sum_hi;         // row sums outside [sum_lo, sum_hi] make the assemble kernel re-shift its rows
@@ -135,7 +136,7 @@ __device__ __forceinline__ void load_first_tile(Frag<IO, D>& xc, const BtParams&
                                                 int wave, int i, int kg)
 {
     const int tok = min((w.tile_begin + wave) * kTileTokens + i, p.n - 1);
-    load_tokens<D>(xc, X + ((size_t)w.g * p.n + tok) * D, kg);
+    load_tokens<D>(xc, X + ((size_t)w.g * p.stride + tok) * D, kg);
 }
 
 template <typename IO, int D, int RB>
@@ -169,7 +170,7 @@ __device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace&
         Frag<IO, D> xn = xc;
         if (tile + kWaves < w.tile_end) {
             const int tok = min((tile + kWaves) * kTileTokens + i, n - 1);
-            load_tokens<D>(xn, X + ((size_t)w.g * n + tok) * D, kg);
+            load_tokens<D>(xn, X + ((size_t)w.g * p.stride + tok) * D, kg);
         } else if (again) {
             load_first_tile<IO, D>(xn, p, w, X, wave, i, kg);
         }
@@ -179,7 +180,7 @@ __device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace&
             for (int s = 0; s < 2; ++s) {
                 const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
                 const int left = max(1, min(8, n - t0));
-                load_values<D>(vh[s], vl[s], vals, (size_t)w.g * n + min(t0, n - 1), left, i);
+                load_values<D>(vh[s], vl[s], vals, (size_t)w.g * p.stride + min(t0, n - 1), left, i);
             }
         }
         f32x16 acc[RB];
@@ -527,8 +528,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
     for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
         const int tok = min(tile * kTileTokens + i, n - 1);
         Frag<IO, D> xc, vc;
-        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
-        load_tokens<D>(vc, vals + ((size_t)g * n + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * p.stride + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * p.stride + tok) * D, kg);
         f32x16 acc[RB], dgam[RB], rho[RB];
         float w;
         int skew = 0;
@@ -569,7 +570,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
             contract_pivots<D, RB, kSplit>(o, acc, s_yf[0], s_yf[1], lane);
             IO* out = reinterpret_cast<IO*>(p.dV);
             const int row0 = tile * kTileTokens + 4 * kg;
-            IO* const lane_base = out + ((size_t)g * n + row0) * D;
+            IO* const lane_base = out + ((size_t)g * p.stride + row0) * D;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
                 if (row0 + 8 * (j >> 2) + (j & 3) < n)
@@ -761,8 +762,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
         const int tok = min(tile * kTileTokens + i, n - 1);
         const bool valid = tile * kTileTokens + i < n;
         Frag<IO, D> xc, vc;
-        load_tokens<D>(xc, X + ((size_t)g * n + tok) * D, kg);
-        load_tokens<D>(vc, vals + ((size_t)g * n + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * p.stride + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * p.stride + tok) * D, kg);
         int skew = 0;
         asm volatile("" : "+v"(skew));
         // similarities scaled to base-2 exponents, once
@@ -873,7 +874,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
             contract_pivots<D, RB, kSplit>(o, dacc, s_zf[0], s_zf[1], lane);
             IO* out = reinterpret_cast<IO*>(side == 0 ? p.dQ : p.dK);
             const int row0 = tile * kTileTokens + 4 * kg;
-            IO* const lane_base = out + ((size_t)g * n + row0) * D;
+            IO* const lane_base = out + ((size_t)g * p.stride + row0) * D;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
                 if (row0 + 8 * (j >> 2) + (j & 3) < n)
@@ -885,7 +886,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
         for (int s = 0; s < 2; ++s) {
             const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
             const int left = max(1, min(8, n - t0));
-            load_values<D>(vh[s], vl[s], X, (size_t)g * n + min(t0, n - 1), left, i);
+            load_values<D>(vh[s], vl[s], X, (size_t)g * p.stride + min(t0, n - 1), left, i);
         }
         transpose_tile<RB, kSplit>(dacc, tr_hi, tr_lo, i, kg);
         contract_tokens<D, RB, kSplit>(dZacc, tr_hi, tr_lo, vh, vl, i, kg);
@@ -1053,6 +1054,7 @@ int run_backward_tiled(const BwdArgs& a)
     p.db_glue = (float*)(a.ws + L.db_glue);
     p.dz_part = (float*)(a.ws + L.dz_part);
     p.G = s.B * s.H; p.H = s.H; p.B = s.B; p.n = s.n; p.r = s.r; p.chunks = L.chunks; p.tiles_per_wg = tiles_per_wg_for(s); p.T = a.iters;
+    p.stride = a.n_stride > 0 ? a.n_stride : s.n;
     p.eps = a.eps;
     {
         // column sums of a row-normalised kernel are at most n: with 2^(55 - ceil(log2(n + 1))) units per

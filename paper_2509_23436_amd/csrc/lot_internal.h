@@ -137,6 +137,7 @@ struct BwdArgs {
     void* dV;
     float* dZ;
     float* dbeta;
+    int n_stride;       // tokens between consecutive problems in Q, K, V, dO, dQ, dK, dV; 0 = s.n
     char* ws;
     BwdWorkspace lay;
     hipStream_t stream;
@@ -193,6 +194,11 @@ int run_backward_tiled(const BwdArgs& a);
 // out[b][h][0][:] = softmax_j(beta_cls <q_0, k_j>) V, j over all n tokens of the problem
 int run_cls_row(const lot_shape& s, const void* Q, const void* K, const void* V, float beta_cls, void* out,
                 hipStream_t stream);   // LOT_ERR_PATH when the shape is outside its set
+
+// Adds the [CLS] row's share to dK and dV (rows >= 1; row 0 is written), writes row 0 of dQ and the
+// per-problem derivative with respect to beta_cls.  Runs after the gradients of rows 1 .. n-1 are in place.
+int run_cls_row_bwd(const lot_shape& s, const void* Q, const void* K, const void* V, const void* dO, float beta_cls,
+                    void* dQ, void* dK, void* dV, float* dbeta_cls, hipStream_t stream);
 
 hipError_t& last_hip_error();
 

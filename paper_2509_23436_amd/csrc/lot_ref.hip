@@ -178,6 +178,124 @@ __global__ void cls_row(const T* __restrict__ Q, const T* __restrict__ K, const 
     }
 }
 
+
+// Backward of the [CLS] row.  With raw_j = <q_cls, k_j>, p = softmax(beta_cls raw), out = sum_j p_j v_j
+// and the incoming gradient dout:  dp_j = <dout, v_j>,  a_j = p_j (dp_j - sum_j' p_j' dp_j')  (the
+// gradient with respect to beta_cls raw_j), and
+//   dq_cls = beta_cls sum_j a_j k_j,   dK_j += beta_cls a_j q_cls,   dV_j += p_j dout,
+//   d beta_cls = sum_j a_j raw_j.
+// Rows j >= 1 of dK and dV already hold the gradient of the doubly-stochastic part and are added to;
+// row 0 (the [CLS] key and value, which only this row sees) and row 0 of dQ are written.  One
+// workgroup per problem, three sweeps over the keys (maximum; normaliser and sum p dp; gradients),
+// the last in chunks whose a_j and p_j sit in LDS; every reduction has a fixed order.
+template <typename T>
+__global__ void cls_row_bwd(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+                            const T* __restrict__ dO, T* __restrict__ dQ, T* __restrict__ dK, T* __restrict__ dV,
+                            float* __restrict__ dbeta_cls, int n, int d, int dv, float beta_cls)
+{
+    __shared__ float s_a[kClsChunk];
+    __shared__ float s_p[kClsChunk];
+    __shared__ float s_red[kClsThreads];
+    extern __shared__ float s_dyn[];        // q_cls [d], dout [dv], parts x d partial sums of dq_cls
+    float* s_q = s_dyn;
+    float* s_do = s_dyn + d;
+    float* s_acc = s_dyn + d + dv;
+    const size_t g = blockIdx.x;
+    const int tid = threadIdx.x;
+    for (int c = tid; c < d; c += kClsThreads) s_q[c] = ld(Q, g * n * d + c);
+    for (int c = tid; c < dv; c += kClsThreads) s_do[c] = ld(dO, g * n * dv + c);
+    __syncthreads();
+    auto score = [&](int j) {
+        float sc = 0.f;
+        for (int c = 0; c < d; ++c) sc = fmaf(s_q[c], ld(K, (g * n + j) * d + c), sc);
+        return sc;                      // raw_j
+    };
+    auto reduce = [&](float v, bool take_max) {
+        s_red[tid] = v;
+        __syncthreads();
+        for (int w = kClsThreads / 2; w > 0; w >>= 1) {
+            if (tid < w) s_red[tid] = take_max ? fmaxf(s_red[tid], s_red[tid + w]) : s_red[tid] + s_red[tid + w];
+            __syncthreads();
+        }
+        const float r = s_red[0];
+        __syncthreads();
+        return r;
+    };
+    // sweep 1: maximum of the scaled scores
+    float m = -INFINITY;
+    for (int j = tid; j < n; j += kClsThreads) m = fmaxf(m, beta_cls * score(j));
+    m = reduce(m, true);
+    // sweep 2: normaliser and sum_j p_j dp_j
+    float z = 0.f, pd = 0.f;
+    for (int j = tid; j < n; j += kClsThreads) {
+        const float e = expf(beta_cls * score(j) - m);
+        float dp = 0.f;
+        for (int c = 0; c < dv; ++c) dp = fmaf(s_do[c], ld(V, (g * n + j) * dv + c), dp);
+        z += e;
+        pd = fmaf(e, dp, pd);
+    }
+    z = reduce(z, false);
+    pd = reduce(pd, false) / z;
+    // sweep 3, in chunks: a_j and p_j to LDS, then column-parallel updates
+    const int parts = kClsThreads / d > 0 ? kClsThreads / d : 1;          // threads per column of dq_cls
+    const int parts_v = kClsThreads / dv > 0 ? kClsThreads / dv : 1;
+    float dq[4] = {0.f, 0.f, 0.f, 0.f};     // up to 4 columns per thread when d > 256
+    float dbc = 0.f;
+    for (int j0 = 0; j0 < n; j0 += kClsChunk) {
+        const int cn = min(kClsChunk, n - j0);
+        for (int j = tid; j < cn; j += kClsThreads) {
+            const float raw = score(j0 + j);
+            const float pj = expf(beta_cls * raw - m) / z;
+            float dp = 0.f;
+            for (int c = 0; c < dv; ++c) dp = fmaf(s_do[c], ld(V, (g * n + j0 + j) * dv + c), dp);
+            const float a = pj * (dp - pd);
+            s_a[j] = a;
+            s_p[j] = pj;
+            dbc = fmaf(a, raw, dbc);
+        }
+        __syncthreads();
+        int slot = 0;
+        for (int c0 = 0; c0 < d; c0 += kClsThreads / parts, ++slot) {
+            const int c = c0 + tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
+            if (c < d && part < parts) {
+                float acc = 0.f;
+                const float qc = beta_cls * s_q[c];
+                for (int j = part; j < cn; j += parts) {
+                    const size_t at = (g * n + j0 + j) * d + c;
+                    acc = fmaf(s_a[j], ld(K, at), acc);
+                    const float add = s_a[j] * qc;
+                    st(dK, at, j0 + j == 0 ? add : ld(dK, at) + add);
+                }
+                dq[slot & 3] += acc;
+            }
+        }
+        for (int c0 = 0; c0 < dv; c0 += kClsThreads / parts_v) {
+            const int c = c0 + tid % (kClsThreads / parts_v), part = tid / (kClsThreads / parts_v);
+            if (c < dv && part < parts_v)
+                for (int j = part; j < cn; j += parts_v) {
+                    const size_t at = (g * n + j0 + j) * dv + c;
+                    const float add = s_p[j] * s_do[c];
+                    st(dV, at, j0 + j == 0 ? add : ld(dV, at) + add);
+                }
+        }
+        __syncthreads();
+    }
+    // dq_cls: combine the parts of each column in order
+    int slot = 0;
+    for (int c0 = 0; c0 < d; c0 += kClsThreads / parts, ++slot) {
+        const int c = c0 + tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
+        if (c < d && part < parts) s_acc[part * d + c] = dq[slot & 3];
+    }
+    __syncthreads();
+    for (int c = tid; c < d; c += kClsThreads) {
+        float tot = 0.f;
+        for (int k = 0; k < parts; ++k) tot += s_acc[k * d + c];
+        st(dQ, g * n * d + c, beta_cls * tot);
+    }
+    dbc = reduce(dbc, false);
+    if (tid == 0) dbeta_cls[g] = dbc;
+}
+
 }  // namespace
 
 int run_cls_row(const lot_shape& s, const void* Q, const void* K, const void* V, float beta_cls, void* out,
@@ -192,6 +310,24 @@ int run_cls_row(const lot_shape& s, const void* Q, const void* K, const void* V,
     else
         cls_row<float><<<G, kClsThreads, shmem, stream>>>((const float*)Q, (const float*)K, (const float*)V,
                                                            (float*)out, s.n, s.d_k, s.d_v, beta_cls);
+    LOT_HIP_CHECK(hipGetLastError());
+    return LOT_OK;
+}
+
+int run_cls_row_bwd(const lot_shape& s, const void* Q, const void* K, const void* V, const void* dO, float beta_cls,
+                    void* dQ, void* dK, void* dV, float* dbeta_cls, hipStream_t stream)
+{
+    const int G = s.B * s.H;
+    const int parts = kClsThreads / s.d_k > 0 ? kClsThreads / s.d_k : 1;
+    const size_t shmem = ((size_t)s.d_k + s.d_v + (size_t)parts * s.d_k) * sizeof(float);
+    if (s.io_dtype == LOT_BF16)
+        cls_row_bwd<uint16_t><<<G, kClsThreads, shmem, stream>>>(
+            (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, (const uint16_t*)dO, (uint16_t*)dQ, (uint16_t*)dK,
+            (uint16_t*)dV, dbeta_cls, s.n, s.d_k, s.d_v, beta_cls);
+    else
+        cls_row_bwd<float><<<G, kClsThreads, shmem, stream>>>(
+            (const float*)Q, (const float*)K, (const float*)V, (const float*)dO, (float*)dQ, (float*)dK, (float*)dV,
+            dbeta_cls, s.n, s.d_k, s.d_v, beta_cls);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }

@@ -18,6 +18,7 @@ PATH_AUTO, PATH_REFERENCE, PATH_FUSED = 0, 1, 2
 
 EXPORTS = ("lot_workspace_bytes", "lot_attention_fwd", "lot_couplings", "lot_attention_fwd_path",
            "lot_couplings_path", "lot_attention_cls_fwd", "lot_attention_cls_fwd_path", "lot_cross_workspace_bytes", "lot_cross_attention_fwd", "lot_cross_attention_fwd_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
+           "lot_attention_cls_bwd", "lot_attention_cls_bwd_path",
            "lot_workspace_status", "lot_strerror", "lot_version")
 
 
@@ -198,6 +199,28 @@ def lot_attention_cls_fwd(Q, K, V, Z, beta, eps, iters, beta_cls, out=None, work
                                             ctypes.c_float(eps), int(iters), ctypes.c_float(beta_cls), _ptr(out),
                                             _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(), int(path)))
     return out
+
+
+def lot_attention_cls_bwd(Q, K, V, Z, beta, eps, iters, beta_cls, dO, workspace=None, path=PATH_AUTO):
+    """(dQ, dK, dV, dZ, dbeta, dbeta_cls[B,H]) of <lot_attention_cls_fwd(...), dO>."""
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
+        _require(t, nm, Q.dtype)
+    _require(Z, "Z", torch.float32)
+    _require(beta, "beta", torch.float32)
+    if dO.shape != V.shape:
+        raise ValueError("dO must have the shape of V")
+    shape = _shape_of(Q, V, Z)
+    if workspace is None:
+        workspace = torch.empty(lot_attention_bwd_workspace_bytes(shape, iters), dtype=torch.uint8, device=Q.device)
+    _require(workspace, "workspace", torch.uint8)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    dZ, dbeta = torch.empty_like(Z), torch.empty_like(beta)
+    dbeta_cls = torch.empty(Q.shape[:2], dtype=torch.float32, device=Q.device)
+    _check(lib().lot_attention_cls_bwd_path(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
+                                            ctypes.c_float(eps), int(iters), ctypes.c_float(beta_cls), _ptr(dO),
+                                            _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dZ), _ptr(dbeta), _ptr(dbeta_cls),
+                                            _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(), int(path)))
+    return dQ, dK, dV, dZ, dbeta, dbeta_cls
 
 
 def lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=None, mass_k=None, out=None, workspace=None,

@@ -128,6 +128,16 @@ def test_cls_and_cross_entry_points_reject_bad_arguments(L):
     assert cls(shape=_shape(n=1)) == -2
     assert cls(out=0) == -1
 
+    def cls_bwd(beta_cls=1.0, shape=s, dbc=0x8000, dO=0x5000, ws_bytes=1 << 40, eps=0.1):
+        return L.lot_attention_cls_bwd(ctypes.byref(shape), vp(0x1000), vp(0x2000), vp(0x3000), vp(0x100), vp(0x200),
+                                       ctypes.c_float(eps), 5, ctypes.c_float(beta_cls), vp(dO),
+                                       vp(0x6000), vp(0x7000), vp(0x9000), vp(0x300), vp(0x400), vp(dbc), vp(1 << 20),
+                                       ctypes.c_size_t(ws_bytes), None)
+
+    assert cls_bwd(beta_cls=-1.0) == -3 and cls_bwd(shape=_shape(n=1)) == -2
+    assert cls_bwd(dbc=0) == -1 and cls_bwd(dO=0) == -1 and cls_bwd(dbc=0x8002) == -7
+    assert cls_bwd(ws_bytes=64) == -6 and cls_bwd(eps=0.0) == -3
+
     x = lot.lot_xshape(1, 1, 40, 70, 32, 32, 8, 0)
     need = ctypes.c_size_t(0)
     assert L.lot_cross_workspace_bytes(ctypes.byref(x), 5, ctypes.byref(need)) == 0 and need.value % 256 == 0

@@ -75,3 +75,80 @@ def test_cls_variant_full_size_deit_on_sampled_problems():
         err = rel_max_err(O[gi], ref[0, 0])
         print("  problem %d rel err %.3e" % (gi, err), flush=True)
         assert err <= 1e-4
+
+
+# ---- backward
+
+BWD_CASES = {
+    "tiny": S(W["tiny"], n=65),
+    "deit_like_f32": S(W["deit_tiny"], B=2, H=3, iters=6, seed=86),
+    "two_tokens": S(W["tiny"], n=2, r=1, seed=81),
+    "bf16_ragged": S(W["long_4k"], B=1, H=2, n=1030, iters=5, seed=82),
+    "bf16_d32": S(W["swin_t_s1"], B=2, H=3, n=400, seed=83),
+    "reference_only": S(W["tiny"], B=1, H=2, n=90, d=16, r=80, iters=4, seed=84),
+    "several_softmax_chunks": S(W["tiny"], B=1, H=2, n=2600, d=32, r=8, iters=3, seed=85),
+}
+
+
+def _bwd_paths(w):
+    tiled = w.d in (32, 64) and w.r <= 64 and w.iters <= 32
+    return ["reference", "fused"] if tiled else ["reference"]
+
+
+@pytest.mark.parametrize("name,path_name", [(nm, pn) for nm in BWD_CASES for pn in _bwd_paths(BWD_CASES[nm])])
+def test_cls_backward_matches_oracle(name, path_name):
+    import torch
+    from oracle import lot_oracle_bwd
+    from paper_2509_23436_amd import lot
+    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED}[path_name]
+    w = BWD_CASES[name]
+    print("case %s path %s: %r" % (name, path_name, w), flush=True)
+    x = synth.make_inputs(w)
+    dO = np.random.default_rng(w.seed + 17).standard_normal(x["V"].shape).astype(np.float32)
+    if w.dtype == "bf16":
+        dO = synth.round_to_bf16(dO)
+    beta_cls = 0.9
+    refs, _ = lot_oracle_bwd.attention_cls_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, beta_cls, dO)
+    dev = to_device(dict(x, dO=dO), w.dtype)
+    got = lot.lot_attention_cls_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, beta_cls,
+                                    dev["dO"], path=path)
+    torch.cuda.synchronize()
+    tol = 2e-2 if w.dtype == "bf16" else 1e-4
+    for nm, g, ref in zip(("dQ", "dK", "dV", "dZ", "dbeta", "dbeta_cls"), got, refs):
+        g = to_host_f64(g)
+        assert np.isfinite(g).all(), nm
+        scale = np.abs(ref).max()
+        if scale < 1e-12:                       # identically zero (one pivot: nothing moves the plan)
+            assert np.abs(g).max() <= 1e-6, nm
+            continue
+        err = rel_max_err(g, ref)
+        print("  %-9s max-norm rel err %.3e (bar %.0e)" % (nm, err, tol), flush=True)
+        assert err <= tol, nm
+        if nm in ("dQ", "dK", "dV"):            # the [CLS] rows on their own scale
+            err0 = rel_max_err(g[:, :, 0], ref[:, :, 0])
+            print("  %-9s row 0 rel err %.3e" % (nm, err0), flush=True)
+            assert err0 <= tol, nm
+
+
+def test_cls_backward_full_size_deit_on_sampled_problems():
+    import torch
+    from oracle import lot_oracle_bwd
+    from paper_2509_23436_amd import lot
+    w = W["deit_tiny"]
+    x = synth.make_inputs(w)
+    dO = np.random.default_rng(9).standard_normal(x["V"].shape).astype(np.float32)
+    dev = to_device(dict(x, dO=dO), w.dtype)
+    got = lot.lot_attention_cls_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, 1.0, dev["dO"])
+    torch.cuda.synchronize()
+    for gi in (0, 191):
+        b, h = gi // w.H, gi % w.H
+        sl = lambda t: np.ascontiguousarray(t[b:b + 1, h:h + 1])           # noqa: E731
+        refs, _ = lot_oracle_bwd.attention_cls_bwd(sl(x["Q"]), sl(x["K"]), sl(x["V"]), x["Z"][h:h + 1],
+                                                   x["beta"][h:h + 1], w.eps, w.iters, 1.0, sl(dO))
+        for nm, g, ref in zip(("dQ", "dK", "dV"), got[:3], refs[:3]):
+            err = rel_max_err(to_host_f64(g[b:b + 1, h:h + 1]), ref)
+            print("  problem %d %-5s rel err %.3e" % (gi, nm, err), flush=True)
+            assert err <= 1e-4, nm
+        err = abs(float(got[5][b, h]) - float(refs[5][0, 0])) / max(1e-12, abs(float(refs[5][0, 0])))
+        print("  problem %d dbeta_cls rel err %.3e" % (gi, err), flush=True)
+        assert err <= 1e-4
