@@ -41,7 +41,7 @@ enum { MODE_ATTENTION = 0, MODE_COUPLINGS = 1 };
 // stamps the constant-rate clock into slot `slot` of its 128-slot record, kept in the last 8 MiB of
 // the workspace (a region only the reference path uses).
 #ifdef LOT_TRACE
-#define LOT_STAMP(slot) do { if (threadIdx.x == 0 && (slot) < 128) p.trace[(size_t)blockIdx.x * 128 + (slot)] = wall_clock64(); } while (0)
+#define LOT_STAMP(slot) do { if (threadIdx.x == 0 && (slot) < 128 && p.trace) p.trace[(size_t)blockIdx.x * 128 + (slot)] = wall_clock64(); } while (0)
 #else
 #define LOT_STAMP(slot) do { } while (0)
 #endif
@@ -724,8 +724,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         }
         LOT_STAMP(5);
 #ifdef LOT_TRACE
-        if (threadIdx.x == 0) p.trace[(size_t)blockIdx.x * 128 + 6] = repolls;
-        if (threadIdx.x == 0) p.trace[(size_t)blockIdx.x * 128 + 7] = valid_a;
+        if (threadIdx.x == 0 && p.trace) p.trace[(size_t)blockIdx.x * 128 + 6] = repolls;
+        if (threadIdx.x == 0 && p.trace) p.trace[(size_t)blockIdx.x * 128 + 7] = valid_a;
 #endif
         __syncthreads();   // LDS is reused by the next item
     }
@@ -788,7 +788,8 @@ int launch(const Args& a, bool want_out)
     p.num_items = G * cluster; p.iters = a.iters; p.mode = want_out ? MODE_ATTENTION : MODE_COUPLINGS;
     p.eps = a.eps;
     p.spin_limit = 1u << 21;
-    p.trace = (unsigned long long*)(a.ws + a.lay.total - (8u << 20));
+    // only where the last 8 MiB of the workspace lie wholly inside the reference path's regions
+    p.trace = a.lay.total >= a.lay.C + (8u << 20) ? (unsigned long long*)(a.ws + a.lay.total - (8u << 20)) : nullptr;
 
     // Fixed-point format of the exchanged column sums: a parity buffer receives at most
     // iters/2 + 1 passes, each adding at most n per pivot, and must stay below 2^55.
