@@ -26,6 +26,13 @@ softmax row over all keys, rows 1.. the method among the other tokens) written w
 operations, pinned by the numpy/C oracle of that variant, by its central finite differences, and by
 the two cases in which one of the two parts receives no gradient.
 
+Cross attention with token masses ("Empirical measures and pivot", "Glued coupling") likewise:
+`forward_cross` is the two solves with marginals (mass_q, beta) and (mass_k, beta) and the glued
+plan with renormalised rows, written with plain torch operations; the masses are data (a padding
+mask), not differentiated.  Pinned by the numpy/C oracle of that forward, its central finite
+differences, the uniform case (which is `forward`) and padding (zero-mass keys receive no gradient
+and change nobody else's).
+
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import this module.
 """
 from __future__ import annotations
@@ -89,4 +96,43 @@ def attention_cls_bwd(Q, K, V, Z, beta, eps, T, beta_cls, dO):
     O = forward_cls(*t, float(eps), int(T), bc)
     loss = (O * torch.tensor(np.asarray(dO, dtype=np.float64))).sum()
     grads = torch.autograd.grad(loss, t + [bc])
+    return tuple(g.detach().numpy() for g in grads), O.detach().numpy()
+
+
+def forward_cross(Q, K, V, Z, beta, mass_q, mass_k, eps, T):
+    """O[B,H,n_q,d_v] = Diag(mu)^-1 Gamma1 Diag(beta)^-1 Gamma2 V for Q [B,H,n_q,d_k], K [B,H,n_k,d_k],
+    V [B,H,n_k,d_v], masses [B,H,n_q] and [B,H,n_k] (nonnegative, summing to one; zero = padding)."""
+    b_log = torch.log(beta)[None, :, None, :]
+    C1 = torch.einsum("bhnc,hrc->bhnr", Q, Z)
+    C2 = torch.einsum("bhnc,hrc->bhnr", K, Z)
+
+    def solve(C, a_log):
+        g = torch.zeros_like(b_log)
+        f = g_before = None
+        for _ in range(T):
+            f = eps * (a_log - torch.logsumexp((C + g) / eps, dim=-1, keepdim=True))
+            g_before = g
+            g = eps * (b_log - torch.logsumexp((C + f) / eps, dim=-2, keepdim=True))
+        return f, g, g_before
+
+    with torch.no_grad():
+        a1_log = torch.log(mass_q)[..., None]          # -inf for padding
+        a2_log = torch.log(mass_k)[..., None]
+    _, g1, g1_before = solve(C1, a1_log)
+    f2, g2, _ = solve(C2, a2_log)
+    gamma2 = torch.exp((C2 + f2 + g2) / eps)                                           # [B,H,n_k,r]
+    Yp = torch.einsum("bhnr,bhnc->bhrc", gamma2, V) / beta[None, :, :, None]
+    # row i of Diag(mu)^-1 Gamma1: exp((C1 + f1 + g1)/eps) / mu_i with f1 = eps (log mu_i - LSE): mu_i cancels
+    rows1 = torch.exp((C1 + g1) / eps - torch.logsumexp((C1 + g1_before) / eps, dim=-1, keepdim=True))
+    return torch.einsum("bhnr,bhrc->bhnc", rows1, Yp)
+
+
+def cross_attention_bwd(Q, K, V, Z, beta, mass_q, mass_k, eps, T, dO):
+    """Gradients of <O, dO> with respect to Q, K, V, Z, beta for cross attention with token masses."""
+    t = [torch.tensor(np.asarray(x, dtype=np.float64), requires_grad=True) for x in (Q, K, V, Z, beta)]
+    mq = torch.tensor(np.asarray(mass_q, dtype=np.float64))
+    mk = torch.tensor(np.asarray(mass_k, dtype=np.float64))
+    O = forward_cross(*t, mq, mk, float(eps), int(T))
+    loss = (O * torch.tensor(np.asarray(dO, dtype=np.float64))).sum()
+    grads = torch.autograd.grad(loss, t)
     return tuple(g.detach().numpy() for g in grads), O.detach().numpy()

@@ -87,3 +87,77 @@ def test_one_pivot_gives_the_weighted_mean_of_the_values(oracle):
     out = _run(oracle, x, eps, iters)
     want = np.einsum("bhj,bhjc->bhc", x["mk"], x["V"])[:, :, None, :]
     assert np.abs(out - want).max() <= 1e-12
+
+
+# ---- backward (oracle.lot_oracle_bwd.cross_attention_bwd)
+
+def _pad(x, n_pad_q=3, n_pad_k=4):
+    """The same problem with the last tokens turned into padding (mass zero, masses renormalised)."""
+    y = dict(x)
+    mq = x["mq"].copy(); mk = x["mk"].copy()
+    mq[..., -n_pad_q:] = 0.0; mk[..., -n_pad_k:] = 0.0
+    y["mq"] = mq / mq.sum(axis=-1, keepdims=True)
+    y["mk"] = mk / mk.sum(axis=-1, keepdims=True)
+    return y
+
+
+def _grads(x, eps, iters, dO):
+    from oracle import lot_oracle_bwd
+    return lot_oracle_bwd.cross_attention_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], x["mq"], x["mk"], eps, iters, dO)
+
+
+def test_forward_of_the_cross_backward_oracle_equals_the_cross_oracle(oracle):
+    for kw, pad in ((dict(), False), (dict(), True), (dict(n_q=9, n_k=40, r=3, iters=1), False), (dict(eps=0.05), True)):
+        x, eps, iters = _case(**kw)
+        if pad:
+            x = _pad(x)
+        dO = np.zeros(x["Q"].shape[:3] + (x["V"].shape[-1],))
+        _, O_t = _grads(x, eps, iters, dO)
+        O_c = _run(oracle, x, eps, iters)
+        assert np.abs(O_t - O_c).max() <= 1e-12 * max(1.0, np.abs(O_c).max())
+
+
+def test_cross_gradients_match_central_differences_of_the_cross_oracle(oracle):
+    for pad in (False, True):
+        x, eps, iters = _case(n_q=11, n_k=14, r=4, iters=4)
+        if pad:
+            x = _pad(x, 2, 3)
+        rng = np.random.default_rng(8)
+        dO = rng.standard_normal(x["Q"].shape[:3] + (x["V"].shape[-1],))
+        grads, _ = _grads(x, eps, iters, dO)
+        loss = lambda y: float((_run(oracle, y, eps, iters) * dO).sum())     # noqa: E731
+        h = 1e-6
+        for name, g in zip(("Q", "K", "V", "Z", "beta"), grads):
+            assert np.isfinite(g).all(), name
+            for _ in range(3):
+                v = rng.standard_normal(x[name].shape)
+                if name == "beta":
+                    v *= 0.1 * x["beta"]
+                fd = (loss(dict(x, **{name: x[name] + h * v})) - loss(dict(x, **{name: x[name] - h * v}))) / (2 * h)
+                an = float((g * v).sum())
+                assert abs(fd - an) <= 2e-6 * max(1.0, abs(an), abs(fd)), (name, pad, fd, an)
+
+
+def test_uniform_masses_and_equal_lengths_give_the_plain_backward(oracle):
+    from oracle import lot_oracle_bwd
+    x, eps, iters = _case(n_q=17, n_k=17)
+    x["mq"] = np.full_like(x["mq"], 1.0 / 17)
+    x["mk"] = np.full_like(x["mk"], 1.0 / 17)
+    dO = np.random.default_rng(2).standard_normal(x["V"].shape)
+    got, _ = _grads(x, eps, iters, dO)
+    ref, _ = lot_oracle_bwd.attention_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], eps, iters, dO)
+    for g, r_ in zip(got, ref):
+        assert np.abs(g - r_).max() <= 1e-11 * max(1.0, np.abs(r_).max())
+
+
+def test_padding_keys_get_no_gradient_and_can_be_dropped(oracle):
+    x, eps, iters = _case()
+    x = _pad(x, n_pad_q=1, n_pad_k=4)
+    x["mq"] = _case()[0]["mq"]                         # queries: all real
+    dO = np.random.default_rng(3).standard_normal(x["Q"].shape[:3] + (x["V"].shape[-1],))
+    (dQ, dK, dV, dZ, db), _ = _grads(x, eps, iters, dO)
+    assert np.abs(dK[:, :, -4:]).max() == 0.0 and np.abs(dV[:, :, -4:]).max() == 0.0
+    short = dict(x, K=x["K"][:, :, :-4], V=x["V"][:, :, :-4], mk=x["mk"][:, :, :-4])
+    (dQ2, dK2, dV2, dZ2, db2), _ = _grads(short, eps, iters, dO)
+    for a, b in ((dQ, dQ2), (dK[:, :, :-4], dK2), (dV[:, :, :-4], dV2), (dZ, dZ2), (db, db2)):
+        assert np.abs(a - b).max() <= 1e-12 * max(1.0, np.abs(b).max())
