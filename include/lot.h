@@ -181,6 +181,23 @@ int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K,
                            void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
+ * Backward of lot_cross_attention_fwd (same inputs; dO [B,H,n_q,d_v]).  Writes dQ [B,H,n_q,d_k],
+ * dK [B,H,n_k,d_k], dV [B,H,n_k,d_v] in io_dtype and dZ, dbeta in fp32 (summed over the batch).  The
+ * masses are data (a padding mask), not differentiated; a key of mass zero receives exactly zero
+ * gradient, a query of mass zero the gradient of its own output row.  Runs on the plain kernels (one
+ * per step, n x r intermediates in the workspace) unless the lengths are equal and both mass
+ * pointers are null, which is lot_attention_bwd.  Workspace:
+ * lot_cross_attention_bwd_workspace_bytes; contents on entry do not matter; lot_workspace_status
+ * applies.  Reproducible bit for bit.
+ */
+int lot_cross_attention_bwd_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out);
+int lot_cross_attention_bwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                            const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                            float eps, int iters, const void* dO,
+                            void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Backward of lot_attention_cls_fwd (same inputs, eps, iters, beta_cls; dO = dL/dout, all n rows).
  * dQ, dK, dV, dZ, dbeta as in lot_attention_bwd: rows 1 .. n-1 carry the gradient of the
  * doubly-stochastic part plus, in dK and dV, the share of the [CLS] row; row 0 of dQ is the gradient

@@ -355,6 +355,57 @@ int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K,
                          hip_stream, path, 0);
 }
 
+int lot_cross_attention_bwd_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out)
+{
+    int rc = validate_xshape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!bytes_out) return LOT_ERR_NULL;
+    if (iters < 1 || iters > (1 << 16)) return LOT_ERR_ITERS;
+    size_t need = carve_bwd_sides(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_k, shape->d_v, iters).total;
+    if (shape->n_q == shape->n_k) {            // uniform masses may then take the tiled kernels
+        const lot_shape s{shape->B, shape->H, shape->n_q, shape->d_k, shape->d_v, shape->r, shape->io_dtype};
+        if (bwd_tiled_supports(s, iters)) {
+            const size_t tiled = carve_bwd_tiled(s, iters).total;
+            if (tiled > need) need = tiled;
+        }
+    }
+    *bytes_out = need;
+    return LOT_OK;
+}
+
+int lot_cross_attention_bwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                            const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                            float eps, int iters, const void* dO,
+                            void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int rc = validate_xshape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!Q || !K || !V || !Z || !beta || !dO || !dQ || !dK || !dV || !dZ || !dbeta || !workspace) return LOT_ERR_NULL;
+    if (!(eps > 0.0f) || !std::isfinite(eps)) return LOT_ERR_EPS;
+    if (iters < 1 || iters > (1 << 16)) return LOT_ERR_ITERS;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(dO, 16) || misaligned(dQ, 16) ||
+        misaligned(dK, 16) || misaligned(dV, 16) || misaligned(Z, 4) || misaligned(beta, 4) || misaligned(dZ, 4) ||
+        misaligned(dbeta, 4) || misaligned(mass_q, 4) || misaligned(mass_k, 4))
+        return LOT_ERR_ALIGN;
+    if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
+    size_t need = 0;
+    rc = lot_cross_attention_bwd_workspace_bytes(shape, iters, &need);
+    if (rc != LOT_OK) return rc;
+    if (workspace_bytes < need) return LOT_ERR_WORKSPACE;
+    const lot_shape s{shape->B, shape->H, shape->n_q > shape->n_k ? shape->n_q : shape->n_k, shape->d_k, shape->d_v,
+                      shape->r, shape->io_dtype};
+    BwdArgs a{};
+    a.s = s; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
+    a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
+    a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
+    // equal lengths and implicit uniform masses: the plain method, with its tiled kernels where they apply
+    if (shape->n_q == shape->n_k && !mass_q && !mass_k && bwd_tiled_supports(s, iters)) return run_backward_tiled(a);
+    a.lay = carve_bwd_sides(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_k, shape->d_v, iters);
+    a.n_q = shape->n_q; a.n_k = shape->n_k; a.mass_q = mass_q; a.mass_k = mass_k;
+    return run_backward(a);
+}
+
 int lot_attention_cls_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
                                const float* Z, const float* beta, float eps, int iters, float beta_cls, const void* dO,
                                void* dQ, void* dK, void* dV, float* dZ, float* dbeta, float* dbeta_cls,

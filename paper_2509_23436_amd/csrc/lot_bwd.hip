@@ -8,18 +8,22 @@
 // potentials after every iteration g^0 .. g^T (T+1 vectors of r numbers per solve: the only
 // per-iteration state the reverse sweep needs) and the final couplings.
 //
-// Notation for one solve (a = 1/n, b = beta):  P^k = a * softmax_rows((C + g^{k-1})/eps) is the plan
-// after the token-side update of iteration k, c^k its column sums, g^k = g^{k-1} + eps log(b / c^k),
-// and the returned coupling is Gamma = P^T * (b / c^T) column-wise.  Reverse sweep, given dGamma:
-//   last step:  s_t = sum_i dGamma_it Gamma_it;  dc_t = -s_t / c^T_t;  db_t += s_t / b_t;
-//               dP_it = dGamma_it b_t / c^T_t + dc_t
-//   step k<T:   (given dg^k)  dc_t = -eps dg^k_t / c^k_t;  db_t += eps dg^k_t / b_t;  dP_it = dc_t
-//   both:       e_i = (1/a) sum_t dP_it P_it;  dY_it = P_it (dP_it - e_i);  dC += dY/eps;
+// Notation for one solve (token masses a_i: 1/n, or the caller's for cross attention; b = beta):
+// W^k = softmax_rows((C + g^{k-1})/eps) is the row-normalised kernel of iteration k,
+// c^k_t = sum_i a_i W^k_it the column sums of the plan after the token-side update,
+// g^k = g^{k-1} + eps log(b / c^k), and the unit-mass coupling is Ghat_it = W^T_it b_t / c^T_t
+// (= Gamma_it / a_i; defined for tokens of mass zero as well).  Reverse sweep, given dGhat:
+//   last step:  s_t = sum_i dGhat_it Ghat_it;  dc_t = -s_t / c^T_t;  db_t += s_t / b_t;
+//               dW_it = dGhat_it b_t / c^T_t + a_i dc_t
+//   step k<T:   (given dg^k)  dc_t = -eps dg^k_t / c^k_t;  db_t += eps dg^k_t / b_t;  dW_it = a_i dc_t
+//   both:       e_i = sum_t dW_it W_it;  dY_it = W_it (dW_it - e_i);  dC += dY/eps;
 //               dg^{k-1}_t = [k<T] dg^k_t + (1/eps) sum_i dY_it
 // with c^k_t = b_t exp((g^{k-1}_t - g^k_t)/eps) read off the stored potentials.
-// Glue (O = n Gamma1 Y', Y' = Diag(b)^-1 Gamma2 V):  dY' = n Gamma1^T dO;  dGamma1 = n dO Y'^T;
-//   dYraw = dY'/b;  db_t -= <dY'_t, Y'_t>/b_t;  dV = Gamma2^T dYraw;  dGamma2 = dYraw V^T.
+// Glue (O = Ghat1 Y', Y'_t = (1/b_t) sum_j a2_j Ghat2_jt V_j):  dY' = Ghat1^T dO;  dGhat1 = dO Y'^T;
+//   dYraw = dY'/b;  db_t -= <dY'_t, Y'_t>/b_t;  dV_j = a2_j sum_t Ghat2_jt dYraw_t;
+//   dGhat2_jt = a2_j <V_j, dYraw_t>.
 // Finally dQ = dC1 Z, dK = dC2 Z, dZ = sum over the batch of dC1^T Q + dC2^T K.
+// The two sides may have different numbers of tokens (cross attention): every step runs per side.
 #include "lot_internal.h"
 #include "lot_plain_kernels.h"
 
@@ -28,22 +32,30 @@ namespace {
 
 constexpr int kChunk = kRefChunk;   // tokens per partial sum
 
-// Gamma[pair][i][t] = exp((C_it + f_i + g_t)/eps), both sides token-major.
-__global__ void bwd_couplings(const float* __restrict__ C, const float* __restrict__ f,
-                              const float* __restrict__ gpot, float* __restrict__ gam,
-                              size_t total, int n, int r, float eps)
+// Weight of token i of problem p: its mass, or `uniform` where the masses are implicit.
+__device__ inline float row_weight(const float* mass, float uniform, size_t row)
+{
+    return mass ? mass[row] : uniform;
+}
+
+// Ghat[p][i][t] = exp((C_it + g_t)/eps - lse_i), lse from the last token-side update.
+__global__ void bwd_unit_couplings(const float* __restrict__ C, const float* __restrict__ lse,
+                                   const float* __restrict__ gpot, float* __restrict__ ghat,
+                                   size_t total, int n, int r, float eps)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
     const size_t row = idx / r;
     const int t = (int)(idx % r);
-    gam[idx] = expf((C[idx] + f[row] + gpot[(row / n) * r + t]) / eps);
+    ghat[idx] = expf((C[idx] + gpot[(row / n) * r + t]) / eps - lse[row]);
 }
 
-// part[p][chunk][t][c] = sum over the chunk's tokens i of A[p][i][t] * X[p][i][c]
-// (A is fp32 [P][n][r]; X is [P][stride][dx] in the I/O type, n rows used).  One block per (p, chunk, t).
+// part[p][chunk][t][c] = sum over the chunk's tokens i of w_i A[p][i][t] * X[p][i][c]
+// (A is fp32 [P][n][r]; X is [P][stride][dx] in the I/O type, n rows used; w = row_weight).
+// One block per (p, chunk, t).
 template <typename T>
 __global__ void bwd_tx_partial(const float* __restrict__ A, const T* __restrict__ X, float* __restrict__ part,
+                               const float* __restrict__ mass, float uniform,
                                int n, int stride, int r, int dx, int chunks)
 {
     const int t = blockIdx.x % r;
@@ -52,7 +64,8 @@ __global__ void bwd_tx_partial(const float* __restrict__ A, const T* __restrict_
     const int i0 = chunk * kChunk, i1 = min(n, i0 + kChunk);
     for (int c = threadIdx.x; c < dx; c += blockDim.x) {
         float acc = 0.f;
-        for (int i = i0; i < i1; ++i) acc = fmaf(A[(p * n + i) * r + t], ld(X, (p * stride + i) * dx + c), acc);
+        for (int i = i0; i < i1; ++i)
+            acc = fmaf(row_weight(mass, uniform, p * n + i) * A[(p * n + i) * r + t], ld(X, (p * stride + i) * dx + c), acc);
         part[((p * chunks + chunk) * r + t) * dx + c] = acc;
     }
 }
@@ -87,10 +100,11 @@ __global__ void bwd_glue_pivots(float* __restrict__ Yp, float* __restrict__ dYp,
     }
 }
 
-// out[p][i][t] = scale * sum_c X[p][i][c] * M[p][t][c]        (dGamma1 = n dO Y'^T, dGamma2 = V dYraw^T)
+// out[p][i][t] = w_i * sum_c X[p][i][c] * M[p][t][c]        (dGhat1 = dO Y'^T, dGhat2 = a2 V dYraw^T)
 template <typename T>
 __global__ void bwd_outer(const T* __restrict__ X, const float* __restrict__ M, float* __restrict__ out,
-                          size_t total, int n, int stride, int r, int dx, float scale)
+                          const float* __restrict__ mass, float uniform,
+                          size_t total, int n, int stride, int r, int dx)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // (p, i, t)
     if (idx >= total) return;
@@ -100,12 +114,13 @@ __global__ void bwd_outer(const T* __restrict__ X, const float* __restrict__ M, 
     float acc = 0.f;
     const size_t row = p * stride + pi % n;          // X is [P][stride][dx]
     for (int c = 0; c < dx; ++c) acc = fmaf(ld(X, row * dx + c), M[(p * r + t) * dx + c], acc);
-    out[idx] = scale * acc;
+    out[idx] = row_weight(mass, uniform, pi) * acc;
 }
 
-// out[p][i][c] = sum_t A[p][i][t] * M[m(p)][t][c], M per problem (per_head = 0) or per head.
+// out[p][i][c] = w_i sum_t A[p][i][t] * M[m(p)][t][c], M per problem (per_head = 0) or per head.
 template <typename T>
 __global__ void bwd_apply(const float* __restrict__ A, const float* __restrict__ M, T* __restrict__ out,
+                          const float* __restrict__ mass, float uniform,
                           size_t total, int n, int stride, int r, int dx, int per_head, int H)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // (p, i, c)
@@ -116,7 +131,7 @@ __global__ void bwd_apply(const float* __restrict__ A, const float* __restrict__
     const size_t m = per_head ? (p % H) : p;
     float acc = 0.f;
     for (int t = 0; t < r; ++t) acc = fmaf(A[pi * r + t], M[(m * r + t) * dx + c], acc);
-    st(out, (p * stride + pi % n) * dx + c, acc);          // out is [P][stride][dx]
+    st(out, (p * stride + pi % n) * dx + c, row_weight(mass, uniform, pi) * acc);          // out is [P][stride][dx]
 }
 
 // colpart[pair][chunk][t] = sum over the chunk's tokens of A_it * B_it (B may be null: plain sum).
@@ -135,7 +150,7 @@ __global__ void bwd_col_partial(const float* __restrict__ A, const float* __rest
 }
 
 // Pivot-side bookkeeping of one reverse step, one thread per (pair, t).
-//   last != 0: colsum holds s_t = sum_i dGamma Gamma  -> dc, rho, db
+//   last != 0: colsum holds s_t = sum_i dGhat Ghat  -> dc, rho, db
 //   last == 0: dg holds dg^k                         -> dc, db
 // c^k_t = beta_t exp((g^{k-1}_t - g^k_t)/eps).
 __global__ void bwd_pivot_pre(const float* __restrict__ part, const float* __restrict__ g_prev,
@@ -160,13 +175,13 @@ __global__ void bwd_pivot_pre(const float* __restrict__ part, const float* __res
     }
 }
 
-// Token side of one reverse step, one thread per (pair, i):
-//   P_it = a softmax_t((C_it + gprev_t)/eps);  dP_it = [last] dGamma_it rho_t + dc_t;
-//   e_i = (1/a) sum_t dP_it P_it;  dY_it = P_it (dP_it - e_i);  dC_it (+)= dY_it/eps;  Ybuf = dY.
+// Token side of one reverse step, one thread per (problem, i):
+//   W_it = softmax_t((C_it + gprev_t)/eps);  dW_it = [last] dGhat_it rho_t + a_i dc_t;
+//   e_i = sum_t dW_it W_it;  dY_it = W_it (dW_it - e_i);  dC_it (+)= dY_it/eps;  Ybuf = dY.
 __global__ void bwd_rows(const float* __restrict__ C, const float* __restrict__ g_prev,
-                         const float* __restrict__ dGam, const float* __restrict__ rho,
+                         const float* __restrict__ dGhat, const float* __restrict__ rho,
                          const float* __restrict__ dc, float* __restrict__ dC, float* __restrict__ Ybuf,
-                         size_t rows, int n, int r, float eps, int last)
+                         const float* __restrict__ mass, size_t rows, int n, int r, float eps, int last)
 {
     const size_t row = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (row >= rows) return;
@@ -175,23 +190,22 @@ __global__ void bwd_rows(const float* __restrict__ C, const float* __restrict__ 
     const float* gp = g_prev + pair * r;
     const float* dcp = dc + pair * r;
     const float* rh = rho + pair * r;
+    const float a = row_weight(mass, 1.f / (float)n, row);
     float m = -INFINITY;
     for (int t = 0; t < r; ++t) m = fmaxf(m, (c[t] + gp[t]) / eps);
     float s = 0.f;
     for (int t = 0; t < r; ++t) s += expf((c[t] + gp[t]) / eps - m);
     const float inv_s = 1.f / s;
-    // e_i = (1/a) sum_t dP_it P_it with P_it = a * exp(.)/s  ->  sum_t dP_it exp(.)/s
     float e = 0.f;
     for (int t = 0; t < r; ++t) {
         const float w = expf((c[t] + gp[t]) / eps - m) * inv_s;
-        const float dP = (last ? dGam[row * r + t] * rh[t] : 0.f) + dcp[t];
-        e = fmaf(dP, w, e);
+        const float dW = (last ? dGhat[row * r + t] * rh[t] : 0.f) + a * dcp[t];
+        e = fmaf(dW, w, e);
     }
-    const float a = 1.f / (float)n;
     for (int t = 0; t < r; ++t) {
         const float w = expf((c[t] + gp[t]) / eps - m) * inv_s;
-        const float dP = (last ? dGam[row * r + t] * rh[t] : 0.f) + dcp[t];
-        const float dY = a * w * (dP - e);
+        const float dW = (last ? dGhat[row * r + t] * rh[t] : 0.f) + a * dcp[t];
+        const float dY = w * (dW - e);
         Ybuf[row * r + t] = dY;
         if (last) dC[row * r + t] = dY / eps;
         else dC[row * r + t] += dY / eps;
@@ -248,124 +262,155 @@ template <typename T>
 int run_backward_t(const BwdArgs& a)
 {
     const lot_shape& s = a.s;
-    const int G = s.B * s.H, n = s.n, r = s.r, pairs = 2 * G, T_ = a.iters;
-    const int chunks = (n + kChunk - 1) / kChunk;
-    const int stride = a.n_stride > 0 ? a.n_stride : n;      // tokens between problems in the caller's tensors
+    const int G = s.B * s.H, r = s.r, pairs = 2 * G, T_ = a.iters;
+    // side 0 = queries (and dO, dQ), side 1 = keys and values
+    const int ns[2] = {a.n_q > 0 ? a.n_q : s.n, a.n_k > 0 ? a.n_k : s.n};
+    const int strides[2] = {a.n_stride > 0 ? a.n_stride : ns[0], a.n_stride > 0 ? a.n_stride : ns[1]};
+    const float* masses[2] = {a.mass_q, a.mass_k};
+    const float unis[2] = {1.f / (float)ns[0], 1.f / (float)ns[1]};
+    const int chunkss[2] = {(ns[0] + kChunk - 1) / kChunk, (ns[1] + kChunk - 1) / kChunk};
+    const void* Xs[2] = {a.Q, a.K};
+    void* dXs[2] = {a.dQ, a.dK};
     const BwdWorkspace& L = a.lay;
-    float* C = (float*)(a.ws + L.C);
-    float* f = (float*)(a.ws + L.f);
-    float* ghist = (float*)(a.ws + L.ghist);       // [T+1][pairs][r]
+    const size_t side1 = (size_t)G * ns[0] * r;          // where side 1 starts in the [rows][r] arrays
+    float* Cb = (float*)(a.ws + L.C);
+    float* lseb = (float*)(a.ws + L.f);
+    float* ghatb = (float*)(a.ws + L.gam);
+    float* dghatb = (float*)(a.ws + L.dgam);
+    float* dCb = (float*)(a.ws + L.dC);
+    float* ybufb = (float*)(a.ws + L.ybuf);
+    float* Cs[2] = {Cb, Cb + side1};
+    float* lses[2] = {lseb, lseb + (size_t)G * ns[0]};
+    float* ghats[2] = {ghatb, ghatb + side1};
+    float* dghats[2] = {dghatb, dghatb + side1};
+    float* dCs[2] = {dCb, dCb + side1};
+    float* ybufs[2] = {ybufb, ybufb + side1};
+    float* ghist = (float*)(a.ws + L.ghist);       // [T+1][2][G][r]
     float* pm = (float*)(a.ws + L.part_m);
     float* ps = (float*)(a.ws + L.part_s);
-    float* gam = (float*)(a.ws + L.gam);           // [pairs][n][r]
-    float* dgam = (float*)(a.ws + L.dgam);
-    float* dC = (float*)(a.ws + L.dC);
-    float* ybuf = (float*)(a.ws + L.ybuf);
-    float* tx_part = (float*)(a.ws + L.tx_part);   // [pairs][chunks][r][dmax]
+    float* tx_part = (float*)(a.ws + L.tx_part);   // [G][chunks][r][dmax]
     float* Yp = (float*)(a.ws + L.Yp);
     float* dYp = (float*)(a.ws + L.dYp);
     float* db_glue = (float*)(a.ws + L.db_glue);
     float* colpart = (float*)(a.ws + L.colpart);
-    float* dc = (float*)(a.ws + L.dc);
+    float* dc = (float*)(a.ws + L.dc);             // [2][G][r], like rho, dg, db_pair
     float* rho = (float*)(a.ws + L.rho);
     float* dg = (float*)(a.ws + L.dg);
     float* db_pair = (float*)(a.ws + L.db_pair);
-    float* dZ_pair = (float*)(a.ws + L.dZ_pair);   // [pairs][r][d_k]
+    float* dZ_pair = (float*)(a.ws + L.dZ_pair);   // [2][G][r][d_k]
     float* Zr = (float*)(a.ws + L.Zr);
     hipStream_t st_ = a.stream;
     ref_mark<<<1, 1, 0, st_>>>((unsigned long long*)a.ws, next_nonce());   // no device-side waits on this path
-    const size_t slab = (size_t)pairs * r;
-    const size_t nelem = (size_t)pairs * n * r;
-    const size_t rows = (size_t)pairs * n;
-    const size_t half = (size_t)G * n * r;
+    const size_t slab = (size_t)G * r;                                     // one side's pivot vector
     const unsigned pr_blocks = blocks_for(slab, 256);
+    auto pot = [&](int k, int side) { return ghist + ((size_t)k * 2 + side) * slab; };
 
-    // ---- forward, keeping the pivot potentials of every iteration
-    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, stride, s.d_k, r,
-                                                         s.io_dtype == LOT_BF16);
-    ref_zero<<<pr_blocks, 256, 0, st_>>>(ghist, slab);
-    for (int k = 1; k <= T_; ++k) {
-        ref_f_update<<<blocks_for(rows, 256), 256, 0, st_>>>(C, ghist + (size_t)(k - 1) * slab, f, rows, n, r, a.eps);
-        ref_g_partial<<<(unsigned)pairs * chunks, 64, 0, st_>>>(C, f, pm, ps, n, r, chunks, a.eps);
-        ref_g_final<<<pr_blocks, 256, 0, st_>>>(pm, ps, a.beta, ghist + (size_t)k * slab, pairs, G, s.H, r, chunks, a.eps);
+    // ---- forward, keeping the pivot potentials of every iteration and the last row normalisers
+    for (int sd = 0; sd < 2; ++sd) {
+        const int n = ns[sd], chunks = chunkss[sd];
+        const size_t total = (size_t)G * n * r, rows = (size_t)G * n;
+        xr_cost<T><<<blocks_for(total, 256), 256, 0, st_>>>((const T*)Xs[sd], a.Z, Cs[sd], total, s.H, n, strides[sd],
+                                                            s.d_k, r, s.io_dtype == LOT_BF16);
+        ref_zero<<<pr_blocks, 256, 0, st_>>>(pot(0, sd), slab);
+        for (int k = 1; k <= T_; ++k) {
+            xr_row_lse<<<blocks_for(rows, 256), 256, 0, st_>>>(Cs[sd], pot(k - 1, sd), lses[sd], rows, n, r, a.eps);
+            xr_col_partial<<<(unsigned)G * chunks, 64, 0, st_>>>(Cs[sd], lses[sd], masses[sd], pm, ps, n, r, chunks, a.eps);
+            xr_col_final<<<pr_blocks, 256, 0, st_>>>(pm, ps, a.beta, pot(k, sd), G, s.H, r, chunks, a.eps);
+        }
+        bwd_unit_couplings<<<blocks_for(total, 256), 256, 0, st_>>>(Cs[sd], lses[sd], pot(T_, sd), ghats[sd], total, n, r, a.eps);
     }
-    bwd_couplings<<<blocks_for(nelem, 256), 256, 0, st_>>>(C, f, ghist + (size_t)T_ * slab, gam, nelem, n, r, a.eps);
-    const float* gam1 = gam;            // [G][n][r]
-    const float* gam2 = gam + half;     // [G][n][r]  (token-major: the transpose of the r x n plan)
 
     // ---- glue
-    // Y' = Diag(beta)^-1 Gamma2 V
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(gam2, (const T*)a.V, tx_part, n, stride, r, s.d_v, chunks);
-    bwd_tx_final<<<blocks_for((size_t)G * r * s.d_v, 256), 256, 0, st_>>>(tx_part, Yp, (size_t)G * r * s.d_v, r, s.d_v, chunks, 1.f);
+    const size_t yelems = (size_t)G * r * s.d_v;
+    // Y'_t = (1/beta_t) sum_j a2_j Ghat2_jt V_j
+    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunkss[1] * r), 64, 0, st_>>>(ghats[1], (const T*)a.V, tx_part, masses[1], unis[1],
+                                                                              ns[1], strides[1], r, s.d_v, chunkss[1]);
+    bwd_tx_final<<<blocks_for(yelems, 256), 256, 0, st_>>>(tx_part, Yp, yelems, r, s.d_v, chunkss[1], 1.f);
     bwd_glue_pivots<<<blocks_for((size_t)G * r, 128), 128, 0, st_>>>(Yp, dYp, a.beta, db_glue, G * r, s.H, r, s.d_v, 0);
-    // dY' = n Gamma1^T dO
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(gam1, (const T*)a.dO, tx_part, n, stride, r, s.d_v, chunks);
-    bwd_tx_final<<<blocks_for((size_t)G * r * s.d_v, 256), 256, 0, st_>>>(tx_part, dYp, (size_t)G * r * s.d_v, r, s.d_v, chunks, (float)n);
-    // dGamma1 = n dO Y'^T (before dY' is rescaled; it does not use dY')
-    bwd_outer<T><<<blocks_for(half, 256), 256, 0, st_>>>((const T*)a.dO, Yp, dgam, half, n, stride, r, s.d_v, (float)n);
+    // dY' = Ghat1^T dO
+    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunkss[0] * r), 64, 0, st_>>>(ghats[0], (const T*)a.dO, tx_part, nullptr, 1.f,
+                                                                              ns[0], strides[0], r, s.d_v, chunkss[0]);
+    bwd_tx_final<<<blocks_for(yelems, 256), 256, 0, st_>>>(tx_part, dYp, yelems, r, s.d_v, chunkss[0], 1.f);
+    // dGhat1 = dO Y'^T (does not use dY')
+    bwd_outer<T><<<blocks_for((size_t)G * ns[0] * r, 256), 256, 0, st_>>>((const T*)a.dO, Yp, dghats[0], nullptr, 1.f,
+                                                                          (size_t)G * ns[0] * r, ns[0], strides[0], r, s.d_v);
     // db_glue, dYraw = dY'/beta
     bwd_glue_pivots<<<blocks_for((size_t)G * r, 128), 128, 0, st_>>>(Yp, dYp, a.beta, db_glue, G * r, s.H, r, s.d_v, 1);
-    // dV = Gamma2^T dYraw ; dGamma2 = V dYraw^T
-    bwd_apply<T><<<blocks_for((size_t)G * n * s.d_v, 256), 256, 0, st_>>>(gam2, dYp, (T*)a.dV, (size_t)G * n * s.d_v, n, stride, r, s.d_v, 0, s.H);
-    bwd_outer<T><<<blocks_for(half, 256), 256, 0, st_>>>((const T*)a.V, dYp, dgam + half, half, n, stride, r, s.d_v, 1.f);
+    // dV_j = a2_j sum_t Ghat2_jt dYraw_t ; dGhat2_jt = a2_j <V_j, dYraw_t>
+    bwd_apply<T><<<blocks_for((size_t)G * ns[1] * s.d_v, 256), 256, 0, st_>>>(ghats[1], dYp, (T*)a.dV, masses[1], unis[1],
+                                                                              (size_t)G * ns[1] * s.d_v, ns[1], strides[1], r, s.d_v, 0, s.H);
+    bwd_outer<T><<<blocks_for((size_t)G * ns[1] * r, 256), 256, 0, st_>>>((const T*)a.V, dYp, dghats[1], masses[1], unis[1],
+                                                                          (size_t)G * ns[1] * r, ns[1], strides[1], r, s.d_v);
 
-    // ---- both Sinkhorn solves, reverse sweep (the two solves side by side: pair = side * G + g)
-    bwd_col_partial<<<(unsigned)pairs * chunks, 64, 0, st_>>>(dgam, gam, colpart, n, r, chunks);
-    for (int k = T_; k >= 1; --k) {
-        const int last = k == T_;
-        const float* g_prev = ghist + (size_t)(k - 1) * slab;
-        const float* g_cur = ghist + (size_t)k * slab;
-        bwd_pivot_pre<<<pr_blocks, 256, 0, st_>>>(colpart, g_prev, g_cur, a.beta, dg, dc, rho, db_pair, pairs, G, s.H, r, chunks, a.eps, last);
-        bwd_rows<<<blocks_for(rows, 256), 256, 0, st_>>>(C, g_prev, dgam, rho, dc, dC, ybuf, rows, n, r, a.eps, last);
-        bwd_col_partial<<<(unsigned)pairs * chunks, 64, 0, st_>>>(ybuf, nullptr, colpart, n, r, chunks);
-        bwd_pivot_post<<<pr_blocks, 256, 0, st_>>>(colpart, dg, pairs, r, chunks, a.eps, last);
-    }
-
-    // ---- similarities: dQ = dC1 Z, dK = dC2 Z, dZ = sum_b (dC1^T Q + dC2^T K)
+    // ---- both Sinkhorn solves, reverse sweep
     bwd_round_z<<<blocks_for((size_t)s.H * r * s.d_k, 256), 256, 0, st_>>>(a.Z, Zr, s.H * r * s.d_k, s.io_dtype == LOT_BF16);
-    bwd_apply<T><<<blocks_for((size_t)G * n * s.d_k, 256), 256, 0, st_>>>(dC, Zr, (T*)a.dQ, (size_t)G * n * s.d_k, n, stride, r, s.d_k, 1, s.H);
-    bwd_apply<T><<<blocks_for((size_t)G * n * s.d_k, 256), 256, 0, st_>>>(dC + half, Zr, (T*)a.dK, (size_t)G * n * s.d_k, n, stride, r, s.d_k, 1, s.H);
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(dC, (const T*)a.Q, tx_part, n, stride, r, s.d_k, chunks);
-    bwd_tx_final<<<blocks_for((size_t)G * r * s.d_k, 256), 256, 0, st_>>>(tx_part, dZ_pair, (size_t)G * r * s.d_k, r, s.d_k, chunks, 1.f);
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(dC + half, (const T*)a.K, tx_part, n, stride, r, s.d_k, chunks);
-    bwd_tx_final<<<blocks_for((size_t)G * r * s.d_k, 256), 256, 0, st_>>>(tx_part, dZ_pair + (size_t)G * r * s.d_k, (size_t)G * r * s.d_k, r, s.d_k, chunks, 1.f);
+    for (int sd = 0; sd < 2; ++sd) {
+        const int n = ns[sd], chunks = chunkss[sd];
+        const size_t rows = (size_t)G * n;
+        float* dc_s = dc + sd * slab; float* rho_s = rho + sd * slab; float* dg_s = dg + sd * slab;
+        float* db_s = db_pair + sd * slab;
+        bwd_col_partial<<<(unsigned)G * chunks, 64, 0, st_>>>(dghats[sd], ghats[sd], colpart, n, r, chunks);
+        for (int k = T_; k >= 1; --k) {
+            const int last = k == T_;
+            bwd_pivot_pre<<<pr_blocks, 256, 0, st_>>>(colpart, pot(k - 1, sd), pot(k, sd), a.beta, dg_s, dc_s, rho_s, db_s, G, G, s.H, r,
+                                                      chunks, a.eps, last);
+            bwd_rows<<<blocks_for(rows, 256), 256, 0, st_>>>(Cs[sd], pot(k - 1, sd), dghats[sd], rho_s, dc_s, dCs[sd], ybufs[sd],
+                                                             masses[sd], rows, n, r, a.eps, last);
+            bwd_col_partial<<<(unsigned)G * chunks, 64, 0, st_>>>(ybufs[sd], nullptr, colpart, n, r, chunks);
+            bwd_pivot_post<<<pr_blocks, 256, 0, st_>>>(colpart, dg_s, G, r, chunks, a.eps, last);
+        }
+        // similarities: dX = dC Z, dZ share = dC^T X
+        bwd_apply<T><<<blocks_for(rows * s.d_k, 256), 256, 0, st_>>>(dCs[sd], Zr, (T*)dXs[sd], nullptr, 1.f, rows * s.d_k, n, strides[sd],
+                                                                     r, s.d_k, 1, s.H);
+        bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(dCs[sd], (const T*)Xs[sd], tx_part, nullptr, 1.f, n,
+                                                                              strides[sd], r, s.d_k, chunks);
+        bwd_tx_final<<<blocks_for((size_t)G * r * s.d_k, 256), 256, 0, st_>>>(tx_part, dZ_pair + (size_t)sd * G * r * s.d_k,
+                                                                              (size_t)G * r * s.d_k, r, s.d_k, chunks, 1.f);
+    }
     bwd_head_sums<<<blocks_for((size_t)s.H * r * (s.d_k + 1), 256), 256, 0, st_>>>(dZ_pair, db_pair, db_glue, a.dZ, a.dbeta, s.B, s.H, r, s.d_k);
+    (void)pairs;
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }
 
 }  // namespace
 
-BwdWorkspace carve_bwd(const lot_shape& s, int iters)
+BwdWorkspace carve_bwd_sides(int B, int H, int n_q, int n_k, int r, int d_k, int d_v, int iters)
 {
     BwdWorkspace w{};
     size_t off = 256;      // the status words come first, as in the other workspaces
     auto take = [&](size_t bytes) { size_t at = off; off += (bytes + 255) / 256 * 256; return at; };
-    const size_t G = (size_t)s.B * s.H, n = s.n, r = s.r, pairs = 2 * G;
-    const size_t chunks = (n + kRefChunk - 1) / kRefChunk;
-    const size_t dmax = s.d_k > s.d_v ? s.d_k : s.d_v;
-    w.C = take(pairs * n * r * 4);
-    w.f = take(pairs * n * 4);
+    const size_t G = (size_t)B * H, rows = G * ((size_t)n_q + n_k), pairs = 2 * G;
+    const size_t nmax = n_q > n_k ? n_q : n_k;
+    const size_t chunks = (nmax + kRefChunk - 1) / kRefChunk;
+    const size_t dmax = d_k > d_v ? d_k : d_v;
+    w.C = take(rows * r * 4);
+    w.f = take(rows * 4);
     w.ghist = take((size_t)(iters + 1) * pairs * r * 4);
-    w.part_m = take(pairs * chunks * r * 4);
-    w.part_s = take(pairs * chunks * r * 4);
-    w.gam = take(pairs * n * r * 4);
-    w.dgam = take(pairs * n * r * 4);
-    w.dC = take(pairs * n * r * 4);
-    w.ybuf = take(pairs * n * r * 4);
+    w.part_m = take(G * chunks * r * 4);
+    w.part_s = take(G * chunks * r * 4);
+    w.gam = take(rows * r * 4);
+    w.dgam = take(rows * r * 4);
+    w.dC = take(rows * r * 4);
+    w.ybuf = take(rows * r * 4);
     w.tx_part = take(G * chunks * r * dmax * 4);
-    w.Yp = take(G * r * s.d_v * 4);
-    w.dYp = take(G * r * s.d_v * 4);
+    w.Yp = take(G * r * d_v * 4);
+    w.dYp = take(G * r * d_v * 4);
     w.db_glue = take(G * r * 4);
-    w.colpart = take(pairs * chunks * r * 4);
+    w.colpart = take(G * chunks * r * 4);
     w.dc = take(pairs * r * 4);
     w.rho = take(pairs * r * 4);
     w.dg = take(pairs * r * 4);
     w.db_pair = take(pairs * r * 4);
-    w.dZ_pair = take(pairs * r * s.d_k * 4);
-    w.Zr = take((size_t)s.H * r * s.d_k * 4);
+    w.dZ_pair = take(pairs * r * d_k * 4);
+    w.Zr = take((size_t)H * r * d_k * 4);
     w.total = off;
     return w;
+}
+
+BwdWorkspace carve_bwd(const lot_shape& s, int iters)
+{
+    return carve_bwd_sides(s.B, s.H, s.n, s.n, s.r, s.d_k, s.d_v, iters);
 }
 
 int run_backward(const BwdArgs& a)

@@ -16,81 +16,6 @@
 namespace lot {
 namespace {
 
-// C[g][i][t] = <x_i, z_t> for one side (n tokens per problem)
-template <typename T>
-__global__ void xr_cost(const T* __restrict__ X, const float* __restrict__ Z, float* __restrict__ C,
-                        size_t total, int H, int n, int d, int r, int round_z)
-{
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const size_t gi = idx / r;
-    const int t = (int)(idx % r);
-    const int g = (int)(gi / n);
-    const T* x = X + gi * d;
-    const float* z = Z + ((size_t)(g % H) * r + t) * d;
-    float acc = 0.f;
-    for (int c = 0; c < d; ++c) {
-        float zv = z[c];
-        if (round_z) zv = bf16_to_f32(f32_to_bf16_rne(zv));
-        acc = fmaf(ld(x, c), zv, acc);
-    }
-    C[idx] = acc;
-}
-
-// lse_i = LSE_t((C_it + g_t)/eps), one thread per (g, i)
-__global__ void xr_row_lse(const float* __restrict__ C, const float* __restrict__ gpot, float* __restrict__ lse,
-                           size_t rows, int n, int r, float eps)
-{
-    const size_t row = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= rows) return;
-    const float* c = C + row * r;
-    const float* g = gpot + (row / n) * r;
-    float m = -INFINITY;
-    for (int t = 0; t < r; ++t) m = fmaxf(m, (c[t] + g[t]) / eps);
-    float s = 0.f;
-    for (int t = 0; t < r; ++t) s += expf((c[t] + g[t]) / eps - m);
-    lse[row] = m + logf(s);
-}
-
-// per (g, chunk, t): running maximum and scaled sum of mass_i exp(C_it/eps - lse_i) over the chunk
-__global__ void xr_col_partial(const float* __restrict__ C, const float* __restrict__ lse,
-                               const float* __restrict__ mass, float* __restrict__ part_m,
-                               float* __restrict__ part_s, int n, int r, int chunks, float eps)
-{
-    const int g = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
-    const int i0 = chunk * kRefChunk, i1 = min(n, i0 + kRefChunk);
-    for (int t = threadIdx.x; t < r; t += blockDim.x) {
-        float m = -INFINITY, s = 0.f;
-        for (int i = i0; i < i1; ++i) {
-            const float w = mass ? mass[(size_t)g * n + i] : 1.f / (float)n;
-            if (!(w > 0.f)) continue;
-            const float x = C[((size_t)g * n + i) * r + t] / eps - lse[(size_t)g * n + i] + logf(w);
-            if (x > m) { s = s * expf(m - x) + 1.f; m = x; }
-            else s += expf(x - m);
-        }
-        part_m[((size_t)g * chunks + chunk) * r + t] = m;
-        part_s[((size_t)g * chunks + chunk) * r + t] = s;
-    }
-}
-
-// g_t = eps (log beta_t - LSE_i(C_it/eps - lse_i + log mass_i)), chunks combined in index order
-__global__ void xr_col_final(const float* __restrict__ part_m, const float* __restrict__ part_s,
-                             const float* __restrict__ beta, float* __restrict__ gpot, int G, int H, int r,
-                             int chunks, float eps)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= G * r) return;
-    const int g = idx / r, t = idx % r;
-    float m = -INFINITY;
-    for (int k = 0; k < chunks; ++k) m = fmaxf(m, part_m[((size_t)g * chunks + k) * r + t]);
-    float s = 0.f;
-    for (int k = 0; k < chunks; ++k) {
-        const float pm = part_m[((size_t)g * chunks + k) * r + t];
-        if (pm > -INFINITY) s += part_s[((size_t)g * chunks + k) * r + t] * expf(pm - m);
-    }
-    gpot[idx] = eps * (logf(beta[(g % H) * r + t]) - (m + logf(s)));
-}
-
 // Y'[g][t][c] = (1/beta_t) sum_j mass_j exp((C2_jt + g2_t)/eps - lse2_j) V_j[c]
 template <typename T>
 __global__ void xr_reduce_y(const float* __restrict__ C, const float* __restrict__ lse,
@@ -148,7 +73,7 @@ int run_cross_reference_t(const CrossArgs& a)
     for (int s = 0; s < 2; ++s) {
         const int n = ns[s], chunks = (n + kRefChunk - 1) / kRefChunk;
         const size_t total = (size_t)G * n * r, rows = (size_t)G * n;
-        xr_cost<T><<<blocks_for(total, 256), 256, 0, st_>>>((const T*)Xs[s], a.Z, Cs[s], total, a.H, n, a.d_k, r,
+        xr_cost<T><<<blocks_for(total, 256), 256, 0, st_>>>((const T*)Xs[s], a.Z, Cs[s], total, a.H, n, n, a.d_k, r,
                                                             a.io_dtype == LOT_BF16);
         ref_zero<<<blocks_for((size_t)G * r, 256), 256, 0, st_>>>(gs[s], (size_t)G * r);
         for (int it = 0; it < a.iters; ++it) {

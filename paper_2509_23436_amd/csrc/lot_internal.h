@@ -112,15 +112,17 @@ struct Args {
 
 // Workspace of the backward pass (plain path): byte offsets, multiples of 256.
 struct BwdWorkspace {
-    size_t C, f, ghist, part_m, part_s;   // forward recomputation; ghist = float [iters+1][2G][r]
-    size_t gam, dgam, dC, ybuf;           // float [2G][n][r] each
+    size_t C, f, ghist, part_m, part_s;   // forward recomputation: float [G (n_q + n_k)][r], row normalisers
+                                          // [G (n_q + n_k)], ghist = float [iters+1][2][G][r]
+    size_t gam, dgam, dC, ybuf;           // float [G (n_q + n_k)][r] each: the query side first
     size_t tx_part;                       // float [G][chunks][r][max(d_k, d_v)]
     size_t Yp, dYp, db_glue;              // float [G][r][d_v] x 2, float [G][r]
-    size_t colpart, dc, rho, dg, db_pair; // float [2G][chunks][r], float [2G][r] x 4
-    size_t dZ_pair, Zr;                   // float [2G][r][d_k], float [H][r][d_k]
+    size_t colpart, dc, rho, dg, db_pair; // float [G][chunks][r], float [2][G][r] x 4
+    size_t dZ_pair, Zr;                   // float [2][G][r][d_k], float [H][r][d_k]
     size_t total;
 };
 BwdWorkspace carve_bwd(const lot_shape& s, int iters);
+BwdWorkspace carve_bwd_sides(int B, int H, int n_q, int n_k, int r, int d_k, int d_v, int iters);
 
 struct BwdArgs {
     lot_shape s;
@@ -137,7 +139,10 @@ struct BwdArgs {
     void* dV;
     float* dZ;
     float* dbeta;
-    int n_stride;       // tokens between consecutive problems in Q, K, V, dO, dQ, dK, dV; 0 = s.n
+    int n_stride;       // tokens between consecutive problems in Q, K, V, dO, dQ, dK, dV; 0 = contiguous
+    int n_q, n_k;       // tokens per problem on the query and on the key side; 0 = s.n (plain path only)
+    const float* mass_q;   // [B,H,n_q] token masses, or null: uniform (plain path only)
+    const float* mass_k;   // [B,H,n_k]
     char* ws;
     BwdWorkspace lay;
     hipStream_t stream;

@@ -19,6 +19,7 @@ PATH_AUTO, PATH_REFERENCE, PATH_FUSED = 0, 1, 2
 EXPORTS = ("lot_workspace_bytes", "lot_attention_fwd", "lot_couplings", "lot_attention_fwd_path",
            "lot_couplings_path", "lot_attention_cls_fwd", "lot_attention_cls_fwd_path", "lot_cross_workspace_bytes", "lot_cross_attention_fwd", "lot_cross_attention_fwd_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
            "lot_attention_cls_bwd", "lot_attention_cls_bwd_path",
+           "lot_cross_attention_bwd_workspace_bytes", "lot_cross_attention_bwd",
            "lot_workspace_status", "lot_strerror", "lot_version")
 
 
@@ -254,3 +255,37 @@ def lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=None, mass_k=No
                                               _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(),
                                               int(path)))
     return out
+
+
+def lot_cross_attention_bwd(Q, K, V, Z, beta, eps, iters, dO, mass_q=None, mass_k=None, workspace=None):
+    """(dQ, dK, dV, dZ, dbeta) of <lot_cross_attention_fwd(...), dO>; the masses are not differentiated."""
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
+        _require(t, nm, Q.dtype)
+    _require(Z, "Z", torch.float32)
+    _require(beta, "beta", torch.float32)
+    B, H, n_q, d_k = Q.shape
+    n_k, d_v = K.shape[2], V.shape[3]
+    if tuple(dO.shape) != (B, H, n_q, d_v):
+        raise ValueError("dO must be [B, H, n_q, d_v]")
+    dt = LOT_F32 if Q.dtype == torch.float32 else LOT_BF16
+    shape = lot_xshape(B, H, n_q, n_k, d_k, d_v, Z.shape[1], dt)
+    for m, nm, n in ((mass_q, "mass_q", n_q), (mass_k, "mass_k", n_k)):
+        if m is not None:
+            _require(m, nm, torch.float32)
+            if tuple(m.shape) != (B, H, n):
+                raise ValueError(nm + " must be [B, H, n]")
+    need = ctypes.c_size_t(0)
+    _check(lib().lot_cross_attention_bwd_workspace_bytes(ctypes.byref(shape), int(iters), ctypes.byref(need)))
+    if workspace is None:
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=Q.device)
+    _require(workspace, "workspace", torch.uint8)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    dZ, dbeta = torch.empty_like(Z), torch.empty_like(beta)
+    null = ctypes.c_void_p(0)
+    _check(lib().lot_cross_attention_bwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
+                                         _ptr(mass_q) if mass_q is not None else null,
+                                         _ptr(mass_k) if mass_k is not None else null,
+                                         ctypes.c_float(eps), int(iters), _ptr(dO),
+                                         _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dZ), _ptr(dbeta),
+                                         _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
+    return dQ, dK, dV, dZ, dbeta

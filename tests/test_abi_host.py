@@ -152,3 +152,15 @@ def test_cls_and_cross_entry_points_reject_bad_arguments(L):
     for kw, code in ((dict(K=0), -1), (dict(eps=-1.0), -3), (dict(mq=0x5002), -7), (dict(ws_bytes=128), -6),
                      (dict(path=7), -9), (dict(path=2, shape=lot.lot_xshape(1, 1, 40, 70, 16, 16, 8, 0)), -9)):
         assert cross(**kw) == code, (kw, code)
+
+    def cross_bwd(mq=0x5000, dO=0x6000, eps=0.1, ws_bytes=1 << 40, iters=5, shape=x, dQ=0x7000):
+        return L.lot_cross_attention_bwd(ctypes.byref(shape), vp(0x1000), vp(0x2000), vp(0x3000), vp(0x100), vp(0x200),
+                                         vp(mq), vp(0), ctypes.c_float(eps), iters, vp(dO), vp(dQ), vp(0x8000), vp(0x9000),
+                                         vp(0x300), vp(0x400), vp(1 << 20), ctypes.c_size_t(ws_bytes), None)
+
+    assert L.lot_cross_attention_bwd_workspace_bytes(ctypes.byref(x), 5, ctypes.byref(need)) == 0 and need.value % 256 == 0
+    assert L.lot_cross_attention_bwd_workspace_bytes(ctypes.byref(x), 0, ctypes.byref(need)) == -4
+    for kw, code in ((dict(dO=0), -1), (dict(dQ=0), -1), (dict(eps=0.0), -3), (dict(iters=0), -4), (dict(mq=0x5002), -7),
+                     (dict(dO=0x6004), -7), (dict(ws_bytes=128), -6),
+                     (dict(shape=lot.lot_xshape(1, 1, 40, 0, 32, 32, 8, 0)), -2)):
+        assert cross_bwd(**kw) == code, (kw, code)

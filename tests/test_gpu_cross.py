@@ -80,3 +80,71 @@ def test_cross_attention_matches_oracle(name, path_name):
     err = rel_max_err(O, ref)
     print("  max-norm rel err %.3e (bar %.0e)" % (err, tol), flush=True)
     assert err <= tol
+
+
+# ---- backward
+
+BWD_CASES = {
+    "tiny_uniform": dict(B=1, H=2, n_q=40, n_k=70, d=32, d_v=32, r=8, seed=510, bf16=False, masses="uniform", eps=0.1, iters=6),
+    "tiny_masses": dict(B=2, H=2, n_q=50, n_k=33, d=32, d_v=32, r=8, seed=511, bf16=False, masses="random", eps=0.1, iters=6),
+    "padded_f32": dict(B=2, H=3, n_q=197, n_k=300, d=64, d_v=64, r=16, seed=512, bf16=False, masses="padded", eps=0.1, iters=8),
+    "bf16_cross": dict(B=1, H=2, n_q=700, n_k=1300, d=64, d_v=64, r=64, seed=513, bf16=True, masses="random", eps=0.05, iters=5),
+    "bf16_padded_d32": dict(B=2, H=3, n_q=600, n_k=400, d=32, d_v=32, r=32, seed=514, bf16=True, masses="padded", eps=0.1, iters=6),
+    "other_dims": dict(B=1, H=2, n_q=60, n_k=90, d=16, d_v=24, r=80, seed=515, bf16=False, masses="random", eps=0.1, iters=4),
+    "equal_uniform_bf16": dict(B=1, H=2, n_q=500, n_k=500, d=64, d_v=64, r=32, seed=516, bf16=True, masses="uniform", eps=0.05, iters=5),
+}
+
+
+@pytest.mark.parametrize("name", list(BWD_CASES))
+def test_cross_backward_matches_oracle(name):
+    import torch
+    from oracle import lot_oracle_bwd
+    from paper_2509_23436_amd import lot
+    c = dict(BWD_CASES[name])
+    eps, iters = c.pop("eps"), c.pop("iters")
+    x = _inputs(**c)
+    print("case %s: %r" % (name, BWD_CASES[name]), flush=True)
+    B, H, n_q, n_k = c["B"], c["H"], c["n_q"], c["n_k"]
+    dO = np.random.default_rng(c["seed"] + 17).standard_normal((B, H, n_q, c["d_v"])).astype(np.float32)
+    if c["bf16"]:
+        dO = synth.round_to_bf16(dO)
+    mq = x["mq"] if x["mq"] is not None else np.full((B, H, n_q), 1.0 / n_q)
+    mk = x["mk"] if x["mk"] is not None else np.full((B, H, n_k), 1.0 / n_k)
+    refs, _ = lot_oracle_bwd.cross_attention_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], mq, mk, eps, iters, dO)
+
+    def dev(a, io=False):
+        if a is None:
+            return None
+        if io and c["bf16"]:
+            return torch.from_numpy(synth.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    ws = None
+    outs = []
+    for fill in (0x00, 0xA5):                       # twice on one workspace with different contents
+        got = lot.lot_cross_attention_bwd(dev(x["Q"], True), dev(x["K"], True), dev(x["V"], True), dev(x["Z"]),
+                                          dev(x["beta"]), eps, iters, dev(dO, True), mass_q=dev(x["mq"]),
+                                          mass_k=dev(x["mk"]), workspace=ws)
+        torch.cuda.synchronize()
+        outs.append(got)
+        if ws is None:
+            shape = lot.lot_xshape(B, H, n_q, n_k, c["d"], c["d_v"], c["r"], 1 if c["bf16"] else 0)
+            import ctypes
+            need = ctypes.c_size_t(0)
+            assert lot.lib().lot_cross_attention_bwd_workspace_bytes(ctypes.byref(shape), iters, ctypes.byref(need)) == 0
+            ws = torch.full((need.value,), fill ^ 0xFF, dtype=torch.uint8, device="cuda")
+    for a, b in zip(*outs):
+        assert torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
+                           b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
+    assert lot.lot_workspace_status(ws) == 0
+    tol = 2e-2 if c["bf16"] else 1e-4
+    for nm, g, ref in zip(("dQ", "dK", "dV", "dZ", "dbeta"), outs[0], refs):
+        g = to_host_f64(g)
+        assert np.isfinite(g).all(), nm
+        err = rel_max_err(g, ref)
+        print("  %-5s max-norm rel err %.3e (bar %.0e)" % (nm, err, tol), flush=True)
+        assert err <= tol, nm
+    if c["masses"] == "padded":                     # padding keys: exactly no gradient
+        pad = mk == 0.0
+        for g in (outs[0][1], outs[0][2]):
+            assert float(to_host_f64(g)[pad].__abs__().max()) == 0.0
