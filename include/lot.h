@@ -184,11 +184,10 @@ int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K,
  * Backward of lot_cross_attention_fwd (same inputs; dO [B,H,n_q,d_v]).  Writes dQ [B,H,n_q,d_k],
  * dK [B,H,n_k,d_k], dV [B,H,n_k,d_v] in io_dtype and dZ, dbeta in fp32 (summed over the batch).  The
  * masses are data (a padding mask), not differentiated; a key of mass zero receives exactly zero
- * gradient, a query of mass zero the gradient of its own output row.  Runs on the plain kernels (one
- * per step, n x r intermediates in the workspace) unless the lengths are equal and both mass
- * pointers are null, which is lot_attention_bwd.  Workspace:
- * lot_cross_attention_bwd_workspace_bytes; contents on entry do not matter; lot_workspace_status
- * applies.  Reproducible bit for bit.
+ * gradient, a query of mass zero the gradient of its own output row.  Execution paths as for
+ * lot_attention_bwd (FUSED: d_k = d_v in {32, 64}, r <= 64, iters <= 32; AUTO prefers it).
+ * Workspace: lot_cross_attention_bwd_workspace_bytes (covers both paths); contents on entry do not
+ * matter; lot_workspace_status applies.  Reproducible bit for bit on either path.
  */
 int lot_cross_attention_bwd_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out);
 int lot_cross_attention_bwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
@@ -196,6 +195,11 @@ int lot_cross_attention_bwd(const lot_xshape* shape, const void* Q, const void* 
                             float eps, int iters, const void* dO,
                             void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+int lot_cross_attention_bwd_path(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                                 const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                                 float eps, int iters, const void* dO,
+                                 void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
  * Backward of lot_attention_cls_fwd (same inputs, eps, iters, beta_cls; dO = dL/dout, all n rows).

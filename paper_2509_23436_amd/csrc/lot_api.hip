@@ -362,22 +362,20 @@ int lot_cross_attention_bwd_workspace_bytes(const lot_xshape* shape, int iters, 
     if (!bytes_out) return LOT_ERR_NULL;
     if (iters < 1 || iters > (1 << 16)) return LOT_ERR_ITERS;
     size_t need = carve_bwd_sides(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_k, shape->d_v, iters).total;
-    if (shape->n_q == shape->n_k) {            // uniform masses may then take the tiled kernels
-        const lot_shape s{shape->B, shape->H, shape->n_q, shape->d_k, shape->d_v, shape->r, shape->io_dtype};
-        if (bwd_tiled_supports(s, iters)) {
-            const size_t tiled = carve_bwd_tiled(s, iters).total;
-            if (tiled > need) need = tiled;
-        }
+    const lot_shape longer = fused_view(*shape);
+    if (bwd_tiled_supports(longer, iters)) {
+        const size_t tiled = carve_bwd_tiled(longer, iters).total;
+        if (tiled > need) need = tiled;
     }
     *bytes_out = need;
     return LOT_OK;
 }
 
-int lot_cross_attention_bwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
-                            const float* Z, const float* beta, const float* mass_q, const float* mass_k,
-                            float eps, int iters, const void* dO,
-                            void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
-                            void* workspace, size_t workspace_bytes, void* hip_stream)
+int lot_cross_attention_bwd_path(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                                 const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                                 float eps, int iters, const void* dO,
+                                 void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream, int path)
 {
     int rc = validate_xshape(shape);
     if (rc != LOT_OK) return rc;
@@ -393,17 +391,35 @@ int lot_cross_attention_bwd(const lot_xshape* shape, const void* Q, const void* 
     rc = lot_cross_attention_bwd_workspace_bytes(shape, iters, &need);
     if (rc != LOT_OK) return rc;
     if (workspace_bytes < need) return LOT_ERR_WORKSPACE;
-    const lot_shape s{shape->B, shape->H, shape->n_q > shape->n_k ? shape->n_q : shape->n_k, shape->d_k, shape->d_v,
-                      shape->r, shape->io_dtype};
+    const lot_shape s = fused_view(*shape);        // n = the longer side
     BwdArgs a{};
     a.s = s; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
     a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
-    // equal lengths and implicit uniform masses: the plain method, with its tiled kernels where they apply
-    if (shape->n_q == shape->n_k && !mass_q && !mass_k && bwd_tiled_supports(s, iters)) return run_backward_tiled(a);
-    a.lay = carve_bwd_sides(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_k, shape->d_v, iters);
     a.n_q = shape->n_q; a.n_k = shape->n_k; a.mass_q = mass_q; a.mass_k = mass_k;
+    bool tiled = false;
+    switch (path) {
+    case LOT_PATH_AUTO: tiled = bwd_tiled_supports(s, iters); break;
+    case LOT_PATH_REFERENCE: tiled = false; break;
+    case LOT_PATH_FUSED:
+        if (!bwd_tiled_supports(s, iters)) return LOT_ERR_PATH;
+        tiled = true;
+        break;
+    default: return LOT_ERR_PATH;
+    }
+    if (tiled) return run_backward_tiled(a);
+    a.lay = carve_bwd_sides(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_k, shape->d_v, iters);
     return run_backward(a);
+}
+
+int lot_cross_attention_bwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
+                            const float* Z, const float* beta, const float* mass_q, const float* mass_k,
+                            float eps, int iters, const void* dO,
+                            void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return lot_cross_attention_bwd_path(shape, Q, K, V, Z, beta, mass_q, mass_k, eps, iters, dO, dQ, dK, dV, dZ, dbeta,
+                                        workspace, workspace_bytes, hip_stream, LOT_PATH_AUTO);
 }
 
 int lot_attention_cls_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,

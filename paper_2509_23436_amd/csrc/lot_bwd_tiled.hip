@@ -79,8 +79,11 @@ struct BtParams {
     float* db_pair;               // [pairs][64]
     float* db_glue;               // [G][64]
     float* dz_part;               // [pairs][chunks][64][D]
-    int G, H, B, n, r, chunks, tiles_per_wg, k, T;
-    int stride;                   // tokens between consecutive problems in Q, K, V, dO, dQ, dK, dV (>= n)
+    int G, H, B, r, chunks, tiles_per_wg, k, T;
+    // per side (0 = queries, dO, dQ; 1 = keys, values, dK, dV):
+    int n_side[2];                // tokens per problem
+    int stride_side[2];           // tokens between consecutive problems in the caller's tensors (>= n_side)
+    const float* mass_side[2];    // [G][n_side] token masses, or null: uniform 1/n_side
     float eps, fx_scale, fx_unscale;
     uint32_t spin_limit;
     float sum_lo, sum_hi;         // row sums outside [sum_lo, sum_hi] make the assemble kernel re-shift its rows
@@ -89,6 +92,13 @@ struct BtParams {
 template <typename IO> __device__ __forceinline__ const IO* rows_of(const BtParams& p, int side)
 {
     return reinterpret_cast<const IO*>(side == 0 ? p.Q : p.K);
+}
+
+// Mass of a token times the number of tokens of its side (1 for uniform masses).
+__device__ __forceinline__ float token_weight(const BtParams& p, int side, int g, int tok)
+{
+    const float* m = p.mass_side[side];
+    return m ? (float)p.n_side[side] * as_global(m)[(size_t)g * p.n_side[side] + tok] : 1.f;
 }
 
 // A column-sum word: the number of workgroups that have contributed in the top byte, their fixed-point
@@ -125,18 +135,20 @@ __device__ __forceinline__ SweepPlace sweep_place(const BtParams& p)
     SweepPlace w;
     w.pair = blockIdx.x / p.chunks; w.chunk = blockIdx.x % p.chunks;
     w.side = w.pair / p.G; w.g = w.pair % p.G; w.h = w.g % p.H;
-    const int ntiles = (p.n + kTileTokens - 1) / kTileTokens;
+    const int ntiles = (p.n_side[w.side] + kTileTokens - 1) / kTileTokens;
     w.tile_begin = w.chunk * p.tiles_per_wg;
     w.tile_end = min(ntiles, w.tile_begin + p.tiles_per_wg);
     return w;
 }
 
-template <typename IO, int D>
-__device__ __forceinline__ void load_first_tile(Frag<IO, D>& xc, const BtParams& p, const SweepPlace& w, const IO* X,
-                                                int wave, int i, int kg)
+// MASS = false: the launch has no token masses; every token weight is the constant 1.
+template <typename IO, int D, bool MASS>
+__device__ __forceinline__ void load_first_tile(Frag<IO, D>& xc, float& mc, const BtParams& p, const SweepPlace& w,
+                                                const IO* X, int wave, int i, int kg)
 {
-    const int tok = min((w.tile_begin + wave) * kTileTokens + i, p.n - 1);
-    load_tokens<D>(xc, X + ((size_t)w.g * p.stride + tok) * D, kg);
+    const int tok = min((w.tile_begin + wave) * kTileTokens + i, p.n_side[w.side] - 1);
+    load_tokens<D>(xc, X + ((size_t)w.g * p.stride_side[w.side] + tok) * D, kg);
+    mc = MASS ? token_weight(p, w.side, w.g, tok) : 1.f;
 }
 
 template <typename IO, int D, int RB>
@@ -152,27 +164,31 @@ __device__ __forceinline__ void stash_head_pivots(const BtParams& p, int h, char
     stash_pivots<D, RB>(zstash, z0, lane);
 }
 
-// One pass over the wavefront's tiles with the potentials in sh.g.  xc holds the first tile's rows on
-// entry and, when `again`, once more on return (requested during the last tile, so that the next
-// pass does not start with a round trip to memory).
-template <typename IO, int D, int RB, bool WITH_U>
+// One pass over the wavefront's tiles with the potentials in sh.g.  xc and mc hold the first tile's
+// rows and token weights on entry and, when `again`, once more on return (requested during the last
+// tile, so that the next pass does not start with a round trip to memory).  The token weights (mass
+// times n, 1 if uniform) multiply the column sums, the Gram matrix (as square roots on both factors)
+// and the key side's contraction with V; the query side's contraction with dO is unweighted.
+template <typename IO, int D, int RB, bool WITH_U, bool MASS>
 __device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace& w, const IO* X, const IO* vals,
-                                            SweepShared<IO, D, RB>& sh, Frag<IO, D>& xc, bool again,
+                                            SweepShared<IO, D, RB>& sh, Frag<IO, D>& xc, float& mc, bool again,
                                             int wave, int lane, float c1,
                                             f32x16 (&cs)[RB], f32x16 (&Gm)[RB][RB], f32x16 (&U)[RB][D / 32])
 {
     constexpr int NB = D / 32;
     constexpr bool kSplit = io_is_f32<IO>::value;
-    const int i = lane & 31, kg = lane >> 5, n = p.n;
+    const int i = lane & 31, kg = lane >> 5, n = p.n_side[w.side], stride = p.stride_side[w.side];
     uint16_t* tr_hi = sh.tr + (wave * 2 + 0) * 64 * kTrStride;
     uint16_t* tr_lo = sh.tr + (wave * 2 + 1) * 64 * kTrStride;
     for (int tile = w.tile_begin + wave; tile < w.tile_end; tile += kWaves) {
         Frag<IO, D> xn = xc;
+        float mn = mc;
         if (tile + kWaves < w.tile_end) {
             const int tok = min((tile + kWaves) * kTileTokens + i, n - 1);
-            load_tokens<D>(xn, X + ((size_t)w.g * p.stride + tok) * D, kg);
+            load_tokens<D>(xn, X + ((size_t)w.g * stride + tok) * D, kg);
+            if (MASS) mn = token_weight(p, w.side, w.g, tok);
         } else if (again) {
-            load_first_tile<IO, D>(xn, p, w, X, wave, i, kg);
+            load_first_tile<IO, D, MASS>(xn, mn, p, w, X, wave, i, kg);
         }
         bf16x8 vh[2][NB], vl[2][NB];
         if (WITH_U) {
@@ -180,7 +196,7 @@ __device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace&
             for (int s = 0; s < 2; ++s) {
                 const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
                 const int left = max(1, min(8, n - t0));
-                load_values<D>(vh[s], vl[s], vals, (size_t)w.g * p.stride + min(t0, n - 1), left, i);
+                load_values<D>(vh[s], vl[s], vals, (size_t)w.g * stride + min(t0, n - 1), left, i);
             }
         }
         f32x16 acc[RB];
@@ -192,18 +208,23 @@ __device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace&
             fetch_pivots<D, RB>(zf, sh.zstash, lane, skew);
             tile_weights<IO, D, RB>(acc, wt, zf, xc, sh.g, kg, c1, tile * kTileTokens + i < n);
         }
+        // what goes through the transposition: W sqrt(m) for the Gram matrix, W m for the keys'
+        // contraction with V, W for the queries' contraction with dO
+        const float wcs = MASS ? wt * mc : wt;
+        const float wtr = !MASS ? wt : WITH_U ? (w.side == 1 ? wcs : wt) : wt * __builtin_amdgcn_sqrtf(mc);
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                acc[mb][j] *= wt;
-                if (!WITH_U) cs[mb][j] += acc[mb][j];
+                if (!WITH_U) cs[mb][j] = fmaf(acc[mb][j], wcs, cs[mb][j]);
+                acc[mb][j] *= wtr;
             }
         transpose_tile<RB, kSplit>(acc, tr_hi, tr_lo, i, kg);
         if (WITH_U) contract_tokens<D, RB, kSplit>(U, tr_hi, tr_lo, vh, vl, i, kg);
         else contract_gram<RB, kSplit>(Gm, tr_hi, tr_lo, i, kg);
         transpose_done();
         xc = xn;
+        mc = mn;
     }
 }
 
@@ -284,14 +305,14 @@ __device__ __forceinline__ void zero_pass(f32x16 (&cs)[RB], f32x16 (&Gm)[RB][RB]
 }
 
 // g^k from g^{k-1} and the complete column sums of pass k
-__device__ __forceinline__ float next_potential(const BtParams& p, float g_prev, unsigned long long word, int h, int t)
+__device__ __forceinline__ float next_potential(const BtParams& p, int side, float g_prev, unsigned long long word, int h, int t)
 {
-    return g_prev + p.eps * logf((float)p.n * p.beta[h * p.r + t] / colsum_of(word, p.fx_unscale));
+    return g_prev + p.eps * logf((float)p.n_side[side] * p.beta[h * p.r + t] / colsum_of(word, p.fx_unscale));
 }
 
 // One pass per launch (WITH_U = false: pass p.k; true: the contraction pass), for grids that cannot
 // be resident at once.
-template <typename IO, int D, int RB, bool WITH_U>
+template <typename IO, int D, int RB, bool WITH_U, bool MASS>
 __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
 {
     constexpr int NB = D / 32;
@@ -304,13 +325,14 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
 
     // the first tile is requested before anything else: its latency overlaps the set-up
     Frag<IO, D> xc;
-    load_first_tile<IO, D>(xc, p, w, X, wave, lane & 31, lane >> 5);
+    float mc;
+    load_first_tile<IO, D, MASS>(xc, mc, p, w, X, wave, lane & 31, lane >> 5);
 
     // g^{k-1} from the column sums of the previous launch
     if (tid < 64) {
         float gv = tid < r ? 0.f : kNegBig;
         if (k > 1 && tid < r)
-            gv = next_potential(p, p.ghist[((size_t)(k - 2) * pairs + w.pair) * 64 + tid],
+            gv = next_potential(p, w.side, p.ghist[((size_t)(k - 2) * pairs + w.pair) * 64 + tid],
                                 p.colacc[((size_t)(k - 1) * pairs + w.pair) * 64 + tid], w.h, tid);
         sh.g[tid] = gv;
         if (!WITH_U && w.chunk == 0) p.ghist[((size_t)(k - 1) * pairs + w.pair) * 64 + tid] = gv;
@@ -328,7 +350,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
             for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
     const IO* vals = reinterpret_cast<const IO*>(w.side == 0 ? p.dO : p.V);
     const float c1 = kLog2e / p.eps;
-    sweep_tiles<IO, D, RB, WITH_U>(p, w, X, vals, sh, xc, false, wave, lane, c1, cs, Gm, U);
+    sweep_tiles<IO, D, RB, WITH_U, MASS>(p, w, X, vals, sh, xc, mc, false, wave, lane, c1, cs, Gm, U);
     if (WITH_U) finish_contraction<IO, D, RB>(p, w, sh, tid, wave, lane, U);
     else finish_pass<IO, D, RB>(p, w, sh, k, tid, wave, lane, cs, Gm);
 }
@@ -336,7 +358,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
 // All T passes and the contraction pass in one launch.  Requires every workgroup of a pair to be
 // resident together (the host checks the grid against the device's capacity); the waits are bounded
 // all the same, and a wait that runs out marks the status word and ends the workgroup.
-template <typename IO, int D, int RB>
+template <typename IO, int D, int RB, bool MASS>
 __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
 {
     constexpr int NB = D / 32;
@@ -350,7 +372,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
     const float c1 = kLog2e / p.eps;
 
     Frag<IO, D> xc;
-    load_first_tile<IO, D>(xc, p, w, X, wave, lane & 31, lane >> 5);
+    float mc;
+    load_first_tile<IO, D, MASS>(xc, mc, p, w, X, wave, lane & 31, lane >> 5);
     if (wave == 0) stash_head_pivots<IO, D, RB>(p, w.h, sh.zstash, lane);
     if (tid == 0) s_ok = 1;
     float gv = tid < r ? 0.f : kNegBig;     // g^{k-1}_t, carried by thread t < 64
@@ -375,7 +398,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
                         s_ok = 0;
                     }
                 } else if (tid < r) {
-                    gv = next_potential(p, gv, word, w.h, tid);
+                    gv = next_potential(p, w.side, gv, word, w.h, tid);
                 }
             }
             sh.g[tid] = gv;
@@ -385,7 +408,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
         if (!s_ok) return;
         f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
         zero_pass<RB, NB>(cs, Gm);
-        sweep_tiles<IO, D, RB, false>(p, w, X, nullptr, sh, xc, true, wave, lane, c1, cs, Gm, U);
+        sweep_tiles<IO, D, RB, false, MASS>(p, w, X, nullptr, sh, xc, mc, true, wave, lane, c1, cs, Gm, U);
         finish_pass<IO, D, RB>(p, w, sh, k, tid, wave, lane, cs, Gm);
     }
     __syncthreads();
@@ -398,7 +421,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
         const IO* vals = reinterpret_cast<const IO*>(w.side == 0 ? p.dO : p.V);
-        sweep_tiles<IO, D, RB, true>(p, w, X, vals, sh, xc, false, wave, lane, c1, cs, Gm, U);
+        sweep_tiles<IO, D, RB, true, MASS>(p, w, X, vals, sh, xc, mc, false, wave, lane, c1, cs, Gm, U);
         __syncthreads();
         finish_contraction<IO, D, RB>(p, w, sh, tid, wave, lane, U);
     }
@@ -429,7 +452,7 @@ __global__ void bt_mid(BtParams p)
         const float cs1 = colsum_of(p.colacc[((size_t)T * pairs + g) * 64 + t], p.fx_unscale);
         const float cs2 = colsum_of(p.colacc[((size_t)T * pairs + p.G + g) * 64 + t], p.fx_unscale);
         y = (u0 + u1) / cs2;
-        dy = (float)p.n * (w0 + w1) / cs1;
+        dy = (float)p.n_side[0] * (w0 + w1) / cs1;
     }
     p.yp[idx] = y;
     p.dyraw[idx] = dy;
@@ -476,7 +499,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
     const int pairs = 2 * p.G;
     const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
     const int side = pair / p.G, g = pair % p.G, h = g % p.H;
-    const int n = p.n, r = p.r, T = p.T;
+    const int n = p.n_side[side], stride = p.stride_side[side], r = p.r, T = p.T;
+    const bool weighted = side == 1 && p.mass_side[1] != nullptr;    // dGamma2 and dV carry the keys' masses
     const float c1 = kLog2e / p.eps;
     const IO* X = rows_of<IO>(p, side);
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
@@ -528,8 +552,9 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
     for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
         const int tok = min(tile * kTileTokens + i, n - 1);
         Frag<IO, D> xc, vc;
-        load_tokens<D>(xc, X + ((size_t)g * p.stride + tok) * D, kg);
-        load_tokens<D>(vc, vals + ((size_t)g * p.stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * stride + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * stride + tok) * D, kg);
+        const float m = weighted ? token_weight(p, 1, g, tok) : 1.f;
         f32x16 acc[RB], dgam[RB], rho[RB];
         float w;
         int skew = 0;
@@ -547,6 +572,12 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
             Frag<IO, D> yfrag[RB];
             fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
             similarity<D, RB>(dgam, yfrag, vc);
+        }
+        if (weighted) {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) dgam[mb][j] *= m;
         }
         load_pivot_vector<RB>(rho, s_rho + skew, kg);
         // q_i = sum_t Gamma_it dGamma_it with Gamma_it = W_it rho'_t
@@ -567,10 +598,16 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
             for (int j = 0; j < 16; ++j) nacc[mb][j] = fmaf(acc[mb][j], q, nacc[mb][j]);
         if (side == 1) {
             f32x16 o[NB];
+            if (weighted) {
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) acc[mb][j] *= m;
+            }
             contract_pivots<D, RB, kSplit>(o, acc, s_yf[0], s_yf[1], lane);
             IO* out = reinterpret_cast<IO*>(p.dV);
             const int row0 = tile * kTileTokens + 4 * kg;
-            IO* const lane_base = out + ((size_t)g * p.stride + row0) * D;
+            IO* const lane_base = out + ((size_t)g * stride + row0) * D;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
                 if (row0 + 8 * (j >> 2) + (j & 3) < n)
@@ -640,7 +677,7 @@ __global__ void bt_recursion(BtParams p, int R)
     const int pair = blockIdx.x, t = threadIdx.x & 63, q = threadIdx.x >> 6, pairs = 2 * p.G, T = p.T;
     const int h = (pair % p.G) % p.H;
     const bool live = t < p.r;
-    const float a = 1.f / (float)p.n;
+    const float a = 1.f / (float)p.n_side[pair / p.G];
     const float b = live ? p.beta[h * p.r + t] : 1.f;
     float s = 0.f, nn = 0.f;
     if (q == 0)
@@ -703,7 +740,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
     const int pairs = 2 * p.G;
     const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
     const int side = pair / p.G, g = pair % p.G, h = g % p.H;
-    const int n = p.n, r = p.r, T = p.T;
+    const int n = p.n_side[side], stride = p.stride_side[side], r = p.r, T = p.T;
     const float c1 = kLog2e / p.eps;
     const IO* X = rows_of<IO>(p, side);
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
@@ -762,8 +799,12 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
         const int tok = min(tile * kTileTokens + i, n - 1);
         const bool valid = tile * kTileTokens + i < n;
         Frag<IO, D> xc, vc;
-        load_tokens<D>(xc, X + ((size_t)g * p.stride + tok) * D, kg);
-        load_tokens<D>(vc, vals + ((size_t)g * p.stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * stride + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * stride + tok) * D, kg);
+        // mass times n of this lane's token: multiplies the column-sum adjoints dc^k on their way into the
+        // row (dW^k_it = a_i dc^k_t) and, for the keys, the incoming gradient of the coupling
+        const float m = token_weight(p, side, g, tok);
+        const float mdc = side == 0 ? m : 1.f;       // the keys' factor is applied to the whole of dW^T instead
         int skew = 0;
         asm volatile("" : "+v"(skew));
         // similarities scaled to base-2 exponents, once
@@ -790,7 +831,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
         // the potentials, a few binary orders.  The row sums are checked; if one leaves the safe range
         // the rows are re-shifted by this iteration's maxima and the iteration is redone (its sums
         // then lie in [1, 64]).
-        auto add_iteration = [&](const float* pot, const f32x16 (&dp)[RB], bool fold) {
+        // (dp holds dW^k up to the row factor ms: dW^k_it = ms dp_it)
+        auto add_iteration = [&](const float* pot, const f32x16 (&dp)[RB], float ms, bool fold) {
             f32x16 e[RB];
             float ssum, sdot;
             for (;;) {
@@ -829,11 +871,12 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
                 fold = true;
             }
             const float w = valid ? rcp_fast(ssum) : 0.f;
-            const float nwe = -(sdot * w) * w;            // -w e^k_i,  e^k_i = sum_t dP_it W_it
+            const float wm = w * ms;
+            const float nwe = -(sdot * wm) * w;           // -w e^k_i,  e^k_i = sum_t dW_it W_it
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(e[mb][j], fmaf(dp[mb][j], w, nwe), dacc[mb][j]);
+                for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(e[mb][j], fmaf(dp[mb][j], wm, nwe), dacc[mb][j]);
         };
         {
             // last iteration: dP^T = dGamma rho + dc^T with rho_t = beta_t / c^T_t = n rho'_t
@@ -854,14 +897,14 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) dp[mb][j] = fmaf(dp[mb][j] * (float)n, rho[mb][j], dc[mb][j]);
+                    for (int j = 0; j < 16; ++j) dp[mb][j] = fmaf(dp[mb][j] * (float)n, rho[mb][j], dc[mb][j] * mdc);
             }
-            add_iteration(s_hist + ((T - 1) * 2 + 0) * 64, dp, true);
+            add_iteration(s_hist + ((T - 1) * 2 + 0) * 64, dp, side == 0 ? 1.f : m, true);
         }
         for (int k = T - 1; k >= 1; --k) {
             f32x16 dp[RB];
             load_pivot_vector<RB>(dp, s_hist + ((k - 1) * 2 + 1) * 64 + skew, kg);
-            add_iteration(s_hist + ((k - 1) * 2 + 0) * 64, dp, false);
+            add_iteration(s_hist + ((k - 1) * 2 + 0) * 64, dp, m, false);
         }
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
@@ -874,7 +917,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
             contract_pivots<D, RB, kSplit>(o, dacc, s_zf[0], s_zf[1], lane);
             IO* out = reinterpret_cast<IO*>(side == 0 ? p.dQ : p.dK);
             const int row0 = tile * kTileTokens + 4 * kg;
-            IO* const lane_base = out + ((size_t)g * p.stride + row0) * D;
+            IO* const lane_base = out + ((size_t)g * stride + row0) * D;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
                 if (row0 + 8 * (j >> 2) + (j & 3) < n)
@@ -886,7 +929,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
         for (int s = 0; s < 2; ++s) {
             const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
             const int left = max(1, min(8, n - t0));
-            load_values<D>(vh[s], vl[s], X, (size_t)g * p.stride + min(t0, n - 1), left, i);
+            load_values<D>(vh[s], vl[s], X, (size_t)g * stride + min(t0, n - 1), left, i);
         }
         transpose_tile<RB, kSplit>(dacc, tr_hi, tr_lo, i, kg);
         contract_tokens<D, RB, kSplit>(dZacc, tr_hi, tr_lo, vh, vl, i, kg);
@@ -951,6 +994,7 @@ int launch_all(const BwdArgs& a, BtParams p)
     const unsigned grid = (unsigned)pairs * p.chunks;
     // The persistent sweep needs the workgroups of a pair resident together: the whole grid fits the
     // device, or a pair is a single workgroup (which then waits for nobody but itself).
+    // (the capacity is taken from the variant with token masses: the same code plus a few registers)
     bool persistent = p.chunks == 1;
     if (!persistent && p.chunks <= 255) {
         static thread_local int capacity_cache[8] = {0};   // per device ordinal
@@ -959,22 +1003,26 @@ int launch_all(const BwdArgs& a, BtParams p)
         int capacity = (dev >= 0 && dev < 8) ? capacity_cache[dev] : 0;
         if (capacity == 0) {
             int per_cu = 0, cus = 0;
-            LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bt_sweep<IO, D, RB>, kThreads, 0));
+            LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bt_sweep<IO, D, RB, true>, kThreads, 0));
             LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
             capacity = per_cu * cus;
             if (dev >= 0 && dev < 8) capacity_cache[dev] = capacity;
         }
         persistent = (int)grid <= capacity;
     }
+    const bool mass = p.mass_side[0] != nullptr || p.mass_side[1] != nullptr;
     if (persistent) {
-        bt_sweep<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
+        if (mass) bt_sweep<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);
+        else bt_sweep<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
     } else {
         for (int k = 1; k <= T; ++k) {
             p.k = k;
-            bt_forward<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
+            if (mass) bt_forward<IO, D, RB, false, true><<<grid, kThreads, 0, st>>>(p);
+            else bt_forward<IO, D, RB, false, false><<<grid, kThreads, 0, st>>>(p);
         }
-        p.k = T;
-        bt_forward<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);     // the contractions, with g^{T-1}
+        p.k = T;       // the contractions, with g^{T-1}
+        if (mass) bt_forward<IO, D, RB, true, true><<<grid, kThreads, 0, st>>>(p);
+        else bt_forward<IO, D, RB, true, false><<<grid, kThreads, 0, st>>>(p);
     }
     bt_mid<D><<<(unsigned)((p.G * 64 * D + 255) / 256), 256, 0, st>>>(p);
     bt_mid2<D><<<(unsigned)((p.G * 64 + 255) / 256), 256, 0, st>>>(p);
@@ -1053,8 +1101,12 @@ int run_backward_tiled(const BwdArgs& a)
     p.db_pair = (float*)(a.ws + L.db_pair);
     p.db_glue = (float*)(a.ws + L.db_glue);
     p.dz_part = (float*)(a.ws + L.dz_part);
-    p.G = s.B * s.H; p.H = s.H; p.B = s.B; p.n = s.n; p.r = s.r; p.chunks = L.chunks; p.tiles_per_wg = tiles_per_wg_for(s); p.T = a.iters;
-    p.stride = a.n_stride > 0 ? a.n_stride : s.n;
+    p.G = s.B * s.H; p.H = s.H; p.B = s.B; p.r = s.r; p.chunks = L.chunks; p.tiles_per_wg = tiles_per_wg_for(s); p.T = a.iters;
+    // s.n is the longer side (cross attention); a side with fewer tiles leaves its last workgroups idle
+    p.n_side[0] = a.n_q > 0 ? a.n_q : s.n;
+    p.n_side[1] = a.n_k > 0 ? a.n_k : s.n;
+    for (int sd = 0; sd < 2; ++sd) p.stride_side[sd] = a.n_stride > 0 ? a.n_stride : p.n_side[sd];
+    p.mass_side[0] = a.mass_q; p.mass_side[1] = a.mass_k;
     p.eps = a.eps;
     {
         // column sums of a row-normalised kernel are at most n: with 2^(55 - ceil(log2(n + 1))) units per

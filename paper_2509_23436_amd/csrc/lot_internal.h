@@ -140,8 +140,8 @@ struct BwdArgs {
     float* dZ;
     float* dbeta;
     int n_stride;       // tokens between consecutive problems in Q, K, V, dO, dQ, dK, dV; 0 = contiguous
-    int n_q, n_k;       // tokens per problem on the query and on the key side; 0 = s.n (plain path only)
-    const float* mass_q;   // [B,H,n_q] token masses, or null: uniform (plain path only)
+    int n_q, n_k;       // tokens per problem on the query and on the key side; 0 = s.n (else s.n = the longer)
+    const float* mass_q;   // [B,H,n_q] token masses, or null: uniform
     const float* mass_k;   // [B,H,n_k]
     char* ws;
     BwdWorkspace lay;

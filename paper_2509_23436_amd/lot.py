@@ -19,7 +19,7 @@ PATH_AUTO, PATH_REFERENCE, PATH_FUSED = 0, 1, 2
 EXPORTS = ("lot_workspace_bytes", "lot_attention_fwd", "lot_couplings", "lot_attention_fwd_path",
            "lot_couplings_path", "lot_attention_cls_fwd", "lot_attention_cls_fwd_path", "lot_cross_workspace_bytes", "lot_cross_attention_fwd", "lot_cross_attention_fwd_path", "lot_attention_bwd_workspace_bytes", "lot_attention_bwd", "lot_attention_bwd_path",
            "lot_attention_cls_bwd", "lot_attention_cls_bwd_path",
-           "lot_cross_attention_bwd_workspace_bytes", "lot_cross_attention_bwd",
+           "lot_cross_attention_bwd_workspace_bytes", "lot_cross_attention_bwd", "lot_cross_attention_bwd_path",
            "lot_workspace_status", "lot_strerror", "lot_version")
 
 
@@ -257,7 +257,8 @@ def lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=None, mass_k=No
     return out
 
 
-def lot_cross_attention_bwd(Q, K, V, Z, beta, eps, iters, dO, mass_q=None, mass_k=None, workspace=None):
+def lot_cross_attention_bwd(Q, K, V, Z, beta, eps, iters, dO, mass_q=None, mass_k=None, workspace=None,
+                            path=PATH_AUTO):
     """(dQ, dK, dV, dZ, dbeta) of <lot_cross_attention_fwd(...), dO>; the masses are not differentiated."""
     for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
         _require(t, nm, Q.dtype)
@@ -282,10 +283,10 @@ def lot_cross_attention_bwd(Q, K, V, Z, beta, eps, iters, dO, mass_q=None, mass_
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
     dZ, dbeta = torch.empty_like(Z), torch.empty_like(beta)
     null = ctypes.c_void_p(0)
-    _check(lib().lot_cross_attention_bwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
+    _check(lib().lot_cross_attention_bwd_path(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
                                          _ptr(mass_q) if mass_q is not None else null,
                                          _ptr(mass_k) if mass_k is not None else null,
                                          ctypes.c_float(eps), int(iters), _ptr(dO),
                                          _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dZ), _ptr(dbeta),
-                                         _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream()))
+                                         _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(), int(path)))
     return dQ, dK, dV, dZ, dbeta
