@@ -168,7 +168,9 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * shift per row instead of a maximum per iteration, and re-shifts when a row sum leaves
  * [2^-40, 2^40]; the environment variable LOT_RESHIFT_BITS (0..40, read at each call) narrows that
  * range to 2^-bits .. 2^bits so that the rarely taken branch runs on ordinary inputs (0: practically
- * every iteration takes it).  Results agree to rounding for every value.
+ * every iteration takes it).  Results agree to rounding for every value.  LOT_BWD_SWEEP_LAUNCHES=1
+ * makes the FUSED path's forward sweep run as one launch per pass (its form on a device that cannot
+ * hold the whole grid at once) where it would otherwise be one persistent kernel; same results.
  */
 int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out);
 int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,

@@ -46,8 +46,9 @@ namespace {
 constexpr int kTargetWgs = 512;     // two workgroups of four wavefronts on each of 256 CUs
 
 // Tiles per workgroup: enough workgroups to fill the device once (set-up and the cross-wavefront
-// reductions at the end of a workgroup are amortised over more tiles, and fewer partial results go
-// through memory), a multiple of the wavefront count, between one and sixteen tiles per wavefront.
+// reductions at the end of a workgroup are amortised over more tiles, fewer partial results go
+// through memory, and the forward sweep can stay one persistent kernel), a multiple of the wavefront
+// count, between one and 256 tiles per wavefront.
 inline int tiles_per_wg_for(const lot_shape& s)
 {
     const long long ntiles = ((long long)s.n + kTileTokens - 1) / kTileTokens;
@@ -55,7 +56,7 @@ inline int tiles_per_wg_for(const lot_shape& s)
     long long per = (ntiles * pairs + kTargetWgs - 1) / kTargetWgs;
     per = (per + kWaves - 1) / kWaves * kWaves;
     if (per < kWaves) per = kWaves;
-    if (per > 16 * kWaves) per = 16 * kWaves;
+    if (per > 256 * kWaves) per = 256 * kWaves;
     return (int)per;
 }
 
@@ -1010,6 +1011,9 @@ int launch_all(const BwdArgs& a, BtParams p)
         }
         persistent = (int)grid <= capacity;
     }
+    // testing aid: run the sweep as one launch per pass although it would fit (the fallback of devices
+    // that cannot hold the grid), so that this form stays exercised
+    if (const char* e = std::getenv("LOT_BWD_SWEEP_LAUNCHES")) persistent = persistent && std::atoi(e) == 0;
     const bool mass = p.mass_side[0] != nullptr || p.mass_side[1] != nullptr;
     if (persistent) {
         if (mass) bt_sweep<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);

@@ -131,9 +131,10 @@ def test_reshifted_rows_give_the_same_gradients(bits, monkeypatch):
 # the float64 oracle differentiates a sample of the (batch, head) problems one by one.  A problem's
 # dQ, dK, dV depend on that problem alone; dZ and dbeta are sums over the batch, so for them the
 # library is run on the sampled problems only (batch of one per head) and compared in full.
-# The forward sweep of the tiled path has two forms; the shapes below cover both: one persistent
-# kernel (whole grid resident: deit_tiny, swin_t_s1, long_*; or one workgroup per pair on a grid
-# larger than the device: bert_base) and one launch per pass (many_chunks: 128 pairs x 5 chunks).
+# The forward sweep of the tiled path is one persistent kernel when the whole grid is resident
+# (deit_tiny, swin_t_s1, long_*, many_chunks) or a pair is one workgroup (bert_base: a grid larger
+# than the device).  Its other form, one launch per pass, is forced from the host in
+# test_sweep_as_one_launch_per_pass_gives_the_same_bits.
 FULL = {
     "deit_tiny": (W["deit_tiny"], [0, 191]),
     "bert_base": (W["bert_base"], [0, 383]),
@@ -142,6 +143,27 @@ FULL = {
     "long_16k": (W["long_16k"], [9]),
     "many_chunks": (S(W["swin_t_s1"], B=8, H=8, n=10240, iters=4, seed=77), [3, 60]),
 }
+
+
+def test_sweep_as_one_launch_per_pass_gives_the_same_bits(monkeypatch):
+    import torch
+    from paper_2509_23436_amd import lot
+    for w in (FULL["many_chunks"][0], CASES["several_chunks_f32"]):
+        x = synth.make_inputs(w)
+        dO = np.random.default_rng(4).standard_normal(x["V"].shape).astype(np.float32)
+        if w.dtype == "bf16":
+            dO = synth.round_to_bf16(dO)
+        dev = to_device(dict(x, dO=dO), w.dtype)
+        outs = []
+        for launches in ("0", "1"):
+            monkeypatch.setenv("LOT_BWD_SWEEP_LAUNCHES", launches)
+            got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, dev["dO"],
+                                        path=lot.PATH_FUSED)
+            torch.cuda.synchronize()
+            outs.append(got)
+        for a, b in zip(*outs):
+            assert torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
+                               b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
 
 
 @pytest.mark.parametrize("name", list(FULL))
