@@ -226,6 +226,9 @@ int lot_attention_cls_bwd_path(const lot_shape* shape, const void* Q, const void
  * Debug: synchronises the device and reads the status word that the fused kernel leaves in the
  * workspace.  LOT_OK, or LOT_ERR_SYNC if a bounded device-side wait between cooperating
  * workgroups gave up (the output of that call is then undefined).  Not part of the hot path.
+ * Testing aid: the environment variable LOT_SPIN_LIMIT (read at each call) sets the poll budget of
+ * those waits; with 0 every wait gives up at once, the kernels end early (every wavefront still
+ * exits) and this function reports the call; the next call on the same workspace is unaffected.
  */
 int lot_workspace_status(const void* workspace);
 

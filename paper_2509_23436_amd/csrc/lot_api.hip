@@ -25,6 +25,15 @@ unsigned long long next_nonce()
     return v ? v : counter.fetch_add(1) + 1;
 }
 
+uint32_t spin_limit()
+{
+    if (const char* e = std::getenv("LOT_SPIN_LIMIT")) {
+        const long long v = std::atoll(e);
+        if (v >= 0 && v <= (1ll << 30)) return (uint32_t)v;
+    }
+    return 1u << 21;
+}
+
 float reshift_limit()
 {
     int bits = 40;

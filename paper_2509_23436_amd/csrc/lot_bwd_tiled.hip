@@ -1089,7 +1089,7 @@ int run_backward_tiled(const BwdArgs& a)
     p.dQ = a.dQ; p.dK = a.dK; p.dV = a.dV; p.dZ = a.dZ; p.dbeta = a.dbeta;
     p.status = (unsigned long long*)a.ws;
     p.nonce = next_nonce();
-    p.spin_limit = 1u << 21;
+    p.spin_limit = spin_limit();
     p.sum_hi = reshift_limit();
     p.sum_lo = 1.0f / p.sum_hi;
     p.colacc = (unsigned long long*)(a.ws + L.colacc);

@@ -787,7 +787,7 @@ int launch(const Args& a, bool want_out)
     p.cluster = cluster; p.cluster_cap = fused_cluster_bound(s);
     p.num_items = G * cluster; p.iters = a.iters; p.mode = want_out ? MODE_ATTENTION : MODE_COUPLINGS;
     p.eps = a.eps;
-    p.spin_limit = 1u << 21;
+    p.spin_limit = spin_limit();
     // only where the last 8 MiB of the workspace lie wholly inside the reference path's regions
     p.trace = a.lay.total >= a.lay.C + (8u << 20) ? (unsigned long long*)(a.ws + a.lay.total - (8u << 20)) : nullptr;
 

@@ -219,6 +219,11 @@ unsigned long long next_nonce();
 // the re-shifting branch run on ordinary inputs (0: practically every iteration takes it).
 float reshift_limit();
 
+// Poll budget of a bounded wait between cooperating workgroups (2^21 polls by default: seconds).  The
+// environment variable LOT_SPIN_LIMIT (read at each call) replaces it: a testing aid -- with 0 every
+// wait gives up at once, the kernels end early and the call is reported by lot_workspace_status.
+uint32_t spin_limit();
+
 #define LOT_HIP_CHECK(expr)                                   \
     do {                                                      \
         hipError_t e_ = (expr);                               \

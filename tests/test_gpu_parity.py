@@ -246,3 +246,49 @@ def test_large_pivot_sizes_match_oracle_on_the_grouped_kernels(name):
     torch.cuda.synchronize()
     assert torch.equal(again.view(torch.int16 if w.dtype == "bf16" else torch.int32),
                        outs["fused"].view(torch.int16 if w.dtype == "bf16" else torch.int32))
+
+
+def test_waits_that_give_up_are_reported_and_the_next_call_recovers(monkeypatch):
+    """With the poll budget of the waits between workgroups set to zero from the host, every wait gives
+    up at once: the kernels must still end, the call must be reported, and an ordinary call on the same
+    workspace afterwards must be correct.  Forward (several workgroups per problem) and backward."""
+    import torch
+    from oracle import lot_oracle_bwd
+    from paper_2509_23436_amd import lot
+    name = "long_4k_h2"
+    w = CASES[name]
+    x, O_ref, _, _ = _oracle_case(name)
+    dev = to_device(x, w.dtype)
+    shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
+    ws = lot.alloc_workspace(shape, w.iters)
+    monkeypatch.setenv("LOT_SPIN_LIMIT", "0")
+    lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, workspace=ws,
+                          path=lot.PATH_FUSED)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(ws) == -10
+    monkeypatch.delenv("LOT_SPIN_LIMIT")
+    out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, workspace=ws,
+                                path=lot.PATH_FUSED)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(ws) == 0
+    assert rel_max_err(to_host_f64(out), O_ref) <= 2e-2
+
+    wb = S(W["long_4k"], B=1, H=2, n=3000, iters=3, seed=37)
+    xb = synth.make_inputs(wb)
+    dO = synth.round_to_bf16(np.random.default_rng(5).standard_normal(xb["V"].shape).astype(np.float32))
+    refs, _ = lot_oracle_bwd.attention_bwd(xb["Q"], xb["K"], xb["V"], xb["Z"], xb["beta"], wb.eps, wb.iters, dO)
+    devb = to_device(dict(xb, dO=dO), wb.dtype)
+    shape_b = lot._shape_of(devb["Q"], devb["V"], devb["Z"])
+    wsb = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape_b, wb.iters), dtype=torch.uint8, device="cuda")
+    monkeypatch.setenv("LOT_SPIN_LIMIT", "0")
+    lot.lot_attention_bwd(devb["Q"], devb["K"], devb["V"], devb["Z"], devb["beta"], wb.eps, wb.iters, devb["dO"],
+                          workspace=wsb, path=lot.PATH_FUSED)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(wsb) == -10
+    monkeypatch.delenv("LOT_SPIN_LIMIT")
+    got = lot.lot_attention_bwd(devb["Q"], devb["K"], devb["V"], devb["Z"], devb["beta"], wb.eps, wb.iters, devb["dO"],
+                                workspace=wsb, path=lot.PATH_FUSED)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(wsb) == 0
+    for g, ref in zip(got, refs):
+        assert rel_max_err(to_host_f64(g), ref) <= 2e-2
