@@ -1,0 +1,53 @@
+"""The torch.autograd glue (paper_2509_23436_amd.autograd) on the GPU: gradients that arrive through
+loss.backward(), with ordinary torch operations before and after the library call, against the
+float64 backward oracle driven through the same chain."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2509_23436_amd import synth
+from util import rel_max_err
+
+pytestmark = pytest.mark.gpu
+W = synth.WORKLOADS
+
+
+@pytest.mark.parametrize("cls", [False, True])
+def test_gradients_through_loss_backward_match_the_oracle(cls):
+    import torch
+    from oracle import lot_oracle_bwd
+    from paper_2509_23436_amd import autograd
+    w = dataclasses.replace(W["tiny"], B=2, H=3, n=150, d=32, r=8, iters=5, seed=90)
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(91)
+    logits = rng.standard_normal(x["beta"].shape).astype(np.float32)      # beta = softmax(logits): a learnable mass
+    mix = (rng.standard_normal((w.d, w.d)) / np.sqrt(w.d)).astype(np.float32)   # an output projection after the attention
+
+    # float64 chain on the CPU: the oracle's forward inside ordinary torch operations
+    t = {k: torch.tensor(np.asarray(v, dtype=np.float64), requires_grad=True) for k, v in
+         dict(Q=x["Q"], K=x["K"], V=x["V"], Z=x["Z"], logits=logits).items()}
+    beta64 = torch.softmax(t["logits"], dim=-1)
+    if cls:
+        bc = torch.full((w.B, w.H), 0.8, dtype=torch.float64)
+        O64 = lot_oracle_bwd.forward_cls(t["Q"], t["K"], t["V"], t["Z"], beta64, w.eps, w.iters, bc)
+    else:
+        O64 = lot_oracle_bwd.forward(t["Q"], t["K"], t["V"], t["Z"], beta64, w.eps, w.iters)
+    loss64 = ((O64 @ torch.tensor(mix, dtype=torch.float64)) ** 2).sum()
+    ref = torch.autograd.grad(loss64, list(t.values()))
+
+    d = {k: torch.tensor(np.asarray(v, dtype=np.float32), device="cuda", requires_grad=True) for k, v in
+         dict(Q=x["Q"], K=x["K"], V=x["V"], Z=x["Z"], logits=logits).items()}
+    beta = torch.softmax(d["logits"], dim=-1)
+    if cls:
+        O = autograd.lot_attention_cls(d["Q"], d["K"], d["V"], d["Z"], beta, w.eps, w.iters, 0.8)
+    else:
+        O = autograd.lot_attention(d["Q"], d["K"], d["V"], d["Z"], beta, w.eps, w.iters)
+    loss = ((O @ torch.tensor(mix, device="cuda")) ** 2).sum()
+    loss.backward()
+    torch.cuda.synchronize()
+    assert abs(float(loss.detach()) - float(loss64.detach())) <= 1e-4 * abs(float(loss64.detach()))
+    for (name, leaf), r64 in zip(d.items(), ref):
+        err = rel_max_err(leaf.grad.double().cpu().numpy(), r64.numpy())
+        print("  d%-6s max-norm rel err %.3e" % (name, err), flush=True)
+        assert err <= 1e-4, name
