@@ -25,11 +25,12 @@ CASES = {
     "bf16_d32": S(W["swin_t_s1"], B=2, H=3, n=400, seed=83),
     "reference_only": S(W["tiny"], B=1, H=2, n=90, d=16, r=80, iters=4, seed=84),
     "several_softmax_chunks": S(W["tiny"], B=1, H=2, n=5000, d=32, r=8, iters=4, seed=85),
+    "grouped_r128_bf16": S(W["long_4k"], B=1, H=2, n=700, r=128, iters=4, seed=87),   # 64 < r <= 256: grouped kernels
 }
 
 
 def _paths(w):
-    fused = w.d in (32, 64) and w.r <= 64
+    fused = w.d in (32, 64) and w.r <= 256
     return ["reference", "fused"] if fused else ["reference"]
 
 
