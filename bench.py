@@ -76,7 +76,7 @@ def runtime_grid(torch, lot, synth, to_device):
                                       workspace=ws)
 
             def timed(fn, reps):
-                for _ in range(3):
+                for _ in range(min(3, reps)):
                     fn()
                 torch.cuda.synchronize()
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -88,12 +88,14 @@ def runtime_grid(torch, lot, synth, to_device):
                 return a.elapsed_time(b) / reps
 
             row = {"n": n, "r": r, "T": 5, "path": "fused" if r <= 64 else "grouped", "fwd_ms": timed(fwd, 50)}
-            if r <= 64:
-                dO = torch.randn_like(dev["V"])
-                wsb = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape, w.iters), dtype=torch.uint8, device="cuda")
-                row["bwd_ms"] = timed(lambda: lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"],
-                                                                    w.eps, w.iters, dO, workspace=wsb), 20)
-                del wsb, dO
+            # backward: the tiled kernels for r <= 64; beyond that the plain kernels (one per step, n x r
+            # intermediates in the workspace): slow, timed with few repetitions
+            dO = torch.randn_like(dev["V"])
+            wsb = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape, w.iters), dtype=torch.uint8, device="cuda")
+            row["bwd_path"] = "tiled" if r <= 64 else "plain"
+            row["bwd_ms"] = timed(lambda: lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"],
+                                                                w.eps, w.iters, dO, workspace=wsb), 20 if r <= 64 else 2)
+            del wsb, dO
             rows.append(row)
             del dev, ws, out
     return rows
@@ -112,7 +114,7 @@ def main() -> int:
                     help="timed calls of the backward pass (reported beside the headline; 0 skips it)")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "reference"])
     ap.add_argument("--runtime-grid", action="store_true",
-                    help="instead of the benchmark, time the forward (and backward where the tiled path applies) "
+                    help="instead of the benchmark, time the forward and the backward "
                          "over the paper's runtime grid: n = 2^10..2^17, r in {32, 64, 128, 256}, T = 5; one JSON line")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB ten times "
