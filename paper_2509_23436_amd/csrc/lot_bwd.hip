@@ -30,7 +30,8 @@
 namespace lot {
 namespace {
 
-constexpr int kChunk = kRefChunk;   // tokens per partial sum
+constexpr int kChunk = kRefChunk;   // tokens per partial column sum
+constexpr int kTxChunk = 256;       // tokens per partial r x d contraction (its partial results are r x d each)
 
 // Weight of token i of problem p: its mass, or `uniform` where the masses are implicit.
 __device__ inline float row_weight(const float* mass, float uniform, size_t row)
@@ -52,21 +53,37 @@ __global__ void bwd_unit_couplings(const float* __restrict__ C, const float* __r
 
 // part[p][chunk][t][c] = sum over the chunk's tokens i of w_i A[p][i][t] * X[p][i][c]
 // (A is fp32 [P][n][r]; X is [P][stride][dx] in the I/O type, n rows used; w = row_weight).
-// One block per (p, chunk, t).
+// One block of 256 threads per (p, chunk, tile of kTxPivots pivots): thread = (pivot of the tile,
+// column class); a thread walks the chunk's tokens for its pivot and every kTxCols-th column, so that
+// a wavefront reads whole stretches of a row of A and of a row of X.
+constexpr int kTxPivots = 16, kTxCols = 16;
 template <typename T>
 __global__ void bwd_tx_partial(const float* __restrict__ A, const T* __restrict__ X, float* __restrict__ part,
                                const float* __restrict__ mass, float uniform,
                                int n, int stride, int r, int dx, int chunks)
 {
-    const int t = blockIdx.x % r;
-    const int chunk = (blockIdx.x / r) % chunks;
-    const size_t p = blockIdx.x / ((size_t)r * chunks);
-    const int i0 = chunk * kChunk, i1 = min(n, i0 + kChunk);
-    for (int c = threadIdx.x; c < dx; c += blockDim.x) {
-        float acc = 0.f;
-        for (int i = i0; i < i1; ++i)
-            acc = fmaf(row_weight(mass, uniform, p * n + i) * A[(p * n + i) * r + t], ld(X, (p * stride + i) * dx + c), acc);
-        part[((p * chunks + chunk) * r + t) * dx + c] = acc;
+    const int ttiles = (r + kTxPivots - 1) / kTxPivots;
+    const int tt = blockIdx.x % ttiles;
+    const int chunk = (blockIdx.x / ttiles) % chunks;
+    const size_t p = blockIdx.x / ((size_t)ttiles * chunks);
+    const int t = tt * kTxPivots + threadIdx.x / kTxCols, cc = threadIdx.x % kTxCols;
+    if (t >= r) return;
+    const int i0 = chunk * kTxChunk, i1 = min(n, i0 + kTxChunk);
+    for (int c0 = 0; c0 < dx; c0 += 4 * kTxCols) {          // four columns of a thread at a time
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int i = i0; i < i1; ++i) {
+            const float a = row_weight(mass, uniform, p * n + i) * A[(p * n + i) * r + t];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = c0 + q * kTxCols + cc;
+                if (c < dx) acc[q] = fmaf(a, ld(X, (p * stride + i) * dx + c), acc[q]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = c0 + q * kTxCols + cc;
+            if (c < dx) part[((p * chunks + chunk) * r + t) * dx + c] = acc[q];
+        }
     }
 }
 // out[p][t][c] = scale * sum over chunks (index order)
@@ -100,20 +117,33 @@ __global__ void bwd_glue_pivots(float* __restrict__ Yp, float* __restrict__ dYp,
     }
 }
 
-// out[p][i][t] = w_i * sum_c X[p][i][c] * M[p][t][c]        (dGhat1 = dO Y'^T, dGhat2 = a2 V dYraw^T)
+// Mt[p][c][t] = M[p][t][c]: the r x dx matrices that meet token rows are transposed once, so that the
+// threads of a wavefront (consecutive pivots t) read consecutive addresses.
+__global__ void bwd_transpose(const float* __restrict__ M, float* __restrict__ Mt, size_t total, int r, int dx)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // (p, c, t)
+    if (idx >= total) return;
+    const size_t p = idx / ((size_t)r * dx);
+    const int c = (int)(idx / r % dx), t = (int)(idx % r);
+    Mt[idx] = M[(p * r + t) * dx + c];
+}
+
+// out[p][i][t] = w_i * sum_c X[p][i][c] * Mt[m(p)][c][t]: the similarities C = X Z^T (Mt = Z^T per head,
+// w = 1), dGhat1 = dO Y'^T and dGhat2 = a2 V dYraw^T (Mt per problem).
 template <typename T>
-__global__ void bwd_outer(const T* __restrict__ X, const float* __restrict__ M, float* __restrict__ out,
+__global__ void bwd_outer(const T* __restrict__ X, const float* __restrict__ Mt, float* __restrict__ out,
                           const float* __restrict__ mass, float uniform,
-                          size_t total, int n, int stride, int r, int dx)
+                          size_t total, int n, int stride, int r, int dx, int per_head, int H)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // (p, i, t)
     if (idx >= total) return;
     const size_t pi = idx / r;
     const int t = (int)(idx % r);
     const size_t p = pi / n;
+    const size_t m = per_head ? (p % H) : p;
     float acc = 0.f;
     const size_t row = p * stride + pi % n;          // X is [P][stride][dx]
-    for (int c = 0; c < dx; ++c) acc = fmaf(ld(X, row * dx + c), M[(p * r + t) * dx + c], acc);
+    for (int c = 0; c < dx; ++c) acc = fmaf(ld(X, row * dx + c), Mt[(m * dx + c) * r + t], acc);
     out[idx] = row_weight(mass, uniform, pi) * acc;
 }
 
@@ -175,16 +205,19 @@ __global__ void bwd_pivot_pre(const float* __restrict__ part, const float* __res
     }
 }
 
-// Token side of one reverse step, one thread per (problem, i):
+// Token side of one reverse step, a group of lanes per (problem, i):
 //   W_it = softmax_t((C_it + gprev_t)/eps);  dW_it = [last] dGhat_it rho_t + a_i dc_t;
 //   e_i = sum_t dW_it W_it;  dY_it = W_it (dW_it - e_i);  dC_it (+)= dY_it/eps;  Ybuf = dY.
 __global__ void bwd_rows(const float* __restrict__ C, const float* __restrict__ g_prev,
                          const float* __restrict__ dGhat, const float* __restrict__ rho,
                          const float* __restrict__ dc, float* __restrict__ dC, float* __restrict__ Ybuf,
-                         const float* __restrict__ mass, size_t rows, int n, int r, float eps, int last)
+                         const float* __restrict__ mass, size_t rows, int n, int r, float eps, int last, int width)
 {
-    const size_t row = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= rows) return;
+    // `width` lanes per row (see row_group_width)
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = tid / width < rows;
+    const size_t row = min(tid / width, rows - 1);
+    const int sub = (int)(tid % width);
     const size_t pair = row / n;
     const float* c = C + row * r;
     const float* gp = g_prev + pair * r;
@@ -192,17 +225,20 @@ __global__ void bwd_rows(const float* __restrict__ C, const float* __restrict__ 
     const float* rh = rho + pair * r;
     const float a = row_weight(mass, 1.f / (float)n, row);
     float m = -INFINITY;
-    for (int t = 0; t < r; ++t) m = fmaxf(m, (c[t] + gp[t]) / eps);
+    for (int t = sub; t < r; t += width) m = fmaxf(m, (c[t] + gp[t]) / eps);
+    m = group_max(m, width);
     float s = 0.f;
-    for (int t = 0; t < r; ++t) s += expf((c[t] + gp[t]) / eps - m);
-    const float inv_s = 1.f / s;
+    for (int t = sub; t < r; t += width) s += expf((c[t] + gp[t]) / eps - m);
+    const float inv_s = 1.f / group_sum(s, width);
     float e = 0.f;
-    for (int t = 0; t < r; ++t) {
+    for (int t = sub; t < r; t += width) {
         const float w = expf((c[t] + gp[t]) / eps - m) * inv_s;
         const float dW = (last ? dGhat[row * r + t] * rh[t] : 0.f) + a * dcp[t];
         e = fmaf(dW, w, e);
     }
-    for (int t = 0; t < r; ++t) {
+    e = group_sum(e, width);
+    if (!live) return;
+    for (int t = sub; t < r; t += width) {
         const float w = expf((c[t] + gp[t]) / eps - m) * inv_s;
         const float dW = (last ? dGhat[row * r + t] * rh[t] : 0.f) + a * dcp[t];
         const float dY = w * (dW - e);
@@ -269,6 +305,7 @@ int run_backward_t(const BwdArgs& a)
     const float* masses[2] = {a.mass_q, a.mass_k};
     const float unis[2] = {1.f / (float)ns[0], 1.f / (float)ns[1]};
     const int chunkss[2] = {(ns[0] + kChunk - 1) / kChunk, (ns[1] + kChunk - 1) / kChunk};
+    const int txchunks[2] = {(ns[0] + kTxChunk - 1) / kTxChunk, (ns[1] + kTxChunk - 1) / kTxChunk};
     const void* Xs[2] = {a.Q, a.K};
     void* dXs[2] = {a.dQ, a.dK};
     const BwdWorkspace& L = a.lay;
@@ -299,21 +336,27 @@ int run_backward_t(const BwdArgs& a)
     float* db_pair = (float*)(a.ws + L.db_pair);
     float* dZ_pair = (float*)(a.ws + L.dZ_pair);   // [2][G][r][d_k]
     float* Zr = (float*)(a.ws + L.Zr);
+    float* Zt = (float*)(a.ws + L.Zt);             // [H][d_k][r]: Z as the forward pass used it, transposed
+    float* Yt = (float*)(a.ws + L.Yt);             // [G][d_v][r]: Y' or dYraw, transposed
     hipStream_t st_ = a.stream;
     ref_mark<<<1, 1, 0, st_>>>((unsigned long long*)a.ws, next_nonce());   // no device-side waits on this path
     const size_t slab = (size_t)G * r;                                     // one side's pivot vector
     const unsigned pr_blocks = blocks_for(slab, 256);
     auto pot = [&](int k, int side) { return ghist + ((size_t)k * 2 + side) * slab; };
+    const int width = row_group_width(r);
+    const int ttiles = (r + kTxPivots - 1) / kTxPivots;
 
     // ---- forward, keeping the pivot potentials of every iteration and the last row normalisers
+    bwd_round_z<<<blocks_for((size_t)s.H * r * s.d_k, 256), 256, 0, st_>>>(a.Z, Zr, s.H * r * s.d_k, s.io_dtype == LOT_BF16);
+    bwd_transpose<<<blocks_for((size_t)s.H * r * s.d_k, 256), 256, 0, st_>>>(Zr, Zt, (size_t)s.H * r * s.d_k, r, s.d_k);
     for (int sd = 0; sd < 2; ++sd) {
         const int n = ns[sd], chunks = chunkss[sd];
         const size_t total = (size_t)G * n * r, rows = (size_t)G * n;
-        xr_cost<T><<<blocks_for(total, 256), 256, 0, st_>>>((const T*)Xs[sd], a.Z, Cs[sd], total, s.H, n, strides[sd],
-                                                            s.d_k, r, s.io_dtype == LOT_BF16);
+        bwd_outer<T><<<blocks_for(total, 256), 256, 0, st_>>>((const T*)Xs[sd], Zt, Cs[sd], nullptr, 1.f, total, n, strides[sd], r,
+                                                              s.d_k, 1, s.H);
         ref_zero<<<pr_blocks, 256, 0, st_>>>(pot(0, sd), slab);
         for (int k = 1; k <= T_; ++k) {
-            xr_row_lse<<<blocks_for(rows, 256), 256, 0, st_>>>(Cs[sd], pot(k - 1, sd), lses[sd], rows, n, r, a.eps);
+            xr_row_lse<<<blocks_for(rows * width, 256), 256, 0, st_>>>(Cs[sd], pot(k - 1, sd), lses[sd], rows, n, r, a.eps, width);
             xr_col_partial<<<(unsigned)G * chunks, 64, 0, st_>>>(Cs[sd], lses[sd], masses[sd], pm, ps, n, r, chunks, a.eps);
             xr_col_final<<<pr_blocks, 256, 0, st_>>>(pm, ps, a.beta, pot(k, sd), G, s.H, r, chunks, a.eps);
         }
@@ -323,27 +366,28 @@ int run_backward_t(const BwdArgs& a)
     // ---- glue
     const size_t yelems = (size_t)G * r * s.d_v;
     // Y'_t = (1/beta_t) sum_j a2_j Ghat2_jt V_j
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunkss[1] * r), 64, 0, st_>>>(ghats[1], (const T*)a.V, tx_part, masses[1], unis[1],
-                                                                              ns[1], strides[1], r, s.d_v, chunkss[1]);
-    bwd_tx_final<<<blocks_for(yelems, 256), 256, 0, st_>>>(tx_part, Yp, yelems, r, s.d_v, chunkss[1], 1.f);
+    bwd_tx_partial<T><<<(unsigned)((size_t)G * txchunks[1] * ttiles), kTxPivots * kTxCols, 0, st_>>>(ghats[1], (const T*)a.V, tx_part, masses[1], unis[1],
+                                                                               ns[1], strides[1], r, s.d_v, txchunks[1]);
+    bwd_tx_final<<<blocks_for(yelems, 256), 256, 0, st_>>>(tx_part, Yp, yelems, r, s.d_v, txchunks[1], 1.f);
     bwd_glue_pivots<<<blocks_for((size_t)G * r, 128), 128, 0, st_>>>(Yp, dYp, a.beta, db_glue, G * r, s.H, r, s.d_v, 0);
     // dY' = Ghat1^T dO
-    bwd_tx_partial<T><<<(unsigned)((size_t)G * chunkss[0] * r), 64, 0, st_>>>(ghats[0], (const T*)a.dO, tx_part, nullptr, 1.f,
-                                                                              ns[0], strides[0], r, s.d_v, chunkss[0]);
-    bwd_tx_final<<<blocks_for(yelems, 256), 256, 0, st_>>>(tx_part, dYp, yelems, r, s.d_v, chunkss[0], 1.f);
+    bwd_tx_partial<T><<<(unsigned)((size_t)G * txchunks[0] * ttiles), kTxPivots * kTxCols, 0, st_>>>(ghats[0], (const T*)a.dO, tx_part, nullptr, 1.f,
+                                                                               ns[0], strides[0], r, s.d_v, txchunks[0]);
+    bwd_tx_final<<<blocks_for(yelems, 256), 256, 0, st_>>>(tx_part, dYp, yelems, r, s.d_v, txchunks[0], 1.f);
     // dGhat1 = dO Y'^T (does not use dY')
-    bwd_outer<T><<<blocks_for((size_t)G * ns[0] * r, 256), 256, 0, st_>>>((const T*)a.dO, Yp, dghats[0], nullptr, 1.f,
-                                                                          (size_t)G * ns[0] * r, ns[0], strides[0], r, s.d_v);
+    bwd_transpose<<<blocks_for(yelems, 256), 256, 0, st_>>>(Yp, Yt, yelems, r, s.d_v);
+    bwd_outer<T><<<blocks_for((size_t)G * ns[0] * r, 256), 256, 0, st_>>>((const T*)a.dO, Yt, dghats[0], nullptr, 1.f,
+                                                                          (size_t)G * ns[0] * r, ns[0], strides[0], r, s.d_v, 0, s.H);
     // db_glue, dYraw = dY'/beta
     bwd_glue_pivots<<<blocks_for((size_t)G * r, 128), 128, 0, st_>>>(Yp, dYp, a.beta, db_glue, G * r, s.H, r, s.d_v, 1);
     // dV_j = a2_j sum_t Ghat2_jt dYraw_t ; dGhat2_jt = a2_j <V_j, dYraw_t>
     bwd_apply<T><<<blocks_for((size_t)G * ns[1] * s.d_v, 256), 256, 0, st_>>>(ghats[1], dYp, (T*)a.dV, masses[1], unis[1],
                                                                               (size_t)G * ns[1] * s.d_v, ns[1], strides[1], r, s.d_v, 0, s.H);
-    bwd_outer<T><<<blocks_for((size_t)G * ns[1] * r, 256), 256, 0, st_>>>((const T*)a.V, dYp, dghats[1], masses[1], unis[1],
-                                                                          (size_t)G * ns[1] * r, ns[1], strides[1], r, s.d_v);
+    bwd_transpose<<<blocks_for(yelems, 256), 256, 0, st_>>>(dYp, Yt, yelems, r, s.d_v);
+    bwd_outer<T><<<blocks_for((size_t)G * ns[1] * r, 256), 256, 0, st_>>>((const T*)a.V, Yt, dghats[1], masses[1], unis[1],
+                                                                          (size_t)G * ns[1] * r, ns[1], strides[1], r, s.d_v, 0, s.H);
 
     // ---- both Sinkhorn solves, reverse sweep
-    bwd_round_z<<<blocks_for((size_t)s.H * r * s.d_k, 256), 256, 0, st_>>>(a.Z, Zr, s.H * r * s.d_k, s.io_dtype == LOT_BF16);
     for (int sd = 0; sd < 2; ++sd) {
         const int n = ns[sd], chunks = chunkss[sd];
         const size_t rows = (size_t)G * n;
@@ -354,18 +398,18 @@ int run_backward_t(const BwdArgs& a)
             const int last = k == T_;
             bwd_pivot_pre<<<pr_blocks, 256, 0, st_>>>(colpart, pot(k - 1, sd), pot(k, sd), a.beta, dg_s, dc_s, rho_s, db_s, G, G, s.H, r,
                                                       chunks, a.eps, last);
-            bwd_rows<<<blocks_for(rows, 256), 256, 0, st_>>>(Cs[sd], pot(k - 1, sd), dghats[sd], rho_s, dc_s, dCs[sd], ybufs[sd],
-                                                             masses[sd], rows, n, r, a.eps, last);
+            bwd_rows<<<blocks_for(rows * width, 256), 256, 0, st_>>>(Cs[sd], pot(k - 1, sd), dghats[sd], rho_s, dc_s, dCs[sd],
+                                                                     ybufs[sd], masses[sd], rows, n, r, a.eps, last, width);
             bwd_col_partial<<<(unsigned)G * chunks, 64, 0, st_>>>(ybufs[sd], nullptr, colpart, n, r, chunks);
             bwd_pivot_post<<<pr_blocks, 256, 0, st_>>>(colpart, dg_s, G, r, chunks, a.eps, last);
         }
         // similarities: dX = dC Z, dZ share = dC^T X
         bwd_apply<T><<<blocks_for(rows * s.d_k, 256), 256, 0, st_>>>(dCs[sd], Zr, (T*)dXs[sd], nullptr, 1.f, rows * s.d_k, n, strides[sd],
                                                                      r, s.d_k, 1, s.H);
-        bwd_tx_partial<T><<<(unsigned)((size_t)G * chunks * r), 64, 0, st_>>>(dCs[sd], (const T*)Xs[sd], tx_part, nullptr, 1.f, n,
-                                                                              strides[sd], r, s.d_k, chunks);
+        bwd_tx_partial<T><<<(unsigned)((size_t)G * txchunks[sd] * ttiles), kTxPivots * kTxCols, 0, st_>>>(dCs[sd], (const T*)Xs[sd], tx_part, nullptr, 1.f, n,
+                                                                                    strides[sd], r, s.d_k, txchunks[sd]);
         bwd_tx_final<<<blocks_for((size_t)G * r * s.d_k, 256), 256, 0, st_>>>(tx_part, dZ_pair + (size_t)sd * G * r * s.d_k,
-                                                                              (size_t)G * r * s.d_k, r, s.d_k, chunks, 1.f);
+                                                                              (size_t)G * r * s.d_k, r, s.d_k, txchunks[sd], 1.f);
     }
     bwd_head_sums<<<blocks_for((size_t)s.H * r * (s.d_k + 1), 256), 256, 0, st_>>>(dZ_pair, db_pair, db_glue, a.dZ, a.dbeta, s.B, s.H, r, s.d_k);
     (void)pairs;
@@ -383,6 +427,7 @@ BwdWorkspace carve_bwd_sides(int B, int H, int n_q, int n_k, int r, int d_k, int
     const size_t G = (size_t)B * H, rows = G * ((size_t)n_q + n_k), pairs = 2 * G;
     const size_t nmax = n_q > n_k ? n_q : n_k;
     const size_t chunks = (nmax + kRefChunk - 1) / kRefChunk;
+    const size_t txchunks = (nmax + kTxChunk - 1) / kTxChunk;
     const size_t dmax = d_k > d_v ? d_k : d_v;
     w.C = take(rows * r * 4);
     w.f = take(rows * 4);
@@ -393,7 +438,7 @@ BwdWorkspace carve_bwd_sides(int B, int H, int n_q, int n_k, int r, int d_k, int
     w.dgam = take(rows * r * 4);
     w.dC = take(rows * r * 4);
     w.ybuf = take(rows * r * 4);
-    w.tx_part = take(G * chunks * r * dmax * 4);
+    w.tx_part = take(G * txchunks * r * dmax * 4);
     w.Yp = take(G * r * d_v * 4);
     w.dYp = take(G * r * d_v * 4);
     w.db_glue = take(G * r * 4);
@@ -404,6 +449,8 @@ BwdWorkspace carve_bwd_sides(int B, int H, int n_q, int n_k, int r, int d_k, int
     w.db_pair = take(pairs * r * 4);
     w.dZ_pair = take(pairs * r * d_k * 4);
     w.Zr = take((size_t)H * r * d_k * 4);
+    w.Zt = take((size_t)H * r * d_k * 4);
+    w.Yt = take(G * r * d_v * 4);
     w.total = off;
     return w;
 }

@@ -70,6 +70,7 @@ int run_cross_reference_t(const CrossArgs& a)
     const float* masses[2] = {a.mass_q, a.mass_k};
     const int ns[2] = {a.n_q, a.n_k};
     ref_mark<<<1, 1, 0, st_>>>((unsigned long long*)a.ws, next_nonce());
+    const int width = row_group_width(r);
     for (int s = 0; s < 2; ++s) {
         const int n = ns[s], chunks = (n + kRefChunk - 1) / kRefChunk;
         const size_t total = (size_t)G * n * r, rows = (size_t)G * n;
@@ -77,7 +78,7 @@ int run_cross_reference_t(const CrossArgs& a)
                                                             a.io_dtype == LOT_BF16);
         ref_zero<<<blocks_for((size_t)G * r, 256), 256, 0, st_>>>(gs[s], (size_t)G * r);
         for (int it = 0; it < a.iters; ++it) {
-            xr_row_lse<<<blocks_for(rows, 256), 256, 0, st_>>>(Cs[s], gs[s], lses[s], rows, n, r, a.eps);
+            xr_row_lse<<<blocks_for(rows * width, 256), 256, 0, st_>>>(Cs[s], gs[s], lses[s], rows, n, r, a.eps, width);
             xr_col_partial<<<(unsigned)G * chunks, 64, 0, st_>>>(Cs[s], lses[s], masses[s], pm, ps, n, r, chunks, a.eps);
             xr_col_final<<<blocks_for((size_t)G * r, 256), 256, 0, st_>>>(pm, ps, a.beta, gs[s], G, a.H, r, chunks, a.eps);
         }

@@ -13,7 +13,7 @@ constexpr int kTileTokens = 32;        // tokens per MFMA tile of the fused kern
 constexpr int kFusedWaves = 4;         // fewest wavefronts per workgroup of the fused kernel
 constexpr int kMaxCluster = 64;        // most workgroups that share one problem
 constexpr int kMaxResidentWgs = 2048;  // upper bound on co-resident workgroups (256 CUs x 8)
-constexpr int kRefChunk = 1024;        // tokens per workgroup in the reference column reduction
+constexpr int kRefChunk = 128;         // tokens per workgroup in the plain kernels' column reductions
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -119,6 +119,7 @@ struct BwdWorkspace {
     size_t Yp, dYp, db_glue;              // float [G][r][d_v] x 2, float [G][r]
     size_t colpart, dc, rho, dg, db_pair; // float [G][chunks][r], float [2][G][r] x 4
     size_t dZ_pair, Zr;                   // float [2][G][r][d_k], float [H][r][d_k]
+    size_t Zt, Yt;                        // transposed copies: float [H][d_k][r], float [G][d_v][r]
     size_t total;
 };
 BwdWorkspace carve_bwd(const lot_shape& s, int iters);

@@ -125,19 +125,42 @@ __global__ void xr_cost(const T* __restrict__ X, const float* __restrict__ Z, fl
     C[idx] = acc;
 }
 
-// lse_i = LSE_t((C_it + g_t)/eps), one thread per (g, i)
-__global__ void xr_row_lse(const float* __restrict__ C, const float* __restrict__ gpot, float* __restrict__ lse,
-                           size_t rows, int n, int r, float eps)
+// Rows of the n x r arrays are walked by a group of `width` adjacent lanes (a power of two, at most 64:
+// the smallest that covers min(r, 64)), so that a wavefront reads whole rows at a time; sums and maxima
+// over a row are butterfly reductions over the group (a fixed order).
+inline int row_group_width(int r)
 {
-    const size_t row = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= rows) return;
+    int w = 1;
+    while (w < r && w < 64) w <<= 1;
+    return w;
+}
+__device__ inline float group_max(float v, int width)
+{
+    for (int o = width >> 1; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ inline float group_sum(float v, int width)
+{
+    for (int o = width >> 1; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// lse_i = LSE_t((C_it + g_t)/eps), `width` lanes per (g, i)
+__global__ void xr_row_lse(const float* __restrict__ C, const float* __restrict__ gpot, float* __restrict__ lse,
+                           size_t rows, int n, int r, float eps, int width)
+{
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t row = min(tid / width, rows - 1);          // lanes past the end repeat the last row, store nothing
+    const int sub = (int)(tid % width);
     const float* c = C + row * r;
     const float* g = gpot + (row / n) * r;
     float m = -INFINITY;
-    for (int t = 0; t < r; ++t) m = fmaxf(m, (c[t] + g[t]) / eps);
+    for (int t = sub; t < r; t += width) m = fmaxf(m, (c[t] + g[t]) / eps);
+    m = group_max(m, width);
     float s = 0.f;
-    for (int t = 0; t < r; ++t) s += expf((c[t] + g[t]) / eps - m);
-    lse[row] = m + logf(s);
+    for (int t = sub; t < r; t += width) s += expf((c[t] + g[t]) / eps - m);
+    s = group_sum(s, width);
+    if (sub == 0 && tid / width < rows) lse[row] = m + logf(s);
 }
 
 // per (g, chunk, t): running maximum and scaled sum of mass_i exp(C_it/eps - lse_i) over the chunk
