@@ -238,7 +238,7 @@ def main() -> int:
         def bstep(k):
             s_ = sets[k % rotate]
             lot.lot_attention_bwd(s_["Q"], s_["K"], s_["V"], s_["Z"], s_["beta"], w.eps, w.iters, dOs[k % rotate],
-                                  workspace=ws_b)
+                                  workspace=ws_b, path=path)
 
         for k in range(3):
             bstep(k)

@@ -57,6 +57,7 @@ struct Workspace {
     size_t Y;             // float [G][r][d_v]
     size_t gamma1;        // float [G][n][r]   (attention via the reference path only)
     size_t gamma2;        // float [G][r][n]
+    size_t Zt;            // float [H][d_k][r]: the pivots as the similarities use them, transposed
     size_t total;
 };
 
@@ -76,6 +77,7 @@ inline Workspace carve(const lot_shape& s)
     w.colacc = take(w.colacc_bytes);
     w.u_part = take(G * cb * 64 * dv * 4);
     w.y_tile = take(G * 64 * dv * 4);
+    w.Zt = take((size_t)s.H * r * s.d_k * 4);
     w.C = take(2 * G * n * r * 4);
     w.f = take(2 * G * n * 4);
     w.g = take(2 * G * r * 4);

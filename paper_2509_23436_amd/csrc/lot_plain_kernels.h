@@ -16,10 +16,41 @@ template <typename T> __device__ inline void st(T* p, size_t i, float v);
 template <> __device__ inline void st<float>(float* p, size_t i, float v) { p[i] = v; }
 template <> __device__ inline void st<uint16_t>(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_rne(v); }
 
-// C[side][g][i][t] = <x_i, z_t>, x from Q (side 0) or K (side 1); bf16 mode rounds Z to bf16.
+// Rows of the n x r arrays are walked by a group of `width` adjacent lanes (a power of two, at most 64:
+// the smallest that covers min(r, 64)), so that a wavefront reads whole rows at a time; sums and maxima
+// over a row are butterfly reductions over the group (a fixed order).
+inline int row_group_width(int r)
+{
+    int w = 1;
+    while (w < r && w < 64) w <<= 1;
+    return w;
+}
+__device__ inline float group_max(float v, int width)
+{
+    for (int o = width >> 1; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ inline float group_sum(float v, int width)
+{
+    for (int o = width >> 1; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Zt[h][c][t] = Z[h][t][c] as the similarities use it (rounded to bf16 for bf16 I/O): transposed once, so
+// that the threads of a wavefront (consecutive pivots) read consecutive addresses.
+__global__ void ref_transpose_z(const float* __restrict__ Z, float* __restrict__ Zt, int count, int r, int d, int round_z)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (h, c, t)
+    if (idx >= count) return;
+    const int h = idx / (r * d), c = idx / r % d, t = idx % r;
+    const float z = Z[((size_t)h * r + t) * d + c];
+    Zt[idx] = round_z ? bf16_to_f32(f32_to_bf16_rne(z)) : z;
+}
+
+// C[side][g][i][t] = <x_i, z_t>, x from Q (side 0) or K (side 1); Zt from ref_transpose_z.
 template <typename T>
-__global__ void ref_cost(const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ Z,
-                         float* __restrict__ C, int G, int H, int n, int n_stride, int d, int r, int round_z)
+__global__ void ref_cost(const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ Zt,
+                         float* __restrict__ C, int G, int H, int n, int n_stride, int d, int r)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t per_side = (size_t)G * n * r;
@@ -30,13 +61,9 @@ __global__ void ref_cost(const T* __restrict__ Q, const T* __restrict__ K, const
     rem %= (size_t)n * r;
     const int i = (int)(rem / r), t = (int)(rem % r);
     const T* x = (side == 0 ? Q : K) + ((size_t)g * n_stride + i) * d;
-    const float* z = Z + ((size_t)(g % H) * r + t) * d;
+    const float* z = Zt + (size_t)(g % H) * d * r + t;
     float acc = 0.f;
-    for (int c = 0; c < d; ++c) {
-        float zv = z[c];
-        if (round_z) zv = bf16_to_f32(f32_to_bf16_rne(zv));
-        acc = fmaf(ld(x, c), zv, acc);
-    }
+    for (int c = 0; c < d; ++c) acc = fmaf(ld(x, c), z[(size_t)c * r], acc);
     C[idx] = acc;
 }
 
@@ -50,19 +77,22 @@ __global__ void ref_zero(float* p, size_t count)
     if (idx < count) p[idx] = 0.f;
 }
 
-// f_i = eps (log(1/n) - LSE_t((C_it + g_t)/eps)), one thread per (side, g, i).
+// f_i = eps (log(1/n) - LSE_t((C_it + g_t)/eps)), `width` lanes per (side, g, i).
 __global__ void ref_f_update(const float* __restrict__ C, const float* __restrict__ gpot,
-                             float* __restrict__ f, size_t rows, int n, int r, float eps)
+                             float* __restrict__ f, size_t rows, int n, int r, float eps, int width)
 {
-    const size_t row = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= rows) return;
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t row = min(tid / width, rows - 1);          // lanes past the end repeat the last row, store nothing
+    const int sub = (int)(tid % width);
     const float* c = C + row * r;
     const float* g = gpot + (row / n) * r;
     float m = -INFINITY;
-    for (int t = 0; t < r; ++t) m = fmaxf(m, (c[t] + g[t]) / eps);
+    for (int t = sub; t < r; t += width) m = fmaxf(m, (c[t] + g[t]) / eps);
+    m = group_max(m, width);
     float s = 0.f;
-    for (int t = 0; t < r; ++t) s += expf((c[t] + g[t]) / eps - m);
-    f[row] = eps * (-logf((float)n) - (m + logf(s)));
+    for (int t = sub; t < r; t += width) s += expf((c[t] + g[t]) / eps - m);
+    s = group_sum(s, width);
+    if (sub == 0 && tid / width < rows) f[row] = eps * (-logf((float)n) - (m + logf(s)));
 }
 
 // Per (pair, chunk of tokens, pivot): running maximum and scaled sum of exp((C_it + f_i)/eps).
@@ -123,26 +153,6 @@ __global__ void xr_cost(const T* __restrict__ X, const float* __restrict__ Z, fl
         acc = fmaf(ld(x, c), zv, acc);
     }
     C[idx] = acc;
-}
-
-// Rows of the n x r arrays are walked by a group of `width` adjacent lanes (a power of two, at most 64:
-// the smallest that covers min(r, 64)), so that a wavefront reads whole rows at a time; sums and maxima
-// over a row are butterfly reductions over the group (a fixed order).
-inline int row_group_width(int r)
-{
-    int w = 1;
-    while (w < r && w < 64) w <<= 1;
-    return w;
-}
-__device__ inline float group_max(float v, int width)
-{
-    for (int o = width >> 1; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-__device__ inline float group_sum(float v, int width)
-{
-    for (int o = width >> 1; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
 }
 
 // lse_i = LSE_t((C_it + g_t)/eps), `width` lanes per (g, i)

@@ -32,18 +32,39 @@ __global__ void ref_couplings(const float* __restrict__ C, const float* __restri
     else gamma2[(g * r + t) * n + i] = v;
 }
 
-// Y'[g][t][c] = (sum_j gamma2[g][t][j] V[g][j][c]) / beta_t ; one block per (g, t), thread per c.
+// Y'[g][t][c] = (sum_j gamma2[g][t][j] V[g][j][c]) / beta_t.  One block of 256 threads per (g, t):
+// thread = (token slice s of 16, column class of 16); a thread sums every 16th token for its columns,
+// the slices are then added in LDS in slice order.
+constexpr int kYSlices = 16, kYCols = 16;
 template <typename T>
 __global__ void ref_reduce_y(const float* __restrict__ gamma2, const T* __restrict__ V,
                              const float* __restrict__ beta, float* __restrict__ Y,
                              int H, int n, int n_stride, int r, int dv)
 {
+    __shared__ float s_part[kYSlices][4 * kYCols];
     const int g = blockIdx.x / r, t = blockIdx.x % r;
+    const int sl = threadIdx.x / kYCols, cc = threadIdx.x % kYCols;
     const float* row = gamma2 + ((size_t)g * r + t) * n;
-    for (int c = threadIdx.x; c < dv; c += blockDim.x) {
-        float acc = 0.f;
-        for (int j = 0; j < n; ++j) acc = fmaf(row[j], ld(V, ((size_t)g * n_stride + j) * dv + c), acc);
-        Y[((size_t)g * r + t) * dv + c] = acc / beta[(g % H) * r + t];
+    for (int c0 = 0; c0 < dv; c0 += 4 * kYCols) {          // four columns of a thread at a time
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int j = sl; j < n; j += kYSlices) {
+            const float w = row[j];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = c0 + q * kYCols + cc;
+                if (c < dv) acc[q] = fmaf(w, ld(V, ((size_t)g * n_stride + j) * dv + c), acc[q]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s_part[sl][q * kYCols + cc] = acc[q];
+        __syncthreads();
+        if (threadIdx.x < 4 * kYCols) {
+            const int c = c0 + threadIdx.x;
+            float tot = 0.f;
+            for (int k = 0; k < kYSlices; ++k) tot += s_part[k][threadIdx.x];
+            if (c < dv) Y[((size_t)g * r + t) * dv + c] = tot / beta[(g % H) * r + t];
+        }
+        __syncthreads();
     }
 }
 
@@ -79,19 +100,21 @@ int run_reference_t(const Args& a, bool want_out)
     const size_t rows = (size_t)pairs * n;
     hipStream_t st_ = a.stream;
     const int nst = a.n_stride > 0 ? a.n_stride : n;
+    const int width = row_group_width(r);
 
     ref_mark<<<1, 1, 0, st_>>>((unsigned long long*)(a.ws + a.lay.status), next_nonce());
-    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, a.Z, C, G, s.H, n, nst, s.d_k, r,
-                                                         s.io_dtype == LOT_BF16);
+    float* Zt = (float*)(a.ws + a.lay.Zt);
+    ref_transpose_z<<<blocks_for((size_t)s.H * r * s.d_k, 256), 256, 0, st_>>>(a.Z, Zt, s.H * r * s.d_k, r, s.d_k, s.io_dtype == LOT_BF16);
+    ref_cost<T><<<blocks_for(nelem, 256), 256, 0, st_>>>((const T*)a.Q, (const T*)a.K, Zt, C, G, s.H, n, nst, s.d_k, r);
     ref_zero<<<blocks_for((size_t)pairs * r, 256), 256, 0, st_>>>(g, (size_t)pairs * r);
     for (int it = 0; it < a.iters; ++it) {
-        ref_f_update<<<blocks_for(rows, 256), 256, 0, st_>>>(C, g, f, rows, n, r, a.eps);
+        ref_f_update<<<blocks_for(rows * width, 256), 256, 0, st_>>>(C, g, f, rows, n, r, a.eps, width);
         ref_g_partial<<<(unsigned)pairs * chunks, 64, 0, st_>>>(C, f, pm, ps, n, r, chunks, a.eps);
         ref_g_final<<<blocks_for((size_t)pairs * r, 256), 256, 0, st_>>>(pm, ps, a.beta, g, pairs, G, s.H, r, chunks, a.eps);
     }
     ref_couplings<<<blocks_for(nelem, 256), 256, 0, st_>>>(C, f, g, a.gamma1, a.gamma2, G, n, r, a.eps);
     if (want_out) {
-        ref_reduce_y<T><<<(unsigned)G * r, 64, 0, st_>>>(a.gamma2, (const T*)a.V, a.beta, Y, s.H, n, nst, r, s.d_v);
+        ref_reduce_y<T><<<(unsigned)G * r, kYSlices * kYCols, 0, st_>>>(a.gamma2, (const T*)a.V, a.beta, Y, s.H, n, nst, r, s.d_v);
         const size_t total = (size_t)G * n * s.d_v;
         ref_expand<T><<<blocks_for(total, 256), 256, 0, st_>>>(a.gamma1, Y, (T*)a.out, total, n, nst, r, s.d_v);
     }
