@@ -220,9 +220,12 @@ __device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace&
                 if (!WITH_U) cs[mb][j] = fmaf(acc[mb][j], wcs, cs[mb][j]);
                 acc[mb][j] *= wtr;
             }
-        transpose_tile<RB, kSplit>(acc, tr_hi, tr_lo, i, kg);
+        // bf16 I/O: the Gram matrix takes its weights as fp16 (the recursion through the iterations divides
+        // by the column sums, so pivots of small mass feel the rounding of their few weights)
+        constexpr bool kHalfGram = !WITH_U && !kSplit;
+        transpose_tile<RB, kSplit, kHalfGram>(acc, tr_hi, tr_lo, i, kg);
         if (WITH_U) contract_tokens<D, RB, kSplit>(U, tr_hi, tr_lo, vh, vl, i, kg);
-        else contract_gram<RB, kSplit>(Gm, tr_hi, tr_lo, i, kg);
+        else contract_gram<RB, kSplit, kHalfGram>(Gm, tr_hi, tr_lo, i, kg);
         transpose_done();
         xc = xn;
         mc = mn;
@@ -493,6 +496,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
     __shared__ __attribute__((aligned(16))) bf16x8 s_yf[2][2 * RB * NB * 64];
     __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
     __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
+    // bf16 I/O: what the bf16 rounding of that operand leaves out (see the incoming-gradient tile below)
+    __shared__ __attribute__((aligned(16))) char s_ystash_lo[kSplit ? 16 : StashBytes<IO, D, RB>::value];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -539,6 +544,11 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) load_pivots_lds<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
         stash_pivots<D, RB>(s_ystash, y0, lane);
+        if (!kSplit) {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb) load_pivots_lds_lo<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
+            stash_pivots<D, RB>(s_ystash_lo, y0, lane);
+        }
     }
     __syncthreads();
 
@@ -570,9 +580,16 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
 #pragma unroll
             for (int j = 0; j < 16; ++j) { acc[mb][j] *= w; dgam[mb][j] = 0.f; }
         {
+            // The incoming gradient of the coupling.  s, q and N below meet in differences (N - P s) that
+            // are an order of magnitude smaller than their terms, so with bf16 I/O the matrix operand is
+            // taken as bf16 hi + lo (two products): its rounding would otherwise show in dbeta.
             Frag<IO, D> yfrag[RB];
             fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
             similarity<D, RB>(dgam, yfrag, vc);
+            if (!kSplit) {
+                fetch_pivots<D, RB>(yfrag, s_ystash_lo, lane, skew);
+                similarity<D, RB>(dgam, yfrag, vc);
+            }
         }
         if (weighted) {
 #pragma unroll
@@ -733,6 +750,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
     __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 64 * kTrStride];
     __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
     __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
+    static_assert(kSplit || sizeof(s_zf[1]) >= (size_t)StashBytes<IO, D, RB>::value, "the lo stash takes the place of s_zf[1]");
+    char* const s_ystash_lo = reinterpret_cast<char*>(s_zf[1]);   // bf16 I/O only (s_zf[1] is then unused)
     float* s_hist = reinterpret_cast<float*>(s_dyn);
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -782,6 +801,13 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) load_pivots_lds<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
         stash_pivots<D, RB>(s_ystash, y0, lane);
+        if (!kSplit) {
+            // bf16 I/O: the lo part of the same operand (see the glue kernel); it takes the place of the
+            // lo half of the Z fragments, which only fp32 I/O uses
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb) load_pivots_lds_lo<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
+            stash_pivots<D, RB>(s_ystash_lo, y0, lane);
+        }
     }
     __syncthreads();   // s_y is reused below for the dZ partial
 
@@ -890,6 +916,10 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
                 Frag<IO, D> yfrag[RB];
                 fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
                 similarity<D, RB>(dp, yfrag, vc);                 // dGamma tile
+                if (!kSplit) {
+                    fetch_pivots<D, RB>(yfrag, s_ystash_lo, lane, skew);
+                    similarity<D, RB>(dp, yfrag, vc);
+                }
             }
             {
                 f32x16 rho[RB], dc[RB];

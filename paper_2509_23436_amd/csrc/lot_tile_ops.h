@@ -46,20 +46,29 @@ __device__ __forceinline__ void tile_weights(f32x16 (&acc)[RB], float& w, const 
     w = valid ? rcp_fast(pair_sum(s0 + s1)) : 0.f;
 }
 
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
 // Writes v (accumulator layout, tokens in lanes) transposed into the wavefront's LDS area as bf16
-// hi (+ lo when SPLIT), so that rows of 32 tokens can be read back as MFMA operands.
-template <int RB, bool SPLIT>
+// hi (+ lo when SPLIT), so that rows of 32 tokens can be read back as MFMA operands.  HALF (without
+// SPLIT): as fp16 instead -- for values in [0, ~1e4] such as coupling weights it keeps 11 bits where
+// bf16 keeps 8, at the same MFMA rate (what falls below its range is far below anything that counts).
+template <int RB, bool SPLIT, bool HALF = false>
 __device__ __forceinline__ void transpose_tile(const f32x16 (&v)[RB], uint16_t* tr_hi, uint16_t* tr_lo, int i, int kg)
 {
+    static_assert(!(SPLIT && HALF), "the split form is bf16");
 #pragma unroll
     for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const float x = v[mb][j];
-            const __bf16 h = (__bf16)x;
             const int pv = pivot_of(mb, j, kg);
-            tr_hi[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, h);
-            if (SPLIT) tr_lo[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, (__bf16)(x - (float)h));
+            if (HALF) {
+                tr_hi[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, (_Float16)x);
+            } else {
+                const __bf16 h = (__bf16)x;
+                tr_hi[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, h);
+                if (SPLIT) tr_lo[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, (__bf16)(x - (float)h));
+            }
         }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -97,9 +106,24 @@ __device__ __forceinline__ void contract_tokens(f32x16 (&U)[RB][D / 32], const u
 }
 
 // Gm[mb][mb2] += sum over the tile's tokens of v_it v_it'   (t in block mb: registers, t' in block mb2: lanes)
-template <int RB, bool SPLIT>
+template <int RB, bool SPLIT, bool HALF = false>
 __device__ __forceinline__ void contract_gram(f32x16 (&Gm)[RB][RB], const uint16_t* tr_hi, const uint16_t* tr_lo, int i, int kg)
 {
+    if (HALF) {         // the tile was written as fp16 (transpose_tile<.., HALF = true>)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            f16x8 a[RB];
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+                a[mb] = *reinterpret_cast<const f16x8*>(tr_hi + (32 * mb + i) * kTrStride + 16 * s + 8 * kg);
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int mb2 = mb; mb2 < RB; ++mb2)
+                    Gm[mb][mb2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mb], a[mb2], Gm[mb][mb2], 0, 0, 0);
+        }
+        return;
+    }
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         bf16x8 ah[RB], al[RB];
@@ -210,6 +234,24 @@ __device__ __forceinline__ void load_pivots_lds(Frag<uint16_t, D>& f, const floa
         f.v[s] = __builtin_convertvector(t, bf16x8);
     }
 }
+// The part of the same row that the bf16 fragment above leaves out: x - bf16(x), again as bf16.  A
+// product taken with both fragments carries the row to about 2^-17.
+template <int D>
+__device__ __forceinline__ void load_pivots_lds_lo(Frag<uint16_t, D>& f, const float* row, int kg)
+{
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+        f32x8 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float x = row[16 * s + 8 * kg + e];
+            t[e] = x - (float)(__bf16)x;
+        }
+        f.v[s] = __builtin_convertvector(t, bf16x8);
+    }
+}
+template <int D>
+__device__ __forceinline__ void load_pivots_lds_lo(Frag<float, D>&, const float*, int) {}   // fp32 fragments are exact
 template <int D>
 __device__ __forceinline__ void load_pivots_lds(Frag<float, D>& f, const float* row, int kg)
 {
