@@ -108,7 +108,9 @@ constexpr int kCountShift = 56;
 constexpr unsigned long long kSumMask = (1ull << kCountShift) - 1;
 __device__ __forceinline__ float colsum_of(unsigned long long word, float unscale)
 {
-    return fmaxf((float)(long long)(word & kSumMask) * unscale, 1.0e-37f);
+    // a sum below the fixed-point resolution reads as half a unit, not as (almost) nothing: the potentials
+    // then move by a bounded amount and the couplings of a starved pivot stay bounded
+    return fmaxf((float)(long long)(word & kSumMask) * unscale, 0.5f * unscale);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1146,7 +1148,6 @@ int run_backward_tiled(const BwdArgs& a)
         // column sums of a row-normalised kernel are at most n: with 2^(55 - ceil(log2(n + 1))) units per
         // one the sum stays below 2^55, clear of the contributor count in the top byte
         int frac = 55 - (int)std::ceil(std::log2((double)s.n + 1.0));
-        if (frac > 40) frac = 40;
         p.fx_scale = std::ldexp(1.0f, frac);
         p.fx_unscale = std::ldexp(1.0f, -frac);
     }

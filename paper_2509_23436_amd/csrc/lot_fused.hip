@@ -461,7 +461,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 tot = s_tot[side][ln];
             }
             if (ln < rr) {
-                const float c = fmaxf(tot, 1.0e-37f);
+                // (sums exchanged in fixed point: one below the resolution reads as half a unit)
+                const float c = fmaxf(tot, p.cluster > 1 ? 0.5f * p.fx_unscale : 1.0e-37f);
                 const float b = s_beta[ln];
                 if (!final) {
                     s_g[side][ln] += p.eps * logf((float)opaque_scalar(p.n_side[side]) * b / c);
@@ -796,7 +797,6 @@ int launch(const Args& a, bool want_out)
     {
         const double max_sum = ((double)a.iters / 2.0 + 1.0) * (double)(n_side[0] > n_side[1] ? n_side[0] : n_side[1]);
         int frac = 55 - (int)std::ceil(std::log2(max_sum + 1.0));
-        if (frac > 40) frac = 40;
         if (frac < 8) return LOT_ERR_PATH;
         p.fx_scale = std::ldexp(1.0f, frac);
         p.fx_unscale = std::ldexp(1.0f, -frac);

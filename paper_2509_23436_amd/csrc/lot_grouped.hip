@@ -127,7 +127,8 @@ __device__ __forceinline__ void load_potentials(const LgParams& p, float* s_g, i
         float gv = t < p.r ? 0.f : kNegBig;
         if (k > 1 && t < p.r) {
             const unsigned long long word = p.colacc[((size_t)(k - 1) * pairs + pair) * kRmax + t];
-            const float cs = fmaxf((float)(long long)word * p.fx_unscale, 1.0e-37f);
+            // (a sum below the fixed-point resolution reads as half a unit: the potentials stay bounded)
+            const float cs = fmaxf((float)(long long)word * p.fx_unscale, 0.5f * p.fx_unscale);
             gv = p.ghist[((size_t)(k - 2) * pairs + pair) * kRmax + t] + p.eps * logf((float)p.n * p.beta[h * p.r + t] / cs);
         }
         s_g[t] = gv;
@@ -283,8 +284,8 @@ __global__ void lg_mid(LgParams p)
         int c = 0;
         for (; c + 1 < p.chunks; c += 2) { u0 += up[(size_t)c * kRmax * D]; u1 += up[(size_t)(c + 1) * kRmax * D]; }
         if (c < p.chunks) u0 += up[(size_t)c * kRmax * D];
-        const float cs1 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * kRmax + t] * p.fx_unscale, 1.0e-37f);
-        const float cs2 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * kRmax + t] * p.fx_unscale, 1.0e-37f);
+        const float cs1 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * kRmax + t] * p.fx_unscale, 0.5f * p.fx_unscale);
+        const float cs2 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * kRmax + t] * p.fx_unscale, 0.5f * p.fx_unscale);
         y = ((float)p.n * p.beta[(g % p.H) * p.r + t] / cs1) * ((u0 + u1) / cs2);
     }
     p.ypp[idx] = y;
@@ -426,7 +427,6 @@ int run_grouped(const Args& a)
     p.eps = a.eps;
     {
         int frac = 62 - (int)std::ceil(std::log2((double)s.n + 1.0));
-        if (frac > 40) frac = 40;
         p.fx_scale = std::ldexp(1.0f, frac);
         p.fx_unscale = std::ldexp(1.0f, -frac);
     }

@@ -214,6 +214,10 @@ LARGE_R = {
     "r200_bf16_d32": S(W["swin_t_s1"], B=1, H=3, n=1000, r=200, iters=5, seed=43),
     "r256_bf16": S(W["long_4k"], B=2, H=2, n=2100, r=256, iters=4, seed=44),
     "r256_f32_one_iteration": S(W["tiny"], B=1, H=1, n=90, d=64, r=256, iters=1, seed=45),
+    # one token and 256 pivots: most column sums are far below 1 (found by a randomised sweep: sums under the
+    # resolution of the fixed-point exchange used to read as 1e-37 and sent the potentials off)
+    "r256_f32_one_token": S(W["tiny"], B=1, H=2, n=1, d=32, r=256, eps=0.05, iters=6, seed=676049889),
+    "r96_f32_one_token": S(W["tiny"], B=2, H=3, n=1, d=32, r=96, eps=0.05, iters=5, seed=465326253),
 }
 
 
