@@ -161,7 +161,8 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * gradient buffers must not alias the inputs, the workspace or each other.  iters <= 65536.
  * Two execution paths, chosen like the forward ones (lot_path): REFERENCE = one plain kernel per
  * step with the n x r intermediates in the workspace, any shape; FUSED = tiled MFMA kernels that
- * keep nothing of size n x r (d_k = d_v in {32, 64}, r <= 64, iters <= 32).  AUTO prefers FUSED.
+ * keep nothing of size n x r (d_k = d_v in {32, 64}, r <= 64, iters <= 32).  AUTO prefers FUSED
+ * (from 16 tokens up; shorter sequences go to the plain kernels, which are exact to fp32 rounding).
  * Results are reproducible bit for bit on either path.  lot_workspace_status applies to this
  * workspace too (the FUSED path's forward sweep waits between workgroups when it runs as one kernel).
  * Testing aid: the FUSED path rebuilds each tile's row-normalised kernels for all iterations with ONE

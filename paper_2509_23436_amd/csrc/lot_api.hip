@@ -316,6 +316,12 @@ int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t*
     return LOT_OK;
 }
 
+// AUTO sends problems of fewer tokens than this to the plain backward kernels: with so few tokens nothing
+// averages out the rounding of the tiled path's bf16 (hi + lo) contractions, and gradients that vanish
+// identically (a single token, say) come out as noise at 1e-3 of the other tensors' scale; the plain
+// kernels are exact to fp32 rounding and cost nothing at this size.
+constexpr int kMinTiledTokens = 16;
+
 // n_stride: tokens between consecutive problems in the token tensors (0 = shape->n)
 static int backward_impl(const lot_shape* shape, const void* Q, const void* K, const void* V,
                          const float* Z, const float* beta, float eps, int iters, const void* dO,
@@ -334,7 +340,7 @@ static int backward_impl(const lot_shape* shape, const void* Q, const void* K, c
     if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
     bool tiled = false;
     switch (path) {
-    case LOT_PATH_AUTO: tiled = bwd_tiled_supports(*shape, iters); break;
+    case LOT_PATH_AUTO: tiled = bwd_tiled_supports(*shape, iters) && shape->n >= kMinTiledTokens; break;
     case LOT_PATH_REFERENCE: tiled = false; break;
     case LOT_PATH_FUSED:
         if (!bwd_tiled_supports(*shape, iters)) return LOT_ERR_PATH;
@@ -408,7 +414,9 @@ int lot_cross_attention_bwd_path(const lot_xshape* shape, const void* Q, const v
     a.n_q = shape->n_q; a.n_k = shape->n_k; a.mass_q = mass_q; a.mass_k = mass_k;
     bool tiled = false;
     switch (path) {
-    case LOT_PATH_AUTO: tiled = bwd_tiled_supports(s, iters); break;
+    case LOT_PATH_AUTO:
+        tiled = bwd_tiled_supports(s, iters) && shape->n_q >= kMinTiledTokens && shape->n_k >= kMinTiledTokens;
+        break;
     case LOT_PATH_REFERENCE: tiled = false; break;
     case LOT_PATH_FUSED:
         if (!bwd_tiled_supports(s, iters)) return LOT_ERR_PATH;
