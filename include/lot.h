@@ -1,5 +1,5 @@
 /*
- * libLOT -- LOT attention forward on AMD MI355X (gfx950): C ABI.
+ * libLOT -- LOT attention, forward and backward, on AMD MI355X (gfx950): C ABI.
  *
  * The operation (paper, Method section, "Conditional OT", "Glued coupling and
  * doubly-stochastic attention", eq. (lotattn), "Rank and complexity"): for every (batch, head)
@@ -17,7 +17,8 @@
  *
  * Conventions for every entry point
  *  - All tensor pointers are DEVICE pointers owned by the caller; the library allocates and frees
- *    nothing and keeps no state between calls.  Outputs must not alias inputs or the workspace.
+ *    nothing and keeps no state between calls that a result depends on (a launch counter and cached
+ *    device properties only).  Outputs must not alias inputs or the workspace.
  *  - Layout: dense row-major, last index fastest.
  *        Q, K : [B, H, n, d_k]      V, out : [B, H, n, d_v]      (element type = shape.io_dtype)
  *        Z    : [H, r, d_k] float   beta   : [H, r] float        (one pivot measure per head)
