@@ -436,15 +436,16 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
 // ---------------------------------------------------------------------------------------------
 // mid: Y'_t = U_t / cs2_t, dYraw_t = n Wd_t / cs1_t, db_glue_t = -<dYraw_t, Y'_t>, rho'_t = beta_t / cs_t
 // ---------------------------------------------------------------------------------------------
-// stage 1: one thread per (g, t, column): sums the per-chunk contractions in chunk order
+// One thread per (g, t, column): sums the per-chunk contractions in chunk order; the D threads of a
+// (g, t) row are adjacent lanes of one wavefront, so the row's dot product <dYraw_t, Y'_t> is a
+// butterfly sum over them and lane 0 of the row writes the per-pivot numbers.
 template <int D>
 __global__ void bt_mid(BtParams p)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= p.G * 64 * D) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;      // the grid covers G * 64 * D exactly: whole wavefronts
     const int g = idx / (64 * D), e = idx % (64 * D), t = e / D;
     const int pairs = 2 * p.G, T = p.T;
-    float y = 0.f, dy = 0.f;
+    float y = 0.f, dy = 0.f, r1 = 0.f, r2 = 0.f;
     if (t < p.r) {
         float u0 = 0.f, u1 = 0.f, w0 = 0.f, w1 = 0.f;     // two interleaved chains each: the loads overlap
         const float* wp = p.u_part + ((size_t)(0 * p.G + g) * p.chunks) * 64 * D + e;
@@ -459,27 +460,20 @@ __global__ void bt_mid(BtParams p)
         const float cs2 = colsum_of(p.colacc[((size_t)T * pairs + p.G + g) * 64 + t], p.fx_unscale);
         y = (u0 + u1) / cs2;
         dy = (float)p.n_side[0] * (w0 + w1) / cs1;
+        const float b = p.beta[(g % p.H) * p.r + t];
+        r1 = b / cs1;
+        r2 = b / cs2;
     }
     p.yp[idx] = y;
     p.dyraw[idx] = dy;
-}
-// stage 2: one thread per (g, t)
-template <int D>
-__global__ void bt_mid2(BtParams p)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= p.G * 64) return;
-    const int g = idx / 64, t = idx % 64, h = g % p.H, pairs = 2 * p.G, T = p.T;
-    float dot = 0.f, r1 = 0.f, r2 = 0.f;
-    if (t < p.r) {
-        for (int c = 0; c < D; ++c) dot = fmaf(p.dyraw[(size_t)idx * D + c], p.yp[(size_t)idx * D + c], dot);
-        const float b = p.beta[h * p.r + t];
-        r1 = b / colsum_of(p.colacc[((size_t)T * pairs + g) * 64 + t], p.fx_unscale);
-        r2 = b / colsum_of(p.colacc[((size_t)T * pairs + p.G + g) * 64 + t], p.fx_unscale);
+    float dot = dy * y;
+#pragma unroll
+    for (int o = D / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+    if (e % D == 0) {
+        p.db_glue[g * 64 + t] = -dot;
+        p.rhop[(size_t)g * 64 + t] = r1;
+        p.rhop[(size_t)(p.G + g) * 64 + t] = r2;
     }
-    p.db_glue[idx] = -dot;
-    p.rhop[(size_t)g * 64 + t] = r1;
-    p.rhop[(size_t)(p.G + g) * 64 + t] = r2;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -686,7 +680,7 @@ __global__ void bt_gram_reduce(BtParams p, int R, size_t total)
 }
 
 // ---------------------------------------------------------------------------------------------
-// recursion over the iterations: one workgroup of 64 threads per pair, thread = pivot
+// recursion over the iterations: one workgroup per pair
 // ---------------------------------------------------------------------------------------------
 __global__ void bt_recursion(BtParams p, int R)
 {
@@ -708,27 +702,41 @@ __global__ void bt_recursion(BtParams p, int R)
     auto colsum = [&](int k) {
         return colsum_of(p.colacc[((size_t)k * pairs + pair) * 64 + t], p.fx_unscale) * a;   // c^k_t
     };
+    // M^k is symmetric: thread t walks a quarter of column t, so that a wavefront reads whole rows.  Only the
+    // vector depends on the step before, so the next step's Gram values (and column sum) are requested
+    // while this step's products run.
+    const bool walks = live && t < R;
+    const int u0 = q * (R / 4);
+    float mcur[16], mnext[16];
+    auto gram_fetch = [&](int k, float (&m)[16]) {
+        const float* col = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + t;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) m[j] = (walks && j < R / 4 && k >= 1) ? col[(size_t)(u0 + j) * R] : 0.f;
+    };
     auto gram_times = [&](int k, float v) {      // (M^k v)_t; v is meaningful in the threads with q == 0
         if (q == 0) s_v[t] = live ? v : 0.f;
+        gram_fetch(k - 1, mnext);
         __syncthreads();
         float acc = 0.f;
-        if (live && t < R) {
-            // M^k is symmetric: thread t walks column t, so that a wavefront reads whole rows
-            const float* col = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + t;
-            const int u0 = q * (R / 4);
-#pragma unroll 8
-            for (int u = u0; u < u0 + R / 4; ++u) acc = fmaf(col[(size_t)u * R], s_v[u], acc);
-        }
-        s_q[q][t] = acc;
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (j < R / 4) acc = fmaf(mcur[j], s_v[u0 + j], acc);
+        s_q[q][t] = walks ? acc : 0.f;
         __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 16; ++j) mcur[j] = mnext[j];
         return (s_q[0][t] + s_q[1][t]) + (s_q[2][t] + s_q[3][t]);
     };
+    gram_fetch(T, mcur);
+    float cs_next = T >= 2 ? colsum(T - 1) : 1.f;
     float db = live ? s / b : 0.f;
     float dc = live ? -s / colsum(T) : 0.f;
     if (q == 0) p.dcs[((size_t)T * pairs + pair) * 64 + t] = dc;
     float dg = -(nn + a * gram_times(T, dc)) / p.eps;          // dg^{T-1}
     for (int k = T - 1; k >= 1; --k) {
-        dc = live ? -p.eps * dg / colsum(k) : 0.f;
+        const float cs = cs_next;
+        cs_next = k >= 2 ? colsum(k - 1) : 1.f;
+        dc = live ? -p.eps * dg / cs : 0.f;
         db += live ? p.eps * dg / b : 0.f;
         if (q == 0) p.dcs[((size_t)k * pairs + pair) * 64 + t] = dc;
         dg = -(a / p.eps) * gram_times(k, dc);                  // dg^{k-1}
@@ -1061,7 +1069,6 @@ int launch_all(const BwdArgs& a, BtParams p)
         else bt_forward<IO, D, RB, true, false><<<grid, kThreads, 0, st>>>(p);
     }
     bt_mid<D><<<(unsigned)((p.G * 64 * D + 255) / 256), 256, 0, st>>>(p);
-    bt_mid2<D><<<(unsigned)((p.G * 64 + 255) / 256), 256, 0, st>>>(p);
     bt_glue<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
     {
         const size_t total = (size_t)T * pairs * R * R;
