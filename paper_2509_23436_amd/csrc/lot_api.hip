@@ -312,6 +312,10 @@ int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t*
         const size_t tiled = carve_bwd_tiled(*shape, iters).total;
         if (tiled > need) need = tiled;
     }
+    if (bwd_grouped_supports(*shape, iters)) {
+        const size_t grouped = carve_bwd_grouped(*shape, iters).total;
+        if (grouped > need) need = grouped;
+    }
     *bytes_out = need;
     return LOT_OK;
 }
@@ -338,12 +342,14 @@ static int backward_impl(const lot_shape* shape, const void* Q, const void* K, c
         misaligned(dbeta, 4))
         return LOT_ERR_ALIGN;
     if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
+    // the tile kernels: r <= 64 in one register tile, larger r with the pivots in groups of 64
+    const bool one_tile = bwd_tiled_supports(*shape, iters), grouped = bwd_grouped_supports(*shape, iters);
     bool tiled = false;
     switch (path) {
-    case LOT_PATH_AUTO: tiled = bwd_tiled_supports(*shape, iters) && shape->n >= kMinTiledTokens; break;
+    case LOT_PATH_AUTO: tiled = (one_tile || grouped) && shape->n >= kMinTiledTokens; break;
     case LOT_PATH_REFERENCE: tiled = false; break;
     case LOT_PATH_FUSED:
-        if (!bwd_tiled_supports(*shape, iters)) return LOT_ERR_PATH;
+        if (!one_tile && !grouped) return LOT_ERR_PATH;
         tiled = true;
         break;
     default: return LOT_ERR_PATH;
@@ -358,7 +364,8 @@ static int backward_impl(const lot_shape* shape, const void* Q, const void* K, c
     a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
     a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
     a.n_stride = n_stride;
-    return tiled ? run_backward_tiled(a) : run_backward(a);
+    if (!tiled) return run_backward(a);
+    return one_tile ? run_backward_tiled(a) : run_backward_grouped(a);
 }
 
 int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,

@@ -1,0 +1,276 @@
+// Device code shared by the forward and the backward pass for pivot sizes beyond one register tile
+// (64 < r <= 256): the pivots are taken in groups of 64.  Per tile of 32 tokens, a first sweep over the
+// groups finds each row's maximum and normaliser; a second sweep rebuilds each group's weights
+// W_it = softmax_t((C_it + g_t)/eps) against them.  (Paper, Method: similarities C = X Z^T, Sinkhorn
+// scaling in the log domain; its runtime study sweeps r up to 256.)
+#pragma once
+#include "lot_internal.h"
+#include "lot_tile.h"
+#include "lot_tile_ops.h"
+
+namespace lot {
+namespace {
+
+constexpr int kGroup = 64;          // pivots per group (two MFMA blocks)
+constexpr int kMaxGroups = 4;
+constexpr int kRmax = kGroup * kMaxGroups;
+constexpr int kGTargetWgs = 512;
+
+struct LgParams {
+    const void* Q; const void* K; const void* V;
+    const float* Z; const float* beta;
+    void* out;
+    unsigned long long* colacc;   // [T+1][pairs][256]
+    float* ghist;                 // [T+1][pairs][256]  g^k, k = 0..T-1 (padding pivots: -1e30)
+    float* u_part;                // [G][chunks][256][D]
+    float* ypp;                   // [G][256][D]  Y''
+    float* rowlse;                // [T][pairs][n] base-2 log-normaliser of every row in pass k (at k - 1), or null: not kept
+    int G, H, n, n_stride, r, groups, chunks, tiles_per_wg, k, T;
+    float eps, fx_scale, fx_unscale;
+};
+
+inline int lg_tiles_per_wg(const lot_shape& s)
+{
+    const long long ntiles = ((long long)s.n + kTileTokens - 1) / kTileTokens;
+    long long per = (ntiles * 2LL * s.B * s.H + kGTargetWgs - 1) / kGTargetWgs;
+    per = (per + kWaves - 1) / kWaves * kWaves;
+    if (per < kWaves) per = kWaves;
+    if (per > 16 * kWaves) per = 16 * kWaves;
+    return (int)per;
+}
+
+// First sweep over the groups for one tile: row maximum (times c1) and reciprocal normaliser.
+template <typename IO, int D>
+__device__ __forceinline__ void row_normaliser(float& mc, float& w, const char* zstash, const Frag<IO, D>& xf,
+                                               const float* pot, int groups, int lane, int kg, float c1, bool valid)
+{
+    float run_m = -INFINITY, run_s = 0.f;
+    for (int p = 0; p < groups; ++p) {
+        int skew = 0;
+        asm volatile("" : "+v"(skew));
+        Frag<IO, D> zf[2];
+        fetch_pivots<D, 2>(zf, zstash + (size_t)p * StashBytes<IO, D, 2>::value, lane, skew);
+        f32x16 acc[2];
+        load_pivot_vector<2>(acc, pot + kGroup * p + skew, kg);
+        similarity<D, 2>(acc, zf, xf);
+        float m0 = acc[0][0], m1 = acc[0][1];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int j = (mb == 0 ? 2 : 0); j < 16; j += 2) {
+                m0 = fmaxf(m0, acc[mb][j]);
+                m1 = fmaxf(m1, acc[mb][j + 1]);
+            }
+        const float new_m = fmaxf(run_m, pair_max(fmaxf(m0, m1)) * c1);
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; j += 2) {
+                s0 += exp2_fast(fmaf(acc[mb][j], c1, -new_m));
+                s1 += exp2_fast(fmaf(acc[mb][j + 1], c1, -new_m));
+            }
+        run_s = run_s * exp2_fast(run_m - new_m) + (s0 + s1);     // exp2(-inf) = 0 for the first group
+        run_m = new_m;
+    }
+    mc = run_m;
+    w = valid ? rcp_fast(pair_sum(run_s)) : 0.f;
+}
+
+// Second sweep, one group: acc <- W_it = exp2((C_it + g_t) c1 - mc) * w for the group's 64 pivots.
+template <typename IO, int D>
+__device__ __forceinline__ void group_weights(f32x16 (&acc)[2], int p, float mc, float w, const char* zstash,
+                                              const Frag<IO, D>& xf, const float* pot, int lane, int kg, float c1)
+{
+    int skew = 0;
+    asm volatile("" : "+v"(skew));
+    Frag<IO, D> zf[2];
+    fetch_pivots<D, 2>(zf, zstash + (size_t)p * StashBytes<IO, D, 2>::value, lane, skew);
+    load_pivot_vector<2>(acc, pot + kGroup * p + skew, kg);
+    similarity<D, 2>(acc, zf, xf);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[mb][j] = exp2_fast(fmaf(acc[mb][j], c1, -mc)) * w;
+}
+
+// Common set-up: pivot fragments of all groups to the LDS stash, g^{k-1} to s_g.
+template <typename IO, int D>
+__device__ __forceinline__ void stash_all_pivots(char* zstash, const float* Z, int h, int r, int groups,
+                                                 int wave, int lane)
+{
+    const int i = lane & 31, kg = lane >> 5;
+    for (int p = wave; p < groups; p += kWaves) {
+        Frag<IO, D> z0[2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            const int t = kGroup * p + 32 * mb + i;
+            load_pivots<D>(z0[mb], Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
+        }
+        stash_pivots<D, 2>(zstash + (size_t)p * StashBytes<IO, D, 2>::value, z0, lane);
+    }
+}
+
+// g^{k-1}_t for all t < 256 into s_g (and, by one workgroup per pair, into ghist[k-1]).
+__device__ __forceinline__ void load_potentials(const LgParams& p, float* s_g, int k, int pair, int h, bool keep, int tid)
+{
+    const int pairs = 2 * p.G;
+    for (int t = tid; t < kRmax; t += kThreads) {
+        float gv = t < p.r ? 0.f : kNegBig;
+        if (k > 1 && t < p.r) {
+            const unsigned long long word = p.colacc[((size_t)(k - 1) * pairs + pair) * kRmax + t];
+            // (a sum below the fixed-point resolution reads as half a unit: the potentials stay bounded)
+            const float cs = fmaxf((float)(long long)word * p.fx_unscale, 0.5f * p.fx_unscale);
+            gv = p.ghist[((size_t)(k - 2) * pairs + pair) * kRmax + t] + p.eps * logf((float)p.n * p.beta[h * p.r + t] / cs);
+        }
+        s_g[t] = gv;
+        if (keep) p.ghist[((size_t)(k - 1) * pairs + pair) * kRmax + t] = gv;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// pass k: column sums of W^k for both solves
+// ---------------------------------------------------------------------------------------------
+template <typename IO, int D>
+__global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
+{
+    __shared__ float s_g[kRmax];
+    __shared__ float s_cs[kWaves][kRmax];
+    extern __shared__ __attribute__((aligned(16))) char s_zstash[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 31, kg = lane >> 5;
+    const int pairs = 2 * p.G;
+    const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
+    const int side = pair / p.G, g = pair % p.G, h = g % p.H;
+    const int n = p.n, k = p.k;
+    const float c1 = kLog2e / p.eps;
+    const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.Q : p.K);
+    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
+
+    Frag<IO, D> xc;
+    {
+        const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
+        load_tokens<D>(xc, X + ((size_t)g * p.n_stride + tok) * D, kg);
+    }
+    load_potentials(p, s_g, k, pair, h, chunk == 0, tid);
+    stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
+    __syncthreads();
+
+    float csg[kMaxGroups] = {0.f, 0.f, 0.f, 0.f};       // this lane's pivot of each group
+    for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
+        Frag<IO, D> xn = xc;
+        if (tile + kWaves < tile_end) {
+            const int tok = min((tile + kWaves) * kTileTokens + i, n - 1);
+            load_tokens<D>(xn, X + ((size_t)g * p.n_stride + tok) * D, kg);
+        }
+        float mc, w;
+        row_normaliser<IO, D>(mc, w, s_zstash, xc, s_g, p.groups, lane, kg, c1, tile * kTileTokens + i < n);
+        // W_it = exp2((C_it + g_t) c1 - L_i) with L_i = mc + log2(row sum): kept for the backward pass
+        if (p.rowlse && kg == 0 && tile * kTileTokens + i < n)
+            p.rowlse[((size_t)(k - 1) * pairs + pair) * n + tile * kTileTokens + i] = mc - __builtin_amdgcn_logf(w);
+#pragma unroll
+        for (int q = 0; q < kMaxGroups; ++q) {
+            if (q < p.groups) {
+                f32x16 acc[2];
+                group_weights<IO, D>(acc, q, mc, w, s_zstash, xc, s_g, lane, kg, c1);
+                float c[32];
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) c[16 * mb + j] = acc[mb][j];
+                csg[q] += reduce_scatter_tokens<32>(c, i);
+            }
+        }
+        xc = xn;
+    }
+    // lane (i, kg) holds pivot 32 (i >> 4) + 8 ((i & 15) >> 2) + 4 kg + (i & 3) of every group
+    const int mine = 32 * (i >> 4) + 8 * ((i & 15) >> 2) + 4 * kg + (i & 3);
+#pragma unroll
+    for (int q = 0; q < kMaxGroups; ++q) s_cs[wave][kGroup * q + mine] = csg[q];
+    __syncthreads();
+    for (int t = tid; t < p.r; t += kThreads) {
+        float tot = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) tot += s_cs[wv][t];
+        const unsigned long long word = (unsigned long long)__float2ll_rn(tot * p.fx_scale);
+        __hip_atomic_fetch_add(p.colacc + ((size_t)k * pairs + pair) * kRmax + t, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// expand: out_i = sum_t W_it Ymat_t over the tokens of one side (potentials g^{T-1} of that side).
+// Forward: side 0, Ymat = Y'', out = O.  Backward: side 1, Ymat_t = rho'_t dYraw_t, out = dV.
+// ---------------------------------------------------------------------------------------------
+template <typename IO, int D>
+__global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, const void* rows, const float* ymat, void* out_rows)
+{
+    constexpr int NB = D / 32;
+    constexpr bool kSplit = io_is_f32<IO>::value;
+    constexpr int kFragsPerGroup = 2 * 2 * NB * 64;
+    __shared__ float s_g[kRmax];
+    __shared__ __attribute__((aligned(16))) float s_y[64 * D];
+    extern __shared__ __attribute__((aligned(16))) char s_dyn[];    // pivot stash, then Y'' fragments (hi, lo) per group
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 31, kg = lane >> 5;
+    const int g = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks, h = g % p.H;
+    const int n = p.n;
+    const float c1 = kLog2e / p.eps;
+    const IO* X = reinterpret_cast<const IO*>(rows);
+    char* s_zstash = s_dyn;
+    bf16x8* yf = reinterpret_cast<bf16x8*>(s_dyn + (size_t)p.groups * StashBytes<IO, D, 2>::value);
+    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
+
+    load_potentials(p, s_g, p.T, side * p.G + g, h, false, tid);
+    stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
+    for (int q = 0; q < p.groups; ++q) {
+        for (int e = tid; e < kGroup * D; e += kThreads) s_y[e] = ymat[((size_t)g * kRmax + (size_t)kGroup * q) * D + e];
+        __syncthreads();
+        lay_out_fragments<D, 2>(s_y, yf + (size_t)(2 * q) * kFragsPerGroup, yf + (size_t)(2 * q + 1) * kFragsPerGroup, tid);
+        __syncthreads();
+    }
+
+    for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
+        const int tok = min(tile * kTileTokens + i, n - 1);
+        Frag<IO, D> xc;
+        load_tokens<D>(xc, X + ((size_t)g * p.n_stride + tok) * D, kg);
+        float mc, w;
+        row_normaliser<IO, D>(mc, w, s_zstash, xc, s_g, p.groups, lane, kg, c1, tile * kTileTokens + i < n);
+        f32x16 o[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) o[nb][j] = 0.f;
+        for (int q = 0; q < p.groups; ++q) {
+            f32x16 acc[2], part[NB];
+            group_weights<IO, D>(acc, q, mc, w, s_zstash, xc, s_g, lane, kg, c1);
+            contract_pivots<D, 2, kSplit>(part, acc, yf + (size_t)(2 * q) * kFragsPerGroup,
+                                          yf + (size_t)(2 * q + 1) * kFragsPerGroup, lane);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) o[nb][j] += part[nb][j];
+        }
+        IO* out = reinterpret_cast<IO*>(out_rows);
+        const int row0 = tile * kTileTokens + 4 * kg;
+        IO* const lane_base = out + ((size_t)g * p.n_stride + row0) * D;
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (row0 + 8 * (j >> 2) + (j & 3) < n)
+                store_out<NB>(lane_base + (8 * (j >> 2) + (j & 3)) * D, i, o[0][j], o[NB - 1][j]);
+    }
+}
+
+__global__ void lg_clear(unsigned long long* p, size_t count)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < count) p[idx] = 0ull;
+}
+
+}  // namespace
+}  // namespace lot

@@ -170,6 +170,16 @@ bool grouped_supports(const lot_shape& s);
 GroupedWorkspace carve_grouped(const lot_shape& s, int iters);
 int run_grouped(const Args& a);          // attention only; LOT_ERR_PATH outside its set
 
+// Backward for 64 < r <= 256 (pivots in groups of 64; uniform token masses).
+struct BwdGroupedWorkspace {
+    size_t colacc, ghist, rowlse, erow, u_part, yp, dyraw, ydv, rhop, s_part, dg_part, dcs, db_pair, db_glue, dz_part;
+    size_t total;      // status words at offset 0
+    int chunks;
+};
+bool bwd_grouped_supports(const lot_shape& s, int iters);
+BwdGroupedWorkspace carve_bwd_grouped(const lot_shape& s, int iters);
+int run_backward_grouped(const BwdArgs& a);   // LOT_ERR_PATH outside its set
+
 // Cross attention / non-uniform token masses.
 struct CrossWorkspace {
     size_t C1, C2, lse1, lse2, g1, g2, part_m, part_s, Y;   // plain path (status words at offset 0)

@@ -34,6 +34,12 @@ CASES = {
     # iterations divides by its column sums, so dbeta there shows the rounding of the Gram matrices and
     # of the incoming coupling gradient (found by a randomised sweep: 5e-2 before those took fp16 / hi+lo)
     "small_mass_pivot_bf16": S(W["swin_t_s1"], B=1, H=3, n=3000, d=32, r=48, eps=0.05, iters=8, seed=959762677),
+    # more than 64 pivots: groups of 64, the last one ragged (96 = 64 + 32, 130 = 2 x 64 + 2), several chunks
+    "grouped_f32_r96": S(W["tiny"], B=1, H=2, n=300, d=32, r=96, eps=0.1, iters=4, seed=77),
+    "grouped_f32_r128_d64": S(W["tiny"], B=1, H=2, n=500, d=64, r=128, eps=0.1, iters=3, seed=78),
+    "grouped_f32_one_iteration": S(W["tiny"], B=1, H=1, n=97, d=32, r=100, eps=0.1, iters=1, seed=79),
+    "grouped_bf16_r256": S(W["long_4k"], B=1, H=2, n=1500, r=256, iters=5, seed=80),
+    "grouped_bf16_r130_d32": S(W["swin_t_s1"], B=2, H=1, n=700, r=130, iters=6, seed=81),
 }
 
 
@@ -43,7 +49,9 @@ def _say(msg):
 
 def _paths_for(w):
     tiled = w.d in (32, 64) and w.r <= 64 and w.iters <= 32
-    return ["reference", "fused"] if tiled else ["reference"]
+    # pivots in groups of 64: what the largest kernel's tables leave room for in a workgroup's local memory
+    grouped = w.d in (32, 64) and 64 < w.r <= (256 if w.dtype == "bf16" or w.d == 32 else 128) and w.iters <= 10
+    return ["reference", "fused"] if tiled or grouped else ["reference"]
 
 
 @pytest.mark.parametrize("name,path_name", [(nm, pn) for nm in CASES for pn in _paths_for(CASES[nm])])
