@@ -88,13 +88,12 @@ def runtime_grid(torch, lot, synth, to_device):
                 return a.elapsed_time(b) / reps
 
             row = {"n": n, "r": r, "T": 5, "path": "fused" if r <= 64 else "grouped", "fwd_ms": timed(fwd, 50)}
-            # backward: the tiled kernels for r <= 64; beyond that the plain kernels (one per step, n x r
-            # intermediates in the workspace): slow, timed with few repetitions
+            # backward: the tiled kernels for r <= 64, beyond that the same tile code with the pivots in groups
             dO = torch.randn_like(dev["V"])
             wsb = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape, w.iters), dtype=torch.uint8, device="cuda")
-            row["bwd_path"] = "tiled" if r <= 64 else "plain"
+            row["bwd_path"] = "tiled" if r <= 64 else "grouped"
             row["bwd_ms"] = timed(lambda: lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"],
-                                                                w.eps, w.iters, dO, workspace=wsb), 20 if r <= 64 else 2)
+                                                                w.eps, w.iters, dO, workspace=wsb), 20)
             del wsb, dO
             rows.append(row)
             del dev, ws, out

@@ -88,12 +88,16 @@ BWD_CASES = {
     "bf16_d32": S(W["swin_t_s1"], B=2, H=3, n=400, seed=83),
     "reference_only": S(W["tiny"], B=1, H=2, n=90, d=16, r=80, iters=4, seed=84),
     "several_softmax_chunks": S(W["tiny"], B=1, H=2, n=2600, d=32, r=8, iters=3, seed=85),
+    # more than 64 pivots: the grouped tile kernels, here with the row stride of the [CLS] layout
+    "grouped_r128_bf16": S(W["long_4k"], B=1, H=2, n=700, r=128, iters=4, seed=87),
+    "grouped_r80_f32": S(W["tiny"], B=1, H=2, n=290, d=32, r=80, iters=4, seed=88),
 }
 
 
 def _bwd_paths(w):
     tiled = w.d in (32, 64) and w.r <= 64 and w.iters <= 32
-    return ["reference", "fused"] if tiled else ["reference"]
+    grouped = w.d in (32, 64) and 64 < w.r <= 128 and w.iters <= 10
+    return ["reference", "fused"] if tiled or grouped else ["reference"]
 
 
 @pytest.mark.parametrize("name,path_name", [(nm, pn) for nm in BWD_CASES for pn in _bwd_paths(BWD_CASES[nm])])
