@@ -162,8 +162,10 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * gradient buffers must not alias the inputs, the workspace or each other.  iters <= 65536.
  * Two execution paths, chosen like the forward ones (lot_path): REFERENCE = one plain kernel per
  * step with the n x r intermediates in the workspace, any shape; FUSED = tiled MFMA kernels that
- * keep nothing of size n x r (d_k = d_v in {32, 64}, r <= 64, iters <= 32).  AUTO prefers FUSED
- * (from 16 tokens up; shorter sequences go to the plain kernels, which are exact to fp32 rounding).
+ * keep nothing of size n x r (d_k = d_v in {32, 64}; r <= 64 with iters <= 32, or 64 < r <= 256 with the
+ * pivots in groups of 64, as far as the per-iteration tables fit a workgroup's local memory: bf16 I/O
+ * any such r with iters <= 15 at d = 64, fp32 I/O at d = 64 only r <= 128; LOT_ERR_PATH beyond).  AUTO prefers
+ * FUSED (from 16 tokens up; shorter sequences go to the plain kernels, which are exact to fp32 rounding).
  * Results are reproducible bit for bit on either path.  lot_workspace_status applies to this
  * workspace too (the FUSED path's forward sweep waits between workgroups when it runs as one kernel).
  * Testing aid: the FUSED path rebuilds each tile's row-normalised kernels for all iterations with ONE
@@ -189,7 +191,8 @@ int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K,
  * dK [B,H,n_k,d_k], dV [B,H,n_k,d_v] in io_dtype and dZ, dbeta in fp32 (summed over the batch).  The
  * masses are data (a padding mask), not differentiated; a key of mass zero receives exactly zero
  * gradient, a query of mass zero the gradient of its own output row.  Execution paths as for
- * lot_attention_bwd (FUSED: d_k = d_v in {32, 64}, r <= 64, iters <= 32; AUTO prefers it).
+ * lot_attention_bwd, except that with token masses or n_q != n_k the FUSED path ends at r <= 64
+ * (iters <= 32); AUTO prefers it.
  * Workspace: lot_cross_attention_bwd_workspace_bytes (covers both paths); contents on entry do not
  * matter; lot_workspace_status applies.  Reproducible bit for bit on either path.
  */
