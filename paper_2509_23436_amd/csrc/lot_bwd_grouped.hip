@@ -48,6 +48,7 @@ struct GbParams {
     float* s_part;                // [pairs][chunks][256]  s_t = sum_i dGamma_it Gamma_it
     float* dg_part;               // [T][pairs][chunks][256]  sum_i W^k_it e^k_i at k - 1
     float* dcs;                   // [T][pairs][256]  dc^k at k - 1
+    float* gmax;                  // [T][pairs]  max_t g^{k-1}_t at k - 1
     float* db_pair;               // [pairs][256]
     float* db_glue;               // [G][256]
     float* dz_part;               // [pairs][chunks][256][D]
@@ -383,7 +384,16 @@ __global__ void __launch_bounds__(kThreads, 2) gb_rec_pass(GbParams p, int k)
         }
         s_dc[t] = dc;
         if (chunk == 0) p.dcs[((size_t)(k - 1) * pairs + pair) * kRmax + t] = dc;
-        s_g[t] = p.f.ghist[((size_t)(k - 1) * pairs + pair) * kRmax + t];
+        const float gv = p.f.ghist[((size_t)(k - 1) * pairs + pair) * kRmax + t];
+        s_g[t] = gv;
+        // the largest potential of this iteration: the assembly scales its per-pivot factors by it
+        float gm = live ? gv : -INFINITY;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) gm = fmaxf(gm, __shfl_xor(gm, o, 64));
+        if (lane == 0) s_cs[0][wave] = gm;
+        __syncthreads();
+        if (chunk == 0 && tid == 0)
+            p.gmax[(size_t)(k - 1) * pairs + pair] = fmaxf(fmaxf(s_cs[0][0], s_cs[0][1]), fmaxf(s_cs[0][2], s_cs[0][3]));
     }
     stash_all_pivots<IO, D>(s_zstash, p.f.Z, h, p.f.r, groups, wave, lane);
     __syncthreads();
@@ -446,72 +456,95 @@ __global__ void __launch_bounds__(kThreads, 2) gb_rec_pass(GbParams p, int k)
 }
 
 // The gradient of the similarities for one tile and one group, summed over the iterations:
-// dacc_it = (a/eps) sum_k W^k_it (dP^k_it - e^k_i).  hist: [T][2][64] for this group, (g^{k-1} c1, dc^k) at k - 1.
+// dacc_it = (a/eps) sum_k W^k_it (dP^k_it - e^k_i).  One exponential per element, not one per iteration:
+// with m_i the row's largest scaled similarity in this group and h_k the largest scaled potential of
+// iteration k,  W^k_it = E_it P^k_t R^k_i,  E_it = exp2(C_it c1 - m_i),  P^k_t = exp2(g^{k-1}_t c1 - h_k),
+// R^k_i = exp2(m_i + h_k - L^k_i)  (E, P <= 1; R is capped at 2^60: beyond that the row's weights in this
+// group are below 2^-60 of the bound anyway), so that
+//   dacc_it = (a/eps) E_it [ sum_k R^k_i A^k_t - sum_k (R^k_i e^k_i) P^k_t + R^T_i B_t dGamma_it ],
+// A^k = P^k dc^k, B = n rho' P^T: two multiply-adds per element and iteration.
+// tab: [T][2][64] for this group, (P^k, A^k) at k - 1; bvec: B for this group; shifts: h_k at k - 1.
 template <typename IO, int D>
 __device__ __forceinline__ void similarity_gradient(f32x16 (&dacc)[2], const char* zst, const char* yhi, const char* ylo,
-                                                    const float* hist, const float* rho_lds,
+                                                    const float* tab, const float* bvec, const float* shifts,
                                                     const Frag<IO, D>& xc, const Frag<IO, D>& vc,
                                                     const float* lse, const float* erow, size_t per_k, int tok, bool valid,
-                                                    int T, int n, float c1, float scale_out, int lane, int kg)
+                                                    int T, float c1, float scale_out, int lane, int kg)
 {
     int skew = 0;
     asm volatile("" : "+v"(skew));
-    f32x16 sc[2];
+    f32x16 E[2];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) sc[mb][j] = 0.f;
+        for (int j = 0; j < 16; ++j) E[mb][j] = 0.f;
     {
         Frag<IO, D> zf[2];
         fetch_pivots<D, 2>(zf, zst, lane, skew);
-        similarity<D, 2>(sc, zf, xc);
+        similarity<D, 2>(E, zf, xc);
     }
+    float m0 = -INFINITY, m1 = -INFINITY;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; j += 2) {
+            m0 = fmaxf(m0, E[mb][j]);
+            m1 = fmaxf(m1, E[mb][j + 1]);
+        }
+    const float m = pair_max(fmaxf(m0, m1)) * c1;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) E[mb][j] = exp2_fast(fmaf(E[mb][j], c1, -m));
+    // row factors: R^k_i (0 for a row past the end) and R^k_i e^k_i
+    auto row_factors = [&](int k, float& R, float& S) {
+        const float L = valid ? lse[(size_t)(k - 1) * per_k + tok] : INFINITY;
+        R = exp2_fast(fminf(m + shifts[k - 1] - L, 60.f));
+        S = R * erow[(size_t)(k - 1) * per_k + tok];
+    };
     // last iteration: dP^T = n rho' dGamma + dc^T
     {
-        f32x16 dp[2], rho[2], dc[2], pot[2];
-        coupling_gradient<IO, D>(dp, yhi, ylo, vc, lane);
-        load_pivot_vector<2>(rho, rho_lds + skew, kg);
-        load_pivot_vector<2>(dc, hist + ((T - 1) * 2 + 1) * kGroup + skew, kg);
-        load_pivot_vector<2>(pot, hist + ((T - 1) * 2 + 0) * kGroup + skew, kg);
-        const float L = valid ? lse[(size_t)(T - 1) * per_k + tok] : INFINITY;
-        const float e = erow[(size_t)(T - 1) * per_k + tok];
+        f32x16 dgam[2], bv[2], P[2], A[2];
+        coupling_gradient<IO, D>(dgam, yhi, ylo, vc, lane);
+        load_pivot_vector<2>(bv, bvec + skew, kg);
+        load_pivot_vector<2>(P, tab + ((T - 1) * 2 + 0) * kGroup + skew, kg);
+        load_pivot_vector<2>(A, tab + ((T - 1) * 2 + 1) * kGroup + skew, kg);
+        float R, S;
+        row_factors(T, R, S);
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                sc[mb][j] *= c1;
-                const float w = exp2_fast(sc[mb][j] + pot[mb][j] - L);
-                dacc[mb][j] = w * (fmaf(dp[mb][j] * (float)n, rho[mb][j], dc[mb][j]) - e);
-            }
+            for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(R, fmaf(bv[mb][j], dgam[mb][j], A[mb][j]), -S * P[mb][j]);
     }
     for (int k = T - 1; k >= 1; --k) {
-        f32x16 dc[2], pot[2];
-        load_pivot_vector<2>(dc, hist + ((k - 1) * 2 + 1) * kGroup + skew, kg);
-        load_pivot_vector<2>(pot, hist + ((k - 1) * 2 + 0) * kGroup + skew, kg);
-        const float L = valid ? lse[(size_t)(k - 1) * per_k + tok] : INFINITY;
-        const float e = erow[(size_t)(k - 1) * per_k + tok];
+        f32x16 P[2], A[2];
+        load_pivot_vector<2>(P, tab + ((k - 1) * 2 + 0) * kGroup + skew, kg);
+        load_pivot_vector<2>(A, tab + ((k - 1) * 2 + 1) * kGroup + skew, kg);
+        float R, S;
+        row_factors(k, R, S);
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const float w = exp2_fast(sc[mb][j] + pot[mb][j] - L);
-                dacc[mb][j] = fmaf(w, dc[mb][j] - e, dacc[mb][j]);
-            }
+            for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(R, A[mb][j], fmaf(-S, P[mb][j], dacc[mb][j]));
     }
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) dacc[mb][j] *= scale_out;
+        for (int j = 0; j < 16; ++j) dacc[mb][j] *= E[mb][j] * scale_out;
 }
 
-// (g^{k-1} c1, dc^k) of the pivots [t0, t0 + count) for all k into LDS, [T][2][count]
-__device__ __forceinline__ void load_history(float* hist, const GbParams& p, int pair, int t0, int count, float c1, int tid)
+// Per-pivot tables of the assembly for the pivots [t0, t0 + 64): (P^k, A^k) for all k into tab ([T][2][64])
+// and B into bvec.
+__device__ __forceinline__ void load_tables(float* tab, float* bvec, const GbParams& p, int pair, int t0, float c1, int tid)
 {
-    const int pairs = 2 * p.f.G;
-    for (int e = tid; e < p.f.T * count; e += kThreads) {
-        const int k = e / count + 1, t = e % count;
-        hist[((k - 1) * 2 + 0) * count + t] = p.f.ghist[((size_t)(k - 1) * pairs + pair) * kRmax + t0 + t] * c1;   // padding: -1e30 c1
-        hist[((k - 1) * 2 + 1) * count + t] = p.dcs[((size_t)(k - 1) * pairs + pair) * kRmax + t0 + t];
+    const int pairs = 2 * p.f.G, T = p.f.T;
+    for (int e = tid; e < T * kGroup; e += kThreads) {
+        const int k = e / kGroup + 1, t = e % kGroup;
+        const float h = p.gmax[(size_t)(k - 1) * pairs + pair] * c1;
+        const float P = exp2_fast(p.f.ghist[((size_t)(k - 1) * pairs + pair) * kRmax + t0 + t] * c1 - h);   // padding: 0
+        tab[((k - 1) * 2 + 0) * kGroup + t] = P;
+        tab[((k - 1) * 2 + 1) * kGroup + t] = P * p.dcs[((size_t)(k - 1) * pairs + pair) * kRmax + t0 + t];
+        if (k == T) bvec[t] = P * (float)p.f.n * p.rhop[(size_t)pair * kRmax + t0 + t];
     }
 }
 
@@ -526,8 +559,8 @@ __global__ void __launch_bounds__(kThreads, 1) gb_assemble_x(GbParams p, int sta
     constexpr bool kSplit = io_is_f32<IO>::value;
     constexpr int kFragsPerGroup = 2 * 2 * NB * 64;
     constexpr int kParts = kSplit ? 2 : 1;
-    __shared__ float s_rho[kRmax];
-    // staging area (a [64][D] matrix during set-up, then the history [T][groups][2][64]) | pivot stash |
+    __shared__ float s_bvec[kRmax], s_shift[64];
+    // staging area (a [64][D] matrix during set-up, then the tables [groups][T][2][64]) | pivot stash |
     // matrix stash hi | (bf16 I/O) lo | Z as B fragments hi | (fp32 I/O) lo
     extern __shared__ __attribute__((aligned(16))) char s_dyn[];
 
@@ -553,7 +586,7 @@ __global__ void __launch_bounds__(kThreads, 1) gb_assemble_x(GbParams p, int sta
     char* s_ylo = s_yhi + (size_t)groups * kStash;
     bf16x8* s_zf = reinterpret_cast<bf16x8*>(s_yhi + (size_t)groups * kStash * (kSplit ? 1 : 2));
 
-    for (int t = tid; t < kRmax; t += kThreads) s_rho[t] = p.rhop[(size_t)pair * kRmax + t];
+    if (tid < T) s_shift[tid] = p.gmax[(size_t)tid * pairs + pair] * c1;
     stash_all_pivots<IO, D>(s_zstash, p.f.Z, h, r, groups, wave, lane);
     for (int q = 0; q < groups; ++q) {
         // Z rows as B fragments (the values the forward pass multiplied with: rounded to bf16 for bf16 I/O)
@@ -574,7 +607,7 @@ __global__ void __launch_bounds__(kThreads, 1) gb_assemble_x(GbParams p, int sta
     }
     __syncthreads();
     for (int q = 0; q < groups; ++q)
-        load_history(s_hist + (size_t)q * T * 2 * kGroup, p, pair, kGroup * q, kGroup, c1, tid);
+        load_tables(s_hist + (size_t)q * T * 2 * kGroup, s_bvec + kGroup * q, p, pair, kGroup * q, c1, tid);
     __syncthreads();
 
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
@@ -594,8 +627,8 @@ __global__ void __launch_bounds__(kThreads, 1) gb_assemble_x(GbParams p, int sta
         for (int q = 0; q < groups; ++q) {
             f32x16 dacc[2], part[NB];
             similarity_gradient<IO, D>(dacc, s_zstash + (size_t)q * kStash, s_yhi + (size_t)q * kStash,
-                                       s_ylo + (size_t)q * kStash, s_hist + (size_t)q * T * 2 * kGroup, s_rho + kGroup * q,
-                                       xc, vc, lse, erow, per_k, tok, valid, T, n, c1, scale_out, lane, kg);
+                                       s_ylo + (size_t)q * kStash, s_hist + (size_t)q * T * 2 * kGroup, s_bvec + kGroup * q,
+                                       s_shift, xc, vc, lse, erow, per_k, tok, valid, T, c1, scale_out, lane, kg);
             const bf16x8* hi = s_zf + (size_t)(kParts * q) * kFragsPerGroup;
             contract_pivots<D, 2, kSplit>(part, dacc, hi, kSplit ? hi + kFragsPerGroup : hi, lane);
 #pragma unroll
@@ -623,7 +656,7 @@ __global__ void __launch_bounds__(kThreads, 2) gb_assemble_z(GbParams p)
     constexpr int kStash = StashBytes<IO, D, 2>::value;
     constexpr bool kSplit = io_is_f32<IO>::value;
     constexpr int kParts = kSplit ? 2 : 1;
-    __shared__ float s_rho[kGroup];
+    __shared__ float s_bvec[kGroup], s_shift[64];
     __shared__ __attribute__((aligned(16))) float s_y[64 * D];
     __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 64 * kTrStride];
     __shared__ __attribute__((aligned(16))) char s_zstash[kStash];
@@ -650,8 +683,8 @@ __global__ void __launch_bounds__(kThreads, 2) gb_assemble_z(GbParams p)
     uint16_t* tr_hi = s_tr + (wave * kParts + 0) * 64 * kTrStride;
     uint16_t* tr_lo = s_tr + (wave * kParts + kParts - 1) * 64 * kTrStride;
 
-    if (tid < kGroup) s_rho[tid] = p.rhop[(size_t)pair * kRmax + kGroup * grp + tid];
-    load_history(s_hist, p, pair, kGroup * grp, kGroup, c1, tid);
+    if (tid < T) s_shift[tid] = p.gmax[(size_t)tid * pairs + pair] * c1;
+    load_tables(s_hist, s_bvec, p, pair, kGroup * grp, c1, tid);
     if (wave == 0) stash_group_pivots<IO, D>(s_zstash, p.f.Z, h, p.f.r, grp, lane);
     stash_matrix_rows<IO, D>(s_yhi, s_ylo, s_y, ymat, yscale, tid, wave, lane);
     __syncthreads();   // s_y is reused below for the dZ partial
@@ -673,8 +706,8 @@ __global__ void __launch_bounds__(kThreads, 2) gb_assemble_z(GbParams p)
         load_tokens<D>(xc, X + ((size_t)g * p.f.n_stride + tok) * D, kg);
         load_tokens<D>(vc, vals + ((size_t)g * p.f.n_stride + tok) * D, kg);
         f32x16 dacc[2];
-        similarity_gradient<IO, D>(dacc, s_zstash, s_yhi, s_ylo, s_hist, s_rho, xc, vc, lse, erow, per_k, tok, valid,
-                                   T, n, c1, scale_out, lane, kg);
+        similarity_gradient<IO, D>(dacc, s_zstash, s_yhi, s_ylo, s_hist, s_bvec, s_shift, xc, vc, lse, erow, per_k, tok, valid,
+                                   T, c1, scale_out, lane, kg);
         bf16x8 vh[2][NB], vl[2][NB];
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -757,7 +790,7 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
     const size_t stage = assemble_x_stage_bytes(D, groups, T);
     const size_t ax_bytes = assemble_x_lds_bytes(kSplit, D, groups, T);
     const size_t az_bytes = (size_t)T * 2 * kGroup * sizeof(float);
-    if (ax_bytes > kLdsBudget || az_bytes > 32 * 1024) return LOT_ERR_PATH;
+    if (ax_bytes > kLdsBudget || T > 64) return LOT_ERR_PATH;
     // more than 64 KB of LDS per workgroup has to be asked for explicitly
     LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(lg_pass<IO, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)stash));
     LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(lg_expand<IO, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(stash + frag_bytes)));
@@ -789,7 +822,7 @@ bool bwd_grouped_supports(const lot_shape& s, int iters)
     if (!grouped_supports(s) || iters < 1) return false;
     const int groups = (s.r + kGroup - 1) / kGroup;
     return assemble_x_lds_bytes(s.io_dtype != LOT_BF16, s.d_k, groups, iters) <= kLdsBudget &&
-           (size_t)iters * 2 * kGroup * sizeof(float) <= 32 * 1024;
+           iters <= 64;
 }
 
 BwdGroupedWorkspace carve_bwd_grouped(const lot_shape& s, int iters)
@@ -814,6 +847,7 @@ BwdGroupedWorkspace carve_bwd_grouped(const lot_shape& s, int iters)
     w.s_part = take(pairs * chunks * kRmax * 4);
     w.dg_part = take(T * pairs * chunks * kRmax * 4);
     w.dcs = take(T * pairs * kRmax * 4);
+    w.gmax = take(T * pairs * 4);
     w.db_pair = take(pairs * kRmax * 4);
     w.db_glue = take(G * kRmax * 4);
     w.dz_part = take(pairs * chunks * kRmax * D * 4);
@@ -843,6 +877,7 @@ int run_backward_grouped(const BwdArgs& a)
     p.s_part = (float*)(a.ws + L.s_part);
     p.dg_part = (float*)(a.ws + L.dg_part);
     p.dcs = (float*)(a.ws + L.dcs);
+    p.gmax = (float*)(a.ws + L.gmax);
     p.db_pair = (float*)(a.ws + L.db_pair);
     p.db_glue = (float*)(a.ws + L.db_glue);
     p.dz_part = (float*)(a.ws + L.dz_part);
