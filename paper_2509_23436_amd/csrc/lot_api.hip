@@ -44,6 +44,12 @@ float reshift_limit()
     return std::ldexp(1.0f, bits);
 }
 
+bool assemble_by_iteration()
+{
+    const char* e = std::getenv("LOT_BWD_ASSEMBLE_BY_ITERATION");
+    return e && std::atoi(e) != 0;
+}
+
 static int validate_shape(const lot_shape* s)
 {
     if (!s) return LOT_ERR_NULL;

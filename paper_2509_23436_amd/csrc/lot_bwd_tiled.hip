@@ -80,6 +80,7 @@ struct BtParams {
     float* db_pair;               // [pairs][64]
     float* db_glue;               // [G][64]
     float* dz_part;               // [pairs][chunks][64][D]
+    unsigned* redo;               // [pairs][chunks]  workgroups whose tiles the assemble kernel redoes iteration by iteration
     int G, H, B, r, chunks, tiles_per_wg, k, T;
     // per side (0 = queries, dO, dQ; 1 = keys, values, dK, dV):
     int n_side[2];                // tokens per problem
@@ -748,8 +749,10 @@ __global__ void bt_recursion(BtParams p, int R)
 // assemble: dC tile over all iterations, then dQ / dK rows and the workgroup's share of dZ
 // ---------------------------------------------------------------------------------------------
 template <typename IO, int D, int RB>
-__global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
+__global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap, const unsigned* redo)
 {
+    // after the all-at-once kernel: only the workgroups that it marked
+    if (redo && redo[blockIdx.x] == 0) return;
     constexpr int NB = D / 32;
     constexpr bool kSplit = io_is_f32<IO>::value;
     extern __shared__ __attribute__((aligned(16))) char s_dyn[];   // [Tcap][2][64] floats: g^{k-1} c1, dc^k
@@ -983,6 +986,290 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap)
 }
 
 // ---------------------------------------------------------------------------------------------
+// assemble, all iterations of a tile at once (T <= 16): the per-iteration work of the kernel above as
+// two small matrix products.  With the rows shifted once, by the row maxima of the last iteration,
+//   e^k_it = E_it P^k_t,   E_it = exp2((C_it + g^{T-1}_t) c1 - max_i),   P^k_t = exp2((g^{k-1}_t - g^{T-1}_t) c1 - h_k)
+// (h_k = the largest such difference, so P <= 1; P^T = 1), the row sums and the row products with dP^k are
+//   ssum^k_i = sum_t Tab[P^k][t] E_it,   sdot^k_i = sum_t Tab[P^k dc^k][t] E_it          (first product: Tab E)
+// and, with w^k_i = 1 / ssum^k_i and the row factors R^k_i = ms w^k_i, S^k_i = R^k_i w^k_i sdot^k_i,
+//   dC_it = (a/eps) E_it [ sum_k R^k_i Tab[P^k dc^k][t] - S^k_i Tab[P^k][t]  +  R^T_i n rho_t dGamma_it ]
+// (second product: Tab^T applied to the row factors).  Both products run on the fp32 matrix cores
+// (32 x 32 x 2 per instruction): one exponential per element instead of one per iteration, and the
+// vector ALU is left with a handful of operations per element.  The row sums are checked against the
+// same range as above; a workgroup that finds one outside marks itself in `redo`, and the kernel above
+// then redoes that workgroup's tiles iteration by iteration.
+// Table rows: 2 (k - 1) = P^k dc^k, 2 (k - 1) + 1 = P^k  (k < T);  2 (T - 1) = dc^T, 2 (T - 1) + 1 = 1.
+// ---------------------------------------------------------------------------------------------
+constexpr int kAllAtOnceIters = 16;
+constexpr int kTabStride = 65;     // floats per table row (64 pivots + 1: rows fall into different banks)
+
+template <typename IO, int D, int RB>
+__global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsigned* redo)
+{
+    constexpr int NB = D / 32;
+    constexpr bool kSplit = io_is_f32<IO>::value;
+    __shared__ float s_brho[64], s_pot[64], s_h[kAllAtOnceIters];
+    __shared__ int s_redo;
+    __shared__ __attribute__((aligned(16))) float s_tab[32 * kTabStride];
+    __shared__ __attribute__((aligned(16))) float s_y[64 * D];
+    constexpr int kParts = kSplit ? 2 : 1;     // bf16 hi only, or hi and lo
+    __shared__ __attribute__((aligned(16))) bf16x8 s_zf[2][2 * RB * NB * 64];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 64 * kTrStride];
+    __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
+    __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
+    static_assert(kSplit || sizeof(s_zf[1]) >= (size_t)StashBytes<IO, D, RB>::value, "the lo stash takes the place of s_zf[1]");
+    char* const s_ystash_lo = reinterpret_cast<char*>(s_zf[1]);   // bf16 I/O only (s_zf[1] is then unused)
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 31, kg = lane >> 5;
+    const int pairs = 2 * p.G;
+    const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
+    const int side = pair / p.G, g = pair % p.G, h = g % p.H;
+    const int n = p.n_side[side], stride = p.stride_side[side], r = p.r, T = p.T;
+    const float c1 = kLog2e / p.eps;
+    const IO* X = rows_of<IO>(p, side);
+    const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
+    const float* ymat = (side == 0 ? p.yp : p.dyraw) + (size_t)g * 64 * D;
+    const float yscale = side == 0 ? (float)n : 1.f;
+    uint16_t* tr_hi = s_tr + (wave * kParts + 0) * 64 * kTrStride;
+    uint16_t* tr_lo = s_tr + (wave * kParts + kParts - 1) * 64 * kTrStride;
+    const float* g_last = p.ghist + ((size_t)(T - 1) * pairs + pair) * 64;
+
+    if (tid == 0) s_redo = 0;
+    if (tid < 64) {
+        s_brho[tid] = (float)n * p.rhop[(size_t)pair * 64 + tid];
+        s_pot[tid] = g_last[tid] * c1;                       // padding: -1e30 c1
+    }
+    // h_k: one wavefront per iteration k < T
+    for (int k = 1 + wave; k < T; k += kWaves) {
+        float dmax = lane < r ? (p.ghist[((size_t)(k - 1) * pairs + pair) * 64 + lane] - g_last[lane]) * c1 : -INFINITY;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) dmax = fmaxf(dmax, __shfl_xor(dmax, o, 64));
+        if (lane == 0) s_h[k - 1] = dmax;
+    }
+    if (wave == 0) {
+        Frag<IO, D> z0[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) {
+            const int t = 32 * mb + i;
+            load_pivots<D>(z0[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
+        }
+        stash_pivots<D, RB>(s_zstash, z0, lane);
+    }
+    // Z rows as B fragments (the values the forward pass multiplied with: rounded to bf16 for bf16 I/O)
+    for (int e = tid; e < 64 * D; e += kThreads) {
+        const int t = e / D;
+        float z = t < r ? p.Z[((size_t)h * r + t) * D + e % D] : 0.f;
+        if (!kSplit) z = (float)(__bf16)z;
+        s_y[e] = z;
+    }
+    __syncthreads();
+    for (int e = tid; e < 32 * 64; e += kThreads) {
+        const int row = e / 64, t = e % 64, k = row / 2 + 1;
+        float v = 0.f;
+        if (k <= T && t < r) {
+            const float dc = p.dcs[((size_t)k * pairs + pair) * 64 + t];
+            if (k == T) {
+                v = (row & 1) ? 1.f : dc;
+            } else {
+                const float P = exp2_fast((p.ghist[((size_t)(k - 1) * pairs + pair) * 64 + t] - g_last[t]) * c1 - s_h[k - 1]);
+                v = (row & 1) ? P : P * dc;
+            }
+        }
+        s_tab[row * kTabStride + t] = v;
+    }
+    lay_out_fragments<D, RB>(s_y, s_zf[0], s_zf[1], tid);
+    __syncthreads();
+    for (int e = tid; e < 64 * D; e += kThreads) s_y[e] = ymat[e] * yscale;
+    __syncthreads();
+    if (wave == 0) {
+        Frag<IO, D> y0[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) load_pivots_lds<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
+        stash_pivots<D, RB>(s_ystash, y0, lane);
+        if (!kSplit) {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb) load_pivots_lds_lo<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
+            stash_pivots<D, RB>(s_ystash_lo, y0, lane);
+        }
+    }
+    __syncthreads();   // s_y is reused below for the dZ partial
+
+    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
+    f32x16 dZacc[RB][NB];
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) dZacc[mb][nb][j] = 0.f;
+    const float scale_out = 1.f / ((float)n * p.eps);   // a / eps
+    bool all_safe = true;
+
+    for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
+        const int tok = min(tile * kTileTokens + i, n - 1);
+        const bool valid = tile * kTileTokens + i < n;
+        Frag<IO, D> xc, vc;
+        load_tokens<D>(xc, X + ((size_t)g * stride + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * stride + tok) * D, kg);
+        const float m = token_weight(p, side, g, tok);
+        const float mdc = side == 0 ? m : 1.f, ms_last = side == 0 ? 1.f : m;
+        int skew = 0;
+        asm volatile("" : "+v"(skew));
+        // E: the last iteration's exponentials, rows shifted by their maxima
+        f32x16 E[RB];
+        load_pivot_vector<RB>(E, s_pot + skew, kg);
+        {
+            f32x16 sc[RB];
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) sc[mb][j] = 0.f;
+            Frag<IO, D> zf[RB];
+            fetch_pivots<D, RB>(zf, s_zstash, lane, skew);
+            similarity<D, RB>(sc, zf, xc);
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) E[mb][j] = fmaf(sc[mb][j], c1, E[mb][j]);
+        }
+        {
+            float m0 = -INFINITY, m1 = -INFINITY;
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; j += 2) {
+                    m0 = fmaxf(m0, E[mb][j]);
+                    m1 = fmaxf(m1, E[mb][j + 1]);
+                }
+            const float mx = pair_max(fmaxf(m0, m1));
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) E[mb][j] = exp2_fast(E[mb][j] - mx);
+        }
+        // the incoming gradient of the coupling times n rho_t, and its row product with E
+        f32x16 dgam[RB];
+        float qd;
+        {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) dgam[mb][j] = 0.f;
+            Frag<IO, D> yfrag[RB];
+            fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
+            similarity<D, RB>(dgam, yfrag, vc);
+            if (!kSplit) {
+                fetch_pivots<D, RB>(yfrag, s_ystash_lo, lane, skew);
+                similarity<D, RB>(dgam, yfrag, vc);
+            }
+            f32x16 br[RB];
+            load_pivot_vector<RB>(br, s_brho + skew, kg);
+            float q0 = 0.f, q1 = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; j += 2) {
+                    dgam[mb][j] *= br[mb][j];
+                    dgam[mb][j + 1] *= br[mb][j + 1];
+                    q0 = fmaf(E[mb][j], dgam[mb][j], q0);
+                    q1 = fmaf(E[mb][j + 1], dgam[mb][j + 1], q1);
+                }
+            qd = pair_sum(q0 + q1);
+        }
+        // first product: rows of the table against E (32 x 32 x 2 per instruction: this lane's pivot of the step)
+        f32x16 rows;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) rows[j] = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const float a = s_tab[i * kTabStride + pivot_of(mb, j, kg) + skew];
+                rows = __builtin_amdgcn_mfma_f32_32x32x2f32(a, E[mb][j], rows, 0, 0, 0);
+            }
+        // row factors, then the second product: the table transposed against them
+        f32x16 br2[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) br2[mb][j] = 0.f;
+        float r_last = 0.f;
+        bool safe = true;
+#pragma unroll
+        for (int s = 0; s < kAllAtOnceIters; ++s) {
+            if (s < T) {
+                // rows 2 s (sdot) and 2 s + 1 (ssum) sit in registers jr, jr + 1 of the lanes with kg == (s / 2) % 2
+                constexpr int kDummy = 0; (void)kDummy;
+                const int jr = 4 * (s / 4) + 2 * (s % 2);
+                float lo, hi;
+                both_halves(rows[jr], lo, hi);
+                float sdot = (s / 2) % 2 == 0 ? lo : hi;
+                both_halves(rows[jr + 1], lo, hi);
+                const float ssum = (s / 2) % 2 == 0 ? lo : hi;
+                safe = safe && ssum >= p.sum_lo && ssum <= p.sum_hi;      // false for NaN too
+                const float w = valid ? rcp_fast(ssum) : 0.f;
+                float R, ms;
+                if (s == T - 1) {
+                    sdot = fmaf(sdot, mdc, qd);
+                    ms = ms_last;
+                    r_last = w * ms;
+                    R = r_last * mdc;
+                } else {
+                    ms = m;
+                    R = w * ms;
+                }
+                const float S = (sdot * (w * ms)) * w;
+                const float b = kg ? -S : R;
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb) {
+                    const float a = s_tab[(2 * s + kg) * kTabStride + 32 * mb + i + skew];
+                    br2[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, br2[mb], 0, 0, 0);
+                }
+            }
+        }
+        all_safe = all_safe && __all(safe);
+        f32x16 dacc[RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) dacc[mb][j] = E[mb][j] * scale_out * fmaf(r_last, dgam[mb][j], br2[mb][j]);
+
+        // dQ (or dK) rows = dC Z
+        {
+            f32x16 o[NB];
+            contract_pivots<D, RB, kSplit>(o, dacc, s_zf[0], s_zf[1], lane);
+            IO* out = reinterpret_cast<IO*>(side == 0 ? p.dQ : p.dK);
+            const int row0 = tile * kTileTokens + 4 * kg;
+            IO* const lane_base = out + ((size_t)g * stride + row0) * D;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (row0 + 8 * (j >> 2) + (j & 3) < n)
+                    store_out<NB>(lane_base + (8 * (j >> 2) + (j & 3)) * D, i, o[0][j], o[NB - 1][j]);
+        }
+        // dZ += dC^T X
+        bf16x8 vh[2][NB], vl[2][NB];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
+            const int left = max(1, min(8, n - t0));
+            load_values<D>(vh[s], vl[s], X, (size_t)g * stride + min(t0, n - 1), left, i);
+        }
+        transpose_tile<RB, kSplit>(dacc, tr_hi, tr_lo, i, kg);
+        contract_tokens<D, RB, kSplit>(dZacc, tr_hi, tr_lo, vh, vl, i, kg);
+        transpose_done();
+    }
+    if (!all_safe) s_redo = 1;         // (every writer writes the same value)
+    __syncthreads();
+    sum_over_waves<D, RB>(dZacc, s_y, wave, i, kg);
+    float* zp = p.dz_part + ((size_t)pair * p.chunks + chunk) * 64 * D;
+    for (int e = tid; e < 32 * RB * D; e += kThreads) zp[e] = s_y[e];
+    if (tid == 0) redo[blockIdx.x] = (unsigned)s_redo;
+}
+
+// ---------------------------------------------------------------------------------------------
 // final: dZ[h][t][c] and dbeta[h][t], summed over chunks, sides and the batch in index order
 // ---------------------------------------------------------------------------------------------
 __global__ void bt_final(BtParams p, int D)
@@ -1076,7 +1363,12 @@ int launch_all(const BwdArgs& a, BtParams p)
     }
     bt_recursion<<<pairs, 256, 0, st>>>(p, R);
     const size_t dyn = (size_t)T * 2 * 64 * sizeof(float);
-    bt_assemble<IO, D, RB><<<grid, kThreads, dyn, st>>>(p, T);
+    if (T <= kAllAtOnceIters && !assemble_by_iteration()) {
+        bt_assemble_mf<IO, D, RB><<<grid, kThreads, 0, st>>>(p, p.redo);
+        bt_assemble<IO, D, RB><<<grid, kThreads, dyn, st>>>(p, T, p.redo);
+    } else {
+        bt_assemble<IO, D, RB><<<grid, kThreads, dyn, st>>>(p, T, nullptr);
+    }
     bt_final<<<(unsigned)((s.H * s.r * (D + 1) + 255) / 256), 256, 0, st>>>(p, D);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
@@ -1114,6 +1406,7 @@ BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters)
     w.db_pair = take(pairs * 64 * 4);
     w.db_glue = take(G * 64 * 4);
     w.dz_part = take(pairs * chunks * 64 * D * 4);
+    w.redo = take(pairs * chunks * 4);
     w.total = off;
     return w;
 }
@@ -1144,6 +1437,7 @@ int run_backward_tiled(const BwdArgs& a)
     p.db_pair = (float*)(a.ws + L.db_pair);
     p.db_glue = (float*)(a.ws + L.db_glue);
     p.dz_part = (float*)(a.ws + L.dz_part);
+    p.redo = (unsigned*)(a.ws + L.redo);
     p.G = s.B * s.H; p.H = s.H; p.B = s.B; p.r = s.r; p.chunks = L.chunks; p.tiles_per_wg = tiles_per_wg_for(s); p.T = a.iters;
     // s.n is the longer side (cross attention); a side with fewer tiles leaves its last workgroups idle
     p.n_side[0] = a.n_q > 0 ? a.n_q : s.n;

@@ -153,7 +153,7 @@ struct BwdArgs {
 
 // Workspace of the backward pass, tiled path.
 struct BwdTiledWorkspace {
-    size_t colacc, ghist, gram_part, gram_full, u_part, yp, dyraw, sn_part, dcs, rhop, db_pair, db_glue, dz_part;
+    size_t colacc, ghist, gram_part, gram_full, u_part, yp, dyraw, sn_part, dcs, rhop, db_pair, db_glue, dz_part, redo;
     size_t total;
     int chunks;
 };
@@ -231,6 +231,13 @@ unsigned long long next_nonce();
 // LOT_RESHIFT_BITS (0..40), read at each call, lowers the limit to 2^bits: a testing aid that makes
 // the re-shifting branch run on ordinary inputs (0: practically every iteration takes it).
 float reshift_limit();
+
+// The tiled backward path assembles the similarity gradients of all iterations of a tile at once (two
+// small matrix products) when there are at most 16 iterations, and redoes, iteration by iteration, only
+// the workgroups in which a row sum left the range above.  The environment variable
+// LOT_BWD_ASSEMBLE_BY_ITERATION (non-zero), read at each call, sends every workgroup through the
+// iteration-by-iteration kernel: a testing aid that keeps that kernel exercised on ordinary inputs.
+bool assemble_by_iteration();
 
 // Poll budget of a bounded wait between cooperating workgroups (2^21 polls by default: seconds).  The
 // environment variable LOT_SPIN_LIMIT (read at each call) replaces it: a testing aid -- with 0 every

@@ -30,6 +30,8 @@ CASES = {
     "bf16_d32_r32": S(W["swin_t_s1"], B=2, H=3, n=700, iters=10, seed=74),
     "eps_small_f32": S(W["tiny"], B=1, H=2, n=300, d=32, r=16, eps=0.05, iters=10, seed=75),
     "one_iteration": S(W["tiny"], B=1, H=2, n=100, d=32, r=8, iters=1, seed=76),
+    "many_iterations_f32": S(W["tiny"], B=1, H=2, n=150, d=32, r=24, iters=20, seed=82),
+    "sixteen_iterations_bf16": S(W["swin_t_s1"], B=1, H=2, n=333, iters=16, seed=83),
     # a pivot of very small mass (beta = 5e-4, a fortieth of the uniform mass): the recursion through the
     # iterations divides by its column sums, so dbeta there shows the rounding of the Gram matrices and
     # of the incoming coupling gradient (found by a randomised sweep: 5e-2 before those took fp16 / hi+lo)
@@ -123,6 +125,34 @@ def test_reshifted_rows_give_the_same_gradients(bits, monkeypatch):
     for name in ("eps_small_f32", "bf16_d64_r64"):
         w = CASES[name]
         _say("case %s, re-shift range 2^+-%s" % (name, bits))
+        x = synth.make_inputs(w)
+        dO = np.random.default_rng(w.seed + 17).standard_normal(x["V"].shape).astype(np.float32)
+        if w.dtype == "bf16":
+            dO = synth.round_to_bf16(dO)
+        refs, _ = lot_oracle_bwd.attention_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, dO)
+        dev = to_device(dict(x, dO=dO), w.dtype)
+        got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, dev["dO"],
+                                    path=lot.PATH_FUSED)
+        torch.cuda.synchronize()
+        tol = 2e-2 if w.dtype == "bf16" else 1e-4
+        for nm, g, ref in zip(("dQ", "dK", "dV", "dZ", "dbeta"), got, refs):
+            err = rel_max_err(to_host_f64(g), ref)
+            _say("  %-5s max-norm rel err %.3e (bar %.0e)" % (nm, err, tol))
+            assert err <= tol, nm
+
+
+def test_assembly_iteration_by_iteration_meets_the_same_bar(monkeypatch):
+    """Up to 16 iterations the tiled path assembles all iterations of a tile at once and sends only the
+    workgroups whose row sums leave the safe range through the iteration-by-iteration kernel; forced from
+    the host, that kernel handles every workgroup and must meet the oracle's bar too.  (More than 16
+    iterations always take it: case `many_iterations_f32`.)"""
+    import torch
+    from oracle import lot_oracle_bwd
+    from paper_2509_23436_amd import lot
+    monkeypatch.setenv("LOT_BWD_ASSEMBLE_BY_ITERATION", "1")
+    for name in ("ragged_f32", "bf16_d32_r32"):
+        w = CASES[name]
+        _say("case %s, assembled iteration by iteration" % name)
         x = synth.make_inputs(w)
         dO = np.random.default_rng(w.seed + 17).standard_normal(x["V"].shape).astype(np.float32)
         if w.dtype == "bf16":
