@@ -99,24 +99,6 @@ __device__ __forceinline__ void stash_matrix_rows(char* hi, char* lo, float* s_y
     }
 }
 
-// acc <- W_it = exp2((C_it + g_t) c1 - L_i) for the 64 pivots of one group (zst: its stash, pot: its g).
-// A row past the end carries L = +inf: weights exactly 0.
-template <typename IO, int D>
-__device__ __forceinline__ void weights_from_lse(f32x16 (&acc)[2], const char* zst, const float* pot,
-                                                 const Frag<IO, D>& xf, float L, int lane, int kg, float c1)
-{
-    int skew = 0;
-    asm volatile("" : "+v"(skew));
-    Frag<IO, D> zf[2];
-    fetch_pivots<D, 2>(zf, zst, lane, skew);
-    load_pivot_vector<2>(acc, pot + skew, kg);
-    similarity<D, 2>(acc, zf, xf);
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[mb][j] = exp2_fast(fmaf(acc[mb][j], c1, -L));
-}
-
 // The incoming gradient of the coupling for one group: dGamma_it = <value row i, matrix row t>.
 template <typename IO, int D>
 __device__ __forceinline__ void coupling_gradient(f32x16 (&dgam)[2], const char* yhi, const char* ylo,
@@ -866,7 +848,7 @@ int run_backward_grouped(const BwdArgs& a)
     p.dO = a.dO; p.dQ = a.dQ; p.dK = a.dK; p.dV = a.dV; p.dZ = a.dZ; p.dbeta = a.dbeta;
     p.f.colacc = (unsigned long long*)(a.ws + L.colacc);
     p.f.ghist = (float*)(a.ws + L.ghist);
-    p.f.rowlse = (float*)(a.ws + L.rowlse);
+    p.f.rowlse = (float*)(a.ws + L.rowlse); p.f.rowlse_all = 1;
     p.f.u_part = nullptr; p.f.ypp = nullptr;
     p.erow = (float*)(a.ws + L.erow);
     p.u_part = (float*)(a.ws + L.u_part);

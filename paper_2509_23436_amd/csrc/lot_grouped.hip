@@ -2,10 +2,10 @@
 // {32, 64}.  (The paper's runtime study sweeps r up to 256.)  Same method as the fused kernel --
 // similarities by MFMA, log-domain Sinkhorn with implicit token potentials, factored apply -- with the
 // pivots taken in groups of 64:
-//   * per tile of 32 tokens, a first sweep over the groups finds each row's maximum and normaliser
-//     (running maximum, rescaled sum); a second sweep rebuilds each group's exponentials against the
-//     final maximum and uses them (column sums, or the contraction with V, or the expansion with Y'').
-//     Two exponentials per element instead of one: the price of never holding more than one group.
+//   * a pass keeps the similarities of all groups of a tile of 32 tokens in registers (up to 128 per
+//     lane) between the row reduction and the exponentials: one exponential per element;
+//   * the last pass leaves each row's log-normaliser in the workspace (4 bytes per token and solve),
+//     from which the contraction with V and the expansion with Y'' rebuild one group's weights at a time;
 //   * column sums are reduced to one pivot per lane after every tile (transposing reduction), so a
 //     lane carries one accumulator per group instead of 32.
 // One launch per step; launch boundaries are the only synchronisation between workgroups:
@@ -48,6 +48,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
     const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
 
+    const float* lse = last_lse(p) + (size_t)pair * n;
     load_potentials(p, s_g, p.T, pair, h, false, tid);
     stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
     __syncthreads();
@@ -70,10 +71,9 @@ __global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
             const int left = max(1, min(8, n - t0));
             load_values<D>(vh[s], vl[s], vals, (size_t)g * p.n_stride + min(t0, n - 1), left, i);
         }
-        float mc, w;
-        row_normaliser<IO, D>(mc, w, s_zstash, xc, s_g, p.groups, lane, kg, c1, tile * kTileTokens + i < n);
+        const float L = tile * kTileTokens + i < n ? lse[tok] : INFINITY;
         f32x16 acc[2];
-        group_weights<IO, D>(acc, grp, mc, w, s_zstash, xc, s_g, lane, kg, c1);
+        weights_from_lse<IO, D>(acc, s_zstash + (size_t)grp * StashBytes<IO, D, 2>::value, s_g + kGroup * grp, xc, L, lane, kg, c1);
         transpose_tile<2, kSplit>(acc, tr_hi, tr_lo, i, kg);
         contract_tokens<D, 2, kSplit>(U, tr_hi, tr_lo, vh, vl, i, kg);
         transpose_done();
@@ -152,6 +152,7 @@ GroupedWorkspace carve_grouped(const lot_shape& s, int iters)
     w.ghist = take((T + 1) * pairs * kRmax * 4);
     w.u_part = take(G * w.chunks * kRmax * D * 4);
     w.ypp = take(G * kRmax * D * 4);
+    w.rowlse = take(pairs * (size_t)s.n * 4);
     w.total = off;
     return w;
 }
@@ -167,6 +168,7 @@ int run_grouped(const Args& a)
     p.ghist = (float*)(a.ws + L.ghist);
     p.u_part = (float*)(a.ws + L.u_part);
     p.ypp = (float*)(a.ws + L.ypp);
+    p.rowlse = (float*)(a.ws + L.rowlse); p.rowlse_all = 0;
     p.G = s.B * s.H; p.H = s.H; p.n = s.n; p.n_stride = a.n_stride > 0 ? a.n_stride : s.n; p.r = s.r;
     p.groups = (s.r + kGroup - 1) / kGroup; p.chunks = L.chunks; p.tiles_per_wg = lg_tiles_per_wg(s); p.T = a.iters;
     p.eps = a.eps;

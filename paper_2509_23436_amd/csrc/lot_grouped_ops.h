@@ -1,8 +1,9 @@
 // Device code shared by the forward and the backward pass for pivot sizes beyond one register tile
-// (64 < r <= 256): the pivots are taken in groups of 64.  Per tile of 32 tokens, a first sweep over the
-// groups finds each row's maximum and normaliser; a second sweep rebuilds each group's weights
-// W_it = softmax_t((C_it + g_t)/eps) against them.  (Paper, Method: similarities C = X Z^T, Sinkhorn
-// scaling in the log domain; its runtime study sweeps r up to 256.)
+// (64 < r <= 256): the pivots are taken in groups of 64.  A pass keeps the similarities of all groups of a
+// tile of 32 tokens in registers (up to 128 per lane) between the row reduction and the exponentials, and
+// leaves each row's log-normaliser L_i in memory, from which the kernels after the last pass rebuild one
+// group's weights W_it = softmax_t((C_it + g_t)/eps) = exp2((C_it + g_t) c1 - L_i) at a time.
+// (Paper, Method: similarities C = X Z^T, Sinkhorn scaling in the log domain; its runtime study sweeps r up to 256.)
 #pragma once
 #include "lot_internal.h"
 #include "lot_tile.h"
@@ -24,7 +25,8 @@ struct LgParams {
     float* ghist;                 // [T+1][pairs][256]  g^k, k = 0..T-1 (padding pivots: -1e30)
     float* u_part;                // [G][chunks][256][D]
     float* ypp;                   // [G][256][D]  Y''
-    float* rowlse;                // [T][pairs][n] base-2 log-normaliser of every row in pass k (at k - 1), or null: not kept
+    float* rowlse;                // base-2 log-normaliser L_i of every row: [T][pairs][n], pass k at k - 1 (rowlse_all), or
+    int rowlse_all;               // [pairs][n] of the last pass only; W_it = exp2((C_it + g_t) c1 - L_i)
     int G, H, n, n_stride, r, groups, chunks, tiles_per_wg, k, T;
     float eps, fx_scale, fx_unscale;
 };
@@ -37,61 +39,6 @@ inline int lg_tiles_per_wg(const lot_shape& s)
     if (per < kWaves) per = kWaves;
     if (per > 16 * kWaves) per = 16 * kWaves;
     return (int)per;
-}
-
-// First sweep over the groups for one tile: row maximum (times c1) and reciprocal normaliser.
-template <typename IO, int D>
-__device__ __forceinline__ void row_normaliser(float& mc, float& w, const char* zstash, const Frag<IO, D>& xf,
-                                               const float* pot, int groups, int lane, int kg, float c1, bool valid)
-{
-    float run_m = -INFINITY, run_s = 0.f;
-    for (int p = 0; p < groups; ++p) {
-        int skew = 0;
-        asm volatile("" : "+v"(skew));
-        Frag<IO, D> zf[2];
-        fetch_pivots<D, 2>(zf, zstash + (size_t)p * StashBytes<IO, D, 2>::value, lane, skew);
-        f32x16 acc[2];
-        load_pivot_vector<2>(acc, pot + kGroup * p + skew, kg);
-        similarity<D, 2>(acc, zf, xf);
-        float m0 = acc[0][0], m1 = acc[0][1];
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int j = (mb == 0 ? 2 : 0); j < 16; j += 2) {
-                m0 = fmaxf(m0, acc[mb][j]);
-                m1 = fmaxf(m1, acc[mb][j + 1]);
-            }
-        const float new_m = fmaxf(run_m, pair_max(fmaxf(m0, m1)) * c1);
-        float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int j = 0; j < 16; j += 2) {
-                s0 += exp2_fast(fmaf(acc[mb][j], c1, -new_m));
-                s1 += exp2_fast(fmaf(acc[mb][j + 1], c1, -new_m));
-            }
-        run_s = run_s * exp2_fast(run_m - new_m) + (s0 + s1);     // exp2(-inf) = 0 for the first group
-        run_m = new_m;
-    }
-    mc = run_m;
-    w = valid ? rcp_fast(pair_sum(run_s)) : 0.f;
-}
-
-// Second sweep, one group: acc <- W_it = exp2((C_it + g_t) c1 - mc) * w for the group's 64 pivots.
-template <typename IO, int D>
-__device__ __forceinline__ void group_weights(f32x16 (&acc)[2], int p, float mc, float w, const char* zstash,
-                                              const Frag<IO, D>& xf, const float* pot, int lane, int kg, float c1)
-{
-    int skew = 0;
-    asm volatile("" : "+v"(skew));
-    Frag<IO, D> zf[2];
-    fetch_pivots<D, 2>(zf, zstash + (size_t)p * StashBytes<IO, D, 2>::value, lane, skew);
-    load_pivot_vector<2>(acc, pot + kGroup * p + skew, kg);
-    similarity<D, 2>(acc, zf, xf);
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[mb][j] = exp2_fast(fmaf(acc[mb][j], c1, -mc)) * w;
 }
 
 // Common set-up: pivot fragments of all groups to the LDS stash, g^{k-1} to s_g.
@@ -128,6 +75,35 @@ __device__ __forceinline__ void load_potentials(const LgParams& p, float* s_g, i
     }
 }
 
+// Where pass k keeps its rows' log-normalisers (null: not kept), and where the last pass has left them.
+__device__ __forceinline__ float* lse_slot(const LgParams& p, int k)
+{
+    if (p.rowlse_all) return p.rowlse + (size_t)(k - 1) * 2 * p.G * p.n;
+    return k == p.T ? p.rowlse : nullptr;
+}
+__device__ __forceinline__ const float* last_lse(const LgParams& p)
+{
+    return p.rowlse + (p.rowlse_all ? (size_t)(p.T - 1) * 2 * p.G * p.n : 0);
+}
+
+// acc <- W_it = exp2((C_it + g_t) c1 - L_i) for the 64 pivots of one group (zst: its stash, pot: its g).
+// A row past the end carries L = +inf: weights exactly 0.
+template <typename IO, int D>
+__device__ __forceinline__ void weights_from_lse(f32x16 (&acc)[2], const char* zst, const float* pot,
+                                                 const Frag<IO, D>& xf, float L, int lane, int kg, float c1)
+{
+    int skew = 0;
+    asm volatile("" : "+v"(skew));
+    Frag<IO, D> zf[2];
+    fetch_pivots<D, 2>(zf, zst, lane, skew);
+    load_pivot_vector<2>(acc, pot + skew, kg);
+    similarity<D, 2>(acc, zf, xf);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[mb][j] = exp2_fast(fmaf(acc[mb][j], c1, -L));
+}
+
 // ---------------------------------------------------------------------------------------------
 // pass k: column sums of W^k for both solves
 // ---------------------------------------------------------------------------------------------
@@ -160,27 +136,63 @@ __global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
     __syncthreads();
 
     float csg[kMaxGroups] = {0.f, 0.f, 0.f, 0.f};       // this lane's pivot of each group
+    float* const lse_keep = lse_slot(p, k);
     for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
         Frag<IO, D> xn = xc;
         if (tile + kWaves < tile_end) {
             const int tok = min((tile + kWaves) * kTileTokens + i, n - 1);
             load_tokens<D>(xn, X + ((size_t)g * p.n_stride + tok) * D, kg);
         }
-        float mc, w;
-        row_normaliser<IO, D>(mc, w, s_zstash, xc, s_g, p.groups, lane, kg, c1, tile * kTileTokens + i < n);
-        // W_it = exp2((C_it + g_t) c1 - L_i) with L_i = mc + log2(row sum): kept for the backward pass
-        if (p.rowlse && kg == 0 && tile * kTileTokens + i < n)
-            p.rowlse[((size_t)(k - 1) * pairs + pair) * n + tile * kTileTokens + i] = mc - __builtin_amdgcn_logf(w);
+        // similarities (plus potentials) of all groups stay in registers between the row reduction and the
+        // exponentials: one exponential per element
+        f32x16 acc[kMaxGroups][2];
+        float m0 = -INFINITY, m1 = -INFINITY;
 #pragma unroll
         for (int q = 0; q < kMaxGroups; ++q) {
             if (q < p.groups) {
-                f32x16 acc[2];
-                group_weights<IO, D>(acc, q, mc, w, s_zstash, xc, s_g, lane, kg, c1);
+                int skew = 0;
+                asm volatile("" : "+v"(skew));
+                Frag<IO, D> zf[2];
+                fetch_pivots<D, 2>(zf, s_zstash + (size_t)q * StashBytes<IO, D, 2>::value, lane, skew);
+                load_pivot_vector<2>(acc[q], s_g + kGroup * q + skew, kg);
+                similarity<D, 2>(acc[q], zf, xc);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; j += 2) {
+                        m0 = fmaxf(m0, acc[q][mb][j]);
+                        m1 = fmaxf(m1, acc[q][mb][j + 1]);
+                    }
+            }
+        }
+        const float mc = pair_max(fmaxf(m0, m1)) * c1;
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int q = 0; q < kMaxGroups; ++q) {
+            if (q < p.groups) {
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; j += 2) {
+                        const float e0 = exp2_fast(fmaf(acc[q][mb][j], c1, -mc));
+                        const float e1 = exp2_fast(fmaf(acc[q][mb][j + 1], c1, -mc));
+                        acc[q][mb][j] = e0; acc[q][mb][j + 1] = e1;
+                        s0 += e0; s1 += e1;
+                    }
+            }
+        }
+        const bool valid = tile * kTileTokens + i < n;
+        const float rowsum = pair_sum(s0 + s1);
+        const float w = valid ? rcp_fast(rowsum) : 0.f;
+        if (lse_keep && kg == 0 && valid) lse_keep[(size_t)pair * n + tile * kTileTokens + i] = mc + __builtin_amdgcn_logf(rowsum);
+#pragma unroll
+        for (int q = 0; q < kMaxGroups; ++q) {
+            if (q < p.groups) {
                 float c[32];
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) c[16 * mb + j] = acc[mb][j];
+                    for (int j = 0; j < 16; ++j) c[16 * mb + j] = acc[q][mb][j] * w;
                 csg[q] += reduce_scatter_tokens<32>(c, i);
             }
         }
@@ -226,6 +238,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
     const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
 
+    const float* lse = last_lse(p) + (size_t)(side * p.G + g) * n;
     load_potentials(p, s_g, p.T, side * p.G + g, h, false, tid);
     stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
     for (int q = 0; q < p.groups; ++q) {
@@ -239,8 +252,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
         const int tok = min(tile * kTileTokens + i, n - 1);
         Frag<IO, D> xc;
         load_tokens<D>(xc, X + ((size_t)g * p.n_stride + tok) * D, kg);
-        float mc, w;
-        row_normaliser<IO, D>(mc, w, s_zstash, xc, s_g, p.groups, lane, kg, c1, tile * kTileTokens + i < n);
+        const float L = tile * kTileTokens + i < n ? lse[tok] : INFINITY;
         f32x16 o[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -248,7 +260,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
             for (int j = 0; j < 16; ++j) o[nb][j] = 0.f;
         for (int q = 0; q < p.groups; ++q) {
             f32x16 acc[2], part[NB];
-            group_weights<IO, D>(acc, q, mc, w, s_zstash, xc, s_g, lane, kg, c1);
+            weights_from_lse<IO, D>(acc, s_zstash + (size_t)q * StashBytes<IO, D, 2>::value, s_g + kGroup * q, xc, L, lane, kg, c1);
             contract_pivots<D, 2, kSplit>(part, acc, yf + (size_t)(2 * q) * kFragsPerGroup,
                                           yf + (size_t)(2 * q + 1) * kFragsPerGroup, lane);
 #pragma unroll

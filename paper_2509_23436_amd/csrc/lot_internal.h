@@ -162,7 +162,7 @@ BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters);
 
 // Forward for 64 < r <= 256 (pivots in groups of 64; one launch per step).
 struct GroupedWorkspace {
-    size_t colacc, ghist, u_part, ypp;   // status words at offset 0
+    size_t colacc, ghist, u_part, ypp, rowlse;   // status words at offset 0
     size_t total;
     int chunks;
 };
