@@ -703,41 +703,27 @@ __global__ void bt_recursion(BtParams p, int R)
     auto colsum = [&](int k) {
         return colsum_of(p.colacc[((size_t)k * pairs + pair) * 64 + t], p.fx_unscale) * a;   // c^k_t
     };
-    // M^k is symmetric: thread t walks a quarter of column t, so that a wavefront reads whole rows.  Only the
-    // vector depends on the step before, so the next step's Gram values (and column sum) are requested
-    // while this step's products run.
-    const bool walks = live && t < R;
-    const int u0 = q * (R / 4);
-    float mcur[16], mnext[16];
-    auto gram_fetch = [&](int k, float (&m)[16]) {
-        const float* col = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + t;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) m[j] = (walks && j < R / 4 && k >= 1) ? col[(size_t)(u0 + j) * R] : 0.f;
-    };
     auto gram_times = [&](int k, float v) {      // (M^k v)_t; v is meaningful in the threads with q == 0
         if (q == 0) s_v[t] = live ? v : 0.f;
-        gram_fetch(k - 1, mnext);
         __syncthreads();
         float acc = 0.f;
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-            if (j < R / 4) acc = fmaf(mcur[j], s_v[u0 + j], acc);
-        s_q[q][t] = walks ? acc : 0.f;
+        if (live && t < R) {
+            // M^k is symmetric: thread t walks column t, so that a wavefront reads whole rows
+            const float* col = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + t;
+            const int u0 = q * (R / 4);
+#pragma unroll 8
+            for (int u = u0; u < u0 + R / 4; ++u) acc = fmaf(col[(size_t)u * R], s_v[u], acc);
+        }
+        s_q[q][t] = acc;
         __syncthreads();
-#pragma unroll
-        for (int j = 0; j < 16; ++j) mcur[j] = mnext[j];
         return (s_q[0][t] + s_q[1][t]) + (s_q[2][t] + s_q[3][t]);
     };
-    gram_fetch(T, mcur);
-    float cs_next = T >= 2 ? colsum(T - 1) : 1.f;
     float db = live ? s / b : 0.f;
     float dc = live ? -s / colsum(T) : 0.f;
     if (q == 0) p.dcs[((size_t)T * pairs + pair) * 64 + t] = dc;
     float dg = -(nn + a * gram_times(T, dc)) / p.eps;          // dg^{T-1}
     for (int k = T - 1; k >= 1; --k) {
-        const float cs = cs_next;
-        cs_next = k >= 2 ? colsum(k - 1) : 1.f;
-        dc = live ? -p.eps * dg / cs : 0.f;
+        dc = live ? -p.eps * dg / colsum(k) : 0.f;
         db += live ? p.eps * dg / b : 0.f;
         if (q == 0) p.dcs[((size_t)k * pairs + pair) * 64 + t] = dc;
         dg = -(a / p.eps) * gram_times(k, dc);                  // dg^{k-1}
