@@ -168,11 +168,14 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * FUSED (from 16 tokens up; shorter sequences go to the plain kernels, which are exact to fp32 rounding).
  * Results are reproducible bit for bit on either path.  lot_workspace_status applies to this
  * workspace too (the FUSED path's forward sweep waits between workgroups when it runs as one kernel).
- * Testing aid: the FUSED path rebuilds each tile's row-normalised kernels for all iterations with ONE
- * shift per row instead of a maximum per iteration, and re-shifts when a row sum leaves
- * [2^-40, 2^40]; the environment variable LOT_RESHIFT_BITS (0..40, read at each call) narrows that
- * range to 2^-bits .. 2^bits so that the rarely taken branch runs on ordinary inputs (0: practically
- * every iteration takes it).  Results agree to rounding for every value.  LOT_BWD_SWEEP_LAUNCHES=1
+ * Testing aids (environment variables read at each call): the FUSED path (r <= 64) rebuilds each tile's
+ * row-normalised kernels for all iterations with ONE shift per row instead of a maximum per iteration,
+ * and checks every row sum against [2^-40, 2^40]: up to 16 iterations all of them are assembled at once
+ * and a workgroup that finds a sum outside is redone by a second kernel, which goes iteration by
+ * iteration and re-shifts the rows of an iteration whose sum leaves the range.  LOT_RESHIFT_BITS (0..40)
+ * narrows the range to 2^-bits .. 2^bits so that these rarely taken branches run on ordinary inputs (0:
+ * practically every iteration takes them); LOT_BWD_ASSEMBLE_BY_ITERATION=1 sends every workgroup through
+ * the second kernel.  Results agree to rounding for every value.  LOT_BWD_SWEEP_LAUNCHES=1
  * makes the FUSED path's forward sweep run as one launch per pass (its form on a device that cannot
  * hold the whole grid at once) where it would otherwise be one persistent kernel; same results.
  */
