@@ -184,6 +184,10 @@ FULL = {
     "long_4k": (W["long_4k"], [5]),
     "long_16k": (W["long_16k"], [9]),
     "many_chunks": (S(W["swin_t_s1"], B=8, H=8, n=10240, iters=4, seed=77), [3, 60]),
+    # the paper's runtime grid (B = 1, H = 8, T = 5) at r = 256 and 128, in the launch configuration the
+    # grid benchmark times: the grouped tile kernels, several workgroups per problem
+    "runtime_grid_r256": (S(W["long_16k"], B=1, H=8, n=65536, r=256, iters=5, seed=94), [5]),
+    "runtime_grid_r128": (S(W["long_16k"], B=1, H=8, n=8192, r=128, iters=5, seed=95), [2]),
 }
 
 
