@@ -229,12 +229,14 @@ __global__ void gb_mid(GbParams p)
 // glue: s_t = rho'_t sum_i W_it dGamma_it (per-workgroup partial sums) and n q_i = n sum_t W_it rho'_t dGamma_it
 // (into erow at T - 1), both solves.
 // ---------------------------------------------------------------------------------------------
-template <typename IO, int D>
-__global__ void __launch_bounds__(kThreads, 1) gb_glue(GbParams p)
+// (kGlueWaves wavefronts per workgroup: the stashes fill most of a compute unit's local memory, so a
+// second wavefront per SIMD has to come from the same workgroup; worth it when a workgroup has many tiles)
+template <typename IO, int D, int kGlueWaves>
+__global__ void __launch_bounds__(64 * kGlueWaves) gb_glue(GbParams p)
 {
     constexpr int kStash = StashBytes<IO, D, 2>::value;
     __shared__ float s_g[kRmax], s_rho[kRmax];
-    __shared__ float s_cs[kWaves][kRmax];
+    __shared__ float s_cs[kGlueWaves][kRmax];
     __shared__ __attribute__((aligned(16))) float s_y[64 * D];
     extern __shared__ __attribute__((aligned(16))) char s_dyn[];   // pivot stash | matrix stash hi | (bf16 I/O) lo, per group
 
@@ -270,7 +272,7 @@ __global__ void __launch_bounds__(kThreads, 1) gb_glue(GbParams p)
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
     const int tile_begin = chunk * p.f.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.f.tiles_per_wg);
     float sg[kMaxGroups] = {0.f, 0.f, 0.f, 0.f};       // this lane's pivot of each group
-    for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
+    for (int tile = tile_begin + wave; tile < tile_end; tile += kGlueWaves) {
         const bool valid = tile * kTileTokens + i < n;
         const int tok = min(tile * kTileTokens + i, n - 1);
         const float L = valid ? lse[tok] : INFINITY;
@@ -305,10 +307,10 @@ __global__ void __launch_bounds__(kThreads, 1) gb_glue(GbParams p)
 #pragma unroll
     for (int q = 0; q < kMaxGroups; ++q) s_cs[wave][kGroup * q + mine] = sg[q];
     __syncthreads();
-    for (int t = tid; t < kRmax; t += kThreads) {
+    for (int t = tid; t < kRmax; t += 64 * kGlueWaves) {
         float tot = 0.f;
 #pragma unroll
-        for (int wv = 0; wv < kWaves; ++wv) tot += s_cs[wv][t];
+        for (int wv = 0; wv < kGlueWaves; ++wv) tot += s_cs[wv][t];
         p.s_part[((size_t)pair * p.f.chunks + chunk) * kRmax + t] = t < p.f.r ? tot * s_rho[t] : 0.f;
     }
 }
@@ -533,8 +535,10 @@ __device__ __forceinline__ void load_tables(float* tab, float* bvec, const GbPar
 // ---------------------------------------------------------------------------------------------
 // assemble-x: dQ / dK rows = dC Z, summed over the groups in order
 // ---------------------------------------------------------------------------------------------
-template <typename IO, int D>
-__global__ void __launch_bounds__(kThreads, 1) gb_assemble_x(GbParams p, int stage_bytes)
+// (WAVES wavefronts per workgroup: the tables fill most of a compute unit's local memory, so a second
+// wavefront per SIMD has to come from the same workgroup)
+template <typename IO, int D, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stage_bytes)
 {
     constexpr int NB = D / 32;
     constexpr int kStash = StashBytes<IO, D, 2>::value;
@@ -595,7 +599,7 @@ __global__ void __launch_bounds__(kThreads, 1) gb_assemble_x(GbParams p, int sta
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
     const int tile_begin = chunk * p.f.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.f.tiles_per_wg);
     const float scale_out = 1.f / ((float)n * p.f.eps);   // a / eps
-    for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
+    for (int tile = tile_begin + wave; tile < tile_end; tile += WAVES) {
         const bool valid = tile * kTileTokens + i < n;
         const int tok = min(tile * kTileTokens + i, n - 1);
         Frag<IO, D> xc, vc;
@@ -761,6 +765,7 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
 {
     constexpr int NB = D / 32;
     constexpr bool kSplit = io_is_f32<IO>::value;
+    constexpr int kAssembleWaves = kSplit ? 4 : 8;     // (fp32 I/O: eight would not fit the register file)
     static_assert(StashBytes<IO, D, 2>::value == 2 * 64 * (kSplit ? (D / 2) * 4 : (D / 16) * 16), "stash size as the host computes it");
     hipStream_t st = a.stream;
     const int pairs = 2 * p.f.G, T = a.iters, groups = p.f.groups;
@@ -776,9 +781,10 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
     // more than 64 KB of LDS per workgroup has to be asked for explicitly
     LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(lg_pass<IO, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)stash));
     LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(lg_expand<IO, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(stash + frag_bytes)));
-    LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(gb_glue<IO, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)glue_bytes));
+    LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(gb_glue<IO, D, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)glue_bytes));
+    LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(gb_glue<IO, D, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)glue_bytes));
     LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(gb_rec_pass<IO, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)stash));
-    LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(gb_assemble_x<IO, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ax_bytes));
+    LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(gb_assemble_x<IO, D, kAssembleWaves>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ax_bytes));
     LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(gb_assemble_z<IO, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)az_bytes));
     const unsigned grid = (unsigned)pairs * p.f.chunks;
     for (int k = 1; k <= T; ++k) {
@@ -788,9 +794,10 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
     gb_contract<IO, D><<<dim3(grid, (unsigned)groups), kThreads, 0, st>>>(p);
     gb_mid<D><<<(unsigned)(p.f.G * kRmax * D / 256), 256, 0, st>>>(p);
     lg_expand<IO, D><<<(unsigned)p.f.G * p.f.chunks, kThreads, stash + frag_bytes, st>>>(p.f, 1, p.f.K, p.ydv, p.dV);
-    gb_glue<IO, D><<<grid, kThreads, glue_bytes, st>>>(p);
+    if (p.f.tiles_per_wg >= 32) gb_glue<IO, D, 8><<<grid, 512, glue_bytes, st>>>(p);
+    else gb_glue<IO, D, 4><<<grid, 256, glue_bytes, st>>>(p);
     for (int k = T; k >= 1; --k) gb_rec_pass<IO, D><<<grid, kThreads, stash, st>>>(p, k);
-    gb_assemble_x<IO, D><<<grid, kThreads, ax_bytes, st>>>(p, (int)stage);
+    gb_assemble_x<IO, D, kAssembleWaves><<<grid, 64 * kAssembleWaves, ax_bytes, st>>>(p, (int)stage);
     gb_assemble_z<IO, D><<<dim3(grid, (unsigned)groups), kThreads, az_bytes, st>>>(p);
     gb_final<<<(unsigned)((a.s.H * a.s.r * (D + 1) + 255) / 256), 256, 0, st>>>(p, D);
     LOT_HIP_CHECK(hipGetLastError());
