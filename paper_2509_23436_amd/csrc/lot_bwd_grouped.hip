@@ -19,10 +19,10 @@
 //
 // Launches (launch boundaries are the only synchronisation between workgroups; both solves share every
 // launch, pair = side * G + g, side 0 = queries):
-//   clear | T x pass (column sums, L^k) | contract (U = sum W2 V, Wd = sum W1 dO, a group per blockIdx.y) |
+//   clear | T x pass (column sums, L^k) | contract (U = sum W2 V, Wd = sum W1 dO, a workgroup per group) |
 //   mid (Y', dYraw, rho') | expand (dV) | glue (s, n q_i) | T x recursion pass (k = T..1: dc^k from the
 //   partial sums of the pass before, e^k_i, column sums of W^k e^k) | assemble-x (dQ, dK) |
-//   assemble-z (dZ partials, a group per blockIdx.y) | final (dZ, dbeta).
+//   assemble-z (dZ partials, a workgroup per group) | final (dZ, dbeta).
 // Every reduction has a fixed order except the forward column sums, which are exchanged as integers:
 // results are reproducible.
 #include "lot_internal.h"
@@ -137,7 +137,9 @@ __global__ void __launch_bounds__(kThreads, 2) gb_contract(GbParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 31, kg = lane >> 5;
     const int pairs = 2 * p.f.G, T = p.f.T;
-    const int pair = blockIdx.x / p.f.chunks, chunk = blockIdx.x % p.f.chunks, grp = blockIdx.y;
+    int wg, grp;
+    if (!group_block(wg, grp, pairs * p.f.chunks, p.f.groups)) return;
+    const int pair = wg / p.f.chunks, chunk = wg % p.f.chunks;
     const int side = pair / p.f.G, g = pair % p.f.G, h = g % p.f.H;
     const int n = p.f.n;
     const float c1 = kLog2e / p.f.eps;
@@ -446,7 +448,7 @@ __global__ void __launch_bounds__(kThreads, 2) gb_rec_pass(GbParams p, int k)
 // R^k_i = exp2(m_i + h_k - L^k_i)  (E, P <= 1; R is capped at 2^60: beyond that the row's weights in this
 // group are below 2^-60 of the bound anyway), so that
 //   dacc_it = (a/eps) E_it [ sum_k R^k_i A^k_t - sum_k (R^k_i e^k_i) P^k_t + R^T_i B_t dGamma_it ],
-// A^k = P^k dc^k, B = n rho' P^T: two multiply-adds per element and iteration.
+// A^k = P^k dc^k, B = n rho' P^T.
 // tab: [T][2][64] for this group, (P^k, A^k) at k - 1; bvec: B for this group; shifts: h_k at k - 1.
 template <typename IO, int D>
 __device__ __forceinline__ void similarity_gradient(f32x16 (&dacc)[2], const char* zst, const char* yhi, const char* ylo,
@@ -486,35 +488,36 @@ __device__ __forceinline__ void similarity_gradient(f32x16 (&dacc)[2], const cha
         R = exp2_fast(fminf(m + shifts[k - 1] - L, 60.f));
         S = R * erow[(size_t)(k - 1) * per_k + tok];
     };
-    // last iteration: dP^T = n rho' dGamma + dc^T
-    {
-        f32x16 dgam[2], bv[2], P[2], A[2];
-        coupling_gradient<IO, D>(dgam, yhi, ylo, vc, lane);
-        load_pivot_vector<2>(bv, bvec + skew, kg);
-        load_pivot_vector<2>(P, tab + ((T - 1) * 2 + 0) * kGroup + skew, kg);
-        load_pivot_vector<2>(A, tab + ((T - 1) * 2 + 1) * kGroup + skew, kg);
-        float R, S;
-        row_factors(T, R, S);
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(R, fmaf(bv[mb][j], dgam[mb][j], A[mb][j]), -S * P[mb][j]);
-    }
-    for (int k = T - 1; k >= 1; --k) {
-        f32x16 P[2], A[2];
-        load_pivot_vector<2>(P, tab + ((k - 1) * 2 + 0) * kGroup + skew, kg);
-        load_pivot_vector<2>(A, tab + ((k - 1) * 2 + 1) * kGroup + skew, kg);
-        float R, S;
-        row_factors(k, R, S);
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) dacc[mb][j] = fmaf(R, A[mb][j], fmaf(-S, P[mb][j], dacc[mb][j]));
-    }
+    // sum_k R^k_i A^k_t - S^k_i P^k_t: a (64 x 2T) by (2T x 32) product on the fp32 matrix cores, two table rows
+    // per instruction (this lane supplies row 2 (k - 1) + kg of the table and the matching row factor)
+    const int i = lane & 31;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) dacc[mb][j] *= E[mb][j] * scale_out;
+        for (int j = 0; j < 16; ++j) dacc[mb][j] = 0.f;
+    float r_last = 0.f;
+    for (int k = 1; k <= T; ++k) {
+        float R, S;
+        row_factors(k, R, S);
+        r_last = R;
+        const float b = kg ? R : -S;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            const float a = tab[((k - 1) * 2 + kg) * kGroup + 32 * mb + i + skew];
+            dacc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, dacc[mb], 0, 0, 0);
+        }
+    }
+    // last iteration: dP^T = n rho' dGamma + dc^T
+    {
+        f32x16 dgam[2], bv[2];
+        coupling_gradient<IO, D>(dgam, yhi, ylo, vc, lane);
+        load_pivot_vector<2>(bv, bvec + skew, kg);
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                dacc[mb][j] = E[mb][j] * scale_out * fmaf(r_last * bv[mb][j], dgam[mb][j], dacc[mb][j]);
+    }
 }
 
 // Per-pivot tables of the assembly for the pivots [t0, t0 + 64): (P^k, A^k) for all k into tab ([T][2][64])
@@ -655,7 +658,9 @@ __global__ void __launch_bounds__(kThreads, 2) gb_assemble_z(GbParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 31, kg = lane >> 5;
     const int pairs = 2 * p.f.G, T = p.f.T;
-    const int pair = blockIdx.x / p.f.chunks, chunk = blockIdx.x % p.f.chunks, grp = blockIdx.y;
+    int wg, grp;
+    if (!group_block(wg, grp, pairs * p.f.chunks, p.f.groups)) return;
+    const int pair = wg / p.f.chunks, chunk = wg % p.f.chunks;
     const int side = pair / p.f.G, g = pair % p.f.G, h = g % p.f.H;
     const int n = p.f.n;
     const float c1 = kLog2e / p.f.eps;
@@ -791,14 +796,14 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
         p.f.k = k;
         lg_pass<IO, D><<<grid, kThreads, stash, st>>>(p.f);
     }
-    gb_contract<IO, D><<<dim3(grid, (unsigned)groups), kThreads, 0, st>>>(p);
+    gb_contract<IO, D><<<group_grid(grid, groups), kThreads, 0, st>>>(p);
     gb_mid<D><<<(unsigned)(p.f.G * kRmax * D / 256), 256, 0, st>>>(p);
     lg_expand<IO, D><<<(unsigned)p.f.G * p.f.chunks, kThreads, stash + frag_bytes, st>>>(p.f, 1, p.f.K, p.ydv, p.dV);
     if (p.f.tiles_per_wg >= 32) gb_glue<IO, D, 8><<<grid, 512, glue_bytes, st>>>(p);
     else gb_glue<IO, D, 4><<<grid, 256, glue_bytes, st>>>(p);
     for (int k = T; k >= 1; --k) gb_rec_pass<IO, D><<<grid, kThreads, stash, st>>>(p, k);
     gb_assemble_x<IO, D, kAssembleWaves><<<grid, 64 * kAssembleWaves, ax_bytes, st>>>(p, (int)stage);
-    gb_assemble_z<IO, D><<<dim3(grid, (unsigned)groups), kThreads, az_bytes, st>>>(p);
+    gb_assemble_z<IO, D><<<group_grid(grid, groups), kThreads, az_bytes, st>>>(p);
     gb_final<<<(unsigned)((a.s.H * a.s.r * (D + 1) + 255) / 256), 256, 0, st>>>(p, D);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;

@@ -9,8 +9,8 @@
 //   * column sums are reduced to one pivot per lane after every tile (transposing reduction), so a
 //     lane carries one accumulator per group instead of 32.
 // One launch per step; launch boundaries are the only synchronisation between workgroups:
-//   clear | T x pass (both solves: pair = side * G + g, side 0 = queries) | reduce (keys, one group per
-//   blockIdx.y: U = sum_j W2 V) | mid (Y'' = n beta/cs1 * U/cs2) | expand (queries -> O).
+//   clear | T x pass (both solves: pair = side * G + g, side 0 = queries) | reduce (keys, one workgroup
+//   per group: U = sum_j W2 V) | mid (Y'' = n beta/cs1 * U/cs2) | expand (queries -> O).
 // Column sums are exchanged as fixed-point integers (atomic adds): order-independent, reproducible.
 #include "lot_internal.h"
 #include "lot_tile.h"
@@ -22,7 +22,7 @@ namespace lot {
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// reduce: U_t = sum_j W2_jt V_j for the pivots of group blockIdx.y (keys; potentials g2^{T-1})
+// reduce: U_t = sum_j W2_jt V_j for the pivots of one group per workgroup (keys; potentials g2^{T-1})
 // ---------------------------------------------------------------------------------------------
 template <typename IO, int D>
 __global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
@@ -37,7 +37,9 @@ __global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 31, kg = lane >> 5;
-    const int g = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks, grp = blockIdx.y;
+    int wg, grp;
+    if (!group_block(wg, grp, p.G * p.chunks, p.groups)) return;
+    const int g = wg / p.chunks, chunk = wg % p.chunks;
     const int pair = p.G + g, h = g % p.H;
     const int n = p.n;
     const float c1 = kLog2e / p.eps;
@@ -125,7 +127,7 @@ int launch_grouped(const Args& a, LgParams p)
         p.k = k;
         lg_pass<IO, D><<<(unsigned)pairs * p.chunks, kThreads, stash, st>>>(p);
     }
-    lg_reduce<IO, D><<<dim3((unsigned)p.G * p.chunks, (unsigned)p.groups), kThreads, stash, st>>>(p);
+    lg_reduce<IO, D><<<group_grid((unsigned)p.G * p.chunks, p.groups), kThreads, stash, st>>>(p);
     lg_mid<D><<<(unsigned)((p.G * kRmax * D + 255) / 256), 256, 0, st>>>(p);
     lg_expand<IO, D><<<(unsigned)p.G * p.chunks, kThreads, stash + frag_bytes, st>>>(p, 0, p.Q, p.ypp, p.out);
     LOT_HIP_CHECK(hipGetLastError());

@@ -41,6 +41,19 @@ inline int lg_tiles_per_wg(const lot_shape& s)
     return (int)per;
 }
 
+// Workgroup (wg, grp) of a launch that gives every one of nwg token ranges to `groups` workgroups, one per
+// pivot group.  Block ids go round the 8 XCDs, each with its own L2: the workgroups that read the same token
+// rows get ids 8 apart, consecutive on one XCD, so that the rows come from HBM once.  False: nothing to do
+// (the grid is rounded up to a multiple of 8 * groups).
+__device__ __forceinline__ bool group_block(int& wg, int& grp, int nwg, int groups)
+{
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    grp = slot % groups;
+    wg = (slot / groups) * 8 + xcd;
+    return wg < nwg;
+}
+inline unsigned group_grid(unsigned nwg, int groups) { return (nwg + 7) / 8 * 8 * (unsigned)groups; }
+
 // Common set-up: pivot fragments of all groups to the LDS stash, g^{k-1} to s_g.
 template <typename IO, int D>
 __device__ __forceinline__ void stash_all_pivots(char* zstash, const float* Z, int h, int r, int groups,
