@@ -169,6 +169,35 @@ def test_assembly_iteration_by_iteration_meets_the_same_bar(monkeypatch):
             assert err <= tol, nm
 
 
+@pytest.mark.parametrize("r", [64, 128])
+@pytest.mark.parametrize("eps", [0.01, 100.0])
+def test_extreme_eps_of_the_ablation_sweep_stay_finite_in_the_backward_pass(eps, r):
+    """The ends of the paper's epsilon sweep: gradients must stay finite on every path (one register tile
+    and grouped pivots); at eps = 0.01, where the exponents spread over hundreds of binary orders and the
+    tile kernels' shared shifts are under the most strain, they must also agree with the plain kernels
+    (at eps = 100 the gradients with respect to Q, K, Z all but vanish and only dV, dbeta are compared)."""
+    import torch
+    from paper_2509_23436_amd import lot
+    w = S(W["long_4k"], B=1, H=2, n=2048, r=r, eps=eps, seed=31)
+    x = synth.make_inputs(w)
+    dO = synth.round_to_bf16(np.random.default_rng(3).standard_normal(x["V"].shape).astype(np.float32))
+    dev = to_device(dict(x, dO=dO), w.dtype)
+    res = {}
+    for pn, path in (("reference", lot.PATH_REFERENCE), ("fused", lot.PATH_FUSED)):
+        got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, dev["dO"],
+                                    path=path)
+        torch.cuda.synchronize()
+        res[pn] = [to_host_f64(g) for g in got]
+        for nm, g in zip(("dQ", "dK", "dV", "dZ", "dbeta"), res[pn]):
+            assert np.isfinite(g).all(), (pn, nm)
+    for nm, a, b in zip(("dQ", "dK", "dV", "dZ", "dbeta"), res["fused"], res["reference"]):
+        if eps > 1.0 and nm in ("dQ", "dK", "dZ"):
+            continue
+        err = rel_max_err(a, b)
+        _say("  eps %g r %d %-5s tile kernels against plain kernels: %.3e" % (eps, r, nm, err))
+        assert err <= 2e-2, nm
+
+
 # Full benchmark sizes: the library runs the WHOLE workload (launch configuration of the benchmark);
 # the float64 oracle differentiates a sample of the (batch, head) problems one by one.  A problem's
 # dQ, dK, dV depend on that problem alone; dZ and dbeta are sums over the batch, so for them the
