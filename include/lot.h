@@ -126,8 +126,9 @@ int lot_attention_cls_fwd_path(const lot_shape* shape, const void* Q, const void
  * out = A V with A = Diag(mu)^-1 Gamma1 Diag(beta)^-1 Gamma2, the glued plan with renormalised rows
  * (for uniform masses and n_q = n_k this is n Gamma, i.e. lot_attention_fwd).  The row of a
  * zero-mass query is still defined (the limit of the formula) and written.
- * Execution paths as for lot_attention_fwd (lot_path): the fused kernel takes d_k = d_v in {32, 64},
- * r <= 64; the plain kernels any shape; AUTO prefers the fused kernel.  Workspace:
+ * Execution paths as for lot_attention_fwd (lot_path): the tile kernels take d_k = d_v in {32, 64}
+ * (r <= 64 the fused kernel, 64 < r <= 256 the grouped kernels); the plain kernels any shape; AUTO
+ * prefers the tile kernels.  Workspace:
  * lot_cross_workspace_bytes; lot_workspace_status applies.
  */
 typedef struct {

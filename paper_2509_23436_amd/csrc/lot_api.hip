@@ -253,6 +253,10 @@ int lot_cross_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_
         const size_t fused = carve(fs).C;      // the fused kernel's regions come first in that layout
         if (fused > need) need = fused;
     }
+    if (grouped_supports(fs)) {
+        const size_t grouped = carve_grouped(fs, iters).total;
+        if (grouped > need) need = grouped;
+    }
     *bytes_out = need;
     return LOT_OK;
 }
@@ -276,6 +280,14 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
     if (rc != LOT_OK) return rc;
     if (workspace_bytes < need) return LOT_ERR_WORKSPACE;
     const lot_shape fs = fused_view(*shape);
+    // pivot sizes beyond one register tile: the grouped kernels stand in for the fused one
+    if (grouped_supports(fs) && (path == LOT_PATH_AUTO || path == LOT_PATH_FUSED)) {
+        Args ga{};
+        ga.s = fs; ga.Q = Q; ga.K = K; ga.V = V; ga.Z = Z; ga.beta = beta; ga.eps = eps; ga.iters = iters; ga.out = out;
+        ga.ws = (char*)workspace; ga.stream = (hipStream_t)hip_stream;
+        ga.n_q = shape->n_q; ga.n_k = shape->n_k; ga.mass_q = mass_q; ga.mass_k = mass_k;
+        return run_grouped(ga);
+    }
     bool fused = false;
     rc = pick_path(fs, path, &fused);
     if (rc != LOT_OK) return rc;

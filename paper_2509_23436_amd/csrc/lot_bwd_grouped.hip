@@ -166,13 +166,13 @@ __global__ void __launch_bounds__(kThreads, 2) gb_contract(GbParams p)
         const int tok = min(tile * kTileTokens + i, n - 1);
         const float L = tile * kTileTokens + i < n ? lse[tok] : INFINITY;
         Frag<IO, D> xc;
-        load_tokens<D>(xc, X + ((size_t)g * p.f.n_stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         bf16x8 vh[2][NB], vl[2][NB];
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
             const int left = max(1, min(8, n - t0));
-            load_values<D>(vh[s], vl[s], vals, (size_t)g * p.f.n_stride + min(t0, n - 1), left, i);
+            load_values<D>(vh[s], vl[s], vals, (size_t)g * p.f.stride_side[side] + min(t0, n - 1), left, i);
         }
         f32x16 acc[2];
         weights_from_lse<IO, D>(acc, s_zstash, s_g, xc, L, lane, kg, c1);
@@ -279,8 +279,8 @@ __global__ void __launch_bounds__(64 * kGlueWaves) gb_glue(GbParams p)
         const int tok = min(tile * kTileTokens + i, n - 1);
         const float L = valid ? lse[tok] : INFINITY;
         Frag<IO, D> xc, vc;
-        load_tokens<D>(xc, X + ((size_t)g * p.f.n_stride + tok) * D, kg);
-        load_tokens<D>(vc, vals + ((size_t)g * p.f.n_stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         float q0 = 0.f, q1 = 0.f;
 #pragma unroll
         for (int q = 0; q < kMaxGroups; ++q) {
@@ -393,7 +393,7 @@ __global__ void __launch_bounds__(kThreads, 2) gb_rec_pass(GbParams p, int k)
         const float L = valid ? lse[tok] : INFINITY;
         const float e_in = k == T ? erow[tok] : 0.f;         // n q_i from the glue
         Frag<IO, D> xc;
-        load_tokens<D>(xc, X + ((size_t)g * p.f.n_stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         f32x16 wt[kMaxGroups][2];
         float y0 = 0.f, y1 = 0.f;
 #pragma unroll
@@ -606,8 +606,8 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
         const bool valid = tile * kTileTokens + i < n;
         const int tok = min(tile * kTileTokens + i, n - 1);
         Frag<IO, D> xc, vc;
-        load_tokens<D>(xc, X + ((size_t)g * p.f.n_stride + tok) * D, kg);
-        load_tokens<D>(vc, vals + ((size_t)g * p.f.n_stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         f32x16 o[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -627,7 +627,7 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
         }
         IO* out = reinterpret_cast<IO*>(side == 0 ? p.dQ : p.dK);
         const int row0 = tile * kTileTokens + 4 * kg;
-        IO* const lane_base = out + ((size_t)g * p.f.n_stride + row0) * D;
+        IO* const lane_base = out + ((size_t)g * p.f.stride_side[side] + row0) * D;
 #pragma unroll
         for (int j = 0; j < 16; ++j)
             if (row0 + 8 * (j >> 2) + (j & 3) < n)
@@ -694,8 +694,8 @@ __global__ void __launch_bounds__(kThreads, 2) gb_assemble_z(GbParams p)
         const bool valid = tile * kTileTokens + i < n;
         const int tok = min(tile * kTileTokens + i, n - 1);
         Frag<IO, D> xc, vc;
-        load_tokens<D>(xc, X + ((size_t)g * p.f.n_stride + tok) * D, kg);
-        load_tokens<D>(vc, vals + ((size_t)g * p.f.n_stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
+        load_tokens<D>(vc, vals + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         f32x16 dacc[2];
         similarity_gradient<IO, D>(dacc, s_zstash, s_yhi, s_ylo, s_hist, s_bvec, s_shift, xc, vc, lse, erow, per_k, tok, valid,
                                    T, c1, scale_out, lane, kg);
@@ -704,7 +704,7 @@ __global__ void __launch_bounds__(kThreads, 2) gb_assemble_z(GbParams p)
         for (int s = 0; s < 2; ++s) {
             const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
             const int left = max(1, min(8, n - t0));
-            load_values<D>(vh[s], vl[s], X, (size_t)g * p.f.n_stride + min(t0, n - 1), left, i);
+            load_values<D>(vh[s], vl[s], X, (size_t)g * p.f.stride_side[side] + min(t0, n - 1), left, i);
         }
         transpose_tile<2, kSplit>(dacc, tr_hi, tr_lo, i, kg);
         contract_tokens<D, 2, kSplit>(dZacc, tr_hi, tr_lo, vh, vl, i, kg);
@@ -876,7 +876,12 @@ int run_backward_grouped(const BwdArgs& a)
     p.db_glue = (float*)(a.ws + L.db_glue);
     p.dz_part = (float*)(a.ws + L.dz_part);
     p.B = s.B;
-    p.f.G = s.B * s.H; p.f.H = s.H; p.f.n = s.n; p.f.n_stride = a.n_stride > 0 ? a.n_stride : s.n; p.f.r = s.r;
+    p.f.G = s.B * s.H; p.f.H = s.H; p.f.n = s.n; p.f.r = s.r;
+    for (int sd = 0; sd < 2; ++sd) {
+        p.f.n_side[sd] = s.n;
+        p.f.stride_side[sd] = a.n_stride > 0 ? a.n_stride : s.n;
+        p.f.mass_side[sd] = nullptr;
+    }
     p.f.groups = (s.r + kGroup - 1) / kGroup; p.f.chunks = L.chunks; p.f.tiles_per_wg = lg_tiles_per_wg(s); p.f.T = a.iters;
     p.f.eps = a.eps;
     {

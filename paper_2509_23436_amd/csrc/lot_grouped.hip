@@ -41,7 +41,8 @@ __global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
     if (!group_block(wg, grp, p.G * p.chunks, p.groups)) return;
     const int g = wg / p.chunks, chunk = wg % p.chunks;
     const int pair = p.G + g, h = g % p.H;
-    const int n = p.n;
+    const int n = p.n_side[1], stride = p.stride_side[1];
+    const float* const mass = p.mass_side[1];     // the keys' masses times n weight the reduction
     const float c1 = kLog2e / p.eps;
     const IO* X = reinterpret_cast<const IO*>(p.K);
     const IO* vals = reinterpret_cast<const IO*>(p.V);
@@ -50,7 +51,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
     const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
 
-    const float* lse = last_lse(p) + (size_t)pair * n;
+    const float* lse = last_lse(p) + (size_t)pair * p.n;
     load_potentials(p, s_g, p.T, pair, h, false, tid);
     stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
     __syncthreads();
@@ -65,17 +66,24 @@ __global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
     for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
         const int tok = min(tile * kTileTokens + i, n - 1);
         Frag<IO, D> xc;
-        load_tokens<D>(xc, X + ((size_t)g * p.n_stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * stride + tok) * D, kg);
         bf16x8 vh[2][NB], vl[2][NB];
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
             const int left = max(1, min(8, n - t0));
-            load_values<D>(vh[s], vl[s], vals, (size_t)g * p.n_stride + min(t0, n - 1), left, i);
+            load_values<D>(vh[s], vl[s], vals, (size_t)g * stride + min(t0, n - 1), left, i);
         }
         const float L = tile * kTileTokens + i < n ? lse[tok] : INFINITY;
         f32x16 acc[2];
         weights_from_lse<IO, D>(acc, s_zstash + (size_t)grp * StashBytes<IO, D, 2>::value, s_g + kGroup * grp, xc, L, lane, kg, c1);
+        if (mass) {
+            const float mt = (float)n * mass[(size_t)g * n + tok];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[mb][j] *= mt;
+        }
         transpose_tile<2, kSplit>(acc, tr_hi, tr_lo, i, kg);
         contract_tokens<D, 2, kSplit>(U, tr_hi, tr_lo, vh, vl, i, kg);
         transpose_done();
@@ -104,7 +112,7 @@ __global__ void lg_mid(LgParams p)
         if (c < p.chunks) u0 += up[(size_t)c * kRmax * D];
         const float cs1 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * kRmax + t] * p.fx_unscale, 0.5f * p.fx_unscale);
         const float cs2 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * kRmax + t] * p.fx_unscale, 0.5f * p.fx_unscale);
-        y = ((float)p.n * p.beta[(g % p.H) * p.r + t] / cs1) * ((u0 + u1) / cs2);
+        y = ((float)p.n_side[0] * p.beta[(g % p.H) * p.r + t] / cs1) * ((u0 + u1) / cs2);
     }
     p.ypp[idx] = y;
 }
@@ -171,7 +179,11 @@ int run_grouped(const Args& a)
     p.u_part = (float*)(a.ws + L.u_part);
     p.ypp = (float*)(a.ws + L.ypp);
     p.rowlse = (float*)(a.ws + L.rowlse); p.rowlse_all = 0;
-    p.G = s.B * s.H; p.H = s.H; p.n = s.n; p.n_stride = a.n_stride > 0 ? a.n_stride : s.n; p.r = s.r;
+    p.G = s.B * s.H; p.H = s.H; p.n = s.n; p.r = s.r;
+    p.n_side[0] = a.n_q > 0 ? a.n_q : s.n;      // s.n is the longer side (cross attention)
+    p.n_side[1] = a.n_k > 0 ? a.n_k : s.n;
+    for (int sd = 0; sd < 2; ++sd) p.stride_side[sd] = a.n_stride > 0 ? a.n_stride : p.n_side[sd];
+    p.mass_side[0] = a.mass_q; p.mass_side[1] = a.mass_k;
     p.groups = (s.r + kGroup - 1) / kGroup; p.chunks = L.chunks; p.tiles_per_wg = lg_tiles_per_wg(s); p.T = a.iters;
     p.eps = a.eps;
     {

@@ -27,7 +27,11 @@ struct LgParams {
     float* ypp;                   // [G][256][D]  Y''
     float* rowlse;                // base-2 log-normaliser L_i of every row: [T][pairs][n], pass k at k - 1 (rowlse_all), or
     int rowlse_all;               // [pairs][n] of the last pass only; W_it = exp2((C_it + g_t) c1 - L_i)
-    int G, H, n, n_stride, r, groups, chunks, tiles_per_wg, k, T;
+    int G, H, n, r, groups, chunks, tiles_per_wg, k, T;   // n: the longer side (layout of the per-token arrays, chunking)
+    // per side (0 = queries and the output, 1 = keys and values):
+    int n_side[2];                // tokens per problem
+    int stride_side[2];           // tokens between consecutive problems in the caller's tensors (>= n_side)
+    const float* mass_side[2];    // [G][n_side] token masses, or null: uniform 1/n_side
     float eps, fx_scale, fx_unscale;
 };
 
@@ -81,7 +85,7 @@ __device__ __forceinline__ void load_potentials(const LgParams& p, float* s_g, i
             const unsigned long long word = p.colacc[((size_t)(k - 1) * pairs + pair) * kRmax + t];
             // (a sum below the fixed-point resolution reads as half a unit: the potentials stay bounded)
             const float cs = fmaxf((float)(long long)word * p.fx_unscale, 0.5f * p.fx_unscale);
-            gv = p.ghist[((size_t)(k - 2) * pairs + pair) * kRmax + t] + p.eps * logf((float)p.n * p.beta[h * p.r + t] / cs);
+            gv = p.ghist[((size_t)(k - 2) * pairs + pair) * kRmax + t] + p.eps * logf((float)p.n_side[pair / p.G] * p.beta[h * p.r + t] / cs);
         }
         s_g[t] = gv;
         if (keep) p.ghist[((size_t)(k - 1) * pairs + pair) * kRmax + t] = gv;
@@ -133,7 +137,8 @@ __global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
     const int pairs = 2 * p.G;
     const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
     const int side = pair / p.G, g = pair % p.G, h = g % p.H;
-    const int n = p.n, k = p.k;
+    const int n = p.n_side[side], stride = p.stride_side[side], k = p.k;
+    const float* const mass = p.mass_side[side];     // token masses times n weight the column sums
     const float c1 = kLog2e / p.eps;
     const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.Q : p.K);
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
@@ -142,7 +147,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
     Frag<IO, D> xc;
     {
         const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
-        load_tokens<D>(xc, X + ((size_t)g * p.n_stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * stride + tok) * D, kg);
     }
     load_potentials(p, s_g, k, pair, h, chunk == 0, tid);
     stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
@@ -154,7 +159,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
         Frag<IO, D> xn = xc;
         if (tile + kWaves < tile_end) {
             const int tok = min((tile + kWaves) * kTileTokens + i, n - 1);
-            load_tokens<D>(xn, X + ((size_t)g * p.n_stride + tok) * D, kg);
+            load_tokens<D>(xn, X + ((size_t)g * stride + tok) * D, kg);
         }
         // similarities (plus potentials) of all groups stay in registers between the row reduction and the
         // exponentials: one exponential per element
@@ -197,7 +202,8 @@ __global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
         const bool valid = tile * kTileTokens + i < n;
         const float rowsum = pair_sum(s0 + s1);
         const float w = valid ? rcp_fast(rowsum) : 0.f;
-        if (lse_keep && kg == 0 && valid) lse_keep[(size_t)pair * n + tile * kTileTokens + i] = mc + __builtin_amdgcn_logf(rowsum);
+        if (lse_keep && kg == 0 && valid) lse_keep[(size_t)pair * p.n + tile * kTileTokens + i] = mc + __builtin_amdgcn_logf(rowsum);
+        const float wm = mass ? w * ((float)n * mass[(size_t)g * n + min(tile * kTileTokens + i, n - 1)]) : w;
 #pragma unroll
         for (int q = 0; q < kMaxGroups; ++q) {
             if (q < p.groups) {
@@ -205,7 +211,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) c[16 * mb + j] = acc[q][mb][j] * w;
+                    for (int j = 0; j < 16; ++j) c[16 * mb + j] = acc[q][mb][j] * wm;
                 csg[q] += reduce_scatter_tokens<32>(c, i);
             }
         }
@@ -243,7 +249,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 31, kg = lane >> 5;
     const int g = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks, h = g % p.H;
-    const int n = p.n;
+    const int n = p.n_side[side], stride = p.stride_side[side];
     const float c1 = kLog2e / p.eps;
     const IO* X = reinterpret_cast<const IO*>(rows);
     char* s_zstash = s_dyn;
@@ -251,7 +257,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
     const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
 
-    const float* lse = last_lse(p) + (size_t)(side * p.G + g) * n;
+    const float* lse = last_lse(p) + (size_t)(side * p.G + g) * p.n;
     load_potentials(p, s_g, p.T, side * p.G + g, h, false, tid);
     stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
     for (int q = 0; q < p.groups; ++q) {
@@ -264,7 +270,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
     for (int tile = tile_begin + wave; tile < tile_end; tile += kWaves) {
         const int tok = min(tile * kTileTokens + i, n - 1);
         Frag<IO, D> xc;
-        load_tokens<D>(xc, X + ((size_t)g * p.n_stride + tok) * D, kg);
+        load_tokens<D>(xc, X + ((size_t)g * stride + tok) * D, kg);
         const float L = tile * kTileTokens + i < n ? lse[tok] : INFINITY;
         f32x16 o[NB];
 #pragma unroll
@@ -283,7 +289,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
         }
         IO* out = reinterpret_cast<IO*>(out_rows);
         const int row0 = tile * kTileTokens + 4 * kg;
-        IO* const lane_base = out + ((size_t)g * p.n_stride + row0) * D;
+        IO* const lane_base = out + ((size_t)g * stride + row0) * D;
 #pragma unroll
         for (int j = 0; j < 16; ++j)
             if (row0 + 8 * (j >> 2) + (j & 3) < n)

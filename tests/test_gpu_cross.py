@@ -41,11 +41,18 @@ CASES = {
     "long_keys_bf16": dict(B=2, H=4, n_q=1024, n_k=9000, d=64, d_v=64, r=64, seed=506, bf16=True, masses="padded", eps=0.05, iters=6),
     "long_queries_bf16": dict(B=2, H=4, n_q=9000, n_k=500, d=64, d_v=64, r=32, seed=507, bf16=True, masses="uniform", eps=0.05, iters=6),
     "other_dims": dict(B=1, H=2, n_q=60, n_k=90, d=16, d_v=24, r=80, seed=505, bf16=False, masses="random", eps=0.1, iters=4),
+    # more than 64 pivots: the grouped tile kernels with per-side sizes and masses (the last group ragged)
+    "grouped_f32_r100": dict(B=1, H=2, n_q=150, n_k=333, d=32, d_v=32, r=100, seed=520, bf16=False, masses="random", eps=0.1, iters=5),
+    "grouped_padded_f32_r128": dict(B=2, H=2, n_q=400, n_k=197, d=64, d_v=64, r=128, seed=521, bf16=False, masses="padded", eps=0.1, iters=4),
+    "grouped_bf16_r256": dict(B=1, H=2, n_q=700, n_k=2100, d=64, d_v=64, r=256, seed=522, bf16=True, masses="padded", eps=0.05, iters=5),
+    "grouped_uniform_bf16_r130": dict(B=2, H=1, n_q=3000, n_k=500, d=32, d_v=32, r=130, seed=523, bf16=True, masses="uniform", eps=0.1, iters=6),
 }
 
 
-def _paths(c):
-    fused = c["d"] == c["d_v"] and c["d"] in (32, 64) and c["r"] <= 64
+def _paths(c, backward=False):
+    tiles = c["d"] == c["d_v"] and c["d"] in (32, 64)
+    # forward: one register tile up to 64 pivots, groups of 64 up to 256; backward with masses / two sizes: up to 64
+    fused = tiles and c["r"] <= (64 if backward else 256)
     return ["reference", "fused"] if fused else ["reference"]
 
 
@@ -98,7 +105,7 @@ BWD_CASES = {
 }
 
 
-@pytest.mark.parametrize("name,path_name", [(nm, pn) for nm in BWD_CASES for pn in _paths(BWD_CASES[nm])])
+@pytest.mark.parametrize("name,path_name", [(nm, pn) for nm in BWD_CASES for pn in _paths(BWD_CASES[nm], backward=True)])
 def test_cross_backward_matches_oracle(name, path_name):
     import torch
     from oracle import lot_oracle_bwd
