@@ -195,8 +195,8 @@ int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K,
  * dK [B,H,n_k,d_k], dV [B,H,n_k,d_v] in io_dtype and dZ, dbeta in fp32 (summed over the batch).  The
  * masses are data (a padding mask), not differentiated; a key of mass zero receives exactly zero
  * gradient, a query of mass zero the gradient of its own output row.  Execution paths as for
- * lot_attention_bwd, except that with token masses or n_q != n_k the FUSED path ends at r <= 64
- * (iters <= 32); AUTO prefers it.
+ * lot_attention_bwd (FUSED: the tile kernels, r <= 64 in one register tile or 64 < r <= 256 in groups of
+ * 64, within the same limits); AUTO prefers it.
  * Workspace: lot_cross_attention_bwd_workspace_bytes (covers both paths); contents on entry do not
  * matter; lot_workspace_status applies.  Reproducible bit for bit on either path.
  */

@@ -407,6 +407,10 @@ int lot_cross_attention_bwd_workspace_bytes(const lot_xshape* shape, int iters, 
         const size_t tiled = carve_bwd_tiled(longer, iters).total;
         if (tiled > need) need = tiled;
     }
+    if (bwd_grouped_supports(longer, iters)) {
+        const size_t grouped = carve_bwd_grouped(longer, iters).total;
+        if (grouped > need) need = grouped;
+    }
     *bytes_out = need;
     return LOT_OK;
 }
@@ -437,19 +441,20 @@ int lot_cross_attention_bwd_path(const lot_xshape* shape, const void* Q, const v
     a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
     a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
     a.n_q = shape->n_q; a.n_k = shape->n_k; a.mass_q = mass_q; a.mass_k = mass_k;
+    const bool one_tile = bwd_tiled_supports(s, iters), grouped = bwd_grouped_supports(s, iters);
     bool tiled = false;
     switch (path) {
     case LOT_PATH_AUTO:
-        tiled = bwd_tiled_supports(s, iters) && shape->n_q >= kMinTiledTokens && shape->n_k >= kMinTiledTokens;
+        tiled = (one_tile || grouped) && shape->n_q >= kMinTiledTokens && shape->n_k >= kMinTiledTokens;
         break;
     case LOT_PATH_REFERENCE: tiled = false; break;
     case LOT_PATH_FUSED:
-        if (!bwd_tiled_supports(s, iters)) return LOT_ERR_PATH;
+        if (!one_tile && !grouped) return LOT_ERR_PATH;
         tiled = true;
         break;
     default: return LOT_ERR_PATH;
     }
-    if (tiled) return run_backward_tiled(a);
+    if (tiled) return one_tile ? run_backward_tiled(a) : run_backward_grouped(a);
     a.lay = carve_bwd_sides(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_k, shape->d_v, iters);
     return run_backward(a);
 }

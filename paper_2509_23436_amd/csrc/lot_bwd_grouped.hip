@@ -1,5 +1,5 @@
 // Backward pass of LOT attention for pivot sizes beyond one register tile: 64 < r <= 256, d_k = d_v in
-// {32, 64}, uniform token masses.  Same gradients as the other backward paths; nothing of size n x r is
+// {32, 64}; per-side token counts and token masses as in cross attention.  Same gradients as the other backward paths; nothing of size n x r is
 // written.  The pivots are taken in groups of 64, as in the forward pass for these sizes.
 //
 // Notation as in the tiled backward path: per solve, W^k_it = softmax_t((C_it + g^{k-1}_t)/eps) is the
@@ -54,6 +54,13 @@ struct GbParams {
     float* dz_part;               // [pairs][chunks][256][D]
     int B;
 };
+
+// Mass of a token times the number of tokens of its side (1 for uniform masses).
+__device__ __forceinline__ float gb_token_weight(const GbParams& p, int side, int g, int tok)
+{
+    const float* m = p.f.mass_side[side];
+    return m ? (float)p.f.n_side[side] * m[(size_t)g * p.f.n_side[side] + tok] : 1.f;
+}
 
 __device__ __forceinline__ float gb_colsum(const GbParams& p, int k, int pair, int t)
 {
@@ -141,11 +148,11 @@ __global__ void __launch_bounds__(kThreads, 2) gb_contract(GbParams p)
     if (!group_block(wg, grp, pairs * p.f.chunks, p.f.groups)) return;
     const int pair = wg / p.f.chunks, chunk = wg % p.f.chunks;
     const int side = pair / p.f.G, g = pair % p.f.G, h = g % p.f.H;
-    const int n = p.f.n;
+    const int n = p.f.n_side[side];        // tokens of this side (p.f.n, the longer side, strides the per-token arrays)
     const float c1 = kLog2e / p.f.eps;
     const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.f.Q : p.f.K);
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.f.V);
-    const float* lse = p.f.rowlse + ((size_t)(T - 1) * pairs + pair) * n;
+    const float* lse = p.f.rowlse + ((size_t)(T - 1) * pairs + pair) * p.f.n;
     uint16_t* tr_hi = s_tr + (wave * 2 + 0) * 64 * kTrStride;
     uint16_t* tr_lo = s_tr + (wave * 2 + 1) * 64 * kTrStride;
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
@@ -176,6 +183,13 @@ __global__ void __launch_bounds__(kThreads, 2) gb_contract(GbParams p)
         }
         f32x16 acc[2];
         weights_from_lse<IO, D>(acc, s_zstash, s_g, xc, L, lane, kg, c1);
+        if (side == 1 && p.f.mass_side[1]) {      // the keys' masses weight their contraction with V
+            const float mt = gb_token_weight(p, 1, g, tok);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[mb][j] *= mt;
+        }
         transpose_tile<2, kSplit>(acc, tr_hi, tr_lo, i, kg);
         contract_tokens<D, 2, kSplit>(U, tr_hi, tr_lo, vh, vl, i, kg);
         transpose_done();
@@ -209,7 +223,7 @@ __global__ void gb_mid(GbParams p)
         if (c < chunks) { w0 += wp[(size_t)c * kRmax * D]; u0 += up[(size_t)c * kRmax * D]; }
         const float cs1 = gb_colsum(p, T, g, t), cs2 = gb_colsum(p, T, G + g, t);
         y = (u0 + u1) / cs2;
-        dy = (float)p.f.n * (w0 + w1) / cs1;
+        dy = (float)p.f.n_side[0] * (w0 + w1) / cs1;
         const float b = p.f.beta[(g % p.f.H) * p.f.r + t];
         r1 = b / cs1;
         r2 = b / cs2;
@@ -248,15 +262,15 @@ __global__ void __launch_bounds__(64 * kGlueWaves) gb_glue(GbParams p)
     const int pairs = 2 * p.f.G, T = p.f.T, groups = p.f.groups;
     const int pair = blockIdx.x / p.f.chunks, chunk = blockIdx.x % p.f.chunks;
     const int side = pair / p.f.G, g = pair % p.f.G, h = g % p.f.H;
-    const int n = p.f.n;
+    const int n = p.f.n_side[side];        // tokens of this side (p.f.n, the longer side, strides the per-token arrays)
     const float c1 = kLog2e / p.f.eps;
     const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.f.Q : p.f.K);
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.f.V);
     // the matrix whose rows meet the value rows: n Y' for the queries, dYraw for the keys
     const float* ymat = (side == 0 ? p.yp : p.dyraw) + (size_t)g * kRmax * D;
     const float yscale = side == 0 ? (float)n : 1.f;
-    const float* lse = p.f.rowlse + ((size_t)(T - 1) * pairs + pair) * n;
-    float* erow = p.erow + ((size_t)(T - 1) * pairs + pair) * n;
+    const float* lse = p.f.rowlse + ((size_t)(T - 1) * pairs + pair) * p.f.n;
+    float* erow = p.erow + ((size_t)(T - 1) * pairs + pair) * p.f.n;
     char* s_zstash = s_dyn;
     char* s_yhi = s_dyn + (size_t)groups * kStash;
     char* s_ylo = s_yhi + (size_t)groups * kStash;
@@ -282,6 +296,7 @@ __global__ void __launch_bounds__(64 * kGlueWaves) gb_glue(GbParams p)
         load_tokens<D>(xc, X + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         load_tokens<D>(vc, vals + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         float q0 = 0.f, q1 = 0.f;
+        const float mk = side == 1 ? gb_token_weight(p, 1, g, tok) : 1.f;
 #pragma unroll
         for (int q = 0; q < kMaxGroups; ++q) {
             if (q < groups) {
@@ -294,7 +309,8 @@ __global__ void __launch_bounds__(64 * kGlueWaves) gb_glue(GbParams p)
                 for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                     for (int j = 0; j < 16; j += 2) {
-                        const float a0 = acc[mb][j] * dgam[mb][j], a1 = acc[mb][j + 1] * dgam[mb][j + 1];
+                        // (mk: the key's mass times n_k, 1 for queries: dGamma2 carries the keys' masses)
+                        const float a0 = acc[mb][j] * dgam[mb][j] * mk, a1 = acc[mb][j + 1] * dgam[mb][j + 1] * mk;
                         c[16 * mb + j] = a0; c[16 * mb + j + 1] = a1;
                         q0 = fmaf(a0, rho[mb][j], q0);
                         q1 = fmaf(a1, rho[mb][j + 1], q1);
@@ -336,11 +352,11 @@ __global__ void __launch_bounds__(kThreads, 2) gb_rec_pass(GbParams p, int k)
     const int pairs = 2 * p.f.G, T = p.f.T, groups = p.f.groups, chunks = p.f.chunks;
     const int pair = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
     const int side = pair / p.f.G, g = pair % p.f.G, h = g % p.f.H;
-    const int n = p.f.n;
+    const int n = p.f.n_side[side];        // tokens of this side (p.f.n, the longer side, strides the per-token arrays)
     const float c1 = kLog2e / p.f.eps, a = 1.f / (float)n;
     const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.f.Q : p.f.K);
-    const float* lse = p.f.rowlse + ((size_t)(k - 1) * pairs + pair) * n;
-    float* erow = p.erow + ((size_t)(k - 1) * pairs + pair) * n;
+    const float* lse = p.f.rowlse + ((size_t)(k - 1) * pairs + pair) * p.f.n;
+    float* erow = p.erow + ((size_t)(k - 1) * pairs + pair) * p.f.n;
 
     static_assert(kThreads == kRmax, "one thread per pivot in the prologue");
     {
@@ -411,7 +427,7 @@ __global__ void __launch_bounds__(kThreads, 2) gb_rec_pass(GbParams p, int k)
                     }
             }
         }
-        const float e = pair_sum(y0 + y1) + e_in;
+        const float e = gb_token_weight(p, side, g, tok) * pair_sum(y0 + y1) + e_in;    // dP^k_it = m_i dc^k_t (+ the glue's part)
         if (valid && kg == 0) erow[tok] = e;
         if (k > 1) {
 #pragma unroll
@@ -455,7 +471,7 @@ __device__ __forceinline__ void similarity_gradient(f32x16 (&dacc)[2], const cha
                                                     const float* tab, const float* bvec, const float* shifts,
                                                     const Frag<IO, D>& xc, const Frag<IO, D>& vc,
                                                     const float* lse, const float* erow, size_t per_k, int tok, bool valid,
-                                                    int T, float c1, float scale_out, int lane, int kg)
+                                                    float m_tok, float m_key, int T, float c1, float scale_out, int lane, int kg)
 {
     int skew = 0;
     asm volatile("" : "+v"(skew));
@@ -500,7 +516,7 @@ __device__ __forceinline__ void similarity_gradient(f32x16 (&dacc)[2], const cha
         float R, S;
         row_factors(k, R, S);
         r_last = R;
-        const float b = kg ? R : -S;
+        const float b = kg ? R * m_tok : -S;        // dP^k_it = m_i dc^k_t
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
             const float a = tab[((k - 1) * 2 + kg) * kGroup + 32 * mb + i + skew];
@@ -516,7 +532,7 @@ __device__ __forceinline__ void similarity_gradient(f32x16 (&dacc)[2], const cha
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-                dacc[mb][j] = E[mb][j] * scale_out * fmaf(r_last * bv[mb][j], dgam[mb][j], dacc[mb][j]);
+                dacc[mb][j] = E[mb][j] * scale_out * fmaf(r_last * m_key * bv[mb][j], dgam[mb][j], dacc[mb][j]);
     }
 }
 
@@ -531,7 +547,7 @@ __device__ __forceinline__ void load_tables(float* tab, float* bvec, const GbPar
         const float P = exp2_fast(p.f.ghist[((size_t)(k - 1) * pairs + pair) * kRmax + t0 + t] * c1 - h);   // padding: 0
         tab[((k - 1) * 2 + 0) * kGroup + t] = P;
         tab[((k - 1) * 2 + 1) * kGroup + t] = P * p.dcs[((size_t)(k - 1) * pairs + pair) * kRmax + t0 + t];
-        if (k == T) bvec[t] = P * (float)p.f.n * p.rhop[(size_t)pair * kRmax + t0 + t];
+        if (k == T) bvec[t] = P * (float)p.f.n_side[pair / p.f.G] * p.rhop[(size_t)pair * kRmax + t0 + t];
     }
 }
 
@@ -559,15 +575,15 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
     const int pairs = 2 * p.f.G, T = p.f.T, groups = p.f.groups;
     const int pair = blockIdx.x / p.f.chunks, chunk = blockIdx.x % p.f.chunks;
     const int side = pair / p.f.G, g = pair % p.f.G, h = g % p.f.H;
-    const int n = p.f.n, r = p.f.r;
+    const int n = p.f.n_side[side], r = p.f.r;
     const float c1 = kLog2e / p.f.eps;
     const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.f.Q : p.f.K);
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.f.V);
     const float* ymat = (side == 0 ? p.yp : p.dyraw) + (size_t)g * kRmax * D;
     const float yscale = side == 0 ? (float)n : 1.f;
-    const size_t per_k = (size_t)pairs * n;
-    const float* lse = p.f.rowlse + (size_t)pair * n;
-    const float* erow = p.erow + (size_t)pair * n;
+    const size_t per_k = (size_t)pairs * p.f.n;
+    const float* lse = p.f.rowlse + (size_t)pair * p.f.n;
+    const float* erow = p.erow + (size_t)pair * p.f.n;
     float* s_y = reinterpret_cast<float*>(s_dyn);
     float* s_hist = reinterpret_cast<float*>(s_dyn);
     char* s_zstash = s_dyn + stage_bytes;
@@ -608,6 +624,7 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
         Frag<IO, D> xc, vc;
         load_tokens<D>(xc, X + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         load_tokens<D>(vc, vals + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
+        const float m_tok = gb_token_weight(p, side, g, tok);
         f32x16 o[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -617,7 +634,8 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
             f32x16 dacc[2], part[NB];
             similarity_gradient<IO, D>(dacc, s_zstash + (size_t)q * kStash, s_yhi + (size_t)q * kStash,
                                        s_ylo + (size_t)q * kStash, s_hist + (size_t)q * T * 2 * kGroup, s_bvec + kGroup * q,
-                                       s_shift, xc, vc, lse, erow, per_k, tok, valid, T, c1, scale_out, lane, kg);
+                                       s_shift, xc, vc, lse, erow, per_k, tok, valid, m_tok, side == 1 ? m_tok : 1.f, T, c1, scale_out,
+                                       lane, kg);
             const bf16x8* hi = s_zf + (size_t)(kParts * q) * kFragsPerGroup;
             contract_pivots<D, 2, kSplit>(part, dacc, hi, kSplit ? hi + kFragsPerGroup : hi, lane);
 #pragma unroll
@@ -662,15 +680,15 @@ __global__ void __launch_bounds__(kThreads, 2) gb_assemble_z(GbParams p)
     if (!group_block(wg, grp, pairs * p.f.chunks, p.f.groups)) return;
     const int pair = wg / p.f.chunks, chunk = wg % p.f.chunks;
     const int side = pair / p.f.G, g = pair % p.f.G, h = g % p.f.H;
-    const int n = p.f.n;
+    const int n = p.f.n_side[side];        // tokens of this side (p.f.n, the longer side, strides the per-token arrays)
     const float c1 = kLog2e / p.f.eps;
     const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.f.Q : p.f.K);
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.f.V);
     const float* ymat = (side == 0 ? p.yp : p.dyraw) + ((size_t)g * kRmax + (size_t)kGroup * grp) * D;
     const float yscale = side == 0 ? (float)n : 1.f;
-    const size_t per_k = (size_t)pairs * n;
-    const float* lse = p.f.rowlse + (size_t)pair * n;
-    const float* erow = p.erow + (size_t)pair * n;
+    const size_t per_k = (size_t)pairs * p.f.n;
+    const float* lse = p.f.rowlse + (size_t)pair * p.f.n;
+    const float* erow = p.erow + (size_t)pair * p.f.n;
     uint16_t* tr_hi = s_tr + (wave * kParts + 0) * 64 * kTrStride;
     uint16_t* tr_lo = s_tr + (wave * kParts + kParts - 1) * 64 * kTrStride;
 
@@ -697,8 +715,9 @@ __global__ void __launch_bounds__(kThreads, 2) gb_assemble_z(GbParams p)
         load_tokens<D>(xc, X + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         load_tokens<D>(vc, vals + ((size_t)g * p.f.stride_side[side] + tok) * D, kg);
         f32x16 dacc[2];
+        const float m_tok = gb_token_weight(p, side, g, tok);
         similarity_gradient<IO, D>(dacc, s_zstash, s_yhi, s_ylo, s_hist, s_bvec, s_shift, xc, vc, lse, erow, per_k, tok, valid,
-                                   T, c1, scale_out, lane, kg);
+                                   m_tok, side == 1 ? m_tok : 1.f, T, c1, scale_out, lane, kg);
         bf16x8 vh[2][NB], vl[2][NB];
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -798,7 +817,7 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
     }
     gb_contract<IO, D><<<group_grid(grid, groups), kThreads, 0, st>>>(p);
     gb_mid<D><<<(unsigned)(p.f.G * kRmax * D / 256), 256, 0, st>>>(p);
-    lg_expand<IO, D><<<(unsigned)p.f.G * p.f.chunks, kThreads, stash + frag_bytes, st>>>(p.f, 1, p.f.K, p.ydv, p.dV);
+    lg_expand<IO, D><<<(unsigned)p.f.G * p.f.chunks, kThreads, stash + frag_bytes, st>>>(p.f, 1, p.f.K, p.ydv, p.dV, 1);
     if (p.f.tiles_per_wg >= 32) gb_glue<IO, D, 8><<<grid, 512, glue_bytes, st>>>(p);
     else gb_glue<IO, D, 4><<<grid, 256, glue_bytes, st>>>(p);
     for (int k = T; k >= 1; --k) gb_rec_pass<IO, D><<<grid, kThreads, stash, st>>>(p, k);
@@ -853,7 +872,6 @@ int run_backward_grouped(const BwdArgs& a)
 {
     const lot_shape& s = a.s;
     if (!bwd_grouped_supports(s, a.iters)) return LOT_ERR_PATH;
-    if (a.mass_q || a.mass_k || (a.n_q > 0 && a.n_q != s.n) || (a.n_k > 0 && a.n_k != s.n)) return LOT_ERR_PATH;
     const BwdGroupedWorkspace L = carve_bwd_grouped(s, a.iters);
     GbParams p{};
     p.f.Q = a.Q; p.f.K = a.K; p.f.V = a.V; p.f.Z = a.Z; p.f.beta = a.beta; p.f.out = nullptr;
@@ -877,11 +895,10 @@ int run_backward_grouped(const BwdArgs& a)
     p.dz_part = (float*)(a.ws + L.dz_part);
     p.B = s.B;
     p.f.G = s.B * s.H; p.f.H = s.H; p.f.n = s.n; p.f.r = s.r;
-    for (int sd = 0; sd < 2; ++sd) {
-        p.f.n_side[sd] = s.n;
-        p.f.stride_side[sd] = a.n_stride > 0 ? a.n_stride : s.n;
-        p.f.mass_side[sd] = nullptr;
-    }
+    p.f.n_side[0] = a.n_q > 0 ? a.n_q : s.n;      // s.n is the longer side (cross attention)
+    p.f.n_side[1] = a.n_k > 0 ? a.n_k : s.n;
+    for (int sd = 0; sd < 2; ++sd) p.f.stride_side[sd] = a.n_stride > 0 ? a.n_stride : p.f.n_side[sd];
+    p.f.mass_side[0] = a.mass_q; p.f.mass_side[1] = a.mass_k;
     p.f.groups = (s.r + kGroup - 1) / kGroup; p.f.chunks = L.chunks; p.f.tiles_per_wg = lg_tiles_per_wg(s); p.f.T = a.iters;
     p.f.eps = a.eps;
     {

@@ -137,7 +137,7 @@ int launch_grouped(const Args& a, LgParams p)
     }
     lg_reduce<IO, D><<<group_grid((unsigned)p.G * p.chunks, p.groups), kThreads, stash, st>>>(p);
     lg_mid<D><<<(unsigned)((p.G * kRmax * D + 255) / 256), 256, 0, st>>>(p);
-    lg_expand<IO, D><<<(unsigned)p.G * p.chunks, kThreads, stash + frag_bytes, st>>>(p, 0, p.Q, p.ypp, p.out);
+    lg_expand<IO, D><<<(unsigned)p.G * p.chunks, kThreads, stash + frag_bytes, st>>>(p, 0, p.Q, p.ypp, p.out, 0);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }

@@ -233,10 +233,11 @@ __global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
 
 // ---------------------------------------------------------------------------------------------
 // expand: out_i = sum_t W_it Ymat_t over the tokens of one side (potentials g^{T-1} of that side).
-// Forward: side 0, Ymat = Y'', out = O.  Backward: side 1, Ymat_t = rho'_t dYraw_t, out = dV.
+// Forward: side 0, Ymat = Y'', out = O.  Backward: side 1, Ymat_t = rho'_t dYraw_t, out = dV, every row times
+// its token's mass times n (weight_rows).
 // ---------------------------------------------------------------------------------------------
 template <typename IO, int D>
-__global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, const void* rows, const float* ymat, void* out_rows)
+__global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, const void* rows, const float* ymat, void* out_rows, int weight_rows)
 {
     constexpr int NB = D / 32;
     constexpr bool kSplit = io_is_f32<IO>::value;
@@ -272,6 +273,7 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
         Frag<IO, D> xc;
         load_tokens<D>(xc, X + ((size_t)g * stride + tok) * D, kg);
         const float L = tile * kTileTokens + i < n ? lse[tok] : INFINITY;
+        const float mt = weight_rows && p.mass_side[side] ? (float)n * p.mass_side[side][(size_t)g * n + tok] : 1.f;
         f32x16 o[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -280,6 +282,12 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
         for (int q = 0; q < p.groups; ++q) {
             f32x16 acc[2], part[NB];
             weights_from_lse<IO, D>(acc, s_zstash + (size_t)q * StashBytes<IO, D, 2>::value, s_g + kGroup * q, xc, L, lane, kg, c1);
+            if (weight_rows) {
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) acc[mb][j] *= mt;
+            }
             contract_pivots<D, 2, kSplit>(part, acc, yf + (size_t)(2 * q) * kFragsPerGroup,
                                           yf + (size_t)(2 * q + 1) * kFragsPerGroup, lane);
 #pragma unroll

@@ -51,8 +51,9 @@ CASES = {
 
 def _paths(c, backward=False):
     tiles = c["d"] == c["d_v"] and c["d"] in (32, 64)
-    # forward: one register tile up to 64 pivots, groups of 64 up to 256; backward with masses / two sizes: up to 64
-    fused = tiles and c["r"] <= (64 if backward else 256)
+    # one register tile up to 64 pivots, groups of 64 up to 256 (backward: as far as its tables fit local memory)
+    limit = 256 if (not backward or c["bf16"] or c["d"] == 32) else 128
+    fused = tiles and c["r"] <= limit
     return ["reference", "fused"] if fused else ["reference"]
 
 
@@ -102,6 +103,11 @@ BWD_CASES = {
     # several chunks per pair on both sides, a different number of tiles on each
     "long_keys_bf16": dict(B=2, H=4, n_q=1024, n_k=6000, d=64, d_v=64, r=64, seed=517, bf16=True, masses="padded", eps=0.05, iters=4),
     "long_queries_f32": dict(B=1, H=2, n_q=5000, n_k=300, d=32, d_v=32, r=16, seed=518, bf16=False, masses="random", eps=0.1, iters=4),
+    # more than 64 pivots: the grouped tile kernels with per-side sizes and masses
+    "grouped_f32_r100": dict(B=1, H=2, n_q=150, n_k=333, d=32, d_v=32, r=100, seed=530, bf16=False, masses="random", eps=0.1, iters=5),
+    "grouped_padded_f32_r128": dict(B=2, H=2, n_q=400, n_k=197, d=64, d_v=64, r=128, seed=531, bf16=False, masses="padded", eps=0.1, iters=4),
+    "grouped_bf16_r256": dict(B=1, H=2, n_q=700, n_k=2100, d=64, d_v=64, r=256, seed=532, bf16=True, masses="padded", eps=0.05, iters=5),
+    "grouped_uniform_bf16_r130": dict(B=2, H=1, n_q=3000, n_k=500, d=32, d_v=32, r=130, seed=533, bf16=True, masses="uniform", eps=0.1, iters=6),
 }
 
 
