@@ -6,9 +6,11 @@ library, so only the inputs are kept between the two calls.
 
     O = lot_attention(Q, K, V, Z, beta, eps, iters)            # Q, K, V [B,H,n,d], Z [H,r,d], beta [H,r]
     O = lot_attention_cls(Q, K, V, Z, beta, eps, iters, beta_cls)
+    O = lot_cross_attention(Q, K, V, Z, beta, eps, iters, mass_q=None, mass_k=None)   # Q [B,H,n_q,d], K, V [B,H,n_k,.]
 
 eps, iters and beta_cls are plain numbers and receive no gradient (the per-problem derivative with
-respect to beta_cls is available from lot.lot_attention_cls_bwd).
+respect to beta_cls is available from lot.lot_attention_cls_bwd); the token masses of cross attention
+are data (a padding mask), not differentiated.
 """
 import torch
 
@@ -47,6 +49,27 @@ class _LOTAttentionCls(torch.autograd.Function):
         return (*grads[:5], None, None, None, None)
 
 
+class _LOTCrossAttention(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, Q, K, V, Z, beta, eps, iters, mass_q, mass_k, path):
+        Q, K, V, Z, beta = (t.contiguous() for t in (Q, K, V, Z, beta))
+        mass_q = None if mass_q is None else mass_q.contiguous()
+        mass_k = None if mass_k is None else mass_k.contiguous()
+        ctx.save_for_backward(Q, K, V, Z, beta)
+        ctx.masses = (mass_q, mass_k)
+        ctx.cfg = (float(eps), int(iters), int(path))
+        return lot.lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=mass_q, mass_k=mass_k, path=path)
+
+    @staticmethod
+    def backward(ctx, dO):
+        Q, K, V, Z, beta = ctx.saved_tensors
+        mass_q, mass_k = ctx.masses
+        eps, iters, path = ctx.cfg
+        grads = lot.lot_cross_attention_bwd(Q, K, V, Z, beta, eps, iters, dO.contiguous().to(Q.dtype),
+                                            mass_q=mass_q, mass_k=mass_k, path=path)
+        return (*grads, None, None, None, None, None)
+
+
 def lot_attention(Q, K, V, Z, beta, eps, iters, path=lot.PATH_AUTO):
     """Differentiable LOT attention: gradients flow to Q, K, V (their dtype) and to Z, beta (float32)."""
     return _LOTAttention.apply(Q, K, V, Z, beta, eps, iters, path)
@@ -55,3 +78,8 @@ def lot_attention(Q, K, V, Z, beta, eps, iters, path=lot.PATH_AUTO):
 def lot_attention_cls(Q, K, V, Z, beta, eps, iters, beta_cls, path=lot.PATH_AUTO):
     """Differentiable [CLS] variant (token 0 = [CLS], a softmax row with temperature beta_cls)."""
     return _LOTAttentionCls.apply(Q, K, V, Z, beta, eps, iters, beta_cls, path)
+
+
+def lot_cross_attention(Q, K, V, Z, beta, eps, iters, mass_q=None, mass_k=None, path=lot.PATH_AUTO):
+    """Differentiable cross attention with optional token masses [B,H,n_q], [B,H,n_k] (zero = padding)."""
+    return _LOTCrossAttention.apply(Q, K, V, Z, beta, eps, iters, mass_q, mass_k, path)

@@ -51,3 +51,39 @@ def test_gradients_through_loss_backward_match_the_oracle(cls):
         err = rel_max_err(leaf.grad.double().cpu().numpy(), r64.numpy())
         print("  d%-6s max-norm rel err %.3e" % (name, err), flush=True)
         assert err <= 1e-4, name
+
+
+def test_cross_attention_gradients_through_loss_backward_match_the_oracle():
+    import torch
+    from oracle import lot_oracle_bwd
+    from paper_2509_23436_amd import autograd
+    B, H, n_q, n_k, d, r, eps, iters = 2, 2, 90, 140, 32, 8, 0.1, 5
+    rng = np.random.default_rng(92)
+    x = dict(Q=rng.standard_normal((B, H, n_q, d)) * d ** -0.5, K=rng.standard_normal((B, H, n_k, d)) * d ** -0.5,
+             V=rng.standard_normal((B, H, n_k, d)), Z=rng.standard_normal((H, r, d)) * d ** -0.5,
+             logits=rng.standard_normal((H, r)))
+    x = {k: v.astype(np.float32) for k, v in x.items()}
+    mass_q = rng.random((B, H, n_q)) + 0.1
+    mass_k = rng.random((B, H, n_k)) + 0.1
+    mass_k[:, :, n_k - 30:] = 0.0                                        # padding keys
+    mass_q = (mass_q / mass_q.sum(-1, keepdims=True)).astype(np.float32)
+    mass_k = (mass_k / mass_k.sum(-1, keepdims=True)).astype(np.float32)
+
+    t = {k: torch.tensor(np.asarray(v, dtype=np.float64), requires_grad=True) for k, v in x.items()}
+    O64 = lot_oracle_bwd.forward_cross(t["Q"], t["K"], t["V"], t["Z"], torch.softmax(t["logits"], dim=-1),
+                                       torch.tensor(mass_q, dtype=torch.float64), torch.tensor(mass_k, dtype=torch.float64),
+                                       eps, iters)
+    loss64 = (O64 ** 2).sum()
+    ref = torch.autograd.grad(loss64, list(t.values()))
+
+    dv = {k: torch.tensor(v, device="cuda", requires_grad=True) for k, v in x.items()}
+    O = autograd.lot_cross_attention(dv["Q"], dv["K"], dv["V"], dv["Z"], torch.softmax(dv["logits"], dim=-1), eps, iters,
+                                     mass_q=torch.tensor(mass_q, device="cuda"), mass_k=torch.tensor(mass_k, device="cuda"))
+    loss = (O ** 2).sum()
+    loss.backward()
+    torch.cuda.synchronize()
+    assert abs(float(loss.detach()) - float(loss64.detach())) <= 1e-4 * abs(float(loss64.detach()))
+    for (name, leaf), r64 in zip(dv.items(), ref):
+        err = rel_max_err(leaf.grad.double().cpu().numpy(), r64.numpy())
+        print("  d%-6s max-norm rel err %.3e" % (name, err), flush=True)
+        assert err <= 1e-4, name
