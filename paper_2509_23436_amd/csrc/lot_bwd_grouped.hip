@@ -1,6 +1,7 @@
 // Backward pass of LOT attention for pivot sizes beyond one register tile: 64 < r <= 256, d_k = d_v in
-// {32, 64}; per-side token counts and token masses as in cross attention.  Same gradients as the other backward paths; nothing of size n x r is
-// written.  The pivots are taken in groups of 64, as in the forward pass for these sizes.
+// {32, 64}; per-side token counts and token masses as in cross attention.  Same gradients as the other
+// backward paths; nothing of size n x r is written.  The pivots are taken in groups of 64, as in the
+// forward pass for these sizes.
 //
 // Notation as in the tiled backward path: per solve, W^k_it = softmax_t((C_it + g^{k-1}_t)/eps) is the
 // row-normalised kernel of iteration k, cs^k_t = sum_i W^k_it, c^k = a cs^k (a = 1/n), dc^k the adjoint of
@@ -13,7 +14,8 @@
 // reduction e^k_i, then a column reduction), T passes in sequence.  Per token and iteration two numbers
 // are kept, the base-2 row log-normaliser L^k_i (written by the forward passes) and e^k_i, so that every
 // later kernel rebuilds W^k_it = exp2((C_it + g^{k-1}_t) c1 - L^k_i) with one exponential and without a
-// reduction over the groups.
+// reduction over the groups.  With token masses (m_i = n a_i, 1 if uniform): cs^k_t = sum_i m_i W^k_it,
+// dP^k_it = m_i dc^k_t, and on the key side dGamma, the contraction with V and the rows of dV carry m_j.
 // (Paper, "Learning": everything is trained by backpropagating through both Sinkhorn problems and the
 // glued composition; its runtime study sweeps r up to 256.  The derivation is this file's.)
 //
