@@ -56,7 +56,7 @@ def compulsory_bytes(w) -> int:
     return 4 * w.d * s * w.G * w.n
 
 
-def runtime_grid(torch, lot, synth, to_device):
+def runtime_grid(torch, lot, synth, to_device, only=None):
     """Forward / backward time over the axes of the paper's runtime study (its values are not published):
     B = 1, H = 8, d = 64, bf16 I/O, eps = 0.05, T = 5 (the paper's default)."""
     import dataclasses
@@ -65,6 +65,8 @@ def runtime_grid(torch, lot, synth, to_device):
     for r in (32, 64, 128, 256):
         for logn in range(10, 18):
             n = 1 << logn
+            if only is not None and (n, r) != only:
+                continue
             w = dataclasses.replace(base, B=1, H=8, n=n, r=r, iters=5, seed=90)
             dev = to_device(synth.make_inputs(w), w.dtype)
             shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
@@ -115,6 +117,8 @@ def main() -> int:
     ap.add_argument("--runtime-grid", action="store_true",
                     help="instead of the benchmark, time the forward and the backward "
                          "over the paper's runtime grid: n = 2^10..2^17, r in {32, 64, 128, 256}, T = 5; one JSON line")
+    ap.add_argument("--grid-point", default=None, metavar="N,R",
+                    help="with --runtime-grid: only this point of the grid (for a kernel trace of one shape)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB ten times "
                          "(used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -141,7 +145,8 @@ def main() -> int:
         print(json.dumps({"calibrate_copy_bytes": args.calibrate_copy << 20, "copies": 10}))
         return 0
     if args.runtime_grid:
-        print(json.dumps({"runtime_grid": runtime_grid(torch, lot, synth, to_device)}))
+        only = tuple(int(v) for v in args.grid_point.split(",")) if args.grid_point else None
+        print(json.dumps({"runtime_grid": runtime_grid(torch, lot, synth, to_device, only)}))
         return 0
     w = synth.WORKLOADS[args.workload]
     path = {"auto": lot.PATH_AUTO, "fused": lot.PATH_FUSED, "reference": lot.PATH_REFERENCE}[args.path]
