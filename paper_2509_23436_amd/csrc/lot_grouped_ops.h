@@ -41,7 +41,7 @@ inline int lg_tiles_per_wg(const lot_shape& s)
     long long per = (ntiles * 2LL * s.B * s.H + kGTargetWgs - 1) / kGTargetWgs;
     per = (per + kWaves - 1) / kWaves * kWaves;
     if (per < kWaves) per = kWaves;
-    if (per > 16 * kWaves) per = 16 * kWaves;
+    if (per > 32 * kWaves) per = 32 * kWaves;
     return (int)per;
 }
 
