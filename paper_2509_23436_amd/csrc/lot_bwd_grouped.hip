@@ -738,17 +738,22 @@ __global__ void __launch_bounds__(kThreads, 2) gb_assemble_z(GbParams p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// final: dZ[h][t][c] and dbeta[h][t], summed over chunks, sides and the batch in index order
+// final: dZ[h][t][c] and dbeta[h][t], summed over chunks, sides and the batch.  32 outputs per workgroup,
+// each summed by 8 threads that take every 8th problem of the batch (in index order) and are then added
+// in order: a fixed order, and enough threads when the batch is large.
 // ---------------------------------------------------------------------------------------------
-__global__ void gb_final(GbParams p, int D)
+constexpr int kFinalSlices = 8, kFinalOutputs = 32;
+__global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) gb_final(GbParams p, int D)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (h, t, c), c == D meaning beta
+    __shared__ float s_part[kFinalSlices][kFinalOutputs];
+    const int o = threadIdx.x % kFinalOutputs, slice = threadIdx.x / kFinalOutputs;
+    const int idx = blockIdx.x * kFinalOutputs + o;     // (h, t, c), c == D meaning beta
     const int r = p.f.r, G = p.f.G, chunks = p.f.chunks;
     const int per = r * (D + 1);
-    if (idx >= p.f.H * per) return;
-    const int h = idx / per, t = (idx % per) / (D + 1), c = idx % (D + 1);
+    const bool live = idx < p.f.H * per;
+    const int h = live ? idx / per : 0, t = live ? (idx % per) / (D + 1) : 0, c = live ? idx % (D + 1) : 0;
     float acc = 0.f;
-    for (int b = 0; b < p.B; ++b) {
+    for (int b = slice; live && b < p.B; b += kFinalSlices) {
         const int g = b * p.f.H + h;
         if (c < D) {
             for (int side = 0; side < 2; ++side) {
@@ -768,8 +773,15 @@ __global__ void gb_final(GbParams p, int D)
             acc += p.db_pair[(size_t)(G + g) * kRmax + t];
         }
     }
-    if (c < D) p.dZ[((size_t)h * r + t) * D + c] = acc;
-    else p.dbeta[h * r + t] = acc;
+    s_part[slice][o] = acc;
+    __syncthreads();
+    if (slice == 0 && live) {
+        float tot = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < kFinalSlices; ++sl) tot += s_part[sl][o];
+        if (c < D) p.dZ[((size_t)h * r + t) * D + c] = tot;
+        else p.dbeta[h * r + t] = tot;
+    }
 }
 
 // Dynamic LDS of the assemble-x kernel, the largest of this path.
@@ -825,7 +837,7 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
     for (int k = T; k >= 1; --k) gb_rec_pass<IO, D><<<grid, kThreads, stash, st>>>(p, k);
     gb_assemble_x<IO, D, kAssembleWaves><<<grid, 64 * kAssembleWaves, ax_bytes, st>>>(p, (int)stage);
     gb_assemble_z<IO, D><<<group_grid(grid, groups), kThreads, az_bytes, st>>>(p);
-    gb_final<<<(unsigned)((a.s.H * a.s.r * (D + 1) + 255) / 256), 256, 0, st>>>(p, D);
+    gb_final<<<(unsigned)((a.s.H * a.s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), kFinalSlices * kFinalOutputs, 0, st>>>(p, D);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }

@@ -283,6 +283,19 @@ __device__ __forceinline__ void finish_pass(const BtParams& p, const SweepPlace&
         }
         __syncthreads();
     }
+    if (p.chunks == 1) {
+        // the only workgroup of its pair: its matrix is the pair's, written whole (blocks above the diagonal
+        // also to their mirror image) where the recursion reads it; no reduction launch follows
+        float* gf = p.gram_full + ((size_t)(k - 1) * pairs + w.pair) * R * R;
+        for (int e = tid; e < R * R; e += kThreads) {
+            const int row = e / R, col = e % R;
+            if (col / 32 < row / 32) continue;
+            const float v = bufs[0][e] + bufs[1][e];
+            gf[e] = v;
+            if (col / 32 > row / 32) gf[col * R + row] = v;
+        }
+        return;
+    }
     float* gp = p.gram_part + (((size_t)(k - 1) * pairs + w.pair) * p.chunks + w.chunk) * R * R;
     for (int e = tid; e < R * R; e += kThreads)
         if (e % R / 32 >= e / R / 32) gp[e] = bufs[0][e] + bufs[1][e];
@@ -1256,16 +1269,21 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
 }
 
 // ---------------------------------------------------------------------------------------------
-// final: dZ[h][t][c] and dbeta[h][t], summed over chunks, sides and the batch in index order
+// final: dZ[h][t][c] and dbeta[h][t], summed over chunks, sides and the batch.  32 outputs per workgroup,
+// each summed by 8 threads that take every 8th problem of the batch (in index order) and are then added
+// in order: a fixed order, and enough threads when the batch is large and H r (D + 1) small.
 // ---------------------------------------------------------------------------------------------
-__global__ void bt_final(BtParams p, int D)
+constexpr int kFinalSlices = 8, kFinalOutputs = 32;
+__global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) bt_final(BtParams p, int D)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;     // (h, t, c), c == D meaning beta
+    __shared__ float s_part[kFinalSlices][kFinalOutputs];
+    const int o = threadIdx.x % kFinalOutputs, slice = threadIdx.x / kFinalOutputs;
+    const int idx = blockIdx.x * kFinalOutputs + o;     // (h, t, c), c == D meaning beta
     const int per = p.r * (D + 1);
-    if (idx >= p.H * per) return;
-    const int h = idx / per, t = (idx % per) / (D + 1), c = idx % (D + 1);
+    const bool live = idx < p.H * per;
+    const int h = live ? idx / per : 0, t = live ? (idx % per) / (D + 1) : 0, c = live ? idx % (D + 1) : 0;
     float acc = 0.f;
-    for (int b = 0; b < p.B; ++b) {
+    for (int b = slice; live && b < p.B; b += kFinalSlices) {
         const int g = b * p.H + h;
         if (c < D) {
             for (int side = 0; side < 2; ++side) {
@@ -1285,8 +1303,15 @@ __global__ void bt_final(BtParams p, int D)
             acc += p.db_pair[(size_t)(p.G + g) * 64 + t];
         }
     }
-    if (c < D) p.dZ[((size_t)h * p.r + t) * D + c] = acc;
-    else p.dbeta[h * p.r + t] = acc;
+    s_part[slice][o] = acc;
+    __syncthreads();
+    if (slice == 0 && live) {
+        float tot = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < kFinalSlices; ++sl) tot += s_part[sl][o];
+        if (c < D) p.dZ[((size_t)h * p.r + t) * D + c] = tot;
+        else p.dbeta[h * p.r + t] = tot;
+    }
 }
 
 // zeroes the column-sum words and records the launch in the status area
@@ -1343,7 +1368,7 @@ int launch_all(const BwdArgs& a, BtParams p)
     }
     bt_mid<D><<<(unsigned)((p.G * 64 * D + 255) / 256), 256, 0, st>>>(p);
     bt_glue<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
-    {
+    if (p.chunks > 1) {      // (a pair with a single workgroup has written its matrices in place)
         const size_t total = (size_t)T * pairs * R * R;
         bt_gram_reduce<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(p, R, total);
     }
@@ -1355,7 +1380,7 @@ int launch_all(const BwdArgs& a, BtParams p)
     } else {
         bt_assemble<IO, D, RB><<<grid, kThreads, dyn, st>>>(p, T, nullptr);
     }
-    bt_final<<<(unsigned)((s.H * s.r * (D + 1) + 255) / 256), 256, 0, st>>>(p, D);
+    bt_final<<<(unsigned)((s.H * s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), kFinalSlices * kFinalOutputs, 0, st>>>(p, D);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }
