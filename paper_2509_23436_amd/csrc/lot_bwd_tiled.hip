@@ -524,6 +524,11 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
     const float* ymat = (side == 0 ? p.yp : p.dyraw) + (size_t)g * 64 * D;
     const float yscale = side == 0 ? (float)n : 1.f;
 
+    // (requested with the rest of the set-up's loads, kept in registers until the staging area is free)
+    constexpr int kMatPer = 64 * D / kThreads;
+    float yreg[kMatPer];
+#pragma unroll
+    for (int q = 0; q < kMatPer; ++q) yreg[q] = ymat[tid + q * kThreads] * yscale;
     if (tid < 64) {
         s_g[tid] = p.ghist[((size_t)(T - 1) * pairs + pair) * 64 + tid];
         s_rho[tid] = p.rhop[(size_t)pair * 64 + tid];
@@ -547,7 +552,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
     lay_out_fragments<D, RB>(s_y, s_yf[0], s_yf[1], tid);
     __syncthreads();
     // rows of ymat as the "pivot" operand of the similarity MFMA (scaled), via LDS staging
-    for (int e = tid; e < 64 * D; e += kThreads) s_y[e] = ymat[e] * yscale;
+#pragma unroll
+    for (int q = 0; q < kMatPer; ++q) s_y[tid + q * kThreads] = yreg[q];
     __syncthreads();
     if (wave == 0) {
         Frag<IO, D> y0[RB];
@@ -1036,6 +1042,19 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
     const float* g_last = p.ghist + ((size_t)(T - 1) * pairs + pair) * 64;
 
     if (tid == 0) s_redo = 0;
+    // Every global load of the set-up is requested here, together (the table's inputs and the matrix rows are
+    // kept in registers until the LDS areas they go to are free): one round trip to memory, not three.
+    constexpr int kTabPer = 32 * 64 / kThreads, kMatPer = 64 * D / kThreads;
+    float tdc[kTabPer], tg[kTabPer], yreg[kMatPer];
+#pragma unroll
+    for (int q = 0; q < kTabPer; ++q) {
+        const int e = tid + q * kThreads, t = e % 64, k = e / 64 / 2 + 1;
+        const bool live = k <= T && t < r;
+        tdc[q] = live ? p.dcs[((size_t)k * pairs + pair) * 64 + t] : 0.f;
+        tg[q] = live && k < T ? p.ghist[((size_t)(k - 1) * pairs + pair) * 64 + t] : 0.f;
+    }
+#pragma unroll
+    for (int q = 0; q < kMatPer; ++q) yreg[q] = ymat[tid + q * kThreads] * yscale;
     if (tid < 64) {
         s_brho[tid] = (float)n * p.rhop[(size_t)pair * 64 + tid];
         s_pot[tid] = g_last[tid] * c1;                       // padding: -1e30 c1
@@ -1064,23 +1083,24 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
         s_y[e] = z;
     }
     __syncthreads();
-    for (int e = tid; e < 32 * 64; e += kThreads) {
-        const int row = e / 64, t = e % 64, k = row / 2 + 1;
+#pragma unroll
+    for (int q = 0; q < kTabPer; ++q) {
+        const int e = tid + q * kThreads, row = e / 64, t = e % 64, k = row / 2 + 1;
         float v = 0.f;
         if (k <= T && t < r) {
-            const float dc = p.dcs[((size_t)k * pairs + pair) * 64 + t];
             if (k == T) {
-                v = (row & 1) ? 1.f : dc;
+                v = (row & 1) ? 1.f : tdc[q];
             } else {
-                const float P = exp2_fast((p.ghist[((size_t)(k - 1) * pairs + pair) * 64 + t] - g_last[t]) * c1 - s_h[k - 1]);
-                v = (row & 1) ? P : P * dc;
+                const float P = exp2_fast(fmaf(tg[q], c1, -s_pot[t]) - s_h[k - 1]);
+                v = (row & 1) ? P : P * tdc[q];
             }
         }
         s_tab[row * kTabStride + t] = v;
     }
     lay_out_fragments<D, RB>(s_y, s_zf[0], s_zf[1], tid);
     __syncthreads();
-    for (int e = tid; e < 64 * D; e += kThreads) s_y[e] = ymat[e] * yscale;
+#pragma unroll
+    for (int q = 0; q < kMatPer; ++q) s_y[tid + q * kThreads] = yreg[q];
     __syncthreads();
     if (wave == 0) {
         Frag<IO, D> y0[RB];
