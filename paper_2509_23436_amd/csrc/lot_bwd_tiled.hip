@@ -123,12 +123,14 @@ __device__ __forceinline__ float colsum_of(unsigned long long word, float unscal
 template <typename IO, int D, int RB> struct SweepShared {
     float g[64];                                   // g^{k-1}
     float cs[kWaves][64];
-    __attribute__((aligned(16))) float buf[64 * 64 > 64 * D ? 64 * 64 : 64 * D];
-    __attribute__((aligned(16))) uint16_t tr[kWaves * 2 * 64 * kTrStride];
+    // (sized for the 32 RB pivots in use: with r <= 32 three workgroups then fit a compute unit's local memory)
+    static constexpr int kR = 32 * RB;
+    __attribute__((aligned(16))) float buf[kR * kR > kR * D ? kR * kR : kR * D];    // a Gram matrix, or a [pivot][D] sum
+    __attribute__((aligned(16))) uint16_t tr[kWaves * 2 * kR * kTrStride];
     __attribute__((aligned(16))) char zstash[StashBytes<IO, D, RB>::value];
+    static_assert(kWaves * 2 * kR * kTrStride * sizeof(uint16_t) >= kR * kR * sizeof(float),
+                  "the transposition area doubles as the second buffer of the Gram reduction");
 };
-static_assert(kWaves * 2 * 64 * kTrStride * sizeof(uint16_t) >= 64 * 64 * sizeof(float),
-              "the transposition area doubles as the second buffer of the Gram reduction");
 
 // Where a workgroup of the sweep works
 struct SweepPlace {
@@ -182,8 +184,8 @@ __device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace&
     constexpr int NB = D / 32;
     constexpr bool kSplit = io_is_f32<IO>::value;
     const int i = lane & 31, kg = lane >> 5, n = p.n_side[w.side], stride = p.stride_side[w.side];
-    uint16_t* tr_hi = sh.tr + (wave * 2 + 0) * 64 * kTrStride;
-    uint16_t* tr_lo = sh.tr + (wave * 2 + 1) * 64 * kTrStride;
+    uint16_t* tr_hi = sh.tr + (wave * 2 + 0) * 32 * RB * kTrStride;
+    uint16_t* tr_lo = sh.tr + (wave * 2 + 1) * 32 * RB * kTrStride;
     for (int tile = w.tile_begin + wave; tile < w.tile_end; tile += kWaves) {
         Frag<IO, D> xn = xc;
         float mn = mc;
@@ -765,7 +767,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap,
     __shared__ __attribute__((aligned(16))) float s_y[64 * D];
     constexpr int kParts = kSplit ? 2 : 1;     // bf16 hi only, or hi and lo
     __shared__ __attribute__((aligned(16))) bf16x8 s_zf[2][2 * RB * NB * 64];
-    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 64 * kTrStride];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 32 * RB * kTrStride];
     __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
     __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
     static_assert(kSplit || sizeof(s_zf[1]) >= (size_t)StashBytes<IO, D, RB>::value, "the lo stash takes the place of s_zf[1]");
@@ -784,8 +786,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap,
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
     const float* ymat = (side == 0 ? p.yp : p.dyraw) + (size_t)g * 64 * D;
     const float yscale = side == 0 ? (float)n : 1.f;
-    uint16_t* tr_hi = s_tr + (wave * kParts + 0) * 64 * kTrStride;
-    uint16_t* tr_lo = s_tr + (wave * kParts + kParts - 1) * 64 * kTrStride;
+    uint16_t* tr_hi = s_tr + (wave * kParts + 0) * 32 * RB * kTrStride;
+    uint16_t* tr_lo = s_tr + (wave * kParts + kParts - 1) * 32 * RB * kTrStride;
 
     for (int e = tid; e < T * 64; e += kThreads) {
         const int k = e / 64 + 1, t = e % 64;
@@ -1016,10 +1018,10 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
     __shared__ float s_brho[64], s_pot[64], s_h[kAllAtOnceIters];
     __shared__ int s_redo;
     __shared__ __attribute__((aligned(16))) float s_tab[32 * kTabStride];
-    __shared__ __attribute__((aligned(16))) float s_y[64 * D];
+    __shared__ __attribute__((aligned(16))) float s_y[32 * RB * D];     // staging of the 32 RB pivot rows in use, then the dZ partial
     constexpr int kParts = kSplit ? 2 : 1;     // bf16 hi only, or hi and lo
     __shared__ __attribute__((aligned(16))) bf16x8 s_zf[2][2 * RB * NB * 64];
-    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 64 * kTrStride];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 32 * RB * kTrStride];
     __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
     __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
     static_assert(kSplit || sizeof(s_zf[1]) >= (size_t)StashBytes<IO, D, RB>::value, "the lo stash takes the place of s_zf[1]");
@@ -1037,14 +1039,14 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
     const IO* vals = reinterpret_cast<const IO*>(side == 0 ? p.dO : p.V);
     const float* ymat = (side == 0 ? p.yp : p.dyraw) + (size_t)g * 64 * D;
     const float yscale = side == 0 ? (float)n : 1.f;
-    uint16_t* tr_hi = s_tr + (wave * kParts + 0) * 64 * kTrStride;
-    uint16_t* tr_lo = s_tr + (wave * kParts + kParts - 1) * 64 * kTrStride;
+    uint16_t* tr_hi = s_tr + (wave * kParts + 0) * 32 * RB * kTrStride;
+    uint16_t* tr_lo = s_tr + (wave * kParts + kParts - 1) * 32 * RB * kTrStride;
     const float* g_last = p.ghist + ((size_t)(T - 1) * pairs + pair) * 64;
 
     if (tid == 0) s_redo = 0;
     // Every global load of the set-up is requested here, together (the table's inputs and the matrix rows are
     // kept in registers until the LDS areas they go to are free): one round trip to memory, not three.
-    constexpr int kTabPer = 32 * 64 / kThreads, kMatPer = 64 * D / kThreads;
+    constexpr int kTabPer = 32 * 64 / kThreads, kMatPer = 32 * RB * D / kThreads;
     float tdc[kTabPer], tg[kTabPer], yreg[kMatPer];
 #pragma unroll
     for (int q = 0; q < kTabPer; ++q) {
@@ -1076,7 +1078,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
         stash_pivots<D, RB>(s_zstash, z0, lane);
     }
     // Z rows as B fragments (the values the forward pass multiplied with: rounded to bf16 for bf16 I/O)
-    for (int e = tid; e < 64 * D; e += kThreads) {
+    for (int e = tid; e < 32 * RB * D; e += kThreads) {
         const int t = e / D;
         float z = t < r ? p.Z[((size_t)h * r + t) * D + e % D] : 0.f;
         if (!kSplit) z = (float)(__bf16)z;
