@@ -808,7 +808,7 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
     hipStream_t st = a.stream;
     const int pairs = 2 * p.f.G, T = a.iters, groups = p.f.groups;
     const size_t words = (size_t)(T + 1) * pairs * kRmax;
-    lg_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.f.colacc, words);
+    lg_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.f.colacc, words, (unsigned long long*)a.ws, next_nonce());
     const size_t stash = (size_t)groups * StashBytes<IO, D, 2>::value;
     const size_t frag_bytes = (size_t)groups * 2 * (2 * 2 * NB * 64) * sizeof(bf16x8);
     const size_t glue_bytes = stash * (kSplit ? 2 : 3);
@@ -920,7 +920,6 @@ int run_backward_grouped(const BwdArgs& a)
         p.f.fx_scale = std::ldexp(1.0f, frac);
         p.f.fx_unscale = std::ldexp(1.0f, -frac);
     }
-    ref_mark<<<1, 1, 0, a.stream>>>((unsigned long long*)a.ws, next_nonce());   // no device-side waits here
     if (s.io_dtype == LOT_BF16) return s.d_k == 64 ? launch_bwd_grouped<uint16_t, 64>(a, p) : launch_bwd_grouped<uint16_t, 32>(a, p);
     return s.d_k == 64 ? launch_bwd_grouped<float, 64>(a, p) : launch_bwd_grouped<float, 32>(a, p);
 }

@@ -124,7 +124,7 @@ int launch_grouped(const Args& a, LgParams p)
     hipStream_t st = a.stream;
     const int pairs = 2 * p.G, T = a.iters;
     const size_t words = (size_t)(T + 1) * pairs * kRmax;
-    lg_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words);
+    lg_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words, (unsigned long long*)a.ws, next_nonce());
     const size_t stash = (size_t)p.groups * StashBytes<IO, D, 2>::value;
     const size_t frag_bytes = (size_t)p.groups * 2 * (2 * 2 * NB * 64) * sizeof(bf16x8);
     // more than 64 KB of LDS per workgroup has to be asked for explicitly
@@ -191,7 +191,6 @@ int run_grouped(const Args& a)
         p.fx_scale = std::ldexp(1.0f, frac);
         p.fx_unscale = std::ldexp(1.0f, -frac);
     }
-    ref_mark<<<1, 1, 0, a.stream>>>((unsigned long long*)a.ws, next_nonce());   // no device-side waits here
     if (s.io_dtype == LOT_BF16) return s.d_k == 64 ? launch_grouped<uint16_t, 64>(a, p) : launch_grouped<uint16_t, 32>(a, p);
     return s.d_k == 64 ? launch_grouped<float, 64>(a, p) : launch_grouped<float, 32>(a, p);
 }

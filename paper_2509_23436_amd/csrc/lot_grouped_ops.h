@@ -305,10 +305,13 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
     }
 }
 
-__global__ void lg_clear(unsigned long long* p, size_t count)
+// zeroes the column-sum words and marks the workspace as used by a launch that cannot fail on the device
+// (word 1 of the status area takes a fresh nonce, which word 0, written only by a wait that gave up, cannot hold)
+__global__ void lg_clear(unsigned long long* p, size_t count, unsigned long long* status, unsigned long long nonce)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx < count) p[idx] = 0ull;
+    if (idx == 0) status[1] = nonce;
 }
 
 }  // namespace
