@@ -456,9 +456,9 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
 // (g, t) row are adjacent lanes of one wavefront, so the row's dot product <dYraw_t, Y'_t> is a
 // butterfly sum over them and lane 0 of the row writes the per-pivot numbers.
 template <int D>
-__global__ void bt_mid(BtParams p)
+__device__ __forceinline__ void mid_body(const BtParams& p, int block)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;      // the grid covers G * 64 * D exactly: whole wavefronts
+    const int idx = block * blockDim.x + threadIdx.x;      // the blocks cover G * 64 * D exactly: whole wavefronts
     const int g = idx / (64 * D), e = idx % (64 * D), t = e / D;
     const int pairs = 2 * p.G, T = p.T;
     float y = 0.f, dy = 0.f, r1 = 0.f, r2 = 0.f;
@@ -679,9 +679,9 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
 // 32 x 32 blocks on and above the diagonal; a sum above the diagonal blocks is also written to its
 // mirror image.
 // ---------------------------------------------------------------------------------------------
-__global__ void bt_gram_reduce(BtParams p, int R, size_t total)
+__device__ __forceinline__ void gram_reduce_body(const BtParams& p, int R, size_t total, size_t block)
 {
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;    // (kp, e)
+    const size_t idx = block * blockDim.x + threadIdx.x;    // (kp, e)
     if (idx >= total) return;
     const int R2 = R * R;
     const size_t kp = idx / R2;
@@ -699,6 +699,16 @@ __global__ void bt_gram_reduce(BtParams p, int R, size_t total)
     const float sum = (a0 + a1) + (a2 + a3);
     p.gram_full[idx] = sum;
     if (col / 32 > row / 32) p.gram_full[kp * R2 + (size_t)col * R + row] = sum;
+}
+
+// mid and Gram reduce share a launch: neither depends on the other, both are short, and the glue kernel
+// that follows needs only the first (blocks [0, mid_blocks) are mid's, the rest the reduction's; total == 0:
+// no reduction, the pairs' only workgroups have written their matrices in place).
+template <int D>
+__global__ void bt_mid_gram(BtParams p, int R, size_t total, int mid_blocks)
+{
+    if ((int)blockIdx.x < mid_blocks) mid_body<D>(p, (int)blockIdx.x);
+    else gram_reduce_body(p, R, total, (size_t)blockIdx.x - mid_blocks);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1388,12 +1398,13 @@ int launch_all(const BwdArgs& a, BtParams p)
         if (mass) bt_forward<IO, D, RB, true, true><<<grid, kThreads, 0, st>>>(p);
         else bt_forward<IO, D, RB, true, false><<<grid, kThreads, 0, st>>>(p);
     }
-    bt_mid<D><<<(unsigned)((p.G * 64 * D + 255) / 256), 256, 0, st>>>(p);
-    bt_glue<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
-    if (p.chunks > 1) {      // (a pair with a single workgroup has written its matrices in place)
-        const size_t total = (size_t)T * pairs * R * R;
-        bt_gram_reduce<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(p, R, total);
+    {
+        const int mid_blocks = p.G * 64 * D / 256;
+        // (a pair with a single workgroup has written its Gram matrices in place: nothing to reduce)
+        const size_t total = p.chunks > 1 ? (size_t)T * pairs * R * R : 0;
+        bt_mid_gram<D><<<(unsigned)(mid_blocks + (total + 255) / 256), 256, 0, st>>>(p, R, total, mid_blocks);
     }
+    bt_glue<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
     bt_recursion<<<pairs, 256, 0, st>>>(p, R);
     const size_t dyn = (size_t)T * 2 * 64 * sizeof(float);
     if (T <= kAllAtOnceIters && !assemble_by_iteration()) {
