@@ -24,8 +24,10 @@
 //
 // Launches:
 //   clear | forward sweep (T passes: column sums and Gram matrices; then the two token contractions
-//   U = sum W2 V, Wd = sum W1 dO) | mid (Y', dYraw) | glue (s, N, dV) | Gram reduce | recursion |
-//   assemble (dQ, dK, dZ partials) | final (dZ, dbeta).
+//   U = sum W2 V, Wd = sum W1 dO) | mid (Y', dYraw) together with the Gram reduce | glue (s, N, dV) |
+//   recursion | assemble, all iterations at once (dQ, dK, dZ partials) | assemble, iteration by iteration
+//   (only workgroups the former marked; every workgroup when there are more than 16 iterations) |
+//   final (dZ, dbeta).
 // The forward sweep is one persistent kernel when all its workgroups can be resident at once: the
 // workgroups of a pair exchange their column sums through one integer atomic per pivot that also
 // counts the contributors, and wait (bounded) for the count before the next pass; the write-out of
