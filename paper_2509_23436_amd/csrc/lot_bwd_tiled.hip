@@ -1235,7 +1235,6 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
         for (int s = 0; s < kAllAtOnceIters; ++s) {
             if (s < T) {
                 // rows 2 s (sdot) and 2 s + 1 (ssum) sit in registers jr, jr + 1 of the lanes with kg == (s / 2) % 2
-                constexpr int kDummy = 0; (void)kDummy;
                 const int jr = 4 * (s / 4) + 2 * (s % 2);
                 float lo, hi;
                 both_halves(rows[jr], lo, hi);
