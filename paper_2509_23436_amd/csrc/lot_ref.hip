@@ -127,71 +127,128 @@ int run_reference_t(const Args& a, bool want_out)
 // The keys are taken in chunks of kClsChunk: scores of a chunk go to LDS once, the running maximum
 // and normaliser are updated the usual way (rescale by exp(old max - new max)), and the chunk's
 // weighted values are added; every reduction has a fixed order.
+// A row product <x, row_j> is shared by kClsLanes neighbouring lanes (lane l takes columns l,
+// l + kClsLanes, ...: consecutive addresses) and combined with a butterfly, which leaves the same
+// sum in all of them; the keys of a chunk are dealt to these lane groups in turn.
 constexpr int kClsChunk = 2048;
-constexpr int kClsThreads = 256;
+constexpr int kClsThreads = 1024;
+constexpr int kClsLanes = 16;
+constexpr int kClsGroups = kClsThreads / kClsLanes;
+constexpr int kClsWaves = kClsThreads / 64;
+
+constexpr int kClsBatch = 4;             // keys per lane group, and columns per lane, whose loads are issued together
+
+// <x, row_j> for the keys j = first + u * step (u < kClsBatch) of one problem (rows = its [n][d]
+// matrix), 0 for keys >= limit.  All loads of a batch are issued before the first product; each
+// lane adds its columns in ascending order.
+template <typename T>
+__device__ __forceinline__ void cls_row_dots(const float* __restrict__ x, const T* __restrict__ rows, int d, int l,
+                                             int first, int step, int limit, float (&out)[kClsBatch])
+{
+    float s[kClsBatch];
+#pragma unroll
+    for (int u = 0; u < kClsBatch; ++u) s[u] = 0.f;
+    for (int c0 = l; c0 < d; c0 += kClsBatch * kClsLanes) {
+        float v[kClsBatch][kClsBatch], xc[kClsBatch];
+#pragma unroll
+        for (int u = 0; u < kClsBatch; ++u)
+#pragma unroll
+            for (int w = 0; w < kClsBatch; ++w) {
+                const int j = first + u * step, c = c0 + w * kClsLanes;
+                v[u][w] = j < limit && c < d ? ld(rows, (size_t)j * d + c) : 0.f;
+            }
+#pragma unroll
+        for (int w = 0; w < kClsBatch; ++w) xc[w] = c0 + w * kClsLanes < d ? x[c0 + w * kClsLanes] : 0.f;
+#pragma unroll
+        for (int u = 0; u < kClsBatch; ++u)
+#pragma unroll
+            for (int w = 0; w < kClsBatch; ++w) s[u] = fmaf(xc[w], v[u][w], s[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kClsBatch; ++u) {
+#pragma unroll
+        for (int w = kClsLanes / 2; w > 0; w >>= 1) s[u] += __shfl_xor(s[u], w);
+        out[u] = s[u];
+    }
+}
+
+// maximum or sum over the workgroup, the same value in every thread: butterfly within a wave, then
+// the wave results in order.  s_red holds kClsWaves floats.
+template <bool kMax>
+__device__ __forceinline__ float cls_reduce(float v, float* s_red)
+{
+#pragma unroll
+    for (int w = 32; w > 0; w >>= 1) {
+        const float o = __shfl_xor(v, w);
+        v = kMax ? fmaxf(v, o) : v + o;
+    }
+    if (threadIdx.x % 64 == 0) s_red[threadIdx.x / 64] = v;
+    __syncthreads();
+    float r = s_red[0];
+#pragma unroll
+    for (int w = 1; w < kClsWaves; ++w) r = kMax ? fmaxf(r, s_red[w]) : r + s_red[w];
+    __syncthreads();
+    return r;
+}
 
 template <typename T>
-__global__ void cls_row(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-                        T* __restrict__ out, int n, int d, int dv, float beta_cls)
+__global__ __launch_bounds__(kClsThreads) void cls_row(const T* __restrict__ Q, const T* __restrict__ K,
+                                                       const T* __restrict__ V, T* __restrict__ out, int n, int d,
+                                                       int dv, float beta_cls)
 {
     __shared__ float s_p[kClsChunk];
-    __shared__ float s_red[kClsThreads];
-    extern __shared__ float s_acc[];        // [parts][dv]
+    __shared__ float s_red[kClsWaves];
+    extern __shared__ float s_dyn[];        // q_cls [d], parts x dv partial sums of the output row
+    float* s_q = s_dyn;
+    float* s_acc = s_dyn + d;
     const size_t g = blockIdx.x;
-    const T* q = Q + g * n * d;
     const int tid = threadIdx.x;
+    const int grp = tid / kClsLanes, l = tid % kClsLanes;
     const int parts = kClsThreads / dv > 0 ? kClsThreads / dv : 1;      // threads per output column
+    for (int c = tid; c < d; c += kClsThreads) s_q[c] = ld(Q, g * n * d + c);
+    __syncthreads();
     float run_max = -INFINITY, run_z = 0.f;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};   // up to 4 columns per thread when dv > 256
+    float acc = 0.f;                        // dv <= 1024: one column per thread
     for (int j0 = 0; j0 < n; j0 += kClsChunk) {
         const int cn = min(kClsChunk, n - j0);
         float m = -INFINITY;
-        for (int j = tid; j < cn; j += kClsThreads) {
-            float sc = 0.f;
-            for (int c = 0; c < d; ++c) sc = fmaf(ld(q, c), ld(K, (g * n + j0 + j) * d + c), sc);
-            sc *= beta_cls;
-            s_p[j] = sc;
-            m = fmaxf(m, sc);
+        for (int j = grp; j < cn; j += kClsBatch * kClsGroups) {
+            float sc[kClsBatch];
+            cls_row_dots(s_q, K + (g * n + j0) * d, d, l, j, kClsGroups, cn, sc);
+#pragma unroll
+            for (int u = 0; u < kClsBatch; ++u) {
+                const int ju = j + u * kClsGroups;
+                if (ju < cn) {
+                    if (l == 0) s_p[ju] = beta_cls * sc[u];
+                    m = fmaxf(m, beta_cls * sc[u]);
+                }
+            }
         }
-        s_red[tid] = m;
-        __syncthreads();
-        for (int w = kClsThreads / 2; w > 0; w >>= 1) {
-            if (tid < w) s_red[tid] = fmaxf(s_red[tid], s_red[tid + w]);
-            __syncthreads();
-        }
-        const float new_max = fmaxf(run_max, s_red[0]);
-        __syncthreads();
+        const float new_max = fmaxf(run_max, cls_reduce<true>(m, s_red));     // also publishes s_p
         float z = 0.f;
         for (int j = tid; j < cn; j += kClsThreads) {
             const float e = expf(s_p[j] - new_max);
             s_p[j] = e;
             z += e;
         }
-        s_red[tid] = z;
-        __syncthreads();
-        for (int w = kClsThreads / 2; w > 0; w >>= 1) {
-            if (tid < w) s_red[tid] += s_red[tid + w];
-            __syncthreads();
-        }
+        z = cls_reduce<false>(z, s_red);
         const float scale = expf(run_max - new_max);      // 0 for the first chunk
-        run_z = run_z * scale + s_red[0];
+        run_z = run_z * scale + z;
         run_max = new_max;
         // weighted values of the chunk: thread = (column c, part); parts interleave the keys
-        int slot = 0;
-        for (int c0 = 0; c0 < dv; c0 += kClsThreads / parts, ++slot) {
-            const int c = c0 + tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
-            float a = 0.f;
-            if (c < dv && part < parts)
-                for (int j = part; j < cn; j += parts) a = fmaf(s_p[j], ld(V, (g * n + j0 + j) * dv + c), a);
-            acc[slot & 3] = acc[slot & 3] * scale + a;
+        const int c = tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
+        float a = 0.f;
+        if (c < dv && part < parts) {
+#pragma unroll 4
+            for (int j = part; j < cn; j += parts) a = fmaf(s_p[j], ld(V, (g * n + j0 + j) * dv + c), a);
         }
+        acc = acc * scale + a;
         __syncthreads();
     }
     // combine the parts of each column in order, normalise, store
-    int slot = 0;
-    for (int c0 = 0; c0 < dv; c0 += kClsThreads / parts, ++slot) {
-        const int c = c0 + tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
-        if (c < dv && part < parts) s_acc[part * dv + c] = acc[slot & 3];
+    {
+        const int c = tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
+        if (c < dv && part < parts) s_acc[part * dv + c] = acc;
     }
     __syncthreads();
     for (int c = tid; c < dv; c += kClsThreads) {
@@ -210,104 +267,162 @@ __global__ void cls_row(const T* __restrict__ Q, const T* __restrict__ K, const 
 // Rows j >= 1 of dK and dV already hold the gradient of the doubly-stochastic part and are added to;
 // row 0 (the [CLS] key and value, which only this row sees) and row 0 of dQ are written.  One
 // workgroup per problem, three sweeps over the keys (maximum; normaliser and sum p dp; gradients),
-// the last in chunks whose a_j and p_j sit in LDS; every reduction has a fixed order.
+// the last in chunks whose a_j and p_j sit in LDS; every reduction has a fixed order.  When all keys
+// fit one chunk, raw_j and dp_j are computed once, in the first sweep, and kept in LDS for the others.
 template <typename T>
-__global__ void cls_row_bwd(const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-                            const T* __restrict__ dO, T* __restrict__ dQ, T* __restrict__ dK, T* __restrict__ dV,
-                            float* __restrict__ dbeta_cls, int n, int d, int dv, float beta_cls)
+__global__ __launch_bounds__(kClsThreads) void cls_row_bwd(const T* __restrict__ Q, const T* __restrict__ K,
+                                                           const T* __restrict__ V, const T* __restrict__ dO,
+                                                           T* __restrict__ dQ, T* __restrict__ dK, T* __restrict__ dV,
+                                                           float* __restrict__ dbeta_cls, int n, int d, int dv,
+                                                           float beta_cls)
 {
     __shared__ float s_a[kClsChunk];
     __shared__ float s_p[kClsChunk];
-    __shared__ float s_red[kClsThreads];
+    __shared__ float s_raw[kClsChunk];
+    __shared__ float s_dp[kClsChunk];
+    __shared__ float s_red[kClsWaves];
     extern __shared__ float s_dyn[];        // q_cls [d], dout [dv], parts x d partial sums of dq_cls
     float* s_q = s_dyn;
     float* s_do = s_dyn + d;
     float* s_acc = s_dyn + d + dv;
     const size_t g = blockIdx.x;
     const int tid = threadIdx.x;
+    const int grp = tid / kClsLanes, l = tid % kClsLanes;
+    const bool kept = n <= kClsChunk;
     for (int c = tid; c < d; c += kClsThreads) s_q[c] = ld(Q, g * n * d + c);
     for (int c = tid; c < dv; c += kClsThreads) s_do[c] = ld(dO, g * n * dv + c);
     __syncthreads();
-    auto score = [&](int j) {
-        float sc = 0.f;
-        for (int c = 0; c < d; ++c) sc = fmaf(s_q[c], ld(K, (g * n + j) * d + c), sc);
-        return sc;                      // raw_j
+    // raw_j and dp_j of the keys first + u * kClsGroups (u < kClsBatch)
+    auto scores = [&](int first, float (&raw)[kClsBatch]) {
+        cls_row_dots(s_q, K + g * n * d, d, l, first, kClsGroups, n, raw);
     };
-    auto reduce = [&](float v, bool take_max) {
-        s_red[tid] = v;
-        __syncthreads();
-        for (int w = kClsThreads / 2; w > 0; w >>= 1) {
-            if (tid < w) s_red[tid] = take_max ? fmaxf(s_red[tid], s_red[tid + w]) : s_red[tid] + s_red[tid + w];
-            __syncthreads();
-        }
-        const float r = s_red[0];
-        __syncthreads();
-        return r;
+    auto slopes = [&](int first, float (&dp)[kClsBatch]) {
+        cls_row_dots(s_do, V + g * n * dv, dv, l, first, kClsGroups, n, dp);
     };
     // sweep 1: maximum of the scaled scores
     float m = -INFINITY;
-    for (int j = tid; j < n; j += kClsThreads) m = fmaxf(m, beta_cls * score(j));
-    m = reduce(m, true);
+    for (int j = grp; j < n; j += kClsBatch * kClsGroups) {
+        float raw[kClsBatch], dp[kClsBatch];
+        scores(j, raw);
+        if (kept) slopes(j, dp);
+#pragma unroll
+        for (int u = 0; u < kClsBatch; ++u) {
+            const int ju = j + u * kClsGroups;
+            if (ju < n) {
+                if (kept && l == 0) { s_raw[ju] = raw[u]; s_dp[ju] = dp[u]; }
+                m = fmaxf(m, beta_cls * raw[u]);
+            }
+        }
+    }
+    m = cls_reduce<true>(m, s_red);         // also publishes s_raw, s_dp
     // sweep 2: normaliser and sum_j p_j dp_j
     float z = 0.f, pd = 0.f;
-    for (int j = tid; j < n; j += kClsThreads) {
-        const float e = expf(beta_cls * score(j) - m);
-        float dp = 0.f;
-        for (int c = 0; c < dv; ++c) dp = fmaf(s_do[c], ld(V, (g * n + j) * dv + c), dp);
-        z += e;
-        pd = fmaf(e, dp, pd);
+    if (kept) {
+        for (int j = tid; j < n; j += kClsThreads) {
+            const float e = expf(beta_cls * s_raw[j] - m);
+            z += e;
+            pd = fmaf(e, s_dp[j], pd);
+        }
+    } else {
+        for (int j = grp; j < n; j += kClsBatch * kClsGroups) {
+            float raw[kClsBatch], dp[kClsBatch];
+            scores(j, raw);
+            slopes(j, dp);
+#pragma unroll
+            for (int u = 0; u < kClsBatch; ++u)
+                if (l == 0 && j + u * kClsGroups < n) {
+                    const float e = expf(beta_cls * raw[u] - m);
+                    z += e;
+                    pd = fmaf(e, dp[u], pd);
+                }
+        }
     }
-    z = reduce(z, false);
-    pd = reduce(pd, false) / z;
+    z = cls_reduce<false>(z, s_red);
+    pd = cls_reduce<false>(pd, s_red) / z;
     // sweep 3, in chunks: a_j and p_j to LDS, then column-parallel updates
     const int parts = kClsThreads / d > 0 ? kClsThreads / d : 1;          // threads per column of dq_cls
     const int parts_v = kClsThreads / dv > 0 ? kClsThreads / dv : 1;
-    float dq[4] = {0.f, 0.f, 0.f, 0.f};     // up to 4 columns per thread when d > 256
+    float dq = 0.f;                         // d <= 1024: one column per thread
     float dbc = 0.f;
     for (int j0 = 0; j0 < n; j0 += kClsChunk) {
         const int cn = min(kClsChunk, n - j0);
-        for (int j = tid; j < cn; j += kClsThreads) {
-            const float raw = score(j0 + j);
-            const float pj = expf(beta_cls * raw - m) / z;
-            float dp = 0.f;
-            for (int c = 0; c < dv; ++c) dp = fmaf(s_do[c], ld(V, (g * n + j0 + j) * dv + c), dp);
-            const float a = pj * (dp - pd);
-            s_a[j] = a;
-            s_p[j] = pj;
-            dbc = fmaf(a, raw, dbc);
+        if (kept) {
+            for (int j = tid; j < cn; j += kClsThreads) {
+                const float raw = s_raw[j];
+                const float pj = expf(beta_cls * raw - m) / z;
+                const float a = pj * (s_dp[j] - pd);
+                s_a[j] = a;
+                s_p[j] = pj;
+                dbc = fmaf(a, raw, dbc);
+            }
+        } else {
+            for (int j = grp; j < cn; j += kClsBatch * kClsGroups) {
+                float raw[kClsBatch], dp[kClsBatch];
+                scores(j0 + j, raw);
+                slopes(j0 + j, dp);
+#pragma unroll
+                for (int u = 0; u < kClsBatch; ++u) {
+                    const int ju = j + u * kClsGroups;
+                    if (l == 0 && ju < cn) {
+                        const float pj = expf(beta_cls * raw[u] - m) / z;
+                        const float a = pj * (dp[u] - pd);
+                        s_a[ju] = a;
+                        s_p[ju] = pj;
+                        dbc = fmaf(a, raw[u], dbc);
+                    }
+                }
+            }
         }
         __syncthreads();
-        int slot = 0;
-        for (int c0 = 0; c0 < d; c0 += kClsThreads / parts, ++slot) {
-            const int c = c0 + tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
+        {
+            const int c = tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
             if (c < d && part < parts) {
                 float acc = 0.f;
                 const float qc = beta_cls * s_q[c];
-                for (int j = part; j < cn; j += parts) {
-                    const size_t at = (g * n + j0 + j) * d + c;
-                    acc = fmaf(s_a[j], ld(K, at), acc);
-                    const float add = s_a[j] * qc;
-                    st(dK, at, j0 + j == 0 ? add : ld(dK, at) + add);
+                for (int j = part; j < cn; j += kClsBatch * parts) {
+                    float kv[kClsBatch], old[kClsBatch];
+#pragma unroll
+                    for (int u = 0; u < kClsBatch; ++u) {
+                        const int ju = j + u * parts;
+                        const size_t at = (g * n + j0 + ju) * d + c;
+                        kv[u] = ju < cn ? ld(K, at) : 0.f;
+                        old[u] = ju < cn && j0 + ju != 0 ? ld(dK, at) : 0.f;       // row 0 is written, not added to
+                    }
+#pragma unroll
+                    for (int u = 0; u < kClsBatch; ++u) {
+                        const int ju = j + u * parts;
+                        if (ju < cn) {
+                            acc = fmaf(s_a[ju], kv[u], acc);
+                            st(dK, (g * n + j0 + ju) * d + c, old[u] + s_a[ju] * qc);
+                        }
+                    }
                 }
-                dq[slot & 3] += acc;
+                dq += acc;
             }
         }
-        for (int c0 = 0; c0 < dv; c0 += kClsThreads / parts_v) {
-            const int c = c0 + tid % (kClsThreads / parts_v), part = tid / (kClsThreads / parts_v);
+        {
+            const int c = tid % (kClsThreads / parts_v), part = tid / (kClsThreads / parts_v);
             if (c < dv && part < parts_v)
-                for (int j = part; j < cn; j += parts_v) {
-                    const size_t at = (g * n + j0 + j) * dv + c;
-                    const float add = s_p[j] * s_do[c];
-                    st(dV, at, j0 + j == 0 ? add : ld(dV, at) + add);
+                for (int j = part; j < cn; j += kClsBatch * parts_v) {
+                    float old[kClsBatch];
+#pragma unroll
+                    for (int u = 0; u < kClsBatch; ++u) {
+                        const int ju = j + u * parts_v;
+                        old[u] = ju < cn && j0 + ju != 0 ? ld(dV, (g * n + j0 + ju) * dv + c) : 0.f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < kClsBatch; ++u) {
+                        const int ju = j + u * parts_v;
+                        if (ju < cn) st(dV, (g * n + j0 + ju) * dv + c, old[u] + s_p[ju] * s_do[c]);
+                    }
                 }
         }
         __syncthreads();
     }
     // dq_cls: combine the parts of each column in order
-    int slot = 0;
-    for (int c0 = 0; c0 < d; c0 += kClsThreads / parts, ++slot) {
-        const int c = c0 + tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
-        if (c < d && part < parts) s_acc[part * d + c] = dq[slot & 3];
+    {
+        const int c = tid % (kClsThreads / parts), part = tid / (kClsThreads / parts);
+        if (c < d && part < parts) s_acc[part * d + c] = dq;
     }
     __syncthreads();
     for (int c = tid; c < d; c += kClsThreads) {
@@ -315,7 +430,7 @@ __global__ void cls_row_bwd(const T* __restrict__ Q, const T* __restrict__ K, co
         for (int k = 0; k < parts; ++k) tot += s_acc[k * d + c];
         st(dQ, g * n * d + c, beta_cls * tot);
     }
-    dbc = reduce(dbc, false);
+    dbc = cls_reduce<false>(dbc, s_red);
     if (tid == 0) dbeta_cls[g] = dbc;
 }
 
@@ -326,7 +441,7 @@ int run_cls_row(const lot_shape& s, const void* Q, const void* K, const void* V,
 {
     const int G = s.B * s.H;
     const int parts = kClsThreads / s.d_v > 0 ? kClsThreads / s.d_v : 1;
-    const size_t shmem = (size_t)parts * s.d_v * sizeof(float);      // d_v <= 1024: at most 4 columns per thread
+    const size_t shmem = ((size_t)s.d_k + (size_t)parts * s.d_v) * sizeof(float);
     if (s.io_dtype == LOT_BF16)
         cls_row<uint16_t><<<G, kClsThreads, shmem, stream>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
                                                               (uint16_t*)out, s.n, s.d_k, s.d_v, beta_cls);
