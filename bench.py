@@ -119,6 +119,9 @@ def main() -> int:
                          "over the paper's runtime grid: n = 2^10..2^17, r in {32, 64, 128, 256}, T = 5; one JSON line")
     ap.add_argument("--grid-point", default=None, metavar="N,R",
                     help="with --runtime-grid: only this point of the grid (for a kernel trace of one shape)")
+    ap.add_argument("--cls", type=float, default=None, metavar="BETA_CLS",
+                    help="time the [CLS] variant instead (token 0 a softmax row with this temperature, LOT attention "
+                         "among the other tokens); not the headline configuration, and no CPU leg")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB ten times "
                          "(used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -158,10 +161,16 @@ def main() -> int:
     sets = [dev] + [{k: (v.clone() if k in ("Q", "K", "V") else v) for k, v in dev.items()} for _ in range(rotate - 1)]
     outs = [torch.empty_like(dev["V"]) for _ in range(rotate)]
 
+    def forward(s, out):
+        if args.cls is None:
+            lot.lot_attention_fwd(s["Q"], s["K"], s["V"], s["Z"], s["beta"], w.eps, w.iters,
+                                  out=out, workspace=ws, path=path)
+        else:
+            lot.lot_attention_cls_fwd(s["Q"], s["K"], s["V"], s["Z"], s["beta"], w.eps, w.iters, args.cls,
+                                      out=out, workspace=ws, path=path)
+
     def step(k):
-        s = sets[k % rotate]
-        lot.lot_attention_fwd(s["Q"], s["K"], s["V"], s["Z"], s["beta"], w.eps, w.iters,
-                              out=outs[k % rotate], workspace=ws, path=path)
+        forward(sets[k % rotate], outs[k % rotate])
 
     for k in range(args.warmup):
         step(k)
@@ -193,8 +202,7 @@ def main() -> int:
         torch.cuda.synchronize()
         tw0 = time.perf_counter()
         for _ in range(args.steps):
-            lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters,
-                                  out=outs[0], workspace=ws, path=path)
+            forward(dev, outs[0])
         torch.cuda.synchronize()
         warm_ms = (time.perf_counter() - tw0) * 1e3 / args.steps
 
@@ -223,7 +231,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "%s: B=%d H=%d n=%d d=%d r=%d io=%s eps=%g T=%d" % (
             w.name, w.B, w.H, w.n, w.d, w.r, w.dtype, w.eps, w.iters),
-            "io_dtype": w.dtype, "path": args.path, "input_sets_rotated": rotate},
+            "io_dtype": w.dtype, "path": args.path, "input_sets_rotated": rotate,
+            "variant": "plain" if args.cls is None else "[CLS] row, beta_cls=%g" % args.cls},
         "head_tokens_per_s": w.G * w.n * args.steps / total_s,
         "kernel_ms": {"mean": kernel_ms, "p10": float(np.percentile(dev_ms, 10)),
                       "p50": float(np.percentile(dev_ms, 50)), "p90": float(np.percentile(dev_ms, 90))},
@@ -241,8 +250,12 @@ def main() -> int:
 
         def bstep(k):
             s_ = sets[k % rotate]
-            lot.lot_attention_bwd(s_["Q"], s_["K"], s_["V"], s_["Z"], s_["beta"], w.eps, w.iters, dOs[k % rotate],
-                                  workspace=ws_b, path=path)
+            if args.cls is None:
+                lot.lot_attention_bwd(s_["Q"], s_["K"], s_["V"], s_["Z"], s_["beta"], w.eps, w.iters, dOs[k % rotate],
+                                      workspace=ws_b, path=path)
+            else:
+                lot.lot_attention_cls_bwd(s_["Q"], s_["K"], s_["V"], s_["Z"], s_["beta"], w.eps, w.iters, args.cls,
+                                          dOs[k % rotate], workspace=ws_b, path=path)
 
         for k in range(3):
             bstep(k)
@@ -264,7 +277,7 @@ def main() -> int:
                                            "algorithmic_bytes": mb}}
         del dOs, ws_b
 
-    if not args.no_cpu:
+    if not args.no_cpu and args.cls is None:
         from oracle import lot_oracle
         cores = min(16, len(os.sched_getaffinity(0)))
         # bounded sample: at most `cores` whole (batch, head) problems of the same workload

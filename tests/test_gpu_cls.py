@@ -26,6 +26,9 @@ CASES = {
     "reference_only": S(W["tiny"], B=1, H=2, n=90, d=16, r=80, iters=4, seed=84),
     "several_softmax_chunks": S(W["tiny"], B=1, H=2, n=5000, d=32, r=8, iters=4, seed=85),
     "grouped_r128_bf16": S(W["long_4k"], B=1, H=2, n=700, r=128, iters=4, seed=87),   # 64 < r <= 256: grouped kernels
+    # head widths below and above what one pass of the softmax row's lane groups covers (16 lanes x 4 columns)
+    "narrow_head": S(W["tiny"], B=1, H=2, n=300, d=8, r=8, iters=4, seed=89),
+    "wide_head": S(W["tiny"], B=1, H=2, n=261, d=136, r=8, iters=4, seed=90),
 }
 
 
@@ -91,6 +94,9 @@ BWD_CASES = {
     # more than 64 pivots: the grouped tile kernels, here with the row stride of the [CLS] layout
     "grouped_r128_bf16": S(W["long_4k"], B=1, H=2, n=700, r=128, iters=4, seed=87),
     "grouped_r80_f32": S(W["tiny"], B=1, H=2, n=290, d=32, r=80, iters=4, seed=88),
+    "narrow_head": S(W["tiny"], B=1, H=2, n=300, d=8, r=8, iters=4, seed=89),
+    "wide_head": S(W["tiny"], B=1, H=2, n=261, d=136, r=8, iters=4, seed=90),
+    "wide_head_bf16_chunks": S(W["long_4k"], B=1, H=1, n=2100, d=136, r=8, iters=3, seed=91),
 }
 
 
