@@ -163,3 +163,45 @@ def test_cls_backward_full_size_deit_on_sampled_problems():
         err = abs(float(got[5][b, h]) - float(refs[5][0, 0])) / max(1e-12, abs(float(refs[5][0, 0])))
         print("  problem %d dbeta_cls rel err %.3e" % (gi, err), flush=True)
         assert err <= 1e-4
+
+
+@pytest.mark.parametrize("d,d_v,bf16", [(16, 40, False), (24, 8, False), (72, 136, True)])
+def test_cls_variant_with_value_width_other_than_key_width(d, d_v, bf16):
+    """Forward and backward with d_v != d_k (plain kernels for the LOT part): the softmax row splits
+    its threads by the key width for dq_cls and dK and by the value width for the output row and dV."""
+    import torch
+    from oracle import lot_oracle, lot_oracle_bwd
+    from paper_2509_23436_amd import lot
+    B, H, n, r, eps, iters, beta_cls = 1, 2, 150, 8, 0.1, 4, 1.3
+    rng = np.random.default_rng(900 + d + d_v)
+    x = {"Q": rng.standard_normal((B, H, n, d)) * d ** -0.5, "K": rng.standard_normal((B, H, n, d)) * d ** -0.5,
+         "V": rng.standard_normal((B, H, n, d_v)), "Z": rng.standard_normal((H, r, d)) * d ** -0.5,
+         "dO": rng.standard_normal((B, H, n, d_v))}
+    x = {k: v.astype(np.float32) for k, v in x.items()}
+    if bf16:
+        x = {k: synth.round_to_bf16(v) for k, v in x.items()}
+    b = rng.random((H, r)) + 0.2
+    x["beta"] = (b / b.sum(axis=-1, keepdims=True)).astype(np.float32)
+    print("case d=%d d_v=%d bf16=%s n=%d r=%d" % (d, d_v, bf16, n, r), flush=True)
+    dtype = "bf16" if bf16 else "f32"
+    tol = 2e-2 if bf16 else 1e-4
+    dev = to_device(x, dtype)
+    ref = lot_oracle.attention_cls(x["Q"], x["K"], x["V"], x["Z"], x["beta"], eps, iters, beta_cls)
+    out = lot.lot_attention_cls_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters, beta_cls)
+    torch.cuda.synchronize()
+    O = to_host_f64(out)
+    assert O.shape == ref.shape
+    err = max(rel_max_err(O[:, :, 0], ref[:, :, 0]), rel_max_err(O[:, :, 1:], ref[:, :, 1:]))
+    print("  forward rel err %.3e (bar %.0e)" % (err, tol), flush=True)
+    assert err <= tol
+    refs, _ = lot_oracle_bwd.attention_cls_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], eps, iters, beta_cls, x["dO"])
+    got = lot.lot_attention_cls_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters, beta_cls, dev["dO"])
+    torch.cuda.synchronize()
+    for nm, g, rf in zip(("dQ", "dK", "dV", "dZ", "dbeta", "dbeta_cls"), got, refs):
+        g = to_host_f64(g)
+        assert g.shape == rf.shape, nm
+        e = rel_max_err(g, rf)
+        print("  %-9s rel err %.3e" % (nm, e), flush=True)
+        assert e <= tol, nm
+        if nm in ("dQ", "dK", "dV"):
+            assert rel_max_err(g[:, :, 0], rf[:, :, 0]) <= tol, nm
