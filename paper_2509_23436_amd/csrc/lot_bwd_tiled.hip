@@ -23,7 +23,7 @@
 // through both Sinkhorn problems and the glued composition.  The derivation is this file's.)
 //
 // Launches:
-//   clear | forward sweep (T passes: column sums and Gram matrices; then the two token contractions
+//   forward sweep (T passes: column sums and Gram matrices; then the two token contractions
 //   U = sum W2 V, Wd = sum W1 dO) | mid (Y', dYraw) together with the Gram reduce | glue (s, N, dV) |
 //   recursion | assemble, all iterations at once (dQ, dK, dZ partials) | assemble, iteration by iteration
 //   (only workgroups the former marked; every workgroup when there are more than 16 iterations) |
@@ -32,8 +32,9 @@
 // workgroups of a pair exchange their column sums through one integer atomic per pivot that also
 // counts the contributors, and wait (bounded) for the count before the next pass; the write-out of
 // the pass's Gram matrix sits between posting and waiting, so the exchange is rarely waited for.
-// Otherwise the sweep is T + 1 launches of the same tile code, with launch boundaries as the only
-// synchronisation.  Both solves share every launch (pair = side * G + g, side 0 = queries).  All
+// (The first workgroup of a pair zeroes the pair's words and says so under the launch's nonce; the
+// others check that before their first post.)  Otherwise the sweep is a clearing launch and T + 1
+// launches of the same tile code, with launch boundaries as the only synchronisation.  Both solves share every launch (pair = side * G + g, side 0 = queries).  All
 // reductions have a fixed order except the column sums, which are exchanged as integers: results
 // are reproducible.
 #include <cstdlib>
@@ -83,6 +84,7 @@ struct BtParams {
     float* db_glue;               // [G][64]
     float* dz_part;               // [pairs][chunks][64][D]
     unsigned* redo;               // [pairs][chunks]  workgroups whose tiles the assemble kernel redoes iteration by iteration
+    unsigned long long* cleared;  // [pairs]  nonce of the launch whose sweep has zeroed the pair's column sums
     int G, H, B, r, chunks, tiles_per_wg, k, T;
     // per side (0 = queries, dO, dQ; 1 = keys, values, dK, dV):
     int n_side[2];                // tokens per problem
@@ -401,6 +403,18 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
     if (wave == 0) stash_head_pivots<IO, D, RB>(p, w.h, sh.zstash, lane);
     if (tid == 0) s_ok = 1;
     float gv = tid < r ? 0.f : kNegBig;     // g^{k-1}_t, carried by thread t < 64
+    if (blockIdx.x == 0 && tid == 0)
+        __hip_atomic_store(p.status + 1, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // this launch
+    if (w.chunk == 0) {
+        // The first workgroup of a pair zeroes the pair's column sums of every pass and announces it
+        // under this launch's nonce; the others wait for that before their first post, a whole pass
+        // later.  (No separate clearing launch.)
+        for (int e = tid; e < (T + 1) * 64; e += kThreads)
+            __hip_atomic_store(p.colacc + ((size_t)(e >> 6) * pairs + w.pair) * 64 + (e & 63), 0ull, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        publish_barrier();   // the zeroes have been acknowledged
+        if (tid == 0) __hip_atomic_store(p.cleared + w.pair, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 
     for (int k = 1; k <= T; ++k) {
         if (tid < 64) {
@@ -433,6 +447,23 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
         f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
         zero_pass<RB, NB>(cs, Gm);
         sweep_tiles<IO, D, RB, false, MASS>(p, w, X, nullptr, sh, xc, mc, true, wave, lane, c1, cs, Gm, U);
+        if (k == 1 && w.chunk != 0) {
+            // first post of this launch: the pair's column sums must have been zeroed
+            if (tid == 0) {
+                bool ok = false;
+                for (uint32_t it = 0; it < p.spin_limit; ++it) {
+                    if (__hip_atomic_load(p.cleared + w.pair, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nonce) { ok = true; break; }
+                    if ((it & 63u) == 63u && __hip_atomic_load(p.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nonce) break;
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                if (!ok) {
+                    __hip_atomic_store(p.status, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    s_ok = 0;
+                }
+            }
+            __syncthreads();
+            if (!s_ok) return;
+        }
         finish_pass<IO, D, RB>(p, w, sh, k, tid, wave, lane, cs, Gm);
     }
     __syncthreads();
@@ -1347,7 +1378,8 @@ __global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) bt_final(BtParam
     }
 }
 
-// zeroes the column-sum words and records the launch in the status area
+// zeroes the column-sum words and records the launch in the status area (only where the sweep is a
+// launch per pass: the persistent sweep clears for itself)
 __global__ void bt_clear(unsigned long long* p, size_t count, unsigned long long* status, unsigned long long nonce)
 {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1361,8 +1393,6 @@ int launch_all(const BwdArgs& a, BtParams p)
     const lot_shape& s = a.s;
     const int pairs = 2 * p.G, T = a.iters, R = 32 * RB;
     hipStream_t st = a.stream;
-    const size_t words = (size_t)(T + 1) * pairs * 64;
-    bt_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words, p.status, p.nonce);
     const unsigned grid = (unsigned)pairs * p.chunks;
     // The persistent sweep needs the workgroups of a pair resident together: the whole grid fits the
     // device, or a pair is a single workgroup (which then waits for nobody but itself).
@@ -1390,6 +1420,8 @@ int launch_all(const BwdArgs& a, BtParams p)
         if (mass) bt_sweep<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);
         else bt_sweep<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
     } else {
+        const size_t words = (size_t)(T + 1) * pairs * 64;
+        bt_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words, p.status, p.nonce);
         for (int k = 1; k <= T; ++k) {
             p.k = k;
             if (mass) bt_forward<IO, D, RB, false, true><<<grid, kThreads, 0, st>>>(p);
@@ -1452,6 +1484,7 @@ BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters)
     w.db_glue = take(G * 64 * 4);
     w.dz_part = take(pairs * chunks * 64 * D * 4);
     w.redo = take(pairs * chunks * 4);
+    w.cleared = take(pairs * 8);
     w.total = off;
     return w;
 }
@@ -1483,6 +1516,7 @@ int run_backward_tiled(const BwdArgs& a)
     p.db_glue = (float*)(a.ws + L.db_glue);
     p.dz_part = (float*)(a.ws + L.dz_part);
     p.redo = (unsigned*)(a.ws + L.redo);
+    p.cleared = (unsigned long long*)(a.ws + L.cleared);
     p.G = s.B * s.H; p.H = s.H; p.B = s.B; p.r = s.r; p.chunks = L.chunks; p.tiles_per_wg = tiles_per_wg_for(s); p.T = a.iters;
     // s.n is the longer side (cross attention); a side with fewer tiles leaves its last workgroups idle
     p.n_side[0] = a.n_q > 0 ? a.n_q : s.n;

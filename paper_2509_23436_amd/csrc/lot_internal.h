@@ -153,7 +153,7 @@ struct BwdArgs {
 
 // Workspace of the backward pass, tiled path.
 struct BwdTiledWorkspace {
-    size_t colacc, ghist, gram_part, gram_full, u_part, yp, dyraw, sn_part, dcs, rhop, db_pair, db_glue, dz_part, redo;
+    size_t colacc, ghist, gram_part, gram_full, u_part, yp, dyraw, sn_part, dcs, rhop, db_pair, db_glue, dz_part, redo, cleared;
     size_t total;
     int chunks;
 };
