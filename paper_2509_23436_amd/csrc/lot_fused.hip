@@ -102,6 +102,12 @@ __device__ inline bool spin_until(uint32_t* counter, uint32_t target, const unsi
 // ---------------------------------------------------------------------------------------------
 // one pass over this wavefront's tiles
 // ---------------------------------------------------------------------------------------------
+// fp32 I/O: the similarities are six bf16 products over pieces of the operands (pivot pieces in LDS)
+// instead of fp32 MFMAs -- except in the one variant whose two workgroups per compute unit would no
+// longer fit the LDS with the 24 KB of pieces.
+template <typename IO, int D, int RB, int WAVES>
+constexpr bool similarity_by_pieces() { return io_is_f32<IO>::value && !(D == 64 && RB == 2 && WAVES == 4); }
+
 template <typename IO, int D, int RB, int EPI, int WAVES>
 __device__ __forceinline__ void run_pass(
     const FusedParams& p, const IO* __restrict__ X, const IO* __restrict__ Xnext, int next_side,
@@ -171,7 +177,8 @@ __device__ __forceinline__ void run_pass(
         asm volatile("" : "+v"(skew));
         f32x16 acc[RB];
         load_pivot_vector<RB>(acc, glds + skew, kg);
-        similarity<D, RB>(acc, zf, xc);
+        if constexpr (similarity_by_pieces<IO, D, RB, WAVES>()) similarity_pieces<D, RB>(acc, zlds, xc, lane, skew);
+        else similarity<D, RB>(acc, zf, xc);
 
         // token-side update: row maximum, exponentials, row sum
         float m0 = acc[0][0], m1 = acc[0][1], m2 = acc[0][2], m3 = acc[0][3];
@@ -358,7 +365,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
     __shared__ float s_beta[64];
     __shared__ __attribute__((aligned(16))) float s_u[64 * D];
     __shared__ __attribute__((aligned(16))) uint16_t s_tr[WAVES * 2 * 64 * kTrStride];
-    __shared__ __attribute__((aligned(16))) char s_zf[RB * sizeof(Frag<IO, D>) * 64];
+    // the pivots' bf16 pieces for the similarity products where those are used (the tile loop reads them from here)
+    __shared__ __attribute__((aligned(16))) char s_zf[similarity_by_pieces<IO, D, RB, WAVES>() ? PieceStashBytes<D, RB>::value : 16];
     __shared__ unsigned long long s_prev[2][2][64];   // last word seen per (side, parity, pivot)
     __shared__ int s_ok;
     __shared__ int s_okx[2];           // outcome of the collect inside an exchange, per side
@@ -401,7 +409,9 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             const int t = 32 * mb + i;
             load_pivots<D>(zf[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
         }
-        if (wave == 0) stash_pivots<D, RB>(s_zf, zf, lane);
+        if constexpr (similarity_by_pieces<IO, D, RB, WAVES>()) {
+            if (wave == 0) stash_pivot_pieces<D, RB>(s_zf, zf, lane);
+        }
         if (tid < 128) s_g[tid >> 6][tid & 63] = (tid & 63) < r ? 0.f : kNegBig;
         if (tid < 64) s_beta[tid] = tid < r ? beta_read : 1.f;
         if (tid < 256) (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch

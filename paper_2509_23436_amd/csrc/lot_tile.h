@@ -295,6 +295,35 @@ __device__ __forceinline__ void fetch_pivots(Frag<float, D> (&zf)[RB], const voi
 }
 
 // acc[mb] += Z_block(mb) X_tile^T   (pivots x tokens); acc enters holding the pivot potentials
+// Eight fp32 numbers as three bf16 vectors whose sum is exact: h = the upper 16 bits, m = the upper
+// 16 bits of what is left, l = the rest (at most 8 significant bits by then).
+struct Pieces { bf16x8 h, m, l; };
+__device__ __forceinline__ void cut_in_three(const float* v, Pieces& out)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 ph, pm, pl;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        uint32_t hb[2], mbits[2], lb[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const float x = v[2 * u + e];
+            hb[e] = __builtin_bit_cast(uint32_t, x);
+            const float r1 = x - __builtin_bit_cast(float, hb[e] & 0xffff0000u);
+            mbits[e] = __builtin_bit_cast(uint32_t, r1);
+            const float r2 = r1 - __builtin_bit_cast(float, mbits[e] & 0xffff0000u);
+            lb[e] = __builtin_bit_cast(uint32_t, r2);
+        }
+        // upper halves of the two words, the first in the low half of the result
+        ph[u] = __builtin_amdgcn_perm(hb[1], hb[0], 0x07060302u);
+        pm[u] = __builtin_amdgcn_perm(mbits[1], mbits[0], 0x07060302u);
+        pl[u] = __builtin_amdgcn_perm(lb[1], lb[0], 0x07060302u);
+    }
+    out.h = __builtin_bit_cast(bf16x8, ph);
+    out.m = __builtin_bit_cast(bf16x8, pm);
+    out.l = __builtin_bit_cast(bf16x8, pl);
+}
+
 template <int D, int RB>
 __device__ __forceinline__ void similarity(f32x16 (&acc)[RB], const Frag<uint16_t, D> (&zf)[RB],
                                            const Frag<uint16_t, D>& xf)
@@ -314,6 +343,50 @@ __device__ __forceinline__ void similarity(f32x16 (&acc)[RB], const Frag<float, 
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
             acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(zf[mb].v[s], xf.v[s], acc[mb], 0, 0, 0);
+}
+
+// The same product with the fp32 operands as three bf16 pieces each (8 + 8 + 8 significant bits, cut,
+// not rounded, so the pieces add up to the number exactly) and the six products that matter: what is
+// left out is below 2^-23 of |z||x|, and six bf16 products cost 3/8 of the matrix-pipe cycles of the
+// fp32 MFMA.  The contraction index may be permuted freely as long as both operands agree: a lane's
+// eight consecutive registers are taken as its eight numbers of one MFMA step.  The pivots' pieces are
+// cut once and kept in LDS ([block][step][piece][lane] vectors of 8); the token rows are cut here.
+template <int D, int RB> struct PieceStashBytes { static constexpr int value = RB * (D / 16) * 3 * 64 * 16; };
+template <int D, int RB>
+__device__ __forceinline__ void stash_pivot_pieces(void* lds, const Frag<float, D> (&zf)[RB], int lane)
+{
+    bf16x8* dst = reinterpret_cast<bf16x8*>(lds);
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            Pieces zp;
+            cut_in_three(zf[mb].v + 8 * s, zp);
+            bf16x8* at = dst + (size_t)((mb * (D / 16) + s) * 3) * 64 + lane;
+            at[0] = zp.h; at[64] = zp.m; at[128] = zp.l;
+        }
+}
+template <int D, int RB>
+__device__ __forceinline__ void similarity_pieces(f32x16 (&acc)[RB], const void* lds, const Frag<float, D>& xf,
+                                                  int lane, int skew)
+{
+    const bf16x8* src = reinterpret_cast<const bf16x8*>(lds) + skew;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+        Pieces xp;
+        cut_in_three(xf.v + 8 * s, xp);
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) {
+            const bf16x8* at = src + (size_t)((mb * (D / 16) + s) * 3) * 64 + lane;
+            const bf16x8 zh = at[0], zm = at[64], zl = at[128];
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zl, xp.h, acc[mb], 0, 0, 0);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, xp.l, acc[mb], 0, 0, 0);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zm, xp.m, acc[mb], 0, 0, 0);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zm, xp.h, acc[mb], 0, 0, 0);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, xp.m, acc[mb], 0, 0, 0);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zh, xp.h, acc[mb], 0, 0, 0);
+        }
+    }
 }
 
 // pivot index of accumulator register j of block mb in lane-half kg
