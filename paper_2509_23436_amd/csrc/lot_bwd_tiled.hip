@@ -131,7 +131,7 @@ template <typename IO, int D, int RB> struct SweepShared {
     static constexpr int kR = 32 * RB;
     __attribute__((aligned(16))) float buf[kR * kR > kR * D ? kR * kR : kR * D];    // a Gram matrix, or a [pivot][D] sum
     __attribute__((aligned(16))) uint16_t tr[kWaves * 2 * kR * kTrStride];
-    __attribute__((aligned(16))) char zstash[StashBytes<IO, D, RB>::value];
+    __attribute__((aligned(16))) char zstash[PivotStashBytes<IO, D, RB>::value];
     static_assert(kWaves * 2 * kR * kTrStride * sizeof(uint16_t) >= kR * kR * sizeof(float),
                   "the transposition area doubles as the second buffer of the Gram reduction");
 };
@@ -171,7 +171,7 @@ __device__ __forceinline__ void stash_head_pivots(const BtParams& p, int h, char
         const int t = 32 * mb + i;
         load_pivots<D>(z0[mb], p.Z + ((size_t)h * p.r + min(t, p.r - 1)) * D, kg, t < p.r);
     }
-    stash_pivots<D, RB>(zstash, z0, lane);
+    stash_similarity_pivots<IO, D, RB>(zstash, z0, lane);
 }
 
 // One pass over the wavefront's tiles with the potentials in sh.g.  xc and mc hold the first tile's
@@ -211,13 +211,7 @@ __device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace&
         }
         f32x16 acc[RB];
         float wt;
-        {
-            int skew = 0;
-            asm volatile("" : "+v"(skew));
-            Frag<IO, D> zf[RB];
-            fetch_pivots<D, RB>(zf, sh.zstash, lane, skew);
-            tile_weights<IO, D, RB>(acc, wt, zf, xc, sh.g, kg, c1, tile * kTileTokens + i < n);
-        }
+        tile_weights<IO, D, RB>(acc, wt, sh.zstash, xc, sh.g, lane, c1, tile * kTileTokens + i < n);
         // what goes through the transposition: W sqrt(m) for the Gram matrix, W m for the keys'
         // contraction with V, W for the queries' contraction with dO
         const float wcs = MASS ? wt * mc : wt;
@@ -539,7 +533,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
     __shared__ float s_part[kWaves][2][64];
     __shared__ __attribute__((aligned(16))) float s_y[64 * D];
     __shared__ __attribute__((aligned(16))) bf16x8 s_yf[2][2 * RB * NB * 64];
-    __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
+    __shared__ __attribute__((aligned(16))) char s_zstash[PivotStashBytes<IO, D, RB>::value];
     __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
     // bf16 I/O: what the bf16 rounding of that operand leaves out (see the incoming-gradient tile below)
     __shared__ __attribute__((aligned(16))) char s_ystash_lo[kSplit ? 16 : StashBytes<IO, D, RB>::value];
@@ -575,7 +569,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
             const int t = 32 * mb + i;
             load_pivots<D>(z0[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
         }
-        stash_pivots<D, RB>(s_zstash, z0, lane);
+        stash_similarity_pivots<IO, D, RB>(s_zstash, z0, lane);
     }
     // keys: the expansion to dV needs rho'_t dYraw_t as B fragments
     if (side == 1) {
@@ -622,9 +616,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
         int skew = 0;
         asm volatile("" : "+v"(skew));
         {
-            Frag<IO, D> zf[RB];
-            fetch_pivots<D, RB>(zf, s_zstash, lane, skew);
-            tile_weights<IO, D, RB>(acc, w, zf, xc, s_g, kg, c1, tile * kTileTokens + i < n);
+            tile_weights<IO, D, RB>(acc, w, s_zstash, xc, s_g, lane, c1, tile * kTileTokens + i < n);
         }
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
@@ -811,7 +803,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap,
     constexpr int kParts = kSplit ? 2 : 1;     // bf16 hi only, or hi and lo
     __shared__ __attribute__((aligned(16))) bf16x8 s_zf[2][2 * RB * NB * 64];
     __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 32 * RB * kTrStride];
-    __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
+    __shared__ __attribute__((aligned(16))) char s_zstash[PivotStashBytes<IO, D, RB>::value];
     __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
     static_assert(kSplit || sizeof(s_zf[1]) >= (size_t)StashBytes<IO, D, RB>::value, "the lo stash takes the place of s_zf[1]");
     char* const s_ystash_lo = reinterpret_cast<char*>(s_zf[1]);   // bf16 I/O only (s_zf[1] is then unused)
@@ -845,7 +837,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap,
             const int t = 32 * mb + i;
             load_pivots<D>(z0[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
         }
-        stash_pivots<D, RB>(s_zstash, z0, lane);
+        stash_similarity_pivots<IO, D, RB>(s_zstash, z0, lane);
     }
     // Z rows as B fragments (the values the forward pass multiplied with: rounded to bf16 for bf16 I/O)
     for (int e = tid; e < 64 * D; e += kThreads) {
@@ -904,9 +896,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap,
 #pragma unroll
             for (int j = 0; j < 16; ++j) { sc[mb][j] = 0.f; dacc[mb][j] = 0.f; }
         {
-            Frag<IO, D> zf[RB];
-            fetch_pivots<D, RB>(zf, s_zstash, lane, skew);
-            similarity<D, RB>(sc, zf, xc);
+            similarity_stashed<IO, D, RB>(sc, s_zstash, xc, lane, skew);
         }
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
@@ -1065,7 +1055,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
     constexpr int kParts = kSplit ? 2 : 1;     // bf16 hi only, or hi and lo
     __shared__ __attribute__((aligned(16))) bf16x8 s_zf[2][2 * RB * NB * 64];
     __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 32 * RB * kTrStride];
-    __shared__ __attribute__((aligned(16))) char s_zstash[StashBytes<IO, D, RB>::value];
+    __shared__ __attribute__((aligned(16))) char s_zstash[PivotStashBytes<IO, D, RB>::value];
     __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
     static_assert(kSplit || sizeof(s_zf[1]) >= (size_t)StashBytes<IO, D, RB>::value, "the lo stash takes the place of s_zf[1]");
     char* const s_ystash_lo = reinterpret_cast<char*>(s_zf[1]);   // bf16 I/O only (s_zf[1] is then unused)
@@ -1118,7 +1108,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
             const int t = 32 * mb + i;
             load_pivots<D>(z0[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
         }
-        stash_pivots<D, RB>(s_zstash, z0, lane);
+        stash_similarity_pivots<IO, D, RB>(s_zstash, z0, lane);
     }
     // Z rows as B fragments (the values the forward pass multiplied with: rounded to bf16 for bf16 I/O)
     for (int e = tid; e < 32 * RB * D; e += kThreads) {
@@ -1191,9 +1181,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) sc[mb][j] = 0.f;
-            Frag<IO, D> zf[RB];
-            fetch_pivots<D, RB>(zf, s_zstash, lane, skew);
-            similarity<D, RB>(sc, zf, xc);
+            similarity_stashed<IO, D, RB>(sc, s_zstash, xc, lane, skew);
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll

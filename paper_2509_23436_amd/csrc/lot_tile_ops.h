@@ -14,16 +14,48 @@ constexpr int kThreads = kWaves * 64;
 // ---------------------------------------------------------------------------------------------
 // tile helpers
 // ---------------------------------------------------------------------------------------------
+template <typename IO, int D, int RB> struct StashBytes { static constexpr int value = RB * (int)sizeof(Frag<IO, D>) * 64; };
+
+// The pivots of the similarity product in LDS, in a layout private to the three functions below.
+// fp32 I/O: as bf16 pieces for six bf16 products per step instead of fp32 MFMAs (3/8 of the matrix-
+// pipe cycles, and no registers for the pivots), except where the 1.5 times larger area would cost a
+// resident workgroup (d = 64 with two pivot blocks).
+template <typename IO, int D, int RB>
+constexpr bool pivots_in_pieces() { return io_is_f32<IO>::value && !(D == 64 && RB == 2); }
+template <typename IO, int D, int RB> struct PivotStashBytes {
+    static constexpr int value = pivots_in_pieces<IO, D, RB>() ? PieceStashBytes<D, RB>::value : StashBytes<IO, D, RB>::value;
+};
+template <typename IO, int D, int RB>
+__device__ __forceinline__ void stash_similarity_pivots(void* lds, const Frag<IO, D> (&zf)[RB], int lane)
+{
+    if constexpr (pivots_in_pieces<IO, D, RB>()) stash_pivot_pieces<D, RB>(lds, zf, lane);
+    else stash_pivots<D, RB>(lds, zf, lane);
+}
+// acc += Z X^T for the tile in xf; skew is an opaque zero that keeps the LDS reads inside the tile loop
+template <typename IO, int D, int RB>
+__device__ __forceinline__ void similarity_stashed(f32x16 (&acc)[RB], const void* zstash, const Frag<IO, D>& xf,
+                                                   int lane, int skew)
+{
+    if constexpr (pivots_in_pieces<IO, D, RB>()) {
+        similarity_pieces<D, RB>(acc, zstash, xf, lane, skew);
+    } else {
+        Frag<IO, D> zf[RB];
+        fetch_pivots<D, RB>(zf, zstash, lane, skew);
+        similarity<D, RB>(acc, zf, xf);
+    }
+}
+
 // On return acc holds e_it = exp2((C_it + g_t) c1 - m_i) (pivots past r give exactly 0) and w the
 // reciprocal of their row sum, so the row-normalised kernel is W_it = acc * w.  pot: LDS, 64 floats.
 template <typename IO, int D, int RB>
-__device__ __forceinline__ void tile_weights(f32x16 (&acc)[RB], float& w, const Frag<IO, D> (&zf)[RB],
-                                             const Frag<IO, D>& xf, const float* pot, int kg, float c1, bool valid)
+__device__ __forceinline__ void tile_weights(f32x16 (&acc)[RB], float& w, const void* zstash,
+                                             const Frag<IO, D>& xf, const float* pot, int lane, float c1, bool valid)
 {
+    const int kg = lane >> 5;
     int skew = 0;
     asm volatile("" : "+v"(skew));
     load_pivot_vector<RB>(acc, pot + skew, kg);
-    similarity<D, RB>(acc, zf, xf);
+    similarity_stashed<IO, D, RB>(acc, zstash, xf, lane, skew);
     float m0 = acc[0][0], m1 = acc[0][1];
 #pragma unroll
     for (int mb = 0; mb < RB; ++mb)
@@ -259,7 +291,6 @@ __device__ __forceinline__ void load_pivots_lds(Frag<float, D>& f, const float* 
     for (int s = 0; s < D / 2; ++s) f.v[s] = row[kg * (D / 2) + s];
 }
 
-template <typename IO, int D, int RB> struct StashBytes { static constexpr int value = RB * (int)sizeof(Frag<IO, D>) * 64; };
 
 
 }  // namespace
