@@ -534,7 +534,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
     __shared__ __attribute__((aligned(16))) float s_y[64 * D];
     __shared__ __attribute__((aligned(16))) bf16x8 s_yf[2][2 * RB * NB * 64];
     __shared__ __attribute__((aligned(16))) char s_zstash[PivotStashBytes<IO, D, RB>::value];
-    __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
+    constexpr bool kYPieces = true;   // the matrix operand of the dGamma product as bf16 pieces (fp32 I/O)
+    __shared__ __attribute__((aligned(16))) char s_ystash[PivotStashBytes<IO, D, RB, kYPieces>::value];
     // bf16 I/O: what the bf16 rounding of that operand leaves out (see the incoming-gradient tile below)
     __shared__ __attribute__((aligned(16))) char s_ystash_lo[kSplit ? 16 : StashBytes<IO, D, RB>::value];
 
@@ -588,7 +589,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
         Frag<IO, D> y0[RB];
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) load_pivots_lds<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
-        stash_pivots<D, RB>(s_ystash, y0, lane);
+        stash_similarity_pivots<IO, D, RB, kYPieces>(s_ystash, y0, lane);
         if (!kSplit) {
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb) load_pivots_lds_lo<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
@@ -626,13 +627,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_glue(BtParams p)
             // The incoming gradient of the coupling.  s, q and N below meet in differences (N - P s) that
             // are an order of magnitude smaller than their terms, so with bf16 I/O the matrix operand is
             // taken as bf16 hi + lo (two products): its rounding would otherwise show in dbeta.
-            Frag<IO, D> yfrag[RB];
-            fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
-            similarity<D, RB>(dgam, yfrag, vc);
-            if (!kSplit) {
-                fetch_pivots<D, RB>(yfrag, s_ystash_lo, lane, skew);
-                similarity<D, RB>(dgam, yfrag, vc);
-            }
+            similarity_stashed<IO, D, RB, kYPieces>(dgam, s_ystash, vc, lane, skew);
+            if (!kSplit) similarity_stashed<IO, D, RB, kYPieces>(dgam, s_ystash_lo, vc, lane, skew);
         }
         if (weighted) {
 #pragma unroll
@@ -804,7 +800,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap,
     __shared__ __attribute__((aligned(16))) bf16x8 s_zf[2][2 * RB * NB * 64];
     __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 32 * RB * kTrStride];
     __shared__ __attribute__((aligned(16))) char s_zstash[PivotStashBytes<IO, D, RB>::value];
-    __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
+    constexpr bool kYPieces = !(D == 32 && RB == 2);   // the matrix operand of the dGamma product as bf16 pieces (fp32 I/O)
+    __shared__ __attribute__((aligned(16))) char s_ystash[PivotStashBytes<IO, D, RB, kYPieces>::value];
     static_assert(kSplit || sizeof(s_zf[1]) >= (size_t)StashBytes<IO, D, RB>::value, "the lo stash takes the place of s_zf[1]");
     char* const s_ystash_lo = reinterpret_cast<char*>(s_zf[1]);   // bf16 I/O only (s_zf[1] is then unused)
     float* s_hist = reinterpret_cast<float*>(s_dyn);
@@ -855,7 +852,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap,
         Frag<IO, D> y0[RB];
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) load_pivots_lds<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
-        stash_pivots<D, RB>(s_ystash, y0, lane);
+        stash_similarity_pivots<IO, D, RB, kYPieces>(s_ystash, y0, lane);
         if (!kSplit) {
             // bf16 I/O: the lo part of the same operand (see the glue kernel); it takes the place of the
             // lo half of the Z fragments, which only fp32 I/O uses
@@ -966,13 +963,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble(BtParams p, int Tcap,
 #pragma unroll
                 for (int j = 0; j < 16; ++j) dp[mb][j] = 0.f;
             {
-                Frag<IO, D> yfrag[RB];
-                fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
-                similarity<D, RB>(dp, yfrag, vc);                 // dGamma tile
-                if (!kSplit) {
-                    fetch_pivots<D, RB>(yfrag, s_ystash_lo, lane, skew);
-                    similarity<D, RB>(dp, yfrag, vc);
-                }
+                similarity_stashed<IO, D, RB, kYPieces>(dp, s_ystash, vc, lane, skew);                 // dGamma tile
+                if (!kSplit) similarity_stashed<IO, D, RB, kYPieces>(dp, s_ystash_lo, vc, lane, skew);
             }
             {
                 f32x16 rho[RB], dc[RB];
@@ -1056,7 +1048,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
     __shared__ __attribute__((aligned(16))) bf16x8 s_zf[2][2 * RB * NB * 64];
     __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * kParts * 32 * RB * kTrStride];
     __shared__ __attribute__((aligned(16))) char s_zstash[PivotStashBytes<IO, D, RB>::value];
-    __shared__ __attribute__((aligned(16))) char s_ystash[StashBytes<IO, D, RB>::value];
+    constexpr bool kYPieces = true;   // the matrix operand of the dGamma product as bf16 pieces (fp32 I/O)
+    __shared__ __attribute__((aligned(16))) char s_ystash[PivotStashBytes<IO, D, RB, kYPieces>::value];
     static_assert(kSplit || sizeof(s_zf[1]) >= (size_t)StashBytes<IO, D, RB>::value, "the lo stash takes the place of s_zf[1]");
     char* const s_ystash_lo = reinterpret_cast<char*>(s_zf[1]);   // bf16 I/O only (s_zf[1] is then unused)
 
@@ -1141,7 +1134,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
         Frag<IO, D> y0[RB];
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) load_pivots_lds<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
-        stash_pivots<D, RB>(s_ystash, y0, lane);
+        stash_similarity_pivots<IO, D, RB, kYPieces>(s_ystash, y0, lane);
         if (!kSplit) {
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb) load_pivots_lds_lo<D>(y0[mb], s_y + (32 * mb + i) * D, kg);
@@ -1210,13 +1203,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) dgam[mb][j] = 0.f;
-            Frag<IO, D> yfrag[RB];
-            fetch_pivots<D, RB>(yfrag, s_ystash, lane, skew);
-            similarity<D, RB>(dgam, yfrag, vc);
-            if (!kSplit) {
-                fetch_pivots<D, RB>(yfrag, s_ystash_lo, lane, skew);
-                similarity<D, RB>(dgam, yfrag, vc);
-            }
+            similarity_stashed<IO, D, RB, kYPieces>(dgam, s_ystash, vc, lane, skew);
+            if (!kSplit) similarity_stashed<IO, D, RB, kYPieces>(dgam, s_ystash_lo, vc, lane, skew);
             f32x16 br[RB];
             load_pivot_vector<RB>(br, s_brho + skew, kg);
             float q0 = 0.f, q1 = 0.f;

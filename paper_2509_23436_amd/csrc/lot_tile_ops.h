@@ -22,21 +22,22 @@ template <typename IO, int D, int RB> struct StashBytes { static constexpr int v
 // resident workgroup (d = 64 with two pivot blocks).
 template <typename IO, int D, int RB>
 constexpr bool pivots_in_pieces() { return io_is_f32<IO>::value && !(D == 64 && RB == 2); }
-template <typename IO, int D, int RB> struct PivotStashBytes {
-    static constexpr int value = pivots_in_pieces<IO, D, RB>() ? PieceStashBytes<D, RB>::value : StashBytes<IO, D, RB>::value;
+// (ALLOW = false keeps the plain layout for one operand of one kernel, where LDS is short.)
+template <typename IO, int D, int RB, bool ALLOW = true> struct PivotStashBytes {
+    static constexpr int value = ALLOW && pivots_in_pieces<IO, D, RB>() ? PieceStashBytes<D, RB>::value : StashBytes<IO, D, RB>::value;
 };
-template <typename IO, int D, int RB>
+template <typename IO, int D, int RB, bool ALLOW = true>
 __device__ __forceinline__ void stash_similarity_pivots(void* lds, const Frag<IO, D> (&zf)[RB], int lane)
 {
-    if constexpr (pivots_in_pieces<IO, D, RB>()) stash_pivot_pieces<D, RB>(lds, zf, lane);
+    if constexpr (ALLOW && pivots_in_pieces<IO, D, RB>()) stash_pivot_pieces<D, RB>(lds, zf, lane);
     else stash_pivots<D, RB>(lds, zf, lane);
 }
 // acc += Z X^T for the tile in xf; skew is an opaque zero that keeps the LDS reads inside the tile loop
-template <typename IO, int D, int RB>
+template <typename IO, int D, int RB, bool ALLOW = true>
 __device__ __forceinline__ void similarity_stashed(f32x16 (&acc)[RB], const void* zstash, const Frag<IO, D>& xf,
                                                    int lane, int skew)
 {
-    if constexpr (pivots_in_pieces<IO, D, RB>()) {
+    if constexpr (ALLOW && pivots_in_pieces<IO, D, RB>()) {
         similarity_pieces<D, RB>(acc, zstash, xf, lane, skew);
     } else {
         Frag<IO, D> zf[RB];
