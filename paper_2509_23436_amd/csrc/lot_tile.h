@@ -204,7 +204,9 @@ __device__ __forceinline__ uint16_t bf16_bits_of(float x) { return __builtin_bit
 // ---------------------------------------------------------------------------------------------
 // bf16: v_mfma_f32_32x32x16_bf16, lane (i = lane % 32, kg = lane / 32) supplies, for step s,
 //       elements [16 s + 8 kg, +8) of row i.                       D/16 steps.
-// fp32: v_mfma_f32_32x32x2_f32, lane supplies element kg*(D/2) + s. D/2 steps.
+// fp32: v_mfma_f32_32x32x2_f32, lane supplies element kg*(D/2) + s. D/2 steps.  The same registers
+//       also feed the bf16-piece form of the product (similarity_pieces below): registers
+//       [8 s, 8 s + 8) of a lane are then its eight numbers of bf16 step s, D/16 steps.
 template <typename IO, int D> struct Frag;
 template <int D> struct Frag<uint16_t, D> { bf16x8 v[D / 16]; };
 template <int D> struct Frag<float, D> { float v[D / 2]; };
