@@ -103,10 +103,9 @@ __device__ inline bool spin_until(uint32_t* counter, uint32_t target, const unsi
 // one pass over this wavefront's tiles
 // ---------------------------------------------------------------------------------------------
 // fp32 I/O: the similarities are six bf16 products over pieces of the operands (pivot pieces in LDS)
-// instead of fp32 MFMAs -- except in the one variant whose two workgroups per compute unit would no
-// longer fit the LDS with the 24 KB of pieces.
+// instead of fp32 MFMAs.
 template <typename IO, int D, int RB, int WAVES>
-constexpr bool similarity_by_pieces() { return io_is_f32<IO>::value && !(D == 64 && RB == 2 && WAVES == 4); }
+constexpr bool similarity_by_pieces() { return io_is_f32<IO>::value; }
 
 template <typename IO, int D, int RB, int EPI, int WAVES>
 __device__ __forceinline__ void run_pass(
@@ -836,8 +835,14 @@ int launch_sized(const Args& a, bool want_out)
     int dev = 0, cus = 0;
     LOT_HIP_CHECK(hipGetDevice(&dev));
     LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    if (a.s.B * a.s.H <= cus) return launch<IO, D, RB, 8>(a, want_out);
-    return launch<IO, D, RB, 4>(a, want_out);
+    // (fp32 I/O at d = 64 with two pivot blocks: the 24 KB of pivot pieces leave no room in the LDS for
+    // two workgroups per compute unit, so that variant always runs with eight wavefronts)
+    if constexpr (io_is_f32<IO>::value && D == 64 && RB == 2) {
+        return launch<IO, D, RB, 8>(a, want_out);
+    } else {
+        if (a.s.B * a.s.H <= cus) return launch<IO, D, RB, 8>(a, want_out);
+        return launch<IO, D, RB, 4>(a, want_out);
+    }
 }
 
 template <typename IO>

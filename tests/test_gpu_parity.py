@@ -38,6 +38,9 @@ CASES = {
     "many_tiles_f32": S(W["deit_tiny"], B=32, H=4, n=700, d=64, r=16, iters=5, seed=34),
     "two_rounds_f32": S(W["tiny"], B=150, H=4, n=160, d=32, r=8, iters=5, seed=35),
     "two_rounds_bf16": S(W["bert_base"], B=50, H=12, n=300, r=32, iters=3, seed=36),
+    # fp32, d = 64, more than 32 pivots always runs with eight wavefronts: more problems than compute units
+    # makes its workgroups take several problems in turn
+    "two_rounds_f32_d64_r40": S(W["tiny"], B=75, H=4, n=160, d=64, r=40, iters=4, seed=37),
 }
 
 
