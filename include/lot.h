@@ -27,8 +27,10 @@
  *  - beta must be strictly positive and sum to one per head (the paper's p^0); this is a caller
  *    precondition and is not checked.
  *  - With io_dtype = LOT_BF16 the similarities are computed from bf16 operands with fp32
- *    accumulation: Z is rounded to bf16 (nearest even) inside the library.  Potentials, sums and
- *    the r x d_v intermediate are fp32 in both modes.  The output is rounded to io_dtype.
+ *    accumulation: Z is rounded to bf16 (nearest even) inside the library.  With LOT_F32 they are
+ *    accurate to fp32 rounding (fp32 matrix instructions, or bf16 products over exact three-way
+ *    pieces of the operands).  Potentials, sums and the r x d_v intermediate are fp32 in both
+ *    modes.  The output is rounded to io_dtype.
  *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream) and
  *    the call returns without synchronising.  Results are bit-identical from run to run.
  *  - Return value: LOT_OK (0) or a negative lot_status.  Argument validation happens before any
