@@ -26,7 +26,6 @@ import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
@@ -54,6 +53,27 @@ def backward_algorithmic_bytes(w) -> int:
 def compulsory_bytes(w) -> int:
     s = 2 if w.dtype == "bf16" else 4
     return 4 * w.d * s * w.G * w.n
+
+
+def device_clocks():
+    """Current engine (sclk) and memory (mclk) clock of every AMD GPU the driver lists, in MHz, read from
+    sysfs (the starred line of pp_dpm_sclk / pp_dpm_mclk); {} where the files are not readable.  Taken
+    before, during and after the timed region so that a slow box can be told from a regression."""
+    import glob
+    import re
+    out = {}
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        card = path.split("/")[4]
+        entry = {}
+        for key, fn in (("sclk_mhz", path), ("mclk_mhz", path.replace("pp_dpm_sclk", "pp_dpm_mclk"))):
+            try:
+                with open(fn) as fh:
+                    m = re.search(r"(\d+)\s*[Mm][Hh]z\s*\*", fh.read())
+                entry[key] = int(m.group(1)) if m else None
+            except OSError:
+                entry[key] = None
+        out[card] = entry
+    return out
 
 
 def runtime_grid(torch, lot, synth, to_device, only=None):
@@ -134,7 +154,7 @@ def main() -> int:
 
     import torch
     from paper_2509_23436_amd import lot, synth
-    from util import to_device
+    to_device = synth.to_device
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -183,14 +203,18 @@ def main() -> int:
     # recorded on the stream the kernels are launched on (torch's current stream)
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    clocks = {"before": device_clocks()}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
         starts[k].record()
         step(k)
         stops[k].record()
+    t_enqueued = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # (read after the clock stops; the device was busy until a moment ago, so this is the loaded state)
+    clocks["after"] = device_clocks()
     total_s = t1 - t0
     dev_ms = np.array([a.elapsed_time(b) for a, b in zip(starts, stops)])
     if lot.lot_workspace_status(ws) != 0:
@@ -227,13 +251,20 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        # operands of the matrix instructions (the similarities and the two contractions with V) are
+        # bf16 for bf16 I/O and exact bf16 pieces of the fp32 numbers for fp32 I/O; every sum, the
+        # potentials and the exponentials are fp32
+        "dtype": "bf16" if w.dtype == "bf16" else "f32",
+        "accumulate_dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "%s: B=%d H=%d n=%d d=%d r=%d io=%s eps=%g T=%d" % (
             w.name, w.B, w.H, w.n, w.d, w.r, w.dtype, w.eps, w.iters),
             "io_dtype": w.dtype, "path": args.path, "input_sets_rotated": rotate,
             "variant": "plain" if args.cls is None else "[CLS] row, beta_cls=%g" % args.cls},
         "head_tokens_per_s": w.G * w.n * args.steps / total_s,
+        "value_at_median_kernel_time": w.tokens / (float(np.percentile(dev_ms, 50)) * 1e-3),
+        "host_enqueue_s": t_enqueued - t0,
+        "clocks": clocks,
         "kernel_ms": {"mean": kernel_ms, "p10": float(np.percentile(dev_ms, 10)),
                       "p50": float(np.percentile(dev_ms, 50)), "p90": float(np.percentile(dev_ms, 90))},
         "warm_ms_per_step": warm_ms,

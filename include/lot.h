@@ -27,7 +27,9 @@
  *  - beta must be strictly positive and sum to one per head (the paper's p^0); this is a caller
  *    precondition and is not checked.
  *  - With io_dtype = LOT_BF16 the similarities are computed from bf16 operands with fp32
- *    accumulation: Z is rounded to bf16 (nearest even) inside the library.  With LOT_F32 they are
+ *    accumulation: Z (fp32, e.g. a learnable parameter) is rounded to bf16 (nearest even) inside
+ *    the library, like the Q and K it meets.  The bf16 tolerance (2e-2 of the largest output) is
+ *    quoted for any fp32 Z, not only for bf16-representable ones.  With LOT_F32 they are
  *    accurate to fp32 rounding (fp32 matrix instructions, or bf16 products over exact three-way
  *    pieces of the operands).  Potentials, sums and the r x d_v intermediate are fp32 in both
  *    modes.  The output is rounded to io_dtype.
@@ -59,7 +61,7 @@ typedef enum {
     LOT_ERR_ALIGN = -7,      /* a tensor pointer is not 16-byte aligned */
     LOT_ERR_HIP = -8,        /* a HIP call failed (see lot_strerror) */
     LOT_ERR_PATH = -9,       /* the requested execution path does not support this shape */
-    LOT_ERR_SYNC = -10       /* lot_workspace_status: a device-side wait gave up */
+    LOT_ERR_SYNC = -10       /* lot_workspace_status / lot_status_words: a device-side wait gave up */
 } lot_status;
 
 typedef struct {
@@ -78,8 +80,18 @@ typedef enum {
                                 64 < r <= 256 grouped kernels, one launch per step (attention only) */
 } lot_path;
 
-/* Bytes of device workspace needed by either entry point for this shape (covers both paths). */
+/*
+ * Bytes of device workspace lot_attention_fwd (and its [CLS] variant) needs for this shape: the size
+ * of what the kernels that LOT_PATH_AUTO selects really use -- a few megabytes on the tile kernels,
+ * independent of n x r (the paper's "Rank and complexity": nothing of that size is formed).  The
+ * _path form sizes a call whose path the caller forces (the plain kernels keep their n x r
+ * intermediates in the workspace); lot_couplings_workspace_bytes does the same for lot_couplings /
+ * lot_couplings_path (path = LOT_PATH_AUTO for the former).  Sizes depend on the device only through
+ * its number of compute units (256 is assumed where no device is present).
+ */
 int lot_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out);
+int lot_workspace_bytes_path(const lot_shape* shape, int iters, int path, size_t* bytes_out);
+int lot_couplings_workspace_bytes(const lot_shape* shape, int iters, int path, size_t* bytes_out);
 
 /* out = LOTAttn(Q, K, V) as defined above (paper eq. (lotattn) with A = n * glued coupling). */
 int lot_attention_fwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
@@ -106,7 +118,7 @@ int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,
  * is [CLS].  Rows 1 .. n-1 of out are the doubly-stochastic LOT attention AMONG tokens 1 .. n-1 (their
  * queries, keys and values only: uniform masses 1/(n-1), the same Z, beta, eps, iters); row 0 is a
  * standard softmax row over ALL n keys, alpha_j = softmax_j(beta_cls <q_0, k_j>), out_0 = sum_j
- * alpha_j v_j.  Same tensors, layout, workspace size (lot_workspace_bytes of the full shape) and
+ * alpha_j v_j.  Same tensors, layout, workspace size (lot_workspace_bytes / _path of the full shape) and
  * rules as lot_attention_fwd; n >= 2, beta_cls > 0 (LOT_ERR_EPS otherwise).  The [CLS] polarisation
  * of the paper is not part of this entry point.
  */
@@ -131,7 +143,7 @@ int lot_attention_cls_fwd_path(const lot_shape* shape, const void* Q, const void
  * Execution paths as for lot_attention_fwd (lot_path): the tile kernels take d_k = d_v in {32, 64}
  * (r <= 64 the fused kernel, 64 < r <= 256 the grouped kernels); the plain kernels any shape; AUTO
  * prefers the tile kernels.  Workspace:
- * lot_cross_workspace_bytes; lot_workspace_status applies.
+ * lot_cross_workspace_bytes (the kernels AUTO selects; _path for a forced path); lot_workspace_status applies.
  */
 typedef struct {
     int32_t B, H;
@@ -141,6 +153,7 @@ typedef struct {
     int32_t io_dtype;
 } lot_xshape;
 int lot_cross_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out);
+int lot_cross_workspace_bytes_path(const lot_xshape* shape, int iters, int path, size_t* bytes_out);
 int lot_cross_attention_fwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
                             const float* Z, const float* beta, const float* mass_q, const float* mass_k,
                             float eps, int iters, void* out,
@@ -160,7 +173,8 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * solves is differentiated, nothing is truncated); dbeta treats the r masses as free variables (no
  * projection onto the simplex).  The forward intermediates are recomputed inside; nothing has to be
  * saved from the forward call.  All gradient buffers are overwritten, not accumulated into.
- * Workspace: lot_attention_bwd_workspace_bytes (separate from, and larger than, the forward one);
+ * Workspace: lot_attention_bwd_workspace_bytes (separate from, and larger than, the forward one: what the
+ * kernels that AUTO selects use; lot_attention_bwd_workspace_bytes_path for a forced path);
  * contents on entry do not matter.  Same ownership, stream and error rules as the forward call;
  * gradient buffers must not alias the inputs, the workspace or each other.  iters <= 65536.
  * Two execution paths, chosen like the forward ones (lot_path): REFERENCE = one plain kernel per
@@ -168,21 +182,19 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * keep nothing of size n x r (d_k = d_v in {32, 64}; r <= 64 with iters <= 32, or 64 < r <= 256 with the
  * pivots in groups of 64, as far as the per-iteration tables fit a workgroup's local memory: bf16 I/O
  * any such r with iters <= 15 at d = 64, fp32 I/O at d = 64 only r <= 128; LOT_ERR_PATH beyond).  AUTO prefers
- * FUSED (from 16 tokens up; shorter sequences go to the plain kernels, which are exact to fp32 rounding).
+ * FUSED, except for fewer than 16 tokens and, with fp32 I/O, for r <= 2: there the rounding of the tile
+ * kernels' split-bf16 contractions (2^-16) is not averaged out, or is magnified by the cancellation in
+ * the gradient of two masses, and the plain kernels, exact to fp32 rounding, run instead.
  * Results are reproducible bit for bit on either path.  lot_workspace_status applies to this
  * workspace too (the FUSED path's forward sweep waits between workgroups when it runs as one kernel).
- * Testing aids (environment variables read at each call): the FUSED path (r <= 64) rebuilds each tile's
- * row-normalised kernels for all iterations with ONE shift per row instead of a maximum per iteration,
- * and checks every row sum against [2^-40, 2^40]: up to 16 iterations all of them are assembled at once
- * and a workgroup that finds a sum outside is redone by a second kernel, which goes iteration by
- * iteration and re-shifts the rows of an iteration whose sum leaves the range.  LOT_RESHIFT_BITS (0..40)
- * narrows the range to 2^-bits .. 2^bits so that these rarely taken branches run on ordinary inputs (0:
- * practically every iteration takes them); LOT_BWD_ASSEMBLE_BY_ITERATION=1 sends every workgroup through
- * the second kernel.  Results agree to rounding for every value.  LOT_BWD_SWEEP_LAUNCHES=1
- * makes the FUSED path's forward sweep run as one launch per pass (its form on a device that cannot
- * hold the whole grid at once) where it would otherwise be one persistent kernel; same results.
+ * The FUSED path (r <= 64) rebuilds each tile's row-normalised kernels for all iterations with ONE shift
+ * per row instead of a maximum per iteration, and checks every row sum against [2^-40, 2^40]: up to 16
+ * iterations all of them are assembled at once and a workgroup that finds a sum outside is redone by a
+ * second kernel, which goes iteration by iteration and re-shifts the rows of an iteration whose sum
+ * leaves the range (lot_debug_set has knobs that make these rarely taken branches run on ordinary inputs).
  */
 int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out);
+int lot_attention_bwd_workspace_bytes_path(const lot_shape* shape, int iters, int path, size_t* bytes_out);
 int lot_attention_bwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
                       const float* Z, const float* beta, float eps, int iters, const void* dO,
                       void* dQ, void* dK, void* dV, float* dZ, float* dbeta,
@@ -199,10 +211,11 @@ int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K,
  * gradient, a query of mass zero the gradient of its own output row.  Execution paths as for
  * lot_attention_bwd (FUSED: the tile kernels, r <= 64 in one register tile or 64 < r <= 256 in groups of
  * 64, within the same limits); AUTO prefers it.
- * Workspace: lot_cross_attention_bwd_workspace_bytes (covers both paths); contents on entry do not
- * matter; lot_workspace_status applies.  Reproducible bit for bit on either path.
+ * Workspace: lot_cross_attention_bwd_workspace_bytes (the kernels AUTO selects; _path for a forced path);
+ * contents on entry do not matter; lot_workspace_status applies.  Reproducible bit for bit on either path.
  */
 int lot_cross_attention_bwd_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out);
+int lot_cross_attention_bwd_workspace_bytes_path(const lot_xshape* shape, int iters, int path, size_t* bytes_out);
 int lot_cross_attention_bwd(const lot_xshape* shape, const void* Q, const void* K, const void* V,
                             const float* Z, const float* beta, const float* mass_q, const float* mass_k,
                             float eps, int iters, const void* dO,
@@ -220,7 +233,7 @@ int lot_cross_attention_bwd_path(const lot_xshape* shape, const void* Q, const v
  * doubly-stochastic part plus, in dK and dV, the share of the [CLS] row; row 0 of dQ is the gradient
  * of the [CLS] query, row 0 of dK and dV that of the [CLS] key and value (which only the softmax row
  * sees).  dbeta_cls [B,H] fp32: the derivative with respect to beta_cls PER (batch, head) problem --
- * sum it for a temperature shared by all of them.  Workspace: lot_attention_bwd_workspace_bytes of
+ * sum it for a temperature shared by all of them.  Workspace: lot_attention_bwd_workspace_bytes (or _path) of
  * the full shape.  Paths and reproducibility as for lot_attention_bwd; the softmax row is one plain
  * kernel (one workgroup per problem) on either path.
  */
@@ -234,14 +247,46 @@ int lot_attention_cls_bwd_path(const lot_shape* shape, const void* Q, const void
                                void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
- * Debug: synchronises the device and reads the status word that the fused kernel leaves in the
- * workspace.  LOT_OK, or LOT_ERR_SYNC if a bounded device-side wait between cooperating
- * workgroups gave up (the output of that call is then undefined).  Not part of the hot path.
- * Testing aid: the environment variable LOT_SPIN_LIMIT (read at each call) sets the poll budget of
- * those waits; with 0 every wait gives up at once, the kernels end early (every wavefront still
- * exits) and this function reports the call; the next call on the same workspace is unaffected.
+ * Waits between workgroups.  The fused forward kernel and the tiled backward's forward sweep are
+ * persistent kernels whose workgroups exchange column sums; every such wait is bounded, and the grid
+ * never exceeds what the device can hold at once.  A kernel of ANOTHER stream that occupies compute
+ * units while one of these starts can still keep part of the grid from becoming resident; a wait then
+ * gives up after its poll budget (seconds), every workgroup leaves, the rows of `out` that a leaving
+ * workgroup owns (in the backward pass: dZ and dbeta) are filled with NaN so that the failure cannot
+ * pass for a result, and the launch is marked in the first two words of the workspace.  The call itself has long returned
+ * LOT_OK by then.  Three ways to see the mark:
+ *   lot_workspace_status        synchronises the device and reads the words (debug).
+ *   lot_workspace_status_async  enqueues, on the caller's stream, a copy of the two words to
+ *                               host_words (pinned host memory, 16 bytes, owned by the caller); no
+ *                               synchronisation.  Once the stream has passed that point,
+ *   lot_status_words            (host only) turns the two words into LOT_OK or LOT_ERR_SYNC.
+ * The next call on the same workspace is unaffected by an earlier failure.
  */
 int lot_workspace_status(const void* workspace);
+int lot_workspace_status_async(const void* workspace, unsigned long long* host_words, void* hip_stream);
+int lot_status_words(const unsigned long long* host_words);
+
+/*
+ * Testing aids (for the library's own tests; no effect on results beyond rounding).  Process-wide;
+ * value < 0 restores the default.  Nothing in the library reads the environment.
+ *   LOT_KNOB_SPIN_LIMIT                poll budget of the bounded waits (default 2^21); 0 makes every
+ *                                      wait give up at once: the kernels end early (every wavefront
+ *                                      still exits) and the status words report the call
+ *   LOT_KNOB_RESHIFT_BITS              0..40: narrows the backward assemble kernel's row-sum range to
+ *                                      2^-bits .. 2^bits (0: practically every iteration re-shifts)
+ *   LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION non-zero: every workgroup through the iteration-by-iteration kernel
+ *   LOT_KNOB_BWD_SWEEP_LAUNCHES        non-zero: the backward's forward sweep as one launch per pass
+ *                                      (its form on a device that cannot hold the whole grid at once)
+ * Returns LOT_OK, or LOT_ERR_SHAPE for an unknown knob.
+ */
+typedef enum {
+    LOT_KNOB_SPIN_LIMIT = 0,
+    LOT_KNOB_RESHIFT_BITS = 1,
+    LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION = 2,
+    LOT_KNOB_BWD_SWEEP_LAUNCHES = 3,
+    LOT_KNOB_COUNT_ = 4
+} lot_knob;
+int lot_debug_set(int knob, long long value);
 
 /* Text for a lot_status; for LOT_ERR_HIP the text of the most recent HIP error on this thread. */
 const char* lot_strerror(int code);

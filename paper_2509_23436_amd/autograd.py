@@ -11,10 +11,63 @@ library, so only the inputs are kept between the two calls.
 eps, iters and beta_cls are plain numbers and receive no gradient (the per-problem derivative with
 respect to beta_cls is available from lot.lot_attention_cls_bwd); the token masses of cross attention
 are data (a padding mask), not differentiated.
+
+Workspaces: one per (device, call kind, shape, iters, path), allocated at the first call and reused, so a
+training step allocates nothing for them after its first iteration.  Calls that share a workspace must be
+on one stream (torch's current stream at each call); use the functions of `lot` with workspaces of your
+own to run the same shape on several streams at once.
+
+Failed waits: after every call the two status words of its workspace are copied to pinned host memory
+on the same stream (no synchronisation); every later call first looks at the copies that have arrived
+and raises if one of them reports a wait between workgroups that gave up (see include/lot.h; the rows
+such a call left unwritten are NaN in any case).  `check_pending(wait=True)` waits for all of them.
 """
 import torch
 
 from . import lot
+
+_workspaces = {}
+_pending = []
+
+
+def _workspace(kind, size_fn, shape_key, device, shape, iters, path):
+    key = (str(device), kind, shape_key, int(iters), int(path))
+    ws = _workspaces.get(key)
+    if ws is None:
+        ws = torch.empty(size_fn(shape, iters, path), dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    return ws
+
+
+def check_pending(wait=False):
+    """Raises RuntimeError if a finished call reported a wait that gave up; with wait=True, waits for
+    every outstanding status copy first (each waits for its own point of its stream only)."""
+    still = []
+    bad = None
+    for what, probe in _pending:
+        if wait or probe.ready():
+            if probe.failed() and bad is None:
+                bad = what
+        else:
+            still.append((what, probe))
+    _pending[:] = still
+    if bad is not None:
+        raise RuntimeError("libLOT: a wait between workgroups gave up during %s (another stream's kernel held "
+                           "compute units while it started?); its result is marked with NaN" % bad)
+
+
+def _after(what, ws):
+    _pending.append((what, lot.StatusProbe(ws)))
+
+
+def _fwd_shape(Q, V, Z):
+    return lot._shape_of(Q, V, Z), (tuple(Q.shape), V.shape[3], Z.shape[1], str(Q.dtype))
+
+
+def _cross_shape(Q, K, V, Z):
+    B, H, n_q, d_k = Q.shape
+    shape = lot.lot_xshape(B, H, n_q, K.shape[2], d_k, V.shape[3], Z.shape[1], lot._dtype_code(Q))
+    return shape, (tuple(Q.shape), K.shape[2], V.shape[3], Z.shape[1], str(Q.dtype))
 
 
 class _LOTAttention(torch.autograd.Function):
@@ -23,13 +76,23 @@ class _LOTAttention(torch.autograd.Function):
         Q, K, V, Z, beta = (t.contiguous() for t in (Q, K, V, Z, beta))
         ctx.save_for_backward(Q, K, V, Z, beta)
         ctx.cfg = (float(eps), int(iters), int(path))
-        return lot.lot_attention_fwd(Q, K, V, Z, beta, eps, iters, path=path)
+        check_pending()
+        lot._dims(Q, K, V, Z, beta)
+        shape, key = _fwd_shape(Q, V, Z)
+        ws = _workspace("fwd", lot.lot_workspace_bytes, key, Q.device, shape, iters, path)
+        out = lot.lot_attention_fwd(Q, K, V, Z, beta, eps, iters, workspace=ws, path=path)
+        _after("lot_attention (forward)", ws)
+        return out
 
     @staticmethod
     def backward(ctx, dO):
         Q, K, V, Z, beta = ctx.saved_tensors
         eps, iters, path = ctx.cfg
-        grads = lot.lot_attention_bwd(Q, K, V, Z, beta, eps, iters, dO.contiguous().to(Q.dtype), path=path)
+        check_pending()
+        shape, key = _fwd_shape(Q, V, Z)
+        ws = _workspace("bwd", lot.lot_attention_bwd_workspace_bytes, key, Q.device, shape, iters, path)
+        grads = lot.lot_attention_bwd(Q, K, V, Z, beta, eps, iters, dO.contiguous().to(Q.dtype), workspace=ws, path=path)
+        _after("lot_attention (backward)", ws)
         return (*grads, None, None, None)
 
 
@@ -39,13 +102,24 @@ class _LOTAttentionCls(torch.autograd.Function):
         Q, K, V, Z, beta = (t.contiguous() for t in (Q, K, V, Z, beta))
         ctx.save_for_backward(Q, K, V, Z, beta)
         ctx.cfg = (float(eps), int(iters), float(beta_cls), int(path))
-        return lot.lot_attention_cls_fwd(Q, K, V, Z, beta, eps, iters, beta_cls, path=path)
+        check_pending()
+        lot._dims(Q, K, V, Z, beta)
+        shape, key = _fwd_shape(Q, V, Z)
+        ws = _workspace("fwd", lot.lot_workspace_bytes, key, Q.device, shape, iters, path)
+        out = lot.lot_attention_cls_fwd(Q, K, V, Z, beta, eps, iters, beta_cls, workspace=ws, path=path)
+        _after("lot_attention_cls (forward)", ws)
+        return out
 
     @staticmethod
     def backward(ctx, dO):
         Q, K, V, Z, beta = ctx.saved_tensors
         eps, iters, beta_cls, path = ctx.cfg
-        grads = lot.lot_attention_cls_bwd(Q, K, V, Z, beta, eps, iters, beta_cls, dO.contiguous().to(Q.dtype), path=path)
+        check_pending()
+        shape, key = _fwd_shape(Q, V, Z)
+        ws = _workspace("bwd", lot.lot_attention_bwd_workspace_bytes, key, Q.device, shape, iters, path)
+        grads = lot.lot_attention_cls_bwd(Q, K, V, Z, beta, eps, iters, beta_cls, dO.contiguous().to(Q.dtype),
+                                          workspace=ws, path=path)
+        _after("lot_attention_cls (backward)", ws)
         return (*grads[:5], None, None, None, None)
 
 
@@ -58,15 +132,26 @@ class _LOTCrossAttention(torch.autograd.Function):
         ctx.save_for_backward(Q, K, V, Z, beta)
         ctx.masses = (mass_q, mass_k)
         ctx.cfg = (float(eps), int(iters), int(path))
-        return lot.lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=mass_q, mass_k=mass_k, path=path)
+        check_pending()
+        lot._dims(Q, K, V, Z, beta, cross=True)
+        shape, key = _cross_shape(Q, K, V, Z)
+        ws = _workspace("xfwd", lot.lot_cross_workspace_bytes, key, Q.device, shape, iters, path)
+        out = lot.lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=mass_q, mass_k=mass_k, workspace=ws,
+                                          path=path)
+        _after("lot_cross_attention (forward)", ws)
+        return out
 
     @staticmethod
     def backward(ctx, dO):
         Q, K, V, Z, beta = ctx.saved_tensors
         mass_q, mass_k = ctx.masses
         eps, iters, path = ctx.cfg
+        check_pending()
+        shape, key = _cross_shape(Q, K, V, Z)
+        ws = _workspace("xbwd", lot.lot_cross_attention_bwd_workspace_bytes, key, Q.device, shape, iters, path)
         grads = lot.lot_cross_attention_bwd(Q, K, V, Z, beta, eps, iters, dO.contiguous().to(Q.dtype),
-                                            mass_q=mass_q, mass_k=mass_k, path=path)
+                                            mass_q=mass_q, mass_k=mass_k, workspace=ws, path=path)
+        _after("lot_cross_attention (backward)", ws)
         return (*grads, None, None, None, None, None)
 
 

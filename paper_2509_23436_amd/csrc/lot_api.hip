@@ -2,7 +2,6 @@
 #include <atomic>
 #include <chrono>
 #include <cmath>
-#include <cstdlib>
 #include <cstdio>
 #include <cstring>
 
@@ -25,29 +24,55 @@ unsigned long long next_nonce()
     return v ? v : counter.fetch_add(1) + 1;
 }
 
+int device_cus()
+{
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            return n;
+        (void)hipGetLastError();   // no device: not an error of any call of ours
+        return 256;
+    }();
+    return cus;
+}
+
+// Testing aids: process-wide knobs set through lot_debug_set (never from the environment).
+static std::atomic<long long> g_knobs[LOT_KNOB_COUNT_] = {};
+static std::atomic<bool> g_knob_set[LOT_KNOB_COUNT_] = {};
+
+static bool knob(int which, long long* v)
+{
+    if (!g_knob_set[which].load(std::memory_order_relaxed)) return false;
+    *v = g_knobs[which].load(std::memory_order_relaxed);
+    return true;
+}
+
 uint32_t spin_limit()
 {
-    if (const char* e = std::getenv("LOT_SPIN_LIMIT")) {
-        const long long v = std::atoll(e);
-        if (v >= 0 && v <= (1ll << 30)) return (uint32_t)v;
-    }
+    long long v;
+    if (knob(LOT_KNOB_SPIN_LIMIT, &v) && v >= 0 && v <= (1ll << 30)) return (uint32_t)v;
     return 1u << 21;
 }
 
 float reshift_limit()
 {
+    long long v;
     int bits = 40;
-    if (const char* e = std::getenv("LOT_RESHIFT_BITS")) {
-        const int v = std::atoi(e);
-        if (v >= 0 && v <= 40) bits = v;
-    }
+    if (knob(LOT_KNOB_RESHIFT_BITS, &v) && v >= 0 && v <= 40) bits = (int)v;
     return std::ldexp(1.0f, bits);
 }
 
 bool assemble_by_iteration()
 {
-    const char* e = std::getenv("LOT_BWD_ASSEMBLE_BY_ITERATION");
-    return e && std::atoi(e) != 0;
+    long long v;
+    return knob(LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION, &v) && v != 0;
+}
+
+bool sweep_by_launches()
+{
+    long long v;
+    return knob(LOT_KNOB_BWD_SWEEP_LAUNCHES, &v) && v != 0;
 }
 
 static int validate_shape(const lot_shape* s)
@@ -57,7 +82,8 @@ static int validate_shape(const lot_shape* s)
     if (s->B < 1 || s->H < 1 || s->n < 1 || s->d_k < 1 || s->d_v < 1 || s->r < 1) return LOT_ERR_SHAPE;
     // ranges that keep every index computation inside 63 bits and every grid inside HIP's limits
     if (s->n > (1 << 24) || s->d_k > 1024 || s->d_v > 1024 || s->r > 1024) return LOT_ERR_SHAPE;
-    if ((int64_t)s->B * s->H > (1 << 20)) return LOT_ERR_SHAPE;
+    // (at most 2^16 problems: per-problem arrays of up to 256 x 64 elements are then indexed within 31 bits)
+    if ((int64_t)s->B * s->H > (1 << 16)) return LOT_ERR_SHAPE;
     // rows of Q, K, V, out must stay 16-byte aligned for the vector loads
     const int esz = s->io_dtype == LOT_BF16 ? 2 : 4;
     if ((s->d_k * esz) % 16 != 0 || (s->d_v * esz) % 16 != 0) return LOT_ERR_SHAPE;
@@ -66,8 +92,51 @@ static int validate_shape(const lot_shape* s)
 
 static bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
 
+// Which kernels a forward call runs.
+enum FwdImpl { FWD_REFERENCE = 0, FWD_FUSED = 1, FWD_GROUPED = 2 };
+
+// n_max: the longer side (cross attention).  `couplings`: lot_couplings, which the grouped kernels do not serve.
+static int pick_forward(const lot_shape& s, int iters, int path, bool couplings, FwdImpl* impl)
+{
+    const bool grouped = !couplings && grouped_supports(s);
+    const bool fused = fused_supports(s);
+    // (astronomical iteration counts whose column sums do not fit the fused kernel's fixed-point
+    // exchange format go to the plain kernels under AUTO)
+    const bool fits = fused_exchange_fits(s.n, iters);
+    switch (path) {
+    case LOT_PATH_AUTO: *impl = grouped ? FWD_GROUPED : (fused && fits) ? FWD_FUSED : FWD_REFERENCE; return LOT_OK;
+    case LOT_PATH_REFERENCE: *impl = FWD_REFERENCE; return LOT_OK;
+    case LOT_PATH_FUSED:
+        if (grouped) { *impl = FWD_GROUPED; return LOT_OK; }
+        if (!fused || !fits) return LOT_ERR_PATH;
+        *impl = FWD_FUSED;
+        return LOT_OK;
+    default: return LOT_ERR_PATH;
+    }
+}
+
+// Bytes of workspace the chosen kernels use: only what they touch, so that the common case (the
+// fused kernel) asks for a few megabytes and the n x r intermediates are charged to the plain path alone.
+static size_t forward_need(const lot_shape& s, int iters, FwdImpl impl)
+{
+    switch (impl) {
+    case FWD_GROUPED: return carve_grouped(s, iters).total;
+    case FWD_FUSED: return carve(s).fused_total;
+    default: return carve(s).total;
+    }
+}
+
+static int sizing_checks(const lot_shape* shape, int iters, const size_t* bytes_out)
+{
+    int rc = validate_shape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!bytes_out) return LOT_ERR_NULL;
+    if (iters < 1) return LOT_ERR_ITERS;
+    return LOT_OK;
+}
+
 static int common_checks(const lot_shape* s, const void* Q, const void* K, const float* Z,
-                         const float* beta, float eps, int iters, void* ws, size_t ws_bytes)
+                         const float* beta, float eps, int iters, void* ws)
 {
     int rc = validate_shape(s);
     if (rc != LOT_OK) return rc;
@@ -76,21 +145,7 @@ static int common_checks(const lot_shape* s, const void* Q, const void* K, const
     if (iters < 1) return LOT_ERR_ITERS;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(Z, 4) || misaligned(beta, 4)) return LOT_ERR_ALIGN;
     if (misaligned(ws, 256)) return LOT_ERR_WORKSPACE;
-    if (ws_bytes < carve(*s).total) return LOT_ERR_WORKSPACE;
     return LOT_OK;
-}
-
-static int pick_path(const lot_shape& s, int path, bool* fused)
-{
-    switch (path) {
-    case LOT_PATH_AUTO: *fused = fused_supports(s); return LOT_OK;
-    case LOT_PATH_REFERENCE: *fused = false; return LOT_OK;
-    case LOT_PATH_FUSED:
-        if (!fused_supports(s)) return LOT_ERR_PATH;
-        *fused = true;
-        return LOT_OK;
-    default: return LOT_ERR_PATH;
-    }
 }
 
 }  // namespace lot
@@ -99,18 +154,30 @@ using namespace lot;
 
 extern "C" {
 
+int lot_workspace_bytes_path(const lot_shape* shape, int iters, int path, size_t* bytes_out)
+{
+    int rc = sizing_checks(shape, iters, bytes_out);
+    if (rc != LOT_OK) return rc;
+    FwdImpl impl;
+    rc = pick_forward(*shape, iters, path, false, &impl);
+    if (rc != LOT_OK) return rc;
+    *bytes_out = forward_need(*shape, iters, impl);
+    return LOT_OK;
+}
+
 int lot_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out)
 {
-    int rc = validate_shape(shape);
+    return lot_workspace_bytes_path(shape, iters, LOT_PATH_AUTO, bytes_out);
+}
+
+int lot_couplings_workspace_bytes(const lot_shape* shape, int iters, int path, size_t* bytes_out)
+{
+    int rc = sizing_checks(shape, iters, bytes_out);
     if (rc != LOT_OK) return rc;
-    if (!bytes_out) return LOT_ERR_NULL;
-    if (iters < 1) return LOT_ERR_ITERS;
-    size_t need = carve(*shape).total;
-    if (grouped_supports(*shape)) {
-        const size_t grouped = carve_grouped(*shape, iters).total;     // grows with iters
-        if (grouped > need) need = grouped;
-    }
-    *bytes_out = need;
+    FwdImpl impl;
+    rc = pick_forward(*shape, iters, path, true, &impl);
+    if (rc != LOT_OK) return rc;
+    *bytes_out = forward_need(*shape, iters, impl);
     return LOT_OK;
 }
 
@@ -120,31 +187,20 @@ static int attention_impl(const lot_shape* shape, const void* Q, const void* K, 
                           const float* Z, const float* beta, float eps, int iters, void* out,
                           void* workspace, size_t workspace_bytes, void* hip_stream, int path, int n_stride)
 {
-    int rc = common_checks(shape, Q, K, Z, beta, eps, iters, workspace, workspace_bytes);
+    int rc = common_checks(shape, Q, K, Z, beta, eps, iters, workspace);
     if (rc != LOT_OK) return rc;
     if (!V || !out) return LOT_ERR_NULL;
     if (misaligned(V, 16) || misaligned(out, 16)) return LOT_ERR_ALIGN;
-    // pivot sizes beyond one register tile: the grouped kernels stand in for the fused one
-    if (grouped_supports(*shape) && (path == LOT_PATH_AUTO || path == LOT_PATH_FUSED)) {
-        if (workspace_bytes < carve_grouped(*shape, iters).total) return LOT_ERR_WORKSPACE;
-        Args ga{};
-        ga.s = *shape; ga.Q = Q; ga.K = K; ga.V = V; ga.Z = Z; ga.beta = beta; ga.eps = eps; ga.iters = iters;
-        ga.out = out; ga.ws = (char*)workspace; ga.stream = (hipStream_t)hip_stream; ga.n_stride = n_stride;
-        return run_grouped(ga);
-    }
-    bool fused = false;
-    rc = pick_path(*shape, path, &fused);
+    FwdImpl impl;
+    rc = pick_forward(*shape, iters, path, false, &impl);
     if (rc != LOT_OK) return rc;
+    if (workspace_bytes < forward_need(*shape, iters, impl)) return LOT_ERR_WORKSPACE;
     Args a{};
     a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
-    a.out = out; a.ws = (char*)workspace; a.lay = carve(*shape); a.stream = (hipStream_t)hip_stream;
-    a.n_stride = n_stride;
-    if (fused) {
-        rc = run_fused(a, true);
-        // AUTO falls back to the reference kernels for the (astronomical) iteration counts whose
-        // column sums do not fit the fused kernel's fixed-point exchange format
-        if (!(rc == LOT_ERR_PATH && path == LOT_PATH_AUTO)) return rc;
-    }
+    a.out = out; a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream; a.n_stride = n_stride;
+    if (impl == FWD_GROUPED) return run_grouped(a);   // pivot sizes beyond one register tile
+    a.lay = carve(*shape);
+    if (impl == FWD_FUSED) return run_fused(a, true);
     a.gamma1 = (float*)(a.ws + a.lay.gamma1);
     a.gamma2 = (float*)(a.ws + a.lay.gamma2);
     return run_reference(a, true);
@@ -167,6 +223,7 @@ int lot_attention_cls_fwd_path(const lot_shape* shape, const void* Q, const void
     if (!(beta_cls > 0.0f) || !std::isfinite(beta_cls)) return LOT_ERR_EPS;
     if (!Q || !K || !V || !out) return LOT_ERR_NULL;
     // doubly-stochastic attention among tokens 1 .. n-1: the same kernels on views that skip row 0
+    // (the workspace of the full shape covers the shorter one: every region grows with n)
     lot_shape inner = *shape;
     inner.n = shape->n - 1;
     const size_t esz = shape->io_dtype == LOT_BF16 ? 2 : 4;
@@ -190,22 +247,19 @@ int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,
                        float* gamma1, float* gamma2,
                        void* workspace, size_t workspace_bytes, void* hip_stream, int path)
 {
-    int rc = common_checks(shape, Q, K, Z, beta, eps, iters, workspace, workspace_bytes);
+    int rc = common_checks(shape, Q, K, Z, beta, eps, iters, workspace);
     if (rc != LOT_OK) return rc;
     if (!gamma1 || !gamma2) return LOT_ERR_NULL;
     if (misaligned(gamma1, 16) || misaligned(gamma2, 16)) return LOT_ERR_ALIGN;
-    bool fused = false;
-    rc = pick_path(*shape, path, &fused);
+    FwdImpl impl;
+    rc = pick_forward(*shape, iters, path, true, &impl);
     if (rc != LOT_OK) return rc;
+    if (workspace_bytes < forward_need(*shape, iters, impl)) return LOT_ERR_WORKSPACE;
     Args a{};
     a.s = *shape; a.Q = Q; a.K = K; a.V = nullptr; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.out = nullptr; a.gamma1 = gamma1; a.gamma2 = gamma2;
     a.ws = (char*)workspace; a.lay = carve(*shape); a.stream = (hipStream_t)hip_stream;
-    if (fused) {
-        rc = run_fused(a, false);
-        if (!(rc == LOT_ERR_PATH && path == LOT_PATH_AUTO)) return rc;
-    }
-    return run_reference(a, false);
+    return impl == FWD_FUSED ? run_fused(a, false) : run_reference(a, false);
 }
 
 int lot_attention_fwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
@@ -241,24 +295,28 @@ static lot_shape fused_view(const lot_xshape& x)
     return lot_shape{x.B, x.H, x.n_q > x.n_k ? x.n_q : x.n_k, x.d_k, x.d_v, x.r, x.io_dtype};
 }
 
-int lot_cross_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out)
+static size_t cross_forward_need(const lot_xshape& x, int iters, FwdImpl impl)
+{
+    if (impl == FWD_REFERENCE) return carve_cross(x.B, x.H, x.n_q, x.n_k, x.r, x.d_v).total;
+    return forward_need(fused_view(x), iters, impl);
+}
+
+int lot_cross_workspace_bytes_path(const lot_xshape* shape, int iters, int path, size_t* bytes_out)
 {
     int rc = validate_xshape(shape);
     if (rc != LOT_OK) return rc;
     if (!bytes_out) return LOT_ERR_NULL;
     if (iters < 1) return LOT_ERR_ITERS;
-    size_t need = carve_cross(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_v).total;
-    const lot_shape fs = fused_view(*shape);
-    if (fused_supports(fs)) {
-        const size_t fused = carve(fs).C;      // the fused kernel's regions come first in that layout
-        if (fused > need) need = fused;
-    }
-    if (grouped_supports(fs)) {
-        const size_t grouped = carve_grouped(fs, iters).total;
-        if (grouped > need) need = grouped;
-    }
-    *bytes_out = need;
+    FwdImpl impl;
+    rc = pick_forward(fused_view(*shape), iters, path, false, &impl);
+    if (rc != LOT_OK) return rc;
+    *bytes_out = cross_forward_need(*shape, iters, impl);
     return LOT_OK;
+}
+
+int lot_cross_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out)
+{
+    return lot_cross_workspace_bytes_path(shape, iters, LOT_PATH_AUTO, bytes_out);
 }
 
 int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const void* K, const void* V,
@@ -275,29 +333,19 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
         misaligned(beta, 4) || misaligned(mass_q, 4) || misaligned(mass_k, 4))
         return LOT_ERR_ALIGN;
     if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
-    size_t need = 0;
-    rc = lot_cross_workspace_bytes(shape, iters, &need);
-    if (rc != LOT_OK) return rc;
-    if (workspace_bytes < need) return LOT_ERR_WORKSPACE;
     const lot_shape fs = fused_view(*shape);
-    // pivot sizes beyond one register tile: the grouped kernels stand in for the fused one
-    if (grouped_supports(fs) && (path == LOT_PATH_AUTO || path == LOT_PATH_FUSED)) {
-        Args ga{};
-        ga.s = fs; ga.Q = Q; ga.K = K; ga.V = V; ga.Z = Z; ga.beta = beta; ga.eps = eps; ga.iters = iters; ga.out = out;
-        ga.ws = (char*)workspace; ga.stream = (hipStream_t)hip_stream;
-        ga.n_q = shape->n_q; ga.n_k = shape->n_k; ga.mass_q = mass_q; ga.mass_k = mass_k;
-        return run_grouped(ga);
-    }
-    bool fused = false;
-    rc = pick_path(fs, path, &fused);
+    FwdImpl impl;
+    rc = pick_forward(fs, iters, path, false, &impl);
     if (rc != LOT_OK) return rc;
-    if (fused) {
+    if (workspace_bytes < cross_forward_need(*shape, iters, impl)) return LOT_ERR_WORKSPACE;
+    if (impl != FWD_REFERENCE) {
         Args f{};
         f.s = fs; f.Q = Q; f.K = K; f.V = V; f.Z = Z; f.beta = beta; f.eps = eps; f.iters = iters; f.out = out;
-        f.ws = (char*)workspace; f.lay = carve(fs); f.stream = (hipStream_t)hip_stream;
+        f.ws = (char*)workspace; f.stream = (hipStream_t)hip_stream;
         f.n_q = shape->n_q; f.n_k = shape->n_k; f.mass_q = mass_q; f.mass_k = mass_k;
-        rc = run_fused(f, true);
-        if (!(rc == LOT_ERR_PATH && path == LOT_PATH_AUTO)) return rc;
+        if (impl == FWD_GROUPED) return run_grouped(f);   // pivot sizes beyond one register tile
+        f.lay = carve(fs);
+        return run_fused(f, true);
     }
     CrossArgs a{};
     a.B = shape->B; a.H = shape->H; a.n_q = shape->n_q; a.n_k = shape->n_k; a.d_k = shape->d_k; a.d_v = shape->d_v;
@@ -317,32 +365,78 @@ int lot_cross_attention_fwd(const lot_xshape* shape, const void* Q, const void* 
                                         workspace_bytes, hip_stream, LOT_PATH_AUTO);
 }
 
-int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out)
-{
-    int rc = validate_shape(shape);
-    if (rc != LOT_OK) return rc;
-    if (!bytes_out) return LOT_ERR_NULL;
-    if (iters < 1) return LOT_ERR_ITERS;
-    if (iters > (1 << 16)) return LOT_ERR_ITERS;   // one stored vector of potentials per iteration
-    // covers both execution paths (the plain one is the larger)
-    size_t need = carve_bwd(*shape, iters).total;
-    if (bwd_tiled_supports(*shape, iters)) {
-        const size_t tiled = carve_bwd_tiled(*shape, iters).total;
-        if (tiled > need) need = tiled;
-    }
-    if (bwd_grouped_supports(*shape, iters)) {
-        const size_t grouped = carve_bwd_grouped(*shape, iters).total;
-        if (grouped > need) need = grouped;
-    }
-    *bytes_out = need;
-    return LOT_OK;
-}
+// Which kernels a backward call runs.
+enum BwdImpl { BWD_PLAIN = 0, BWD_TILED = 1, BWD_GROUPED = 2 };
 
 // AUTO sends problems of fewer tokens than this to the plain backward kernels: with so few tokens nothing
 // averages out the rounding of the tiled path's bf16 (hi + lo) contractions, and gradients that vanish
 // identically (a single token, say) come out as noise at 1e-3 of the other tensors' scale; the plain
 // kernels are exact to fp32 rounding and cost nothing at this size.
 constexpr int kMinTiledTokens = 16;
+// ... and fp32 problems with at most this many pivots: the gradient of the masses is then a difference of
+// nearly equal terms, which magnifies the 2^-16 of the same contractions to just above 1e-4 of its scale.
+constexpr int kMinTiledPivotsF32 = 2;
+
+// s.n = the longer side; n_short = the shorter one
+static int pick_backward(const lot_shape& s, int n_short, int iters, int path, BwdImpl* impl)
+{
+    const bool one_tile = bwd_tiled_supports(s, iters), grouped = bwd_grouped_supports(s, iters);
+    const BwdImpl tile_impl = one_tile ? BWD_TILED : BWD_GROUPED;
+    switch (path) {
+    case LOT_PATH_AUTO: {
+        bool tiled = (one_tile || grouped) && n_short >= kMinTiledTokens;
+        if (s.io_dtype == LOT_F32 && s.r <= kMinTiledPivotsF32) tiled = false;
+        *impl = tiled ? tile_impl : BWD_PLAIN;
+        return LOT_OK;
+    }
+    case LOT_PATH_REFERENCE: *impl = BWD_PLAIN; return LOT_OK;
+    case LOT_PATH_FUSED:
+        if (!one_tile && !grouped) return LOT_ERR_PATH;
+        *impl = tile_impl;
+        return LOT_OK;
+    default: return LOT_ERR_PATH;
+    }
+}
+
+static size_t backward_need(const lot_shape& s, int n_q, int n_k, int iters, BwdImpl impl)
+{
+    switch (impl) {
+    case BWD_TILED: return carve_bwd_tiled(s, iters).total;
+    case BWD_GROUPED: return carve_bwd_grouped(s, iters).total;
+    default: return carve_bwd_sides(s.B, s.H, n_q, n_k, s.r, s.d_k, s.d_v, iters).total;
+    }
+}
+
+int lot_attention_bwd_workspace_bytes_path(const lot_shape* shape, int iters, int path, size_t* bytes_out)
+{
+    int rc = validate_shape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!bytes_out) return LOT_ERR_NULL;
+    if (iters < 1) return LOT_ERR_ITERS;
+    if (iters > (1 << 16)) return LOT_ERR_ITERS;   // one stored vector of potentials per iteration
+    BwdImpl impl;
+    rc = pick_backward(*shape, shape->n, iters, path, &impl);
+    if (rc != LOT_OK) return rc;
+    size_t need = backward_need(*shape, shape->n, shape->n, iters, impl);
+    // The [CLS] variant runs these kernels on the n - 1 other tokens with this workspace; at the one
+    // length where that changes the choice of kernels the larger of the two sizes is returned.
+    if (shape->n >= 2) {
+        lot_shape inner = *shape;
+        inner.n = shape->n - 1;
+        BwdImpl inner_impl;
+        if (pick_backward(inner, inner.n, iters, path, &inner_impl) == LOT_OK && inner_impl != impl) {
+            const size_t other = backward_need(inner, inner.n, inner.n, iters, inner_impl);
+            if (other > need) need = other;
+        }
+    }
+    *bytes_out = need;
+    return LOT_OK;
+}
+
+int lot_attention_bwd_workspace_bytes(const lot_shape* shape, int iters, size_t* bytes_out)
+{
+    return lot_attention_bwd_workspace_bytes_path(shape, iters, LOT_PATH_AUTO, bytes_out);
+}
 
 // n_stride: tokens between consecutive problems in the token tensors (0 = shape->n)
 static int backward_impl(const lot_shape* shape, const void* Q, const void* K, const void* V,
@@ -361,29 +455,18 @@ static int backward_impl(const lot_shape* shape, const void* Q, const void* K, c
         return LOT_ERR_ALIGN;
     if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
     // the tile kernels: r <= 64 in one register tile, larger r with the pivots in groups of 64
-    const bool one_tile = bwd_tiled_supports(*shape, iters), grouped = bwd_grouped_supports(*shape, iters);
-    bool tiled = false;
-    switch (path) {
-    case LOT_PATH_AUTO: tiled = (one_tile || grouped) && shape->n >= kMinTiledTokens; break;
-    case LOT_PATH_REFERENCE: tiled = false; break;
-    case LOT_PATH_FUSED:
-        if (!one_tile && !grouped) return LOT_ERR_PATH;
-        tiled = true;
-        break;
-    default: return LOT_ERR_PATH;
-    }
-    size_t need = 0;
-    rc = lot_attention_bwd_workspace_bytes(shape, iters, &need);
+    BwdImpl impl;
+    rc = pick_backward(*shape, shape->n, iters, path, &impl);
     if (rc != LOT_OK) return rc;
-    if (workspace_bytes < need) return LOT_ERR_WORKSPACE;
+    if (workspace_bytes < backward_need(*shape, shape->n, shape->n, iters, impl)) return LOT_ERR_WORKSPACE;
     BwdArgs a{};
     a.lay = carve_bwd(*shape, iters);
     a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
     a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
     a.n_stride = n_stride;
-    if (!tiled) return run_backward(a);
-    return one_tile ? run_backward_tiled(a) : run_backward_grouped(a);
+    if (impl == BWD_PLAIN) return run_backward(a);
+    return impl == BWD_TILED ? run_backward_tiled(a) : run_backward_grouped(a);
 }
 
 int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
@@ -395,24 +478,23 @@ int lot_attention_bwd_path(const lot_shape* shape, const void* Q, const void* K,
                          hip_stream, path, 0);
 }
 
-int lot_cross_attention_bwd_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out)
+int lot_cross_attention_bwd_workspace_bytes_path(const lot_xshape* shape, int iters, int path, size_t* bytes_out)
 {
     int rc = validate_xshape(shape);
     if (rc != LOT_OK) return rc;
     if (!bytes_out) return LOT_ERR_NULL;
     if (iters < 1 || iters > (1 << 16)) return LOT_ERR_ITERS;
-    size_t need = carve_bwd_sides(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_k, shape->d_v, iters).total;
     const lot_shape longer = fused_view(*shape);
-    if (bwd_tiled_supports(longer, iters)) {
-        const size_t tiled = carve_bwd_tiled(longer, iters).total;
-        if (tiled > need) need = tiled;
-    }
-    if (bwd_grouped_supports(longer, iters)) {
-        const size_t grouped = carve_bwd_grouped(longer, iters).total;
-        if (grouped > need) need = grouped;
-    }
-    *bytes_out = need;
+    BwdImpl impl;
+    rc = pick_backward(longer, shape->n_q < shape->n_k ? shape->n_q : shape->n_k, iters, path, &impl);
+    if (rc != LOT_OK) return rc;
+    *bytes_out = backward_need(longer, shape->n_q, shape->n_k, iters, impl);
     return LOT_OK;
+}
+
+int lot_cross_attention_bwd_workspace_bytes(const lot_xshape* shape, int iters, size_t* bytes_out)
+{
+    return lot_cross_attention_bwd_workspace_bytes_path(shape, iters, LOT_PATH_AUTO, bytes_out);
 }
 
 int lot_cross_attention_bwd_path(const lot_xshape* shape, const void* Q, const void* K, const void* V,
@@ -431,30 +513,17 @@ int lot_cross_attention_bwd_path(const lot_xshape* shape, const void* Q, const v
         misaligned(dbeta, 4) || misaligned(mass_q, 4) || misaligned(mass_k, 4))
         return LOT_ERR_ALIGN;
     if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
-    size_t need = 0;
-    rc = lot_cross_attention_bwd_workspace_bytes(shape, iters, &need);
-    if (rc != LOT_OK) return rc;
-    if (workspace_bytes < need) return LOT_ERR_WORKSPACE;
     const lot_shape s = fused_view(*shape);        // n = the longer side
+    BwdImpl impl;
+    rc = pick_backward(s, shape->n_q < shape->n_k ? shape->n_q : shape->n_k, iters, path, &impl);
+    if (rc != LOT_OK) return rc;
+    if (workspace_bytes < backward_need(s, shape->n_q, shape->n_k, iters, impl)) return LOT_ERR_WORKSPACE;
     BwdArgs a{};
     a.s = s; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
     a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
     a.n_q = shape->n_q; a.n_k = shape->n_k; a.mass_q = mass_q; a.mass_k = mass_k;
-    const bool one_tile = bwd_tiled_supports(s, iters), grouped = bwd_grouped_supports(s, iters);
-    bool tiled = false;
-    switch (path) {
-    case LOT_PATH_AUTO:
-        tiled = (one_tile || grouped) && shape->n_q >= kMinTiledTokens && shape->n_k >= kMinTiledTokens;
-        break;
-    case LOT_PATH_REFERENCE: tiled = false; break;
-    case LOT_PATH_FUSED:
-        if (!one_tile && !grouped) return LOT_ERR_PATH;
-        tiled = true;
-        break;
-    default: return LOT_ERR_PATH;
-    }
-    if (tiled) return one_tile ? run_backward_tiled(a) : run_backward_grouped(a);
+    if (impl != BWD_PLAIN) return impl == BWD_TILED ? run_backward_tiled(a) : run_backward_grouped(a);
     a.lay = carve_bwd_sides(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_k, shape->d_v, iters);
     return run_backward(a);
 }
@@ -517,7 +586,33 @@ int lot_workspace_status(const void* workspace)
     unsigned long long words[2] = {0, 0};
     LOT_HIP_CHECK(hipDeviceSynchronize());
     LOT_HIP_CHECK(hipMemcpy(words, workspace, sizeof(words), hipMemcpyDeviceToHost));
-    return (words[1] != 0 && words[0] == words[1]) ? LOT_ERR_SYNC : LOT_OK;
+    return lot_status_words(words);
+}
+
+int lot_workspace_status_async(const void* workspace, unsigned long long* host_words, void* hip_stream)
+{
+    if (!workspace || !host_words) return LOT_ERR_NULL;
+    LOT_HIP_CHECK(hipMemcpyAsync(host_words, workspace, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost,
+                                 (hipStream_t)hip_stream));
+    return LOT_OK;
+}
+
+int lot_status_words(const unsigned long long* host_words)
+{
+    if (!host_words) return LOT_ERR_NULL;
+    return (host_words[1] != 0 && host_words[0] == host_words[1]) ? LOT_ERR_SYNC : LOT_OK;
+}
+
+int lot_debug_set(int knob, long long value)
+{
+    if (knob < 0 || knob >= LOT_KNOB_COUNT_) return LOT_ERR_SHAPE;
+    if (value < 0) {
+        g_knob_set[knob].store(false, std::memory_order_relaxed);
+        return LOT_OK;
+    }
+    g_knobs[knob].store(value, std::memory_order_relaxed);
+    g_knob_set[knob].store(true, std::memory_order_relaxed);
+    return LOT_OK;
 }
 
 const char* lot_strerror(int code)

@@ -37,7 +37,6 @@
 // launches of the same tile code, with launch boundaries as the only synchronisation.  Both solves share every launch (pair = side * G + g, side 0 = queries).  All
 // reductions have a fixed order except the column sums, which are exchanged as integers: results
 // are reproducible.
-#include <cstdlib>
 
 #include "lot_internal.h"
 #include "lot_tile.h"
@@ -46,7 +45,7 @@
 namespace lot {
 namespace {
 
-constexpr int kTargetWgs = 512;     // two workgroups of four wavefronts on each of 256 CUs
+inline int target_wgs() { return 2 * device_cus(); }   // two workgroups of four wavefronts per compute unit
 
 // Tiles per workgroup: enough workgroups to fill the device once (set-up and the cross-wavefront
 // reductions at the end of a workgroup are amortised over more tiles, fewer partial results go
@@ -56,7 +55,8 @@ inline int tiles_per_wg_for(const lot_shape& s)
 {
     const long long ntiles = ((long long)s.n + kTileTokens - 1) / kTileTokens;
     const long long pairs = 2LL * s.B * s.H;
-    long long per = (ntiles * pairs + kTargetWgs - 1) / kTargetWgs;
+    const long long target = target_wgs();
+    long long per = (ntiles * pairs + target - 1) / target;
     per = (per + kWaves - 1) / kWaves * kWaves;
     if (per < kWaves) per = kWaves;
     if (per > 256 * kWaves) per = 256 * kWaves;
@@ -1349,6 +1349,9 @@ __global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) bt_final(BtParam
         float tot = 0.f;
 #pragma unroll
         for (int sl = 0; sl < kFinalSlices; ++sl) tot += s_part[sl][o];
+        // a sweep whose wait between workgroups gave up has marked this launch: the gradients of the
+        // pivots and their masses are made NaN, so that the failure cannot pass for a result
+        if (p.status[0] == p.nonce) tot = __builtin_nanf("");
         if (c < D) p.dZ[((size_t)h * p.r + t) * D + c] = tot;
         else p.dbeta[h * p.r + t] = tot;
     }
@@ -1390,7 +1393,7 @@ int launch_all(const BwdArgs& a, BtParams p)
     }
     // testing aid: run the sweep as one launch per pass although it would fit (the fallback of devices
     // that cannot hold the grid), so that this form stays exercised
-    if (const char* e = std::getenv("LOT_BWD_SWEEP_LAUNCHES")) persistent = persistent && std::atoi(e) == 0;
+    if (sweep_by_launches()) persistent = false;
     const bool mass = p.mass_side[0] != nullptr || p.mass_side[1] != nullptr;
     if (persistent) {
         if (mass) bt_sweep<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);

@@ -343,6 +343,30 @@ __device__ __forceinline__ void run_pass(
     mfirst = mcur;
 }
 
+// A workgroup that leaves because a wait between workgroups gave up fills the rows it owns with NaN
+// (the output rows of its query chunk, or its rows of the first coupling): whoever reads the result
+// sees at once that the call failed, also without looking at the status words.
+template <typename IO, int D>
+__device__ __forceinline__ void poison_rows(const FusedParams& p, int g, int tile_begin, int tile_end, int threads)
+{
+    const int n = p.n_side[1];
+    const int row0 = tile_begin * kTileTokens, row1 = min(n, tile_end * kTileTokens);
+    if (row1 <= row0) return;
+    const float nanf32 = __builtin_nanf("");
+    if (p.out != nullptr) {
+        IO* base = reinterpret_cast<IO*>(p.out) + ((size_t)g * p.stride_side[1] + row0) * D;
+        const int count = (row1 - row0) * D;
+        for (int e = threadIdx.x; e < count; e += threads) {
+            if constexpr (io_is_f32<IO>::value) as_global(base)[e] = nanf32;
+            else as_global(base)[e] = (uint16_t)0x7fc0u;
+        }
+    } else if (p.gamma1 != nullptr) {
+        float* base = p.gamma1 + ((size_t)g * n + row0) * p.r;
+        const int count = (row1 - row0) * p.r;
+        for (int e = threadIdx.x; e < count; e += threads) as_global(base)[e] = nanf32;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // the kernel
 // ---------------------------------------------------------------------------------------------
@@ -629,7 +653,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 // what is collected along with this post: keys' pass `it` after a query pass (for
                 // the last iteration that is the keys' final update), queries' pass `it - 1` after
                 // a key pass
-                if (!exchange(side, it, with_u, side ^ 1, side == 1 ? it : it - 1, side == 1 && it == p.iters)) return;
+                if (!exchange(side, it, with_u, side ^ 1, side == 1 ? it : it - 1, side == 1 && it == p.iters)) {
+                    poison_rows<IO, D>(p, g, tile_begins[1], tile_ends[1], kThreads);
+                    return;
+                }
             }
         }
         float* yt = p.y_tile + (size_t)g * 64 * D;
@@ -644,7 +671,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 s_ok = ok;
             }
             lds_barrier();
-            if (!s_ok) return;
+            if (!s_ok) { poison_rows<IO, D>(p, g, tile_begins[1], tile_ends[1], kThreads); return; }
             const int per = (64 * D + p.cluster - 1) / p.cluster;
             const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
             const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
@@ -673,7 +700,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         }
         lds_barrier();
         __builtin_amdgcn_s_setprio(0);
-        if (!s_ok) return;
+        if (!s_ok) { poison_rows<IO, D>(p, g, tile_begins[1], tile_ends[1], kThreads); return; }
 
         LOT_STAMP(2);
         if (!attention) {
@@ -694,7 +721,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     s_ok = ok;
                 }
                 lds_barrier();
-                if (!s_ok) return;
+                if (!s_ok) { poison_rows<IO, D>(p, g, tile_begins[1], tile_ends[1], kThreads); return; }
                 constexpr int kChunks = 64 * D / 4 / kThreads;   // 16-byte chunks per thread
                 const int ft = wave * 64 + fresh_lane();
                 f32x4 v[kChunks];
@@ -759,7 +786,7 @@ int launch(const Args& a, bool want_out)
         LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         capacity = per_cu * cus;
         if (capacity < 1) { last_hip_error() = hipErrorLaunchOutOfResources; return LOT_ERR_HIP; }
-        if (capacity > kMaxResidentWgs) capacity = kMaxResidentWgs;
+        if (capacity > max_resident_wgs()) capacity = max_resident_wgs();
         if (dev >= 0 && dev < 8) capacity_cache[dev] = capacity;
     }
 
@@ -801,12 +828,10 @@ int launch(const Args& a, bool want_out)
     // only where the last 8 MiB of the workspace lie wholly inside the reference path's regions
     p.trace = a.lay.total >= a.lay.C + (8u << 20) ? (unsigned long long*)(a.ws + a.lay.total - (8u << 20)) : nullptr;
 
-    // Fixed-point format of the exchanged column sums: a parity buffer receives at most
-    // iters/2 + 1 passes, each adding at most n per pivot, and must stay below 2^55.
+    // fixed-point format of the exchanged column sums
     {
-        const double max_sum = ((double)a.iters / 2.0 + 1.0) * (double)(n_side[0] > n_side[1] ? n_side[0] : n_side[1]);
-        int frac = 55 - (int)std::ceil(std::log2(max_sum + 1.0));
-        if (frac < 8) return LOT_ERR_PATH;
+        const int frac = fused_exchange_frac_bits(n_side[0] > n_side[1] ? n_side[0] : n_side[1], a.iters);
+        if (frac < 0) return LOT_ERR_PATH;
         p.fx_scale = std::ldexp(1.0f, frac);
         p.fx_unscale = std::ldexp(1.0f, -frac);
     }

@@ -15,7 +15,7 @@ namespace {
 constexpr int kGroup = 64;          // pivots per group (two MFMA blocks)
 constexpr int kMaxGroups = 4;
 constexpr int kRmax = kGroup * kMaxGroups;
-constexpr int kGTargetWgs = 512;
+inline int g_target_wgs() { return 2 * device_cus(); }   // two workgroups per compute unit
 
 struct LgParams {
     const void* Q; const void* K; const void* V;
@@ -38,7 +38,8 @@ struct LgParams {
 inline int lg_tiles_per_wg(const lot_shape& s)
 {
     const long long ntiles = ((long long)s.n + kTileTokens - 1) / kTileTokens;
-    long long per = (ntiles * 2LL * s.B * s.H + kGTargetWgs - 1) / kGTargetWgs;
+    const long long target = g_target_wgs();
+    long long per = (ntiles * 2LL * s.B * s.H + target - 1) / target;
     per = (per + kWaves - 1) / kWaves * kWaves;
     if (per < kWaves) per = kWaves;
     if (per > 32 * kWaves) per = 32 * kWaves;

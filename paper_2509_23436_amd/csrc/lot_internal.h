@@ -12,10 +12,15 @@ namespace lot {
 constexpr int kTileTokens = 32;        // tokens per MFMA tile of the fused kernel
 constexpr int kFusedWaves = 4;         // fewest wavefronts per workgroup of the fused kernel
 constexpr int kMaxCluster = 64;        // most workgroups that share one problem
-constexpr int kMaxResidentWgs = 2048;  // upper bound on co-resident workgroups (256 CUs x 8)
+constexpr int kMaxWgsPerCu = 8;         // upper bound on co-resident workgroups per compute unit
 constexpr int kRefChunk = 128;         // tokens per workgroup in the plain kernels' column reductions
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Compute units of the current device, asked once per process; 256 (MI355X) where no device answers,
+// so that workspace sizes can still be computed on a host without a GPU.
+int device_cus();
+inline int max_resident_wgs() { return kMaxWgsPerCu * device_cus(); }
 
 // Largest cluster size the fused launcher may pick for this shape (host-only arithmetic, so
 // the workspace size can be computed without a device).
@@ -25,7 +30,7 @@ inline int fused_cluster_bound(const lot_shape& s)
     const int tiles = (s.n + kTileTokens - 1) / kTileTokens;
     int c = (tiles + kFusedWaves - 1) / kFusedWaves;
     if (c > kMaxCluster) c = kMaxCluster;
-    int by_capacity = kMaxResidentWgs / problems;
+    int by_capacity = max_resident_wgs() / problems;
     if (by_capacity < 1) by_capacity = 1;
     if (c > by_capacity) c = by_capacity;
     return c < 1 ? 1 : c;
@@ -35,6 +40,20 @@ inline bool fused_supports(const lot_shape& s)
 {
     return s.d_k == s.d_v && (s.d_k == 32 || s.d_k == 64) && s.r >= 1 && s.r <= 64;
 }
+
+// Fixed-point format of the column sums that the fused kernel's workgroups exchange: a parity buffer
+// receives at most iters/2 + 1 passes, each adding at most n per pivot, and must stay below 2^55 with
+// at least 8 fractional bits.  Returns the number of fractional bits, or a negative number when the
+// sums do not fit (astronomical iteration counts only).
+inline int fused_exchange_frac_bits(int n_longer, int iters)
+{
+    const double max_sum = ((double)iters / 2.0 + 1.0) * (double)n_longer;
+    int bits = 0;
+    while (bits < 64 && (double)(1ull << bits) < max_sum + 1.0) ++bits;   // ceil(log2(max_sum + 1))
+    const int frac = 55 - bits;
+    return frac >= 8 ? frac : -1;
+}
+inline bool fused_exchange_fits(int n_longer, int iters) { return fused_exchange_frac_bits(n_longer, iters) >= 0; }
 
 // Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
 struct Workspace {
@@ -48,6 +67,7 @@ struct Workspace {
     size_t colacc_bytes;
     size_t u_part;        // float [G][cluster_bound][64][d_v]
     size_t y_tile;        // float [G][64][d_v]
+    size_t fused_total;   // end of the regions the fused kernel uses
     // reference path
     size_t C;             // float [2][G][n][r]
     size_t f;             // float [2][G][n]
@@ -77,6 +97,7 @@ inline Workspace carve(const lot_shape& s)
     w.colacc = take(w.colacc_bytes);
     w.u_part = take(G * cb * 64 * dv * 4);
     w.y_tile = take(G * 64 * dv * 4);
+    w.fused_total = off;
     w.Zt = take((size_t)s.H * r * s.d_k * 4);
     w.C = take(2 * G * n * r * 4);
     w.f = take(2 * G * n * 4);
@@ -227,22 +248,26 @@ unsigned long long next_nonce();
 // The backward assemble kernel normalises the rows of exponentials of all iterations of a tile with
 // one shift per row instead of each iteration's exact row maximum, checks the row sums, and re-shifts
 // when a sum leaves [1/limit, limit].  2^40 by default: every exponential that matters (down to 2^-24
-// of the row maximum) then stays far from the ends of the fp32 range.  The environment variable
-// LOT_RESHIFT_BITS (0..40), read at each call, lowers the limit to 2^bits: a testing aid that makes
-// the re-shifting branch run on ordinary inputs (0: practically every iteration takes it).
+// of the row maximum) then stays far from the ends of the fp32 range.  lot_debug_set(LOT_KNOB_RESHIFT_BITS,
+// bits) with bits in 0..40 lowers the limit to 2^bits: a testing aid that makes the re-shifting branch
+// run on ordinary inputs (0: practically every iteration takes it).
 float reshift_limit();
 
 // The tiled backward path assembles the similarity gradients of all iterations of a tile at once (two
 // small matrix products) when there are at most 16 iterations, and redoes, iteration by iteration, only
-// the workgroups in which a row sum left the range above.  The environment variable
-// LOT_BWD_ASSEMBLE_BY_ITERATION (non-zero), read at each call, sends every workgroup through the
-// iteration-by-iteration kernel: a testing aid that keeps that kernel exercised on ordinary inputs.
+// the workgroups in which a row sum left the range above.  lot_debug_set(LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION,
+// 1) sends every workgroup through the iteration-by-iteration kernel: a testing aid that keeps that
+// kernel exercised on ordinary inputs.
 bool assemble_by_iteration();
 
-// Poll budget of a bounded wait between cooperating workgroups (2^21 polls by default: seconds).  The
-// environment variable LOT_SPIN_LIMIT (read at each call) replaces it: a testing aid -- with 0 every
-// wait gives up at once, the kernels end early and the call is reported by lot_workspace_status.
+// Poll budget of a bounded wait between cooperating workgroups (2^21 polls by default: seconds).
+// lot_debug_set(LOT_KNOB_SPIN_LIMIT, v) replaces it: a testing aid -- with 0 every wait gives up at
+// once, the kernels end early and the call is reported by lot_workspace_status.
 uint32_t spin_limit();
+
+// Testing aid (LOT_KNOB_BWD_SWEEP_LAUNCHES): run the tiled backward's forward sweep as one launch per
+// pass although the persistent form would fit.
+bool sweep_by_launches();
 
 #define LOT_HIP_CHECK(expr)                                   \
     do {                                                      \

@@ -9,8 +9,10 @@ random-number streams.
 Recipe (the paper's workloads, shapes only): Q, K, V, Z are i.i.d. N(0,1) scaled by d^-1/2;
 the pivot masses (the paper's p^0 / sigma, "Empirical measures and pivot" in Method) are the
 softmax of r i.i.d. N(0,1) logits per head, hence strictly positive and summing to one.  For
-the bf16 workloads Q, K, V and Z are rounded to bf16 (round to nearest even) here, before
-either side reads them, so input rounding is not part of any error that is compared.
+the bf16 workloads Q, K, V and (by default) Z are rounded to bf16 (round to nearest even) here,
+before either side reads them, so input rounding is not part of any error that is compared.  The
+library takes Z in fp32 whatever the I/O type (a learnable parameter): `round_pivots=False` leaves it
+unrounded, so that the library's own handling of an ordinary fp32 Z is compared as well.
 """
 from __future__ import annotations
 
@@ -112,10 +114,11 @@ def shrink(w: Workload, **kw) -> Workload:
     return replace(w, **kw)
 
 
-def make_inputs(w: Workload, d_v: int | None = None) -> dict:
+def make_inputs(w: Workload, d_v: int | None = None, round_pivots: bool = True) -> dict:
     """Q, K: [B,H,n,d]; V: [B,H,n,d_v]; Z: [H,r,d]; beta: [H,r] -- all float32 numpy arrays.
 
-    For dtype == "bf16" the values of Q, K, V, Z are bf16 representable (see `bf16_bits`).
+    For dtype == "bf16" the values of Q, K, V (and of Z unless round_pivots is False) are bf16
+    representable (see `bf16_bits`).
     """
     d_v = w.d if d_v is None else d_v
     scale = float(w.d) ** -0.5
@@ -127,5 +130,25 @@ def make_inputs(w: Workload, d_v: int | None = None) -> dict:
     e = np.exp(logits - logits.max(axis=1, keepdims=True))
     beta = (e / e.sum(axis=1, keepdims=True)).astype(np.float32)
     if w.dtype == "bf16":
-        q, k, v, z = (round_to_bf16(t) for t in (q, k, v, z))
+        q, k, v = (round_to_bf16(t) for t in (q, k, v))
+        if round_pivots:
+            z = round_to_bf16(z)
     return {"Q": q, "K": k, "V": v, "Z": z, "beta": beta}
+
+
+def to_device(x: dict, dtype: str) -> dict:
+    """numpy inputs (float32; Q, K, V, dO bf16-representable when dtype == 'bf16') -> torch device tensors.
+    Z and beta stay float32 whatever the I/O type."""
+    import torch
+    dev = {}
+    for k in ("Q", "K", "V", "dO"):
+        if k not in x:
+            continue
+        if dtype == "bf16":
+            bits = bf16_bits(x[k]).view(np.int16)
+            dev[k] = torch.from_numpy(bits).cuda().view(torch.bfloat16)
+        else:
+            dev[k] = torch.from_numpy(np.ascontiguousarray(x[k])).cuda()
+    dev["Z"] = torch.from_numpy(np.ascontiguousarray(x["Z"], dtype=np.float32)).cuda()
+    dev["beta"] = torch.from_numpy(np.ascontiguousarray(x["beta"], dtype=np.float32)).cuda()
+    return dev

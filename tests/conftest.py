@@ -17,3 +17,13 @@ def oracle():
     from oracle import lot_oracle
     lot_oracle.build()
     return lot_oracle
+
+
+@pytest.fixture
+def knobs():
+    """The library's testing aids (lot_debug_set), restored to their defaults afterwards."""
+    from paper_2509_23436_amd import lot
+    yield lot
+    for k in (lot.KNOB_SPIN_LIMIT, lot.KNOB_RESHIFT_BITS, lot.KNOB_BWD_ASSEMBLE_BY_ITERATION,
+              lot.KNOB_BWD_SWEEP_LAUNCHES):
+        lot.lot_debug_set(k, -1)

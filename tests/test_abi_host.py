@@ -42,12 +42,122 @@ def test_workspace_bytes_and_shape_validation(L):
     assert L.lot_workspace_bytes(ctypes.byref(_shape(n=4096)), 5, ctypes.byref(big)) == 0
     assert big.value > out.value
     for bad in (dict(n=0), dict(r=0), dict(B=0), dict(H=-1), dict(d_k=0), dict(d_v=0), dict(n=1 << 25),
-                dict(d_k=30), dict(d_v=6)):
+                dict(d_k=30), dict(d_v=6), dict(B=1 << 12, H=17)):
         assert L.lot_workspace_bytes(ctypes.byref(_shape(**bad)), 5, ctypes.byref(out)) == -2, bad
     assert L.lot_workspace_bytes(ctypes.byref(_shape(io_dtype=7)), 5, ctypes.byref(out)) == -5
     assert L.lot_workspace_bytes(ctypes.byref(_shape()), 0, ctypes.byref(out)) == -4
     assert L.lot_workspace_bytes(None, 5, ctypes.byref(out)) == -1
     assert L.lot_workspace_bytes(ctypes.byref(_shape()), 5, None) == -1
+
+
+def _need(fn, shape, iters, *path):
+    out = ctypes.c_size_t(0)
+    rc = fn(ctypes.byref(shape), iters, *path, ctypes.byref(out))
+    assert rc == 0, rc
+    return out.value
+
+
+def test_workspace_is_sized_for_the_kernels_that_run(L):
+    """The tile kernels keep nothing of size n x r, and the workspace query must say so: it returns what the
+    kernels AUTO selects use; the plain kernels' n x r intermediates are charged only to a caller who
+    forces them."""
+    MB = 1 << 20
+    headline = lot.lot_shape(2, 8, 16384, 64, 64, 64, lot.LOT_BF16)
+    auto = _need(L.lot_workspace_bytes, headline, 10)
+    assert auto <= 32 * MB
+    assert auto == _need(L.lot_workspace_bytes_path, headline, 10, lot.PATH_AUTO)
+    assert auto == _need(L.lot_workspace_bytes_path, headline, 10, lot.PATH_FUSED)
+    assert auto == _need(L.lot_couplings_workspace_bytes, headline, 10, lot.PATH_AUTO)
+    plain = _need(L.lot_workspace_bytes_path, headline, 10, lot.PATH_REFERENCE)
+    assert plain >= 4 * 16 * 16384 * 64 * 4           # two similarity matrices and two couplings
+    assert _need(L.lot_attention_bwd_workspace_bytes, headline, 10) <= 128 * MB    # per-iteration Gram matrices
+    assert _need(L.lot_attention_bwd_workspace_bytes_path, headline, 10, lot.PATH_REFERENCE) >= 5 * 2 * 16 * 16384 * 64 * 4
+    # the largest point of the paper's runtime grid (grouped kernels)
+    corner = lot.lot_shape(1, 8, 131072, 64, 64, 256, lot.LOT_BF16)
+    assert _need(L.lot_workspace_bytes, corner, 5) <= 64 * MB
+    assert _need(L.lot_attention_bwd_workspace_bytes, corner, 5) <= 1024 * MB
+    # lot_couplings has no grouped kernels: beyond 64 pivots it is the plain kernels under AUTO too
+    assert _need(L.lot_couplings_workspace_bytes, corner, 5, lot.PATH_AUTO) > 1024 * MB
+    out = ctypes.c_size_t(0)
+    assert L.lot_couplings_workspace_bytes(ctypes.byref(corner), 5, lot.PATH_FUSED, ctypes.byref(out)) == -9
+    assert L.lot_workspace_bytes_path(ctypes.byref(_shape(d_k=128, d_v=128)), 5, lot.PATH_FUSED, ctypes.byref(out)) == -9
+    assert L.lot_workspace_bytes_path(ctypes.byref(_shape()), 5, 9, ctypes.byref(out)) == -9
+    # the backward of short or two-pivot fp32 problems runs on the plain kernels under AUTO
+    short = _shape(n=12)
+    assert _need(L.lot_attention_bwd_workspace_bytes, short, 5) == \
+        _need(L.lot_attention_bwd_workspace_bytes_path, short, 5, lot.PATH_REFERENCE)
+    two = _shape(n=4096, r=2)
+    assert _need(L.lot_attention_bwd_workspace_bytes, two, 5) == \
+        _need(L.lot_attention_bwd_workspace_bytes_path, two, 5, lot.PATH_REFERENCE)
+    # cross attention
+    x = lot.lot_xshape(2, 8, 16384, 4096, 64, 64, 64, lot.LOT_BF16)
+    assert _need(L.lot_cross_workspace_bytes, x, 10) <= 32 * MB
+    assert _need(L.lot_cross_workspace_bytes_path, x, 10, lot.PATH_REFERENCE) > 64 * MB
+    assert _need(L.lot_cross_attention_bwd_workspace_bytes, x, 10) <= 128 * MB
+
+
+def test_a_call_checks_the_workspace_against_the_path_it_takes(L):
+    headline = lot.lot_shape(2, 8, 16384, 64, 64, 64, lot.LOT_BF16)
+    auto = _need(L.lot_workspace_bytes, headline, 10)
+    assert _call_fwd(L, shape=headline, iters=10, ws_bytes=auto - 1) == -6
+    assert _call_fwd(L, shape=headline, iters=10, ws_bytes=auto, path=lot.PATH_REFERENCE) == -6
+
+
+def test_status_words_and_testing_knobs(L):
+    words = (ctypes.c_ulonglong * 2)(0, 0)
+    assert L.lot_status_words(words) == 0
+    words[0], words[1] = 5, 7
+    assert L.lot_status_words(words) == 0            # the failed launch is not the last one
+    words[0] = 7
+    assert L.lot_status_words(words) == -10
+    assert L.lot_status_words(None) == -1
+    assert L.lot_workspace_status_async(None, words, None) == -1
+    assert L.lot_workspace_status_async(ctypes.c_void_p(4096), None, None) == -1
+    assert L.lot_debug_set(lot.KNOB_SPIN_LIMIT, 0) == 0
+    assert L.lot_debug_set(lot.KNOB_SPIN_LIMIT, -1) == 0
+    assert L.lot_debug_set(17, 1) == -2 and L.lot_debug_set(-1, 1) == -2
+
+
+def test_the_binding_checks_every_tensor_against_the_shape_before_calling(L):
+    """The C ABI sees only pointers: a tensor that is shorter than the shape says would be read or
+    written past its end.  The binding therefore compares every tensor with the others on the host."""
+    import torch
+    B, H, n, d, r = 2, 3, 40, 32, 8
+    t = lambda *shape, dtype=torch.float32: torch.zeros(shape, dtype=dtype)      # noqa: E731
+    good = dict(Q=t(B, H, n, d), K=t(B, H, n, d), V=t(B, H, n, d), Z=t(H, r, d), beta=t(H, r))
+
+    def fwd(**kw):
+        a = dict(good, **kw)
+        return lot.lot_attention_fwd(a["Q"], a["K"], a["V"], a["Z"], a["beta"], 0.1, 3, out=a.get("out"))
+
+    for kw in (dict(K=t(B, H, n - 1, d)), dict(K=t(B, H + 1, n, d)), dict(K=t(B, H, n, d + 8)), dict(V=t(B, H, n + 5, d)),
+               dict(V=t(B + 1, H, n, d)), dict(Z=t(H, r, d + 32)), dict(Z=t(H - 1, r, d)), dict(beta=t(H, r + 1)),
+               dict(beta=t(H * r)), dict(out=t(B, H, n - 1, d)), dict(out=t(B, H, n, 2 * d)),
+               dict(Q=t(B * H, n, d)), dict(Q=t(B, H, n, d).transpose(2, 3))):
+        with pytest.raises(ValueError):
+            fwd(**kw)
+    for kw in (dict(K=t(B, H, n, d, dtype=torch.bfloat16)), dict(Z=t(H, r, d, dtype=torch.bfloat16)),
+               dict(beta=t(H, r, dtype=torch.float64)), dict(Q=t(B, H, n, d, dtype=torch.float16)),
+               dict(out=t(B, H, n, d, dtype=torch.bfloat16))):
+        with pytest.raises(TypeError):
+            fwd(**kw)
+    # consistent shapes on the host side: refused too (there is no CPU path), again before any call
+    with pytest.raises(ValueError, match="device"):
+        fwd()
+    with pytest.raises(ValueError):
+        lot.lot_couplings(good["Q"], t(B, H, n + 1, d), good["Z"], good["beta"], 0.1, 3)
+    with pytest.raises(ValueError):
+        lot.lot_attention_bwd(good["Q"], good["K"], good["V"], good["Z"], good["beta"], 0.1, 3, t(B, H, n, d + 8))
+    with pytest.raises(ValueError):
+        lot.lot_attention_cls_bwd(good["Q"], good["K"], good["V"], good["Z"], good["beta"], 0.1, 3, 1.0, t(B, H, n - 1, d))
+    with pytest.raises(ValueError):     # cross attention: K and V must agree on the key count
+        lot.lot_cross_attention_fwd(good["Q"], t(B, H, 70, d), t(B, H, 71, d), good["Z"], good["beta"], 0.1, 3)
+    with pytest.raises(ValueError):
+        lot.lot_cross_attention_fwd(good["Q"], t(B, H, 70, d), t(B, H, 70, d), good["Z"], good["beta"], 0.1, 3,
+                                    mass_k=t(B, H, 69))
+    with pytest.raises(ValueError):
+        lot.lot_cross_attention_bwd(good["Q"], t(B, H, 70, d), t(B, H, 70, d), good["Z"], good["beta"], 0.1, 3,
+                                    t(B, H, 70, d))     # dO must follow the queries
 
 
 def _call_fwd(L, shape=None, Q=4096, K=8192, V=12288, Z=256, beta=512, eps=0.1, iters=5, out=16384,

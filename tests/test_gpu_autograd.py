@@ -87,3 +87,40 @@ def test_cross_attention_gradients_through_loss_backward_match_the_oracle():
         err = rel_max_err(leaf.grad.double().cpu().numpy(), r64.numpy())
         print("  d%-6s max-norm rel err %.3e" % (name, err), flush=True)
         assert err <= 1e-4, name
+
+
+def test_workspaces_are_reused_and_a_failed_wait_is_raised_by_a_later_call(knobs):
+    """One workspace per shape (a training step allocates none after its first iteration), and a wait
+    between workgroups that gave up surfaces, without any device synchronisation by the glue, as an
+    exception at a later call.  The wait is made to give up from the host (poll budget zero): every
+    kernel still ends normally."""
+    import torch
+    from paper_2509_23436_amd import autograd, lot
+    w = dataclasses.replace(W["long_4k"], B=1, H=2, iters=3, seed=93)       # several workgroups per problem
+    x = synth.make_inputs(w)
+    d = {k: torch.tensor(x[k], device="cuda").to(torch.bfloat16 if k in ("Q", "K", "V") else torch.float32)
+         for k in ("Q", "K", "V", "Z", "beta")}
+    for k in ("Q", "K", "V", "Z"):
+        d[k].requires_grad_(True)
+    autograd._workspaces.clear()
+    for step in range(3):
+        O = autograd.lot_attention(d["Q"], d["K"], d["V"], d["Z"], d["beta"], w.eps, w.iters)
+        O.float().pow(2).sum().backward()
+        if step == 0:
+            held = {k: v.data_ptr() for k, v in autograd._workspaces.items()}
+            assert len(held) == 2                                           # forward and backward
+    assert {k: v.data_ptr() for k, v in autograd._workspaces.items()} == held
+    autograd.check_pending(wait=True)                                       # nothing failed so far
+
+    lot.lot_debug_set(lot.KNOB_SPIN_LIMIT, 0)
+    with torch.no_grad():
+        O = autograd.lot_attention(d["Q"], d["K"], d["V"], d["Z"], d["beta"], w.eps, w.iters)
+    lot.lot_debug_set(lot.KNOB_SPIN_LIMIT, -1)
+    with pytest.raises(RuntimeError, match="gave up"):
+        autograd.check_pending(wait=True)
+    assert torch.isnan(O.float()).any()
+    # the next call on the same workspace is an ordinary one
+    with torch.no_grad():
+        O = autograd.lot_attention(d["Q"], d["K"], d["V"], d["Z"], d["beta"], w.eps, w.iters)
+    autograd.check_pending(wait=True)
+    assert torch.isfinite(O.float()).all()

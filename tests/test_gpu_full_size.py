@@ -79,6 +79,8 @@ GRID = {
     "n_131072_r64_T5": (dataclasses.replace(synth.WORKLOADS["long_64k"], B=1, H=2, n=131072, iters=5, seed=60), [1]),
     "n_8192_r128_T5": (dataclasses.replace(synth.WORKLOADS["long_4k"], B=1, H=2, n=8192, r=128, iters=5, seed=61), [0, 1]),
     "n_4096_r256_T5": (dataclasses.replace(synth.WORKLOADS["long_4k"], B=1, H=2, n=4096, r=256, iters=5, seed=62), [1]),
+    # the largest point of the grid, in the launch configuration the grid benchmark times (B = 1, H = 8)
+    "n_131072_r256_T5": (dataclasses.replace(synth.WORKLOADS["long_64k"], B=1, H=8, n=131072, r=256, iters=5, seed=63), [5]),
 }
 
 

@@ -4,21 +4,7 @@ import numpy as np
 from paper_2509_23436_amd import synth
 
 
-def to_device(x, dtype):
-    """numpy inputs (float32, bf16-representable when dtype == 'bf16') -> torch device tensors."""
-    import torch
-    dev = {}
-    for k in ("Q", "K", "V", "dO"):
-        if k not in x:
-            continue
-        if dtype == "bf16":
-            bits = synth.bf16_bits(x[k]).view(np.int16)
-            dev[k] = torch.from_numpy(bits).cuda().view(torch.bfloat16)
-        else:
-            dev[k] = torch.from_numpy(np.ascontiguousarray(x[k])).cuda()
-    dev["Z"] = torch.from_numpy(np.ascontiguousarray(x["Z"])).cuda()
-    dev["beta"] = torch.from_numpy(np.ascontiguousarray(x["beta"])).cuda()
-    return dev
+to_device = synth.to_device
 
 
 def to_host_f64(t):
@@ -35,3 +21,22 @@ def rel_max_err(got, ref):
 def tolerance(dtype):
     """Bars stated for the target: fp32 <= 1e-4 on O and 1e-5 on marginals; bf16 I/O <= 2e-2 on O."""
     return (1e-4, 1e-5) if dtype == "f32" else (2e-2, 1e-5)
+
+
+def workspace_for(shape, iters, paths=(0, 1, 2), couplings=True, backward=False):
+    """One device workspace large enough for every listed execution path of this shape (paths a shape
+    does not support are skipped)."""
+    import torch
+    from paper_2509_23436_amd import lot
+    need = 0
+    for path in paths:
+        for fn, wanted in ((lot.lot_workspace_bytes, True), (lot.lot_couplings_workspace_bytes, couplings),
+                           (lot.lot_attention_bwd_workspace_bytes, backward)):
+            if not wanted:
+                continue
+            try:
+                need = max(need, fn(shape, iters, path))
+            except lot.LotError as e:
+                if e.code != -9:
+                    raise
+    return torch.empty(need, dtype=torch.uint8, device="cuda")
