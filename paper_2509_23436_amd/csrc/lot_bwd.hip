@@ -179,29 +179,51 @@ __global__ void bwd_col_partial(const float* __restrict__ A, const float* __rest
     }
 }
 
-// Pivot-side bookkeeping of one reverse step, one thread per (pair, t).
+// Pivot-side bookkeeping of one reverse step, one workgroup of 256 threads per pair.
 //   last != 0: colsum holds s_t = sum_i dGhat Ghat  -> dc, rho, db
 //   last == 0: dg holds dg^k                         -> dc, db
 // c^k_t = beta_t exp((g^{k-1}_t - g^k_t)/eps).
-__global__ void bwd_pivot_pre(const float* __restrict__ part, const float* __restrict__ g_prev,
+// The potentials are defined up to a common constant, so every dg^k sums to zero over the pivots; the
+// step dg^k -> dg^{k-1} leaves the direction c^k unchanged (it is the one eigenvector of that map with
+// eigenvalue 1, and it changes no similarity gradient), so whatever rounding puts into the sum would
+// stay for all remaining iterations and end up, T times over, in the gradient of the masses.  The sum is
+// therefore taken out of dg^k along c^k (sum_t c^k_t = 1) before it is used.
+__global__ void __launch_bounds__(256) bwd_pivot_pre(const float* __restrict__ part, const float* __restrict__ g_prev,
                               const float* __restrict__ g_cur, const float* __restrict__ beta,
-                              const float* __restrict__ dg, float* __restrict__ dc, float* __restrict__ rho,
-                              float* __restrict__ db, int pairs, int G, int H, int r, int chunks, float eps, int last)
+                              float* __restrict__ dg, float* __restrict__ dc, float* __restrict__ rho,
+                              float* __restrict__ db, int G, int H, int r, int chunks, float eps, int last)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= pairs * r) return;
-    const int pair = idx / r, t = idx % r;
-    const float b = beta[((pair % G) % H) * r + t];
-    const float c = b * expf((g_prev[idx] - g_cur[idx]) / eps);
-    if (last) {
-        float s = 0.f;
-        for (int k = 0; k < chunks; ++k) s += part[((size_t)pair * chunks + k) * r + t];
-        dc[idx] = -s / c;
-        rho[idx] = b / c;
-        db[idx] = s / b;          // first contribution of this solve
-    } else {
-        dc[idx] = -eps * dg[idx] / c;
-        db[idx] += eps * dg[idx] / b;
+    __shared__ float s_sum[256];
+    const int pair = blockIdx.x;
+    const float* bh = beta + ((pair % G) % H) * r;
+    float total = 0.f;
+    if (!last) {
+        float mine = 0.f;
+        for (int t = threadIdx.x; t < r; t += 256) mine += dg[(size_t)pair * r + t];
+        s_sum[threadIdx.x] = mine;
+        __syncthreads();
+        for (int half = 128; half > 0; half >>= 1) {
+            if ((int)threadIdx.x < half) s_sum[threadIdx.x] += s_sum[threadIdx.x + half];
+            __syncthreads();
+        }
+        total = s_sum[0];
+    }
+    for (int t = threadIdx.x; t < r; t += 256) {
+        const size_t idx = (size_t)pair * r + t;
+        const float b = bh[t];
+        const float c = b * expf((g_prev[idx] - g_cur[idx]) / eps);
+        if (last) {
+            float s = 0.f;
+            for (int k = 0; k < chunks; ++k) s += part[((size_t)pair * chunks + k) * r + t];
+            dc[idx] = -s / c;
+            rho[idx] = b / c;
+            db[idx] = s / b;          // first contribution of this solve
+        } else {
+            const float d = dg[idx] - c * total;
+            dg[idx] = d;
+            dc[idx] = -eps * d / c;
+            db[idx] += eps * d / b;
+        }
     }
 }
 
@@ -396,8 +418,8 @@ int run_backward_t(const BwdArgs& a)
         bwd_col_partial<<<(unsigned)G * chunks, 64, 0, st_>>>(dghats[sd], ghats[sd], colpart, n, r, chunks);
         for (int k = T_; k >= 1; --k) {
             const int last = k == T_;
-            bwd_pivot_pre<<<pr_blocks, 256, 0, st_>>>(colpart, pot(k - 1, sd), pot(k, sd), a.beta, dg_s, dc_s, rho_s, db_s, G, G, s.H, r,
-                                                      chunks, a.eps, last);
+            bwd_pivot_pre<<<(unsigned)G, 256, 0, st_>>>(colpart, pot(k - 1, sd), pot(k, sd), a.beta, dg_s, dc_s, rho_s, db_s, G, s.H, r,
+                                                        chunks, a.eps, last);
             bwd_rows<<<blocks_for(rows * width, 256), 256, 0, st_>>>(Cs[sd], pot(k - 1, sd), dghats[sd], rho_s, dc_s, dCs[sd],
                                                                      ybufs[sd], masses[sd], rows, n, r, a.eps, last, width);
             bwd_col_partial<<<(unsigned)G * chunks, 64, 0, st_>>>(ybufs[sd], nullptr, colpart, n, r, chunks);

@@ -365,6 +365,26 @@ __global__ void __launch_bounds__(kThreads, 2) gb_rec_pass(GbParams p, int k)
         const int t = tid;
         const bool live = t < p.f.r;
         float dc = 0.f;
+        float dg = 0.f;
+        if (live && k < T) {
+            float acc = 0.f;
+            for (int c = 0; c < chunks; ++c) acc += p.dg_part[(((size_t)k * pairs + pair) * chunks + c) * kRmax + t];
+            dg = -(a / p.f.eps) * acc;                  // dg^k
+        }
+        // The potentials are defined up to a common constant, so dg^k sums to zero over the pivots, and the
+        // step to dg^{k-1} leaves the direction c^k unchanged (it changes no similarity gradient): what
+        // rounding puts into that sum would stay for all remaining iterations and end up, T times over, in
+        // the gradient of the masses.  It is taken out along c^k (sum_t c^k_t = 1).  Fixed order of additions.
+        float dg_total = 0.f;
+        if (k < T) {
+            float v = dg;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            if (lane == 0) s_cs[1][wave] = v;
+            __syncthreads();
+            dg_total = (s_cs[1][0] + s_cs[1][1]) + (s_cs[1][2] + s_cs[1][3]);
+            __syncthreads();
+        }
         if (live) {
             const float b = p.f.beta[h * p.f.r + t];
             const float ck = gb_colsum(p, k, pair, t) * a;
@@ -375,9 +395,7 @@ __global__ void __launch_bounds__(kThreads, 2) gb_rec_pass(GbParams p, int k)
                 dc = -s / ck;
                 db_add = s / b;
             } else {
-                float acc = 0.f;
-                for (int c = 0; c < chunks; ++c) acc += p.dg_part[(((size_t)k * pairs + pair) * chunks + c) * kRmax + t];
-                const float dg = -(a / p.f.eps) * acc;                  // dg^k
+                dg -= ck * dg_total;
                 dc = -p.f.eps * dg / ck;
                 db_add = p.f.eps * dg / b;
             }

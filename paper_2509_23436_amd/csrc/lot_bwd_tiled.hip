@@ -741,6 +741,7 @@ __global__ void bt_recursion(BtParams p, int R)
     // the quarters are added in a fixed order by the threads with q == 0, which carry the recursion.
     __shared__ float s_v[64];
     __shared__ float s_q[4][64];
+    __shared__ float s_dg[64];
     const int pair = blockIdx.x, t = threadIdx.x & 63, q = threadIdx.x >> 6, pairs = 2 * p.G, T = p.T;
     const int h = (pair % p.G) % p.H;
     const bool live = t < p.r;
@@ -770,12 +771,27 @@ __global__ void bt_recursion(BtParams p, int R)
         __syncthreads();
         return (s_q[0][t] + s_q[1][t]) + (s_q[2][t] + s_q[3][t]);
     };
+    // The potentials are defined up to a common constant, so every dg^k sums to zero over the pivots, and
+    // the step dg^k -> dg^{k-1} leaves the direction c^k unchanged (its eigenvector of eigenvalue 1, which
+    // changes no similarity gradient): whatever rounding puts into that sum would stay for all remaining
+    // iterations and end up, T times over, in the gradient of the masses.  It is taken out along c^k
+    // (sum_t c^k_t = 1) before dg^k is used.
+    auto without_sum = [&](float dg, float ck) {
+        if (q == 0) s_dg[t] = live ? dg : 0.f;
+        __syncthreads();
+        float total = 0.f;
+        for (int u = 0; u < 64; ++u) total += s_dg[u];
+        __syncthreads();
+        return dg - ck * total;
+    };
     float db = live ? s / b : 0.f;
     float dc = live ? -s / colsum(T) : 0.f;
     if (q == 0) p.dcs[((size_t)T * pairs + pair) * 64 + t] = dc;
     float dg = -(nn + a * gram_times(T, dc)) / p.eps;          // dg^{T-1}
     for (int k = T - 1; k >= 1; --k) {
-        dc = live ? -p.eps * dg / colsum(k) : 0.f;
+        const float ck = colsum(k);
+        dg = without_sum(dg, ck);
+        dc = live ? -p.eps * dg / ck : 0.f;
         db += live ? p.eps * dg / b : 0.f;
         if (q == 0) p.dcs[((size_t)k * pairs + pair) * 64 + t] = dc;
         dg = -(a / p.eps) * gram_times(k, dc);                  // dg^{k-1}

@@ -146,10 +146,8 @@ def test_cross_backward_matches_oracle(name, path_name):
         outs.append(got)
         if ws is None:
             shape = lot.lot_xshape(B, H, n_q, n_k, c["d"], c["d_v"], c["r"], 1 if c["bf16"] else 0)
-            import ctypes
-            need = ctypes.c_size_t(0)
-            assert lot.lib().lot_cross_attention_bwd_workspace_bytes(ctypes.byref(shape), iters, ctypes.byref(need)) == 0
-            ws = torch.full((need.value,), fill ^ 0xFF, dtype=torch.uint8, device="cuda")
+            need = lot.lot_cross_attention_bwd_workspace_bytes(shape, iters, path)
+            ws = torch.full((need,), fill ^ 0xFF, dtype=torch.uint8, device="cuda")
     for a, b in zip(*outs):
         assert torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
                            b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
