@@ -61,7 +61,8 @@ typedef enum {
     LOT_ERR_ALIGN = -7,      /* a tensor pointer is not 16-byte aligned */
     LOT_ERR_HIP = -8,        /* a HIP call failed (see lot_strerror) */
     LOT_ERR_PATH = -9,       /* the requested execution path does not support this shape */
-    LOT_ERR_SYNC = -10       /* lot_workspace_status / lot_status_words: a device-side wait gave up */
+    LOT_ERR_SYNC = -10,      /* lot_workspace_status / lot_status_words: a device-side wait gave up */
+    LOT_ERR_SCRATCH = -11    /* lot_attention_fwd_static: the shape needs more than the fixed scratch array */
 } lot_status;
 
 typedef struct {
@@ -97,6 +98,25 @@ int lot_couplings_workspace_bytes(const lot_shape* shape, int iters, int path, s
 int lot_attention_fwd(const lot_shape* shape, const void* Q, const void* K, const void* V,
                       const float* Z, const float* beta, float eps, int iters, void* out,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * lot_attention_fwd for callers that cannot allocate device memory or hand one over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same operation, kernels,
+ * arguments and rules as lot_attention_fwd with LOT_PATH_AUTO, minus the workspace: the scratch memory
+ * is a fixed array inside the library, lot_static_scratch_bytes() = 32 MiB of device memory, which
+ * every GPU that the library runs on holds until the process ends.  A shape whose kernels need more
+ * (lot_workspace_bytes tells) is refused with LOT_ERR_SCRATCH before anything is launched; the
+ * headline shape (B = 2, H = 8, n = 16384, r = 64) needs 18 MiB.  The call allocates and frees nothing
+ * (no hipMalloc, no hipFree, no allocating library routine); the address of the array is looked up
+ * once per device, at the first call with that device current.  The array needs no clearing between
+ * calls (the kernels mark what they use per launch), but every call on one GPU shares it: calls that
+ * overlap on one GPU (two streams, two threads) race and give undefined results -- serialise them, or
+ * use lot_attention_fwd with workspaces of your own.
+ */
+size_t lot_static_scratch_bytes(void);
+int lot_attention_fwd_static(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                             const float* Z, const float* beta, float eps, int iters, void* out,
+                             void* hip_stream);
 
 /* Debug route: the two couplings themselves (paper: Gamma^(1) and Gamma^(2) in scaling form). */
 int lot_couplings(const lot_shape* shape, const void* Q, const void* K,

@@ -279,6 +279,63 @@ int lot_couplings(const lot_shape* shape, const void* Q, const void* K,
                               hip_stream, LOT_PATH_AUTO);
 }
 
+// ---------------------------------------------------------------------------------------------
+// lot_attention_fwd without a workspace argument: the scratch memory is a fixed array of this library
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr int kStaticScratchDevices = 64;
+// Every device that loads the library holds its own copy of this array, at its own address, until the
+// process ends.  In host code the name is only a handle: the device address is asked for once per
+// device (scratch_of_current_device) and that pointer is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::atomic<void*> g_scratch_ptr[kStaticScratchDevices] = {};
+
+static int scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    LOT_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticScratchDevices) {
+        last_hip_error() = hipErrorInvalidDevice;
+        return LOT_ERR_HIP;
+    }
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        // the current device's copy; two threads that race here obtain the same address
+        LOT_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (ptr == nullptr) {
+            last_hip_error() = hipErrorInvalidSymbol;
+            return LOT_ERR_HIP;
+        }
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return LOT_OK;
+}
+
+size_t lot_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int lot_attention_fwd_static(const lot_shape* shape, const void* Q, const void* K, const void* V,
+                             const float* Z, const float* beta, float eps, int iters, void* out, void* hip_stream)
+{
+    // everything that can be refused is refused before the first HIP call
+    int rc = validate_shape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!Q || !K || !V || !Z || !beta || !out) return LOT_ERR_NULL;
+    if (!(eps > 0.0f) || !std::isfinite(eps)) return LOT_ERR_EPS;
+    if (iters < 1) return LOT_ERR_ITERS;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(out, 16) || misaligned(Z, 4) ||
+        misaligned(beta, 4))
+        return LOT_ERR_ALIGN;
+    FwdImpl impl;
+    rc = pick_forward(*shape, iters, LOT_PATH_AUTO, false, &impl);
+    if (rc != LOT_OK) return rc;
+    if (forward_need(*shape, iters, impl) > kStaticScratchBytes) return LOT_ERR_SCRATCH;
+    void* ws = nullptr;
+    rc = scratch_of_current_device(&ws);
+    if (rc != LOT_OK) return rc;
+    return attention_impl(shape, Q, K, V, Z, beta, eps, iters, out, ws, kStaticScratchBytes, hip_stream, LOT_PATH_AUTO, 0);
+}
+
 static int validate_xshape(const lot_xshape* s)
 {
     if (!s) return LOT_ERR_NULL;
@@ -629,6 +686,8 @@ const char* lot_strerror(int code)
     case LOT_ERR_HIP: return hipGetErrorString(last_hip_error());
     case LOT_ERR_PATH: return "the requested execution path does not support this shape";
     case LOT_ERR_SYNC: return "a device-side wait between workgroups gave up";
+    case LOT_ERR_SCRATCH: return "the shape needs more scratch memory than the library's fixed array holds "
+                                 "(use lot_attention_fwd with a workspace of the caller's)";
     default: return "unknown status";
     }
 }

@@ -22,7 +22,7 @@ KNOB_SPIN_LIMIT, KNOB_RESHIFT_BITS, KNOB_BWD_ASSEMBLE_BY_ITERATION, KNOB_BWD_SWE
 ERR_SYNC = -10
 
 EXPORTS = ("lot_workspace_bytes", "lot_workspace_bytes_path", "lot_couplings_workspace_bytes",
-           "lot_attention_fwd", "lot_attention_fwd_path",
+           "lot_attention_fwd", "lot_attention_fwd_path", "lot_attention_fwd_static", "lot_static_scratch_bytes",
            "lot_couplings", "lot_couplings_path",
            "lot_attention_cls_fwd", "lot_attention_cls_fwd_path",
            "lot_cross_workspace_bytes", "lot_cross_workspace_bytes_path",
@@ -77,6 +77,9 @@ def lib():
         L.lot_cross_attention_bwd_workspace_bytes_path.argtypes = [xp, ci, ci, szp]
         L.lot_attention_fwd.argtypes = [sp, vp, vp, vp, vp, vp, cf, ci, vp, vp, sz, vp]
         L.lot_attention_fwd_path.argtypes = L.lot_attention_fwd.argtypes + [ci]
+        L.lot_attention_fwd_static.argtypes = [sp, vp, vp, vp, vp, vp, cf, ci, vp, vp]
+        L.lot_static_scratch_bytes.argtypes = []
+        L.lot_static_scratch_bytes.restype = sz
         L.lot_couplings.argtypes = [sp, vp, vp, vp, vp, cf, ci, vp, vp, vp, sz, vp]
         L.lot_couplings_path.argtypes = L.lot_couplings.argtypes + [ci]
         L.lot_attention_cls_fwd.argtypes = [sp, vp, vp, vp, vp, vp, cf, ci, cf, vp, vp, sz, vp]
@@ -97,7 +100,7 @@ def lib():
         L.lot_strerror.restype = ctypes.c_char_p
         L.lot_version.argtypes = []
         for name in EXPORTS:
-            if name != "lot_strerror":
+            if name not in ("lot_strerror", "lot_static_scratch_bytes"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -245,6 +248,22 @@ def lot_attention_fwd(Q, K, V, Z, beta, eps, iters, out=None, workspace=None, pa
     _check(lib().lot_attention_fwd_path(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
                                         ctypes.c_float(eps), int(iters), _ptr(out), _ptr(workspace),
                                         workspace.numel(), _stream(), int(path)))
+    return out
+
+
+def lot_static_scratch_bytes() -> int:
+    return int(lib().lot_static_scratch_bytes())
+
+
+def lot_attention_fwd_static(Q, K, V, Z, beta, eps, iters, out):
+    """lot_attention_fwd for callers that cannot allocate: no workspace argument (the library's own
+    fixed scratch array is used), `out` is required."""
+    B, H, n, _, d_k, d_v, r, code = _dims(Q, K, V, Z, beta)
+    shape = lot_shape(B, H, n, d_k, d_v, r, code)
+    _require(out, "out", Q.dtype, (B, H, n, d_v), Q.device)
+    _on_current_device(Q.device)
+    _check(lib().lot_attention_fwd_static(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(Z), _ptr(beta),
+                                          ctypes.c_float(eps), int(iters), _ptr(out), _stream()))
     return out
 
 

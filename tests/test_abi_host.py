@@ -194,7 +194,7 @@ def test_couplings_rejects_bad_arguments(L):
 
 
 def test_strerror_texts(L):
-    for code in range(0, -11, -1):
+    for code in range(0, -12, -1):
         if code == -8:
             continue
         text = L.lot_strerror(code).decode()
