@@ -134,6 +134,9 @@ def main() -> int:
     ap.add_argument("--bwd-steps", type=int, default=50,
                     help="timed calls of the backward pass (reported beside the headline; 0 skips it)")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "reference"])
+    ap.add_argument("--streaming", action="store_true",
+                    help="testing aid: the fused forward re-reads Q and K in every pass also where the kernel "
+                         "matrix would fit on chip (what sequences too long for that run)")
     ap.add_argument("--runtime-grid", action="store_true",
                     help="instead of the benchmark, time the forward and the backward "
                          "over the paper's runtime grid: n = 2^10..2^17, r in {32, 64, 128, 256}, T = 5; one JSON line")
@@ -171,6 +174,8 @@ def main() -> int:
         only = tuple(int(v) for v in args.grid_point.split(",")) if args.grid_point else None
         print(json.dumps({"runtime_grid": runtime_grid(torch, lot, synth, to_device, only)}))
         return 0
+    if args.streaming:
+        lot.lot_debug_set(lot.KNOB_FWD_STREAMING, 1)
     w = synth.WORKLOADS[args.workload]
     path = {"auto": lot.PATH_AUTO, "fused": lot.PATH_FUSED, "reference": lot.PATH_REFERENCE}[args.path]
     x = synth.make_inputs(w)

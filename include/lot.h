@@ -297,6 +297,8 @@ int lot_status_words(const unsigned long long* host_words);
  *   LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION non-zero: every workgroup through the iteration-by-iteration kernel
  *   LOT_KNOB_BWD_SWEEP_LAUNCHES        non-zero: the backward's forward sweep as one launch per pass
  *                                      (its form on a device that cannot hold the whole grid at once)
+ *   LOT_KNOB_FWD_STREAMING             non-zero: the fused forward re-reads Q and K in every pass (what it
+ *                                      does for long sequences) also where the kernel matrix would fit on chip
  * Returns LOT_OK, or LOT_ERR_SHAPE for an unknown knob.
  */
 typedef enum {
@@ -304,7 +306,8 @@ typedef enum {
     LOT_KNOB_RESHIFT_BITS = 1,
     LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION = 2,
     LOT_KNOB_BWD_SWEEP_LAUNCHES = 3,
-    LOT_KNOB_COUNT_ = 4
+    LOT_KNOB_FWD_STREAMING = 4,
+    LOT_KNOB_COUNT_ = 5
 } lot_knob;
 int lot_debug_set(int knob, long long value);
 

@@ -69,6 +69,12 @@ bool assemble_by_iteration()
     return knob(LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION, &v) && v != 0;
 }
 
+bool forward_streaming_only()
+{
+    long long v;
+    return knob(LOT_KNOB_FWD_STREAMING, &v) && v != 0;
+}
+
 bool sweep_by_launches()
 {
     long long v;

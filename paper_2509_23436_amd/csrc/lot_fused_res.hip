@@ -1,0 +1,61 @@
+// Instantiations of the fused kernel that keep the kernel matrix exp(C/eps) on chip between the
+// Sinkhorn iterations (queries' share in registers, keys' share in LDS; see lot_fused_kernel.h), and
+// their dispatch.  A variant is taken when no wavefront would own more than NT tiles of a side.
+#include "lot_fused_kernel.h"
+
+namespace lot {
+namespace {
+
+// Largest NT per variant: what the register file (queries) and the LDS (keys) hold.  bf16 I/O keeps the
+// matrix as bf16 pairs: 8 RB registers per tile; fp32 I/O as fp32: 16 RB registers per tile, and its
+// pivot pieces already take up to 24 KB of LDS.
+template <typename IO, int D, int RB, int WAVES>
+int launch_resident(const Args& a)
+{
+    int rc = launch<IO, D, RB, WAVES, 1>(a, true);
+    if (rc != LOT_ERR_PATH) return rc;
+    if constexpr (!io_is_f32<IO>::value || RB == 1) {
+        rc = launch<IO, D, RB, WAVES, 2>(a, true);
+        if (rc != LOT_ERR_PATH) return rc;
+    }
+    if constexpr (!io_is_f32<IO>::value) {
+        rc = launch<IO, D, RB, WAVES, 4>(a, true);
+    }
+    return rc;
+}
+
+// workgroup size as for the streaming variants (lot_fused.hip)
+template <typename IO, int D, int RB>
+int launch_resident_sized(const Args& a)
+{
+    int dev = 0, cus = 0;
+    LOT_HIP_CHECK(hipGetDevice(&dev));
+    LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if constexpr (io_is_f32<IO>::value && D == 64 && RB == 2) {
+        return launch_resident<IO, D, RB, 8>(a);
+    } else {
+        if (a.s.B * a.s.H <= cus) return launch_resident<IO, D, RB, 8>(a);
+        return launch_resident<IO, D, RB, 4>(a);
+    }
+}
+
+template <typename IO>
+int dispatch_resident(const Args& a)
+{
+    const int d = a.s.d_k, rb = a.s.r <= 32 ? 1 : 2;
+    if (d == 32 && rb == 1) return launch_resident_sized<IO, 32, 1>(a);
+    if (d == 32 && rb == 2) return launch_resident_sized<IO, 32, 2>(a);
+    if (d == 64 && rb == 1) return launch_resident_sized<IO, 64, 1>(a);
+    if (d == 64 && rb == 2) return launch_resident_sized<IO, 64, 2>(a);
+    return LOT_ERR_PATH;
+}
+
+}  // namespace
+
+int run_fused_resident(const Args& a)
+{
+    if (!fused_supports(a.s) || a.mass_q != nullptr || a.mass_k != nullptr) return LOT_ERR_PATH;
+    return a.s.io_dtype == LOT_BF16 ? dispatch_resident<uint16_t>(a) : dispatch_resident<float>(a);
+}
+
+}  // namespace lot

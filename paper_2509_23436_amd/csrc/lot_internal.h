@@ -228,6 +228,7 @@ int run_cross_reference(const CrossArgs& a);
 // Each returns LOT_OK or LOT_ERR_HIP (the failing hipError_t is left in last_hip_error()).
 int run_reference(const Args& a, bool want_out);
 int run_fused(const Args& a, bool want_out);
+int run_fused_resident(const Args& a);   // attention, uniform masses; LOT_ERR_PATH where the kernel matrix does not fit on chip
 int run_backward(const BwdArgs& a);
 int run_backward_tiled(const BwdArgs& a);
 // out[b][h][0][:] = softmax_j(beta_cls <q_0, k_j>) V, j over all n tokens of the problem
@@ -264,6 +265,10 @@ bool assemble_by_iteration();
 // lot_debug_set(LOT_KNOB_SPIN_LIMIT, v) replaces it: a testing aid -- with 0 every wait gives up at
 // once, the kernels end early and the call is reported by lot_workspace_status.
 uint32_t spin_limit();
+
+// Testing aid (LOT_KNOB_FWD_STREAMING): the fused forward never keeps the kernel matrix on chip, so that
+// the variants that re-read Q and K in every pass (what long sequences run) are exercised on short ones.
+bool forward_streaming_only();
 
 // Testing aid (LOT_KNOB_BWD_SWEEP_LAUNCHES): run the tiled backward's forward sweep as one launch per
 // pass although the persistent form would fit.
