@@ -412,21 +412,6 @@ __device__ __forceinline__ void res_from_lds(uint32_t (&w)[NW], const u32x4* src
     }
 }
 
-// maximum over the 64 lanes of a wavefront, in every lane (all lanes active)
-__device__ __forceinline__ float wave_max64(float x)
-{
-    x = fmaxf(x, dpp_move<0xB1>(x));    // quad_perm [1,0,3,2]
-    x = fmaxf(x, dpp_move<0x4E>(x));    // quad_perm [2,3,0,1]
-    x = fmaxf(x, dpp_move<0x141>(x));   // row_half_mirror
-    x = fmaxf(x, dpp_move<0x140>(x));   // row_mirror: every lane of a row of 16 holds the row's maximum
-    const int xi = __builtin_bit_cast(int, x);
-    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0));
-    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16));
-    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 32));
-    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 48));
-    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
-}
-
 // Request the rows of this wavefront's first tile of `side` (what a streaming pass expects in xfirst).
 template <typename IO, int D>
 __device__ __forceinline__ void request_first_tile(const FusedParams& p, const IO* X, Frag<IO, D>& xfirst,
@@ -937,12 +922,15 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 // (sums exchanged in fixed point: one below the resolution reads as half a unit)
                 const float c = fmaxf(tot, p.cluster > 1 ? 0.5f * p.fx_unscale : 1.0e-37f);
                 const float b = s_beta[ln];
+                // (hardware reciprocal and base-2 logarithm, each good to one unit in the last place: this
+                // runs on one wavefront while the others wait for the potentials)
+                const float cinv = rcp_fast(c);
                 if (!final) {
-                    s_g[side][ln] += p.eps * logf((float)opaque_scalar(p.n_side[side]) * b / c);
+                    s_g[side][ln] += (p.eps * kLn2) * __builtin_amdgcn_logf((float)opaque_scalar(p.n_side[side]) * b * cinv);
                 } else {
                     // the last pass's potentials stay: the epilogue rebuilds its coupling from them
-                    s_rho[side][ln] = b / c;
-                    if (side == 0) s_csinv[ln] = 1.f / c;
+                    s_rho[side][ln] = b * cinv;
+                    if (side == 0) s_csinv[ln] = cinv;
                 }
             } else if (final) {
                 s_rho[side][ln] = 0.f;
@@ -951,12 +939,17 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             if constexpr (NT > 0) {
                 if (!final) {
                     // how far the potentials have moved from those folded into the kept kernel matrix
+                    // Any common shift will do for v as long as nothing leaves the fp32 range: that of
+                    // pivot 0.  As long as every pivot stays within kDriftLimit / 2 binary orders of it, the
+                    // spread is within kDriftLimit; otherwise (or when something is not finite) the next pass
+                    // of this side recomputes the kernel matrix.
                     const bool lv = ln < rr;
-                    const float d = lv ? (s_g[side][ln] - s_gref[side][ln]) * c1 : 0.f;
-                    const float dmax = wave_max64(lv ? d : -INFINITY);
-                    const float dmin = -wave_max64(lv ? -d : -INFINITY);
-                    s_v[side][ln] = lv ? exp2_fast(d - dmax) : 0.f;
-                    if (ln == 0) s_fill[side] = (dmax - dmin <= kDriftLimit) ? 0 : 1;   // (also when not finite)
+                    const float d = (s_g[side][ln] - s_gref[side][ln]) * c1;
+                    const float d0 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, d)));
+                    const float rel = d - d0;
+                    s_v[side][ln] = lv ? exp2_fast(rel) : 0.f;
+                    const bool any_far = __any(lv && !(fabsf(rel) <= 0.5f * kDriftLimit));   // (all 64 lanes take part)
+                    if (ln == 0) s_fill[side] = any_far ? 1 : 0;
                 }
             }
             return ok;

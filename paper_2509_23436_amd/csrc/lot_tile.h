@@ -28,6 +28,7 @@ template <typename T> __device__ __forceinline__ LOT_GLOBAL T* as_global(T* p) {
 constexpr float kNegBig = -1.0e30f;   // potential of a padding pivot: its exponential is exactly 0
 constexpr int kTrStride = 40;         // uint16 per row of the transposed coupling tile (32 + 8 pad)
 constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kLn2 = 0.69314718055994530942f;
 
 // ---------------------------------------------------------------------------------------------
 // small device helpers
