@@ -297,8 +297,13 @@ int lot_status_words(const unsigned long long* host_words);
  *   LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION non-zero: every workgroup through the iteration-by-iteration kernel
  *   LOT_KNOB_BWD_SWEEP_LAUNCHES        non-zero: the backward's forward sweep as one launch per pass
  *                                      (its form on a device that cannot hold the whole grid at once)
- *   LOT_KNOB_FWD_STREAMING             non-zero: the fused forward re-reads Q and K in every pass (what it
- *                                      does for long sequences) also where the kernel matrix would fit on chip
+ *   LOT_KNOB_FWD_STREAMING             1: the fused forward re-reads Q and K in every pass (what it does for
+ *                                      long sequences) also where the kernel matrix would fit on chip;
+ *                                      2: short sequences on the workgroup-level kept-matrix kernels instead
+ *                                      of the wavefront-per-side kernel
+ *   LOT_KNOB_FWD_DRIFT_LIMIT           0..32: the forward kernels that keep exp(C/eps) on chip recompute it once
+ *                                      the potentials have spread over more than this many binary orders
+ *                                      (default 32; 0: in every iteration)
  * Returns LOT_OK, or LOT_ERR_SHAPE for an unknown knob.
  */
 typedef enum {
@@ -307,7 +312,8 @@ typedef enum {
     LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION = 2,
     LOT_KNOB_BWD_SWEEP_LAUNCHES = 3,
     LOT_KNOB_FWD_STREAMING = 4,
-    LOT_KNOB_COUNT_ = 5
+    LOT_KNOB_FWD_DRIFT_LIMIT = 5,
+    LOT_KNOB_COUNT_ = 6
 } lot_knob;
 int lot_debug_set(int knob, long long value);
 

@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libLOT.so")
-SOURCES = ["lot_api.hip", "lot_ref.hip", "lot_fused.hip", "lot_fused_res.hip", "lot_bwd.hip", "lot_bwd_tiled.hip", "lot_cross.hip", "lot_grouped.hip", "lot_bwd_grouped.hip"]
+SOURCES = ["lot_api.hip", "lot_ref.hip", "lot_fused.hip", "lot_fused_res.hip", "lot_wave.hip", "lot_bwd.hip", "lot_bwd_tiled.hip", "lot_cross.hip", "lot_grouped.hip", "lot_bwd_grouped.hip"]
 # packed-fp32 code generation is switched off on purpose (see the design notes)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -69,10 +69,17 @@ bool assemble_by_iteration()
     return knob(LOT_KNOB_BWD_ASSEMBLE_BY_ITERATION, &v) && v != 0;
 }
 
-bool forward_streaming_only()
+int forward_variants()
 {
     long long v;
-    return knob(LOT_KNOB_FWD_STREAMING, &v) && v != 0;
+    return knob(LOT_KNOB_FWD_STREAMING, &v) && (v == 1 || v == 2) ? (int)v : 0;
+}
+
+float drift_limit()
+{
+    long long v;
+    if (knob(LOT_KNOB_FWD_DRIFT_LIMIT, &v) && v >= 0 && v <= 32) return (float)v;
+    return 32.f;
 }
 
 bool sweep_by_launches()

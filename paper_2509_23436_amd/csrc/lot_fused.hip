@@ -67,7 +67,12 @@ int run_fused(const Args& a, bool want_out)
 {
     if (!fused_supports(a.s)) return LOT_ERR_PATH;
     // the variants that keep the kernel matrix on chip, where a workgroup's share of it fits
-    if (want_out && a.mass_q == nullptr && a.mass_k == nullptr && !forward_streaming_only()) {
+    if (want_out && a.mass_q == nullptr && a.mass_k == nullptr && forward_variants() != 1) {
+        // short sequences: a wavefront per side, the whole kernel matrix in its registers
+        if (forward_variants() != 2) {
+            const int rc = run_wave(a);
+            if (rc != LOT_ERR_PATH) return rc;
+        }
         const int rc = run_fused_resident(a);
         if (rc != LOT_ERR_PATH) return rc;
     }

@@ -51,6 +51,7 @@ struct FusedParams {
     float eps;
     float fx_scale, fx_unscale;   // 2^F and 2^-F of the fixed-point column sums
     uint32_t spin_limit;
+    float drift_half;            // NT > 0: a pivot's potential may move this many binary orders away from pivot 0's before the kernel matrix is recomputed
     unsigned long long* trace;   // LOT_TRACE builds only
 };
 
@@ -334,16 +335,13 @@ __device__ __forceinline__ void run_pass(
 //     v_t = exp((g_t - gref_t)/eps - shift),  s_i = sum_t Kt_it v_t,  colsum_t = v_t sum_i Kt_it / s_i
 // which are the same row-normalised couplings and column sums as a pass that recomputes everything
 // (the shift and the row factors cancel).  The potentials may drift from gref by at most kDriftLimit
-// binary orders between the largest and the smallest change; beyond that (extreme eps) the next pass of
+// binary orders between the largest and the smallest change (lot_debug_set can lower that for tests); beyond that (extreme eps) the next pass of
 // that side is a fill again, with the current potentials folded in, so the result never depends on
 // products that underflow.  With bf16 I/O the kept matrix is bf16 (pairs in one register): it meets the
 // bf16 operands of the matrix instructions in the two contractions anyway, and a relative 2^-9 on a
 // kernel entry is a change of eps 2^-9 in a similarity, below the rounding of the bf16 Q and K
 // themselves; with fp32 I/O it is kept in fp32.
-#ifndef LOT_DRIFT_LIMIT
-#define LOT_DRIFT_LIMIT 32.f
-#endif
-constexpr float kDriftLimit = LOT_DRIFT_LIMIT;
+constexpr float kDriftLimit = 32.f;
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 template <typename IO> struct res_packed { static constexpr bool value = !io_is_f32<IO>::value; };
@@ -455,7 +453,8 @@ __device__ __forceinline__ void fill_pass(
         return;
     }
     Frag<IO, D> xc = xfirst;
-#pragma unroll(TO_LDS ? 1 : NT)
+    constexpr int kUnrollSlots = TO_LDS ? 1 : NT;   // unrolled only where the slot picks registers
+#pragma unroll kUnrollSlots
     for (int slot = 0; slot < NT; ++slot) {
         const int tile = tile_begin + wave + slot * WAVES;
         if (tile < tile_end) {
@@ -520,7 +519,8 @@ __device__ __forceinline__ void cheap_pass(
 #pragma unroll
             for (int j = 0; j < 16; ++j) v[mb][j] = 1.f;
     }
-#pragma unroll(FROM_LDS ? 1 : NT)
+    constexpr int kUnrollSlots = FROM_LDS ? 1 : NT;   // unrolled only where the slot picks registers
+#pragma unroll kUnrollSlots
     for (int slot = 0; slot < NT; ++slot) {
         const int tile = tile_begin + wave + slot * WAVES;
         if (tile < tile_end) {
@@ -948,7 +948,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     const float d0 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, d)));
                     const float rel = d - d0;
                     s_v[side][ln] = lv ? exp2_fast(rel) : 0.f;
-                    const bool any_far = __any(lv && !(fabsf(rel) <= 0.5f * kDriftLimit));   // (all 64 lanes take part)
+                    const bool any_far = __any(lv && !(fabsf(rel) <= p.drift_half));   // (all 64 lanes take part)
                     if (ln == 0) s_fill[side] = any_far ? 1 : 0;
                 }
             }
@@ -1375,6 +1375,7 @@ int launch(const Args& a, bool want_out)
     p.num_items = G * cluster; p.iters = a.iters; p.mode = want_out ? MODE_ATTENTION : MODE_COUPLINGS;
     p.eps = a.eps;
     p.spin_limit = spin_limit();
+    p.drift_half = 0.5f * drift_limit();
 #ifdef LOT_TRACE
     // developer builds: 128 stamps of 8 bytes per workgroup right behind the fused kernel's regions (the
     // caller of such a build allocates 8 MiB more than lot_workspace_bytes says)

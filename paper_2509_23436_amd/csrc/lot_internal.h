@@ -228,6 +228,7 @@ int run_cross_reference(const CrossArgs& a);
 // Each returns LOT_OK or LOT_ERR_HIP (the failing hipError_t is left in last_hip_error()).
 int run_reference(const Args& a, bool want_out);
 int run_fused(const Args& a, bool want_out);
+int run_wave(const Args& a);             // attention, uniform masses, each side within one wavefront's registers; else LOT_ERR_PATH
 int run_fused_resident(const Args& a);   // attention, uniform masses; LOT_ERR_PATH where the kernel matrix does not fit on chip
 int run_backward(const BwdArgs& a);
 int run_backward_tiled(const BwdArgs& a);
@@ -266,9 +267,15 @@ bool assemble_by_iteration();
 // once, the kernels end early and the call is reported by lot_workspace_status.
 uint32_t spin_limit();
 
-// Testing aid (LOT_KNOB_FWD_STREAMING): the fused forward never keeps the kernel matrix on chip, so that
-// the variants that re-read Q and K in every pass (what long sequences run) are exercised on short ones.
-bool forward_streaming_only();
+// Testing aid (LOT_KNOB_FWD_STREAMING): 1 = the fused forward never keeps the kernel matrix on chip, so that
+// the variants that re-read Q and K in every pass (what long sequences run) are exercised on short ones;
+// 2 = no wavefront-per-side kernel, so that the workgroup-level kept-matrix variants are; 0 = as shipped.
+int forward_variants();
+
+// The forward kernels that keep the kernel matrix on chip recompute it when the potentials have spread
+// over more than this many binary orders since it was computed (32).  Testing aid (LOT_KNOB_FWD_DRIFT_LIMIT):
+// a smaller value, down to 0 (recompute in every iteration), so that this path runs on ordinary inputs.
+float drift_limit();
 
 // Testing aid (LOT_KNOB_BWD_SWEEP_LAUNCHES): run the tiled backward's forward sweep as one launch per
 // pass although the persistent form would fit.

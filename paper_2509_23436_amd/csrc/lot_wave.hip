@@ -1,0 +1,466 @@
+// LOT attention forward for short sequences: one workgroup of two wavefronts per (batch, head) problem,
+// wavefront 0 the keys' solve, wavefront 1 the queries'.
+//
+// A side of at most 32 NT tokens has a kernel matrix exp(C/eps) of NT tiles of 32 tokens x 32 RB
+// pivots, which one wavefront can hold in its registers (bf16 pairs for bf16 I/O, fp32 for fp32 I/O;
+// one wavefront per SIMD, so the whole register file is its own).  The two Sinkhorn solves of a problem
+// are independent until the very end (paper, Method: the two entropic problems share only Z, beta and
+// eps), so each wavefront runs all T iterations of its side on its own, in the scaling form the paper
+// prints (Gamma = Diag(u) exp(C/eps) Diag(v)): per iteration one sweep over its registers
+//     s_i = sum_t Kt_it v_t,   colsum_t = v_t sum_i Kt_it / s_i,   g_t += eps log(n beta_t / colsum_t)
+// a reduction over the lanes (one pivot per lane afterwards), the pivot update in that layout, and the
+// new v handed back to the tile layout through 256 bytes of LDS.  No workgroup barrier, no global
+// memory and no exponential per element inside the iterations; Q and K are read once.  The last key
+// sweep also contracts with V (transposing its tiles through LDS, as the fused kernel does); the two
+// wavefronts meet once, after which the queries' wavefront expands O = n Gamma1 Diag(beta)^-1 (Gamma2 V).
+// As in the fused kernel's kept-matrix variants the potentials may drift from those folded into the
+// kept matrix by kDriftLimit / 2 binary orders per pivot before the matrix is recomputed.
+#include "lot_fused_kernel.h"
+
+namespace lot {
+namespace {
+
+struct WaveParams {
+    const void* Q; const void* K; const void* V;
+    const float* Z; const float* beta;
+    void* out;
+    int G, H, r, iters;
+    int n_side[2];        // 0 = keys and values, 1 = queries and the output
+    int stride_side[2];   // tokens between consecutive problems in memory
+    float eps;
+    float drift_half;     // a pivot's potential may move this many binary orders away from pivot 0's before the kernel matrix is recomputed
+};
+
+// pivot that lane (i, kg) holds after reduce_scatter_tokens<16 RB>
+template <int RB> __device__ __forceinline__ int reduced_pivot(int i, int kg)
+{
+    const int q = RB == 2 ? i : i >> 1;
+    return 32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3);
+}
+
+__device__ __forceinline__ void wave_sync_lds()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <typename IO, int D, int RB, int NT>
+__global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) lot_wave_kernel(WaveParams p)
+{
+    constexpr int NB = D / 32;
+    constexpr int NW = ResWords<IO, RB>::value;
+    constexpr bool kSplit = io_is_f32<IO>::value;
+    constexpr bool kPieces = io_is_f32<IO>::value;
+    __shared__ __attribute__((aligned(16))) float s_vec[2][64];       // per side: a per-pivot vector on its way into tile layout
+    __shared__ __attribute__((aligned(16))) float s_fac[64];          // keys: v_t / colsum_t, the factor of the rows of U
+    __shared__ __attribute__((aligned(16))) float s_qs[64];           // queries: n rho_t v_t
+    __shared__ __attribute__((aligned(16))) float s_u[64 * D];        // U, then Y'
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[2 * 32 * RB * kTrStride];   // keys: transposed tile (hi, lo)
+    __shared__ __attribute__((aligned(16))) bf16x8 s_yf[2][2 * RB * NB * 64];         // Y'' as MFMA operand fragments (hi, lo)
+    __shared__ __attribute__((aligned(16))) char s_zf[kPieces ? PieceStashBytes<D, RB>::value : 16];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int side = __builtin_amdgcn_readfirstlane(tid >> 6);       // 0: keys, 1: queries
+    const int i = lane & 31, kg = lane >> 5;
+    const int g = blockIdx.x, h = g % p.H;
+    const int r = p.r;
+    const int n = p.n_side[side], stride = p.stride_side[side];
+    const float c1 = kLog2e / p.eps;
+    const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.K : p.Q) + (size_t)g * stride * D;
+    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+
+    // ---- pivots
+    Frag<IO, D> zf[RB];
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb) {
+        const int t = 32 * mb + i;
+        load_pivots<D>(zf[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
+    }
+    // the first tile's rows
+    Frag<IO, D> xc;
+    load_tokens<D>(xc, X + (size_t)min(i, n - 1) * D, kg);
+    // this lane's pivot in the layout the column sums are reduced to
+    const int piv = reduced_pivot<RB>(i, kg);
+    const bool live = piv < r;
+    const float beta_l = as_global(p.beta)[(size_t)h * r + min(piv, r - 1)];
+    const float nbeta = (float)n * beta_l;
+    float g_l = 0.f, gref_l = 0.f;        // this pivot's potential, and the one folded into the kept matrix
+    if constexpr (kPieces) {
+        if (side == 0) stash_pivot_pieces<D, RB>(s_zf, zf, lane);
+        __syncthreads();
+    }
+
+    uint32_t kq[NT][NW];
+#pragma unroll
+    for (int sl = 0; sl < NT; ++sl)
+#pragma unroll
+        for (int q = 0; q < NW; ++q) kq[sl][q] = 0u;
+
+    // ---- the kernel matrix with the current potentials folded in (zero at first; -big for padding pivots).
+    //      A single wavefront per SIMD has nobody to switch to while it waits for memory, so the rows of
+    //      kAhead tiles are kept in flight.
+    constexpr int kAhead = NT < 4 ? NT : 4;
+    auto fill = [&](bool first) __attribute__((always_inline)) {
+        f32x16 gv[RB];
+        s_vec[side][piv] = live ? g_l : kNegBig;
+        wave_sync_lds();
+        load_pivot_vector<RB>(gv, s_vec[side], kg);
+        wave_sync_lds();
+        // (addresses are formed from a lane index that the compiler cannot see through: hoisted out of the
+        // iteration loop, the addresses of all slots would be hundreds of live registers)
+        int io = i;
+        asm volatile("" : "+v"(io));
+        Frag<IO, D> xs[kAhead];
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            if (a == 0 && first) xs[0] = xc;      // (requested before the pivots were loaded)
+            else if (a < ntiles) load_tokens<D>(xs[a], X + (size_t)min(a * kTileTokens + io, n - 1) * D, kg);
+        }
+#pragma unroll
+        for (int slot = 0; slot < NT; ++slot) {
+            if (slot < ntiles) {
+                f32x16 acc[RB];
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb) acc[mb] = gv[mb];
+                if constexpr (kPieces) similarity_pieces<D, RB>(acc, s_zf, xs[slot % kAhead], lane, 0);
+                else similarity<D, RB>(acc, zf, xs[slot % kAhead]);
+                if (slot + kAhead < NT) {
+                    if (slot + kAhead < ntiles)
+                        load_tokens<D>(xs[slot % kAhead], X + (size_t)min((slot + kAhead) * kTileTokens + io, n - 1) * D, kg);
+                }
+                float m0 = acc[0][0], m1 = acc[0][1], m2 = acc[0][2], m3 = acc[0][3];
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = (mb == 0 ? 4 : 0); j < 16; j += 4) {
+                        m0 = fmaxf(m0, acc[mb][j]);
+                        m1 = fmaxf(m1, acc[mb][j + 1]);
+                        m2 = fmaxf(m2, acc[mb][j + 2]);
+                        m3 = fmaxf(m3, acc[mb][j + 3]);
+                    }
+                const float mc = pair_max(fmaxf(fmaxf(m0, m1), fmaxf(m2, m3))) * c1;
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) acc[mb][j] = exp2_fast(fmaf(acc[mb][j], c1, -mc));
+                res_pack<IO, RB>(kq[slot], acc);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // (slots are not interleaved: that would only cost registers)
+        }
+        gref_l = g_l;
+    };
+
+    f32x16 vC[RB];                       // v in tile layout
+    float v_l = 1.f;                     // this lane's pivot's v
+    float rho_l = 0.f;                   // after the last iteration: beta_t / colsum_t (queries), 1 / colsum_t (keys)
+
+    // one sweep over the kept matrix: column sums of Kt_it / s_i (the factor v_t is applied afterwards)
+    auto sweep = [&](f32x16 (&cs)[RB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) cs[mb][j] = 0.f;
+#pragma unroll
+        for (int slot = 0; slot < NT; ++slot) {
+            if (slot < ntiles) {
+                f32x16 k[RB];
+                res_unpack<IO, RB>(k, kq[slot]);
+                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; j += 4) {
+                        s0 = fmaf(k[mb][j], vC[mb][j], s0);
+                        s1 = fmaf(k[mb][j + 1], vC[mb][j + 1], s1);
+                        s2 = fmaf(k[mb][j + 2], vC[mb][j + 2], s2);
+                        s3 = fmaf(k[mb][j + 3], vC[mb][j + 3], s3);
+                    }
+                const float s = pair_sum((s0 + s1) + (s2 + s3));
+                const float w = slot * kTileTokens + i < n ? rcp_fast(s) : 0.f;
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) cs[mb][j] = fmaf(k[mb][j], w, cs[mb][j]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // the same sweep for the keys' last iteration: also U = sum_j (Kt_jt / s_j) V_j
+    f32x16 U[RB][NB];
+    auto sweep_with_values = [&](f32x16 (&cs)[RB]) __attribute__((always_inline)) {
+        const IO* V = reinterpret_cast<const IO*>(p.V);
+        uint16_t* tr_hi = s_tr;
+        uint16_t* tr_lo = s_tr + 32 * RB * kTrStride;
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) cs[mb][j] = 0.f;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
+        }
+        constexpr int kVAhead = NT < 2 ? NT : 2;
+        bf16x8 vhs[kVAhead][2][NB], vls[kVAhead][2][NB];
+        int kgo = kg;
+        asm volatile("" : "+v"(kgo));       // (opaque, as in the fill: keeps the addresses inside the loop)
+        auto request_values = [&](int slot, bf16x8 (&vh)[2][NB], bf16x8 (&vl)[2][NB]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const int t0 = slot * kTileTokens + 16 * s2 + 8 * kgo;
+                const int left = max(1, min(8, n - t0));
+                load_values<D>(vh[s2], vl[s2], V, (size_t)g * stride + min(t0, n - 1), left, i);
+            }
+        };
+#pragma unroll
+        for (int a = 0; a < kVAhead; ++a)
+            if (a < ntiles) request_values(a, vhs[a], vls[a]);
+#pragma unroll
+        for (int slot = 0; slot < NT; ++slot) {
+            if (slot < ntiles) {
+                bf16x8 vh[2][NB], vl[2][NB];
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) { vh[s2][nb] = vhs[slot % kVAhead][s2][nb]; vl[s2][nb] = vls[slot % kVAhead][s2][nb]; }
+                if (slot + kVAhead < NT) {
+                    if (slot + kVAhead < ntiles) request_values(slot + kVAhead, vhs[slot % kVAhead], vls[slot % kVAhead]);
+                }
+                f32x16 k[RB];
+                res_unpack<IO, RB>(k, kq[slot]);
+                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; j += 4) {
+                        s0 = fmaf(k[mb][j], vC[mb][j], s0);
+                        s1 = fmaf(k[mb][j + 1], vC[mb][j + 1], s1);
+                        s2 = fmaf(k[mb][j + 2], vC[mb][j + 2], s2);
+                        s3 = fmaf(k[mb][j + 3], vC[mb][j + 3], s3);
+                    }
+                const float s = pair_sum((s0 + s1) + (s2 + s3));
+                const float w = slot * kTileTokens + i < n ? rcp_fast(s) : 0.f;
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const float x = k[mb][j] * w;
+                        cs[mb][j] += x;
+                        const __bf16 hh = (__bf16)x;
+                        const int pv = pivot_of(mb, j, kg);
+                        tr_hi[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, hh);
+                        if (kSplit) tr_lo[pv * kTrStride + i] = __builtin_bit_cast(uint16_t, (__bf16)(x - (float)hh));
+                    }
+                wave_sync_lds();
+#pragma unroll
+                for (int s2i = 0; s2i < 2; ++s2i) {
+#pragma unroll
+                    for (int mb = 0; mb < RB; ++mb) {
+                        const bf16x8 ah = *reinterpret_cast<const bf16x8*>(tr_hi + (32 * mb + i) * kTrStride + 16 * s2i + 8 * kg);
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vh[s2i][nb], U[mb][nb], 0, 0, 0);
+                        if (kSplit) {
+                            const bf16x8 al = *reinterpret_cast<const bf16x8*>(tr_lo + (32 * mb + i) * kTrStride + 16 * s2i + 8 * kg);
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb) {
+                                U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, vh[s2i][nb], U[mb][nb], 0, 0, 0);
+                                U[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, vl[s2i][nb], U[mb][nb], 0, 0, 0);
+                            }
+                        }
+                    }
+                }
+                wave_sync_lds();
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- the iterations of this side.  The kept matrix is written only at the top of the outer loop (once,
+    //      unless the potentials drift too far from those folded into it); the inner loop only reads it.
+    int it = 1;
+    bool first = true;
+    while (it <= p.iters) {
+        fill(first);
+        first = false;
+        v_l = live ? 1.f : 0.f;
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) vC[mb][j] = 1.f;     // (padding pivots hold zeros in the kept matrix)
+        bool refill = false;
+        for (; it <= p.iters && !refill; ++it) {
+            f32x16 cs[RB];
+            const bool last = it == p.iters;
+            if (last && side == 0) sweep_with_values(cs);
+            else sweep(cs);
+            float c[16 * RB];
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) c[16 * mb + j] = cs[mb][j];
+            const float tot = reduce_scatter_tokens<16 * RB>(c, i);
+            const float colsum = fmaxf(tot * v_l, 1.0e-37f);
+            const float cinv = rcp_fast(colsum);
+            if (!last) {
+                g_l += (p.eps * kLn2) * __builtin_amdgcn_logf(nbeta * cinv);
+                // v for the next sweep, shifted by pivot 0's change (lane 0 holds pivot 0)
+                const float d = (g_l - gref_l) * c1;
+                const float d0 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, d)));
+                const float rel = d - d0;
+                refill = __any(live && !(fabsf(rel) <= p.drift_half));   // the potentials go into the kept matrix
+                v_l = live ? exp2_fast(rel) : 0.f;
+                s_vec[side][piv] = v_l;
+                wave_sync_lds();
+                load_pivot_vector<RB>(vC, s_vec[side], kg);
+                wave_sync_lds();
+            } else {
+                rho_l = side == 0 ? cinv : beta_l * cinv;
+            }
+        }
+    }
+
+    // ---- the two sides meet
+    if (side == 0) {
+        // Y'_t = v_t U_t / colsum_t: rows of U scaled per pivot, into LDS as [pivot][D]
+        s_fac[piv] = live ? v_l * rho_l : 0.f;
+        wave_sync_lds();
+        f32x16 fac[RB];
+        load_pivot_vector<RB>(fac, s_fac, kg);
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) s_u[pivot_of(mb, j, kg) * D + NB * i + nb] = U[mb][nb][j] * fac[mb][j];
+    } else {
+        s_qs[piv] = live ? (float)n * rho_l * v_l : 0.f;      // n rho1_t, and the v_t the expansion leaves out
+    }
+    __syncthreads();
+    if (side == 0) return;
+
+    // ---- queries: Y''_t = n rho1_t v_t Y'_t as MFMA operand fragments (hi + lo), then O = sum_t (Kt_it / s_i) Y''_t
+    bf16x8* yf_hi = s_yf[0];
+    bf16x8* yf_lo = s_yf[1];
+    for (int f = lane; f < 2 * RB * NB * 64; f += 64) {
+        const int fl = f & 63, fi = fl & 31, fkg = fl >> 5;
+        const int snb = f >> 6, s = snb / NB, nb = snb % NB;
+        f32x8 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int pv = 32 * (s >> 1) + 16 * (s & 1) + 8 * (e >> 2) + 4 * fkg + (e & 3);
+            t[e] = s_u[pv * D + NB * fi + nb] * s_qs[pv];
+        }
+        bf16x8 hi, lo;
+        split_bf16(t, hi, lo);
+        yf_hi[f] = hi;
+        yf_lo[f] = lo;
+    }
+    wave_sync_lds();
+    IO* const out = reinterpret_cast<IO*>(p.out);
+#pragma unroll
+    for (int slot = 0; slot < NT; ++slot) {
+        if (slot < ntiles) {
+            f32x16 k[RB];
+            res_unpack<IO, RB>(k, kq[slot]);
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; j += 4) {
+                    s0 = fmaf(k[mb][j], vC[mb][j], s0);
+                    s1 = fmaf(k[mb][j + 1], vC[mb][j + 1], s1);
+                    s2 = fmaf(k[mb][j + 2], vC[mb][j + 2], s2);
+                    s3 = fmaf(k[mb][j + 3], vC[mb][j + 3], s3);
+                }
+            const float w = rcp_fast(pair_sum((s0 + s1) + (s2 + s3)));
+            f32x16 oacc[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) oacc[nb][j] = 0.f;
+#pragma unroll
+            for (int st = 0; st < 2 * RB; ++st) {
+                f32x8 wv;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wv[e] = k[st >> 1][8 * (st & 1) + e] * w;
+                bf16x8 ah, al;
+                if (kSplit) split_bf16(wv, ah, al);
+                else ah = __builtin_convertvector(wv, bf16x8);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const bf16x8 yh = yf_hi[(st * NB + nb) * 64 + lane];
+                    oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, yh, oacc[nb], 0, 0, 0);
+                    if (kSplit) {
+                        const bf16x8 yl = yf_lo[(st * NB + nb) * 64 + lane];
+                        oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, yh, oacc[nb], 0, 0, 0);
+                        oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, yl, oacc[nb], 0, 0, 0);
+                    }
+                }
+            }
+            const int row0 = slot * kTileTokens + 4 * kg;
+            IO* const lane_base = out + ((size_t)g * stride + row0) * D;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (row0 + 8 * (j >> 2) + (j & 3) < n)
+                    store_out<NB>(lane_base + (8 * (j >> 2) + (j & 3)) * D, i, oacc[0][j], oacc[NB - 1][j]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <typename IO, int D, int RB, int NT>
+int launch_wave(const Args& a)
+{
+    const lot_shape& s = a.s;
+    WaveParams p{};
+    p.Q = a.Q; p.K = a.K; p.V = a.V; p.Z = a.Z; p.beta = a.beta; p.out = a.out;
+    p.G = s.B * s.H; p.H = s.H; p.r = s.r; p.iters = a.iters; p.eps = a.eps;
+    p.n_side[0] = a.n_k > 0 ? a.n_k : s.n;
+    p.n_side[1] = a.n_q > 0 ? a.n_q : s.n;
+    for (int sd = 0; sd < 2; ++sd) p.stride_side[sd] = a.n_stride > 0 ? a.n_stride : p.n_side[sd];
+    p.drift_half = 0.5f * drift_limit();
+    lot_wave_kernel<IO, D, RB, NT><<<dim3((unsigned)p.G), dim3(128), 0, a.stream>>>(p);
+    LOT_HIP_CHECK(hipGetLastError());
+    return LOT_OK;
+}
+
+// the smallest NT of the compiled set {2, 4, 8, 16} that holds `tiles`, within what the registers take
+// (NT times the words per tile at most 128)
+template <typename IO, int D, int RB>
+int launch_wave_sized(const Args& a, int tiles)
+{
+    constexpr int kMaxNT = 128 / ResWords<IO, RB>::value;
+    if (tiles <= 2) return launch_wave<IO, D, RB, 2>(a);
+    if constexpr (kMaxNT >= 4) { if (tiles <= 4) return launch_wave<IO, D, RB, 4>(a); }
+    if constexpr (kMaxNT >= 8) { if (tiles <= 8) return launch_wave<IO, D, RB, 8>(a); }
+    if constexpr (kMaxNT >= 16) { if (tiles <= 16) return launch_wave<IO, D, RB, 16>(a); }
+    return LOT_ERR_PATH;
+}
+
+template <typename IO>
+int dispatch_wave(const Args& a, int tiles)
+{
+    const int d = a.s.d_k, rb = a.s.r <= 32 ? 1 : 2;
+    if (d == 32 && rb == 1) return launch_wave_sized<IO, 32, 1>(a, tiles);
+    if (d == 32 && rb == 2) return launch_wave_sized<IO, 32, 2>(a, tiles);
+    if (d == 64 && rb == 1) return launch_wave_sized<IO, 64, 1>(a, tiles);
+    if (d == 64 && rb == 2) return launch_wave_sized<IO, 64, 2>(a, tiles);
+    return LOT_ERR_PATH;
+}
+
+}  // namespace
+
+// Attention with uniform token masses where each side fits one wavefront's registers; LOT_ERR_PATH otherwise.
+int run_wave(const Args& a)
+{
+    if (!fused_supports(a.s) || a.mass_q != nullptr || a.mass_k != nullptr || a.out == nullptr) return LOT_ERR_PATH;
+    const int n_k = a.n_k > 0 ? a.n_k : a.s.n, n_q = a.n_q > 0 ? a.n_q : a.s.n;
+    const int longer = n_k > n_q ? n_k : n_q;
+    const int tiles = (longer + kTileTokens - 1) / kTileTokens;
+    return a.s.io_dtype == LOT_BF16 ? dispatch_wave<uint16_t>(a, tiles) : dispatch_wave<float>(a, tiles);
+}
+
+}  // namespace lot

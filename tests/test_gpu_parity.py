@@ -142,6 +142,48 @@ def test_bf16_io_with_an_unrounded_fp32_z_matches_oracle(name):
         assert err <= 2e-2
 
 
+# The fused path has three families of kernels and AUTO / FUSED pick by size: a wavefront per side with
+# the whole kernel matrix exp(C/eps) in its registers (short sequences), workgroups that keep their share
+# of it on chip (registers + LDS), and the streaming kernel that recomputes it in every pass (long
+# sequences).  The cases above run whatever is picked; here every family is made to run every case it
+# supports (testing knobs of the library), and the kept-matrix kernels also with the limit on the drift of
+# the potentials set to zero, which makes them recompute the matrix in every iteration (the path that
+# extreme eps takes).
+VARIANTS = {
+    "streaming": {"KNOB_FWD_STREAMING": 1},
+    "workgroup_kept": {"KNOB_FWD_STREAMING": 2},
+    "workgroup_kept_refilled": {"KNOB_FWD_STREAMING": 2, "KNOB_FWD_DRIFT_LIMIT": 0},
+    "wave_refilled": {"KNOB_FWD_DRIFT_LIMIT": 0},
+    "wave_some_refills": {"KNOB_FWD_DRIFT_LIMIT": 2},
+}
+VARIANT_CASES = ["tiny", "deit_tiny", "bert_base_b4", "swin_t_s1_b2", "long_4k_h2", "ragged_f32", "ragged_bf16",
+                 "one_token", "n31_r1", "n33_r64_bf16", "f32_d64_r64", "bf16_d32_r8", "eps_small", "eps_large",
+                 "many_tiles_bf16", "two_rounds_f32"]
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("name", VARIANT_CASES)
+def test_every_family_of_forward_kernels_matches_oracle(name, variant, knobs):
+    import torch
+    from paper_2509_23436_amd import lot
+    w = CASES[name]
+    _say("case %s on %s: %r" % (name, variant, w))
+    x, O_ref, _, _ = _oracle_case(name)
+    dev = to_device(x, w.dtype)
+    for knob, value in VARIANTS[variant].items():
+        lot.lot_debug_set(getattr(lot, knob), value)
+    outs = []
+    for _ in range(2):
+        out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, path=lot.PATH_FUSED)
+        torch.cuda.synchronize()
+        outs.append(out)
+    err = rel_max_err(to_host_f64(outs[0]), O_ref)
+    _say("  max-norm rel err %.3e (bar %.0e)" % (err, tolerance(w.dtype)[0]))
+    assert err <= tolerance(w.dtype)[0]
+    view = torch.int16 if w.dtype == "bf16" else torch.int32
+    assert torch.equal(outs[0].view(view), outs[1].view(view))          # bit-reproducible
+
+
 @pytest.mark.parametrize("path_name", ["reference", "fused"])
 def test_runs_are_bit_identical(path_name):
     import torch
