@@ -1074,6 +1074,41 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             return s_okx[side] != 0;
         };
 
+        // ---- cluster-wide sum of U: once every workgroup of the cluster has posted its share, each sums
+        //      one slice of them (raw, still unnormalised) and publishes it.  False if a wait gave up.
+        float* yt = p.y_tile + (size_t)g * 64 * D;
+        auto reduce_u_slice = [&]() __attribute__((always_inline)) -> bool {
+            __builtin_amdgcn_s_setprio(3);
+            if (tid == 0) {
+                const bool ok = spin_until(p.arrive + g, (uint32_t)p.cluster, p.status, p.nonce, p.spin_limit);
+                if (!ok) give_up(p.status, p.nonce);
+                s_ok = ok;
+            }
+            lds_barrier();
+            if (!s_ok) return false;
+            const int per = (64 * D + p.cluster - 1) / p.cluster;
+            const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
+            const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
+            const __amdgpu_buffer_rsrc_t upv = coherent_view(up);
+            for (int e = e0 + wave * 64 + fresh_lane(); e < e1; e += kThreads) {
+                float acc = 0.f;
+                // (sixteen loads in flight at a time: every batch is one round trip to memory)
+                for (int k0 = 0; k0 < p.cluster; k0 += 16) {
+                    float v[16];
+#pragma unroll
+                    for (int j = 0; j < 16; ++j)
+                        v[j] = ldc_f32(upv, (uint32_t)(((size_t)min(k0 + j, p.cluster - 1) * 64 * D + e) * 4));
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) acc += (k0 + j < p.cluster) ? v[j] : 0.f;
+                }
+                st_coherent(yt + e, acc);
+            }
+            publish_barrier();   // the slice has been acknowledged
+            if (tid == 0) __hip_atomic_fetch_add(p.yready + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_setprio(0);
+            return true;
+        };
+
         bool unit_k = false, unit_q = false;   // NT > 0: the last pass of that side refilled the kernel matrix (v = 1)
         uint32_t kq[kKept ? NT : 1][NW];
         if constexpr (NT > 0) {
@@ -1167,38 +1202,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             }
         }
         }
-        float* yt = p.y_tile + (size_t)g * 64 * D;
         if (attention && p.cluster > 1) {
-            // The U partials were posted a whole pass ago.  Each workgroup of the cluster sums one
-            // slice of them (raw, still unnormalised) and publishes it; this runs before the last
-            // column sums are collected, whose polls are already in flight.
-            __builtin_amdgcn_s_setprio(3);
-            if (tid == 0) {
-                const bool ok = spin_until(p.arrive + g, (uint32_t)p.cluster, p.status, p.nonce, p.spin_limit);
-                if (!ok) give_up(p.status, p.nonce);
-                s_ok = ok;
-            }
-            lds_barrier();
-            if (!s_ok) { poison_rows<IO, D>(p, g, tile_begins[1], tile_ends[1], kThreads); return; }
-            const int per = (64 * D + p.cluster - 1) / p.cluster;
-            const int e0 = chunk * per, e1 = min(64 * D, e0 + per);
-            const float* up = p.u_part + (size_t)g * p.cluster_cap * 64 * D;
-            const __amdgpu_buffer_rsrc_t upv = coherent_view(up);
-            for (int e = e0 + wave * 64 + fresh_lane(); e < e1; e += kThreads) {
-                float acc = 0.f;
-                for (int k0 = 0; k0 < p.cluster; k0 += 8) {
-                    float v[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        v[j] = ldc_f32(upv, (uint32_t)(((size_t)min(k0 + j, p.cluster - 1) * 64 * D + e) * 4));
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) acc += (k0 + j < p.cluster) ? v[j] : 0.f;
-                }
-                st_coherent(yt + e, acc);
-            }
-            publish_barrier();   // the slice has been acknowledged
-            if (tid == 0) __hip_atomic_fetch_add(p.yready + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __builtin_amdgcn_s_setprio(0);
+            // The U partials were posted a whole pass ago: this runs before the last column sums are
+            // collected, whose polls are already in flight.
+            if (!reduce_u_slice()) { poison_rows<IO, D>(p, g, tile_begins[1], tile_ends[1], kThreads); return; }
         }
         // the queries' final update (the keys' was taken with the last exchange)
         __builtin_amdgcn_s_setprio(3);
