@@ -237,13 +237,26 @@ def main() -> int:
 
     ms_per_step = total_s * 1e3 / args.steps
     kernel_ms = float(dev_ms.mean())
+    # Which kernels ran decides what a call has to move.  The kernels that keep exp(C/eps) on chip read
+    # Q, K, V once and write O once (the compulsory bytes); the streaming kernel re-reads Q and K in every
+    # pass (the pass-streaming model M1, which is also the yardstick the 60 % target was defined on:
+    # M1 bytes / time / peak >= 0.6 means a call of the headline shape within 170 us).
+    kernels = "cls" if args.cls is not None else lot.lot_forward_kernels(shape, w.iters, path)
     m1 = algorithmic_bytes(w)
-    achieved = m1 / (kernel_ms * 1e-3) / 1e9
-    traffic = None
+    m0 = compulsory_bytes(w)
+    model_bytes = m0 if kernels in ("kept_workgroup", "kept_wavefront") else m1
+    achieved = model_bytes / (kernel_ms * 1e-3) / 1e9
+    # measured traffic is not something this run can observe: it is read from the committed summary of the
+    # rocprofv3 --pmc runs of this same command, if there is one for this workload and these kernels
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "lot_fused_%s_traffic.json" % w.name)
     if os.path.exists(tpath):
         with open(tpath) as fh:
-            traffic = json.load(fh).get("hbm_bytes_per_launch")
+            tj = json.load(fh)
+        if tj.get("kernels") == kernels:
+            traffic = tj.get("hbm_bytes_per_launch")
+            traffic_source = "profiles/lot_fused_%s_traffic.json (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; %s)" % (
+                w.name, tj.get("measured", "date not recorded"))
 
     result = {
         "metric": "LOT attention fwd tokens/sec per GPU + achieved HBM GB/s (% peak) at n=16384",
@@ -274,9 +287,15 @@ def main() -> int:
                       "p50": float(np.percentile(dev_ms, 50)), "p90": float(np.percentile(dev_ms, 90))},
         "warm_ms_per_step": warm_ms,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes": m1, "compulsory_bytes": compulsory_bytes(w),
-                     "compulsory_frac": compulsory_bytes(w) / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernels": kernels, "algorithmic_bytes": model_bytes,
+                     "algorithmic_bytes_model": ("Q, K, V read once, O written once" if model_bytes == m0 else
+                                                 "pass-streaming (M1): Q read T+1 times, K T times, V once, O once"),
+                     "compulsory_bytes": m0, "compulsory_frac": m0 / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     # the yardstick of the 60 % target: what a kernel that re-reads its rows in every pass
+                     # would have to move in the same time (not bytes that this run moved, unless it streamed)
+                     "pass_streaming_yardstick": {"bytes": m1, "GB_per_s_equivalent": m1 / (kernel_ms * 1e-3) / 1e9,
+                                                  "frac": m1 / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}},
     }
 
     if args.bwd_steps > 0:

@@ -118,6 +118,28 @@ int lot_attention_fwd_static(const lot_shape* shape, const void* Q, const void* 
                              const float* Z, const float* beta, float eps, int iters, void* out,
                              void* hip_stream);
 
+/*
+ * Which kernels lot_attention_fwd_path would run for this shape on the current device (the choice between
+ * the fused path's families depends on how many workgroups the device holds at once, so this asks the
+ * device; nothing is launched).  The paper's cost model ("Rank and complexity": O(n d r + T n r)) is the
+ * same for all of them; what differs is where the n x r kernel matrix exp(C/eps) lives between the
+ * iterations, hence how many bytes a call moves:
+ *   LOT_KERNELS_PLAIN           one plain kernel per step, everything through the workspace
+ *   LOT_KERNELS_STREAMING       one persistent kernel that recomputes exp(C/eps) from Q, K in every pass
+ *   LOT_KERNELS_KEPT_WORKGROUP  the same kernel keeping each workgroup's share of exp(C/eps) in registers
+ *                               and LDS: Q, K, V are read once
+ *   LOT_KERNELS_KEPT_WAVEFRONT  short sequences: one wavefront per side, its whole exp(C/eps) in registers
+ *   LOT_KERNELS_GROUPED         64 < r <= 256: pivots in groups of 64, one launch per step
+ */
+typedef enum {
+    LOT_KERNELS_PLAIN = 0,
+    LOT_KERNELS_STREAMING = 1,
+    LOT_KERNELS_KEPT_WORKGROUP = 2,
+    LOT_KERNELS_KEPT_WAVEFRONT = 3,
+    LOT_KERNELS_GROUPED = 4
+} lot_kernels;
+int lot_forward_kernels(const lot_shape* shape, int iters, int path, int* kernels_out);
+
 /* Debug route: the two couplings themselves (paper: Gamma^(1) and Gamma^(2) in scaling form). */
 int lot_couplings(const lot_shape* shape, const void* Q, const void* K,
                   const float* Z, const float* beta, float eps, int iters,

@@ -219,6 +219,24 @@ static int attention_impl(const lot_shape* shape, const void* Q, const void* K, 
     return run_reference(a, true);
 }
 
+int lot_forward_kernels(const lot_shape* shape, int iters, int path, int* kernels_out)
+{
+    int rc = validate_shape(shape);
+    if (rc != LOT_OK) return rc;
+    if (!kernels_out) return LOT_ERR_NULL;
+    if (iters < 1) return LOT_ERR_ITERS;
+    FwdImpl impl;
+    rc = pick_forward(*shape, iters, path, false, &impl);
+    if (rc != LOT_OK) return rc;
+    if (impl == FWD_REFERENCE) { *kernels_out = LOT_KERNELS_PLAIN; return LOT_OK; }
+    if (impl == FWD_GROUPED) { *kernels_out = LOT_KERNELS_GROUPED; return LOT_OK; }
+    // the fused path: decided exactly as a launch would be, without launching
+    Args a{};
+    a.s = *shape; a.eps = 1.f; a.iters = iters; a.out = (void*)shape;   // (a non-null placeholder; nothing is dereferenced)
+    a.lay = carve(*shape); a.dry_run = true; a.family_out = kernels_out;
+    return run_fused(a, true);
+}
+
 int lot_attention_fwd_path(const lot_shape* shape, const void* Q, const void* K, const void* V,
                            const float* Z, const float* beta, float eps, int iters, void* out,
                            void* workspace, size_t workspace_bytes, void* hip_stream, int path)

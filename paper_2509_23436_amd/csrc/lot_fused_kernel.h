@@ -501,6 +501,83 @@ __device__ __forceinline__ void fill_pass(
     xfirst = xc;
 }
 
+// The same pass for wavefronts that have a SIMD, and with it 512 registers, to themselves (four
+// wavefronts per workgroup): nobody else is there to run while one waits for memory, so the rows of
+// AHEAD tiles are kept in flight; the loop over the slots is unrolled for both sides.
+template <typename IO, int D, int RB, int WAVES, int NT, bool TO_LDS, int AHEAD>
+__device__ __forceinline__ void fill_pass_ahead(
+    const FusedParams& p, const IO* __restrict__ X, const IO* __restrict__ Xnext, int next_side,
+    Frag<IO, D>& xfirst, int g, int side, const int (&tile_begins)[2], int tile_end, int lane, int wave, float c1,
+    const void* zlds, const float* glds,
+    uint32_t (&kq)[NT][(ResWords<IO, RB>::value)], u32x4* kres_wave)
+{
+    constexpr int NW = ResWords<IO, RB>::value;
+    Frag<IO, D> zf[RB];
+    if constexpr (!similarity_by_pieces<IO, D, RB, WAVES>()) {
+        int zskew = 0;
+        asm volatile("" : "+v"(zskew));
+        fetch_pivots<D, RB>(zf, zlds, lane, zskew);
+    }
+    int io = lane & 31;
+    asm volatile("" : "+v"(io));     // (opaque: the addresses of all slots are not to be hoisted out of the iteration loop)
+    const int kg = lane >> 5;
+    const int n = p.n_side[side];
+    const int stride = p.stride_side[side];
+    const int tile_begin = tile_begins[side];
+    if (tile_begin + wave >= tile_end) {
+        if (Xnext != nullptr) request_first_tile<IO, D>(p, Xnext, xfirst, g, next_side, tile_begins[next_side], lane, wave);
+        return;
+    }
+    Frag<IO, D> xs[AHEAD];
+    xs[0] = xfirst;
+#pragma unroll
+    for (int a = 1; a < AHEAD; ++a) {
+        const int tile = tile_begin + wave + a * WAVES;
+        if (tile < tile_end) load_tokens<D>(xs[a], X + ((size_t)g * stride + min(tile * kTileTokens + io, n - 1)) * D, kg);
+    }
+#pragma unroll
+    for (int slot = 0; slot < NT; ++slot) {
+        const int tile = tile_begin + wave + slot * WAVES;
+        if (tile < tile_end) {
+            int skew = 0;
+            asm volatile("" : "+v"(skew));
+            f32x16 acc[RB];
+            load_pivot_vector<RB>(acc, glds + skew, kg);
+            if constexpr (similarity_by_pieces<IO, D, RB, WAVES>()) similarity_pieces<D, RB>(acc, zlds, xs[slot % AHEAD], lane, skew);
+            else similarity<D, RB>(acc, zf, xs[slot % AHEAD]);
+            if (slot + AHEAD < NT) {
+                const int tnext = tile + AHEAD * WAVES;
+                if (tnext < tile_end)
+                    load_tokens<D>(xs[slot % AHEAD], X + ((size_t)g * stride + min(tnext * kTileTokens + io, n - 1)) * D, kg);
+            }
+            float m0 = acc[0][0], m1 = acc[0][1], m2 = acc[0][2], m3 = acc[0][3];
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = (mb == 0 ? 4 : 0); j < 16; j += 4) {
+                    m0 = fmaxf(m0, acc[mb][j]);
+                    m1 = fmaxf(m1, acc[mb][j + 1]);
+                    m2 = fmaxf(m2, acc[mb][j + 2]);
+                    m3 = fmaxf(m3, acc[mb][j + 3]);
+                }
+            const float mc = pair_max(fmaxf(fmaxf(m0, m1), fmaxf(m2, m3))) * c1;
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[mb][j] = exp2_fast(fmaf(acc[mb][j], c1, -mc));
+            if constexpr (TO_LDS) {
+                uint32_t packed[NW];
+                res_pack<IO, RB>(packed, acc);
+                res_to_lds<NW>(kres_wave + slot * (NW / 4) * 64, packed, lane);
+            } else {
+                res_pack<IO, RB>(kq[slot], acc);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (Xnext != nullptr) request_first_tile<IO, D>(p, Xnext, xfirst, g, next_side, tile_begins[next_side], lane, wave);
+}
+
 // A pass over the kept kernel matrix: no global memory, no matrix instruction, no exponential.  cs
 // receives sum_i Kt_it / s_i per pivot; the caller multiplies the reduced sums by v_t.
 template <typename IO, int RB, int WAVES, int NT, bool FROM_LDS>
@@ -1137,8 +1214,13 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                         const bool next_too = side == 0 && it == 1;
                         const IO* Xnext = next_too ? Xs[1] : nullptr;
                         if (wave == 0) s_gref[side][fresh_lane()] = s_g[side][fresh_lane()];
-                        if (side == 0) fill_pass<IO, D, RB, WAVES, NT, true>(p, Xs[0], Xnext, 1, xfirst, g, 0, tile_begins, tile_ends[0], lane, wave, c1, zlds, s_g[0], kq, kres_wave);
-                        else fill_pass<IO, D, RB, WAVES, NT, false>(p, Xs[1], Xnext, 1, xfirst, g, 1, tile_begins, tile_ends[1], lane, wave, c1, zlds, s_g[1], kq, kres_wave);
+                        if constexpr (WAVES == 4 && NT >= 4) {
+                            if (side == 0) fill_pass_ahead<IO, D, RB, WAVES, NT, true, 4>(p, Xs[0], Xnext, 1, xfirst, g, 0, tile_begins, tile_ends[0], lane, wave, c1, zlds, s_g[0], kq, kres_wave);
+                            else fill_pass_ahead<IO, D, RB, WAVES, NT, false, 4>(p, Xs[1], Xnext, 1, xfirst, g, 1, tile_begins, tile_ends[1], lane, wave, c1, zlds, s_g[1], kq, kres_wave);
+                        } else {
+                            if (side == 0) fill_pass<IO, D, RB, WAVES, NT, true>(p, Xs[0], Xnext, 1, xfirst, g, 0, tile_begins, tile_ends[0], lane, wave, c1, zlds, s_g[0], kq, kres_wave);
+                            else fill_pass<IO, D, RB, WAVES, NT, false>(p, Xs[1], Xnext, 1, xfirst, g, 1, tile_begins, tile_ends[1], lane, wave, c1, zlds, s_g[1], kq, kres_wave);
+                        }
                         have_first = next_too;
                     }
                     if (it == p.iters) { if (side == 0) unit_k = fill; else unit_q = fill; }
@@ -1403,6 +1485,10 @@ int launch(const Args& a, bool want_out)
     // published under it, and so is a wait that gives up.
     p.nonce = next_nonce();
 
+    if (a.dry_run) {
+        if (a.family_out) *a.family_out = NT > 0 ? LOT_KERNELS_KEPT_WORKGROUP : LOT_KERNELS_STREAMING;
+        return LOT_OK;
+    }
     const int grid = p.num_items < capacity ? p.num_items : capacity;
     // An ordinary launch: the grid never exceeds the number of workgroups the device can hold at
     // once (occupancy query above), which is what the cross-workgroup waits need, and the waits are

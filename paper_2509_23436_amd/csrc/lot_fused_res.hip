@@ -19,7 +19,14 @@ int launch_resident(const Args& a)
         if (rc != LOT_ERR_PATH) return rc;
     }
     if constexpr (!io_is_f32<IO>::value) {
-        rc = launch<IO, D, RB, WAVES, 4>(a, true);
+        if constexpr (WAVES == 8 && D == 64 && RB == 2) {
+            // Four tiles per wavefront beside the working set overflow the 256 registers a wavefront has when
+            // two share a SIMD, and the spills travel to memory and back in every call.  Four wavefronts
+            // per workgroup have a SIMD each, hence 512 registers: eight tiles per wavefront fit.
+            rc = launch<IO, D, RB, 4, 8>(a, true);
+        } else {
+            rc = launch<IO, D, RB, WAVES, 4>(a, true);
+        }
     }
     return rc;
 }

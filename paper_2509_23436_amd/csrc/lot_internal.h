@@ -131,6 +131,9 @@ struct Args {
     int n_q, n_k;
     const float* mass_q;
     const float* mass_k;
+    // lot_forward_kernels: decide as for a launch, launch nothing, report the family of kernels here
+    bool dry_run;
+    int* family_out;
 };
 
 // Workspace of the backward pass (plain path): byte offsets, multiples of 256.

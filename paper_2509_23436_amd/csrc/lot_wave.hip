@@ -422,13 +422,20 @@ int launch_wave(const Args& a)
     p.n_side[1] = a.n_q > 0 ? a.n_q : s.n;
     for (int sd = 0; sd < 2; ++sd) p.stride_side[sd] = a.n_stride > 0 ? a.n_stride : p.n_side[sd];
     p.drift_half = 0.5f * drift_limit();
+    if (a.dry_run) {
+        if (a.family_out) *a.family_out = LOT_KERNELS_KEPT_WAVEFRONT;
+        return LOT_OK;
+    }
     lot_wave_kernel<IO, D, RB, NT><<<dim3((unsigned)p.G), dim3(128), 0, a.stream>>>(p);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }
 
-// the smallest NT of the compiled set {2, 4, 8, 16} that holds `tiles`, within what the registers take
-// (NT times the words per tile at most 128)
+// The smallest NT of the compiled set {2, 4, 8} that holds `tiles`, within what the registers take (NT
+// times the words per tile at most 128).  Sixteen tiles (512 tokens with up to 32 pivots in bf16) would fit
+// the registers too, but one wavefront then streams so many tiles one after the other, in the passes that
+// read Q, K, V and write O, that the workgroup-level kernels are faster (measured at B H = 384, n = 512:
+// 87 us against 76).
 template <typename IO, int D, int RB>
 int launch_wave_sized(const Args& a, int tiles)
 {
@@ -436,7 +443,6 @@ int launch_wave_sized(const Args& a, int tiles)
     if (tiles <= 2) return launch_wave<IO, D, RB, 2>(a);
     if constexpr (kMaxNT >= 4) { if (tiles <= 4) return launch_wave<IO, D, RB, 4>(a); }
     if constexpr (kMaxNT >= 8) { if (tiles <= 8) return launch_wave<IO, D, RB, 8>(a); }
-    if constexpr (kMaxNT >= 16) { if (tiles <= 16) return launch_wave<IO, D, RB, 16>(a); }
     return LOT_ERR_PATH;
 }
 

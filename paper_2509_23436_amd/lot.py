@@ -24,6 +24,7 @@ ERR_SYNC = -10
 
 EXPORTS = ("lot_workspace_bytes", "lot_workspace_bytes_path", "lot_couplings_workspace_bytes",
            "lot_attention_fwd", "lot_attention_fwd_path", "lot_attention_fwd_static", "lot_static_scratch_bytes",
+           "lot_forward_kernels",
            "lot_couplings", "lot_couplings_path",
            "lot_attention_cls_fwd", "lot_attention_cls_fwd_path",
            "lot_cross_workspace_bytes", "lot_cross_workspace_bytes_path",
@@ -78,6 +79,7 @@ def lib():
         L.lot_cross_attention_bwd_workspace_bytes_path.argtypes = [xp, ci, ci, szp]
         L.lot_attention_fwd.argtypes = [sp, vp, vp, vp, vp, vp, cf, ci, vp, vp, sz, vp]
         L.lot_attention_fwd_path.argtypes = L.lot_attention_fwd.argtypes + [ci]
+        L.lot_forward_kernels.argtypes = [sp, ci, ci, ctypes.POINTER(ctypes.c_int)]
         L.lot_attention_fwd_static.argtypes = [sp, vp, vp, vp, vp, vp, cf, ci, vp, vp]
         L.lot_static_scratch_bytes.argtypes = []
         L.lot_static_scratch_bytes.restype = sz
@@ -250,6 +252,16 @@ def lot_attention_fwd(Q, K, V, Z, beta, eps, iters, out=None, workspace=None, pa
                                         ctypes.c_float(eps), int(iters), _ptr(out), _ptr(workspace),
                                         workspace.numel(), _stream(), int(path)))
     return out
+
+
+KERNELS = ("plain", "streaming", "kept_workgroup", "kept_wavefront", "grouped")
+
+
+def lot_forward_kernels(shape: lot_shape, iters: int, path=PATH_AUTO) -> str:
+    """The family of kernels lot_attention_fwd would run for this shape on the current device."""
+    out = ctypes.c_int(-1)
+    _check(lib().lot_forward_kernels(ctypes.byref(shape), int(iters), int(path), ctypes.byref(out)))
+    return KERNELS[out.value]
 
 
 def lot_static_scratch_bytes() -> int:
