@@ -216,9 +216,9 @@ def main() -> int:
         step(k)
         stops[k].record()
     t_enqueued = time.perf_counter()
+    clocks["during"] = device_clocks()      # (the queue is still draining: the clocks under load)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    # (read after the clock stops; the device was busy until a moment ago, so this is the loaded state)
     clocks["after"] = device_clocks()
     total_s = t1 - t0
     dev_ms = np.array([a.elapsed_time(b) for a, b in zip(starts, stops)])

@@ -321,8 +321,9 @@ int lot_status_words(const unsigned long long* host_words);
  *                                      (its form on a device that cannot hold the whole grid at once)
  *   LOT_KNOB_FWD_STREAMING             1: the fused forward re-reads Q and K in every pass (what it does for
  *                                      long sequences) also where the kernel matrix would fit on chip;
- *                                      2: short sequences on the workgroup-level kept-matrix kernels instead
- *                                      of the wavefront-per-side kernel
+ *                                      2: the workgroup-level kept-matrix kernels wherever they fit (short
+ *                                      sequences instead of the wavefront-per-side kernel; few iterations
+ *                                      instead of the streaming kernel)
  *   LOT_KNOB_FWD_DRIFT_LIMIT           0..32: the forward kernels that keep exp(C/eps) on chip recompute it once
  *                                      the potentials have spread over more than this many binary orders
  *                                      (default 32; 0: in every iteration)

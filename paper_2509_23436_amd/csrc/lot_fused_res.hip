@@ -62,6 +62,11 @@ int dispatch_resident(const Args& a)
 int run_fused_resident(const Args& a)
 {
     if (!fused_supports(a.s) || a.mass_q != nullptr || a.mass_k != nullptr) return LOT_ERR_PATH;
+    // More than 32 pivots and few iterations: computing and storing the kernel matrix, then sweeping it once
+    // more for the first column sums, costs more than the few passes it saves (measured over B H = 8 .. 16,
+    // n = 4096 .. 32768: 3-15 % slower than the streaming kernel at T = 3 and 5, level or faster from T = 10).
+    // Up to 32 pivots keeping it is never slower.  (The testing knob that asks for these kernels overrides this.)
+    if (a.s.r > 32 && a.iters < 8 && forward_variants() != 2) return LOT_ERR_PATH;
     return a.s.io_dtype == LOT_BF16 ? dispatch_resident<uint16_t>(a) : dispatch_resident<float>(a);
 }
 

@@ -272,7 +272,8 @@ uint32_t spin_limit();
 
 // Testing aid (LOT_KNOB_FWD_STREAMING): 1 = the fused forward never keeps the kernel matrix on chip, so that
 // the variants that re-read Q and K in every pass (what long sequences run) are exercised on short ones;
-// 2 = no wavefront-per-side kernel, so that the workgroup-level kept-matrix variants are; 0 = as shipped.
+// 2 = no wavefront-per-side kernel, and the workgroup-level kept-matrix variants wherever they fit (also
+// where few iterations make AUTO prefer the streaming kernel), so that these are; 0 = as shipped.
 int forward_variants();
 
 // The forward kernels that keep the kernel matrix on chip recompute it when the potentials have spread
