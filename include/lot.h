@@ -77,8 +77,9 @@ typedef struct {
 typedef enum {
     LOT_PATH_AUTO = 0,
     LOT_PATH_REFERENCE = 1,  /* one plain kernel per step, similarities materialised (any shape) */
-    LOT_PATH_FUSED = 2       /* MFMA kernels; d_k = d_v in {32, 64}: r <= 64 one persistent kernel,
-                                64 < r <= 256 grouped kernels, one launch per step (attention only) */
+    LOT_PATH_FUSED = 2       /* MFMA kernels; d_k = d_v in {32, 64}: r <= 64 one kernel per call (see
+                                lot_forward_kernels for its families), 64 < r <= 256 grouped kernels, one
+                                launch per step (attention only) */
 } lot_path;
 
 /*
