@@ -73,7 +73,10 @@ typedef struct {
     int32_t io_dtype;    /* lot_dtype of Q, K, V, out */
 } lot_shape;
 
-/* Which kernels run.  AUTO picks FUSED when the shape is in its compiled set, else REFERENCE. */
+/* Which kernels run.  AUTO picks FUSED when the shape is in its compiled set and both sides have at least
+ * 16 tokens, else REFERENCE (with a handful of tokens and a small eps a pivot can be so far from every
+ * token of a side that its column sum leaves the fp32 range in the tile kernels' linear-domain sums; the
+ * plain kernels work in the log domain throughout). */
 typedef enum {
     LOT_PATH_AUTO = 0,
     LOT_PATH_REFERENCE = 1,  /* one plain kernel per step, similarities materialised (any shape) */

@@ -108,8 +108,19 @@ static bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0
 // Which kernels a forward call runs.
 enum FwdImpl { FWD_REFERENCE = 0, FWD_FUSED = 1, FWD_GROUPED = 2 };
 
-// n_max: the longer side (cross attention).  `couplings`: lot_couplings, which the grouped kernels do not serve.
-static int pick_forward(const lot_shape& s, int iters, int path, bool couplings, FwdImpl* impl)
+// AUTO sends problems with fewer tokens than this on either side to the plain kernels.  The tile kernels
+// form the column sums of the row-normalised kernel in the linear domain: a pivot that is far from EVERY
+// token of a side (all its entries below 2^-126 of their rows' maxima) then has a sum that fp32 cannot
+// hold, and its potential comes out wrong although its mass has to go somewhere.  With a handful of tokens
+// and a small eps that happens (a randomised sweep found it with one or two tokens at eps = 0.02); with
+// sixteen tokens it takes every one of them to lie 87 nats below its row's maximum at that pivot, which
+// similarities of the workloads' scale do not produce.  The plain kernels work in the log domain
+// throughout and cost nothing at this size.
+constexpr int kMinFusedTokens = 16;
+
+// s.n = the longer side (cross attention), n_short = the shorter one.  `couplings`: lot_couplings, which
+// the grouped kernels do not serve.
+static int pick_forward(const lot_shape& s, int n_short, int iters, int path, bool couplings, FwdImpl* impl)
 {
     const bool grouped = !couplings && grouped_supports(s);
     const bool fused = fused_supports(s);
@@ -117,7 +128,9 @@ static int pick_forward(const lot_shape& s, int iters, int path, bool couplings,
     // exchange format go to the plain kernels under AUTO)
     const bool fits = fused_exchange_fits(s.n, iters);
     switch (path) {
-    case LOT_PATH_AUTO: *impl = grouped ? FWD_GROUPED : (fused && fits) ? FWD_FUSED : FWD_REFERENCE; return LOT_OK;
+    case LOT_PATH_AUTO:
+        *impl = n_short < kMinFusedTokens ? FWD_REFERENCE : grouped ? FWD_GROUPED : (fused && fits) ? FWD_FUSED : FWD_REFERENCE;
+        return LOT_OK;
     case LOT_PATH_REFERENCE: *impl = FWD_REFERENCE; return LOT_OK;
     case LOT_PATH_FUSED:
         if (grouped) { *impl = FWD_GROUPED; return LOT_OK; }
@@ -172,9 +185,21 @@ int lot_workspace_bytes_path(const lot_shape* shape, int iters, int path, size_t
     int rc = sizing_checks(shape, iters, bytes_out);
     if (rc != LOT_OK) return rc;
     FwdImpl impl;
-    rc = pick_forward(*shape, iters, path, false, &impl);
+    rc = pick_forward(*shape, shape->n, iters, path, false, &impl);
     if (rc != LOT_OK) return rc;
-    *bytes_out = forward_need(*shape, iters, impl);
+    size_t need = forward_need(*shape, iters, impl);
+    // The [CLS] variant runs these kernels on the n - 1 other tokens with this workspace; at the one length
+    // where that changes the choice of kernels the larger of the two sizes is returned.
+    if (shape->n >= 2) {
+        lot_shape inner = *shape;
+        inner.n = shape->n - 1;
+        FwdImpl inner_impl;
+        if (pick_forward(inner, inner.n, iters, path, false, &inner_impl) == LOT_OK && inner_impl != impl) {
+            const size_t other = forward_need(inner, iters, inner_impl);
+            if (other > need) need = other;
+        }
+    }
+    *bytes_out = need;
     return LOT_OK;
 }
 
@@ -188,7 +213,7 @@ int lot_couplings_workspace_bytes(const lot_shape* shape, int iters, int path, s
     int rc = sizing_checks(shape, iters, bytes_out);
     if (rc != LOT_OK) return rc;
     FwdImpl impl;
-    rc = pick_forward(*shape, iters, path, true, &impl);
+    rc = pick_forward(*shape, shape->n, iters, path, true, &impl);
     if (rc != LOT_OK) return rc;
     *bytes_out = forward_need(*shape, iters, impl);
     return LOT_OK;
@@ -205,7 +230,7 @@ static int attention_impl(const lot_shape* shape, const void* Q, const void* K, 
     if (!V || !out) return LOT_ERR_NULL;
     if (misaligned(V, 16) || misaligned(out, 16)) return LOT_ERR_ALIGN;
     FwdImpl impl;
-    rc = pick_forward(*shape, iters, path, false, &impl);
+    rc = pick_forward(*shape, shape->n, iters, path, false, &impl);
     if (rc != LOT_OK) return rc;
     if (workspace_bytes < forward_need(*shape, iters, impl)) return LOT_ERR_WORKSPACE;
     Args a{};
@@ -226,7 +251,7 @@ int lot_forward_kernels(const lot_shape* shape, int iters, int path, int* kernel
     if (!kernels_out) return LOT_ERR_NULL;
     if (iters < 1) return LOT_ERR_ITERS;
     FwdImpl impl;
-    rc = pick_forward(*shape, iters, path, false, &impl);
+    rc = pick_forward(*shape, shape->n, iters, path, false, &impl);
     if (rc != LOT_OK) return rc;
     if (impl == FWD_REFERENCE) { *kernels_out = LOT_KERNELS_PLAIN; return LOT_OK; }
     if (impl == FWD_GROUPED) { *kernels_out = LOT_KERNELS_GROUPED; return LOT_OK; }
@@ -283,7 +308,7 @@ int lot_couplings_path(const lot_shape* shape, const void* Q, const void* K,
     if (!gamma1 || !gamma2) return LOT_ERR_NULL;
     if (misaligned(gamma1, 16) || misaligned(gamma2, 16)) return LOT_ERR_ALIGN;
     FwdImpl impl;
-    rc = pick_forward(*shape, iters, path, true, &impl);
+    rc = pick_forward(*shape, shape->n, iters, path, true, &impl);
     if (rc != LOT_OK) return rc;
     if (workspace_bytes < forward_need(*shape, iters, impl)) return LOT_ERR_WORKSPACE;
     Args a{};
@@ -358,7 +383,7 @@ int lot_attention_fwd_static(const lot_shape* shape, const void* Q, const void* 
         misaligned(beta, 4))
         return LOT_ERR_ALIGN;
     FwdImpl impl;
-    rc = pick_forward(*shape, iters, LOT_PATH_AUTO, false, &impl);
+    rc = pick_forward(*shape, shape->n, iters, LOT_PATH_AUTO, false, &impl);
     if (rc != LOT_OK) return rc;
     if (forward_need(*shape, iters, impl) > kStaticScratchBytes) return LOT_ERR_SCRATCH;
     void* ws = nullptr;
@@ -396,7 +421,7 @@ int lot_cross_workspace_bytes_path(const lot_xshape* shape, int iters, int path,
     if (!bytes_out) return LOT_ERR_NULL;
     if (iters < 1) return LOT_ERR_ITERS;
     FwdImpl impl;
-    rc = pick_forward(fused_view(*shape), iters, path, false, &impl);
+    rc = pick_forward(fused_view(*shape), shape->n_q < shape->n_k ? shape->n_q : shape->n_k, iters, path, false, &impl);
     if (rc != LOT_OK) return rc;
     *bytes_out = cross_forward_need(*shape, iters, impl);
     return LOT_OK;
@@ -423,7 +448,7 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
     if (misaligned(workspace, 256)) return LOT_ERR_WORKSPACE;
     const lot_shape fs = fused_view(*shape);
     FwdImpl impl;
-    rc = pick_forward(fs, iters, path, false, &impl);
+    rc = pick_forward(fs, shape->n_q < shape->n_k ? shape->n_q : shape->n_k, iters, path, false, &impl);
     if (rc != LOT_OK) return rc;
     if (workspace_bytes < cross_forward_need(*shape, iters, impl)) return LOT_ERR_WORKSPACE;
     if (impl != FWD_REFERENCE) {
