@@ -578,16 +578,123 @@ __device__ __forceinline__ void fill_pass_ahead(
     if (Xnext != nullptr) request_first_tile<IO, D>(p, Xnext, xfirst, g, next_side, tile_begins[next_side], lane, wave);
 }
 
-// A pass over the kept kernel matrix: no global memory, no matrix instruction, no exponential.  cs
-// receives sum_i Kt_it / s_i per pivot; the caller multiplies the reduced sums by v_t.
+// The kept matrix as operand of the matrix cores (bf16 I/O: two bf16 entries per register).  A lane's
+// 8 RB words of a tile are, four at a time, its 8 numbers of one MFMA step over 16 pivots: step s covers
+// the lane's accumulator registers 8 (s & 1) .. + 7 of pivot block s >> 1.  The row sums
+// s_i = sum_t Kt_it v_t are then one small product per step with v as the other operand: rows of that
+// operand alternate between the leading bf16 part of v (even rows) and the rest (odd rows), so that the
+// first two result registers of every lane hold the two parts of its token's sum, over all pivots and to
+// fp32 accuracy.  `vhl` points at [2][64] bf16: leading parts, then the rests.
+template <int RB>
+__device__ __forceinline__ void kept_v_fragments(bf16x8 (&vf)[2 * RB], const uint16_t* vhl, bool unit_v, int lane)
+{
+    const int kg = lane >> 5;
+    const uint16_t* src = vhl + (lane & 1) * 64 + 4 * kg;
+#pragma unroll
+    for (int s = 0; s < 2 * RB; ++s) {
+        const u32x2 a = *reinterpret_cast<const u32x2*>(src + 16 * s);
+        const u32x2 b = *reinterpret_cast<const u32x2*>(src + 16 * s + 8);
+        u32x4 t;
+        t[0] = a[0]; t[1] = a[1]; t[2] = b[0]; t[3] = b[1];
+        if (unit_v) {   // right after a fill: v = 1 (padding pivots hold zeros in the kept matrix)
+            const uint32_t one = (lane & 1) ? 0u : 0x3f803f80u;
+            t[0] = one; t[1] = one; t[2] = one; t[3] = one;
+        }
+        vf[s] = __builtin_bit_cast(bf16x8, t);
+    }
+}
+template <int RB>
+__device__ __forceinline__ f32x16 kept_row_sums(const bf16x8 (&vf)[2 * RB], const uint32_t (&w)[8 * RB])
+{
+    f32x16 d;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) d[j] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 2 * RB; ++s) {
+        u32x4 t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = w[4 * s + e];
+        d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[s], __builtin_bit_cast(bf16x8, t), d, 0, 0, 0);
+    }
+    return d;
+}
+// cs_t += Kt_it w for the lane's 16 RB pivots, straight from the packed words: a two-term bf16 dot
+// product whose other operand is (w, 0) or (0, w).  w enters as bf16: its rounding (2^-9, zero mean,
+// independent from token to token) averages out over the tokens of a column sum; the weights of the
+// output rows and of the contraction with V are formed in fp32 elsewhere.  (These dot products were
+// measured to share a pipe with the matrix instructions -- 32 of them and the four row-sum products of a
+// tile take 340 cycles one after the other -- but unpacking and multiply-adds on the vector unit, for all
+// or for half of the registers, measured slower in the kernel: 1.55-1.7 us per pass against 1.45-1.6.)
+template <int RB>
+__device__ __forceinline__ void kept_column_sums(f32x16 (&cs)[RB], const uint32_t (&w)[8 * RB], float weight)
+{
+    const uint32_t wb = (uint32_t)bf16_bits_of(weight);
+    const bf16x2 w_even = __builtin_bit_cast(bf16x2, wb), w_odd = __builtin_bit_cast(bf16x2, wb << 16);
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const bf16x2 pr = __builtin_bit_cast(bf16x2, w[8 * mb + q]);
+            cs[mb][2 * q] = __builtin_amdgcn_fdot2_f32_bf16(pr, w_even, cs[mb][2 * q], false);
+            cs[mb][2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(pr, w_odd, cs[mb][2 * q + 1], false);
+        }
+}
+
+// A pass over the kept kernel matrix: no global memory, no exponential.  cs receives sum_i Kt_it / s_i
+// per pivot; the caller multiplies the reduced sums by v_t.  fp32 I/O: vector arithmetic on the fp32
+// entries.  bf16 I/O: the row sums on the matrix cores, straight from the packed words, and under way
+// for the next tile while the vector unit forms the column sums of the current one.
 template <typename IO, int RB, int WAVES, int NT, bool FROM_LDS>
 __device__ __forceinline__ void cheap_pass(
-    const FusedParams& p, int side, int tile_begin, int tile_end, int lane, int wave, const float* vlds, bool unit_v,
+    const FusedParams& p, int side, int tile_begin, int tile_end, int lane, int wave, const float* vlds,
+    const uint16_t* vhl, bool unit_v,
     f32x16 (&cs)[RB], const uint32_t (&kq)[NT][(ResWords<IO, RB>::value)], const u32x4* kres_wave)
 {
     constexpr int NW = ResWords<IO, RB>::value;
     const int i = lane & 31, kg = lane >> 5;
     const int n = p.n_side[side];
+    if constexpr (res_packed<IO>::value) {
+        bf16x8 vf[2 * RB];
+        kept_v_fragments<RB>(vf, vhl, unit_v, lane);
+        const int mine = tile_end - tile_begin - wave;                 // tiles of this wavefront: ceil(mine / WAVES), at most NT
+        if (mine <= 0) return;
+        // (the row sums of slot + 1 are issued before the vector unit starts on slot: two result blocks in turn)
+        auto words_of = [&](uint32_t (&w)[NW], int slot) __attribute__((always_inline)) {
+            if constexpr (FROM_LDS) res_from_lds<NW>(w, kres_wave + slot * (NW / 4) * 64, lane);
+            else {
+#pragma unroll
+                for (int q = 0; q < NW; ++q) w[q] = kq[slot][q];
+            }
+        };
+        if (mine > (NT - 1) * WAVES && tile_end * kTileTokens <= n) {
+            // every slot in use and no token past the end: no test inside
+            uint32_t w[2][NW];
+            f32x16 d[2];
+            words_of(w[0], 0);
+            d[0] = kept_row_sums<RB>(vf, w[0]);
+#pragma unroll
+            for (int slot = 0; slot < NT; ++slot) {
+                if (slot + 1 < NT) {
+                    words_of(w[(slot + 1) & 1], slot + 1);
+                    d[(slot + 1) & 1] = kept_row_sums<RB>(vf, w[(slot + 1) & 1]);
+                }
+                kept_column_sums<RB>(cs, w[slot & 1], rcp_fast(d[slot & 1][0] + d[slot & 1][1]));
+            }
+            return;
+        }
+#pragma unroll
+        for (int slot = 0; slot < NT; ++slot) {
+            const int tile = tile_begin + wave + slot * WAVES;
+            if (tile < tile_end) {
+                uint32_t w[NW];
+                words_of(w, slot);
+                const f32x16 d = kept_row_sums<RB>(vf, w);
+                const int tok = tile * kTileTokens + i;
+                kept_column_sums<RB>(cs, w, tok < n ? rcp_fast(d[0] + d[1]) : 0.f);
+            }
+        }
+        return;
+    } else {
     f32x16 v[RB];
     load_pivot_vector<RB>(v, vlds, kg);
     if (unit_v) {      // right after a fill: the potentials are inside the kept matrix (padding pivots hold zeros there)
@@ -627,6 +734,7 @@ __device__ __forceinline__ void cheap_pass(
 #pragma unroll
                 for (int j = 0; j < 16; ++j) cs[mb][j] = fmaf(k[mb][j], w, cs[mb][j]);
         }
+    }
     }
 }
 
@@ -883,6 +991,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
     __shared__ __attribute__((aligned(16))) char s_zst[kKept && !similarity_by_pieces<IO, D, RB, WAVES>() ? RB * (D / 16) * 64 * 16 : 16];
     __shared__ float s_gref[2][64];    // NT > 0: the potentials folded into the kept kernel matrix, per side
     __shared__ float s_v[2][64];       // NT > 0: exp((g - gref)/eps - shift) per side
+    __shared__ __attribute__((aligned(16))) uint16_t s_vhl[2][2][64];   // ... as bf16: leading part, rest (operand of the row-sum products)
     __shared__ int s_fill[2];          // NT > 0: the next pass of this side must recompute the kernel matrix
     // the pivots' bf16 pieces for the similarity products where those are used (the tile loop reads them from here)
     __shared__ __attribute__((aligned(16))) char s_zf[similarity_by_pieces<IO, D, RB, WAVES>() ? PieceStashBytes<D, RB>::value : 16];
@@ -905,6 +1014,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
 
     for (int item = blockIdx.x; item < p.num_items; item += gridDim.x) {
         LOT_STAMP(0);
+#ifdef LOT_TRACE
+        unsigned long long clk0 = 0;
+        if (threadIdx.x == 0 && p.trace) clk0 = clock64();
+#endif
         const int g = item / p.cluster, chunk = item % p.cluster, h = g % p.H;
         const int tile_begins[2] = {chunk * p.tpw_side[0], chunk * p.tpw_side[1]};
         const int tile_ends[2] = {min(ntiles_side[0], tile_begins[0] + p.tpw_side[0]),
@@ -935,7 +1048,12 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         }
         if (tid < 128) s_g[tid >> 6][tid & 63] = (tid & 63) < r ? 0.f : kNegBig;
         if constexpr (NT > 0) {
-            if (tid < 128) { s_gref[tid >> 6][tid & 63] = 0.f; s_v[tid >> 6][tid & 63] = (tid & 63) < r ? 1.f : 0.f; }
+            if (tid < 128) {
+                s_gref[tid >> 6][tid & 63] = 0.f;
+                s_v[tid >> 6][tid & 63] = (tid & 63) < r ? 1.f : 0.f;
+                s_vhl[tid >> 6][0][tid & 63] = (tid & 63) < r ? (uint16_t)0x3f80u : (uint16_t)0u;
+                s_vhl[tid >> 6][1][tid & 63] = 0;
+            }
             if (tid < 2) s_fill[tid] = 0;
         }
         if (tid < 64) s_beta[tid] = tid < r ? beta_read : 1.f;
@@ -1024,7 +1142,13 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     const float d = (s_g[side][ln] - s_gref[side][ln]) * c1;
                     const float d0 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, d)));
                     const float rel = d - d0;
-                    s_v[side][ln] = lv ? exp2_fast(rel) : 0.f;
+                    const float vv = lv ? exp2_fast(rel) : 0.f;
+                    s_v[side][ln] = vv;
+                    if constexpr (res_packed<IO>::value) {
+                        const __bf16 vh = (__bf16)vv;
+                        s_vhl[side][0][ln] = __builtin_bit_cast(uint16_t, vh);
+                        s_vhl[side][1][ln] = bf16_bits_of(vv - (float)vh);
+                    }
                     const bool any_far = __any(lv && !(fabsf(rel) <= p.drift_half));   // (all 64 lanes take part)
                     if (ln == 0) s_fill[side] = any_far ? 1 : 0;
                 }
@@ -1238,8 +1362,8 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                                                               s_v[0], fill, cs, U, block);
                         alive = exchange(0, it, true, 1, it - 1, false, !fill);
                     } else {
-                        if (side == 0) cheap_pass<IO, RB, WAVES, NT, true>(p, 0, tile_begins[0], tile_ends[0], lane, wave, s_v[0], fill, cs, kq, kres_wave);
-                        else cheap_pass<IO, RB, WAVES, NT, false>(p, 1, tile_begins[1], tile_ends[1], lane, wave, s_v[1], fill, cs, kq, kres_wave);
+                        if (side == 0) cheap_pass<IO, RB, WAVES, NT, true>(p, 0, tile_begins[0], tile_ends[0], lane, wave, s_v[0], &s_vhl[0][0][0], fill, cs, kq, kres_wave);
+                        else cheap_pass<IO, RB, WAVES, NT, false>(p, 1, tile_begins[1], tile_ends[1], lane, wave, s_v[1], &s_vhl[1][0][0], fill, cs, kq, kres_wave);
                         alive = exchange(side, it, false, side ^ 1, side == 1 ? it : it - 1, side == 1 && it == p.iters, !fill);
                     }
                     if (!alive) {
@@ -1367,7 +1491,9 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         }
         LOT_STAMP(5);
 #ifdef LOT_TRACE
-        if (threadIdx.x == 0 && p.trace) p.trace[(size_t)blockIdx.x * 128 + 6] = repolls;
+        if (threadIdx.x == 0 && p.trace) p.trace[(size_t)blockIdx.x * 128 + 6] = clock64() - clk0;
+#endif
+#ifdef LOT_TRACE
         if (threadIdx.x == 0 && p.trace) p.trace[(size_t)blockIdx.x * 128 + 7] = valid_a;
 #endif
         __syncthreads();   // LDS is reused by the next item
