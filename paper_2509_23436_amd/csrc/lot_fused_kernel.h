@@ -2,6 +2,9 @@
 // (lot_fused.hip: the streaming variants; lot_fused_res.hip: the variants that keep the kernel matrix
 // on chip).  See lot_fused.hip for the description of the work decomposition.
 #pragma once
+#ifndef LOT_ACCUM_AHEAD
+#define LOT_ACCUM_AHEAD 3
+#endif
 #include <cmath>
 #include <type_traits>
 
@@ -19,7 +22,10 @@ enum { MODE_ATTENTION = 0, MODE_COUPLINGS = 1 };
 // stamps the constant-rate clock into slot `slot` of its 128-slot record, kept in the last 8 MiB of
 // the workspace (a region only the reference path uses).
 #ifdef LOT_TRACE
-#define LOT_STAMP(slot) do { if (threadIdx.x == 0 && (slot) < 128 && p.trace) p.trace[(size_t)blockIdx.x * 128 + (slot)] = wall_clock64(); } while (0)
+#ifndef LOT_TRACE_THREAD
+#define LOT_TRACE_THREAD 0
+#endif
+#define LOT_STAMP(slot) do { if (threadIdx.x == LOT_TRACE_THREAD && (slot) < 128 && p.trace) p.trace[(size_t)blockIdx.x * 128 + (slot)] = wall_clock64(); } while (0)
 #else
 #define LOT_STAMP(slot) do { } while (0)
 #endif
@@ -38,7 +44,7 @@ struct FusedParams {
     uint32_t* yready;     // [G]
     unsigned long long* cleared;   // [G]: holds this launch's nonce once the problem's counters are zero
     unsigned long long nonce;
-    unsigned long long* colacc;   // [G][2 sides][2 parities][64]: count << 56 | fixed-point column sum
+    unsigned long long* colacc;   // [G][2 sides][2 parities][64]: count << kCountShift | fixed-point column sum
     float* u_part;        // [G][cluster_cap][64][D]
     float* y_tile;        // [G][64][D]
     int G, H, r;
@@ -54,6 +60,11 @@ struct FusedParams {
     float drift_half;            // NT > 0: a pivot's potential may move this many binary orders away from pivot 0's before the kernel matrix is recomputed
     unsigned long long* trace;   // LOT_TRACE builds only
 };
+
+// Format of an exchanged column sum: arrivals in the top ten bits (every wavefront but the first of every
+// workgroup of a problem posts: up to 64 * 7), the fixed-point sum below.
+constexpr int kCountShift = 54;
+constexpr unsigned kCountMask = 0x3ffu;
 
 // Poll *counter until it reaches target.  Thread 0 only.  False if the budget ran out or another
 // workgroup already gave up.
@@ -742,15 +753,24 @@ __device__ __forceinline__ void cheap_pass(
 // by MFMA (the factor v_t is left out here as well; the caller applies it to the rows of U).  The
 // coupling tile is transposed through LDS like in run_pass; the transposition area is the beginning of
 // this wavefront's own block of kept data, which is why the words of the next slot are fetched before
-// the current slot's transposed tile is written (block layout: see the kernel).
-template <typename IO, int D, int RB, int WAVES, int NT>
+// the current slot's transposed tile is written (block layout: see the kernel).  The value rows of AHEAD
+// tiles are kept in flight: this is the only pass of these variants that reads memory it has not asked
+// for long before, and with one wavefront per SIMD nobody else runs while it waits.
+template <typename IO, int D, int RB, int WAVES, int NT, int AHEAD>
 __device__ __forceinline__ void accum_from_kept(
     const FusedParams& p, const IO* __restrict__ V, int g, int tile_begin, int tile_end, int lane, int wave,
-    const float* vlds, bool unit_v, f32x16 (&cs)[RB], f32x16 (&U)[RB][D / 32], char* block)
+    const float* vlds, const uint16_t* vhl, bool unit_v, f32x16 (&cs)[RB], f32x16 (&U)[RB][D / 32], char* block)
 {
     constexpr int NW = ResWords<IO, RB>::value;
     constexpr int NB = D / 32;
     constexpr bool kSplit = io_is_f32<IO>::value;
+    constexpr bool kAhead = AHEAD > 1;       // value rows of several tiles in flight, row sums on the matrix cores
+    static_assert(!kAhead || res_packed<IO>::value, "the deep variant is written for bf16 I/O");
+    // (an opaque copy of the lane index for the addresses of the value rows: formed from the plain one, the
+    // addresses of all slots are hoisted out of the iteration loop and spilled)
+    int lane_o = lane;
+    asm volatile("" : "+v"(lane_o));
+    const int io = lane_o & 31, kgo = lane_o >> 5;
     const int i = lane & 31, kg = lane >> 5;
     const int n = p.n_side[0];
     const int stride = p.stride_side[0];
@@ -758,43 +778,77 @@ __device__ __forceinline__ void accum_from_kept(
     uint16_t* tr_hi = reinterpret_cast<uint16_t*>(block);
     uint16_t* tr_lo = tr_hi + 32 * RB * kTrStride;
     if (tile_begin + wave >= tile_end) return;
+    bf16x8 vf[kAhead ? 2 * RB : 1];
+    if constexpr (kAhead) kept_v_fragments<RB>(vf, vhl, unit_v, lane);
+    uint32_t raw[kAhead ? AHEAD : 1][16];
+    const bool inside = tile_end * kTileTokens <= n;   // no token of this workgroup's tiles is past the end
+    auto request_values = [&](int buf, int tile) __attribute__((always_inline)) {
+        if constexpr (kAhead) {
+            const uint16_t* Vu = reinterpret_cast<const uint16_t*>(V);
+            if (inside) {
+                request_value_rows_inside<D>(raw[buf], Vu + ((size_t)g * stride + tile * kTileTokens + 8 * kgo) * D + (D / 32) * io);
+            } else {
+                const int t0 = tile * kTileTokens + 8 * kgo;
+                request_value_rows<D>(raw[buf], Vu, io, [&](int s, int e) -> size_t {
+                    return (size_t)g * stride + min(t0 + 16 * s + e, n - 1);
+                });
+            }
+        }
+    };
+    if constexpr (kAhead) {
+#pragma unroll
+        for (int a = 0; a < AHEAD; ++a) {
+            const int tile = tile_begin + wave + a * WAVES;
+            if (a < NT && tile < tile_end) request_values(a, tile);
+        }
+    }
     uint32_t cur[NW], nxt[NW];
     res_from_lds<NW>(cur, kres_wave, lane);
 #pragma unroll
     for (int q = 0; q < NW; ++q) nxt[q] = 0u;
-#pragma nounroll
+    constexpr int kUnrollSlots = kAhead ? NT : 1;   // unrolled only where the slot picks the registers of the value rows
+#pragma unroll kUnrollSlots
     for (int slot = 0; slot < NT; ++slot) {
         const int tile = tile_begin + wave + slot * WAVES;
         if (tile < tile_end) {
-            if (tile + WAVES < tile_end) res_from_lds<NW>(nxt, kres_wave + (slot + 1) * (NW / 4) * 64, lane);
+            if (slot + 1 < NT && tile + WAVES < tile_end) res_from_lds<NW>(nxt, kres_wave + (slot + 1) * (NW / 4) * 64, lane);
             bf16x8 vh[2][NB], vl[2][NB];
+            if constexpr (!kAhead) {
+                // (requested now, used at the end of the tile)
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
-                const int left = max(1, min(8, n - t0));
-                load_values<D>(vh[s], vl[s], V, (size_t)g * stride + min(t0, n - 1), left, i);
+                for (int s = 0; s < 2; ++s) {
+                    const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
+                    const int left = max(1, min(8, n - t0));
+                    load_values<D>(vh[s], vl[s], V, (size_t)g * stride + min(t0, n - 1), left, i);
+                }
             }
             f32x16 k[RB];
             res_unpack<IO, RB>(k, cur);
-            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-            if (unit_v) {
-#pragma unroll
-                for (int mb = 0; mb < RB; ++mb)
-#pragma unroll
-                    for (int j = 0; j < 16; j += 4) { s0 += k[mb][j]; s1 += k[mb][j + 1]; s2 += k[mb][j + 2]; s3 += k[mb][j + 3]; }
+            float s;
+            if constexpr (kAhead) {
+                const f32x16 d = kept_row_sums<RB>(vf, cur);
+                s = d[0] + d[1];
             } else {
+                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+                if (unit_v) {
 #pragma unroll
-                for (int mb = 0; mb < RB; ++mb)
+                    for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x4 v = *reinterpret_cast<const f32x4*>(vlds + 32 * mb + 8 * q + 4 * kg);
-                        s0 = fmaf(k[mb][4 * q], v[0], s0);
-                        s1 = fmaf(k[mb][4 * q + 1], v[1], s1);
-                        s2 = fmaf(k[mb][4 * q + 2], v[2], s2);
-                        s3 = fmaf(k[mb][4 * q + 3], v[3], s3);
-                    }
+                        for (int j = 0; j < 16; j += 4) { s0 += k[mb][j]; s1 += k[mb][j + 1]; s2 += k[mb][j + 2]; s3 += k[mb][j + 3]; }
+                } else {
+#pragma unroll
+                    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x4 v = *reinterpret_cast<const f32x4*>(vlds + 32 * mb + 8 * q + 4 * kg);
+                            s0 = fmaf(k[mb][4 * q], v[0], s0);
+                            s1 = fmaf(k[mb][4 * q + 1], v[1], s1);
+                            s2 = fmaf(k[mb][4 * q + 2], v[2], s2);
+                            s3 = fmaf(k[mb][4 * q + 3], v[3], s3);
+                        }
+                }
+                s = pair_sum((s0 + s1) + (s2 + s3));
             }
-            const float s = pair_sum((s0 + s1) + (s2 + s3));
             const int tok = tile * kTileTokens + i;
             const float w = tok < n ? rcp_fast(s) : 0.f;
             // (the words of this slot and of the next are in registers: their bytes may be overwritten now)
@@ -814,6 +868,7 @@ __device__ __forceinline__ void accum_from_kept(
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if constexpr (kAhead) value_fragments<D>(vh, raw[slot % AHEAD]);   // (the first use of what was fetched AHEAD tiles ago)
 #pragma unroll
             for (int s2i = 0; s2i < 2; ++s2i) {
 #pragma unroll
@@ -834,9 +889,13 @@ __device__ __forceinline__ void accum_from_kept(
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
+            if constexpr (kAhead) {
+                if (slot + AHEAD < NT && tile + AHEAD * WAVES < tile_end) request_values(slot % AHEAD, tile + AHEAD * WAVES);
+            }
 #pragma unroll
             for (int q = 0; q < NW; ++q) cur[q] = nxt[q];
         }
+        if constexpr (kAhead) __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -958,6 +1017,12 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
     constexpr int NW = ResWords<IO, RB>::value;
     constexpr bool kKept = NT > 0;
     constexpr bool kSplitIO = io_is_f32<IO>::value;
+    // Wavefronts of a workgroup that post its column sums to the problem's accumulators.  With four
+    // wavefronts, each of the three that reduce posts its own share.  With eight, seven posts per
+    // workgroup were measured to cost more than they save (the acknowledgements of so many atomics on the
+    // same words take microseconds, and every reload of a spilled register in the next pass waits for
+    // them): the seven leave their shares in LDS and one of them posts the sum.
+    constexpr int kPosters = WAVES == 4 ? WAVES - 1 : 1;
     // NT == 0: s_u holds the workgroup's sum of U, s_big the transposition areas of the two contraction
     // passes (every wavefront its own, hi and lo), later the fragments of Y''.
     // NT > 0: s_big is one block per wavefront.  A block holds the wavefront's share of the keys' kernel
@@ -978,7 +1043,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
     constexpr int kBigBytes = kKept ? kKeptBytes : kTrBytes;
     static_assert(!kKept || NT == 1 || kTrWave <= 2 * kSlotBytes, "the transposed tile must fit the two slots already fetched");
     __shared__ float s_wave_part[2][WAVES][64];   // per side: the reader of one pass never meets the writers of the next
-    __shared__ float s_tot[2][64];     // cluster == 1: this workgroup's column sums, per side
+    __shared__ __attribute__((aligned(16))) float s_hand[16 * RB * 64];   // the first wavefront's column sums, on their way to the others
     __shared__ float s_g[2][64];       // pivot potentials per side (0 = keys, 1 = queries)
     __shared__ float s_rho[2][64];     // beta_t / colsum_t after the last iteration
     __shared__ float s_csinv[64];      // 1 / colsum_t of the key side after the last iteration
@@ -1012,7 +1077,14 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
     bf16x8* yf_lo = yf_hi + 2 * RB * NB * 64;
     const bool attention = p.mode == MODE_ATTENTION;
 
-    for (int item = blockIdx.x; item < p.num_items; item += gridDim.x) {
+    // Block ids go round the 8 XCDs of the device.  When the grid is one item per workgroup and a multiple
+    // of 8, the items are dealt so that consecutive ones -- the workgroups of one problem, which exchange
+    // sums all the time -- sit on one XCD (measured: a round of the counted exchange between 16 workgroups
+    // takes 0.68 us there against 0.94 us when they are spread over the dies).  Any other mapping is as
+    // correct; this one is only nearer.
+    const bool dealt = (int)gridDim.x == p.num_items && (gridDim.x & 7u) == 0u;
+    const int first_item = dealt ? (int)((blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
+    for (int item = first_item; item < p.num_items; item += gridDim.x) {
         LOT_STAMP(0);
 #ifdef LOT_TRACE
         unsigned long long clk0 = 0;
@@ -1058,7 +1130,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         }
         if (tid < 64) s_beta[tid] = tid < r ? beta_read : 1.f;
         if (tid < 256) (&s_prev[0][0][0])[tid] = 0ull;   // the accumulators start at zero in every launch
-        if (blockIdx.x == 0 && tid == 0 && item == (int)blockIdx.x)
+        if (blockIdx.x == 0 && tid == 0 && item == first_item)
             __hip_atomic_store(p.status + 1, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // this launch; nobody else writes it
         if (p.cluster > 1 && chunk == 0) {
             // The first workgroup of a problem zeroes the problem's accumulators and counters, then
@@ -1086,14 +1158,20 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
         auto collect_w0 = [&](int side, int it, bool final, unsigned long long early) -> bool {
             const int ln = fresh_lane();
             const int rr = opaque_scalar(r);
+            // (everything this needs from LDS is asked for first: the answers arrive while the poll is awaited)
+            const unsigned long long prev = p.cluster > 1 ? s_prev[side][it & 1][ln] : 0ull;
+            const float b = s_beta[ln];
+            const float g_old = s_g[side][ln];
+            float gref = 0.f;
+            if constexpr (NT > 0) gref = s_gref[side][ln];
             float tot = 0.f;
             bool ok = true;
             if (p.cluster > 1) {
                 // every pivot's word carries its own arrival count: complete when all 64 agree
                 const unsigned long long* src = p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + ln;
-                const unsigned long long prev = s_prev[side][it & 1][ln];
                 unsigned long long word = early;   // a poll that was started ahead; validated here
-                ok = __all(((unsigned)((word >> 56) - (prev >> 56)) & 0xffu) == (unsigned)p.cluster);
+                const unsigned arrivals = (unsigned)p.cluster * (unsigned)kPosters;
+                ok = __all(((unsigned)((word >> kCountShift) - (prev >> kCountShift)) & kCountMask) == arrivals);
 #ifdef LOT_TRACE
                 valid_a += ok ? 1 : 0;
 #endif
@@ -1102,26 +1180,30 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     ++repolls;
 #endif
                     word = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (__all(((unsigned)((word >> 56) - (prev >> 56)) & 0xffu) == (unsigned)p.cluster)) { ok = true; break; }
+                    if (__all(((unsigned)((word >> kCountShift) - (prev >> kCountShift)) & kCountMask) == arrivals)) { ok = true; break; }
                     if ((k & 63u) == 63u && gave_up(p.status, p.nonce)) break;
                     __builtin_amdgcn_s_sleep(1);
                 }
                 s_prev[side][it & 1][ln] = word;
-                const unsigned long long mask = (1ull << 56) - 1ull;
+                const unsigned long long mask = (1ull << kCountShift) - 1ull;
                 tot = (float)(long long)((word & mask) - (prev & mask)) * p.fx_unscale;
                 if (!ok && ln == 0) give_up(p.status, p.nonce);
             } else {
-                tot = s_tot[side][ln];
+                // a single workgroup: the totals its wavefronts left in LDS (fixed order of the additions)
+                tot = s_wave_part[side][1][ln];
+#pragma unroll
+                for (int wv = 2; wv < WAVES; ++wv) tot += s_wave_part[side][wv][ln];
             }
+            float g_new = g_old;
             if (ln < rr) {
                 // (sums exchanged in fixed point: one below the resolution reads as half a unit)
                 const float c = fmaxf(tot, p.cluster > 1 ? 0.5f * p.fx_unscale : 1.0e-37f);
-                const float b = s_beta[ln];
                 // (hardware reciprocal and base-2 logarithm, each good to one unit in the last place: this
                 // runs on one wavefront while the others wait for the potentials)
                 const float cinv = rcp_fast(c);
                 if (!final) {
-                    s_g[side][ln] += (p.eps * kLn2) * __builtin_amdgcn_logf((float)opaque_scalar(p.n_side[side]) * b * cinv);
+                    g_new = g_old + (p.eps * kLn2) * __builtin_amdgcn_logf((float)opaque_scalar(p.n_side[side]) * b * cinv);
+                    s_g[side][ln] = g_new;
                 } else {
                     // the last pass's potentials stay: the epilogue rebuilds its coupling from them
                     s_rho[side][ln] = b * cinv;
@@ -1139,7 +1221,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     // spread is within kDriftLimit; otherwise (or when something is not finite) the next pass
                     // of this side recomputes the kernel matrix.
                     const bool lv = ln < rr;
-                    const float d = (s_g[side][ln] - s_gref[side][ln]) * c1;
+                    const float d = (g_new - gref) * c1;
                     const float d0 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, d)));
                     const float rel = d - d0;
                     const float vv = lv ? exp2_fast(rel) : 0.f;
@@ -1179,7 +1261,11 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             LOT_STAMP(9 + 6 * ((it - 1) * 2 + side));   // pass done
             __builtin_amdgcn_s_setprio(3);
             if (p.cluster > 1 && wave == 0 && cit >= 1) {
-                // start the poll now; it completes while this pass's sums are reduced
+                // start the poll now; it completes during the hand-over.  (Started inside the pass -- into a
+                // register or straight into LDS -- it would be there in time, but every reload of a spilled
+                // register in the pass then waits for it as well: measured, the sweeps take 2.3-2.6 us instead
+                // of 1.5.  Sent off before the pass, into LDS, it mostly finds the sums incomplete, and the
+                // second poll then costs a whole round trip: 0.9 us per collect instead of 0.7.)
                 early_word = ldc_u64(coherent_view(p.colacc),
                                      (uint32_t)(((((size_t)2 * g + cside) * 2 + (cit & 1)) * 64 + lane) * 8));
                 // after the very last pass the query side is collected as well
@@ -1187,27 +1273,66 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                     early_word2 = ldc_u64(coherent_view(p.colacc),
                                           (uint32_t)(((((size_t)2 * g + 1) * 2 + (it & 1)) * 64 + lane) * 8));
             }
-            {
-                // this wavefront's column sums: one pivot per lane after the transposing reduction
+            // The first wavefront hands its column sums to the others through LDS and turns to the other
+            // side's sums at once (they do not depend on this pass at all); the others add their shares of
+            // what it left, reduce over the tokens (one pivot per lane after the transposing reduction) and
+            // post: one fire-and-forget atomic per pivot and wavefront, the sum in fixed point (integer
+            // addition: the total does not depend on arrival order) plus one count.  Two workgroup barriers:
+            // the hand-over, and the publication of the updated potentials.
+            constexpr int kUnits = 4 * RB;                         // 16-byte units of a lane's accumulators
+            f32x4* const hand = reinterpret_cast<f32x4*>(s_hand);
+            if (wave == 0) {
+#pragma unroll
+                for (int u = 0; u < kUnits; ++u) {
+                    f32x4 t;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[e] = cs[u >> 2][4 * (u & 3) + e];
+                    hand[u * 64 + lane] = t;
+                }
+            }
+            lds_barrier();
+            LOT_STAMP(10 + 6 * ((it - 1) * 2 + side));   // handed over
+            if (wave == 0) {
+                bool ok = true;
+                if (cit >= 1) ok = collect_w0(cside, cit, cfinal, early_word);
+                if (fresh_lane() == 0) s_okx[side] = ok;
+                LOT_STAMP(11 + 6 * ((it - 1) * 2 + side));   // collected
+            } else {
+                const int u0 = (wave - 1) * kUnits / (WAVES - 1), u1 = wave * kUnits / (WAVES - 1);
+#pragma unroll
+                for (int u = 0; u < kUnits; ++u)
+                {
+                        const f32x4 t = hand[u * 64 + lane];
+                        const float m = (u >= u0 && u < u1) ? 1.f : 0.f;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) cs[u >> 2][4 * (u & 3) + e] = fmaf(t[e], m, cs[u >> 2][4 * (u & 3) + e]);
+                    }
                 float c[16 * RB];
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
                     for (int j = 0; j < 16; ++j) c[16 * mb + j] = cs[mb][j];
-                const float total = reduce_scatter_tokens<16 * RB>(c, i);
+                float tot = reduce_scatter_tokens<16 * RB>(c, i);
                 const int q = RB == 2 ? i : i >> 1;   // accumulator register this lane ended up with
-                s_wave_part[side][wave][32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3)] = total;
+                const int pv = 32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * kg + (q & 3);
+                if (pv >= opaque_scalar(r)) tot = 0.f;   // padding pivots
+                if constexpr (NT > 0) {
+                    if (cheap) tot *= s_v[side][pv];     // a pass over the kept kernel matrix leaves the factor v_t out
+                }
+                // (RB == 1: two lanes hold every total.  One of them posts it; the other posts a zero to the
+                // word 32 further on, which belongs to no pivot: the collecting wavefront waits for all 64 counts)
+                const bool second = RB == 1 && (i & 1) != 0;
+                const int word_of = second ? 32 + pv : pv;
+                if (second) tot = 0.f;
+                if (p.cluster > 1 && kPosters > 1) {
+                    const unsigned long long word = (1ull << kCountShift) + (unsigned long long)__float2ll_rn(tot * p.fx_scale);
+                    __hip_atomic_fetch_add(p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + word_of, word,
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    s_wave_part[side][wave][word_of] = tot;
+                }
+                LOT_STAMP(11 + 6 * ((it - 1) * 2 + side));   // (a posting wavefront: posted)
             }
-            LOT_STAMP(10 + 6 * ((it - 1) * 2 + side));   // own sums reduced
-            if (wave == 0) {
-                // The other side's sums do not depend on this pass at all: they are taken now, while
-                // the slower wavefronts are still arriving, and the updated potentials are published
-                // by the barrier below.
-                bool ok = true;
-                if (cit >= 1) ok = collect_w0(cside, cit, cfinal, early_word);
-                if (fresh_lane() == 0) s_okx[side] = ok;
-            }
-            LOT_STAMP(11 + 6 * ((it - 1) * 2 + side));   // collected
             if (with_u) {
                 // Workgroup total of U in s_u.  The wavefronts dump their accumulators into separate
                 // buffers (s_u itself and the now idle transposition area), in rounds when there are
@@ -1244,26 +1369,16 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
             } else {
                 lds_barrier();
             }
-            LOT_STAMP(12 + 6 * ((it - 1) * 2 + side));   // all wavefronts' sums in LDS, potentials published
-            if (wave == 0) {
+            LOT_STAMP(12 + 6 * ((it - 1) * 2 + side));   // potentials published
+            if (kPosters == 1 && p.cluster > 1 && wave == 1) {
+                // one post per workgroup: the second wavefront adds up what the others left (fixed order)
                 const int ln = fresh_lane();
-                float tot = s_wave_part[side][0][ln];
+                float tot = s_wave_part[side][1][ln];
 #pragma unroll
-                for (int wv = 1; wv < WAVES; ++wv) tot += s_wave_part[side][wv][ln];
-                if (ln >= opaque_scalar(r)) tot = 0.f;   // padding pivots (their LDS slots may never have been written)
-                if constexpr (NT > 0) {
-                    if (cheap) tot *= s_v[side][ln];     // a pass over the kept kernel matrix leaves the factor v_t out
-                }
-                if (p.cluster > 1) {
-                    // one fire-and-forget atomic per pivot: the workgroup's column sum in fixed point
-                    // (integer addition: the total does not depend on arrival order) plus one count
-                    const unsigned long long word = (1ull << 56) + (unsigned long long)__float2ll_rn(tot * p.fx_scale);
-                    __hip_atomic_fetch_add(p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + ln, word,
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                } else {
-                    s_tot[side][ln] = tot;
-                }
-                LOT_STAMP(13 + 6 * ((it - 1) * 2 + side));   // posted
+                for (int wv = 2; wv < WAVES; ++wv) tot += s_wave_part[side][wv][ln];
+                const unsigned long long word = (1ull << kCountShift) + (unsigned long long)__float2ll_rn(tot * p.fx_scale);
+                __hip_atomic_fetch_add(p.colacc + (((size_t)2 * g + side) * 2 + (it & 1)) * 64 + ln, word,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             if (with_u && p.cluster > 1) {
                 float* up = p.u_part + ((size_t)g * p.cluster_cap + chunk) * 64 * D;
@@ -1358,8 +1473,10 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                                 for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
-                        accum_from_kept<IO, D, RB, WAVES, NT>(p, reinterpret_cast<const IO*>(p.V), g, tile_begins[0], tile_ends[0], lane, wave,
-                                                              s_v[0], fill, cs, U, block);
+                        // (a SIMD and its 512 registers to itself: three tiles' value rows in flight; otherwise one)
+                        accum_from_kept<IO, D, RB, WAVES, NT, (WAVES == 4 && NT >= 8 ? LOT_ACCUM_AHEAD : 1)>(
+                            p, reinterpret_cast<const IO*>(p.V), g, tile_begins[0], tile_ends[0], lane, wave,
+                            s_v[0], &s_vhl[0][0][0], fill, cs, U, block);
                         alive = exchange(0, it, true, 1, it - 1, false, !fill);
                     } else {
                         if (side == 0) cheap_pass<IO, RB, WAVES, NT, true>(p, 0, tile_begins[0], tile_ends[0], lane, wave, s_v[0], &s_vhl[0][0][0], fill, cs, kq, kres_wave);

@@ -42,15 +42,15 @@ inline bool fused_supports(const lot_shape& s)
 }
 
 // Fixed-point format of the column sums that the fused kernel's workgroups exchange: a parity buffer
-// receives at most iters/2 + 1 passes, each adding at most n per pivot, and must stay below 2^55 with
-// at least 8 fractional bits.  Returns the number of fractional bits, or a negative number when the
+// receives at most iters/2 + 1 passes, each adding at most n per pivot, and must stay below 2^53 (the
+// top ten bits of a word count the arrivals) with at least 8 fractional bits.  Returns the number of fractional bits, or a negative number when the
 // sums do not fit (astronomical iteration counts only).
 inline int fused_exchange_frac_bits(int n_longer, int iters)
 {
     const double max_sum = ((double)iters / 2.0 + 1.0) * (double)n_longer;
     int bits = 0;
     while (bits < 64 && (double)(1ull << bits) < max_sum + 1.0) ++bits;   // ceil(log2(max_sum + 1))
-    const int frac = 55 - bits;
+    const int frac = 53 - bits;
     return frac >= 8 ? frac : -1;
 }
 inline bool fused_exchange_fits(int n_longer, int iters) { return fused_exchange_frac_bits(n_longer, iters) >= 0; }

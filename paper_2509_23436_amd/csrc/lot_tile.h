@@ -454,6 +454,52 @@ __device__ __forceinline__ void load_values(bf16x8 (&hi)[D / 32], bf16x8 (&lo)[D
     for (int nb = 0; nb < NB; ++nb) split_bf16(t[nb], hi[nb], lo[nb]);
 }
 
+// The same in two steps, for passes that keep the value rows of several tiles in flight: the loads leave
+// what they fetched untouched (one register per row: two bf16 channels for D = 64, one for D = 32), and the
+// operand fragments are formed from those registers only when the tile is multiplied -- formed right behind
+// the loads they would make the wavefront wait for the data at once.  `row_of(s, e)` gives the row of
+// token e of step s (16 tokens in all), already clamped to the tensor.
+template <int D, typename RowOf>
+__device__ __forceinline__ void request_value_rows(uint32_t (&raw)[16], const uint16_t* V, int i, RowOf row_of)
+{
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const size_t row = row_of(s, e);
+            if (D == 64) raw[8 * s + e] = *as_global(reinterpret_cast<const uint32_t*>(V + row * D + 2 * i));
+            else raw[8 * s + e] = as_global(V)[row * D + i];
+        }
+}
+// (all 16 rows in range: `base` points at the lane's element of the first row, the others are constant offsets)
+template <int D>
+__device__ __forceinline__ void request_value_rows_inside(uint32_t (&raw)[16], const uint16_t* base)
+{
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (D == 64) raw[8 * s + e] = *as_global(reinterpret_cast<const uint32_t*>(base + (16 * s + e) * D));
+            else raw[8 * s + e] = as_global(base)[(16 * s + e) * D];
+        }
+}
+template <int D>
+__device__ __forceinline__ void value_fragments(bf16x8 (&hi)[2][D / 32], const uint32_t (&raw)[16])
+{
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        u32x4 lo16, hi16;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t a = raw[8 * s + 2 * k], b = raw[8 * s + 2 * k + 1];
+            lo16[k] = (a & 0xffffu) | (b << 16);
+            hi16[k] = (a >> 16) | (b & 0xffff0000u);
+        }
+        hi[s][0] = __builtin_bit_cast(bf16x8, lo16);
+        if (D == 64) hi[s][D / 32 - 1] = __builtin_bit_cast(bf16x8, hi16);
+    }
+}
+
 template <int NB> __device__ __forceinline__ void store_out(uint16_t* row, int i, float a, float b)
 {
     if (NB == 2) *as_global(reinterpret_cast<uint32_t*>(row + 2 * i)) = (uint32_t)bf16_bits_of(a) | ((uint32_t)bf16_bits_of(b) << 16);
