@@ -225,9 +225,10 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * gradient buffers must not alias the inputs, the workspace or each other.  iters <= 65536.
  * Two execution paths, chosen like the forward ones (lot_path): REFERENCE = one plain kernel per
  * step with the n x r intermediates in the workspace, any shape; FUSED = tiled MFMA kernels that
- * keep nothing of size n x r (d_k = d_v in {32, 64}; r <= 64 with iters <= 32, or 64 < r <= 256 with the
- * pivots in groups of 64, as far as the per-iteration tables fit a workgroup's local memory: bf16 I/O
- * any such r with iters <= 15 at d = 64, fp32 I/O at d = 64 only r <= 128; LOT_ERR_PATH beyond).  AUTO prefers
+ * keep nothing of size n x r (d_k = d_v in {32, 64}; r <= 64, or 64 < r <= 256 with the pivots in groups
+ * of 64; iters <= 64: the per-iteration tables live in a workgroup's local memory, and where those of all
+ * groups do not fit there together the kernel that assembles dQ and dK runs once per run of groups, with
+ * fp32 partial rows in the workspace in between; LOT_ERR_PATH beyond).  AUTO prefers
  * FUSED, except for fewer than 16 tokens and, with fp32 I/O, for r <= 2: there the rounding of the tile
  * kernels' split-bf16 contractions (2^-16) is not averaged out, or is magnified by the cancellation in
  * the gradient of two masses, and the plain kernels, exact to fp32 rounding, run instead.

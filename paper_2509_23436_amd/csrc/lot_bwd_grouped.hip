@@ -54,6 +54,7 @@ struct GbParams {
     float* db_pair;               // [pairs][256]
     float* db_glue;               // [G][256]
     float* dz_part;               // [pairs][chunks][256][D]
+    float* x_part;                // [pairs][n][D]: partial dQ / dK rows between launches of the assemble-x kernel (if several)
     int B;
 };
 
@@ -576,8 +577,12 @@ __device__ __forceinline__ void load_tables(float* tab, float* bvec, const GbPar
 // ---------------------------------------------------------------------------------------------
 // (WAVES wavefronts per workgroup: the tables fill most of a compute unit's local memory, so a second
 // wavefront per SIMD has to come from the same workgroup)
+// Where the tables of all groups do not fit a workgroup's local memory together, the kernel is launched
+// once per run of `nq` consecutive groups (from group q0): every launch but the last leaves its partial
+// rows, in fp32, in `partial` [pair][token][D], and every launch but the first starts from them.
 template <typename IO, int D, int WAVES>
-__global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stage_bytes)
+__global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stage_bytes, int q0, int nq, float* partial,
+                                                            int first, int last)
 {
     constexpr int NB = D / 32;
     constexpr int kStash = StashBytes<IO, D, 2>::value;
@@ -592,7 +597,7 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 31, kg = lane >> 5;
-    const int pairs = 2 * p.f.G, T = p.f.T, groups = p.f.groups;
+    const int pairs = 2 * p.f.G, T = p.f.T, groups = nq;   // (the groups of this launch)
     const int pair = blockIdx.x / p.f.chunks, chunk = blockIdx.x % p.f.chunks;
     const int side = pair / p.f.G, g = pair % p.f.G, h = g % p.f.H;
     const int n = p.f.n_side[side], r = p.f.r;
@@ -612,12 +617,20 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
     bf16x8* s_zf = reinterpret_cast<bf16x8*>(s_yhi + (size_t)groups * kStash * (kSplit ? 1 : 2));
 
     if (tid < T) s_shift[tid] = p.gmax[(size_t)tid * pairs + pair] * c1;
-    stash_all_pivots<IO, D>(s_zstash, p.f.Z, h, r, groups, wave, lane);
+    for (int q = wave; q < groups; q += WAVES) {
+        Frag<IO, D> z0[2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            const int t = kGroup * (q0 + q) + 32 * mb + i;
+            load_pivots<D>(z0[mb], p.f.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
+        }
+        stash_pivots<D, 2>(s_zstash + (size_t)q * kStash, z0, lane);
+    }
     for (int q = 0; q < groups; ++q) {
         // Z rows as B fragments (the values the forward pass multiplied with: rounded to bf16 for bf16 I/O)
         __syncthreads();
         for (int e = tid; e < kGroup * D; e += kThreads) {
-            const int t = kGroup * q + e / D;
+            const int t = kGroup * (q0 + q) + e / D;
             float z = t < r ? p.f.Z[((size_t)h * r + t) * D + e % D] : 0.f;
             if (!kSplit) z = (float)(__bf16)z;
             s_y[e] = z;
@@ -628,11 +641,11 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
         bf16x8* hi = s_zf + (size_t)(kParts * q) * kFragsPerGroup;
         lay_out_fragments<D, 2>(s_y, hi, kSplit ? hi + kFragsPerGroup : reinterpret_cast<bf16x8*>(s_ylo + (size_t)q * kStash), tid);
         stash_matrix_rows<IO, D>(s_yhi + (size_t)q * kStash, s_ylo + (size_t)q * kStash, s_y,
-                                 ymat + (size_t)kGroup * q * D, yscale, tid, wave, lane);
+                                 ymat + (size_t)kGroup * (q0 + q) * D, yscale, tid, wave, lane);
     }
     __syncthreads();
     for (int q = 0; q < groups; ++q)
-        load_tables(s_hist + (size_t)q * T * 2 * kGroup, s_bvec + kGroup * q, p, pair, kGroup * q, c1, tid);
+        load_tables(s_hist + (size_t)q * T * 2 * kGroup, s_bvec + kGroup * q, p, pair, kGroup * (q0 + q), c1, tid);
     __syncthreads();
 
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
@@ -650,6 +663,15 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int j = 0; j < 16; ++j) o[nb][j] = 0.f;
+        const int prow0 = tile * kTileTokens + 4 * kg;
+        float* const pbase = partial + ((size_t)pair * p.f.n + prow0) * D + NB * i;
+        if (!first) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (prow0 + 8 * (j >> 2) + (j & 3) < n)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) o[nb][j] = pbase[(size_t)(8 * (j >> 2) + (j & 3)) * D + nb];
+        }
         for (int q = 0; q < groups; ++q) {
             f32x16 dacc[2], part[NB];
             similarity_gradient<IO, D>(dacc, s_zstash + (size_t)q * kStash, s_yhi + (size_t)q * kStash,
@@ -662,6 +684,14 @@ __global__ void __launch_bounds__(64 * WAVES) gb_assemble_x(GbParams p, int stag
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) o[nb][j] += part[nb][j];
+        }
+        if (!last) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (prow0 + 8 * (j >> 2) + (j & 3) < n)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) pbase[(size_t)(8 * (j >> 2) + (j & 3)) * D + nb] = o[nb][j];
+            continue;
         }
         IO* out = reinterpret_cast<IO*>(side == 0 ? p.dQ : p.dK);
         const int row0 = tile * kTileTokens + 4 * kg;
@@ -815,6 +845,14 @@ inline size_t assemble_x_lds_bytes(bool f32, int D, int groups, int T)
     return assemble_x_stage_bytes(D, groups, T) + groups * stash * (f32 ? 2 : 3) + groups * frags * (f32 ? 2 : 1);
 }
 constexpr size_t kLdsBudget = 160 * 1024 - 2048;    // per workgroup, less the kernel's static arrays
+// Groups of pivots whose tables the assemble-x kernel holds at once: all of them where they fit, otherwise
+// as many as fit (at least one: a group with 64 iterations is 32 KB of tables beside 32-48 KB of operands).
+inline int assemble_x_groups_per_launch(bool f32, int D, int groups, int T)
+{
+    int nq = groups;
+    while (nq > 1 && assemble_x_lds_bytes(f32, D, nq, T) > kLdsBudget) --nq;
+    return nq;
+}
 
 template <typename IO, int D>
 int launch_bwd_grouped(const BwdArgs& a, GbParams p)
@@ -830,8 +868,9 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
     const size_t stash = (size_t)groups * StashBytes<IO, D, 2>::value;
     const size_t frag_bytes = (size_t)groups * 2 * (2 * 2 * NB * 64) * sizeof(bf16x8);
     const size_t glue_bytes = stash * (kSplit ? 2 : 3);
-    const size_t stage = assemble_x_stage_bytes(D, groups, T);
-    const size_t ax_bytes = assemble_x_lds_bytes(kSplit, D, groups, T);
+    const int ax_groups = assemble_x_groups_per_launch(kSplit, D, groups, T);
+    const size_t stage = assemble_x_stage_bytes(D, ax_groups, T);
+    const size_t ax_bytes = assemble_x_lds_bytes(kSplit, D, ax_groups, T);
     const size_t az_bytes = (size_t)T * 2 * kGroup * sizeof(float);
     if (ax_bytes > kLdsBudget || T > 64) return LOT_ERR_PATH;
     // more than 64 KB of LDS per workgroup has to be asked for explicitly
@@ -853,7 +892,11 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
     if (p.f.tiles_per_wg >= 32) gb_glue<IO, D, 8><<<grid, 512, glue_bytes, st>>>(p);
     else gb_glue<IO, D, 4><<<grid, 256, glue_bytes, st>>>(p);
     for (int k = T; k >= 1; --k) gb_rec_pass<IO, D><<<grid, kThreads, stash, st>>>(p, k);
-    gb_assemble_x<IO, D, kAssembleWaves><<<grid, 64 * kAssembleWaves, ax_bytes, st>>>(p, (int)stage);
+    for (int q0 = 0; q0 < groups; q0 += ax_groups) {
+        const int nq = groups - q0 < ax_groups ? groups - q0 : ax_groups;
+        gb_assemble_x<IO, D, kAssembleWaves><<<grid, 64 * kAssembleWaves, ax_bytes, st>>>(
+            p, (int)stage, q0, nq, p.x_part, q0 == 0 ? 1 : 0, q0 + nq >= groups ? 1 : 0);
+    }
     gb_assemble_z<IO, D><<<group_grid(grid, groups), kThreads, az_bytes, st>>>(p);
     gb_final<<<(unsigned)((a.s.H * a.s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), kFinalSlices * kFinalOutputs, 0, st>>>(p, D);
     LOT_HIP_CHECK(hipGetLastError());
@@ -866,7 +909,8 @@ bool bwd_grouped_supports(const lot_shape& s, int iters)
 {
     if (!grouped_supports(s) || iters < 1) return false;
     const int groups = (s.r + kGroup - 1) / kGroup;
-    return assemble_x_lds_bytes(s.io_dtype != LOT_BF16, s.d_k, groups, iters) <= kLdsBudget &&
+    const bool f32 = s.io_dtype != LOT_BF16;
+    return assemble_x_lds_bytes(f32, s.d_k, assemble_x_groups_per_launch(f32, s.d_k, groups, iters), iters) <= kLdsBudget &&
            iters <= 64;
 }
 
@@ -896,6 +940,13 @@ BwdGroupedWorkspace carve_bwd_grouped(const lot_shape& s, int iters)
     w.db_pair = take(pairs * kRmax * 4);
     w.db_glue = take(G * kRmax * 4);
     w.dz_part = take(pairs * chunks * kRmax * D * 4);
+    {
+        // partial dQ / dK rows between the launches of the assemble-x kernel, where it takes several
+        const int groups = (s.r + kGroup - 1) / kGroup;
+        const bool f32 = s.io_dtype != LOT_BF16;
+        const bool several = assemble_x_groups_per_launch(f32, s.d_k, groups, iters) < groups;
+        w.x_part = take(several ? pairs * n * D * 4 : 0);
+    }
     w.total = off;
     return w;
 }
@@ -925,6 +976,7 @@ int run_backward_grouped(const BwdArgs& a)
     p.db_pair = (float*)(a.ws + L.db_pair);
     p.db_glue = (float*)(a.ws + L.db_glue);
     p.dz_part = (float*)(a.ws + L.dz_part);
+    p.x_part = (float*)(a.ws + L.x_part);
     p.B = s.B;
     p.f.G = s.B * s.H; p.f.H = s.H; p.f.n = s.n; p.f.r = s.r;
     p.f.n_side[0] = a.n_q > 0 ? a.n_q : s.n;      // s.n is the longer side (cross attention)

@@ -1450,8 +1450,9 @@ int launch_all(const BwdArgs& a, BtParams p)
 
 bool bwd_tiled_supports(const lot_shape& s, int iters)
 {
-    // the assemble kernel keeps the potentials and column-sum adjoints of all iterations in LDS
-    return fused_supports(s) && iters <= 32;
+    // the assemble kernel keeps the potentials and column-sum adjoints of all iterations in LDS: 512 bytes
+    // per iteration beside up to 107 KB of operands
+    return fused_supports(s) && iters <= 64;
 }
 
 BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters)

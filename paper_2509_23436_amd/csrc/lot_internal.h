@@ -196,7 +196,7 @@ int run_grouped(const Args& a);          // attention only; LOT_ERR_PATH outside
 
 // Backward for 64 < r <= 256 (pivots in groups of 64; uniform token masses).
 struct BwdGroupedWorkspace {
-    size_t colacc, ghist, rowlse, erow, u_part, yp, dyraw, ydv, rhop, s_part, dg_part, dcs, gmax, db_pair, db_glue, dz_part;
+    size_t colacc, ghist, rowlse, erow, u_part, yp, dyraw, ydv, rhop, s_part, dg_part, dcs, gmax, db_pair, db_glue, dz_part, x_part;
     size_t total;      // status words at offset 0
     int chunks;
 };

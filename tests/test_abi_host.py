@@ -222,8 +222,8 @@ def test_backward_rejects_bad_arguments(L):
                      (dict(eps=0.0), -3), (dict(iters=0), -4), (dict(dO=0x5004), -7), (dict(dZ=0x7002), -7),
                      (dict(ws=(1 << 20) + 8), -6), (dict(ws_bytes=64), -6), (dict(path=5), -9),
                      (dict(path=2, shape=_shape(r=300)), -9), (dict(path=2, shape=_shape(d_k=48, d_v=48)), -9),
-                     (dict(path=2, shape=_shape(r=200, d_k=64, d_v=64)), -9),   # fp32, d = 64, more than 128 pivots: plain kernels only
-                     (dict(path=2, iters=40), -9)):
+                     (dict(path=2, iters=65), -9),       # the tile kernels' per-iteration tables: 64 iterations at most
+                     (dict(path=2, iters=65, shape=_shape(r=200, d_k=64, d_v=64)), -9)):
         assert call(**kw) == code, (kw, code)
 
 

@@ -42,6 +42,14 @@ CASES = {
     "grouped_f32_one_iteration": S(W["tiny"], B=1, H=1, n=97, d=32, r=100, eps=0.1, iters=1, seed=79),
     "grouped_bf16_r256": S(W["long_4k"], B=1, H=2, n=1500, r=256, iters=5, seed=80),
     "grouped_bf16_r130_d32": S(W["swin_t_s1"], B=2, H=1, n=700, r=130, iters=6, seed=81),
+    # more iterations than the tile kernels took at first (their per-iteration tables: 32 at most then)
+    "forty_iterations_f32": S(W["tiny"], B=1, H=2, n=150, d=32, r=24, iters=40, seed=84),
+    "sixty_four_iterations_bf16": S(W["swin_t_s1"], B=1, H=2, n=333, iters=64, seed=85),
+    # more than 64 pivots where the tables of all groups do not fit a workgroup's local memory together: the
+    # kernel that assembles dQ and dK runs once per run of groups, with fp32 partial rows in between
+    "grouped_f32_r256_d64": S(W["tiny"], B=1, H=2, n=500, d=64, r=256, eps=0.1, iters=3, seed=86),
+    "grouped_bf16_r256_twenty_iterations": S(W["long_4k"], B=1, H=2, n=1500, r=256, iters=20, seed=87),
+    "grouped_bf16_r200_forty_iterations": S(W["long_4k"], B=1, H=1, n=900, r=200, eps=0.1, iters=40, seed=88),
 }
 
 
@@ -50,9 +58,8 @@ def _say(msg):
 
 
 def _paths_for(w):
-    tiled = w.d in (32, 64) and w.r <= 64 and w.iters <= 32
-    # pivots in groups of 64: what the largest kernel's tables leave room for in a workgroup's local memory
-    grouped = w.d in (32, 64) and 64 < w.r <= (256 if w.dtype == "bf16" or w.d == 32 else 128) and w.iters <= 10
+    tiled = w.d in (32, 64) and w.r <= 64 and w.iters <= 64
+    grouped = w.d in (32, 64) and 64 < w.r <= 256 and w.iters <= 64     # pivots in groups of 64
     return ["reference", "fused"] if tiled or grouped else ["reference"]
 
 

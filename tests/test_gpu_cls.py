@@ -101,8 +101,8 @@ BWD_CASES = {
 
 
 def _bwd_paths(w):
-    tiled = w.d in (32, 64) and w.r <= 64 and w.iters <= 32
-    grouped = w.d in (32, 64) and 64 < w.r <= 128 and w.iters <= 10
+    tiled = w.d in (32, 64) and w.r <= 64 and w.iters <= 64
+    grouped = w.d in (32, 64) and 64 < w.r <= 256 and w.iters <= 64
     return ["reference", "fused"] if tiled or grouped else ["reference"]
 
 
