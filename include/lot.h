@@ -80,9 +80,15 @@ typedef struct {
 typedef enum {
     LOT_PATH_AUTO = 0,
     LOT_PATH_REFERENCE = 1,  /* one plain kernel per step, similarities materialised (any shape) */
-    LOT_PATH_FUSED = 2       /* MFMA kernels; d_k = d_v in {32, 64}: r <= 64 one kernel per call (see
+    LOT_PATH_FUSED = 2,      /* MFMA kernels; d_k = d_v in {32, 64}: r <= 64 one kernel per call (see
                                 lot_forward_kernels for its families), 64 < r <= 256 grouped kernels, one
                                 launch per step (attention only) */
+    LOT_PATH_STEPWISE = 3    /* the same MFMA tile code with launch boundaries as the only synchronisation
+                                between workgroups (one launch per Sinkhorn pass; no kernel waits for
+                                another workgroup): for a device that kernels of other streams share, where
+                                the persistent kernels' grids may not become resident together (see "Waits
+                                between workgroups" below).  d_k = d_v in {32, 64}, r <= 256; attention and
+                                its backward, the [CLS] and cross variants; not lot_couplings */
 } lot_path;
 
 /*
@@ -307,7 +313,10 @@ int lot_attention_cls_bwd_path(const lot_shape* shape, const void* Q, const void
  *                               host_words (pinned host memory, 16 bytes, owned by the caller); no
  *                               synchronisation.  Once the stream has passed that point,
  *   lot_status_words            (host only) turns the two words into LOT_OK or LOT_ERR_SYNC.
- * The next call on the same workspace is unaffected by an earlier failure.
+ * The next call on the same workspace is unaffected by an earlier failure.  A caller that shares the device
+ * with other streams' kernels can avoid the waits altogether with LOT_PATH_STEPWISE (same results to
+ * rounding, T + 4 launches instead of one); the Python autograd wrapper raises on a reported failure
+ * and runs its later AUTO calls on that path.
  */
 int lot_workspace_status(const void* workspace);
 int lot_workspace_status_async(const void* workspace, unsigned long long* host_words, void* hip_stream);

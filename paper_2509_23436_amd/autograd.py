@@ -21,6 +21,9 @@ Failed waits: after every call the two status words of its workspace are copied 
 on the same stream (no synchronisation); every later call first looks at the copies that have arrived
 and raises if one of them reports a wait between workgroups that gave up (see include/lot.h; the rows
 such a call left unwritten are NaN in any case).  `check_pending(wait=True)` waits for all of them.
+After such a report the calls that were left to choose their kernels (path = lot.PATH_AUTO) run on
+lot.PATH_STEPWISE where the shape allows it: the same tile kernels, one launch per Sinkhorn pass, no waits
+between workgroups, so whatever shares the device cannot make them fail again (`stepwise_after_failure`).
 """
 import torch
 
@@ -28,6 +31,7 @@ from . import lot
 
 _workspaces = {}
 _pending = []
+stepwise_after_failure = False      # set by check_pending at the first reported failure; may be reset by the caller
 
 
 def _workspace(kind, size_fn, shape_key, device, shape, iters, path):
@@ -52,8 +56,22 @@ def check_pending(wait=False):
             still.append((what, probe))
     _pending[:] = still
     if bad is not None:
+        global stepwise_after_failure
+        stepwise_after_failure = True
         raise RuntimeError("libLOT: a wait between workgroups gave up during %s (another stream's kernel held "
                            "compute units while it started?); its result is marked with NaN" % bad)
+
+
+def _resolve(path, shape, iters, fwd_size, bwd_size):
+    """AUTO -> STEPWISE once a wait has failed in this process, where both passes support the shape on it."""
+    if path != lot.PATH_AUTO or not stepwise_after_failure:
+        return path
+    try:
+        fwd_size(shape, iters, lot.PATH_STEPWISE)
+        bwd_size(shape, iters, lot.PATH_STEPWISE)
+    except RuntimeError:
+        return path
+    return lot.PATH_STEPWISE
 
 
 def _after(what, ws):
@@ -75,10 +93,11 @@ class _LOTAttention(torch.autograd.Function):
     def forward(ctx, Q, K, V, Z, beta, eps, iters, path):
         Q, K, V, Z, beta = (t.contiguous() for t in (Q, K, V, Z, beta))
         ctx.save_for_backward(Q, K, V, Z, beta)
-        ctx.cfg = (float(eps), int(iters), int(path))
         check_pending()
         lot._dims(Q, K, V, Z, beta)
         shape, key = _fwd_shape(Q, V, Z)
+        path = _resolve(path, shape, iters, lot.lot_workspace_bytes, lot.lot_attention_bwd_workspace_bytes)
+        ctx.cfg = (float(eps), int(iters), int(path))
         ws = _workspace("fwd", lot.lot_workspace_bytes, key, Q.device, shape, iters, path)
         out = lot.lot_attention_fwd(Q, K, V, Z, beta, eps, iters, workspace=ws, path=path)
         _after("lot_attention (forward)", ws)
@@ -101,10 +120,11 @@ class _LOTAttentionCls(torch.autograd.Function):
     def forward(ctx, Q, K, V, Z, beta, eps, iters, beta_cls, path):
         Q, K, V, Z, beta = (t.contiguous() for t in (Q, K, V, Z, beta))
         ctx.save_for_backward(Q, K, V, Z, beta)
-        ctx.cfg = (float(eps), int(iters), float(beta_cls), int(path))
         check_pending()
         lot._dims(Q, K, V, Z, beta)
         shape, key = _fwd_shape(Q, V, Z)
+        path = _resolve(path, shape, iters, lot.lot_workspace_bytes, lot.lot_attention_bwd_workspace_bytes)
+        ctx.cfg = (float(eps), int(iters), float(beta_cls), int(path))
         ws = _workspace("fwd", lot.lot_workspace_bytes, key, Q.device, shape, iters, path)
         out = lot.lot_attention_cls_fwd(Q, K, V, Z, beta, eps, iters, beta_cls, workspace=ws, path=path)
         _after("lot_attention_cls (forward)", ws)
@@ -131,10 +151,11 @@ class _LOTCrossAttention(torch.autograd.Function):
         mass_k = None if mass_k is None else mass_k.contiguous()
         ctx.save_for_backward(Q, K, V, Z, beta)
         ctx.masses = (mass_q, mass_k)
-        ctx.cfg = (float(eps), int(iters), int(path))
         check_pending()
         lot._dims(Q, K, V, Z, beta, cross=True)
         shape, key = _cross_shape(Q, K, V, Z)
+        path = _resolve(path, shape, iters, lot.lot_cross_workspace_bytes, lot.lot_cross_attention_bwd_workspace_bytes)
+        ctx.cfg = (float(eps), int(iters), int(path))
         ws = _workspace("xfwd", lot.lot_cross_workspace_bytes, key, Q.device, shape, iters, path)
         out = lot.lot_cross_attention_fwd(Q, K, V, Z, beta, eps, iters, mass_q=mass_q, mass_k=mass_k, workspace=ws,
                                           path=path)

@@ -122,7 +122,7 @@ constexpr int kMinFusedTokens = 16;
 // the grouped kernels do not serve.
 static int pick_forward(const lot_shape& s, int n_short, int iters, int path, bool couplings, FwdImpl* impl)
 {
-    const bool grouped = !couplings && grouped_supports(s);
+    const bool grouped = !couplings && grouped_supports(s) && s.r > 64;
     const bool fused = fused_supports(s);
     // (astronomical iteration counts whose column sums do not fit the fused kernel's fixed-point
     // exchange format go to the plain kernels under AUTO)
@@ -136,6 +136,10 @@ static int pick_forward(const lot_shape& s, int n_short, int iters, int path, bo
         if (grouped) { *impl = FWD_GROUPED; return LOT_OK; }
         if (!fused || !fits) return LOT_ERR_PATH;
         *impl = FWD_FUSED;
+        return LOT_OK;
+    case LOT_PATH_STEPWISE:      // the grouped kernels take any r <= 256: launch boundaries only
+        if (couplings || !grouped_supports(s)) return LOT_ERR_PATH;
+        *impl = FWD_GROUPED;
         return LOT_OK;
     default: return LOT_ERR_PATH;
     }
@@ -507,6 +511,10 @@ static int pick_backward(const lot_shape& s, int n_short, int iters, int path, B
         if (!one_tile && !grouped) return LOT_ERR_PATH;
         *impl = tile_impl;
         return LOT_OK;
+    case LOT_PATH_STEPWISE:      // BWD_TILED then runs its forward sweep as one launch per pass
+        if (!one_tile && !grouped) return LOT_ERR_PATH;
+        *impl = tile_impl;
+        return LOT_OK;
     default: return LOT_ERR_PATH;
     }
 }
@@ -577,7 +585,7 @@ static int backward_impl(const lot_shape* shape, const void* Q, const void* K, c
     a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
     a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
-    a.n_stride = n_stride;
+    a.n_stride = n_stride; a.stepwise = path == LOT_PATH_STEPWISE;
     if (impl == BWD_PLAIN) return run_backward(a);
     return impl == BWD_TILED ? run_backward_tiled(a) : run_backward_grouped(a);
 }
@@ -636,6 +644,7 @@ int lot_cross_attention_bwd_path(const lot_xshape* shape, const void* Q, const v
     a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.dZ = dZ; a.dbeta = dbeta;
     a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream;
     a.n_q = shape->n_q; a.n_k = shape->n_k; a.mass_q = mass_q; a.mass_k = mass_k;
+    a.stepwise = path == LOT_PATH_STEPWISE;
     if (impl != BWD_PLAIN) return impl == BWD_TILED ? run_backward_tiled(a) : run_backward_grouped(a);
     a.lay = carve_bwd_sides(shape->B, shape->H, shape->n_q, shape->n_k, shape->r, shape->d_k, shape->d_v, iters);
     return run_backward(a);

@@ -907,7 +907,7 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
 
 bool bwd_grouped_supports(const lot_shape& s, int iters)
 {
-    if (!grouped_supports(s) || iters < 1) return false;
+    if (!grouped_supports(s) || s.r <= 64 || iters < 1) return false;
     const int groups = (s.r + kGroup - 1) / kGroup;
     const bool f32 = s.io_dtype != LOT_BF16;
     return assemble_x_lds_bytes(f32, s.d_k, assemble_x_groups_per_launch(f32, s.d_k, groups, iters), iters) <= kLdsBudget &&

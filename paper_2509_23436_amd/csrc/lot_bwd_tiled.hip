@@ -1409,7 +1409,7 @@ int launch_all(const BwdArgs& a, BtParams p)
     }
     // testing aid: run the sweep as one launch per pass although it would fit (the fallback of devices
     // that cannot hold the grid), so that this form stays exercised
-    if (sweep_by_launches()) persistent = false;
+    if (sweep_by_launches() || a.stepwise) persistent = false;
     const bool mass = p.mass_side[0] != nullptr || p.mass_side[1] != nullptr;
     if (persistent) {
         if (mass) bt_sweep<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);

@@ -1,5 +1,6 @@
 // LOT attention forward for pivot sizes beyond one register tile: 64 < r <= 256, d_k = d_v in
-// {32, 64}.  (The paper's runtime study sweeps r up to 256.)  Same method as the fused kernel --
+// {32, 64}.  (The paper's runtime study sweeps r up to 256.)  Smaller r runs here too when the caller asks
+// for a path on which no kernel waits for another workgroup.  Same method as the fused kernel --
 // similarities by MFMA, log-domain Sinkhorn with implicit token potentials, factored apply -- with the
 // pivots taken in groups of 64:
 //   * a pass keeps the similarities of all groups of a tile of 32 tokens in registers (up to 128 per
@@ -146,7 +147,7 @@ int launch_grouped(const Args& a, LgParams p)
 
 bool grouped_supports(const lot_shape& s)
 {
-    return s.d_k == s.d_v && (s.d_k == 32 || s.d_k == 64) && s.r > 64 && s.r <= kRmax;
+    return s.d_k == s.d_v && (s.d_k == 32 || s.d_k == 64) && s.r <= kRmax;
 }
 
 GroupedWorkspace carve_grouped(const lot_shape& s, int iters)

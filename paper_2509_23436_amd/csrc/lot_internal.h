@@ -173,6 +173,7 @@ struct BwdArgs {
     char* ws;
     BwdWorkspace lay;
     hipStream_t stream;
+    bool stepwise;         // no kernel may wait for another workgroup: the tiled sweep runs one launch per pass
 };
 
 // Workspace of the backward pass, tiled path.
@@ -184,7 +185,8 @@ struct BwdTiledWorkspace {
 bool bwd_tiled_supports(const lot_shape& s, int iters);
 BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters);
 
-// Forward for 64 < r <= 256 (pivots in groups of 64; one launch per step).
+// Forward with the pivots in groups of 64, one launch per step: 64 < r <= 256 under AUTO, any r <= 256 for a
+// caller that asks for launch boundaries as the only synchronisation between workgroups.
 struct GroupedWorkspace {
     size_t colacc, ghist, u_part, ypp, rowlse;   // status words at offset 0
     size_t total;

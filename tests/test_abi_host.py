@@ -89,6 +89,15 @@ def test_workspace_is_sized_for_the_kernels_that_run(L):
     two = _shape(n=4096, r=2)
     assert _need(L.lot_attention_bwd_workspace_bytes, two, 5) == \
         _need(L.lot_attention_bwd_workspace_bytes_path, two, 5, lot.PATH_REFERENCE)
+    # the path without waits between workgroups: the grouped kernels' few megabytes at any r <= 256, the same
+    # backward workspace as the tile kernels otherwise use; not for lot_couplings, not outside d in {32, 64}
+    assert _need(L.lot_workspace_bytes_path, headline, 10, lot.PATH_STEPWISE) <= 32 * MB
+    assert _need(L.lot_workspace_bytes_path, corner, 5, lot.PATH_STEPWISE) == _need(L.lot_workspace_bytes, corner, 5)
+    assert _need(L.lot_attention_bwd_workspace_bytes_path, headline, 10, lot.PATH_STEPWISE) == \
+        _need(L.lot_attention_bwd_workspace_bytes, headline, 10)
+    assert L.lot_couplings_workspace_bytes(ctypes.byref(headline), 10, lot.PATH_STEPWISE, ctypes.byref(out)) == -9
+    assert L.lot_workspace_bytes_path(ctypes.byref(_shape(d_k=128, d_v=128)), 5, lot.PATH_STEPWISE, ctypes.byref(out)) == -9
+    assert L.lot_workspace_bytes_path(ctypes.byref(_shape(r=300)), 5, lot.PATH_STEPWISE, ctypes.byref(out)) == -9
     # cross attention
     x = lot.lot_xshape(2, 8, 16384, 4096, 64, 64, 64, lot.LOT_BF16)
     assert _need(L.lot_cross_workspace_bytes, x, 10) <= 32 * MB

@@ -60,7 +60,8 @@ def _say(msg):
 def _paths_for(w):
     tiled = w.d in (32, 64) and w.r <= 64 and w.iters <= 64
     grouped = w.d in (32, 64) and 64 < w.r <= 256 and w.iters <= 64     # pivots in groups of 64
-    return ["reference", "fused"] if tiled or grouped else ["reference"]
+    # "stepwise": the same tile kernels with launch boundaries as the only synchronisation between workgroups
+    return ["reference", "fused", "stepwise"] if tiled or grouped else ["reference"]
 
 
 @pytest.mark.parametrize("name,path_name", [(nm, pn) for nm in CASES for pn in _paths_for(CASES[nm])])
@@ -68,7 +69,7 @@ def test_backward_matches_oracle(name, path_name):
     import torch
     from oracle import lot_oracle_bwd
     from paper_2509_23436_amd import lot
-    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED}[path_name]
+    path = {"reference": lot.PATH_REFERENCE, "fused": lot.PATH_FUSED, "stepwise": lot.PATH_STEPWISE}[path_name]
     w = CASES[name]
     _say("case %s path %s: %r" % (name, path_name, w))
     x = synth.make_inputs(w)

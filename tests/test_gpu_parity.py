@@ -110,6 +110,44 @@ def test_attention_and_couplings_match_oracle(name, path_name):
     assert gerr <= 1e-4
 
 
+# The path on which no kernel waits for another workgroup (launch boundaries only): the grouped tile kernels,
+# here also with r <= 64, on every case whose head width they take.  Same bars.
+STEPWISE = [nm for nm, w in CASES.items() if w.d in (32, 64) and w.n >= 16]
+
+
+@pytest.mark.parametrize("name", STEPWISE)
+def test_stepwise_path_matches_oracle(name):
+    import torch
+    from paper_2509_23436_amd import lot
+    w = CASES[name]
+    _say("case %s path stepwise: %r" % (name, w))
+    x, O_ref, _, _ = _oracle_case(name)
+    dev = to_device(x, w.dtype)
+    shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
+    assert lot.lot_forward_kernels(shape, w.iters, lot.PATH_STEPWISE) == "grouped"
+    ws = lot.alloc_workspace(shape, w.iters, path=lot.PATH_STEPWISE)
+    ws.fill_(0xA5)                                  # whatever an earlier call left there must not matter
+    out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters,
+                                workspace=ws, path=lot.PATH_STEPWISE)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(ws) == 0
+    O = to_host_f64(out)
+    assert np.isfinite(O).all()
+    err = rel_max_err(O, O_ref)
+    _say("  O: max-norm rel err %.3e (bar %.0e)" % (err, tolerance(w.dtype)[0]))
+    assert err <= tolerance(w.dtype)[0]
+    # no wait exists on this path: a poll budget of zero changes nothing
+    lot.lot_debug_set(lot.KNOB_SPIN_LIMIT, 0)
+    try:
+        again = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters,
+                                      workspace=ws, path=lot.PATH_STEPWISE)
+        torch.cuda.synchronize()
+        assert lot.lot_workspace_status(ws) == 0
+    finally:
+        lot.lot_debug_set(lot.KNOB_SPIN_LIMIT, -1)
+    assert torch.equal(again, out)
+
+
 # An ordinary fp32 Z (a learnable pivot) under bf16 I/O: the harness does NOT round it, the oracle takes
 # it as it is, and whatever the library does with it (it feeds bf16 operands to the matrix cores) is
 # part of the error.  Shapes of the BERT, Swin and long-context workloads (batch shrunk so that the
