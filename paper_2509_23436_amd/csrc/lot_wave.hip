@@ -1,5 +1,7 @@
 // LOT attention forward for short sequences: one workgroup of two wavefronts per (batch, head) problem,
-// wavefront 0 the keys' solve, wavefront 1 the queries'.
+// wavefront 0 the keys' solve, wavefront 1 the queries' -- or, for sides of up to 64 NT tokens, WS = 2
+// wavefronts per side, each holding half of the side's tiles, which add up their column sums through
+// local memory once per iteration (the only workgroup barrier of an iteration).
 //
 // A side of at most 32 NT tokens has a kernel matrix exp(C/eps) of NT tiles of 32 tokens x 32 RB
 // pivots, which one wavefront can hold in its registers (bf16 pairs for bf16 I/O, fp32 for fp32 I/O;
@@ -29,7 +31,14 @@ struct WaveParams {
     int stride_side[2];   // tokens between consecutive problems in memory
     float eps;
     float drift_half;     // a pivot's potential may move this many binary orders away from pivot 0's before the kernel matrix is recomputed
+    unsigned long long* trace;   // LOT_TRACE builds only: 32 stamps for the first wavefront of each side, 128 per workgroup
 };
+
+#ifdef LOT_TRACE
+#define LOT_WSTAMP(slot) do { if (lane == 0 && part == 0 && p.trace) p.trace[(size_t)blockIdx.x * 128 + side * 32 + (slot)] = wall_clock64(); } while (0)
+#else
+#define LOT_WSTAMP(slot) do { } while (0)
+#endif
 
 // pivot that lane (i, kg) holds after reduce_scatter_tokens<16 RB>
 template <int RB> __device__ __forceinline__ int reduced_pivot(int i, int kg)
@@ -45,41 +54,95 @@ __device__ __forceinline__ void wave_sync_lds()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <typename IO, int D, int RB, int NT>
-__global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) lot_wave_kernel(WaveParams p)
+// WS wavefronts per side (the first WS of the workgroup are the keys'), NT tiles per wavefront; WPE wavefronts
+// share a SIMD's registers (1: all 512 for one wavefront; 2: twice as many problems resident).
+// One word of every 128-byte line of `bytes` bytes from `base` (at most 64 kLoads lines): the lines are then
+// on their way into the caches while the wavefront works on something else, and the loads that later fetch
+// the rows find them there.  The words are handed back so that the caller can keep them alive until a point
+// where waiting for them costs nothing (a dropped result would let the register be reused while the load is
+// still in flight).
+template <int kLoads>
+__device__ __forceinline__ void touch_lines(uint32_t (&word)[kLoads], const void* base, int bytes, int lane)
+{
+    const int lines = (bytes + 127) / 128;
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+        const int line = min(lane + 64 * k, lines - 1);
+        word[k] = lines > 0 ? *as_global(reinterpret_cast<const uint32_t*>(static_cast<const char*>(base) + (size_t)line * 128)) : 0u;
+    }
+}
+template <int kLoads> __device__ __forceinline__ void touched(const uint32_t (&word)[kLoads])
+{
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) asm volatile("" ::"v"(word[k]));
+}
+
+template <typename IO, int D, int RB, int NT, int WS, int WPE>
+__global__ void __launch_bounds__(128 * WS) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) lot_wave_kernel(WaveParams p)
 {
     constexpr int NB = D / 32;
     constexpr int NW = ResWords<IO, RB>::value;
     constexpr bool kSplit = io_is_f32<IO>::value;
     constexpr bool kPieces = io_is_f32<IO>::value;
-    __shared__ __attribute__((aligned(16))) float s_vec[2][64];       // per side: a per-pivot vector on its way into tile layout
-    __shared__ __attribute__((aligned(16))) float s_fac[64];          // keys: v_t / colsum_t, the factor of the rows of U
+    __shared__ __attribute__((aligned(16))) float s_vec[2 * WS][64];  // per wavefront: a per-pivot vector on its way into tile layout
+    __shared__ __attribute__((aligned(16))) float s_part[WS > 1 ? 2 : 1][2 * WS][64];   // column sums of a side's wavefronts (two parities)
+    __shared__ __attribute__((aligned(16))) float s_fac[WS][64];      // keys: v_t / colsum_t, the factor of the rows of U
     __shared__ __attribute__((aligned(16))) float s_qs[64];           // queries: n rho_t v_t
-    __shared__ __attribute__((aligned(16))) float s_u[64 * D];        // U, then Y'
-    __shared__ __attribute__((aligned(16))) uint16_t s_tr[2 * 32 * RB * kTrStride];   // keys: transposed tile (hi, lo)
+    constexpr int kUBufs = WS < 2 ? WS : 2;
+    __shared__ __attribute__((aligned(16))) float s_u[kUBufs][64 * D];   // the key wavefronts' shares of U, scaled to Y' (wavefronts 2, 3 add to 0, 1)
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[WS][2 * 32 * RB * kTrStride];   // keys: transposed tile (hi, lo)
     __shared__ __attribute__((aligned(16))) bf16x8 s_yf[2][2 * RB * NB * 64];         // Y'' as MFMA operand fragments (hi, lo)
     __shared__ __attribute__((aligned(16))) char s_zf[kPieces ? PieceStashBytes<D, RB>::value : 16];
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int side = __builtin_amdgcn_readfirstlane(tid >> 6);       // 0: keys, 1: queries
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int side = wave / WS, part = wave % WS;                    // side 0: keys, 1: queries
     const int i = lane & 31, kg = lane >> 5;
     const int g = blockIdx.x, h = g % p.H;
     const int r = p.r;
     const int n = p.n_side[side], stride = p.stride_side[side];
     const float c1 = kLog2e / p.eps;
+    // this wavefront's tiles: NT consecutive ones from tile part * NT of the side (tok0 = its first token)
+    const int tok0 = part * NT * kTileTokens;
+    // (none of them below n: an idle wavefront, which still takes part in every barrier; token indices are
+    // clamped to n - 1 wherever they form an address)
     const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.K : p.Q) + (size_t)g * stride * D;
-    const int ntiles = (n + kTileTokens - 1) / kTileTokens;
+    const int ntiles = max(0, min((n + kTileTokens - 1) / kTileTokens - part * NT, NT));
 
-    // ---- pivots
-    Frag<IO, D> zf[RB];
+    LOT_WSTAMP(0);
+    // ---- pivots: operand fragments, needed only where the kernel matrix is computed (loaded there: held in
+    //      registers through the iterations they would only take room)
+    auto load_all_pivots = [&](Frag<IO, D> (&zf)[RB]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int mb = 0; mb < RB; ++mb) {
-        const int t = 32 * mb + i;
-        load_pivots<D>(zf[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
-    }
+        for (int mb = 0; mb < RB; ++mb) {
+            const int t = 32 * mb + i;
+            load_pivots<D>(zf[mb], p.Z + ((size_t)h * r + min(t, r - 1)) * D, kg, t < r);
+        }
+    };
+#ifdef LOT_TRACE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    LOT_WSTAMP(21);
+#endif
     // the first tile's rows
     Frag<IO, D> xc;
-    load_tokens<D>(xc, X + (size_t)min(i, n - 1) * D, kg);
+    load_tokens<D>(xc, X + (size_t)min(tok0 + i, n - 1) * D, kg);
+    // the rows of the tiles that the first pass does not request at once (it keeps kAhead tiles in flight) and,
+    // on the keys' side, the value rows of the last sweep: touched now, so that they stream in from memory
+    // while the first tiles and the iterations are worked on
+    constexpr int kAheadMax = WPE >= 2 ? 2 : 4;      // (half of a SIMD's registers has no room for four tiles' rows)
+    constexpr int kAhead = NT < kAheadMax ? NT : kAheadMax;
+    constexpr int kRowBytes = D * (int)sizeof(IO);
+    constexpr int kTouchX = NT > kAhead ? ((NT - kAhead) * kTileTokens * kRowBytes / 128 + 63) / 64 : 1;
+    constexpr int kTouchV = (NT * kTileTokens * kRowBytes / 128 + 63) / 64;
+    uint32_t touch_x[kTouchX], touch_v[kTouchV];
+    {
+        const int first = tok0 + kAhead * kTileTokens, last = min(n, tok0 + NT * kTileTokens);
+        touch_lines<kTouchX>(touch_x, X + (size_t)min(first, n - 1) * D, NT > kAhead ? max(last - first, 0) * kRowBytes : 0, lane);
+    }
+#ifdef LOT_TRACE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    LOT_WSTAMP(22);
+#endif
     // this lane's pivot in the layout the column sums are reduced to
     const int piv = reduced_pivot<RB>(i, kg);
     const bool live = piv < r;
@@ -87,7 +150,11 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
     const float nbeta = (float)n * beta_l;
     float g_l = 0.f, gref_l = 0.f;        // this pivot's potential, and the one folded into the kept matrix
     if constexpr (kPieces) {
-        if (side == 0) stash_pivot_pieces<D, RB>(s_zf, zf, lane);
+        if (wave == 0) {
+            Frag<IO, D> zf[RB];
+            load_all_pivots(zf);
+            stash_pivot_pieces<D, RB>(s_zf, zf, lane);
+        }
         __syncthreads();
     }
 
@@ -100,13 +167,15 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
     // ---- the kernel matrix with the current potentials folded in (zero at first; -big for padding pivots).
     //      A single wavefront per SIMD has nobody to switch to while it waits for memory, so the rows of
     //      kAhead tiles are kept in flight.
-    constexpr int kAhead = NT < 4 ? NT : 4;
     auto fill = [&](bool first) __attribute__((always_inline)) {
+        Frag<IO, D> zf[RB];
+        if constexpr (!kPieces) load_all_pivots(zf);
         f32x16 gv[RB];
-        s_vec[side][piv] = live ? g_l : kNegBig;
+        s_vec[wave][piv] = live ? g_l : kNegBig;
         wave_sync_lds();
-        load_pivot_vector<RB>(gv, s_vec[side], kg);
+        load_pivot_vector<RB>(gv, s_vec[wave], kg);
         wave_sync_lds();
+        if (first) LOT_WSTAMP(20);
         // (addresses are formed from a lane index that the compiler cannot see through: hoisted out of the
         // iteration loop, the addresses of all slots would be hundreds of live registers)
         int io = i;
@@ -115,7 +184,7 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
         for (int a = 0; a < kAhead; ++a) {
             if (a == 0 && first) xs[0] = xc;      // (requested before the pivots were loaded)
-            else if (a < ntiles) load_tokens<D>(xs[a], X + (size_t)min(a * kTileTokens + io, n - 1) * D, kg);
+            else if (a < ntiles) load_tokens<D>(xs[a], X + (size_t)min(tok0 + a * kTileTokens + io, n - 1) * D, kg);
         }
 #pragma unroll
         for (int slot = 0; slot < NT; ++slot) {
@@ -127,7 +196,7 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
                 else similarity<D, RB>(acc, zf, xs[slot % kAhead]);
                 if (slot + kAhead < NT) {
                     if (slot + kAhead < ntiles)
-                        load_tokens<D>(xs[slot % kAhead], X + (size_t)min((slot + kAhead) * kTileTokens + io, n - 1) * D, kg);
+                        load_tokens<D>(xs[slot % kAhead], X + (size_t)min(tok0 + (slot + kAhead) * kTileTokens + io, n - 1) * D, kg);
                 }
                 float m0 = acc[0][0], m1 = acc[0][1], m2 = acc[0][2], m3 = acc[0][3];
 #pragma unroll
@@ -145,6 +214,7 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
                     for (int j = 0; j < 16; ++j) acc[mb][j] = exp2_fast(fmaf(acc[mb][j], c1, -mc));
                 res_pack<IO, RB>(kq[slot], acc);
+                if (first) LOT_WSTAMP(12 + slot);
             }
             __builtin_amdgcn_sched_barrier(0);   // (slots are not interleaved: that would only cost registers)
         }
@@ -177,7 +247,7 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
                         s3 = fmaf(k[mb][j + 3], vC[mb][j + 3], s3);
                     }
                 const float s = pair_sum((s0 + s1) + (s2 + s3));
-                const float w = slot * kTileTokens + i < n ? rcp_fast(s) : 0.f;
+                const float w = tok0 + slot * kTileTokens + i < n ? rcp_fast(s) : 0.f;
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -191,8 +261,8 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
     f32x16 U[RB][NB];
     auto sweep_with_values = [&](f32x16 (&cs)[RB]) __attribute__((always_inline)) {
         const IO* V = reinterpret_cast<const IO*>(p.V);
-        uint16_t* tr_hi = s_tr;
-        uint16_t* tr_lo = s_tr + 32 * RB * kTrStride;
+        uint16_t* tr_hi = s_tr[part];
+        uint16_t* tr_lo = s_tr[part] + 32 * RB * kTrStride;
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) {
 #pragma unroll
@@ -209,7 +279,7 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
         auto request_values = [&](int slot, bf16x8 (&vh)[2][NB], bf16x8 (&vl)[2][NB]) __attribute__((always_inline)) {
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
-                const int t0 = slot * kTileTokens + 16 * s2 + 8 * kgo;
+                const int t0 = tok0 + slot * kTileTokens + 16 * s2 + 8 * kgo;
                 const int left = max(1, min(8, n - t0));
                 load_values<D>(vh[s2], vl[s2], V, (size_t)g * stride + min(t0, n - 1), left, i);
             }
@@ -241,7 +311,7 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
                         s3 = fmaf(k[mb][j + 3], vC[mb][j + 3], s3);
                     }
                 const float s = pair_sum((s0 + s1) + (s2 + s3));
-                const float w = slot * kTileTokens + i < n ? rcp_fast(s) : 0.f;
+                const float w = tok0 + slot * kTileTokens + i < n ? rcp_fast(s) : 0.f;
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -279,86 +349,144 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
     };
 
     // ---- the iterations of this side.  The kept matrix is written only at the top of the outer loop (once,
-    //      unless the potentials drift too far from those folded into it); the inner loop only reads it.
+    //      unless the potentials drift too far from those folded into it); the inner loop only reads it.  The
+    //      last iteration is code of its own behind the loop (the keys' last sweep also contracts with V and needs
+    //      registers that the loop should not have to make room for).
+    auto column_sums = [&](f32x16 (&cs)[RB], int it) __attribute__((always_inline)) -> float {
+        float c[16 * RB];
+#pragma unroll
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) c[16 * mb + j] = cs[mb][j];
+        float tot = reduce_scatter_tokens<16 * RB>(c, i);
+        if constexpr (WS > 1) {
+            // the side's wavefronts add up their shares, each in the same order: identical potentials, hence
+            // identical decisions, on all of them.  One barrier per iteration on every wavefront of the
+            // workgroup (both sides run p.iters iterations); the slots alternate, so that a wavefront already
+            // in the next iteration does not overwrite what another one still reads.
+            s_part[it & 1][wave][lane] = tot;
+            __syncthreads();
+            tot = 0.f;
+#pragma unroll
+            for (int q = 0; q < WS; ++q) tot += s_part[it & 1][side * WS + q][lane];
+        }
+        return fmaxf(tot * v_l, 1.0e-37f);
+    };
     int it = 1;
-    bool first = true;
-    while (it <= p.iters) {
+    bool first = true, refill = true;
+    do {
         fill(first);
+        if (first) {
+            touched<kTouchX>(touch_x);
+            if (side == 0) {
+                const int last = min(n, tok0 + NT * kTileTokens);
+                touch_lines<kTouchV>(touch_v, reinterpret_cast<const IO*>(p.V) + ((size_t)g * stride + min(tok0, n - 1)) * D,
+                                     max(last - tok0, 0) * kRowBytes, lane);
+            } else {
+#pragma unroll
+                for (int k = 0; k < kTouchV; ++k) touch_v[k] = 0u;
+            }
+            LOT_WSTAMP(1);
+        }
         first = false;
         v_l = live ? 1.f : 0.f;
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
             for (int j = 0; j < 16; ++j) vC[mb][j] = 1.f;     // (padding pivots hold zeros in the kept matrix)
-        bool refill = false;
-        for (; it <= p.iters && !refill; ++it) {
+        refill = false;
+        for (; it < p.iters && !refill; ++it) {
             f32x16 cs[RB];
-            const bool last = it == p.iters;
-            if (last && side == 0) sweep_with_values(cs);
-            else sweep(cs);
-            float c[16 * RB];
-#pragma unroll
-            for (int mb = 0; mb < RB; ++mb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) c[16 * mb + j] = cs[mb][j];
-            const float tot = reduce_scatter_tokens<16 * RB>(c, i);
-            const float colsum = fmaxf(tot * v_l, 1.0e-37f);
-            const float cinv = rcp_fast(colsum);
-            if (!last) {
-                g_l += (p.eps * kLn2) * __builtin_amdgcn_logf(nbeta * cinv);
-                // v for the next sweep, shifted by pivot 0's change (lane 0 holds pivot 0)
-                const float d = (g_l - gref_l) * c1;
-                const float d0 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, d)));
-                const float rel = d - d0;
-                refill = __any(live && !(fabsf(rel) <= p.drift_half));   // the potentials go into the kept matrix
-                v_l = live ? exp2_fast(rel) : 0.f;
-                s_vec[side][piv] = v_l;
-                wave_sync_lds();
-                load_pivot_vector<RB>(vC, s_vec[side], kg);
-                wave_sync_lds();
-            } else {
-                rho_l = side == 0 ? cinv : beta_l * cinv;
-            }
+            sweep(cs);
+            const float cinv = rcp_fast(column_sums(cs, it));
+            g_l += (p.eps * kLn2) * __builtin_amdgcn_logf(nbeta * cinv);
+            // v for the next sweep, shifted by pivot 0's change (lane 0 holds pivot 0)
+            const float d = (g_l - gref_l) * c1;
+            const float d0 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, d)));
+            const float rel = d - d0;
+            refill = __any(live && !(fabsf(rel) <= p.drift_half));   // the potentials go into the kept matrix
+            v_l = live ? exp2_fast(rel) : 0.f;
+            s_vec[wave][piv] = v_l;
+            wave_sync_lds();
+            load_pivot_vector<RB>(vC, s_vec[wave], kg);
+            wave_sync_lds();
+            LOT_WSTAMP(1 + min(it, 24));
         }
+    } while (refill);
+    {
+        f32x16 cs[RB];
+        if (side == 0) sweep_with_values(cs);
+        else sweep(cs);
+        const float cinv = rcp_fast(column_sums(cs, p.iters));
+        rho_l = side == 0 ? cinv : beta_l * cinv;
+        LOT_WSTAMP(1 + min(p.iters, 24));
     }
 
+    touched<kTouchV>(touch_v);
     // ---- the two sides meet
     if (side == 0) {
-        // Y'_t = v_t U_t / colsum_t: rows of U scaled per pivot, into LDS as [pivot][D]
-        s_fac[piv] = live ? v_l * rho_l : 0.f;
+        // Y'_t = v_t U_t / colsum_t: rows of this wavefront's share of U scaled per pivot, into LDS as [pivot][D]
+        s_fac[part][piv] = live ? v_l * rho_l : 0.f;
         wave_sync_lds();
         f32x16 fac[RB];
-        load_pivot_vector<RB>(fac, s_fac, kg);
+        load_pivot_vector<RB>(fac, s_fac[part], kg);
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) s_u[pivot_of(mb, j, kg) * D + NB * i + nb] = U[mb][nb][j] * fac[mb][j];
-    } else {
+                for (int j = 0; j < 16; ++j) U[mb][nb][j] *= fac[mb][j];
+        if (part < kUBufs) {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) s_u[part][pivot_of(mb, j, kg) * D + NB * i + nb] = U[mb][nb][j];
+        }
+    } else if (part == 0) {
         s_qs[piv] = live ? (float)n * rho_l * v_l : 0.f;      // n rho1_t, and the v_t the expansion leaves out
     }
+    if constexpr (WS > kUBufs) {
+        // (a fixed order of additions: the result does not depend on which wavefront arrives first)
+        __syncthreads();
+        if (side == 0 && part >= kUBufs) {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) s_u[part - kUBufs][pivot_of(mb, j, kg) * D + NB * i + nb] += U[mb][nb][j];
+        }
+    }
+    LOT_WSTAMP(27);
     __syncthreads();
-    if (side == 0) return;
+    LOT_WSTAMP(28);
 
-    // ---- queries: Y''_t = n rho1_t v_t Y'_t as MFMA operand fragments (hi + lo), then O = sum_t (Kt_it / s_i) Y''_t
+    // ---- Y''_t = n rho1_t v_t Y'_t as MFMA operand fragments (hi + lo), laid out by the whole workgroup; then the
+    //      queries' wavefronts expand O = sum_t (Kt_it / s_i) Y''_t
     bf16x8* yf_hi = s_yf[0];
     bf16x8* yf_lo = s_yf[1];
-    for (int f = lane; f < 2 * RB * NB * 64; f += 64) {
+    for (int f = tid; f < 2 * RB * NB * 64; f += 128 * WS) {
         const int fl = f & 63, fi = fl & 31, fkg = fl >> 5;
         const int snb = f >> 6, s = snb / NB, nb = snb % NB;
         f32x8 t;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int pv = 32 * (s >> 1) + 16 * (s & 1) + 8 * (e >> 2) + 4 * fkg + (e & 3);
-            t[e] = s_u[pv * D + NB * fi + nb] * s_qs[pv];
+            float y = s_u[0][pv * D + NB * fi + nb];
+#pragma unroll
+            for (int q = 1; q < kUBufs; ++q) y += s_u[q][pv * D + NB * fi + nb];
+            t[e] = y * s_qs[pv];
         }
         bf16x8 hi, lo;
         split_bf16(t, hi, lo);
         yf_hi[f] = hi;
         yf_lo[f] = lo;
     }
-    wave_sync_lds();
+    __syncthreads();
+    LOT_WSTAMP(29);
+    if (side == 0) return;
     IO* const out = reinterpret_cast<IO*>(p.out);
 #pragma unroll
     for (int slot = 0; slot < NT; ++slot) {
@@ -400,7 +528,7 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
                     }
                 }
             }
-            const int row0 = slot * kTileTokens + 4 * kg;
+            const int row0 = tok0 + slot * kTileTokens + 4 * kg;
             IO* const lane_base = out + ((size_t)g * stride + row0) * D;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
@@ -409,9 +537,10 @@ __global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+    LOT_WSTAMP(30);
 }
 
-template <typename IO, int D, int RB, int NT>
+template <typename IO, int D, int RB, int NT, int WS, int WPE>
 int launch_wave(const Args& a)
 {
     const lot_shape& s = a.s;
@@ -422,27 +551,46 @@ int launch_wave(const Args& a)
     p.n_side[1] = a.n_q > 0 ? a.n_q : s.n;
     for (int sd = 0; sd < 2; ++sd) p.stride_side[sd] = a.n_stride > 0 ? a.n_stride : p.n_side[sd];
     p.drift_half = 0.5f * drift_limit();
+#ifdef LOT_TRACE
+    p.trace = (unsigned long long*)(a.ws + a.lay.fused_total);   // (developer builds: see the fused kernel)
+#endif
     if (a.dry_run) {
         if (a.family_out) *a.family_out = LOT_KERNELS_KEPT_WAVEFRONT;
         return LOT_OK;
     }
-    lot_wave_kernel<IO, D, RB, NT><<<dim3((unsigned)p.G), dim3(128), 0, a.stream>>>(p);
+    lot_wave_kernel<IO, D, RB, NT, WS, WPE><<<dim3((unsigned)p.G), dim3(128 * WS), 0, a.stream>>>(p);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }
 
-// The smallest NT of the compiled set {2, 4, 8} that holds `tiles`, within what the registers take (NT
-// times the words per tile at most 128).  Sixteen tiles (512 tokens with up to 32 pivots in bf16) would fit
-// the registers too, but one wavefront then streams so many tiles one after the other, in the passes that
-// read Q, K, V and write O, that the workgroup-level kernels are faster (measured at B H = 384, n = 512:
-// 87 us against 76).
+// One wavefront per side: the smallest NT of the compiled set {2, 4, 8} that holds `tiles`, within what the
+// registers take (NT times the words per tile at most 128).  Nine to sixteen tiles (up to 512 tokens): two
+// wavefronts per side with eight tiles each -- one wavefront with sixteen would fit the registers too (up to 32
+// pivots in bf16) but streams so many tiles one after the other, in the passes that read Q, K, V and write O,
+// that the workgroup-level kernels were faster (measured at B H = 384, n = 512: 87 us against 76).  With at
+// most 64 kept words per lane two wavefronts share a SIMD's registers when there are more problems than
+// compute units, so that all of them are resident at once.
 template <typename IO, int D, int RB>
 int launch_wave_sized(const Args& a, int tiles)
 {
-    constexpr int kMaxNT = 128 / ResWords<IO, RB>::value;
-    if (tiles <= 2) return launch_wave<IO, D, RB, 2>(a);
-    if constexpr (kMaxNT >= 4) { if (tiles <= 4) return launch_wave<IO, D, RB, 4>(a); }
-    if constexpr (kMaxNT >= 8) { if (tiles <= 8) return launch_wave<IO, D, RB, 8>(a); }
+    constexpr int NW = ResWords<IO, RB>::value;
+    constexpr int kMaxNT = 128 / NW;
+    if (tiles <= 2) return launch_wave<IO, D, RB, 2, 1, 1>(a);
+    if constexpr (kMaxNT >= 4) { if (tiles <= 4) return launch_wave<IO, D, RB, 4, 1, 1>(a); }
+    if constexpr (kMaxNT >= 8) {
+        if (tiles <= 8) return launch_wave<IO, D, RB, 8, 1, 1>(a);
+        if (tiles <= 16) {
+            if constexpr (8 * NW <= 64) {
+#ifdef LOT_EXPERIMENT_W4
+                if (a.s.B * a.s.H > device_cus()) return launch_wave<IO, D, RB, 4, 4, 4>(a);
+                return launch_wave<IO, D, RB, 4, 4, 2>(a);
+#else
+                if (a.s.B * a.s.H > device_cus()) return launch_wave<IO, D, RB, 8, 2, 2>(a);
+#endif
+            }
+            return launch_wave<IO, D, RB, 8, 2, 1>(a);
+        }
+    }
     return LOT_ERR_PATH;
 }
 
