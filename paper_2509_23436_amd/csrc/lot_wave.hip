@@ -129,12 +129,14 @@ __global__ void __launch_bounds__(128 * WS) __attribute__((amdgpu_waves_per_eu(W
     // the rows of the tiles that the first pass does not request at once (it keeps kAhead tiles in flight) and,
     // on the keys' side, the value rows of the last sweep: touched now, so that they stream in from memory
     // while the first tiles and the iterations are worked on
-    constexpr int kAheadMax = WPE >= 2 ? 2 : 4;      // (half of a SIMD's registers has no room for four tiles' rows)
+    constexpr int kAheadMax = 4;
     constexpr int kAhead = NT < kAheadMax ? NT : kAheadMax;
     constexpr int kRowBytes = D * (int)sizeof(IO);
     constexpr int kTouchX = NT > kAhead ? ((NT - kAhead) * kTileTokens * kRowBytes / 128 + 63) / 64 : 1;
     constexpr int kTouchV = (NT * kTileTokens * kRowBytes / 128 + 63) / 64;
     uint32_t touch_x[kTouchX], touch_v[kTouchV];
+#pragma unroll
+    for (int k = 0; k < kTouchV; ++k) touch_v[k] = 0u;
     {
         const int first = tok0 + kAhead * kTileTokens, last = min(n, tok0 + NT * kTileTokens);
         touch_lines<kTouchX>(touch_x, X + (size_t)min(first, n - 1) * D, NT > kAhead ? max(last - first, 0) * kRowBytes : 0, lane);
@@ -378,14 +380,6 @@ __global__ void __launch_bounds__(128 * WS) __attribute__((amdgpu_waves_per_eu(W
         fill(first);
         if (first) {
             touched<kTouchX>(touch_x);
-            if (side == 0) {
-                const int last = min(n, tok0 + NT * kTileTokens);
-                touch_lines<kTouchV>(touch_v, reinterpret_cast<const IO*>(p.V) + ((size_t)g * stride + min(tok0, n - 1)) * D,
-                                     max(last - tok0, 0) * kRowBytes, lane);
-            } else {
-#pragma unroll
-                for (int k = 0; k < kTouchV; ++k) touch_v[k] = 0u;
-            }
             LOT_WSTAMP(1);
         }
         first = false;
@@ -396,6 +390,13 @@ __global__ void __launch_bounds__(128 * WS) __attribute__((amdgpu_waves_per_eu(W
             for (int j = 0; j < 16; ++j) vC[mb][j] = 1.f;     // (padding pivots hold zeros in the kept matrix)
         refill = false;
         for (; it < p.iters && !refill; ++it) {
+            // (the value rows are touched from inside the loop: memory operations complete in order, and whatever
+            // the compiler reloads on the way into the loop would otherwise wait for these lines to arrive)
+            if (it == 1 && side == 0) {
+                const int last = min(n, tok0 + NT * kTileTokens);
+                touch_lines<kTouchV>(touch_v, reinterpret_cast<const IO*>(p.V) + ((size_t)g * stride + min(tok0, n - 1)) * D,
+                                     max(last - tok0, 0) * kRowBytes, lane);
+            }
             f32x16 cs[RB];
             sweep(cs);
             const float cinv = rcp_fast(column_sums(cs, it));
