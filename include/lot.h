@@ -81,8 +81,8 @@ typedef enum {
     LOT_PATH_AUTO = 0,
     LOT_PATH_REFERENCE = 1,  /* one plain kernel per step, similarities materialised (any shape) */
     LOT_PATH_FUSED = 2,      /* MFMA kernels; d_k = d_v in {32, 64}: r <= 64 one kernel per call (see
-                                lot_forward_kernels for its families), 64 < r <= 256 grouped kernels, one
-                                launch per step (attention only) */
+                                lot_forward_kernels for its families), 64 < r <= 256 grouped kernels
+                                (attention only) */
     LOT_PATH_STEPWISE = 3    /* the same MFMA tile code with launch boundaries as the only synchronisation
                                 between workgroups (one launch per Sinkhorn pass; no kernel waits for
                                 another workgroup): for a device that kernels of other streams share, where
@@ -139,7 +139,8 @@ int lot_attention_fwd_static(const lot_shape* shape, const void* Q, const void* 
  *   LOT_KERNELS_KEPT_WORKGROUP  the same kernel keeping each workgroup's share of exp(C/eps) in registers
  *                               and LDS: Q, K, V are read once
  *   LOT_KERNELS_KEPT_WAVEFRONT  short sequences: one wavefront per side, its whole exp(C/eps) in registers
- *   LOT_KERNELS_GROUPED         64 < r <= 256: pivots in groups of 64, one launch per step
+ *   LOT_KERNELS_GROUPED         64 < r <= 256: pivots in groups of 64; one launch per step, or (short sequences:
+ *                               few tiles per workgroup) everything after the clearing in one launch
  */
 typedef enum {
     LOT_KERNELS_PLAIN = 0,
@@ -300,8 +301,8 @@ int lot_attention_cls_bwd_path(const lot_shape* shape, const void* Q, const void
                                void* workspace, size_t workspace_bytes, void* hip_stream, int path);
 
 /*
- * Waits between workgroups.  The fused forward kernel and the tiled backward's forward sweep are
- * persistent kernels whose workgroups exchange column sums; every such wait is bounded, and the grid
+ * Waits between workgroups.  The fused forward kernel, the one-launch form of the grouped forward and the
+ * tiled backward's forward sweep are persistent kernels whose workgroups exchange column sums; every such wait is bounded, and the grid
  * never exceeds what the device can hold at once.  A kernel of ANOTHER stream that occupies compute
  * units while one of these starts can still keep part of the grid from becoming resident; a wait then
  * gives up after its poll budget (seconds), every workgroup leaves, the rows of `out` that a leaving
@@ -341,6 +342,9 @@ int lot_status_words(const unsigned long long* host_words);
  *   LOT_KNOB_FWD_DRIFT_LIMIT           0..32: the forward kernels that keep exp(C/eps) on chip recompute it once
  *                                      the potentials have spread over more than this many binary orders
  *                                      (default 32; 0: in every iteration)
+ *   LOT_KNOB_GROUPED_ONE_LAUNCH_TILES  the grouped forward (r > 64) runs as one launch when a workgroup has at
+ *                                      most this many tiles of 32 tokens per side and the grid fits the device
+ *                                      (default 8; 0: always one launch per step; large: wherever it fits)
  * Returns LOT_OK, or LOT_ERR_SHAPE for an unknown knob.
  */
 typedef enum {
@@ -350,7 +354,8 @@ typedef enum {
     LOT_KNOB_BWD_SWEEP_LAUNCHES = 3,
     LOT_KNOB_FWD_STREAMING = 4,
     LOT_KNOB_FWD_DRIFT_LIMIT = 5,
-    LOT_KNOB_COUNT_ = 6
+    LOT_KNOB_GROUPED_ONE_LAUNCH_TILES = 6,
+    LOT_KNOB_COUNT_ = 7
 } lot_knob;
 int lot_debug_set(int knob, long long value);
 

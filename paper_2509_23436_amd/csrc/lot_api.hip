@@ -82,6 +82,13 @@ float drift_limit()
     return 32.f;
 }
 
+int grouped_one_launch_tiles()
+{
+    long long v;
+    if (knob(LOT_KNOB_GROUPED_ONE_LAUNCH_TILES, &v) && v >= 0) return v > (1 << 20) ? (1 << 20) : (int)v;
+    return 8;
+}
+
 bool sweep_by_launches()
 {
     long long v;
@@ -240,6 +247,7 @@ static int attention_impl(const lot_shape* shape, const void* Q, const void* K, 
     Args a{};
     a.s = *shape; a.Q = Q; a.K = K; a.V = V; a.Z = Z; a.beta = beta; a.eps = eps; a.iters = iters;
     a.out = out; a.ws = (char*)workspace; a.stream = (hipStream_t)hip_stream; a.n_stride = n_stride;
+    a.stepwise = path == LOT_PATH_STEPWISE;
     if (impl == FWD_GROUPED) return run_grouped(a);   // pivot sizes beyond one register tile
     a.lay = carve(*shape);
     if (impl == FWD_FUSED) return run_fused(a, true);
@@ -460,6 +468,7 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
         f.s = fs; f.Q = Q; f.K = K; f.V = V; f.Z = Z; f.beta = beta; f.eps = eps; f.iters = iters; f.out = out;
         f.ws = (char*)workspace; f.stream = (hipStream_t)hip_stream;
         f.n_q = shape->n_q; f.n_k = shape->n_k; f.mass_q = mass_q; f.mass_k = mass_k;
+        f.stepwise = path == LOT_PATH_STEPWISE;
         if (impl == FWD_GROUPED) return run_grouped(f);   // pivot sizes beyond one register tile
         f.lay = carve(fs);
         return run_fused(f, true);

@@ -66,26 +66,6 @@ struct FusedParams {
 constexpr int kCountShift = 54;
 constexpr unsigned kCountMask = 0x3ffu;
 
-// Poll *counter until it reaches target.  Thread 0 only.  False if the budget ran out or another
-// workgroup already gave up.
-__device__ inline bool gave_up(const unsigned long long* status, unsigned long long nonce)
-{
-    return __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nonce;
-}
-__device__ inline void give_up(unsigned long long* status, unsigned long long nonce)
-{
-    __hip_atomic_store(status, nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline bool spin_until(uint32_t* counter, uint32_t target, const unsigned long long* status,
-                                  unsigned long long nonce, uint32_t limit)
-{
-    for (uint32_t k = 0; k < limit; ++k) {
-        if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) return true;
-        if ((k & 63u) == 63u && gave_up(status, nonce)) return false;
-        __builtin_amdgcn_s_sleep(1);
-    }
-    return false;
-}
 
 
 

@@ -9,9 +9,18 @@
 //     from which the contraction with V and the expansion with Y'' rebuild one group's weights at a time;
 //   * column sums are reduced to one pivot per lane after every tile (transposing reduction), so a
 //     lane carries one accumulator per group instead of 32.
-// One launch per step; launch boundaries are the only synchronisation between workgroups:
+// Two forms of the same steps
 //   clear | T x pass (both solves: pair = side * G + g, side 0 = queries) | reduce (keys, one workgroup
-//   per group: U = sum_j W2 V) | mid (Y'' = n beta/cs1 * U/cs2) | expand (queries -> O).
+//   per group: U = sum_j W2 V) | mid (Y'' = n beta/cs1 * U/cs2) | expand (queries -> O):
+//   * one launch per step, launch boundaries the only synchronisation between workgroups (any size; the form
+//     of LOT_PATH_STEPWISE);
+//   * lg_persistent: everything after the clearing in ONE launch, for the sizes where the launches themselves
+//     are what a call costs (short sequences).  A workgroup keeps its chunk of one side for the whole call, the
+//     pivots and the potentials stay in its LDS, and what the launch boundaries ordered is ordered by bounded
+//     waits: the words of a pass carry, in their top byte, the number of workgroups that have added their share,
+//     and one wavefront per workgroup polls them (a poll per word and thread crowds out the additions
+//     themselves: measured 0.5 ms per wait); the keys' workgroups count themselves off after storing their share
+//     of U, form a slice of Y'' each once all have, and count themselves off again for the queries' workgroups.
 // Column sums are exchanged as fixed-point integers (atomic adds): order-independent, reproducible.
 #include "lot_internal.h"
 #include "lot_tile.h"
@@ -25,23 +34,19 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // reduce: U_t = sum_j W2_jt V_j for the pivots of one group per workgroup (keys; potentials g2^{T-1})
 // ---------------------------------------------------------------------------------------------
-template <typename IO, int D>
-__global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
+// One group's share of U from the key tiles of one workgroup, with the keys' potentials g^{T-1} in s_g and the
+// pivots in s_zstash (the workgroup has synchronised on both).  COHERENT: the result is for another workgroup
+// of this launch and is written through the caches.
+template <typename IO, int D, bool COHERENT>
+__device__ __forceinline__ void reduce_tiles(const LgParams& p, int g, int chunk, int grp, const float* s_g, float* s_buf,
+                                             uint16_t* s_tr, const char* s_zstash)
 {
     constexpr int NB = D / 32;
     constexpr bool kSplit = io_is_f32<IO>::value;
-    __shared__ float s_g[kRmax];
-    __shared__ __attribute__((aligned(16))) float s_buf[64 * D];
-    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * 2 * 64 * kTrStride];
-    extern __shared__ __attribute__((aligned(16))) char s_zstash[];
-
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 31, kg = lane >> 5;
-    int wg, grp;
-    if (!group_block(wg, grp, p.G * p.chunks, p.groups)) return;
-    const int g = wg / p.chunks, chunk = wg % p.chunks;
-    const int pair = p.G + g, h = g % p.H;
+    const int pair = p.G + g;
     const int n = p.n_side[1], stride = p.stride_side[1];
     const float* const mass = p.mass_side[1];     // the keys' masses times n weight the reduction
     const float c1 = kLog2e / p.eps;
@@ -53,9 +58,6 @@ __global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
     const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
 
     const float* lse = last_lse(p) + (size_t)pair * p.n;
-    load_potentials(p, s_g, p.T, pair, h, false, tid);
-    stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
-    __syncthreads();
 
     f32x16 U[2][NB];
 #pragma unroll
@@ -91,7 +93,28 @@ __global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
     }
     sum_over_waves<D, 2>(U, s_buf, wave, i, kg);
     float* up = p.u_part + (((size_t)g * p.chunks + chunk) * kRmax + (size_t)kGroup * grp) * D;
-    for (int e = tid; e < kGroup * D; e += kThreads) up[e] = s_buf[e];
+    for (int e = tid; e < kGroup * D; e += kThreads) {
+        if (COHERENT) st_coherent(up + e, s_buf[e]);
+        else up[e] = s_buf[e];
+    }
+}
+
+template <typename IO, int D>
+__global__ void __launch_bounds__(kThreads, 2) lg_reduce(LgParams p)
+{
+    __shared__ float s_g[kRmax];
+    __shared__ __attribute__((aligned(16))) float s_buf[64 * D];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tr[kWaves * 2 * 64 * kTrStride];
+    extern __shared__ __attribute__((aligned(16))) char s_zstash[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int wg, grp;
+    if (!group_block(wg, grp, p.G * p.chunks, p.groups)) return;
+    const int g = wg / p.chunks, chunk = wg % p.chunks, h = g % p.H;
+    load_potentials(p, s_g, p.T, p.G + g, h, false, tid);
+    stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
+    __syncthreads();
+    reduce_tiles<IO, D, false>(p, g, chunk, grp, s_g, s_buf, s_tr, s_zstash);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -111,11 +134,204 @@ __global__ void lg_mid(LgParams p)
         int c = 0;
         for (; c + 1 < p.chunks; c += 2) { u0 += up[(size_t)c * kRmax * D]; u1 += up[(size_t)(c + 1) * kRmax * D]; }
         if (c < p.chunks) u0 += up[(size_t)c * kRmax * D];
-        const float cs1 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + g) * kRmax + t] * p.fx_unscale, 0.5f * p.fx_unscale);
-        const float cs2 = fmaxf((float)(long long)p.colacc[((size_t)T * pairs + p.G + g) * kRmax + t] * p.fx_unscale, 0.5f * p.fx_unscale);
+        const float cs1 = colsum_of(p, p.colacc[((size_t)T * pairs + g) * kRmax + t]);
+        const float cs2 = colsum_of(p, p.colacc[((size_t)T * pairs + p.G + g) * kRmax + t]);
         y = ((float)p.n_side[0] * p.beta[(g % p.H) * p.r + t] / cs1) * ((u0 + u1) / cs2);
     }
     p.ypp[idx] = y;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The one-launch form
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kPersistentLdsMax = 160 * 1024;
+
+// LDS of lg_persistent: potentials, pivots of all groups, then the largest of the stages' working areas.
+constexpr int kCountShiftLg = 56;     // an exchanged word: workgroups that have added their share in the top byte
+// 64-bit words that hold the counters of the one-launch form: [G][2] unsigned
+inline size_t lg_counter_words(size_t G, size_t) { return G; }
+
+// The first wavefront of a workgroup polls the words of one pass of one pair until each carries `chunks`
+// arrivals; lane l then holds the words of pivots l, 64 + l, ... in word[].  False, for the whole workgroup, if
+// the poll budget ran out or another workgroup of the launch has given up.  Ends with a workgroup barrier.
+__device__ __forceinline__ bool wait_for_words(const LgParams& p, const unsigned long long* words, unsigned long long (&word)[kMaxGroups],
+                                               int* s_flag, int tid)
+{
+    if (tid < 64) {
+        const __amdgpu_buffer_rsrc_t view = coherent_view(words);
+        bool ok = false;
+        for (uint32_t k = 0; k < p.spin_limit; ++k) {
+            bool all = true;
+#pragma unroll
+            for (int q = 0; q < kMaxGroups; ++q) {
+                const int t = kGroup * q + tid;
+                word[q] = t < p.r ? ldc_u64(view, (uint32_t)t * 8u) : ((unsigned long long)p.chunks << kCountShiftLg);
+                all = all && (int)(word[q] >> kCountShiftLg) == p.chunks;
+            }
+            if (__all(all)) { ok = true; break; }
+            if ((k & 63u) == 63u && gave_up(p.status, p.nonce)) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (tid == 0) {
+            if (!ok) give_up(p.status, p.nonce);
+            s_flag[0] = ok;
+        }
+    }
+    __syncthreads();
+    return s_flag[0] != 0;
+}
+
+template <typename IO, int D>
+inline size_t persistent_lds_bytes(int groups)
+{
+    constexpr int NB = D / 32;
+    const size_t stash = (size_t)groups * StashBytes<IO, D, 2>::value;
+    const size_t pass = (size_t)kWaves * kRmax * sizeof(float);
+    const size_t reduce = (size_t)64 * D * sizeof(float) + (size_t)kWaves * 2 * 64 * kTrStride * sizeof(uint16_t);
+    const size_t expand = (size_t)64 * D * sizeof(float) + (size_t)groups * 2 * (2 * 2 * NB * 64) * sizeof(bf16x8);
+    const size_t work = pass > reduce ? (pass > expand ? pass : expand) : (reduce > expand ? reduce : expand);
+    return kRmax * sizeof(float) + 64 + stash + work;
+}
+
+// Waits (thread 0 polls) until `target` workgroups have counted themselves off at *counter.  False, for the
+// whole workgroup, if the poll budget ran out or another workgroup of the launch has given up.
+__device__ __forceinline__ bool wait_for_count(const LgParams& p, unsigned* counter, unsigned target, int* s_flag, int tid)
+{
+    if (tid == 0) {
+        const bool ok = spin_until(counter, target, p.status, p.nonce, p.spin_limit);
+        if (!ok) give_up(p.status, p.nonce);
+        s_flag[0] = ok;
+    }
+    __syncthreads();
+    const bool ok = s_flag[0] != 0;
+    __syncthreads();
+    return ok;
+}
+// Counts the workgroup off at *counter once everything its wavefronts have stored or added has left them.
+// Returns, to every thread, how many had counted themselves off before.
+__device__ __forceinline__ unsigned count_off(unsigned* counter, int* s_flag, int tid)
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) s_flag[1] = (int)__hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    return (unsigned)s_flag[1];
+}
+
+template <typename IO, int D>
+__device__ __forceinline__ void poison_chunk(const LgParams& p, int g, int chunk)
+{
+    const int n = p.n_side[0];
+    const int row0 = chunk * p.tiles_per_wg * kTileTokens, row1 = min(n, row0 + p.tiles_per_wg * kTileTokens);
+    if (row1 <= row0) return;
+    IO* base = reinterpret_cast<IO*>(p.out) + ((size_t)g * p.stride_side[0] + row0) * D;
+    for (int e = threadIdx.x; e < (row1 - row0) * D; e += kThreads) {
+        if constexpr (io_is_f32<IO>::value) as_global(base)[e] = __builtin_nanf("");
+        else as_global(base)[e] = (uint16_t)0x7fc0u;
+    }
+}
+
+// Workgroup (pair, chunk) = blockIdx.x: T passes over its chunk of its side, then (keys) its share of U and, for
+// the last key workgroup of a problem to get there, Y''; (queries) the expansion of its chunk once Y'' is there.
+// Every workgroup of the grid must be resident at once (the launcher checks the occupancy); every wait is
+// bounded, marks the launch in the status words when it gives up, and a query workgroup that leaves early
+// fills its rows of the output with NaN.
+template <typename IO, int D>
+__global__ void __launch_bounds__(kThreads, 2) lg_persistent(LgParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) char s_all[];
+    float* const s_g = reinterpret_cast<float*>(s_all);
+    int* const s_flag = reinterpret_cast<int*>(s_all + kRmax * sizeof(float));
+    char* const s_zstash = s_all + kRmax * sizeof(float) + 64;
+    char* const s_work = s_zstash + (size_t)p.groups * StashBytes<IO, D, 2>::value;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int pairs = 2 * p.G, T = p.T;
+    const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
+    const int side = pair / p.G, g = pair % p.G, h = g % p.H;
+    const float nside = (float)p.n_side[side];
+
+    Frag<IO, D> xc;
+    first_tile_of_pass<IO, D>(xc, p, pair, chunk, wave, lane);
+    for (int t = tid; t < kRmax; t += kThreads) s_g[t] = t < p.r ? 0.f : kNegBig;
+    stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
+    __syncthreads();
+
+    for (int k = 1; k <= T; ++k) {
+        pass_tiles<IO, D>(p, k, pair, chunk, s_g, reinterpret_cast<float (*)[kRmax]>(s_work), s_zstash, xc);
+        if (k == T) break;
+        first_tile_of_pass<IO, D>(xc, p, pair, chunk, wave, lane);
+        unsigned long long word[kMaxGroups];
+        const bool ok = wait_for_words(p, p.colacc + ((size_t)k * pairs + pair) * kRmax, word, s_flag, tid);
+        if (!ok) {
+            if (side == 0) poison_chunk<IO, D>(p, g, chunk);
+            return;
+        }
+        // g^k = g^{k-1} + eps log(n beta / column sum), the same on every workgroup of the pair
+        if (tid < 64) {
+#pragma unroll
+            for (int q = 0; q < kMaxGroups; ++q) {
+                const int t = kGroup * q + tid;
+                if (t < p.r) s_g[t] += p.eps * logf(nside * p.beta[h * p.r + t] / colsum_of(p, word[q]));
+            }
+        }
+        __syncthreads();
+    }
+    // s_g = g^{T-1}, the potentials of the last pass: what the contraction and the expansion rebuild the weights from
+    // (the rows' log-normalisers that the last pass stored are read back below)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    if (side == 1) {
+        float* const s_buf = reinterpret_cast<float*>(s_work);
+        uint16_t* const s_tr = reinterpret_cast<uint16_t*>(s_work + (size_t)64 * D * sizeof(float));
+        for (int grp = 0; grp < p.groups; ++grp) {
+            reduce_tiles<IO, D, true>(p, g, chunk, grp, s_g, s_buf, s_tr, s_zstash);
+            __syncthreads();
+        }
+        // Y'' once every key workgroup of the problem has stored its share of U and the last column sums of both
+        // sides are complete; each key workgroup forms the slice of Y'' that falls to it, four columns per thread
+        count_off(p.sync + 2 * g, s_flag, tid);
+        unsigned long long word[kMaxGroups];
+        if (!wait_for_count(p, p.sync + 2 * g, (unsigned)p.chunks, s_flag, tid) ||
+            !wait_for_words(p, p.colacc + ((size_t)T * pairs + g) * kRmax, word, s_flag, tid) ||
+            !wait_for_words(p, p.colacc + ((size_t)T * pairs + p.G + g) * kRmax, word, s_flag, tid))
+            return;
+        const __amdgpu_buffer_rsrc_t v1 = coherent_view(p.colacc + ((size_t)T * pairs + g) * kRmax);
+        const __amdgpu_buffer_rsrc_t v2 = coherent_view(p.colacc + ((size_t)T * pairs + p.G + g) * kRmax);
+        const __amdgpu_buffer_rsrc_t uv = coherent_view(p.u_part + (size_t)g * p.chunks * kRmax * D);
+        float* const ypp = p.ypp + (size_t)g * kRmax * D;
+        for (int e4 = chunk * kThreads + tid; e4 < kRmax * D / 4; e4 += p.chunks * kThreads) {
+            const int t = (4 * e4) / D;
+            f32x4 u0 = {0.f, 0.f, 0.f, 0.f}, u1 = u0;
+            float scale = 0.f;
+            if (t < p.r) {
+                const unsigned long long c1w = ldc_u64(v1, (uint32_t)t * 8u), c2w = ldc_u64(v2, (uint32_t)t * 8u);
+                int c = 0;
+#pragma unroll 4
+                for (; c + 1 < p.chunks; c += 2) {
+                    u0 += ldc_f32x4(uv, (uint32_t)(((size_t)c * kRmax * D + 4 * (size_t)e4) * sizeof(float)));
+                    u1 += ldc_f32x4(uv, (uint32_t)(((size_t)(c + 1) * kRmax * D + 4 * (size_t)e4) * sizeof(float)));
+                }
+                if (c < p.chunks) u0 += ldc_f32x4(uv, (uint32_t)(((size_t)c * kRmax * D + 4 * (size_t)e4) * sizeof(float)));
+                scale = ((float)p.n_side[0] * p.beta[h * p.r + t] / colsum_of(p, c1w)) / colsum_of(p, c2w);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) st_coherent(ypp + 4 * (size_t)e4 + q, scale * (u0[q] + u1[q]));
+        }
+        count_off(p.sync + 2 * g + 1, s_flag, tid);
+        return;
+    }
+
+    // queries: wait for Y'' of the problem, then expand this chunk
+    if (!wait_for_count(p, p.sync + 2 * g + 1, (unsigned)p.chunks, s_flag, tid)) {
+        poison_chunk<IO, D>(p, g, chunk);
+        return;
+    }
+    float* const s_y = reinterpret_cast<float*>(s_work);
+    bf16x8* const yf = reinterpret_cast<bf16x8*>(s_work + (size_t)64 * D * sizeof(float));
+    expand_tiles<IO, D, true>(p, 0, g, chunk, p.Q, p.ypp, p.out, 0, s_g, s_y, s_zstash, yf);
 }
 
 template <typename IO, int D>
@@ -124,8 +340,52 @@ int launch_grouped(const Args& a, LgParams p)
     constexpr int NB = D / 32;
     hipStream_t st = a.stream;
     const int pairs = 2 * p.G, T = a.iters;
-    const size_t words = (size_t)(T + 1) * pairs * kRmax;
-    lg_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words, (unsigned long long*)a.ws, next_nonce());
+    // (the counters of the one-launch form sit right behind the words and are cleared with them)
+    const size_t words = (size_t)(T + 1) * pairs * kRmax + lg_counter_words(p.G, T);
+    p.nonce = next_nonce();
+    lg_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words, (unsigned long long*)a.ws, p.nonce);
+
+    // The one-launch form, where the launches are what the call costs: the whole grid must be resident at once,
+    // and a workgroup should have few tiles (the keys' workgroups alone contract with V there, group after group).
+    if (!a.stepwise) {
+        const size_t lds = persistent_lds_bytes<IO, D>(p.groups);
+        static thread_local int per_cu_cache[8][kMaxGroups + 1] = {};   // per device ordinal and number of groups
+        int dev = 0;
+        LOT_HIP_CHECK(hipGetDevice(&dev));
+        int per_cu = (dev >= 0 && dev < 8) ? per_cu_cache[dev][p.groups] : 0;
+        if (per_cu == 0 && lds <= kPersistentLdsMax) {
+            LOT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(lg_persistent<IO, D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lg_persistent<IO, D>, kThreads, lds));
+            if (per_cu < 1) per_cu = -1;
+            if (dev >= 0 && dev < 8) per_cu_cache[dev][p.groups] = per_cu;
+        }
+        // (one workgroup per compute unit: with two, the one that polls holds up the one that still works -- measured)
+        const long long capacity = per_cu > 0 ? (long long)device_cus() : 0;
+        const int ntiles = (a.s.n + kTileTokens - 1) / kTileTokens;
+        long long c = capacity / pairs;
+        if (c > p.chunks) c = p.chunks;          // (the workspace holds that many shares of U per problem)
+        if (c > 255) c = 255;                    // (the arrival count of a word is a byte)
+        if (c >= 1) {
+            int per = (int)((ntiles + c - 1) / c);
+            per = (per + kWaves - 1) / kWaves * kWaves;
+            if (per <= grouped_one_launch_tiles()) {
+                LgParams q = p;
+                q.tiles_per_wg = per;
+                q.chunks = (ntiles + per - 1) / per;
+                q.count_one = 1ull << kCountShiftLg;
+                q.count_mask = 0xffull << kCountShiftLg;
+                const int frac = kCountShiftLg - 2 - (int)std::ceil(std::log2((double)a.s.n + 1.0));
+                q.fx_scale = std::ldexp(1.0f, frac);
+                q.fx_unscale = std::ldexp(1.0f, -frac);
+                q.status = (unsigned long long*)a.ws;
+                q.sync = reinterpret_cast<unsigned*>(p.colacc + (size_t)(T + 1) * pairs * kRmax);
+                q.spin_limit = spin_limit();
+                lg_persistent<IO, D><<<(unsigned)pairs * q.chunks, kThreads, lds, st>>>(q);
+                LOT_HIP_CHECK(hipGetLastError());
+                return LOT_OK;
+            }
+        }
+    }
     const size_t stash = (size_t)p.groups * StashBytes<IO, D, 2>::value;
     const size_t frag_bytes = (size_t)p.groups * 2 * (2 * 2 * NB * 64) * sizeof(bf16x8);
     // more than 64 KB of LDS per workgroup has to be asked for explicitly
@@ -159,7 +419,7 @@ GroupedWorkspace carve_grouped(const lot_shape& s, int iters)
     const size_t ntiles = ((size_t)s.n + kTileTokens - 1) / kTileTokens;
     const size_t per = (size_t)lg_tiles_per_wg(s);
     w.chunks = (int)((ntiles + per - 1) / per);
-    w.colacc = take((T + 1) * pairs * kRmax * 8);
+    w.colacc = take(((T + 1) * pairs * kRmax + lg_counter_words(G, T)) * 8);       // the words, then the counters of the one-launch form
     w.ghist = take((T + 1) * pairs * kRmax * 4);
     w.u_part = take(G * w.chunks * kRmax * D * 4);
     w.ypp = take(G * kRmax * D * 4);
@@ -185,6 +445,7 @@ int run_grouped(const Args& a)
     p.n_side[1] = a.n_k > 0 ? a.n_k : s.n;
     for (int sd = 0; sd < 2; ++sd) p.stride_side[sd] = a.n_stride > 0 ? a.n_stride : p.n_side[sd];
     p.mass_side[0] = a.mass_q; p.mass_side[1] = a.mass_k;
+    p.count_one = 0; p.count_mask = 0; p.status = nullptr; p.sync = nullptr; p.nonce = 0; p.spin_limit = 0;
     p.groups = (s.r + kGroup - 1) / kGroup; p.chunks = L.chunks; p.tiles_per_wg = lg_tiles_per_wg(s); p.T = a.iters;
     p.eps = a.eps;
     {

@@ -33,7 +33,22 @@ struct LgParams {
     int stride_side[2];           // tokens between consecutive problems in the caller's tensors (>= n_side)
     const float* mass_side[2];    // [G][n_side] token masses, or null: uniform 1/n_side
     float eps, fx_scale, fx_unscale;
+    // The one-launch form only (zero otherwise): the top byte of an exchanged word counts the workgroups that
+    // have added their share (count_one = 1 << 56 rides on every addition, count_mask covers the byte).
+    unsigned long long count_one, count_mask;
+    unsigned long long* status;   // [0] = nonce of a launch in which a wait gave up, [1] = nonce of the last launch
+    unsigned long long nonce;
+    unsigned* sync;               // [G][2]: key workgroups that have stored their share of U; ... their slice of Y''
+                                  // (cleared per launch)
+    uint32_t spin_limit;
 };
+
+// the sum an exchanged word carries (a sum below the fixed-point resolution reads as half a unit: the
+// potentials stay bounded)
+__device__ __forceinline__ float colsum_of(const LgParams& p, unsigned long long word)
+{
+    return fmaxf((float)(long long)(word & ~p.count_mask) * p.fx_unscale, 0.5f * p.fx_unscale);
+}
 
 inline int lg_tiles_per_wg(const lot_shape& s)
 {
@@ -84,8 +99,7 @@ __device__ __forceinline__ void load_potentials(const LgParams& p, float* s_g, i
         float gv = t < p.r ? 0.f : kNegBig;
         if (k > 1 && t < p.r) {
             const unsigned long long word = p.colacc[((size_t)(k - 1) * pairs + pair) * kRmax + t];
-            // (a sum below the fixed-point resolution reads as half a unit: the potentials stay bounded)
-            const float cs = fmaxf((float)(long long)word * p.fx_unscale, 0.5f * p.fx_unscale);
+            const float cs = colsum_of(p, word);
             gv = p.ghist[((size_t)(k - 2) * pairs + pair) * kRmax + t] + p.eps * logf((float)p.n_side[pair / p.G] * p.beta[h * p.r + t] / cs);
         }
         s_g[t] = gv;
@@ -125,34 +139,35 @@ __device__ __forceinline__ void weights_from_lse(f32x16 (&acc)[2], const char* z
 // ---------------------------------------------------------------------------------------------
 // pass k: column sums of W^k for both solves
 // ---------------------------------------------------------------------------------------------
+// The rows of a wavefront's first tile of a pass (requested before whatever the pass still waits for).
 template <typename IO, int D>
-__global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
+__device__ __forceinline__ void first_tile_of_pass(Frag<IO, D>& xc, const LgParams& p, int pair, int chunk, int wave, int lane)
 {
-    __shared__ float s_g[kRmax];
-    __shared__ float s_cs[kWaves][kRmax];
-    extern __shared__ __attribute__((aligned(16))) char s_zstash[];
+    const int side = pair / p.G, g = pair % p.G;
+    const int n = p.n_side[side];
+    const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.Q : p.K);
+    const int tok = min((chunk * p.tiles_per_wg + wave) * kTileTokens + (lane & 31), n - 1);
+    load_tokens<D>(xc, X + ((size_t)g * p.stride_side[side] + tok) * D, lane >> 5);
+}
 
+// The tiles of pass k of one workgroup, with the potentials g^{k-1} in s_g and the pivots in s_zstash (the
+// workgroup has synchronised on both), xc = the rows of the wavefront's first tile: adds the workgroup's
+// column sums to the pass's words.
+template <typename IO, int D>
+__device__ __forceinline__ void pass_tiles(const LgParams& p, int k, int pair, int chunk, const float* s_g,
+                                           float (*s_cs)[kRmax], const char* s_zstash, Frag<IO, D> xc)
+{
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 31, kg = lane >> 5;
     const int pairs = 2 * p.G;
-    const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
-    const int side = pair / p.G, g = pair % p.G, h = g % p.H;
-    const int n = p.n_side[side], stride = p.stride_side[side], k = p.k;
+    const int side = pair / p.G, g = pair % p.G;
+    const int n = p.n_side[side], stride = p.stride_side[side];
     const float* const mass = p.mass_side[side];     // token masses times n weight the column sums
     const float c1 = kLog2e / p.eps;
     const IO* X = reinterpret_cast<const IO*>(side == 0 ? p.Q : p.K);
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
     const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
-
-    Frag<IO, D> xc;
-    {
-        const int tok = min((tile_begin + wave) * kTileTokens + i, n - 1);
-        load_tokens<D>(xc, X + ((size_t)g * stride + tok) * D, kg);
-    }
-    load_potentials(p, s_g, k, pair, h, chunk == 0, tid);
-    stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
-    __syncthreads();
 
     float csg[kMaxGroups] = {0.f, 0.f, 0.f, 0.f};       // this lane's pivot of each group
     float* const lse_keep = lse_slot(p, k);
@@ -227,9 +242,28 @@ __global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
         float tot = 0.f;
 #pragma unroll
         for (int wv = 0; wv < kWaves; ++wv) tot += s_cs[wv][t];
-        const unsigned long long word = (unsigned long long)__float2ll_rn(tot * p.fx_scale);
+        const unsigned long long word = (unsigned long long)__float2ll_rn(tot * p.fx_scale) + p.count_one;
         __hip_atomic_fetch_add(p.colacc + ((size_t)k * pairs + pair) * kRmax + t, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+}
+
+template <typename IO, int D>
+__global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
+{
+    __shared__ float s_g[kRmax];
+    __shared__ float s_cs[kWaves][kRmax];
+    extern __shared__ __attribute__((aligned(16))) char s_zstash[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int pair = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks;
+    const int h = (pair % p.G) % p.H;
+    Frag<IO, D> xc;
+    first_tile_of_pass<IO, D>(xc, p, pair, chunk, wave, lane);
+    load_potentials(p, s_g, p.k, pair, h, chunk == 0, tid);
+    stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
+    __syncthreads();
+    pass_tiles<IO, D>(p, p.k, pair, chunk, s_g, s_cs, s_zstash, xc);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -237,33 +271,31 @@ __global__ void __launch_bounds__(kThreads, 2) lg_pass(LgParams p)
 // Forward: side 0, Ymat = Y'', out = O.  Backward: side 1, Ymat_t = rho'_t dYraw_t, out = dV, every row times
 // its token's mass times n (weight_rows).
 // ---------------------------------------------------------------------------------------------
-template <typename IO, int D>
-__global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, const void* rows, const float* ymat, void* out_rows, int weight_rows)
+// The tiles of the expansion for one workgroup, with the side's potentials g^{T-1} in s_g and the pivots in
+// s_zstash (the caller has stored both; this synchronises).  COHERENT: ymat was written by another workgroup
+// of this launch and is read past the caches that might still hold an older copy.
+template <typename IO, int D, bool COHERENT>
+__device__ __forceinline__ void expand_tiles(const LgParams& p, int side, int g, int chunk, const void* rows, const float* ymat,
+                                             void* out_rows, int weight_rows, const float* s_g, float* s_y,
+                                             const char* s_zstash, bf16x8* yf)
 {
     constexpr int NB = D / 32;
     constexpr bool kSplit = io_is_f32<IO>::value;
     constexpr int kFragsPerGroup = 2 * 2 * NB * 64;
-    __shared__ float s_g[kRmax];
-    __shared__ __attribute__((aligned(16))) float s_y[64 * D];
-    extern __shared__ __attribute__((aligned(16))) char s_dyn[];    // pivot stash, then Y'' fragments (hi, lo) per group
-
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 31, kg = lane >> 5;
-    const int g = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks, h = g % p.H;
     const int n = p.n_side[side], stride = p.stride_side[side];
     const float c1 = kLog2e / p.eps;
     const IO* X = reinterpret_cast<const IO*>(rows);
-    char* s_zstash = s_dyn;
-    bf16x8* yf = reinterpret_cast<bf16x8*>(s_dyn + (size_t)p.groups * StashBytes<IO, D, 2>::value);
     const int ntiles = (n + kTileTokens - 1) / kTileTokens;
     const int tile_begin = chunk * p.tiles_per_wg, tile_end = min(ntiles, tile_begin + p.tiles_per_wg);
-
     const float* lse = last_lse(p) + (size_t)(side * p.G + g) * p.n;
-    load_potentials(p, s_g, p.T, side * p.G + g, h, false, tid);
-    stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
+    const float* const yg = ymat + (size_t)g * kRmax * D;
+    const __amdgpu_buffer_rsrc_t yview = coherent_view(yg);
     for (int q = 0; q < p.groups; ++q) {
-        for (int e = tid; e < kGroup * D; e += kThreads) s_y[e] = ymat[((size_t)g * kRmax + (size_t)kGroup * q) * D + e];
+        for (int e = tid; e < kGroup * D; e += kThreads)
+            s_y[e] = COHERENT ? ldc_f32(yview, (uint32_t)((kGroup * q * D + e) * sizeof(float))) : yg[(size_t)kGroup * q * D + e];
         __syncthreads();
         lay_out_fragments<D, 2>(s_y, yf + (size_t)(2 * q) * kFragsPerGroup, yf + (size_t)(2 * q + 1) * kFragsPerGroup, tid);
         __syncthreads();
@@ -304,6 +336,21 @@ __global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, c
             if (row0 + 8 * (j >> 2) + (j & 3) < n)
                 store_out<NB>(lane_base + (8 * (j >> 2) + (j & 3)) * D, i, o[0][j], o[NB - 1][j]);
     }
+}
+
+template <typename IO, int D>
+__global__ void __launch_bounds__(kThreads, 2) lg_expand(LgParams p, int side, const void* rows, const float* ymat, void* out_rows, int weight_rows)
+{
+    __shared__ float s_g[kRmax];
+    __shared__ __attribute__((aligned(16))) float s_y[64 * D];
+    extern __shared__ __attribute__((aligned(16))) char s_dyn[];    // pivot stash, then Y'' fragments (hi, lo) per group
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = blockIdx.x / p.chunks, chunk = blockIdx.x % p.chunks, h = g % p.H;
+    load_potentials(p, s_g, p.T, side * p.G + g, h, false, tid);
+    stash_all_pivots<IO, D>(s_dyn, p.Z, h, p.r, p.groups, wave, lane);
+    expand_tiles<IO, D, false>(p, side, g, chunk, rows, ymat, out_rows, weight_rows, s_g, s_y, s_dyn,
+                               reinterpret_cast<bf16x8*>(s_dyn + (size_t)p.groups * StashBytes<IO, D, 2>::value));
 }
 
 // zeroes the column-sum words and marks the workspace as used by a launch that cannot fail on the device

@@ -131,6 +131,7 @@ struct Args {
     int n_q, n_k;
     const float* mass_q;
     const float* mass_k;
+    bool stepwise;       // grouped kernels: one launch per step (no kernel waits for another workgroup)
     // lot_forward_kernels: decide as for a launch, launch nothing, report the family of kernels here
     bool dry_run;
     int* family_out;
@@ -286,6 +287,7 @@ float drift_limit();
 // Testing aid (LOT_KNOB_BWD_SWEEP_LAUNCHES): run the tiled backward's forward sweep as one launch per
 // pass although the persistent form would fit.
 bool sweep_by_launches();
+int grouped_one_launch_tiles();   // testing aid: tiles per workgroup up to which the grouped forward is one launch
 
 #define LOT_HIP_CHECK(expr)                                   \
     do {                                                      \

@@ -25,5 +25,6 @@ def knobs():
     from paper_2509_23436_amd import lot
     yield lot
     for k in (lot.KNOB_SPIN_LIMIT, lot.KNOB_RESHIFT_BITS, lot.KNOB_BWD_ASSEMBLE_BY_ITERATION,
-              lot.KNOB_BWD_SWEEP_LAUNCHES, lot.KNOB_FWD_STREAMING, lot.KNOB_FWD_DRIFT_LIMIT):
+              lot.KNOB_BWD_SWEEP_LAUNCHES, lot.KNOB_FWD_STREAMING, lot.KNOB_FWD_DRIFT_LIMIT,
+              lot.KNOB_GROUPED_ONE_LAUNCH_TILES):
         lot.lot_debug_set(k, -1)

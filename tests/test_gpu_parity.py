@@ -373,13 +373,17 @@ LARGE_R = {
 }
 
 
+# The grouped kernels have two forms: one launch per step, and everything after the clearing in one launch
+# (the form AUTO takes where a workgroup has few tiles).  Each case runs in both.
+@pytest.mark.parametrize("form", ["one_launch", "launch_per_step"])
 @pytest.mark.parametrize("name", list(LARGE_R))
-def test_large_pivot_sizes_match_oracle_on_the_grouped_kernels(name):
+def test_large_pivot_sizes_match_oracle_on_the_grouped_kernels(name, form, knobs):
     import torch
     from oracle import lot_oracle
     from paper_2509_23436_amd import lot
     w = LARGE_R[name]
-    _say("case %s: %r" % (name, w))
+    _say("case %s, %s: %r" % (name, form, w))
+    lot.lot_debug_set(lot.KNOB_GROUPED_ONE_LAUNCH_TILES, (1 << 20) if form == "one_launch" else 0)
     x = synth.make_inputs(w)
     O_ref, _ = lot_oracle.attention(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, threads=4)
     dev = to_device(x, w.dtype)
@@ -402,6 +406,38 @@ def test_large_pivot_sizes_match_oracle_on_the_grouped_kernels(name):
     torch.cuda.synchronize()
     assert torch.equal(again.view(torch.int16 if w.dtype == "bf16" else torch.int32),
                        outs["fused"].view(torch.int16 if w.dtype == "bf16" else torch.int32))
+
+
+def test_one_launch_grouped_forward_reports_a_wait_that_gives_up(knobs):
+    """The one-launch form of the grouped forward waits between workgroups; with the poll budget set to zero from
+    the host every wait gives up at once: the kernel still ends, the output rows are NaN, the status words report
+    the call, and an ordinary call on the same workspace afterwards is correct."""
+    import torch
+    from oracle import lot_oracle
+    from paper_2509_23436_amd import lot
+    w = LARGE_R["r128_bf16"]
+    x = synth.make_inputs(w)
+    O_ref, _ = lot_oracle.attention(x["Q"], x["K"], x["V"], x["Z"], x["beta"], w.eps, w.iters, threads=4)
+    dev = to_device(x, w.dtype)
+    shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
+    ws = lot.alloc_workspace(shape, w.iters)
+    lot.lot_debug_set(lot.KNOB_GROUPED_ONE_LAUNCH_TILES, 1 << 20)
+    lot.lot_debug_set(lot.KNOB_SPIN_LIMIT, 0)
+    bad = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, workspace=ws)
+    assert lot.StatusProbe(ws).failed()
+    assert lot.lot_workspace_status(ws) == -10
+    assert torch.isnan(bad.float()).all()
+    lot.lot_debug_set(lot.KNOB_SPIN_LIMIT, -1)
+    out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, workspace=ws)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(ws) == 0
+    assert rel_max_err(to_host_f64(out), O_ref) <= 2e-2
+    # the path without waits is indifferent to the poll budget
+    lot.lot_debug_set(lot.KNOB_SPIN_LIMIT, 0)
+    out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters,
+                                workspace=lot.alloc_workspace(shape, w.iters, path=lot.PATH_STEPWISE), path=lot.PATH_STEPWISE)
+    torch.cuda.synchronize()
+    assert rel_max_err(to_host_f64(out), O_ref) <= 2e-2
 
 
 def test_waits_that_give_up_are_reported_and_the_next_call_recovers(knobs):
