@@ -133,7 +133,7 @@ def main() -> int:
     ap.add_argument("--warm-too", action="store_true", help="also time calls on one fixed set of buffers")
     ap.add_argument("--bwd-steps", type=int, default=50,
                     help="timed calls of the backward pass (reported beside the headline; 0 skips it)")
-    ap.add_argument("--path", default="auto", choices=["auto", "fused", "reference"])
+    ap.add_argument("--path", default="auto", choices=["auto", "fused", "reference", "stepwise"])
     ap.add_argument("--streaming", action="store_true",
                     help="testing aid: the fused forward re-reads Q and K in every pass also where the kernel "
                          "matrix would fit on chip (what sequences too long for that run)")
@@ -177,11 +177,12 @@ def main() -> int:
     if args.streaming:
         lot.lot_debug_set(lot.KNOB_FWD_STREAMING, 1)
     w = synth.WORKLOADS[args.workload]
-    path = {"auto": lot.PATH_AUTO, "fused": lot.PATH_FUSED, "reference": lot.PATH_REFERENCE}[args.path]
+    path = {"auto": lot.PATH_AUTO, "fused": lot.PATH_FUSED, "reference": lot.PATH_REFERENCE,
+            "stepwise": lot.PATH_STEPWISE}[args.path]
     x = synth.make_inputs(w)
     dev = to_device(x, w.dtype)
     shape = lot._shape_of(dev["Q"], dev["V"], dev["Z"])
-    ws = lot.alloc_workspace(shape, w.iters)
+    ws = lot.alloc_workspace(shape, w.iters, path=path)
     rotate = max(1, args.rotate)
     sets = [dev] + [{k: (v.clone() if k in ("Q", "K", "V") else v) for k, v in dev.items()} for _ in range(rotate - 1)]
     outs = [torch.empty_like(dev["V"]) for _ in range(rotate)]
@@ -304,7 +305,7 @@ def main() -> int:
     if args.bwd_steps > 0:
         # backward pass on the same rotating inputs (separate, larger workspace)
         dOs = [torch.randn_like(sets[k]["V"]) for k in range(rotate)]
-        ws_b = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape, w.iters), dtype=torch.uint8, device="cuda")
+        ws_b = torch.empty(lot.lot_attention_bwd_workspace_bytes(shape, w.iters, path), dtype=torch.uint8, device="cuda")
 
         def bstep(k):
             s_ = sets[k % rotate]
