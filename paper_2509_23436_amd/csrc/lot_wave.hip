@@ -1,7 +1,7 @@
 // LOT attention forward for short sequences: one workgroup of two wavefronts per (batch, head) problem,
-// wavefront 0 the keys' solve, wavefront 1 the queries' -- or, for sides of up to 64 NT tokens, WS = 2
-// wavefronts per side, each holding half of the side's tiles, which add up their column sums through
-// local memory once per iteration (the only workgroup barrier of an iteration).
+// wavefront 0 the keys' solve, wavefront 1 the queries' -- or WS = 2 or 4 wavefronts per side, each holding
+// NT of the side's tiles, which add up their column sums through local memory once per iteration (the only
+// workgroup barrier of an iteration).
 //
 // A side of at most 32 NT tokens has a kernel matrix exp(C/eps) of NT tiles of 32 tokens x 32 RB
 // pivots, which one wavefront can hold in its registers (bf16 pairs for bf16 I/O, fp32 for fp32 I/O;
@@ -564,30 +564,36 @@ int launch_wave(const Args& a)
     return LOT_OK;
 }
 
-// One wavefront per side: the smallest NT of the compiled set {2, 4, 8} that holds `tiles`, within what the
-// registers take (NT times the words per tile at most 128).  Nine to sixteen tiles (up to 512 tokens): two
-// wavefronts per side with eight tiles each -- one wavefront with sixteen would fit the registers too (up to 32
-// pivots in bf16) but streams so many tiles one after the other, in the passes that read Q, K, V and write O,
-// that the workgroup-level kernels were faster (measured at B H = 384, n = 512: 87 us against 76).  With at
-// most 64 kept words per lane two wavefronts share a SIMD's registers when there are more problems than
-// compute units, so that all of them are resident at once.
+// Which variant a shape runs (NT tiles per wavefront, WS wavefronts per side, WPE wavefronts per SIMD).
+//   * No more problems than compute units: every workgroup has a compute unit of its own, so a side is spread over
+//     four wavefronts (eight per workgroup, two per SIMD with 256 registers each): every phase is a quarter as long,
+//     for one workgroup barrier per iteration.  Up to 8, 16 or 32 tiles per side (n <= 256, 512, 1024) as far as
+//     the kept words per lane stay within 64.  Measured against one or two wavefronts per side: DeiT shape
+//     27 -> 21 us, B H = 192 at n = 512, r = 32 35 -> 27, B H = 8 at n = 512, r = 64 54 -> 37.
+//   * Otherwise one wavefront per side with the smallest NT of {2, 4, 8} that holds the tiles (NT times the words
+//     per tile at most 128), and for nine to sixteen tiles two wavefronts per side with eight tiles each -- one
+//     wavefront with sixteen would fit the registers too (up to 32 pivots in bf16) but streams so many tiles one
+//     after the other, in the passes that read Q, K, V and write O, that the workgroup-level kernels were faster
+//     (measured at B H = 384, n = 512: 87 us against 76).  With at most 64 kept words per lane two wavefronts
+//     share a SIMD's registers there, so that all workgroups are resident at once.
 template <typename IO, int D, int RB>
 int launch_wave_sized(const Args& a, int tiles)
 {
     constexpr int NW = ResWords<IO, RB>::value;
     constexpr int kMaxNT = 128 / NW;
+    const bool roomy = a.s.B * a.s.H <= device_cus();
     if (tiles <= 2) return launch_wave<IO, D, RB, 2, 1, 1>(a);
+    if (roomy) {
+        if (tiles <= 8) return launch_wave<IO, D, RB, 2, 4, 2>(a);
+        if constexpr (4 * NW <= 64) { if (tiles <= 16) return launch_wave<IO, D, RB, 4, 4, 2>(a); }
+        if constexpr (8 * NW <= 64) { if (tiles <= 32) return launch_wave<IO, D, RB, 8, 4, 2>(a); }
+    }
     if constexpr (kMaxNT >= 4) { if (tiles <= 4) return launch_wave<IO, D, RB, 4, 1, 1>(a); }
     if constexpr (kMaxNT >= 8) {
         if (tiles <= 8) return launch_wave<IO, D, RB, 8, 1, 1>(a);
         if (tiles <= 16) {
             if constexpr (8 * NW <= 64) {
-#ifdef LOT_EXPERIMENT_W4
-                if (a.s.B * a.s.H > device_cus()) return launch_wave<IO, D, RB, 4, 4, 4>(a);
-                return launch_wave<IO, D, RB, 4, 4, 2>(a);
-#else
-                if (a.s.B * a.s.H > device_cus()) return launch_wave<IO, D, RB, 8, 2, 2>(a);
-#endif
+                if (!roomy) return launch_wave<IO, D, RB, 8, 2, 2>(a);
             }
             return launch_wave<IO, D, RB, 8, 2, 1>(a);
         }

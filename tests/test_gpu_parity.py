@@ -41,11 +41,15 @@ CASES = {
     # fp32, d = 64, more than 32 pivots always runs with eight wavefronts: more problems than compute units
     # makes its workgroups take several problems in turn
     "two_rounds_f32_d64_r40": S(W["tiny"], B=75, H=4, n=160, d=64, r=40, iters=4, seed=37),
-    # 257 to 512 tokens: two wavefronts per side share a side's tiles (the second one with a ragged or a
-    # single tile), fp32 and bf16 kept words, one and two pivot blocks
+    # 257 to 512 tokens: several wavefronts per side share a side's tiles (the last one with a ragged or a
+    # single tile, or none), fp32 and bf16 kept words, one and two pivot blocks
     "two_waves_per_side_f32": S(W["deit_tiny"], B=3, H=3, n=400, d=64, r=16, iters=6, seed=38),
     "two_waves_per_side_bf16_r64": S(W["bert_base"], B=2, H=3, n=450, r=64, iters=7, seed=39),
     "two_waves_per_side_one_extra_token": S(W["bert_base"], B=2, H=2, n=257, r=20, iters=5, seed=40),
+    # up to 1024 tokens with no more problems than compute units: four wavefronts per side, eight tiles each
+    "four_waves_per_side_bf16": S(W["bert_base"], B=2, H=3, n=900, r=24, iters=6, seed=47),
+    # more problems than compute units, 257-512 tokens, more kept words than two wavefronts per SIMD have room for
+    "two_waves_per_side_many_problems_r64": S(W["bert_base"], B=70, H=4, n=400, r=64, iters=3, seed=48),
 }
 
 
