@@ -23,6 +23,8 @@ CASES = {
     "two_tokens": S(W["tiny"], n=2, r=1, seed=81),
     "bf16_ragged": S(W["long_4k"], B=2, H=2, n=1030, iters=5, seed=82),
     "bf16_d32": S(W["swin_t_s1"], B=2, H=3, n=400, seed=83),
+    # 999 tokens among themselves, no more problems than compute units: four wavefronts per side
+    "bf16_four_wavefronts_per_side": S(W["bert_base"], B=1, H=2, n=1000, r=32, iters=6, seed=86),
     "reference_only": S(W["tiny"], B=1, H=2, n=90, d=16, r=80, iters=4, seed=84),
     "several_softmax_chunks": S(W["tiny"], B=1, H=2, n=5000, d=32, r=8, iters=4, seed=85),
     "grouped_r128_bf16": S(W["long_4k"], B=1, H=2, n=700, r=128, iters=4, seed=87),   # 64 < r <= 256: grouped kernels
@@ -89,6 +91,8 @@ BWD_CASES = {
     "two_tokens": S(W["tiny"], n=2, r=1, seed=81),
     "bf16_ragged": S(W["long_4k"], B=1, H=2, n=1030, iters=5, seed=82),
     "bf16_d32": S(W["swin_t_s1"], B=2, H=3, n=400, seed=83),
+    # 999 tokens among themselves, no more problems than compute units: four wavefronts per side
+    "bf16_four_wavefronts_per_side": S(W["bert_base"], B=1, H=2, n=1000, r=32, iters=6, seed=86),
     "reference_only": S(W["tiny"], B=1, H=2, n=90, d=16, r=80, iters=4, seed=84),
     "several_softmax_chunks": S(W["tiny"], B=1, H=2, n=2600, d=32, r=8, iters=3, seed=85),
     # more than 64 pivots: the grouped tile kernels, here with the row stride of the [CLS] layout

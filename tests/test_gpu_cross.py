@@ -41,6 +41,11 @@ CASES = {
     "long_keys_bf16": dict(B=2, H=4, n_q=1024, n_k=9000, d=64, d_v=64, r=64, seed=506, bf16=True, masses="padded", eps=0.05, iters=6),
     "long_queries_bf16": dict(B=2, H=4, n_q=9000, n_k=500, d=64, d_v=64, r=32, seed=507, bf16=True, masses="uniform", eps=0.05, iters=6),
     "other_dims": dict(B=1, H=2, n_q=60, n_k=90, d=16, d_v=24, r=80, seed=505, bf16=False, masses="random", eps=0.1, iters=4),
+    # uniform masses, short sides of different lengths: the wavefront-per-side kernels with several wavefronts per
+    # side, some of them without a tile on the shorter side
+    "short_queries_long_keys_bf16": dict(B=2, H=2, n_q=100, n_k=400, d=64, d_v=64, r=32, seed=508, bf16=True, masses="uniform", eps=0.05, iters=7),
+    "long_queries_few_keys_bf16": dict(B=1, H=3, n_q=900, n_k=70, d=64, d_v=64, r=24, seed=509, bf16=True, masses="uniform", eps=0.1, iters=6),
+    "ragged_sides_f32": dict(B=2, H=1, n_q=77, n_k=230, d=32, d_v=32, r=48, seed=499, bf16=False, masses="uniform", eps=0.1, iters=9),
     # more than 64 pivots: the grouped tile kernels with per-side sizes and masses (the last group ragged)
     "grouped_f32_r100": dict(B=1, H=2, n_q=150, n_k=333, d=32, d_v=32, r=100, seed=520, bf16=False, masses="random", eps=0.1, iters=5),
     "grouped_padded_f32_r128": dict(B=2, H=2, n_q=400, n_k=197, d=64, d_v=64, r=128, seed=521, bf16=False, masses="padded", eps=0.1, iters=4),
