@@ -142,7 +142,7 @@ int lot_attention_fwd_static(const lot_shape* shape, const void* Q, const void* 
  *                               workgroup per problem, one, two or four wavefronts per side holding the side's whole
  *                               exp(C/eps) in their registers
  *   LOT_KERNELS_GROUPED         64 < r <= 256: pivots in groups of 64; one launch per step, or (short sequences:
- *                               few tiles per workgroup) everything after the clearing in one launch
+ *                               few tiles per workgroup) everything in one launch
  */
 typedef enum {
     LOT_KERNELS_PLAIN = 0,

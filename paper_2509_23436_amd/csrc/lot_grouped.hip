@@ -14,7 +14,7 @@
 //   per group: U = sum_j W2 V) | mid (Y'' = n beta/cs1 * U/cs2) | expand (queries -> O):
 //   * one launch per step, launch boundaries the only synchronisation between workgroups (any size; the form
 //     of LOT_PATH_STEPWISE);
-//   * lg_persistent: everything after the clearing in ONE launch, for the sizes where the launches themselves
+//   * lg_persistent: everything in ONE launch, for the sizes where the launches themselves
 //     are what a call costs (short sequences).  A workgroup keeps its chunk of one side for the whole call, the
 //     pivots and the potentials stay in its LDS, and what the launch boundaries ordered is ordered by bounded
 //     waits: the words of a pass carry, in their top byte, the number of workgroups that have added their share,
@@ -148,8 +148,9 @@ constexpr size_t kPersistentLdsMax = 160 * 1024;
 
 // LDS of lg_persistent: potentials, pivots of all groups, then the largest of the stages' working areas.
 constexpr int kCountShiftLg = 56;     // an exchanged word: workgroups that have added their share in the top byte
-// 64-bit words that hold the counters of the one-launch form: [G][2] unsigned
-inline size_t lg_counter_words(size_t G, size_t) { return G; }
+// 64-bit words that hold the counters of the one-launch form: [G][2] unsigned, then one word per pair that takes
+// the launch's nonce once the pair's words and counters have been zeroed
+inline size_t lg_counter_words(size_t G, size_t) { return G + 2 * G; }
 
 // The first wavefront of a workgroup polls the words of one pass of one pair until each carries `chunks`
 // arrivals; lane l then holds the words of pivots l, 64 + l, ... in word[].  False, for the whole workgroup, if
@@ -207,6 +208,24 @@ __device__ __forceinline__ bool wait_for_count(const LgParams& p, unsigned* coun
     __syncthreads();
     return ok;
 }
+// Waits (thread 0 polls) until *word holds this launch's nonce: the pair's words and counters have been zeroed.
+__device__ __forceinline__ bool wait_for_nonce(const LgParams& p, const unsigned long long* word, int* s_flag, int tid)
+{
+    if (tid == 0) {
+        bool ok = false;
+        for (uint32_t k = 0; k < p.spin_limit; ++k) {
+            if (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.nonce) { ok = true; break; }
+            if ((k & 63u) == 63u && gave_up(p.status, p.nonce)) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (!ok) give_up(p.status, p.nonce);
+        s_flag[0] = ok;
+    }
+    __syncthreads();
+    const bool ok = s_flag[0] != 0;
+    __syncthreads();
+    return ok;
+}
 // Counts the workgroup off at *counter once everything its wavefronts have stored or added has left them.
 // Returns, to every thread, how many had counted themselves off before.
 __device__ __forceinline__ unsigned count_off(unsigned* counter, int* s_flag, int tid)
@@ -256,6 +275,23 @@ __global__ void __launch_bounds__(kThreads, 2) lg_persistent(LgParams p)
     first_tile_of_pass<IO, D>(xc, p, pair, chunk, wave, lane);
     for (int t = tid; t < kRmax; t += kThreads) s_g[t] = t < p.r ? 0.f : kNegBig;
     stash_all_pivots<IO, D>(s_zstash, p.Z, h, p.r, p.groups, wave, lane);
+    // No clearing launch: the first workgroup of a pair zeroes the pair's words of every pass (the keys' also the
+    // problem's two counters) and then publishes the launch's nonce; the others wait for it before they add anything.
+    unsigned long long* const ready = reinterpret_cast<unsigned long long*>(p.sync + 2 * (size_t)p.G);
+    if (chunk == 0) {
+        for (int k = 1; k <= T; ++k)
+            for (int t = tid; t < kRmax; t += kThreads)
+                __hip_atomic_store(p.colacc + ((size_t)k * pairs + pair) * kRmax + t, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (side == 1 && tid < 2) __hip_atomic_store(p.sync + 2 * g + tid, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (blockIdx.x == 0 && tid == 0)   // this launch; word 0, written only by a wait that gave up, cannot hold the same nonce
+            __hip_atomic_store(p.status + 1, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) __hip_atomic_store(ready + pair, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (!wait_for_nonce(p, ready + pair, s_flag, tid)) {
+        if (side == 0) poison_chunk<IO, D>(p, g, chunk);
+        return;
+    }
     __syncthreads();
 
     for (int k = 1; k <= T; ++k) {
@@ -324,8 +360,10 @@ __global__ void __launch_bounds__(kThreads, 2) lg_persistent(LgParams p)
         return;
     }
 
-    // queries: wait for Y'' of the problem, then expand this chunk
-    if (!wait_for_count(p, p.sync + 2 * g + 1, (unsigned)p.chunks, s_flag, tid)) {
+    // queries: wait for Y'' of the problem (its counter is valid once the keys' first workgroup has zeroed it), then
+    // expand this chunk
+    if (!wait_for_nonce(p, ready + p.G + g, s_flag, tid) ||
+        !wait_for_count(p, p.sync + 2 * g + 1, (unsigned)p.chunks, s_flag, tid)) {
         poison_chunk<IO, D>(p, g, chunk);
         return;
     }
@@ -340,10 +378,8 @@ int launch_grouped(const Args& a, LgParams p)
     constexpr int NB = D / 32;
     hipStream_t st = a.stream;
     const int pairs = 2 * p.G, T = a.iters;
-    // (the counters of the one-launch form sit right behind the words and are cleared with them)
-    const size_t words = (size_t)(T + 1) * pairs * kRmax + lg_counter_words(p.G, T);
+    const size_t words = (size_t)(T + 1) * pairs * kRmax;
     p.nonce = next_nonce();
-    lg_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words, (unsigned long long*)a.ws, p.nonce);
 
     // The one-launch form, where the launches are what the call costs: the whole grid must be resident at once,
     // and a workgroup should have few tiles (the keys' workgroups alone contract with V there, group after group).
@@ -386,6 +422,7 @@ int launch_grouped(const Args& a, LgParams p)
             }
         }
     }
+    lg_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words, (unsigned long long*)a.ws, p.nonce);
     const size_t stash = (size_t)p.groups * StashBytes<IO, D, 2>::value;
     const size_t frag_bytes = (size_t)p.groups * 2 * (2 * 2 * NB * 64) * sizeof(bf16x8);
     // more than 64 KB of LDS per workgroup has to be asked for explicitly

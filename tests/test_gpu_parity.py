@@ -377,7 +377,7 @@ LARGE_R = {
 }
 
 
-# The grouped kernels have two forms: one launch per step, and everything after the clearing in one launch
+# The grouped kernels have two forms: one launch per step, and everything in one launch
 # (the form AUTO takes where a workgroup has few tiles).  Each case runs in both.
 @pytest.mark.parametrize("form", ["one_launch", "launch_per_step"])
 @pytest.mark.parametrize("name", list(LARGE_R))
