@@ -67,14 +67,17 @@ int run_fused(const Args& a, bool want_out)
 {
     if (!fused_supports(a.s)) return LOT_ERR_PATH;
     // the variants that keep the kernel matrix on chip, where a workgroup's share of it fits
-    if (want_out && a.mass_q == nullptr && a.mass_k == nullptr && forward_variants() != 1) {
-        // short sequences: a wavefront per side, the whole kernel matrix in its registers
+    if (want_out && forward_variants() != 1) {
+        // short sequences: a workgroup per problem, the whole kernel matrix in its wavefronts' registers
         if (forward_variants() != 2) {
             const int rc = run_wave(a);
             if (rc != LOT_ERR_PATH) return rc;
         }
-        const int rc = run_fused_resident(a);
-        if (rc != LOT_ERR_PATH) return rc;
+        // (the workgroup-level kept-matrix kernels take uniform token masses only)
+        if (a.mass_q == nullptr && a.mass_k == nullptr) {
+            const int rc = run_fused_resident(a);
+            if (rc != LOT_ERR_PATH) return rc;
+        }
     }
     return a.s.io_dtype == LOT_BF16 ? dispatch<uint16_t>(a, want_out) : dispatch<float>(a, want_out);
 }

@@ -29,6 +29,7 @@ struct WaveParams {
     int G, H, r, iters;
     int n_side[2];        // 0 = keys and values, 1 = queries and the output
     int stride_side[2];   // tokens between consecutive problems in memory
+    const float* mass_side[2];   // [G][n_side] token masses, or null: uniform 1 / n_side
     float eps;
     float drift_half;     // a pivot's potential may move this many binary orders away from pivot 0's before the kernel matrix is recomputed
     unsigned long long* trace;   // LOT_TRACE builds only: 32 stamps for the first wavefront of each side, 128 per workgroup
@@ -165,6 +166,17 @@ __global__ void __launch_bounds__(128 * WS) __attribute__((amdgpu_waves_per_eu(W
     for (int sl = 0; sl < NT; ++sl)
 #pragma unroll
         for (int q = 0; q < NW; ++q) kq[sl][q] = 0u;
+    // token masses times n (1 for uniform masses): they weight what a token adds to the column sums and to the
+    // contraction with V, not its own row of the output (paper, "Empirical measures and pivot": general marginals)
+    float nm[NT];
+    {
+        const float* const mass = p.mass_side[side];
+#pragma unroll
+        for (int sl = 0; sl < NT; ++sl) {
+            const int tok = tok0 + sl * kTileTokens + i;
+            nm[sl] = (mass != nullptr && tok < n) ? (float)n * as_global(mass)[(size_t)g * n + tok] : 1.f;
+        }
+    }
 
     // ---- the kernel matrix with the current potentials folded in (zero at first; -big for padding pivots).
     //      A single wavefront per SIMD has nobody to switch to while it waits for memory, so the rows of
@@ -249,7 +261,7 @@ __global__ void __launch_bounds__(128 * WS) __attribute__((amdgpu_waves_per_eu(W
                         s3 = fmaf(k[mb][j + 3], vC[mb][j + 3], s3);
                     }
                 const float s = pair_sum((s0 + s1) + (s2 + s3));
-                const float w = tok0 + slot * kTileTokens + i < n ? rcp_fast(s) : 0.f;
+                const float w = tok0 + slot * kTileTokens + i < n ? rcp_fast(s) * nm[slot] : 0.f;
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -313,7 +325,7 @@ __global__ void __launch_bounds__(128 * WS) __attribute__((amdgpu_waves_per_eu(W
                         s3 = fmaf(k[mb][j + 3], vC[mb][j + 3], s3);
                     }
                 const float s = pair_sum((s0 + s1) + (s2 + s3));
-                const float w = tok0 + slot * kTileTokens + i < n ? rcp_fast(s) : 0.f;
+                const float w = tok0 + slot * kTileTokens + i < n ? rcp_fast(s) * nm[slot] : 0.f;
 #pragma unroll
                 for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -551,6 +563,7 @@ int launch_wave(const Args& a)
     p.n_side[0] = a.n_k > 0 ? a.n_k : s.n;
     p.n_side[1] = a.n_q > 0 ? a.n_q : s.n;
     for (int sd = 0; sd < 2; ++sd) p.stride_side[sd] = a.n_stride > 0 ? a.n_stride : p.n_side[sd];
+    p.mass_side[0] = a.mass_k; p.mass_side[1] = a.mass_q;
     p.drift_half = 0.5f * drift_limit();
 #ifdef LOT_TRACE
     p.trace = (unsigned long long*)(a.ws + a.lay.fused_total);   // (developer builds: see the fused kernel)
@@ -614,10 +627,10 @@ int dispatch_wave(const Args& a, int tiles)
 
 }  // namespace
 
-// Attention with uniform token masses where each side fits one wavefront's registers; LOT_ERR_PATH otherwise.
+// Attention where each side fits the registers of a workgroup's wavefronts; LOT_ERR_PATH otherwise.
 int run_wave(const Args& a)
 {
-    if (!fused_supports(a.s) || a.mass_q != nullptr || a.mass_k != nullptr || a.out == nullptr) return LOT_ERR_PATH;
+    if (!fused_supports(a.s) || a.out == nullptr) return LOT_ERR_PATH;
     const int n_k = a.n_k > 0 ? a.n_k : a.s.n, n_q = a.n_q > 0 ? a.n_q : a.s.n;
     const int longer = n_k > n_q ? n_k : n_q;
     const int tiles = (longer + kTileTokens - 1) / kTileTokens;
