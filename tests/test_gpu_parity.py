@@ -50,6 +50,9 @@ CASES = {
     "four_waves_per_side_bf16": S(W["bert_base"], B=2, H=3, n=900, r=24, iters=6, seed=47),
     # more problems than compute units, 257-512 tokens, more kept words than two wavefronts per SIMD have room for
     "two_waves_per_side_many_problems_r64": S(W["bert_base"], B=70, H=4, n=400, r=64, iters=3, seed=48),
+    # the same regime in fp32 and with head width 32, the last wavefront of a side ragged
+    "many_problems_f32_n300": S(W["tiny"], B=90, H=3, n=300, d=32, r=16, iters=4, seed=49),
+    "many_problems_bf16_d32_n290": S(W["swin_t_s1"], B=100, H=3, n=290, iters=5, seed=55),
 }
 
 
