@@ -73,11 +73,8 @@ int run_fused(const Args& a, bool want_out)
             const int rc = run_wave(a);
             if (rc != LOT_ERR_PATH) return rc;
         }
-        // (the workgroup-level kept-matrix kernels take uniform token masses only)
-        if (a.mass_q == nullptr && a.mass_k == nullptr) {
-            const int rc = run_fused_resident(a);
-            if (rc != LOT_ERR_PATH) return rc;
-        }
+        const int rc = run_fused_resident(a);
+        if (rc != LOT_ERR_PATH) return rc;
     }
     return a.s.io_dtype == LOT_BF16 ? dispatch<uint16_t>(a, want_out) : dispatch<float>(a, want_out);
 }

@@ -416,7 +416,7 @@ __device__ __forceinline__ void request_first_tile(const FusedParams& p, const I
 // run_pass<EPI_NONE> (current potentials folded in, rows shifted by their maxima) and keeps it: in kq
 // (registers) or, TO_LDS, in this wavefront's block of the LDS area.  It forms no sums: the caller
 // follows it with a pass over the kept matrix with v = 1 (holding the column-sum accumulators as
-// well would not leave the registers for it).  Uniform token masses only.  At most NT tiles per
+// well would not leave the registers for it).  At most NT tiles per
 // wavefront (the launcher's condition for these variants).  The loop over the slots is unrolled only
 // where the slot picks registers.
 template <typename IO, int D, int RB, int WAVES, int NT, bool TO_LDS>
@@ -635,11 +635,15 @@ __device__ __forceinline__ void kept_column_sums(f32x16 (&cs)[RB], const uint32_
 // per pivot; the caller multiplies the reduced sums by v_t.  fp32 I/O: vector arithmetic on the fp32
 // entries.  bf16 I/O: the row sums on the matrix cores, straight from the packed words, and under way
 // for the next tile while the vector unit forms the column sums of the current one.
-template <typename IO, int RB, int WAVES, int NT, bool FROM_LDS>
+// MASS: the tokens carry masses; nm[slot] = n times the mass of this lane's token of the wavefront's tile `slot`
+// (kept in registers: fetched per pass, with one wavefront per SIMD, every tile would wait for memory -- measured
+// 313 us against 191 on the streaming kernel at the headline shape); it multiplies what the token adds to the column sums.
+template <typename IO, int RB, int WAVES, int NT, bool FROM_LDS, bool MASS>
 __device__ __forceinline__ void cheap_pass(
     const FusedParams& p, int side, int tile_begin, int tile_end, int lane, int wave, const float* vlds,
     const uint16_t* vhl, bool unit_v,
-    f32x16 (&cs)[RB], const uint32_t (&kq)[NT][(ResWords<IO, RB>::value)], const u32x4* kres_wave)
+    f32x16 (&cs)[RB], const uint32_t (&kq)[NT][(ResWords<IO, RB>::value)], const u32x4* kres_wave,
+    const float (&nm)[MASS ? NT : 1])
 {
     constexpr int NW = ResWords<IO, RB>::value;
     const int i = lane & 31, kg = lane >> 5;
@@ -669,7 +673,8 @@ __device__ __forceinline__ void cheap_pass(
                     words_of(w[(slot + 1) & 1], slot + 1);
                     d[(slot + 1) & 1] = kept_row_sums<RB>(vf, w[(slot + 1) & 1]);
                 }
-                kept_column_sums<RB>(cs, w[slot & 1], rcp_fast(d[slot & 1][0] + d[slot & 1][1]));
+                const float weight = rcp_fast(d[slot & 1][0] + d[slot & 1][1]);
+                kept_column_sums<RB>(cs, w[slot & 1], MASS ? weight * nm[MASS ? slot : 0] : weight);
             }
             return;
         }
@@ -681,7 +686,7 @@ __device__ __forceinline__ void cheap_pass(
                 words_of(w, slot);
                 const f32x16 d = kept_row_sums<RB>(vf, w);
                 const int tok = tile * kTileTokens + i;
-                kept_column_sums<RB>(cs, w, tok < n ? rcp_fast(d[0] + d[1]) : 0.f);
+                kept_column_sums<RB>(cs, w, tok < n ? rcp_fast(d[0] + d[1]) * (MASS ? nm[MASS ? slot : 0] : 1.f) : 0.f);
             }
         }
         return;
@@ -694,7 +699,7 @@ __device__ __forceinline__ void cheap_pass(
 #pragma unroll
             for (int j = 0; j < 16; ++j) v[mb][j] = 1.f;
     }
-    constexpr int kUnrollSlots = FROM_LDS ? 1 : NT;   // unrolled only where the slot picks registers
+    constexpr int kUnrollSlots = (FROM_LDS && !MASS) ? 1 : NT;   // unrolled only where the slot picks registers
 #pragma unroll kUnrollSlots
     for (int slot = 0; slot < NT; ++slot) {
         const int tile = tile_begin + wave + slot * WAVES;
@@ -719,7 +724,7 @@ __device__ __forceinline__ void cheap_pass(
                 }
             const float s = pair_sum((s0 + s1) + (s2 + s3));
             const int tok = tile * kTileTokens + i;
-            const float w = tok < n ? rcp_fast(s) : 0.f;
+            const float w = tok < n ? rcp_fast(s) * (MASS ? nm[MASS ? slot : 0] : 1.f) : 0.f;
 #pragma unroll
             for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
@@ -736,10 +741,11 @@ __device__ __forceinline__ void cheap_pass(
 // the current slot's transposed tile is written (block layout: see the kernel).  The value rows of AHEAD
 // tiles are kept in flight: this is the only pass of these variants that reads memory it has not asked
 // for long before, and with one wavefront per SIMD nobody else runs while it waits.
-template <typename IO, int D, int RB, int WAVES, int NT, int AHEAD>
+template <typename IO, int D, int RB, int WAVES, int NT, int AHEAD, bool MASS>
 __device__ __forceinline__ void accum_from_kept(
     const FusedParams& p, const IO* __restrict__ V, int g, int tile_begin, int tile_end, int lane, int wave,
-    const float* vlds, const uint16_t* vhl, bool unit_v, f32x16 (&cs)[RB], f32x16 (&U)[RB][D / 32], char* block)
+    const float* vlds, const uint16_t* vhl, bool unit_v, f32x16 (&cs)[RB], f32x16 (&U)[RB][D / 32], char* block,
+    const float (&nm)[MASS ? NT : 1])
 {
     constexpr int NW = ResWords<IO, RB>::value;
     constexpr int NB = D / 32;
@@ -786,7 +792,7 @@ __device__ __forceinline__ void accum_from_kept(
     res_from_lds<NW>(cur, kres_wave, lane);
 #pragma unroll
     for (int q = 0; q < NW; ++q) nxt[q] = 0u;
-    constexpr int kUnrollSlots = kAhead ? NT : 1;   // unrolled only where the slot picks the registers of the value rows
+    constexpr int kUnrollSlots = (kAhead || MASS) ? NT : 1;   // unrolled only where the slot picks registers (value rows, masses)
 #pragma unroll kUnrollSlots
     for (int slot = 0; slot < NT; ++slot) {
         const int tile = tile_begin + wave + slot * WAVES;
@@ -830,7 +836,8 @@ __device__ __forceinline__ void accum_from_kept(
                 s = pair_sum((s0 + s1) + (s2 + s3));
             }
             const int tok = tile * kTileTokens + i;
-            const float w = tok < n ? rcp_fast(s) : 0.f;
+            float w = tok < n ? rcp_fast(s) : 0.f;
+            if constexpr (MASS) w *= nm[MASS ? slot : 0];   // the keys' masses weight U as well
             // (the words of this slot and of the next are in registers: their bytes may be overwritten now)
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -989,7 +996,7 @@ __device__ __forceinline__ void poison_rows(const FusedParams& p, int g, int til
 // partial column sums are posted right after the pass, and collected only when that side's next
 // pass is about to start -- one whole pass of the other side later -- so the latency of the
 // exchange (and the spread between workgroups) is hidden behind useful work.
-template <typename IO, int D, int RB, int WAVES, int NT>
+template <typename IO, int D, int RB, int WAVES, int NT, bool MASS = false>
 __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
 {
     constexpr int NB = D / 32;
@@ -1415,6 +1422,21 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
                 for (int q = 0; q < NW; ++q) kq[sl][q] = 0u;
             char* const block = s_big + (size_t)wave * kBlockBytes;
             u32x4* const kres_wave = reinterpret_cast<u32x4*>(block);
+            // n times the mass of this lane's token of every tile of the wavefront, per side (a side without masses
+            // of its own: 1; a token past the end takes the last one's, its weight is 0 anyway)
+            float nmass[2][MASS ? NT : 1];
+            if constexpr (MASS) {
+#pragma unroll
+                for (int sd = 0; sd < 2; ++sd) {
+                    const float* const ms = p.mass_side[sd];
+                    const int ns = p.n_side[sd];
+#pragma unroll
+                    for (int sl = 0; sl < NT; ++sl) {
+                        const int tok = min((tile_begins[sd] + wave + sl * WAVES) * kTileTokens + i, ns - 1);
+                        nmass[sd][sl] = ms != nullptr ? (float)ns * as_global(ms)[(size_t)g * ns + tok] : 1.f;
+                    }
+                }
+            }
             const void* const zlds = similarity_by_pieces<IO, D, RB, WAVES>() ? (const void*)s_zf : (const void*)s_zst;
             bool have_first = true;     // xfirst holds the first key tile
             // One pass and its exchange.  The last key pass (with_u_c = true_type: it also contracts with V) is
@@ -1454,13 +1476,13 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
 #pragma unroll
                                 for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
                         // (a SIMD and its 512 registers to itself: three tiles' value rows in flight; otherwise one)
-                        accum_from_kept<IO, D, RB, WAVES, NT, (WAVES == 4 && NT >= 8 ? LOT_ACCUM_AHEAD : 1)>(
+                        accum_from_kept<IO, D, RB, WAVES, NT, (WAVES == 4 && NT >= 8 ? LOT_ACCUM_AHEAD : 1), MASS>(
                             p, reinterpret_cast<const IO*>(p.V), g, tile_begins[0], tile_ends[0], lane, wave,
-                            s_v[0], &s_vhl[0][0][0], fill, cs, U, block);
+                            s_v[0], &s_vhl[0][0][0], fill, cs, U, block, nmass[0]);
                         alive = exchange(0, it, true, 1, it - 1, false, !fill);
                     } else {
-                        if (side == 0) cheap_pass<IO, RB, WAVES, NT, true>(p, 0, tile_begins[0], tile_ends[0], lane, wave, s_v[0], &s_vhl[0][0][0], fill, cs, kq, kres_wave);
-                        else cheap_pass<IO, RB, WAVES, NT, false>(p, 1, tile_begins[1], tile_ends[1], lane, wave, s_v[1], &s_vhl[1][0][0], fill, cs, kq, kres_wave);
+                        if (side == 0) cheap_pass<IO, RB, WAVES, NT, true, MASS>(p, 0, tile_begins[0], tile_ends[0], lane, wave, s_v[0], &s_vhl[0][0][0], fill, cs, kq, kres_wave, nmass[0]);
+                        else cheap_pass<IO, RB, WAVES, NT, false, MASS>(p, 1, tile_begins[1], tile_ends[1], lane, wave, s_v[1], &s_vhl[1][0][0], fill, cs, kq, kres_wave, nmass[1]);
                         alive = exchange(side, it, false, side ^ 1, side == 1 ? it : it - 1, side == 1 && it == p.iters, !fill);
                     }
                     if (!alive) {
@@ -1598,7 +1620,7 @@ __global__ void __launch_bounds__(WAVES * 64, 2) lot_fused_kernel(FusedParams p)
 }
 
 // Workgroups the device holds at once for this variant (asked once per device and variant).
-template <typename IO, int D, int RB, int WAVES, int NT>
+template <typename IO, int D, int RB, int WAVES, int NT, bool MASS = false>
 int fused_capacity(int* out)
 {
     static thread_local int capacity_cache[8] = {0};   // per device ordinal
@@ -1607,7 +1629,7 @@ int fused_capacity(int* out)
     int capacity = (dev >= 0 && dev < 8) ? capacity_cache[dev] : 0;
     if (capacity == 0) {
         int per_cu = 0, cus = 0;
-        LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lot_fused_kernel<IO, D, RB, WAVES, NT>, WAVES * 64, 0));
+        LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lot_fused_kernel<IO, D, RB, WAVES, NT, MASS>, WAVES * 64, 0));
         LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         capacity = per_cu * cus;
         if (capacity < 1) { last_hip_error() = hipErrorLaunchOutOfResources; return LOT_ERR_HIP; }
@@ -1642,17 +1664,17 @@ inline FusedSplit fused_split(const Args& a, int waves, int capacity)
 }
 
 // NT > 0: the variant that keeps the kernel matrix on chip; the caller has checked that no wavefront
-// gets more than NT tiles of a side (LOT_ERR_PATH otherwise) and that the token masses are uniform.
-template <typename IO, int D, int RB, int WAVES, int NT>
+// gets more than NT tiles of a side (LOT_ERR_PATH otherwise); MASS: the instantiation that takes token masses.
+template <typename IO, int D, int RB, int WAVES, int NT, bool MASS = false>
 int launch(const Args& a, bool want_out)
 {
     constexpr int kThreads = WAVES * 64;
     const lot_shape& s = a.s;
     const int G = s.B * s.H;
-    auto kernel = lot_fused_kernel<IO, D, RB, WAVES, NT>;
+    auto kernel = lot_fused_kernel<IO, D, RB, WAVES, NT, MASS>;
     int capacity = 0;
     {
-        const int rc = fused_capacity<IO, D, RB, WAVES, NT>(&capacity);
+        const int rc = fused_capacity<IO, D, RB, WAVES, NT, MASS>(&capacity);
         if (rc != LOT_OK) return rc;
     }
 
@@ -1662,7 +1684,7 @@ int launch(const Args& a, bool want_out)
     const FusedSplit split = fused_split(a, WAVES, capacity);
     const int cluster = split.cluster;
     if (NT > 0) {
-        if ((split.tiles_per_wg + WAVES - 1) / WAVES > NT || !want_out || a.mass_q != nullptr || a.mass_k != nullptr)
+        if ((split.tiles_per_wg + WAVES - 1) / WAVES > NT || !want_out || ((a.mass_q != nullptr || a.mass_k != nullptr) && !MASS))
             return LOT_ERR_PATH;
     }
 

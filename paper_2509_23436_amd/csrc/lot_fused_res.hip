@@ -9,13 +9,13 @@ namespace {
 // Largest NT per variant: what the register file (queries) and the LDS (keys) hold.  bf16 I/O keeps the
 // matrix as bf16 pairs: 8 RB registers per tile; fp32 I/O as fp32: 16 RB registers per tile, and its
 // pivot pieces already take up to 24 KB of LDS.
-template <typename IO, int D, int RB, int WAVES>
+template <typename IO, int D, int RB, int WAVES, bool MASS>
 int launch_resident(const Args& a)
 {
-    int rc = launch<IO, D, RB, WAVES, 1>(a, true);
+    int rc = launch<IO, D, RB, WAVES, 1, MASS>(a, true);
     if (rc != LOT_ERR_PATH) return rc;
     if constexpr (!io_is_f32<IO>::value || RB == 1) {
-        rc = launch<IO, D, RB, WAVES, 2>(a, true);
+        rc = launch<IO, D, RB, WAVES, 2, MASS>(a, true);
         if (rc != LOT_ERR_PATH) return rc;
     }
     if constexpr (!io_is_f32<IO>::value) {
@@ -23,9 +23,9 @@ int launch_resident(const Args& a)
             // Four tiles per wavefront beside the working set overflow the 256 registers a wavefront has when
             // two share a SIMD, and the spills travel to memory and back in every call.  Four wavefronts
             // per workgroup have a SIMD each, hence 512 registers: eight tiles per wavefront fit.
-            rc = launch<IO, D, RB, 4, 8>(a, true);
+            rc = launch<IO, D, RB, 4, 8, MASS>(a, true);
         } else {
-            rc = launch<IO, D, RB, WAVES, 4>(a, true);
+            rc = launch<IO, D, RB, WAVES, 4, MASS>(a, true);
         }
     }
     return rc;
@@ -38,11 +38,13 @@ int launch_resident_sized(const Args& a)
     int dev = 0, cus = 0;
     LOT_HIP_CHECK(hipGetDevice(&dev));
     LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    // (token masses: instantiations of their own, so that the kernels without them stay exactly as they are)
+    const bool mass = a.mass_q != nullptr || a.mass_k != nullptr;
     if constexpr (io_is_f32<IO>::value && D == 64 && RB == 2) {
-        return launch_resident<IO, D, RB, 8>(a);
+        return mass ? launch_resident<IO, D, RB, 8, true>(a) : launch_resident<IO, D, RB, 8, false>(a);
     } else {
-        if (a.s.B * a.s.H <= cus) return launch_resident<IO, D, RB, 8>(a);
-        return launch_resident<IO, D, RB, 4>(a);
+        if (a.s.B * a.s.H <= cus) return mass ? launch_resident<IO, D, RB, 8, true>(a) : launch_resident<IO, D, RB, 8, false>(a);
+        return mass ? launch_resident<IO, D, RB, 4, true>(a) : launch_resident<IO, D, RB, 4, false>(a);
     }
 }
 
@@ -61,7 +63,7 @@ int dispatch_resident(const Args& a)
 
 int run_fused_resident(const Args& a)
 {
-    if (!fused_supports(a.s) || a.mass_q != nullptr || a.mass_k != nullptr) return LOT_ERR_PATH;
+    if (!fused_supports(a.s)) return LOT_ERR_PATH;
     // More than 32 pivots and few iterations: computing and storing the kernel matrix, then sweeping it once
     // more for the first column sums, costs more than the few passes it saves (measured over B H = 8 .. 16,
     // n = 4096 .. 32768: 3-15 % slower than the streaming kernel at T = 3 and 5, level or faster from T = 10).
