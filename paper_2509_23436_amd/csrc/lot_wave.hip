@@ -30,6 +30,8 @@ struct WaveParams {
     int n_side[2];        // 0 = keys and values, 1 = queries and the output
     int stride_side[2];   // tokens between consecutive problems in memory
     const float* mass_side[2];   // [G][n_side] token masses, or null: uniform 1 / n_side
+    unsigned long long* status;  // the workspace's status words: [1] takes the launch's nonce (nothing here can fail,
+    unsigned long long nonce;    // and a mark that an earlier, failed launch of another kernel left must not outlive it)
     float eps;
     float drift_half;     // a pivot's potential may move this many binary orders away from pivot 0's before the kernel matrix is recomputed
     unsigned long long* trace;   // LOT_TRACE builds only: 32 stamps for the first wavefront of each side, 128 per workgroup
@@ -101,6 +103,7 @@ __global__ void __launch_bounds__(128 * WS) __attribute__((amdgpu_waves_per_eu(W
     const int i = lane & 31, kg = lane >> 5;
     const int g = blockIdx.x, h = g % p.H;
     const int r = p.r;
+    if (g == 0 && tid == 0) __hip_atomic_store(p.status + 1, p.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int n = p.n_side[side], stride = p.stride_side[side];
     const float c1 = kLog2e / p.eps;
     // this wavefront's tiles: NT consecutive ones from tile part * NT of the side (tok0 = its first token)
@@ -572,6 +575,8 @@ int launch_wave(const Args& a)
         if (a.family_out) *a.family_out = LOT_KERNELS_KEPT_WAVEFRONT;
         return LOT_OK;
     }
+    p.status = (unsigned long long*)(a.ws + a.lay.status);
+    p.nonce = next_nonce();
     lot_wave_kernel<IO, D, RB, NT, WS, WPE><<<dim3((unsigned)p.G), dim3(128 * WS), 0, a.stream>>>(p);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;

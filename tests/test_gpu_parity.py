@@ -475,6 +475,17 @@ def test_waits_that_give_up_are_reported_and_the_next_call_recovers(knobs):
     assert not lot.StatusProbe(ws).failed()
     assert lot.lot_workspace_status(ws) == 0
     assert rel_max_err(to_host_f64(out), O_ref) <= 2e-2
+    # a failure mark does not outlive the next launch on the workspace, whichever kernels that launch runs: fail once
+    # more, then let a problem that the wavefront-per-side kernels take use the same workspace
+    lot.lot_debug_set(lot.KNOB_SPIN_LIMIT, 0)
+    lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], w.eps, w.iters, workspace=ws, path=lot.PATH_FUSED)
+    lot.lot_debug_set(lot.KNOB_SPIN_LIMIT, -1)
+    assert lot.lot_workspace_status(ws) == -10
+    short = {k: (v[:, :, :200].contiguous() if k in ("Q", "K", "V") else v) for k, v in dev.items()}
+    assert lot.lot_forward_kernels(lot._shape_of(short["Q"], short["V"], short["Z"]), w.iters) == "kept_wavefront"
+    lot.lot_attention_fwd(short["Q"], short["K"], short["V"], short["Z"], short["beta"], w.eps, w.iters, workspace=ws)
+    torch.cuda.synchronize()
+    assert lot.lot_workspace_status(ws) == 0
 
     wb = S(W["long_4k"], B=1, H=2, n=3000, iters=3, seed=37)
     xb = synth.make_inputs(wb)
