@@ -238,9 +238,9 @@ int lot_cross_attention_fwd_path(const lot_xshape* shape, const void* Q, const v
  * of 64; iters <= 64: the per-iteration tables live in a workgroup's local memory, and where those of all
  * groups do not fit there together the kernel that assembles dQ and dK runs once per run of groups, with
  * fp32 partial rows in the workspace in between; LOT_ERR_PATH beyond).  AUTO prefers
- * FUSED, except for fewer than 16 tokens and, with fp32 I/O, for r <= 2: there the rounding of the tile
- * kernels' split-bf16 contractions (2^-16) is not averaged out, or is magnified by the cancellation in
- * the gradient of two masses, and the plain kernels, exact to fp32 rounding, run instead.
+ * FUSED, except for fewer than 16 tokens and for r <= 2: there the rounding of the tile kernels'
+ * contractions (2^-16 with fp32 I/O, bf16 operands with bf16 I/O) is not averaged out, or is magnified by
+ * the cancellation in the gradient of two masses, and the plain kernels, exact to fp32 rounding, run instead.
  * Results are reproducible bit for bit on either path.  lot_workspace_status applies to this
  * workspace too (the FUSED path's forward sweep waits between workgroups when it runs as one kernel).
  * The FUSED path (r <= 64) rebuilds each tile's row-normalised kernels for all iterations with ONE shift
@@ -347,6 +347,10 @@ int lot_status_words(const unsigned long long* host_words);
  *   LOT_KNOB_GROUPED_ONE_LAUNCH_TILES  the grouped forward (r > 64) runs as one launch when a workgroup has at
  *                                      most this many tiles of 32 tokens per side and the grid fits the device
  *                                      (default 8; 0: always one launch per step; large: wherever it fits)
+ *   LOT_KNOB_BWD_SWEEP_RECOMPUTE       non-zero: the backward's forward sweep recomputes the similarities in every
+ *                                      pass also where a wavefront has so few tiles that it would keep them in
+ *                                      registers (the two forms differ by rounding, 1e-7; the one-launch-per-pass
+ *                                      form always recomputes)
  * Returns LOT_OK, or LOT_ERR_SHAPE for an unknown knob.
  */
 typedef enum {
@@ -357,7 +361,8 @@ typedef enum {
     LOT_KNOB_FWD_STREAMING = 4,
     LOT_KNOB_FWD_DRIFT_LIMIT = 5,
     LOT_KNOB_GROUPED_ONE_LAUNCH_TILES = 6,
-    LOT_KNOB_COUNT_ = 7
+    LOT_KNOB_BWD_SWEEP_RECOMPUTE = 7,
+    LOT_KNOB_COUNT_ = 8
 } lot_knob;
 int lot_debug_set(int knob, long long value);
 

@@ -89,6 +89,12 @@ int grouped_one_launch_tiles()
     return 8;
 }
 
+bool sweep_keeps_similarities()
+{
+    long long v;
+    return !(knob(LOT_KNOB_BWD_SWEEP_RECOMPUTE, &v) && v != 0);
+}
+
 bool sweep_by_launches()
 {
     long long v;
@@ -499,9 +505,11 @@ enum BwdImpl { BWD_PLAIN = 0, BWD_TILED = 1, BWD_GROUPED = 2 };
 // identically (a single token, say) come out as noise at 1e-3 of the other tensors' scale; the plain
 // kernels are exact to fp32 rounding and cost nothing at this size.
 constexpr int kMinTiledTokens = 16;
-// ... and fp32 problems with at most this many pivots: the gradient of the masses is then a difference of
-// nearly equal terms, which magnifies the 2^-16 of the same contractions to just above 1e-4 of its scale.
-constexpr int kMinTiledPivotsF32 = 2;
+// ... and problems with at most this many pivots: the gradient of the masses is then a difference of nearly
+// equal terms, which magnifies the 2^-16 of the same contractions to just above 1e-4 of its scale with fp32
+// I/O, and the bf16 roundings of the tile kernels to just above 2e-2 with bf16 I/O (a randomised sweep found
+// 2.02e-2 with two pivots and fifteen iterations).
+constexpr int kMinTiledPivots = 2;
 
 // s.n = the longer side; n_short = the shorter one
 static int pick_backward(const lot_shape& s, int n_short, int iters, int path, BwdImpl* impl)
@@ -511,7 +519,7 @@ static int pick_backward(const lot_shape& s, int n_short, int iters, int path, B
     switch (path) {
     case LOT_PATH_AUTO: {
         bool tiled = (one_tile || grouped) && n_short >= kMinTiledTokens;
-        if (s.io_dtype == LOT_F32 && s.r <= kMinTiledPivotsF32) tiled = false;
+        if (s.r <= kMinTiledPivots) tiled = false;
         *impl = tiled ? tile_impl : BWD_PLAIN;
         return LOT_OK;
     }

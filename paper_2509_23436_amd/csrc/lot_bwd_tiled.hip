@@ -235,6 +235,84 @@ __device__ __forceinline__ void sweep_tiles(const BtParams& p, const SweepPlace&
     }
 }
 
+// The same pass for a workgroup none of whose wavefronts has more than KEEP tiles: the similarities C_it of the
+// wavefront's tiles stay in registers from the first pass on (ck, and the token weights in mk), so the later
+// passes and the contraction pass read no token rows and run no similarity product -- which with fp32 I/O is
+// most of a pass (six bf16 products over the pieces of every row, and cutting the rows into them).  `first`:
+// compute them (the rows of all KEEP tiles are requested together).  The weights are formed as (C + g), where the
+// pass above lets the product accumulate onto g: the two differ by rounding (1e-7), which is why a shape runs all
+// its passes in one of the two forms.
+template <typename IO, int D, int RB, bool WITH_U, bool MASS, int KEEP>
+__device__ __forceinline__ void sweep_kept_tiles(const BtParams& p, const SweepPlace& w, const IO* X, const IO* vals,
+                                                 SweepShared<IO, D, RB>& sh, bool first, int wave, int lane, float c1,
+                                                 f32x16 (&ck)[KEEP][RB], float (&mk)[KEEP],
+                                                 f32x16 (&cs)[RB], f32x16 (&Gm)[RB][RB], f32x16 (&U)[RB][D / 32])
+{
+    constexpr int NB = D / 32;
+    constexpr bool kSplit = io_is_f32<IO>::value;
+    const int i = lane & 31, kg = lane >> 5, n = p.n_side[w.side], stride = p.stride_side[w.side];
+    uint16_t* tr_hi = sh.tr + (wave * 2 + 0) * 32 * RB * kTrStride;
+    uint16_t* tr_lo = sh.tr + (wave * 2 + 1) * 32 * RB * kTrStride;
+    if (first) {
+        Frag<IO, D> xs[KEEP];
+#pragma unroll
+        for (int slot = 0; slot < KEEP; ++slot) {
+            const int tile = w.tile_begin + wave + slot * kWaves;
+            const int tok = min(tile * kTileTokens + i, n - 1);
+            if (tile < w.tile_end) {
+                load_tokens<D>(xs[slot], X + ((size_t)w.g * stride + tok) * D, kg);
+                mk[slot] = MASS ? token_weight(p, w.side, w.g, tok) : 1.f;
+            }
+        }
+#pragma unroll
+        for (int slot = 0; slot < KEEP; ++slot) {
+            const int tile = w.tile_begin + wave + slot * kWaves;
+            if (tile < w.tile_end) {
+#pragma unroll
+                for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) ck[slot][mb][j] = 0.f;
+                int skew = 0;
+                asm volatile("" : "+v"(skew));
+                similarity_stashed<IO, D, RB>(ck[slot], sh.zstash, xs[slot], lane, skew);
+            }
+        }
+    }
+#pragma unroll
+    for (int slot = 0; slot < KEEP; ++slot) {
+        const int tile = w.tile_begin + wave + slot * kWaves;
+        if (tile < w.tile_end) {
+            bf16x8 vh[2][NB], vl[2][NB];
+            if (WITH_U) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const int t0 = tile * kTileTokens + 16 * s + 8 * kg;
+                    const int left = max(1, min(8, n - t0));
+                    load_values<D>(vh[s], vl[s], vals, (size_t)w.g * stride + min(t0, n - 1), left, i);
+                }
+            }
+            f32x16 acc[RB];
+            float wt;
+            tile_weights_from_similarities<RB>(acc, wt, ck[slot], sh.g, lane, c1, tile * kTileTokens + i < n);
+            const float mc = mk[slot];
+            const float wcs = MASS ? wt * mc : wt;
+            const float wtr = !MASS ? wt : WITH_U ? (w.side == 1 ? wcs : wt) : wt * __builtin_amdgcn_sqrtf(mc);
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    if (!WITH_U) cs[mb][j] = fmaf(acc[mb][j], wcs, cs[mb][j]);
+                    acc[mb][j] *= wtr;
+                }
+            constexpr bool kHalfGram = !WITH_U && !kSplit;
+            transpose_tile<RB, kSplit, kHalfGram>(acc, tr_hi, tr_lo, i, kg);
+            if (WITH_U) contract_tokens<D, RB, kSplit>(U, tr_hi, tr_lo, vh, vl, i, kg);
+            else contract_gram<RB, kSplit, kHalfGram>(Gm, tr_hi, tr_lo, i, kg);
+            transpose_done();
+        }
+    }
+}
+
 // End of pass k: the workgroup's column sums go to one integer atomic per pivot (which also counts
 // the workgroup), its Gram matrix to this chunk's slot of gram_part.  Contains barriers.
 // Only the blocks on and above the diagonal of the (symmetric) Gram matrix are accumulated and
@@ -378,7 +456,7 @@ __global__ void __launch_bounds__(kThreads, 2) bt_forward(BtParams p)
 // All T passes and the contraction pass in one launch.  Requires every workgroup of a pair to be
 // resident together (the host checks the grid against the device's capacity); the waits are bounded
 // all the same, and a wait that runs out marks the status word and ends the workgroup.
-template <typename IO, int D, int RB, bool MASS>
+template <typename IO, int D, int RB, bool MASS, int KEEP = 0>
 __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
 {
     constexpr int NB = D / 32;
@@ -392,8 +470,10 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
     const float c1 = kLog2e / p.eps;
 
     Frag<IO, D> xc;
-    float mc;
-    load_first_tile<IO, D, MASS>(xc, mc, p, w, X, wave, lane & 31, lane >> 5);
+    float mc = 1.f;
+    if constexpr (KEEP == 0) load_first_tile<IO, D, MASS>(xc, mc, p, w, X, wave, lane & 31, lane >> 5);
+    f32x16 ck[KEEP > 0 ? KEEP : 1][RB];      // KEEP > 0: the similarities of this wavefront's tiles, from the first pass on
+    float mk[KEEP > 0 ? KEEP : 1];
     if (wave == 0) stash_head_pivots<IO, D, RB>(p, w.h, sh.zstash, lane);
     if (tid == 0) s_ok = 1;
     float gv = tid < r ? 0.f : kNegBig;     // g^{k-1}_t, carried by thread t < 64
@@ -440,7 +520,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
         if (!s_ok) return;
         f32x16 cs[RB], Gm[RB][RB], U[RB][NB];
         zero_pass<RB, NB>(cs, Gm);
-        sweep_tiles<IO, D, RB, false, MASS>(p, w, X, nullptr, sh, xc, mc, true, wave, lane, c1, cs, Gm, U);
+        if constexpr (KEEP > 0) sweep_kept_tiles<IO, D, RB, false, MASS, KEEP>(p, w, X, nullptr, sh, k == 1, wave, lane, c1, ck, mk, cs, Gm, U);
+        else sweep_tiles<IO, D, RB, false, MASS>(p, w, X, nullptr, sh, xc, mc, true, wave, lane, c1, cs, Gm, U);
         if (k == 1 && w.chunk != 0) {
             // first post of this launch: the pair's column sums must have been zeroed
             if (tid == 0) {
@@ -470,7 +551,8 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) U[mb][nb][j] = 0.f;
         const IO* vals = reinterpret_cast<const IO*>(w.side == 0 ? p.dO : p.V);
-        sweep_tiles<IO, D, RB, true, MASS>(p, w, X, vals, sh, xc, mc, false, wave, lane, c1, cs, Gm, U);
+        if constexpr (KEEP > 0) sweep_kept_tiles<IO, D, RB, true, MASS, KEEP>(p, w, X, vals, sh, false, wave, lane, c1, ck, mk, cs, Gm, U);
+        else sweep_tiles<IO, D, RB, true, MASS>(p, w, X, vals, sh, xc, mc, false, wave, lane, c1, cs, Gm, U);
         __syncthreads();
         finish_contraction<IO, D, RB>(p, w, sh, tid, wave, lane, U);
     }
@@ -1392,28 +1474,35 @@ int launch_all(const BwdArgs& a, BtParams p)
     // The persistent sweep needs the workgroups of a pair resident together: the whole grid fits the
     // device, or a pair is a single workgroup (which then waits for nobody but itself).
     // (the capacity is taken from the variant with token masses: the same code plus a few registers)
+    // which form of the sweep kernel this shape takes: with token masses; at most two tiles per wavefront, whose
+    // similarities then stay in registers between the passes (measured: DeiT shape, fp32, backward 170 -> 135 us;
+    // B H = 192, n = 256, r = 64: fp32 336 -> 258, bf16 186 -> 177; four kept tiles with bf16 I/O and 32 pivots, the
+    // BERT shape, gained nothing and are not compiled); or the plain one
+    const bool mass = p.mass_side[0] != nullptr || p.mass_side[1] != nullptr;
+    const int per_wave = (p.tiles_per_wg + kWaves - 1) / kWaves;
+    const int form = mass ? 0 : (per_wave <= 2 && sweep_keeps_similarities()) ? 1 : 2;
+    void (*const sweep)(BtParams) = form == 0 ? bt_sweep<IO, D, RB, true, 0> : form == 1 ? bt_sweep<IO, D, RB, false, 2>
+                                                                                            : bt_sweep<IO, D, RB, false, 0>;
     bool persistent = p.chunks == 1;
     if (!persistent && p.chunks <= 255) {
-        static thread_local int capacity_cache[8] = {0};   // per device ordinal
+        static thread_local int capacity_cache[8][3] = {};   // per device ordinal and form of the kernel
         int dev = 0;
         LOT_HIP_CHECK(hipGetDevice(&dev));
-        int capacity = (dev >= 0 && dev < 8) ? capacity_cache[dev] : 0;
+        int capacity = (dev >= 0 && dev < 8) ? capacity_cache[dev][form] : 0;
         if (capacity == 0) {
             int per_cu = 0, cus = 0;
-            LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bt_sweep<IO, D, RB, true>, kThreads, 0));
+            LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sweep, kThreads, 0));
             LOT_HIP_CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
             capacity = per_cu * cus;
-            if (dev >= 0 && dev < 8) capacity_cache[dev] = capacity;
+            if (dev >= 0 && dev < 8) capacity_cache[dev][form] = capacity;
         }
         persistent = (int)grid <= capacity;
     }
     // testing aid: run the sweep as one launch per pass although it would fit (the fallback of devices
     // that cannot hold the grid), so that this form stays exercised
     if (sweep_by_launches() || a.stepwise) persistent = false;
-    const bool mass = p.mass_side[0] != nullptr || p.mass_side[1] != nullptr;
     if (persistent) {
-        if (mass) bt_sweep<IO, D, RB, true><<<grid, kThreads, 0, st>>>(p);
-        else bt_sweep<IO, D, RB, false><<<grid, kThreads, 0, st>>>(p);
+        sweep<<<grid, kThreads, 0, st>>>(p);
     } else {
         const size_t words = (size_t)(T + 1) * pairs * 64;
         bt_clear<<<(unsigned)((words + 255) / 256), 256, 0, st>>>(p.colacc, words, p.status, p.nonce);

@@ -287,6 +287,7 @@ float drift_limit();
 // Testing aid (LOT_KNOB_BWD_SWEEP_LAUNCHES): run the tiled backward's forward sweep as one launch per
 // pass although the persistent form would fit.
 bool sweep_by_launches();
+bool sweep_keeps_similarities();   // testing aid: false = the backward sweep recomputes the similarities in every pass
 int grouped_one_launch_tiles();   // testing aid: tiles per workgroup up to which the grouped forward is one launch
 
 #define LOT_HIP_CHECK(expr)                                   \

@@ -79,6 +79,39 @@ __device__ __forceinline__ void tile_weights(f32x16 (&acc)[RB], float& w, const 
     w = valid ? rcp_fast(pair_sum(s0 + s1)) : 0.f;
 }
 
+// The same from similarities that are already there (c: C_it of the tile, accumulator layout): acc = c + g first.
+template <int RB>
+__device__ __forceinline__ void tile_weights_from_similarities(f32x16 (&acc)[RB], float& w, const f32x16 (&c)[RB],
+                                                               const float* pot, int lane, float c1, bool valid)
+{
+    const int kg = lane >> 5;
+    load_pivot_vector<RB>(acc, pot, kg);
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[mb][j] += c[mb][j];
+    float m0 = acc[0][0], m1 = acc[0][1];
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int j = (mb == 0 ? 2 : 0); j < 16; j += 2) {
+            m0 = fmaxf(m0, acc[mb][j]);
+            m1 = fmaxf(m1, acc[mb][j + 1]);
+        }
+    const float mc = pair_max(fmaxf(m0, m1)) * c1;
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; j += 2) {
+            const float e0 = exp2_fast(fmaf(acc[mb][j], c1, -mc));
+            const float e1 = exp2_fast(fmaf(acc[mb][j + 1], c1, -mc));
+            acc[mb][j] = e0; acc[mb][j + 1] = e1;
+            s0 += e0; s1 += e1;
+        }
+    w = valid ? rcp_fast(pair_sum(s0 + s1)) : 0.f;
+}
+
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 // Writes v (accumulator layout, tokens in lanes) transposed into the wavefront's LDS area as bf16

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libLOT.so")
 LOT_F32, LOT_BF16 = 0, 1
 PATH_AUTO, PATH_REFERENCE, PATH_FUSED, PATH_STEPWISE = 0, 1, 2, 3
 KNOB_SPIN_LIMIT, KNOB_RESHIFT_BITS, KNOB_BWD_ASSEMBLE_BY_ITERATION, KNOB_BWD_SWEEP_LAUNCHES = 0, 1, 2, 3
-KNOB_FWD_STREAMING, KNOB_FWD_DRIFT_LIMIT, KNOB_GROUPED_ONE_LAUNCH_TILES = 4, 5, 6
+KNOB_FWD_STREAMING, KNOB_FWD_DRIFT_LIMIT, KNOB_GROUPED_ONE_LAUNCH_TILES, KNOB_BWD_SWEEP_RECOMPUTE = 4, 5, 6, 7
 ERR_SYNC = -10
 
 EXPORTS = ("lot_workspace_bytes", "lot_workspace_bytes_path", "lot_couplings_workspace_bytes",

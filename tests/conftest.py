@@ -26,5 +26,5 @@ def knobs():
     yield lot
     for k in (lot.KNOB_SPIN_LIMIT, lot.KNOB_RESHIFT_BITS, lot.KNOB_BWD_ASSEMBLE_BY_ITERATION,
               lot.KNOB_BWD_SWEEP_LAUNCHES, lot.KNOB_FWD_STREAMING, lot.KNOB_FWD_DRIFT_LIMIT,
-              lot.KNOB_GROUPED_ONE_LAUNCH_TILES):
+              lot.KNOB_GROUPED_ONE_LAUNCH_TILES, lot.KNOB_BWD_SWEEP_RECOMPUTE):
         lot.lot_debug_set(k, -1)
