@@ -64,11 +64,14 @@ int dispatch_resident(const Args& a)
 int run_fused_resident(const Args& a)
 {
     if (!fused_supports(a.s)) return LOT_ERR_PATH;
-    // More than 32 pivots and few iterations: computing and storing the kernel matrix, then sweeping it once
+    // bf16 I/O, more than 32 pivots and few iterations: computing and storing the kernel matrix, then sweeping it once
     // more for the first column sums, costs more than the few passes it saves (measured over B H = 8 .. 16,
     // n = 4096 .. 32768: 3-15 % slower than the streaming kernel at T = 3 and 5, level or faster from T = 10).
-    // Up to 32 pivots keeping it is never slower.  (The testing knob that asks for these kernels overrides this.)
-    if (a.s.r > 32 && a.iters < 8 && forward_variants() != 2) return LOT_ERR_PATH;
+    // Up to 32 pivots keeping it is never slower; and with fp32 I/O, where a pass of the streaming kernel is mostly
+    // its similarity product (six bf16 products over pieces of every row), keeping wins from the third iteration
+    // (B H = 8 .. 16, n = 1024 .. 4096, 48 and 64 pivots, T = 3, 5, 7: 45-85 us against 62-157).
+    // (The testing knob that asks for these kernels overrides this.)
+    if (a.s.io_dtype == LOT_BF16 && a.s.r > 32 && a.iters < 8 && forward_variants() != 2) return LOT_ERR_PATH;
     return a.s.io_dtype == LOT_BF16 ? dispatch_resident<uint16_t>(a) : dispatch_resident<float>(a);
 }
 
