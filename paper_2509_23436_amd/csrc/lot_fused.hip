@@ -70,11 +70,15 @@ int run_fused(const Args& a, bool want_out)
     if (want_out && forward_variants() != 1) {
         // short sequences: a workgroup per problem, the whole kernel matrix in its wavefronts' registers
         if (forward_variants() != 2) {
-            const int rc = run_wave(a);
+            const int rc = run_wave(a, false);
             if (rc != LOT_ERR_PATH) return rc;
         }
         const int rc = run_fused_resident(a);
         if (rc != LOT_ERR_PATH) return rc;
+        if (forward_variants() != 2) {
+            const int rc_wave = run_wave(a, true);
+            if (rc_wave != LOT_ERR_PATH) return rc_wave;
+        }
     }
     return a.s.io_dtype == LOT_BF16 ? dispatch<uint16_t>(a, want_out) : dispatch<float>(a, want_out);
 }

@@ -234,8 +234,10 @@ int run_cross_reference(const CrossArgs& a);
 // Each returns LOT_OK or LOT_ERR_HIP (the failing hipError_t is left in last_hip_error()).
 int run_reference(const Args& a, bool want_out);
 int run_fused(const Args& a, bool want_out);
-int run_wave(const Args& a);             // attention, uniform masses, each side within one wavefront's registers; else LOT_ERR_PATH
-int run_fused_resident(const Args& a);   // attention, uniform masses; LOT_ERR_PATH where the kernel matrix does not fit on chip
+// attention, each side within the registers of a workgroup's wavefronts; else LOT_ERR_PATH.  last_resort: also the forms
+// that only pay where the workgroup-level kernels (run_fused_resident) have declined
+int run_wave(const Args& a, bool last_resort);
+int run_fused_resident(const Args& a);   // attention; LOT_ERR_PATH where the kernel matrix does not fit on chip
 int run_backward(const BwdArgs& a);
 int run_backward_tiled(const BwdArgs& a);
 // out[b][h][0][:] = softmax_j(beta_cls <q_0, k_j>) V, j over all n tokens of the problem

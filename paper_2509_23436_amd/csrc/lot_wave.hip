@@ -594,18 +594,36 @@ int launch_wave(const Args& a)
 //     after the other, in the passes that read Q, K, V and write O, that the workgroup-level kernels were faster
 //     (measured at B H = 384, n = 512: 87 us against 76).  With at most 64 kept words per lane two wavefronts
 //     share a SIMD's registers there, so that all workgroups are resident at once.
+//   * 17 to 32 tiles a side (n <= 1024, up to 32 pivots in bf16) take the form of four wavefronts with eight tiles
+//     each also when the problems outnumber the compute units: the workgroups then run in rounds, which the
+//     streaming kernel, the only other one such a batch has, does not make up for (B H = 264 .. 768, n = 700 and
+//     1024: T = 5 76-126 us against 78-149, T = 10 90-146 against 134-245).
 template <typename IO, int D, int RB>
-int launch_wave_sized(const Args& a, int tiles)
+int launch_wave_sized(const Args& a, int tiles, bool last_resort)
 {
     constexpr int NW = ResWords<IO, RB>::value;
     constexpr int kMaxNT = 128 / NW;
     const bool roomy = a.s.B * a.s.H <= device_cus();
+    // Where a tile takes 16 registers or more, the forms of four wavefronts per side with two wavefronts on a SIMD
+    // also win when the problems outnumber the compute units: one wavefront that holds eight such tiles has the
+    // SIMD to itself and nothing to hide its latencies behind (measured at B H = 264 .. 768, T = 5 and 10: bf16 I/O
+    // with 64 pivots, n = 200 .. 256, 44-116 us -> 35-68; n = 400 .. 512, 98-225 us -> 71-149; fp32 I/O with 32
+    // pivots level within 10 %, so that one stays as it was beyond eight tiles).
+    constexpr bool kWide = NW >= 16;
     if (tiles <= 2) return launch_wave<IO, D, RB, 2, 1, 1>(a);
-    if (roomy) {
+    if (roomy || (kWide && tiles > 4)) {
         if (tiles <= 8) return launch_wave<IO, D, RB, 2, 4, 2>(a);
-        if constexpr (4 * NW <= 64) { if (tiles <= 16) return launch_wave<IO, D, RB, 4, 4, 2>(a); }
-        if constexpr (8 * NW <= 64) { if (tiles <= 32) return launch_wave<IO, D, RB, 8, 4, 2>(a); }
     }
+    if (roomy || (kWide && !io_is_f32<IO>::value)) {
+        if constexpr (4 * NW <= 64) { if (tiles <= 16) return launch_wave<IO, D, RB, 4, 4, 2>(a); }
+    }
+    if constexpr (8 * NW <= 64) { if (tiles <= 32 && (roomy || tiles > 16)) return launch_wave<IO, D, RB, 8, 4, 2>(a); }
+    // fp32 I/O with more than 32 pivots, up to 512 tokens a side: four tiles of 32 registers beside the working set
+    // overflow the 256 registers of a wavefront by far, and the form lives on spilled registers.  Where the
+    // workgroup-level kernels hold the problem they are faster (B H = 8 and 48: 51-76 us against 68-86); where the
+    // problems are too many for those, this still beats the streaming kernel (B H = 192 .. 768: 87-270 us against
+    // 143-671): so it is offered only after the workgroup-level kernels have declined.
+    if constexpr (NW == 32) { if (tiles > 8 && tiles <= 16) return last_resort ? launch_wave<IO, D, RB, 4, 4, 2>(a) : LOT_ERR_PATH; }
     if constexpr (kMaxNT >= 4) { if (tiles <= 4) return launch_wave<IO, D, RB, 4, 1, 1>(a); }
     if constexpr (kMaxNT >= 8) {
         if (tiles <= 8) return launch_wave<IO, D, RB, 8, 1, 1>(a);
@@ -620,26 +638,26 @@ int launch_wave_sized(const Args& a, int tiles)
 }
 
 template <typename IO>
-int dispatch_wave(const Args& a, int tiles)
+int dispatch_wave(const Args& a, int tiles, bool last_resort)
 {
     const int d = a.s.d_k, rb = a.s.r <= 32 ? 1 : 2;
-    if (d == 32 && rb == 1) return launch_wave_sized<IO, 32, 1>(a, tiles);
-    if (d == 32 && rb == 2) return launch_wave_sized<IO, 32, 2>(a, tiles);
-    if (d == 64 && rb == 1) return launch_wave_sized<IO, 64, 1>(a, tiles);
-    if (d == 64 && rb == 2) return launch_wave_sized<IO, 64, 2>(a, tiles);
+    if (d == 32 && rb == 1) return launch_wave_sized<IO, 32, 1>(a, tiles, last_resort);
+    if (d == 32 && rb == 2) return launch_wave_sized<IO, 32, 2>(a, tiles, last_resort);
+    if (d == 64 && rb == 1) return launch_wave_sized<IO, 64, 1>(a, tiles, last_resort);
+    if (d == 64 && rb == 2) return launch_wave_sized<IO, 64, 2>(a, tiles, last_resort);
     return LOT_ERR_PATH;
 }
 
 }  // namespace
 
 // Attention where each side fits the registers of a workgroup's wavefronts; LOT_ERR_PATH otherwise.
-int run_wave(const Args& a)
+int run_wave(const Args& a, bool last_resort)
 {
     if (!fused_supports(a.s) || a.out == nullptr) return LOT_ERR_PATH;
     const int n_k = a.n_k > 0 ? a.n_k : a.s.n, n_q = a.n_q > 0 ? a.n_q : a.s.n;
     const int longer = n_k > n_q ? n_k : n_q;
     const int tiles = (longer + kTileTokens - 1) / kTileTokens;
-    return a.s.io_dtype == LOT_BF16 ? dispatch_wave<uint16_t>(a, tiles) : dispatch_wave<float>(a, tiles);
+    return a.s.io_dtype == LOT_BF16 ? dispatch_wave<uint16_t>(a, tiles, last_resort) : dispatch_wave<float>(a, tiles, last_resort);
 }
 
 }  // namespace lot

@@ -48,11 +48,23 @@ CASES = {
     "two_waves_per_side_one_extra_token": S(W["bert_base"], B=2, H=2, n=257, r=20, iters=5, seed=40),
     # up to 1024 tokens with no more problems than compute units: four wavefronts per side, eight tiles each
     "four_waves_per_side_bf16": S(W["bert_base"], B=2, H=3, n=900, r=24, iters=6, seed=47),
-    # more problems than compute units, 257-512 tokens, more kept words than two wavefronts per SIMD have room for
+    # more problems than compute units, 257-512 tokens, 16 kept words per tile: four wavefronts per side, four tiles each
     "two_waves_per_side_many_problems_r64": S(W["bert_base"], B=70, H=4, n=400, r=64, iters=3, seed=48),
     # the same regime in fp32 and with head width 32, the last wavefront of a side ragged
     "many_problems_f32_n300": S(W["tiny"], B=90, H=3, n=300, d=32, r=16, iters=4, seed=49),
     "many_problems_bf16_d32_n290": S(W["swin_t_s1"], B=100, H=3, n=290, iters=5, seed=55),
+    # more problems than compute units in the other forms that regime has: 16 or 32 kept words per tile with five
+    # to eight tiles a side (four wavefronts per side, two tiles each), 8 kept words per tile with five to eight
+    # tiles (one wavefront per side) and with 17 to 32 (four wavefronts per side, eight tiles each: the workgroups
+    # run in rounds), three or four tiles of 32 words (one wavefront per side), and fp32 with more than 32 pivots
+    # and nine to sixteen tiles, too many problems for the workgroup-level kernels (the form that lives on
+    # spilled registers)
+    "many_problems_bf16_r64_n230": S(W["bert_base"], B=70, H=4, n=230, r=64, iters=4, seed=56),
+    "many_problems_f32_r64_n230": S(W["tiny"], B=70, H=4, n=230, d=64, r=64, iters=4, seed=57),
+    "many_problems_bf16_r16_n200": S(W["bert_base"], B=90, H=3, n=200, r=16, iters=4, seed=58),
+    "many_problems_bf16_r24_n900": S(W["bert_base"], B=66, H=4, n=900, r=24, iters=4, seed=59),
+    "many_problems_f32_r40_n100": S(W["tiny"], B=90, H=3, n=100, d=64, r=40, iters=4, seed=60),
+    "many_problems_f32_r48_n400": S(W["tiny"], B=66, H=4, n=400, d=64, r=48, iters=5, seed=61),
 }
 
 
@@ -124,6 +136,17 @@ def test_attention_and_couplings_match_oracle(name, path_name):
 
 # The path on which no kernel waits for another workgroup (launch boundaries only): the grouped tile kernels,
 # here also with r <= 64, on every case whose head width they take.  Same bars.
+@pytest.mark.parametrize("name", [nm for nm in CASES if nm.startswith("many_problems_") or nm == "two_waves_per_side_many_problems_r64"])
+def test_many_short_problems_run_on_the_wavefront_kernels(name):
+    """The cases above that were written for the forms of the wavefront-level kernels do run on that family
+    (otherwise they would pass on the streaming kernel and cover nothing new)."""
+    from paper_2509_23436_amd import lot
+    w = CASES[name]
+    dev = to_device(synth.make_inputs(w), w.dtype)
+    assert w.B * w.H > 256
+    assert lot.lot_forward_kernels(lot._shape_of(dev["Q"], dev["V"], dev["Z"]), w.iters) == "kept_wavefront"
+
+
 STEPWISE = [nm for nm, w in CASES.items() if w.d in (32, 64) and w.n >= 16]
 
 
