@@ -138,7 +138,7 @@ int lot_attention_fwd_static(const lot_shape* shape, const void* Q, const void* 
  *   LOT_KERNELS_STREAMING       one persistent kernel that recomputes exp(C/eps) from Q, K in every pass
  *   LOT_KERNELS_KEPT_WORKGROUP  the same kernel keeping each workgroup's share of exp(C/eps) in registers
  *                               and LDS: Q, K, V are read once
- *   LOT_KERNELS_KEPT_WAVEFRONT  short sequences (up to 512 tokens; 1024 with no more problems than compute units): a
+ *   LOT_KERNELS_KEPT_WAVEFRONT  short sequences (up to 512 tokens; 1024 with bf16 I/O and at most 32 pivots): a
  *                               workgroup per problem, one, two or four wavefronts per side holding the side's whole
  *                               exp(C/eps) in their registers
  *   LOT_KERNELS_GROUPED         64 < r <= 256: pivots in groups of 64; one launch per step, or (short sequences:

@@ -63,6 +63,8 @@ inline int tiles_per_wg_for(const lot_shape& s)
     return (int)per;
 }
 
+constexpr int kMaxTiledIters = 64;   // the recursion and the assembly keep per-iteration vectors of 64 pivots in LDS
+
 struct BtParams {
     const void* Q; const void* K; const void* V; const void* dO;
     const float* Z; const float* beta;
@@ -817,66 +819,140 @@ __global__ void bt_mid_gram(BtParams p, int R, size_t total, int mid_blocks)
 // ---------------------------------------------------------------------------------------------
 // recursion over the iterations: one workgroup per pair
 // ---------------------------------------------------------------------------------------------
-__global__ void bt_recursion(BtParams p, int R)
+// Sum over the 64 lanes of a wavefront, the same bits in every lane: the two halves and the two rows of 16 of
+// a half through lane swaps, then rotations within the rows of 16 (every lane adds the same pairs, in the
+// same tree).  No LDS: about sixty cycles, where six shuffles through the LDS crossbar take several hundred.
+__device__ __forceinline__ float wave_sum(float x)
 {
-    // 256 threads: thread (q, t) = (tid / 64, tid % 64) sums a quarter of the products of row t;
-    // the quarters are added in a fixed order by the threads with q == 0, which carry the recursion.
-    __shared__ float s_v[64];
-    __shared__ float s_q[4][64];
-    __shared__ float s_dg[64];
-    const int pair = blockIdx.x, t = threadIdx.x & 63, q = threadIdx.x >> 6, pairs = 2 * p.G, T = p.T;
+    float lo, hi;
+    both_halves(x, lo, hi);
+    x = lo + hi;
+    x = swap16_add(x, x);
+    x += dpp_move<0x128>(x);   // row_ror:8
+    x += dpp_move<0x124>(x);   // row_ror:4
+    x += dpp_move<0x122>(x);   // row_ror:2
+    x += dpp_move<0x121>(x);   // row_ror:1
+    return x;
+}
+
+// Four wavefronts: thread (q, t) = (tid / 64, tid % 64) sums the products of R / 4 rows of M^k (R x R, R = 32 or 64)
+// with column t.
+// All four carry the recursion, with the same operations in the same order (hence the same bits), so what a
+// step needs of the pivot vector's other lanes a wavefront reads from its own lanes, and the only exchange of a
+// step is the one between the four partial sums and their addition (one workgroup barrier).  The chain of T
+// steps is all latency -- a step is a few hundred cycles of work, a load from memory 1.5 us -- so nothing in it
+// may wait for memory or divide.  KEPT > 0 (T <= KEPT): the shares of all T Gram matrices are requested before
+// the chain starts and sit in registers (a wavefront has a SIMD's 512 to itself); KEPT == 0: any T, the matrix
+// of the next step is requested before this one's is used, which hides one step's worth of the latency.
+template <int KEPT, int R>
+__global__ void __launch_bounds__(256) bt_recursion(BtParams p)
+{
+    constexpr int kPer = R / 4, per = kPer;   // rows of M^k per thread
+    constexpr int kHeld = KEPT > 0 ? KEPT : 2;
+    __shared__ float s_c[kMaxTiledIters][64]; // c^k_t, k = 1 .. T
+    __shared__ float s_q[2][4][64];           // the partial sums (two parities: one barrier per step)
+    const int pair = blockIdx.x, t = threadIdx.x & 63, pairs = 2 * p.G, T = p.T;
+    const int q = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = (pair % p.G) % p.H;
     const bool live = t < p.r;
     const float a = 1.f / (float)p.n_side[pair / p.G];
     const float b = live ? p.beta[h * p.r + t] : 1.f;
-    float s = 0.f, nn = 0.f;
-    if (q == 0)
-        for (int c = 0; c < p.chunks; ++c) {
-            s += p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 0) * 64 + t];
-            nn += p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 1) * 64 + t];
-        }
-    auto colsum = [&](int k) {
-        return colsum_of(p.colacc[((size_t)k * pairs + pair) * 64 + t], p.fx_unscale) * a;   // c^k_t
+    float gm[kHeld][kPer];
+    auto fetch = [&](float (&dst)[kPer], int k) {
+        // M^k is symmetric: thread t walks column t, so that a wavefront reads whole rows
+        const float* col = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + min(t, R - 1);
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) dst[j] = j < per ? col[(size_t)(q * per + j) * R] : 0.f;
     };
-    auto gram_times = [&](int k, float v) {      // (M^k v)_t; v is meaningful in the threads with q == 0
-        if (q == 0) s_v[t] = live ? v : 0.f;
-        __syncthreads();
-        float acc = 0.f;
-        if (live && t < R) {
-            // M^k is symmetric: thread t walks column t, so that a wavefront reads whole rows
-            const float* col = p.gram_full + ((size_t)(k - 1) * pairs + pair) * R * R + t;
-            const int u0 = q * (R / 4);
-#pragma unroll 8
-            for (int u = u0; u < u0 + R / 4; ++u) acc = fmaf(col[(size_t)u * R], s_v[u], acc);
+    if constexpr (KEPT > 0) {
+#pragma unroll
+        for (int kk = KEPT - 1; kk >= 0; --kk)
+            if (kk < T) fetch(gm[kk], kk + 1);
+    } else {
+        fetch(gm[0], T);
+    }
+    for (int e = threadIdx.x; e < T * 64; e += 256) {
+        const int k = e / 64 + 1, u = e % 64;
+        s_c[k - 1][u] = colsum_of(p.colacc[((size_t)k * pairs + pair) * 64 + u], p.fx_unscale) * a;   // c^k_u
+    }
+    // s and N of the pair: the chunks' shares, every fourth one per wavefront (eight loads in flight), then the
+    // four partial sums in a fixed order
+    {
+        float ps = 0.f, pn = 0.f;
+        for (int c0 = q; c0 < p.chunks; c0 += 16) {
+            float vs[4], vn[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = c0 + 4 * j;
+                vs[j] = c < p.chunks ? p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 0) * 64 + t] : 0.f;
+                vn[j] = c < p.chunks ? p.sn_part[(((size_t)pair * p.chunks + c) * 2 + 1) * 64 + t] : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { ps += vs[j]; pn += vn[j]; }
         }
-        s_q[q][t] = acc;
-        __syncthreads();
-        return (s_q[0][t] + s_q[1][t]) + (s_q[2][t] + s_q[3][t]);
+        s_q[0][q][t] = ps;
+        s_q[1][q][t] = pn;
+    }
+    __syncthreads();
+    const float s = (s_q[0][0][t] + s_q[0][1][t]) + (s_q[0][2][t] + s_q[0][3][t]);
+    const float nn = (s_q[1][0][t] + s_q[1][1][t]) + (s_q[1][2][t] + s_q[1][3][t]);
+    __syncthreads();
+    int parity = 0;
+    auto gram_times = [&](const float (&m)[kPer], float v) {             // (M^k v)_t with this thread's rows of M^k in m
+        const int vbits = __builtin_bit_cast(int, live ? v : 0.f);
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+            if (j < per) acc = fmaf(m[j], __builtin_bit_cast(float, __builtin_amdgcn_readlane(vbits, q * per + j)), acc);
+        s_q[parity][q][t] = live && t < R ? acc : 0.f;
+        lds_barrier();     // (orders LDS only: a full barrier would wait for the stores of dc^k and for the matrices still on their way)
+        const float sum = (s_q[parity][0][t] + s_q[parity][1][t]) + (s_q[parity][2][t] + s_q[parity][3][t]);
+        parity ^= 1;
+        return sum;
     };
     // The potentials are defined up to a common constant, so every dg^k sums to zero over the pivots, and
     // the step dg^k -> dg^{k-1} leaves the direction c^k unchanged (its eigenvector of eigenvalue 1, which
     // changes no similarity gradient): whatever rounding puts into that sum would stay for all remaining
     // iterations and end up, T times over, in the gradient of the masses.  It is taken out along c^k
     // (sum_t c^k_t = 1) before dg^k is used.
-    auto without_sum = [&](float dg, float ck) {
-        if (q == 0) s_dg[t] = live ? dg : 0.f;
-        __syncthreads();
-        float total = 0.f;
-        for (int u = 0; u < 64; ++u) total += s_dg[u];
-        __syncthreads();
-        return dg - ck * total;
-    };
+    const float eps_over_b = live ? p.eps / b : 0.f;
     float db = live ? s / b : 0.f;
-    float dc = live ? -s / colsum(T) : 0.f;
+    float dc = live ? -s / s_c[T - 1][t] : 0.f;
+    float dg = 0.f;
     if (q == 0) p.dcs[((size_t)T * pairs + pair) * 64 + t] = dc;
-    float dg = -(nn + a * gram_times(T, dc)) / p.eps;          // dg^{T-1}
-    for (int k = T - 1; k >= 1; --k) {
-        const float ck = colsum(k);
-        dg = without_sum(dg, ck);
-        dc = live ? -p.eps * dg / ck : 0.f;
-        db += live ? p.eps * dg / b : 0.f;
+    auto step = [&](int k, const float (&m)[kPer], float ck, float eps_over_ck) {       // dg^k -> dg^{k-1}, k < T
+        dg -= ck * wave_sum(live ? dg : 0.f);
+        dc = live ? -dg * eps_over_ck : 0.f;
+        db += dg * eps_over_b;
         if (q == 0) p.dcs[((size_t)k * pairs + pair) * 64 + t] = dc;
-        dg = -(a / p.eps) * gram_times(k, dc);                  // dg^{k-1}
+        dg = -(a / p.eps) * gram_times(m, dc);
+    };
+    // (the column sums and their reciprocals of the next step are read and formed while this one runs)
+    float ck = T > 1 ? s_c[T - 2][t] : 1.f, eck = live ? p.eps / ck : 0.f;
+    if constexpr (KEPT > 0) {
+#pragma unroll
+        for (int kk = KEPT - 1; kk >= 0; --kk) {
+            const int k = kk + 1;
+            if (k > T) continue;
+            if (k == T) {
+                dg = -(nn + a * gram_times(gm[kk], dc)) / p.eps;     // dg^{T-1}
+            } else {
+                const float ck_now = ck, eck_now = eck;
+                if (k > 1) { ck = s_c[k - 2][t]; eck = live ? p.eps / ck : 0.f; }
+                step(k, gm[kk], ck_now, eck_now);
+            }
+        }
+    } else {
+        if (T > 1) fetch(gm[1], T - 1);
+        dg = -(nn + a * gram_times(gm[0], dc)) / p.eps;      // dg^{T-1}
+        for (int k = T - 1; k >= 1; --k) {
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) gm[0][j] = gm[1][j];
+            if (k > 1) fetch(gm[1], k - 1);
+            const float ck_now = ck, eck_now = eck;
+            if (k > 1) { ck = s_c[k - 2][t]; eck = live ? p.eps / ck : 0.f; }
+            step(k, gm[0], ck_now, eck_now);
+        }
     }
     if (q == 0) p.db_pair[(size_t)pair * 64 + t] = live ? db : 0.f;
 }
@@ -1522,7 +1598,13 @@ int launch_all(const BwdArgs& a, BtParams p)
         bt_mid_gram<D><<<(unsigned)(mid_blocks + (total + 255) / 256), 256, 0, st>>>(p, R, total, mid_blocks);
     }
     bt_glue<IO, D, RB><<<grid, kThreads, 0, st>>>(p);
-    bt_recursion<<<pairs, 256, 0, st>>>(p, R);
+    if (R == 32) {
+        if (T <= 16) bt_recursion<16, 32><<<pairs, 256, 0, st>>>(p);
+        else bt_recursion<0, 32><<<pairs, 256, 0, st>>>(p);
+    } else {
+        if (T <= 16) bt_recursion<16, 64><<<pairs, 256, 0, st>>>(p);
+        else bt_recursion<0, 64><<<pairs, 256, 0, st>>>(p);
+    }
     const size_t dyn = (size_t)T * 2 * 64 * sizeof(float);
     if (T <= kAllAtOnceIters && !assemble_by_iteration()) {
         bt_assemble_mf<IO, D, RB><<<grid, kThreads, 0, st>>>(p, p.redo);
@@ -1541,7 +1623,7 @@ bool bwd_tiled_supports(const lot_shape& s, int iters)
 {
     // the assemble kernel keeps the potentials and column-sum adjoints of all iterations in LDS: 512 bytes
     // per iteration beside up to 107 KB of operands
-    return fused_supports(s) && iters <= 64;
+    return fused_supports(s) && iters <= kMaxTiledIters;
 }
 
 BwdTiledWorkspace carve_bwd_tiled(const lot_shape& s, int iters)
