@@ -27,6 +27,7 @@
 //   assemble-z (dZ partials, a workgroup per group) | final (dZ, dbeta).
 // Every reduction has a fixed order except the forward column sums, which are exchanged as integers:
 // results are reproducible.
+#include <mutex>
 #include "lot_internal.h"
 #include "lot_tile.h"
 #include "lot_tile_ops.h"
@@ -892,10 +893,41 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
     if (p.f.tiles_per_wg >= 32) gb_glue<IO, D, 8><<<grid, 512, glue_bytes, st>>>(p);
     else gb_glue<IO, D, 4><<<grid, 256, glue_bytes, st>>>(p);
     for (int k = T; k >= 1; --k) gb_rec_pass<IO, D><<<grid, kThreads, stash, st>>>(p, k);
-    for (int q0 = 0; q0 < groups; q0 += ax_groups) {
-        const int nq = groups - q0 < ax_groups ? groups - q0 : ax_groups;
-        gb_assemble_x<IO, D, kAssembleWaves><<<grid, 64 * kAssembleWaves, ax_bytes, st>>>(
-            p, (int)stage, q0, nq, p.x_part, q0 == 0 ? 1 : 0, q0 + nq >= groups ? 1 : 0);
+    {
+        // The dQ/dK assembly writes rows, nothing per workgroup, so it need not share the other kernels' split of
+        // a side into workgroups -- and should not: its set-up (the tables and operands of all groups) costs as
+        // much as several tiles, and its LDS lets one or two workgroups on a compute unit.  It takes at least one
+        // tile per wavefront, and as many more as bring the grid down to what the device holds at once (with
+        // twice that, every compute unit pays the set-up twice: n = 4096, r = 128 56 -> 30 us).
+        int occ = 1;
+        {
+            // (asked once per device and LDS size: the last answer is kept)
+            static std::mutex guard;
+            static int last_dev = -1, last_occ = 0;
+            static size_t last_bytes = 0;
+            int dev = 0;
+            LOT_HIP_CHECK(hipGetDevice(&dev));
+            std::lock_guard<std::mutex> lock(guard);
+            if (dev != last_dev || ax_bytes != last_bytes) {
+                LOT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&last_occ, gb_assemble_x<IO, D, kAssembleWaves>,
+                                                                           64 * kAssembleWaves, ax_bytes));
+                last_dev = dev; last_bytes = ax_bytes;
+            }
+            occ = last_occ;
+        }
+        const long long capacity = (long long)(occ > 0 ? occ : 1) * device_cus();
+        const int ntiles = (p.f.n + kTileTokens - 1) / kTileTokens;
+        int per = p.f.tiles_per_wg > kAssembleWaves ? p.f.tiles_per_wg : kAssembleWaves;
+        while ((long long)pairs * ((ntiles + per - 1) / per) > capacity && per < ntiles) per += kAssembleWaves;
+        GbParams px = p;
+        px.f.tiles_per_wg = per;
+        px.f.chunks = (ntiles + per - 1) / per;
+        const unsigned grid_x = (unsigned)pairs * px.f.chunks;
+        for (int q0 = 0; q0 < groups; q0 += ax_groups) {
+            const int nq = groups - q0 < ax_groups ? groups - q0 : ax_groups;
+            gb_assemble_x<IO, D, kAssembleWaves><<<grid_x, 64 * kAssembleWaves, ax_bytes, st>>>(
+                px, (int)stage, q0, nq, p.x_part, q0 == 0 ? 1 : 0, q0 + nq >= groups ? 1 : 0);
+        }
     }
     gb_assemble_z<IO, D><<<group_grid(grid, groups), kThreads, az_bytes, st>>>(p);
     gb_final<<<(unsigned)((a.s.H * a.s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), kFinalSlices * kFinalOutputs, 0, st>>>(p, D);
