@@ -589,11 +589,10 @@ int launch_wave(const Args& a)
 //     the kept words per lane stay within 64.  Measured against one or two wavefronts per side: DeiT shape
 //     27 -> 21 us, B H = 192 at n = 512, r = 32 35 -> 27, B H = 8 at n = 512, r = 64 54 -> 37.
 //   * Otherwise one wavefront per side with the smallest NT of {2, 4, 8} that holds the tiles (NT times the words
-//     per tile at most 128), and for nine to sixteen tiles two wavefronts per side with eight tiles each -- one
-//     wavefront with sixteen would fit the registers too (up to 32 pivots in bf16) but streams so many tiles one
-//     after the other, in the passes that read Q, K, V and write O, that the workgroup-level kernels were faster
-//     (measured at B H = 384, n = 512: 87 us against 76).  With at most 64 kept words per lane two wavefronts
-//     share a SIMD's registers there, so that all workgroups are resident at once.
+//     per tile at most 128), and for nine to sixteen tiles with fp32 I/O two wavefronts per side with eight tiles
+//     each (bf16 I/O: four with four each, see below) -- one wavefront with sixteen would fit the registers too
+//     (up to 32 pivots in bf16) but streams so many tiles one after the other, in the passes that read Q, K, V and
+//     write O, that the workgroup-level kernels were faster (measured at B H = 384, n = 512: 87 us against 76).
 //   * 17 to 32 tiles a side (n <= 1024, up to 32 pivots in bf16) take the form of four wavefronts with eight tiles
 //     each also when the problems outnumber the compute units: the workgroups then run in rounds, which the
 //     streaming kernel, the only other one such a batch has, does not make up for (B H = 264 .. 768, n = 700 and
@@ -608,13 +607,16 @@ int launch_wave_sized(const Args& a, int tiles, bool last_resort)
     // also win when the problems outnumber the compute units: one wavefront that holds eight such tiles has the
     // SIMD to itself and nothing to hide its latencies behind (measured at B H = 264 .. 768, T = 5 and 10: bf16 I/O
     // with 64 pivots, n = 200 .. 256, 44-116 us -> 35-68; n = 400 .. 512, 98-225 us -> 71-149; fp32 I/O with 32
-    // pivots level within 10 %, so that one stays as it was beyond eight tiles).
+    // pivots level within 10 %, so that one stays as it was beyond eight tiles).  With bf16 I/O the form of four
+    // wavefronts with four tiles each also takes nine to sixteen tiles of 8 words from the two wavefronts with
+    // eight (same sweep, up to 32 pivots, n = 400 .. 512: T = 5 37-79 us -> 37-68, T = 10 44-90 -> 46-81; the
+    // BERT shape 52 -> 49).
     constexpr bool kWide = NW >= 16;
     if (tiles <= 2) return launch_wave<IO, D, RB, 2, 1, 1>(a);
     if (roomy || (kWide && tiles > 4)) {
         if (tiles <= 8) return launch_wave<IO, D, RB, 2, 4, 2>(a);
     }
-    if (roomy || (kWide && !io_is_f32<IO>::value)) {
+    if (roomy || !io_is_f32<IO>::value) {
         if constexpr (4 * NW <= 64) { if (tiles <= 16) return launch_wave<IO, D, RB, 4, 4, 2>(a); }
     }
     if constexpr (8 * NW <= 64) { if (tiles <= 32 && (roomy || tiles > 16)) return launch_wave<IO, D, RB, 8, 4, 2>(a); }
@@ -627,12 +629,7 @@ int launch_wave_sized(const Args& a, int tiles, bool last_resort)
     if constexpr (kMaxNT >= 4) { if (tiles <= 4) return launch_wave<IO, D, RB, 4, 1, 1>(a); }
     if constexpr (kMaxNT >= 8) {
         if (tiles <= 8) return launch_wave<IO, D, RB, 8, 1, 1>(a);
-        if (tiles <= 16) {
-            if constexpr (8 * NW <= 64) {
-                if (!roomy) return launch_wave<IO, D, RB, 8, 2, 2>(a);
-            }
-            return launch_wave<IO, D, RB, 8, 2, 1>(a);
-        }
+        if (tiles <= 16) return launch_wave<IO, D, RB, 8, 2, 1>(a);
     }
     return LOT_ERR_PATH;
 }
