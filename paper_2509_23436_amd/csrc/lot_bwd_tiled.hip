@@ -1484,34 +1484,45 @@ __global__ void __launch_bounds__(kThreads, 2) bt_assemble_mf(BtParams p, unsign
 
 // ---------------------------------------------------------------------------------------------
 // final: dZ[h][t][c] and dbeta[h][t], summed over chunks, sides and the batch.  32 outputs per workgroup,
-// each summed by 8 threads that take every 8th problem of the batch (in index order) and are then added
-// in order: a fixed order, and enough threads when the batch is large and H r (D + 1) small.
+// each summed by 8 to 32 threads (`slices`) that take every slices-th of the (problem of the batch, side, chunk) shares, four loads
+// in flight each, and are then added in order: a fixed order, and one round of loads whether the shares are many
+// problems with one chunk each or few problems with many chunks.
 // ---------------------------------------------------------------------------------------------
-constexpr int kFinalSlices = 8, kFinalOutputs = 32;
+constexpr int kFinalSlices = 32, kFinalOutputs = 32;      // (kFinalSlices: the most a launch may ask for)
+// Threads per output: as many as keep the launch within a quarter of a million threads (beyond that, starting the
+// wavefronts costs more than their loads save: 33280 outputs with 32 threads each 9.1 us, with 8 each 5.9 us).
+inline int final_slices(long long outputs)
+{
+    int slices = kFinalSlices;
+    while (slices > 8 && outputs * slices > 262144) slices /= 2;
+    return slices;
+}
 __global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) bt_final(BtParams p, int D)
 {
     __shared__ float s_part[kFinalSlices][kFinalOutputs];
-    const int o = threadIdx.x % kFinalOutputs, slice = threadIdx.x / kFinalOutputs;
+    const int o = threadIdx.x % kFinalOutputs, slice = threadIdx.x / kFinalOutputs, slices = blockDim.x / kFinalOutputs;
     const int idx = blockIdx.x * kFinalOutputs + o;     // (h, t, c), c == D meaning beta
     const int per = p.r * (D + 1);
     const bool live = idx < p.H * per;
     const int h = live ? idx / per : 0, t = live ? (idx % per) / (D + 1) : 0, c = live ? idx % (D + 1) : 0;
     float acc = 0.f;
-    for (int b = slice; live && b < p.B; b += kFinalSlices) {
-        const int g = b * p.H + h;
-        if (c < D) {
-            for (int side = 0; side < 2; ++side) {
-                const float* src = p.dz_part + ((size_t)(side * p.G + g) * p.chunks) * 64 * D + t * D + c;
-                float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-                int ch = 0;
-                for (; ch + 3 < p.chunks; ch += 4) {
-                    a0 += src[(size_t)ch * 64 * D]; a1 += src[(size_t)(ch + 1) * 64 * D];
-                    a2 += src[(size_t)(ch + 2) * 64 * D]; a3 += src[(size_t)(ch + 3) * 64 * D];
-                }
-                for (; ch < p.chunks; ++ch) a0 += src[(size_t)ch * 64 * D];
-                acc += (a0 + a1) + (a2 + a3);
-            }
-        } else {
+    if (live && c < D) {
+        // the shares of every (problem of the batch, side, chunk): every kFinalSlices-th one, four loads in flight
+        const int items = p.B * 2 * p.chunks;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        auto share = [&](int j) {
+            if (j >= items) return 0.f;
+            const int ch = j % p.chunks, side = (j / p.chunks) % 2, g = (j / (2 * p.chunks)) * p.H + h;
+            return p.dz_part[(((size_t)(side * p.G + g) * p.chunks) + ch) * 64 * D + t * D + c];
+        };
+        for (int j = slice; j < items; j += 4 * slices) {
+            const float v0 = share(j), v1 = share(j + slices), v2 = share(j + 2 * slices), v3 = share(j + 3 * slices);
+            a0 += v0; a1 += v1; a2 += v2; a3 += v3;
+        }
+        acc = (a0 + a1) + (a2 + a3);
+    } else if (live) {
+        for (int b = slice; b < p.B; b += slices) {
+            const int g = b * p.H + h;
             acc += p.db_glue[g * 64 + t];
             acc += p.db_pair[(size_t)g * 64 + t];
             acc += p.db_pair[(size_t)(p.G + g) * 64 + t];
@@ -1521,8 +1532,7 @@ __global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) bt_final(BtParam
     __syncthreads();
     if (slice == 0 && live) {
         float tot = 0.f;
-#pragma unroll
-        for (int sl = 0; sl < kFinalSlices; ++sl) tot += s_part[sl][o];
+        for (int sl = 0; sl < slices; ++sl) tot += s_part[sl][o];
         // a sweep whose wait between workgroups gave up has marked this launch: the gradients of the
         // pivots and their masses are made NaN, so that the failure cannot pass for a result
         if (p.status[0] == p.nonce) tot = __builtin_nanf("");
@@ -1612,7 +1622,7 @@ int launch_all(const BwdArgs& a, BtParams p)
     } else {
         bt_assemble<IO, D, RB><<<grid, kThreads, dyn, st>>>(p, T, nullptr);
     }
-    bt_final<<<(unsigned)((s.H * s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), kFinalSlices * kFinalOutputs, 0, st>>>(p, D);
+    bt_final<<<(unsigned)((s.H * s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), final_slices(s.H * s.r * (D + 1)) * kFinalOutputs, 0, st>>>(p, D);
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }
