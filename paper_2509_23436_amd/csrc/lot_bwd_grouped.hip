@@ -801,7 +801,7 @@ inline int final_slices(long long outputs)
     while (slices > 8 && outputs * slices > 262144) slices /= 2;
     return slices;
 }
-__global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) gb_final(GbParams p, int D)
+__global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) gb_final(GbParams p, int D, int step_q, int step_ch)   // (slices / chunks, slices % chunks)
 {
     __shared__ float s_part[kFinalSlices][kFinalOutputs];
     const int o = threadIdx.x % kFinalOutputs, slice = threadIdx.x / kFinalOutputs, slices = blockDim.x / kFinalOutputs;
@@ -812,16 +812,23 @@ __global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) gb_final(GbParam
     const int h = live ? idx / per : 0, t = live ? (idx % per) / (D + 1) : 0, c = live ? idx % (D + 1) : 0;
     float acc = 0.f;
     if (live && c < D) {
-        // the shares of every (problem of the batch, side, chunk): every kFinalSlices-th one, four loads in flight
-        const int items = p.B * 2 * chunks;
+        // the shares of every (problem of the batch, side, chunk), numbered (side B + b) chunks + chunk: every
+        // slices-th one, four loads in flight; the walk carries (row, chunk) along instead of dividing each time
+        const int rows = 2 * p.B;
+        int q = slice / chunks, ch = slice % chunks;
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-        auto share = [&](int j) {
-            if (j >= items) return 0.f;
-            const int ch = j % chunks, side = (j / chunks) % 2, g = (j / (2 * chunks)) * p.f.H + h;
-            return p.dz_part[(((size_t)(side * G + g) * chunks) + ch) * kRmax * D + t * D + c];
+        auto next_share = [&]() {
+            float v = 0.f;
+            if (q < rows) {
+                const int side = q >= p.B ? 1 : 0, g = (q - side * p.B) * p.f.H + h;
+                v = p.dz_part[(((size_t)(side * G + g) * chunks) + ch) * kRmax * D + t * D + c];
+            }
+            q += step_q; ch += step_ch;
+            if (ch >= chunks) { ch -= chunks; ++q; }
+            return v;
         };
-        for (int j = slice; j < items; j += 4 * slices) {
-            const float v0 = share(j), v1 = share(j + slices), v2 = share(j + 2 * slices), v3 = share(j + 3 * slices);
+        while (q < rows) {
+            const float v0 = next_share(), v1 = next_share(), v2 = next_share(), v3 = next_share();
             a0 += v0; a1 += v1; a2 += v2; a3 += v3;
         }
         acc = (a0 + a1) + (a2 + a3);
@@ -907,8 +914,10 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
         // The dQ/dK assembly writes rows, nothing per workgroup, so it need not share the other kernels' split of
         // a side into workgroups -- and should not: its set-up (the tables and operands of all groups) costs as
         // much as several tiles, and its LDS lets one or two workgroups on a compute unit.  It takes at least one
-        // tile per wavefront, and as many more as bring the grid down to what the device holds at once (with
-        // twice that, every compute unit pays the set-up twice: n = 4096, r = 128 56 -> 30 us).
+        // tile per wavefront, and up to four where that brings the grid down to what the device holds at once (with
+        // twice that, every compute unit pays the set-up twice: n = 4096, r = 128 56 -> 30 us; with many tiles per
+        // wavefront the set-up no longer counts and two rounds of shorter workgroups balance better: n = 131072,
+        // r = 256 650 us as it was, 699 in one round).
         int occ = 1;
         {
             // (asked once per device and LDS size: the last answer is kept)
@@ -928,7 +937,7 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
         const long long capacity = (long long)(occ > 0 ? occ : 1) * device_cus();
         const int ntiles = (p.f.n + kTileTokens - 1) / kTileTokens;
         int per = p.f.tiles_per_wg > kAssembleWaves ? p.f.tiles_per_wg : kAssembleWaves;
-        while ((long long)pairs * ((ntiles + per - 1) / per) > capacity && per < ntiles) per += kAssembleWaves;
+        while ((long long)pairs * ((ntiles + per - 1) / per) > capacity && per < 4 * kAssembleWaves) per += kAssembleWaves;
         GbParams px = p;
         px.f.tiles_per_wg = per;
         px.f.chunks = (ntiles + per - 1) / per;
@@ -940,7 +949,10 @@ int launch_bwd_grouped(const BwdArgs& a, GbParams p)
         }
     }
     gb_assemble_z<IO, D><<<group_grid(grid, groups), kThreads, az_bytes, st>>>(p);
-    gb_final<<<(unsigned)((a.s.H * a.s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), final_slices(a.s.H * a.s.r * (D + 1)) * kFinalOutputs, 0, st>>>(p, D);
+    {
+        const int slices = final_slices(a.s.H * a.s.r * (D + 1));
+        gb_final<<<(unsigned)((a.s.H * a.s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), slices * kFinalOutputs, 0, st>>>(p, D, slices / p.f.chunks, slices % p.f.chunks);
+    }
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }

@@ -1497,7 +1497,7 @@ inline int final_slices(long long outputs)
     while (slices > 8 && outputs * slices > 262144) slices /= 2;
     return slices;
 }
-__global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) bt_final(BtParams p, int D)
+__global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) bt_final(BtParams p, int D, int step_q, int step_ch)   // (slices / chunks, slices % chunks)
 {
     __shared__ float s_part[kFinalSlices][kFinalOutputs];
     const int o = threadIdx.x % kFinalOutputs, slice = threadIdx.x / kFinalOutputs, slices = blockDim.x / kFinalOutputs;
@@ -1507,16 +1507,23 @@ __global__ void __launch_bounds__(kFinalSlices * kFinalOutputs) bt_final(BtParam
     const int h = live ? idx / per : 0, t = live ? (idx % per) / (D + 1) : 0, c = live ? idx % (D + 1) : 0;
     float acc = 0.f;
     if (live && c < D) {
-        // the shares of every (problem of the batch, side, chunk): every kFinalSlices-th one, four loads in flight
-        const int items = p.B * 2 * p.chunks;
+        // the shares of every (problem of the batch, side, chunk), numbered (side B + b) chunks + chunk: every
+        // slices-th one, four loads in flight; the walk carries (row, chunk) along instead of dividing each time
+        const int rows = 2 * p.B;
+        int q = slice / p.chunks, ch = slice % p.chunks;
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-        auto share = [&](int j) {
-            if (j >= items) return 0.f;
-            const int ch = j % p.chunks, side = (j / p.chunks) % 2, g = (j / (2 * p.chunks)) * p.H + h;
-            return p.dz_part[(((size_t)(side * p.G + g) * p.chunks) + ch) * 64 * D + t * D + c];
+        auto next_share = [&]() {
+            float v = 0.f;
+            if (q < rows) {
+                const int side = q >= p.B ? 1 : 0, g = (q - side * p.B) * p.H + h;
+                v = p.dz_part[(((size_t)(side * p.G + g) * p.chunks) + ch) * 64 * D + t * D + c];
+            }
+            q += step_q; ch += step_ch;
+            if (ch >= p.chunks) { ch -= p.chunks; ++q; }
+            return v;
         };
-        for (int j = slice; j < items; j += 4 * slices) {
-            const float v0 = share(j), v1 = share(j + slices), v2 = share(j + 2 * slices), v3 = share(j + 3 * slices);
+        while (q < rows) {
+            const float v0 = next_share(), v1 = next_share(), v2 = next_share(), v3 = next_share();
             a0 += v0; a1 += v1; a2 += v2; a3 += v3;
         }
         acc = (a0 + a1) + (a2 + a3);
@@ -1622,7 +1629,10 @@ int launch_all(const BwdArgs& a, BtParams p)
     } else {
         bt_assemble<IO, D, RB><<<grid, kThreads, dyn, st>>>(p, T, nullptr);
     }
-    bt_final<<<(unsigned)((s.H * s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), final_slices(s.H * s.r * (D + 1)) * kFinalOutputs, 0, st>>>(p, D);
+    {
+        const int slices = final_slices(s.H * s.r * (D + 1));
+        bt_final<<<(unsigned)((s.H * s.r * (D + 1) + kFinalOutputs - 1) / kFinalOutputs), slices * kFinalOutputs, 0, st>>>(p, D, slices / p.chunks, slices % p.chunks);
+    }
     LOT_HIP_CHECK(hipGetLastError());
     return LOT_OK;
 }
