@@ -563,39 +563,45 @@ __global__ void __launch_bounds__(kThreads, 2) bt_sweep(BtParams p)
 // ---------------------------------------------------------------------------------------------
 // mid: Y'_t = U_t / cs2_t, dYraw_t = n Wd_t / cs1_t, db_glue_t = -<dYraw_t, Y'_t>, rho'_t = beta_t / cs_t
 // ---------------------------------------------------------------------------------------------
-// One thread per (g, t, column): sums the per-chunk contractions in chunk order; the D threads of a
+// One thread per (g, t, four columns): sums the per-chunk contractions in chunk order; the D / 4 threads of a
 // (g, t) row are adjacent lanes of one wavefront, so the row's dot product <dYraw_t, Y'_t> is a
 // butterfly sum over them and lane 0 of the row writes the per-pivot numbers.
 template <int D>
 __device__ __forceinline__ void mid_body(const BtParams& p, int block)
 {
-    const int idx = block * blockDim.x + threadIdx.x;      // the blocks cover G * 64 * D exactly: whole wavefronts
-    const int g = idx / (64 * D), e = idx % (64 * D), t = e / D;
+    const int idx = block * blockDim.x + threadIdx.x;      // the blocks cover G * 64 * D / 4 exactly: whole wavefronts
+    const int g = idx / (16 * D), e = (idx % (16 * D)) * 4, t = e / D;
     const int pairs = 2 * p.G, T = p.T;
-    float y = 0.f, dy = 0.f, r1 = 0.f, r2 = 0.f;
+    f32x4 y = {0.f, 0.f, 0.f, 0.f}, dy = y;
+    float r1 = 0.f, r2 = 0.f;
     if (t < p.r) {
-        float u0 = 0.f, u1 = 0.f, w0 = 0.f, w1 = 0.f;     // two interleaved chains each: the loads overlap
-        const float* wp = p.u_part + ((size_t)(0 * p.G + g) * p.chunks) * 64 * D + e;
-        const float* up = p.u_part + ((size_t)(1 * p.G + g) * p.chunks) * 64 * D + e;
+        f32x4 u0 = y, u1 = y, w0 = y, w1 = y;     // two interleaved chains each: the loads overlap
+        const f32x4* wp = reinterpret_cast<const f32x4*>(p.u_part + ((size_t)(0 * p.G + g) * p.chunks) * 64 * D + e);
+        const f32x4* up = reinterpret_cast<const f32x4*>(p.u_part + ((size_t)(1 * p.G + g) * p.chunks) * 64 * D + e);
+        constexpr int kStep = 16 * D;             // f32x4 words between consecutive chunks
         int c = 0;
         for (; c + 1 < p.chunks; c += 2) {
-            w0 += wp[(size_t)c * 64 * D]; w1 += wp[(size_t)(c + 1) * 64 * D];
-            u0 += up[(size_t)c * 64 * D]; u1 += up[(size_t)(c + 1) * 64 * D];
+            w0 += wp[(size_t)c * kStep]; w1 += wp[(size_t)(c + 1) * kStep];
+            u0 += up[(size_t)c * kStep]; u1 += up[(size_t)(c + 1) * kStep];
         }
-        if (c < p.chunks) { w0 += wp[(size_t)c * 64 * D]; u0 += up[(size_t)c * 64 * D]; }
+        if (c < p.chunks) { w0 += wp[(size_t)c * kStep]; u0 += up[(size_t)c * kStep]; }
         const float cs1 = colsum_of(p.colacc[((size_t)T * pairs + g) * 64 + t], p.fx_unscale);
         const float cs2 = colsum_of(p.colacc[((size_t)T * pairs + p.G + g) * 64 + t], p.fx_unscale);
-        y = (u0 + u1) / cs2;
-        dy = (float)p.n_side[0] * (w0 + w1) / cs1;
+        const float ns = (float)p.n_side[0];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            y[q] = (u0[q] + u1[q]) / cs2;
+            dy[q] = ns * (w0[q] + w1[q]) / cs1;
+        }
         const float b = p.beta[(g % p.H) * p.r + t];
         r1 = b / cs1;
         r2 = b / cs2;
     }
-    p.yp[idx] = y;
-    p.dyraw[idx] = dy;
-    float dot = dy * y;
+    reinterpret_cast<f32x4*>(p.yp)[idx] = y;
+    reinterpret_cast<f32x4*>(p.dyraw)[idx] = dy;
+    float dot = (dy[0] * y[0] + dy[1] * y[1]) + (dy[2] * y[2] + dy[3] * y[3]);
 #pragma unroll
-    for (int o = D / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+    for (int o = D / 8; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
     if (e % D == 0) {
         p.db_glue[g * 64 + t] = -dot;
         p.rhop[(size_t)g * 64 + t] = r1;
@@ -1609,7 +1615,7 @@ int launch_all(const BwdArgs& a, BtParams p)
         else bt_forward<IO, D, RB, true, false><<<grid, kThreads, 0, st>>>(p);
     }
     {
-        const int mid_blocks = p.G * 64 * D / 256;
+        const int mid_blocks = (int)((size_t)p.G * 64 * D / 1024);     // four columns per thread
         // (a pair with a single workgroup has written its Gram matrices in place: nothing to reduce)
         const size_t total = p.chunks > 1 ? (size_t)T * pairs * R * R : 0;
         bt_mid_gram<D><<<(unsigned)(mid_blocks + (total + 255) / 256), 256, 0, st>>>(p, R, total, mid_blocks);
