@@ -22,13 +22,13 @@ def _say(msg):
     sys.stdout.flush()
 
 
-def _draw(seed, dtype):
-    rng = np.random.default_rng(1000 * (1 if dtype == "f32" else 2) + seed)
+def _draw(seed, dtype, many_pivots=False):
+    rng = np.random.default_rng(1000 * (1 if dtype == "f32" else 2) + seed + (500 if many_pivots else 0))
     case = {
         "kind": str(rng.choice(["plain", "cls", "cross", "cross"])),
         "d": int(rng.choice([32, 64])),
-        "r": int(rng.choice([3, 7, 16, 31, 32, 33, 48, 64])),
-        "B": int(rng.choice([1, 2, 3, 30, 90])),
+        "r": int(rng.choice([65, 96, 100, 128, 129, 200, 256]) if many_pivots else rng.choice([3, 7, 16, 31, 32, 33, 48, 64])),
+        "B": int(rng.choice([1, 2, 3]) if many_pivots else rng.choice([1, 2, 3, 30, 90])),
         "H": int(rng.integers(1, 5)),
         "n": int(rng.choice([16, 17, 31, 32, 33, 64, 100, 197, 256, 257, 500, 513, 1000, 1500, 2049])),
         "iters": int(rng.choice([1, 2, 3, 5, 8, 10, 15, 16, 17, 20])),
@@ -57,10 +57,20 @@ def _check(tag, got, ref, tol):
 @pytest.mark.parametrize("seed", SEEDS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_drawn_case_matches_the_oracles(dtype, seed):
+    _run(_draw(seed, dtype), dtype, seed)
+
+
+@pytest.mark.parametrize("seed", SEEDS[:16])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_drawn_case_with_more_than_64_pivots_matches_the_oracles(dtype, seed):
+    """The same with 65 to 256 pivots: the kernels that take the pivots in groups of 64."""
+    _run(_draw(seed, dtype, many_pivots=True), dtype, seed)
+
+
+def _run(c, dtype, seed):
     import torch
     from oracle import lot_oracle, lot_oracle_bwd
     from paper_2509_23436_amd import lot
-    c = _draw(seed, dtype)
     bf16 = dtype == "bf16"
     tol = 2e-2 if bf16 else 1e-4
     _say("drawn case %s %d: %r" % (dtype, seed, c))
