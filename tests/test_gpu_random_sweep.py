@@ -1,7 +1,7 @@
 """GPU parity on shapes nobody picked by hand: for each seed a variant (plain, [CLS], cross attention with
 uniform, random or padded masses), a shape and the method's parameters are drawn from lists that mix tile
 boundaries, ragged tails, few and many problems, and every regime of the dispatch rules; the forward output
-and all gradients of the path AUTO selects are compared with the fp64 oracles, to the bars of the other parity tests
+and all gradients (of the path AUTO selects, and of FUSED and STEPWISE by name) are compared with the fp64 oracles, to the bars of the other parity tests
 (fp32 I/O 1e-4, bf16 I/O 2e-2, max-norm relative).  The draws are seeded: the same cases on every run."""
 import dataclasses
 import sys
@@ -67,13 +67,23 @@ def test_drawn_case_with_more_than_64_pivots_matches_the_oracles(dtype, seed):
     _run(_draw(seed, dtype, many_pivots=True), dtype, seed)
 
 
-def _run(c, dtype, seed):
+@pytest.mark.parametrize("seed", SEEDS[:12])
+@pytest.mark.parametrize("path_name", ["fused", "stepwise"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_drawn_case_on_a_forced_path_matches_the_oracles(dtype, path_name, seed):
+    """The tile kernels asked for by name: with waits between workgroups (FUSED) and with launch boundaries only
+    (STEPWISE), whatever AUTO would have picked for the shape."""
+    _run(_draw(seed, dtype, many_pivots=seed % 3 == 2), dtype, seed, path_name)
+
+
+def _run(c, dtype, seed, path_name="auto"):
     import torch
     from oracle import lot_oracle, lot_oracle_bwd
     from paper_2509_23436_amd import lot
+    path = {"auto": lot.PATH_AUTO, "fused": lot.PATH_FUSED, "stepwise": lot.PATH_STEPWISE}[path_name]
     bf16 = dtype == "bf16"
     tol = 2e-2 if bf16 else 1e-4
-    _say("drawn case %s %d: %r" % (dtype, seed, c))
+    _say("drawn case %s %d on path %s: %r" % (dtype, seed, path_name, c))
     w = dataclasses.replace(synth.WORKLOADS["tiny"], B=c["B"], H=c["H"], n=c["n"], d=c["d"], r=c["r"], eps=c["eps"],
                             iters=c["iters"], seed=c["seed"], dtype=dtype)
     x = synth.make_inputs(w)
@@ -85,15 +95,15 @@ def _run(c, dtype, seed):
     if c["kind"] == "plain":
         O_ref = lot_oracle.attention(x["Q"], x["K"], x["V"], x["Z"], x["beta"], eps, iters, threads=16)[0]
         refs, _ = lot_oracle_bwd.attention_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], eps, iters, dO)
-        out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters)
-        got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters, dev["dO"])
+        out = lot.lot_attention_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters, path=path)
+        got = lot.lot_attention_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters, dev["dO"], path=path)
         names = ("dQ", "dK", "dV", "dZ", "dbeta")
     elif c["kind"] == "cls":
         bc = c["beta_cls"]
         O_ref = lot_oracle.attention_cls(x["Q"], x["K"], x["V"], x["Z"], x["beta"], eps, iters, bc, threads=16)
         refs, _ = lot_oracle_bwd.attention_cls_bwd(x["Q"], x["K"], x["V"], x["Z"], x["beta"], eps, iters, bc, dO)
-        out = lot.lot_attention_cls_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters, bc)
-        got = lot.lot_attention_cls_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters, bc, dev["dO"])
+        out = lot.lot_attention_cls_fwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters, bc, path=path)
+        got = lot.lot_attention_cls_bwd(dev["Q"], dev["K"], dev["V"], dev["Z"], dev["beta"], eps, iters, bc, dev["dO"], path=path)
         names = ("dQ", "dK", "dV", "dZ", "dbeta", "dbeta_cls")
     else:
         B, H, n, n_k, d = c["B"], c["H"], c["n"], c["n_k"], c["d"]
@@ -124,9 +134,9 @@ def _run(c, dtype, seed):
             return torch.from_numpy(np.ascontiguousarray(a)).cuda()
         Kd, Vd = on_device(K, True), on_device(V, True)
         out = lot.lot_cross_attention_fwd(dev["Q"], Kd, Vd, dev["Z"], dev["beta"], eps, iters,
-                                          mass_q=on_device(mq), mass_k=on_device(mk))
+                                          mass_q=on_device(mq), mass_k=on_device(mk), path=path)
         got = lot.lot_cross_attention_bwd(dev["Q"], Kd, Vd, dev["Z"], dev["beta"], eps, iters, dev["dO"],
-                                          mass_q=on_device(mq), mass_k=on_device(mk))
+                                          mass_q=on_device(mq), mass_k=on_device(mk), path=path)
         names = ("dQ", "dK", "dV", "dZ", "dbeta")
     torch.cuda.synchronize()
     _check("O", out, O_ref, tol)
